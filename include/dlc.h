@@ -1,0 +1,175 @@
+/*
+ * dlc.h -- C ABI of the MI355X (gfx950) error-bounded compressor for DLRM
+ * embedding-lookup payloads (arXiv 2407.04272).
+ *
+ * One GPU's share of the all-to-all payload -- T embedding-lookup tensors of
+ * B rows x D elements, row-major, fp32 or fp16, resident in device memory --
+ * is compressed into ONE device buffer plus size metadata (pipeline stages 1
+ * and 2 of Section III-A; "multiple tensors into a single compressed tensor",
+ * Section I), and decompressed on the receiving side (stage 4).  Per-table
+ * error bounds come from sampled statistics (Eq. 1, Algorithm 1
+ * OfflineAnalysis) and are tightened per iteration (Algorithm 1 OnlineDecay).
+ *
+ * Conventions
+ *  - plain pointers and sizes only; every pointer is marked HOST or DEVICE.
+ *  - device buffers are caller-owned; the library never frees or reallocates
+ *    them.  A context owns its own workspace, allocated in dlc_create on the
+ *    device that is current at that time.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Unless stated otherwise a call only enqueues work on that stream.
+ *  - return value: DLC_OK or a negative dlc_status.  Errors that only the GPU
+ *    can see (output capacity exceeded, corrupt container) are recorded in a
+ *    device status word and returned by dlc_sync_status.
+ *  - a context is not thread-safe; calls that share a context must be issued
+ *    on one stream (or be ordered by the caller).
+ */
+#ifndef DLC_H
+#define DLC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dlc_ctx dlc_ctx;
+
+enum { DLC_F32 = 0, DLC_F16 = 1 };
+
+typedef enum {
+    DLC_OK = 0,
+    DLC_EINVAL = -1,    /* bad argument (null/misaligned pointer, geometry out of range, eb <= 0 or not finite) */
+    DLC_ENOMEM = -2,    /* workspace allocation failed */
+    DLC_ECAPACITY = -3, /* output buffer too small; nothing was written past its capacity */
+    DLC_ECORRUPT = -4,  /* container fails validation */
+    DLC_EHIP = -5,      /* a HIP runtime call failed */
+    DLC_ESTATE = -6     /* call order (bounds not set), or an internal invariant failed */
+} dlc_status;
+
+/* Geometry and format parameters of one payload (Section III-D leaves them open). */
+typedef struct {
+    int32_t dtype;         /* DLC_F32 or DLC_F16 */
+    int32_t num_tables;    /* T >= 1 */
+    int64_t batch;         /* B >= 1 rows per table */
+    int64_t dim;           /* D >= 1 elements per row; B*D < 2^31 */
+    int32_t radius;        /* R: power of two in [8, 2048]; alphabet 2R, symbol 0 = verbatim escape */
+    int32_t chunk_symbols; /* S: symbols per chunk, one of 64, 128, 256 */
+    int32_t max_code_len;  /* LMAX <= 12, 2^LMAX >= 2R */
+    int32_t reserved;      /* 0 */
+} dlc_config;
+
+/* Per-table statistics of a sampled batch: what Eq. 1 needs, plus the value range. */
+typedef struct {
+    float min, max;          /* over finite elements (+inf / -inf if there are none) */
+    uint64_t count;          /* B*D */
+    uint32_t n_rows;         /* B */
+    uint32_t n_unique_raw;   /* N_original: distinct rows, raw bit patterns */
+    uint32_t n_unique_quant; /* N_compressed: distinct rows after quantisation at probe_eb */
+    float probe_eb;
+} dlc_table_stats;
+
+enum { DLC_CLASS_SMALL = 0, DLC_CLASS_MEDIUM = 1, DLC_CLASS_LARGE = 2 };
+enum { DLC_DECAY_NONE = 0, DLC_DECAY_STEPWISE = 1, DLC_DECAY_DROP = 2 };
+
+/* Hyper-parameters of Algorithm 1. */
+typedef struct {
+    int32_t mode;        /* 0: global_eb is an absolute bound (the paper's mode); 1: a fraction of (max-min) */
+    int32_t decay_kind;  /* DLC_DECAY_* ; stepwise is the paper's default (Section III-C) */
+    double global_eb;    /* GlobalEB = MediumEB */
+    double alpha, beta;  /* LargeEB = GlobalEB*alpha, SmallEB = GlobalEB/beta */
+    double h_large;      /* L_EMB_hindex: eta < h_large -> large */
+    double h_small;      /* S_EMB_hindex: eta > h_small -> small; otherwise medium */
+    int64_t decay_start; /* first iteration of the initial phase */
+    int64_t decay_len;   /* its length in iterations */
+    int32_t decay_steps; /* number of equal drops of the staircase */
+    int32_t reserved;    /* 0 */
+    double decay_mult0;  /* multiplier at the start of the phase (2 = "Decay_2x"); 1 after the phase */
+    double eb_min, eb_max; /* clamp, each applied when > 0 */
+    double rel_floor;    /* when > 0: eb >= rel_floor*(max-min) */
+} dlc_controller_params;
+
+/* Creates a context for one geometry and allocates its device workspace (HOST call, allocates). */
+int dlc_create(dlc_ctx** ctx_out /*HOST*/, const dlc_config* cfg /*HOST*/);
+void dlc_destroy(dlc_ctx* ctx);
+
+/* Worst-case container size in bytes for this geometry (every element an escape); 0 if cfg is invalid. */
+size_t dlc_compress_bound(const dlc_config* cfg /*HOST*/);
+/* Device workspace a context of this geometry holds (statistics workspace excluded: allocated on first use). */
+size_t dlc_workspace_bytes(const dlc_config* cfg /*HOST*/);
+
+/*
+ * Statistics reduction (Eq. 1; Algorithm 1, OfflineAnalysis: sampleData + homoIndexCal inputs).
+ *   d_payload  DEVICE  [T][B][D] row-major, dtype of the context, 16-byte aligned
+ *   h_probe_eb HOST    T bounds at which rows are quantised for N_compressed
+ *   h_stats    HOST    T entries, caller-owned, filled on return
+ * Distinct-row counts are exact (hashing, then every hash match is verified element by element).
+ * Synchronises `stream` before returning.  Allocates its own workspace on first use.
+ */
+int dlc_stats(dlc_ctx* ctx, const void* d_payload, const float* h_probe_eb, dlc_table_stats* h_stats, void* stream);
+
+/*
+ * Dual-level error-bound controller (Algorithm 1: EMBClassification, LargeEB/MediumEB/SmallEB, OnlineDecay).
+ *   h_stats == NULL : h_eb_inout holds T explicit bounds, taken as they are.
+ *   h_stats != NULL : bounds are derived: class from eta = (N_original - N_compressed)/N_original and the two
+ *                     thresholds (or from h_class_override[t] when that is >= 0), class bound from params,
+ *                     times the iteration multiplier, clamp, floor; rounded once to fp32 and written to
+ *                     h_eb_inout (T, HOST) and, if given, the classes to h_class_out (T, HOST).
+ * The bounds are then copied to the context's device memory on `stream` (ordered before later compress calls
+ * on that stream).  Every bound must be finite and > 0.
+ */
+int dlc_set_error_bounds(dlc_ctx* ctx, const dlc_table_stats* h_stats, const dlc_controller_params* params,
+                         const int32_t* h_class_override, int64_t iteration, float* h_eb_inout,
+                         int32_t* h_class_out, void* stream);
+
+/*
+ * Compress (Section III-D quantisation encoder without predictor + Huffman entropy encoder; Section III-E
+ * single launch sequence writing all tables into one buffer at scanned offsets).
+ *   d_payload    DEVICE  [T][B][D], 16-byte aligned
+ *   d_out        DEVICE  container, 16-byte aligned, `out_capacity` bytes; never written past capacity
+ *   d_out_bytes  DEVICE  uint64[1+T]: [0] container bytes (0 on failure), [1+t] bytes attributable to table t
+ * Asynchronous on `stream`.  DLC_ESTATE if bounds were never set.  Capacity overflow is detected on the GPU
+ * before the overflowing write: d_out_bytes[0] = 0 and dlc_sync_status returns DLC_ECAPACITY.
+ */
+int dlc_compress(dlc_ctx* ctx, const void* d_payload, void* d_out, size_t out_capacity, uint64_t* d_out_bytes,
+                 void* stream);
+
+/*
+ * Decompress (chunk-parallel decoding, Section III-E) a container produced for this context's geometry.
+ *   d_comp        DEVICE  container, 16-byte aligned, comp_bytes long
+ *   d_payload_out DEVICE  [T][B][D] in the context's dtype, 16-byte aligned, out_capacity >= T*B*D*sizeof(dtype)
+ * Asynchronous on `stream`.  The container is self-describing (geometry, per-table bounds, code lengths); it is
+ * validated on the GPU and a mismatch or inconsistency is reported by dlc_sync_status as DLC_ECORRUPT, in
+ * which case the output holds unspecified values but no access left the two buffers.
+ */
+int dlc_decompress(dlc_ctx* ctx, const void* d_comp, size_t comp_bytes, void* d_payload_out, size_t out_capacity,
+                   void* stream);
+
+/* Waits for `stream`, returns the first device-side error since the previous call (DLC_OK if none), clears it. */
+int dlc_sync_status(dlc_ctx* ctx, void* stream);
+
+/*
+ * Inspection for tests (each synchronises `stream`):
+ *   dlc_quantize       symbols (uint16, DEVICE, T*B*D) of d_payload at the current bounds -- the quantiser alone
+ *   dlc_read_histogram the code histogram (uint32[T][2R], HOST) left by the last dlc_compress
+ *   dlc_read_codebook  code lengths (uint8[T][2R]) and codewords (uint16[T][2R]) left by the last dlc_compress
+ */
+int dlc_quantize(dlc_ctx* ctx, const void* d_payload, uint16_t* d_symbols, void* stream);
+int dlc_read_histogram(dlc_ctx* ctx, uint32_t* h_hist, void* stream);
+int dlc_read_codebook(dlc_ctx* ctx, uint8_t* h_len, uint16_t* h_code, void* stream);
+
+/*
+ * Kernel timing with HIP events on the caller's stream.
+ *   dlc_profile_enable  level 0 off; 1 = the two dominant kernels (encode, decode); 2 = every kernel
+ *   dlc_profile_read    synchronises, returns the number of kernel slots; for slot i < max_slots:
+ *                       names[i] (static string), total_ms[i], launches[i]; then resets the counters
+ */
+int dlc_profile_enable(dlc_ctx* ctx, int level);
+int dlc_profile_read(dlc_ctx* ctx, int max_slots, const char** names, float* total_ms, int32_t* launches);
+
+const char* dlc_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DLC_H */

@@ -1,0 +1,206 @@
+"""ctypes binding of libdlc.so: argument marshalling only -- every step runs in the HIP kernels.
+
+PyTorch is used for device memory and streams.  There is no CPU fallback: if the library is missing
+or cannot be loaded, importing names from here raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libdlc.so")
+
+F32, F16 = 0, 1
+OK, EINVAL, ENOMEM, ECAPACITY, ECORRUPT, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6
+CLASS_SMALL, CLASS_MEDIUM, CLASS_LARGE = 0, 1, 2
+DECAY_NONE, DECAY_STEPWISE, DECAY_DROP = 0, 1, 2
+
+
+class Config(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("num_tables", C.c_int32), ("batch", C.c_int64), ("dim", C.c_int64),
+                ("radius", C.c_int32), ("chunk_symbols", C.c_int32), ("max_code_len", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+class TableStats(C.Structure):
+    _fields_ = [("min", C.c_float), ("max", C.c_float), ("count", C.c_uint64), ("n_rows", C.c_uint32),
+                ("n_unique_raw", C.c_uint32), ("n_unique_quant", C.c_uint32), ("probe_eb", C.c_float)]
+
+
+class ControllerParams(C.Structure):
+    _fields_ = [("mode", C.c_int32), ("decay_kind", C.c_int32), ("global_eb", C.c_double), ("alpha", C.c_double),
+                ("beta", C.c_double), ("h_large", C.c_double), ("h_small", C.c_double),
+                ("decay_start", C.c_int64), ("decay_len", C.c_int64), ("decay_steps", C.c_int32),
+                ("reserved", C.c_int32), ("decay_mult0", C.c_double), ("eb_min", C.c_double),
+                ("eb_max", C.c_double), ("rel_floor", C.c_double)]
+
+
+EXPORTS = ["dlc_create", "dlc_destroy", "dlc_compress_bound", "dlc_workspace_bytes", "dlc_stats",
+           "dlc_set_error_bounds", "dlc_compress", "dlc_decompress", "dlc_sync_status", "dlc_quantize",
+           "dlc_read_histogram", "dlc_read_codebook", "dlc_profile_enable", "dlc_profile_read", "dlc_strerror"]
+
+_lib = None
+
+
+def lib():
+    """Loads libdlc.so (built beforehand by ``paper_2407_04272_amd.build`` / ``__graft_entry__.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2407_04272_amd.build` "
+                               "(there is no fallback path)")
+        L = C.CDLL(_LIB_PATH)
+        vp, i32, i64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
+        L.dlc_create.argtypes = [C.POINTER(vp), C.POINTER(Config)]
+        L.dlc_destroy.argtypes = [vp]
+        L.dlc_destroy.restype = None
+        L.dlc_compress_bound.argtypes = [C.POINTER(Config)]
+        L.dlc_compress_bound.restype = sz
+        L.dlc_workspace_bytes.argtypes = [C.POINTER(Config)]
+        L.dlc_workspace_bytes.restype = sz
+        L.dlc_stats.argtypes = [vp, vp, vp, C.POINTER(TableStats), vp]
+        L.dlc_set_error_bounds.argtypes = [vp, C.POINTER(TableStats), C.POINTER(ControllerParams), vp, i64, vp, vp, vp]
+        L.dlc_compress.argtypes = [vp, vp, vp, sz, vp, vp]
+        L.dlc_decompress.argtypes = [vp, vp, sz, vp, sz, vp]
+        L.dlc_sync_status.argtypes = [vp, vp]
+        L.dlc_quantize.argtypes = [vp, vp, vp, vp]
+        L.dlc_read_histogram.argtypes = [vp, vp, vp]
+        L.dlc_read_codebook.argtypes = [vp, vp, vp, vp]
+        L.dlc_profile_enable.argtypes = [vp, i32]
+        L.dlc_profile_read.argtypes = [vp, i32, vp, vp, vp]
+        L.dlc_strerror.argtypes = [i32]
+        L.dlc_strerror.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def dlc_strerror(status: int) -> str:
+    return lib().dlc_strerror(status).decode()
+
+
+class DlcError(RuntimeError):
+    def __init__(self, status, where):
+        super().__init__(f"{where}: {dlc_strerror(status)} ({status})")
+        self.status = status
+
+
+def _check(status, where):
+    if status != OK:
+        raise DlcError(status, where)
+
+
+def make_config(dtype, T, B, D, radius=512, chunk_symbols=256, max_code_len=12) -> Config:
+    return Config(dtype, T, B, D, radius, chunk_symbols, max_code_len, 0)
+
+
+def dlc_compress_bound(cfg: Config) -> int:
+    return int(lib().dlc_compress_bound(C.byref(cfg)))
+
+
+def dlc_workspace_bytes(cfg: Config) -> int:
+    return int(lib().dlc_workspace_bytes(C.byref(cfg)))
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(int(stream.cuda_stream))
+
+
+def _np_ptr(a):
+    return a.ctypes.data_as(C.c_void_p) if a is not None else None
+
+
+class Context:
+    """One geometry; owns the library context.  Methods carry the C entry points' names without the prefix."""
+
+    def __init__(self, cfg: Config):
+        self.cfg = cfg
+        self._h = C.c_void_p()
+        _check(lib().dlc_create(C.byref(self._h), C.byref(cfg)), "dlc_create")
+        self.T, self.B, self.D = cfg.num_tables, cfg.batch, cfg.dim
+        self.K = 2 * cfg.radius
+
+    def close(self):
+        if self._h:
+            lib().dlc_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- statistics and controller ----
+    def stats(self, d_payload, probe_eb, stream=None):
+        pe = np.ascontiguousarray(np.broadcast_to(np.asarray(probe_eb, np.float32), (self.T,)))
+        out = (TableStats * self.T)()
+        _check(lib().dlc_stats(self._h, C.c_void_p(d_payload.data_ptr()), _np_ptr(pe), out, _stream_ptr(stream)),
+               "dlc_stats")
+        return out
+
+    def set_error_bounds(self, eb=None, stats=None, params: ControllerParams | None = None, class_override=None,
+                         iteration: int = 0, stream=None):
+        """explicit: set_error_bounds(eb=...);  derived: set_error_bounds(stats=..., params=...).
+        -> (eb float32[T], class int32[T] or None)"""
+        if stats is None:
+            ebs = np.ascontiguousarray(np.broadcast_to(np.asarray(eb, np.float32), (self.T,))).copy()
+            st = lib().dlc_set_error_bounds(self._h, None, None, None, iteration, _np_ptr(ebs), None,
+                                            _stream_ptr(stream))
+            _check(st, "dlc_set_error_bounds")
+            return ebs, None
+        ebs = np.zeros(self.T, np.float32)
+        cls = np.zeros(self.T, np.int32)
+        ov = np.ascontiguousarray(class_override, np.int32) if class_override is not None else None
+        st = lib().dlc_set_error_bounds(self._h, stats, C.byref(params), _np_ptr(ov), iteration, _np_ptr(ebs),
+                                        _np_ptr(cls), _stream_ptr(stream))
+        _check(st, "dlc_set_error_bounds")
+        return ebs, cls
+
+    # ---- compress / decompress ----
+    def compress(self, d_payload, d_out, d_out_bytes, stream=None, capacity=None):
+        cap = d_out.numel() * d_out.element_size() if capacity is None else capacity
+        return lib().dlc_compress(self._h, C.c_void_p(d_payload.data_ptr()), C.c_void_p(d_out.data_ptr()), cap,
+                                  C.c_void_p(d_out_bytes.data_ptr()), _stream_ptr(stream))
+
+    def decompress(self, d_comp, comp_bytes, d_payload_out, stream=None):
+        cap = d_payload_out.numel() * d_payload_out.element_size()
+        return lib().dlc_decompress(self._h, C.c_void_p(d_comp.data_ptr()), comp_bytes,
+                                    C.c_void_p(d_payload_out.data_ptr()), cap, _stream_ptr(stream))
+
+    def sync_status(self, stream=None) -> int:
+        return lib().dlc_sync_status(self._h, _stream_ptr(stream))
+
+    # ---- inspection ----
+    def quantize(self, d_payload, d_symbols, stream=None):
+        _check(lib().dlc_quantize(self._h, C.c_void_p(d_payload.data_ptr()), C.c_void_p(d_symbols.data_ptr()),
+                                  _stream_ptr(stream)), "dlc_quantize")
+
+    def read_histogram(self, stream=None) -> np.ndarray:
+        h = np.zeros((self.T, self.K), np.uint32)
+        _check(lib().dlc_read_histogram(self._h, _np_ptr(h), _stream_ptr(stream)), "dlc_read_histogram")
+        return h
+
+    def read_codebook(self, stream=None):
+        ln = np.zeros((self.T, self.K), np.uint8)
+        code = np.zeros((self.T, self.K), np.uint16)
+        _check(lib().dlc_read_codebook(self._h, _np_ptr(ln), _np_ptr(code), _stream_ptr(stream)), "dlc_read_codebook")
+        return ln, code
+
+    def profile_enable(self, level: int):
+        _check(lib().dlc_profile_enable(self._h, level), "dlc_profile_enable")
+
+    def profile_read(self) -> dict:
+        n = 16
+        names = (C.c_char_p * n)()
+        ms = (C.c_float * n)()
+        cnt = (C.c_int32 * n)()
+        k = lib().dlc_profile_read(self._h, n, names, ms, cnt)
+        if k < 0:
+            raise DlcError(k, "dlc_profile_read")
+        return {names[i].decode(): (float(ms[i]), int(cnt[i])) for i in range(min(k, n))}

@@ -1,0 +1,444 @@
+// Host side of libdlc: context, argument checks, workspace, error-bound controller, C ABI.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <vector>
+
+#include "dlc_internal.h"
+
+namespace dlc {
+hipError_t compress_set_attributes();
+
+struct Prof {
+    int level = 0;
+    struct Rec { int slot; hipEvent_t a, b; };
+    std::vector<Rec> recs;       // recorded pairs awaiting read-out
+    std::vector<hipEvent_t> pool;
+    hipEvent_t pending[P_NSLOTS] = {};
+    float total_ms[P_NSLOTS] = {};
+    int32_t launches[P_NSLOTS] = {};
+    hipEvent_t get() {
+        if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        (void)hipEventCreate(&e);
+        return e;
+    }
+};
+
+void prof_begin(void* p, int slot, hipStream_t s) {
+    Prof* pr = static_cast<Prof*>(p);
+    hipEvent_t e = pr->get();
+    (void)hipEventRecord(e, s);
+    pr->pending[slot] = e;
+}
+void prof_end(void* p, int slot, hipStream_t s) {
+    Prof* pr = static_cast<Prof*>(p);
+    hipEvent_t e = pr->get();
+    (void)hipEventRecord(e, s);
+    pr->recs.push_back({slot, pr->pending[slot], e});
+}
+
+static const char* kSlotNames[P_NSLOTS] = {"k_zero", "k_hist", "k_codebook", "k_layout", "k_encode", "k_finalize",
+                                           "k_dec_prepare", "k_decode", "k_outliers"};
+}  // namespace dlc
+
+using namespace dlc;
+
+struct dlc_ctx {
+    dlc_config cfg;
+    Geom g;
+    Ws ws;
+    int device = 0;
+    bool bounds_set = false;
+    uint64_t epoch = 0;
+    uint32_t stats_M = 0;
+    Prof prof;
+    // pinned staging ring for the per-table quantiser parameters (one slot per set_error_bounds call)
+    static constexpr int kRing = 16;
+    QParam* pin = nullptr;
+    hipEvent_t pin_ev[kRing] = {};
+    bool pin_used[kRing] = {};
+    int pin_next = 0;
+};
+
+static size_t a256(size_t x) { return (x + 255) & ~size_t(255); }
+
+static bool make_geom(const dlc_config* c, Geom* g) {
+    if (!c) return false;
+    if (c->dtype != DLC_F32 && c->dtype != DLC_F16) return false;
+    if (c->num_tables < 1 || c->batch < 1 || c->dim < 1) return false;
+    if (c->batch > 0x7FFFFFFFll || c->dim > 0x7FFFFFFFll) return false;
+    const uint64_t n = (uint64_t)c->batch * (uint64_t)c->dim;
+    if (n > 0x7FFFFFFFull) return false;
+    const int R = c->radius;
+    if (R < 8 || R > 2048 || (R & (R - 1))) return false;
+    const int L = c->max_code_len;
+    if (L < 1 || L > kLmaxLimit || (1 << L) < 2 * R) return false;
+    const int S = c->chunk_symbols;
+    if (S != 64 && S != 128 && S != 256) return false;
+    if (c->reserved != 0) return false;
+    const uint64_t GS = (uint64_t)kW * S;
+    const uint64_t G = (n + GS - 1) / GS;
+    const uint64_t NG = G * (uint64_t)c->num_tables;
+    if (NG * GS > 0xFFFFFFFFull) return false;                                 // element positions are 32-bit
+    if (NG * kW * (((uint64_t)S * L + 31) / 32) > 0xFFFFFFFFull) return false;  // word offsets are 32-bit
+    g->T = (uint32_t)c->num_tables; g->B = (uint32_t)c->batch; g->D = (uint32_t)c->dim; g->n = (uint32_t)n;
+    g->G = (uint32_t)G; g->NG = (uint32_t)NG; g->S = (uint32_t)S; g->R = (uint32_t)R; g->K = 2u * R;
+    g->LMAX = (uint32_t)L; g->dtype = (uint32_t)c->dtype; g->es = c->dtype == DLC_F16 ? 2u : 4u;
+    g->vec = (n % 4 == 0) ? 1u : 0u;
+    return true;
+}
+
+static size_t a16(size_t x) { return (x + 15) & ~size_t(15); }
+
+extern "C" size_t dlc_compress_bound(const dlc_config* cfg) {
+    Geom g;
+    if (!make_geom(cfg, &g)) return 0;
+    size_t off = a16(kHeaderBytes + (size_t)kDirBytes * g.T);
+    off = a16(off + (size_t)g.T * ((g.K + 3) & ~3u));
+    off = a16(off + 4 * (size_t)g.NG);
+    off = a16(off + (size_t)kW * g.NG);
+    off = a16(off + 8 * (size_t)g.n * g.T);
+    const size_t wpc = ((size_t)g.S * g.LMAX + 31) / 32;
+    return off + 4 * wpc * kW * g.NG;
+}
+
+// carve the workspace; with base == nullptr only sizes are computed
+static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        uint8_t* p = base ? base + off : nullptr;
+        off = a256(off + bytes);
+        return p;
+    };
+    uint8_t* qp = take(sizeof(QParam) * g.T);
+    // cleared per call: histograms, escape totals, first 16 bytes of the control block
+    size_t z0 = off;
+    uint8_t* hist = base ? base + off : nullptr;
+    off += (size_t)g.T * g.K * 4;
+    uint8_t* tout = base ? base + off : nullptr;
+    off += a16((size_t)g.T * 4);
+    uint8_t* ctrl = base ? base + off : nullptr;
+    size_t z1 = off + 16;
+    off = a256(off + sizeof(Ctrl));
+    uint8_t* gout = take(4 * (size_t)g.NG);
+    uint8_t* gbase = take(4 * (size_t)g.NG);
+    uint8_t* tmeta = take(sizeof(TMeta) * g.T);
+    uint8_t* lay = take(sizeof(Layout));
+    uint8_t* enc = take(2 * (size_t)g.T * g.K);
+    uint8_t* lens = take((size_t)g.T * g.K);
+    uint8_t* state = take(8 * (size_t)g.NG);
+    uint8_t* ws0 = take(4 * (size_t)g.T);
+    uint8_t* ws1 = take(4 * (size_t)g.T);
+    uint8_t* lut = take(((size_t)g.T << g.LMAX) * 2);
+    uint8_t* dlay = take(sizeof(DecLayout));
+    uint8_t* dtab = take(sizeof(DecTable) * g.T);
+    if (w) {
+        w->base = base; w->bytes = off;
+        w->qp = (QParam*)qp;
+        w->zero_begin = base ? base + z0 : nullptr; w->zero_end = base ? base + z1 : nullptr;
+        w->hist = (uint32_t*)hist; w->table_outliers = (uint32_t*)tout; w->ctrl = (Ctrl*)ctrl; w->ctrl_call = (Ctrl*)ctrl;
+        w->group_outliers = (uint32_t*)gout; w->group_out_base = (uint32_t*)gbase; w->tmeta = (TMeta*)tmeta;
+        w->layout = (Layout*)lay; w->enc = (uint16_t*)enc; w->lens = lens; w->state = (uint64_t*)state;
+        w->word_start = (uint32_t*)ws0; w->word_end = (uint32_t*)ws1; w->lut = (uint16_t*)lut;
+        w->dlay = (DecLayout*)dlay; w->dtab = (DecTable*)dtab;
+    }
+    return off;
+}
+
+extern "C" size_t dlc_workspace_bytes(const dlc_config* cfg) {
+    Geom g;
+    if (!make_geom(cfg, &g)) return 0;
+    return carve(g, nullptr, nullptr);
+}
+
+extern "C" int dlc_create(dlc_ctx** out, const dlc_config* cfg) {
+    if (!out) return DLC_EINVAL;
+    *out = nullptr;
+    Geom g;
+    if (!make_geom(cfg, &g)) return DLC_EINVAL;
+    dlc_ctx* c = new (std::nothrow) dlc_ctx();
+    if (!c) return DLC_ENOMEM;
+    c->cfg = *cfg;
+    c->g = g;
+    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return DLC_EHIP; }
+    const size_t bytes = carve(g, nullptr, nullptr);
+    uint8_t* base = nullptr;
+    if (hipMalloc((void**)&base, bytes) != hipSuccess) { (void)hipGetLastError(); delete c; return DLC_ENOMEM; }
+    if (hipMemset(base, 0, bytes) != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }
+    carve(g, base, &c->ws);
+    if (compress_set_attributes() != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }
+    if (hipHostMalloc((void**)&c->pin, sizeof(QParam) * g.T * dlc_ctx::kRing, hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipFree(base);
+        delete c;
+        return DLC_ENOMEM;
+    }
+    for (int i = 0; i < dlc_ctx::kRing; ++i)
+        if (hipEventCreateWithFlags(&c->pin_ev[i], hipEventDisableTiming) != hipSuccess) {
+            dlc_destroy(c);
+            return DLC_EHIP;
+        }
+    *out = c;
+    return DLC_OK;
+}
+
+extern "C" void dlc_destroy(dlc_ctx* c) {
+    if (!c) return;
+    (void)hipDeviceSynchronize();
+    for (auto& r : c->prof.recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    for (auto e : c->prof.pool) (void)hipEventDestroy(e);
+    for (int i = 0; i < dlc_ctx::kRing; ++i)
+        if (c->pin_ev[i]) (void)hipEventDestroy(c->pin_ev[i]);
+    if (c->pin) (void)hipHostFree(c->pin);
+    if (c->ws.base) (void)hipFree(c->ws.base);
+    if (c->ws.stats_base) (void)hipFree(c->ws.stats_base);
+    delete c;
+}
+
+static QParam make_qparam(float eb) {
+    QParam q;
+    q.eb = eb;
+    q.ebx2 = eb * 2.0f;
+    q.inv = (float)(1.0 / (double)q.ebx2);
+    std::memcpy(&q.eb_bits, &eb, 4);
+    return q;
+}
+
+static bool good_eb(float e) { return e > 0.0f && std::isfinite(e); }
+
+// ---- Algorithm 1 -----------------------------------------------------------------------------------
+static int classify(double eta, const dlc_controller_params* p) {
+    if (eta > p->h_small) return DLC_CLASS_SMALL;
+    if (eta < p->h_large) return DLC_CLASS_LARGE;
+    return DLC_CLASS_MEDIUM;
+}
+
+static double iteration_multiplier(const dlc_controller_params* p, int64_t i) {
+    if (p->decay_kind == DLC_DECAY_NONE || p->decay_len <= 0) return 1.0;
+    const int64_t end = p->decay_start + p->decay_len;
+    if (i >= end) return 1.0;
+    if (p->decay_kind == DLC_DECAY_DROP || i < p->decay_start) return p->decay_mult0;
+    const int64_t steps = p->decay_steps;
+    if (steps < 1) return 1.0;
+    int64_t s = ((i - p->decay_start) * steps) / p->decay_len;
+    if (s >= steps) return 1.0;
+    return p->decay_mult0 - (p->decay_mult0 - 1.0) * (double)s / (double)steps;
+}
+
+extern "C" int dlc_set_error_bounds(dlc_ctx* c, const dlc_table_stats* st, const dlc_controller_params* p,
+                                    const int32_t* cls_override, int64_t iteration, float* eb, int32_t* cls_out,
+                                    void* stream) {
+    if (!c || !eb) return DLC_EINVAL;
+    const uint32_t T = c->g.T;
+    if (st) {
+        if (!p) return DLC_EINVAL;
+        if (p->decay_kind < DLC_DECAY_NONE || p->decay_kind > DLC_DECAY_DROP || (p->mode != 0 && p->mode != 1))
+            return DLC_EINVAL;
+        const double mult = iteration_multiplier(p, iteration);
+        for (uint32_t t = 0; t < T; ++t) {
+            const double eta = ((double)st[t].n_unique_raw - (double)st[t].n_unique_quant) / (double)st[t].n_unique_raw;
+            int cls = classify(eta, p);
+            if (cls_override && cls_override[t] >= 0) cls = cls_override[t];
+            if (cls < DLC_CLASS_SMALL || cls > DLC_CLASS_LARGE) return DLC_EINVAL;
+            const double range = (double)st[t].max - (double)st[t].min;
+            double e = p->mode == 1 ? p->global_eb * range : p->global_eb;
+            if (cls == DLC_CLASS_LARGE) e = e * p->alpha;
+            if (cls == DLC_CLASS_SMALL) e = e / p->beta;
+            e = e * mult;
+            if (p->eb_min > 0.0 && e < p->eb_min) e = p->eb_min;
+            if (p->eb_max > 0.0 && e > p->eb_max) e = p->eb_max;
+            if (p->rel_floor > 0.0) {
+                const double f = p->rel_floor * range;
+                if (e < f) e = f;
+            }
+            eb[t] = (float)e;
+            if (cls_out) cls_out[t] = cls;
+        }
+    }
+    for (uint32_t t = 0; t < T; ++t)
+        if (!good_eb(eb[t])) return DLC_EINVAL;
+    const int slot = c->pin_next;
+    c->pin_next = (slot + 1) % dlc_ctx::kRing;
+    if (c->pin_used[slot] && hipEventSynchronize(c->pin_ev[slot]) != hipSuccess) return DLC_EHIP;  // copy 16 calls ago
+    QParam* h = c->pin + (size_t)slot * T;
+    for (uint32_t t = 0; t < T; ++t) h[t] = make_qparam(eb[t]);
+    if (hipMemcpyAsync(c->ws.qp, h, sizeof(QParam) * T, hipMemcpyHostToDevice, (hipStream_t)stream) != hipSuccess)
+        return DLC_EHIP;
+    if (hipEventRecord(c->pin_ev[slot], (hipStream_t)stream) != hipSuccess) return DLC_EHIP;
+    c->pin_used[slot] = true;
+    c->bounds_set = true;
+    return DLC_OK;
+}
+
+static bool aligned16(const void* p) { return p && (((uintptr_t)p) & 15u) == 0; }
+
+extern "C" int dlc_compress(dlc_ctx* c, const void* d_payload, void* d_out, size_t cap, uint64_t* d_out_bytes,
+                            void* stream) {
+    if (!c || !aligned16(d_payload) || !aligned16(d_out) || !d_out_bytes || (((uintptr_t)d_out_bytes) & 7u))
+        return DLC_EINVAL;
+    if (!c->bounds_set) return DLC_ESTATE;
+    if (cap < kHeaderBytes) return DLC_ECAPACITY;
+    c->epoch += 1;
+    if (c->epoch >= (1ull << 30)) {  // look-back records carry a 30-bit call counter
+        if (hipMemsetAsync(c->ws.state, 0, 8 * (size_t)c->g.NG, (hipStream_t)stream) != hipSuccess) return DLC_EHIP;
+        c->epoch = 1;
+    }
+    hipError_t e = launch_compress(c->g, d_payload, (uint8_t*)d_out, cap, d_out_bytes, c->ws, c->epoch, c->prof.level,
+                                   &c->prof, (hipStream_t)stream);
+    return e == hipSuccess ? DLC_OK : DLC_EHIP;
+}
+
+extern "C" int dlc_decompress(dlc_ctx* c, const void* d_comp, size_t comp_bytes, void* d_out, size_t cap, void* stream) {
+    if (!c || !aligned16(d_comp) || !aligned16(d_out)) return DLC_EINVAL;
+    if (cap < (size_t)c->g.n * c->g.T * c->g.es) return DLC_ECAPACITY;
+    if (comp_bytes < kHeaderBytes) return DLC_ECORRUPT;
+    hipError_t e = launch_decompress(c->g, (const uint8_t*)d_comp, comp_bytes, d_out, c->ws, c->prof.level, &c->prof,
+                                     (hipStream_t)stream);
+    return e == hipSuccess ? DLC_OK : DLC_EHIP;
+}
+
+extern "C" int dlc_sync_status(dlc_ctx* c, void* stream) {
+    if (!c) return DLC_EINVAL;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return DLC_EHIP;
+    int32_t st = 0;
+    if (hipMemcpy(&st, &c->ws.ctrl->status, 4, hipMemcpyDeviceToHost) != hipSuccess) return DLC_EHIP;
+    if (st != 0) {
+        if (hipMemset(&c->ws.ctrl->status, 0, 4) != hipSuccess) return DLC_EHIP;
+    }
+    return st;
+}
+
+static float ord_dec(uint32_t o) {
+    uint32_t b = (o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o;
+    float f;
+    std::memcpy(&f, &b, 4);
+    return f;
+}
+
+extern "C" int dlc_stats(dlc_ctx* c, const void* d_payload, const float* probe_eb, dlc_table_stats* out, void* stream) {
+    if (!c || !aligned16(d_payload) || !probe_eb || !out) return DLC_EINVAL;
+    const Geom& g = c->g;
+    for (uint32_t t = 0; t < g.T; ++t)
+        if (!good_eb(probe_eb[t])) return DLC_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    Ws& w = c->ws;
+    if (!w.stats_base) {
+        uint32_t M = 64;
+        while (M < 2ull * g.B) M <<= 1;
+        size_t off = 0;
+        auto take = [&](size_t b) { size_t o = off; off = a256(off + b); return o; };
+        const size_t o_probe = take(sizeof(QParam) * g.T);
+        const size_t o_keys = take(2ull * g.T * M * 8);
+        const size_t o_owner = take(2ull * g.T * M * 4);
+        const size_t o_hash = take(2ull * g.T * g.B * 8);
+        const size_t o_mm = take(8ull * g.T);
+        const size_t o_un = take(8ull * g.T);
+        uint8_t* base = nullptr;
+        if (hipMalloc((void**)&base, off) != hipSuccess) { (void)hipGetLastError(); return DLC_ENOMEM; }
+        w.stats_base = base; w.stats_bytes = off;
+        w.probe = (QParam*)(base + o_probe); w.keys = (uint64_t*)(base + o_keys); w.owner = (uint32_t*)(base + o_owner);
+        w.rowhash = (uint64_t*)(base + o_hash); w.st_minmax = (uint32_t*)(base + o_mm); w.st_unique = (uint32_t*)(base + o_un);
+        c->stats_M = M;
+    }
+    const uint32_t M = c->stats_M;
+    std::vector<QParam> pq(g.T);
+    for (uint32_t t = 0; t < g.T; ++t) pq[t] = make_qparam(probe_eb[t]);
+    std::vector<uint32_t> mm(2 * g.T), un(2 * g.T);
+    for (uint32_t attempt = 0; attempt < 4; ++attempt) {
+        std::vector<uint32_t> mm0(2 * g.T);
+        for (uint32_t t = 0; t < g.T; ++t) { mm0[2 * t] = 0xFFFFFFFFu; mm0[2 * t + 1] = 0u; }
+        if (hipMemcpyAsync(w.probe, pq.data(), sizeof(QParam) * g.T, hipMemcpyHostToDevice, s) != hipSuccess) return DLC_EHIP;
+        if (hipMemcpyAsync(w.st_minmax, mm0.data(), 8ull * g.T, hipMemcpyHostToDevice, s) != hipSuccess) return DLC_EHIP;
+        if (hipMemsetAsync(w.keys, 0, 2ull * g.T * M * 8, s) != hipSuccess) return DLC_EHIP;
+        if (hipMemsetAsync(w.owner, 0xFF, 2ull * g.T * M * 4, s) != hipSuccess) return DLC_EHIP;
+        if (hipMemsetAsync(w.st_unique, 0, 8ull * g.T, s) != hipSuccess) return DLC_EHIP;
+        if (hipMemsetAsync(&w.ctrl->collide, 0, 4, s) != hipSuccess) return DLC_EHIP;
+        if (hipStreamSynchronize(s) != hipSuccess) return DLC_EHIP;  // staging vectors above are reused per attempt
+        if (launch_stats(g, d_payload, w.probe, w, M, 0x51ED270Bu * (attempt + 1), s) != hipSuccess) return DLC_EHIP;
+        uint32_t collide = 0;
+        if (hipMemcpyAsync(mm.data(), w.st_minmax, 8ull * g.T, hipMemcpyDeviceToHost, s) != hipSuccess) return DLC_EHIP;
+        if (hipMemcpyAsync(un.data(), w.st_unique, 8ull * g.T, hipMemcpyDeviceToHost, s) != hipSuccess) return DLC_EHIP;
+        if (hipMemcpyAsync(&collide, &w.ctrl->collide, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return DLC_EHIP;
+        if (hipStreamSynchronize(s) != hipSuccess) return DLC_EHIP;
+        const int st = dlc_sync_status(c, stream);
+        if (st != DLC_OK) return st;
+        if (collide == 0) {
+            for (uint32_t t = 0; t < g.T; ++t) {
+                out[t].min = mm[2 * t] == 0xFFFFFFFFu ? std::numeric_limits<float>::infinity() : ord_dec(mm[2 * t]);
+                out[t].max = mm[2 * t + 1] == 0u ? -std::numeric_limits<float>::infinity() : ord_dec(mm[2 * t + 1]);
+                out[t].count = g.n;
+                out[t].n_rows = g.B;
+                out[t].n_unique_raw = un[2 * t];
+                out[t].n_unique_quant = un[2 * t + 1];
+                out[t].probe_eb = probe_eb[t];
+            }
+            return DLC_OK;
+        }
+    }
+    return DLC_ESTATE;  // four different hash salts all collided: not expected
+}
+
+extern "C" int dlc_quantize(dlc_ctx* c, const void* d_payload, uint16_t* d_sym, void* stream) {
+    if (!c || !aligned16(d_payload) || !d_sym) return DLC_EINVAL;
+    if (!c->bounds_set) return DLC_ESTATE;
+    if (launch_quantize(c->g, d_payload, c->ws.qp, d_sym, (hipStream_t)stream) != hipSuccess) return DLC_EHIP;
+    return hipStreamSynchronize((hipStream_t)stream) == hipSuccess ? DLC_OK : DLC_EHIP;
+}
+
+extern "C" int dlc_read_histogram(dlc_ctx* c, uint32_t* h_hist, void* stream) {
+    if (!c || !h_hist) return DLC_EINVAL;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return DLC_EHIP;
+    return hipMemcpy(h_hist, c->ws.hist, 4ull * c->g.T * c->g.K, hipMemcpyDeviceToHost) == hipSuccess ? DLC_OK : DLC_EHIP;
+}
+
+extern "C" int dlc_read_codebook(dlc_ctx* c, uint8_t* h_len, uint16_t* h_code, void* stream) {
+    if (!c || !h_len || !h_code) return DLC_EINVAL;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return DLC_EHIP;
+    const size_t n = (size_t)c->g.T * c->g.K;
+    if (hipMemcpy(h_len, c->ws.lens, n, hipMemcpyDeviceToHost) != hipSuccess) return DLC_EHIP;
+    if (hipMemcpy(h_code, c->ws.enc, 2 * n, hipMemcpyDeviceToHost) != hipSuccess) return DLC_EHIP;
+    for (size_t i = 0; i < n; ++i) h_code[i] &= 0x0FFFu;
+    return DLC_OK;
+}
+
+extern "C" int dlc_profile_enable(dlc_ctx* c, int level) {
+    if (!c || level < 0 || level > 2) return DLC_EINVAL;
+    c->prof.level = level;
+    return DLC_OK;
+}
+
+extern "C" int dlc_profile_read(dlc_ctx* c, int max_slots, const char** names, float* total_ms, int32_t* launches) {
+    if (!c) return DLC_EINVAL;
+    Prof& p = c->prof;
+    for (auto& r : p.recs) {
+        if (hipEventSynchronize(r.b) != hipSuccess) return DLC_EHIP;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) { p.total_ms[r.slot] += ms; p.launches[r.slot] += 1; }
+        p.pool.push_back(r.a);
+        p.pool.push_back(r.b);
+    }
+    p.recs.clear();
+    for (int i = 0; i < P_NSLOTS && i < max_slots; ++i) {
+        if (names) names[i] = kSlotNames[i];
+        if (total_ms) total_ms[i] = p.total_ms[i];
+        if (launches) launches[i] = p.launches[i];
+    }
+    for (int i = 0; i < P_NSLOTS; ++i) { p.total_ms[i] = 0.f; p.launches[i] = 0; }
+    return P_NSLOTS;
+}
+
+extern "C" const char* dlc_strerror(int s) {
+    switch (s) {
+        case DLC_OK: return "ok";
+        case DLC_EINVAL: return "invalid argument";
+        case DLC_ENOMEM: return "out of device memory";
+        case DLC_ECAPACITY: return "output capacity too small";
+        case DLC_ECORRUPT: return "corrupt or mismatching container";
+        case DLC_EHIP: return "HIP runtime error";
+        case DLC_ESTATE: return "bad call order or internal invariant";
+        default: return "unknown status";
+    }
+}

@@ -1,0 +1,271 @@
+// Decompression kernels for gfx950: container validation + decode tables, chunk-parallel decode,
+// escape scatter.
+#include <algorithm>
+
+#include "dlc_internal.h"
+
+namespace dlc {
+
+__device__ __forceinline__ uint64_t d_a16(uint64_t x) { return (x + 15ull) & ~15ull; }
+
+// ------------------------------------------------------------------------------------------------
+// One work-group per table: checks the header against the context's geometry and the table's
+// directory entry against the header, rebuilds the canonical code from the stored lengths and fills
+// the table's decode table: entry[i] = len << 12 | symbol for the codeword that prefixes the LMAX-bit
+// string i.  Anything inconsistent marks the table (or the whole container) invalid.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp, uint64_t comp_bytes, uint16_t* lut,
+                                                     DecLayout* dlay, DecTable* dtab, Ctrl* ctrl) {
+    __shared__ uint32_t s_ok;
+    __shared__ uint32_t s_cl[kLmaxLimit + 2], s_first[kLmaxLimit + 2], s_index[kLmaxLimit + 2];
+    __shared__ uint16_t s_sorted[4096];
+    __shared__ uint8_t s_len[4096];
+    const uint32_t tid = threadIdx.x, t = blockIdx.x;
+    const uint32_t* h = reinterpret_cast<const uint32_t*>(comp);
+    const uint64_t* q = reinterpret_cast<const uint64_t*>(comp);
+    DecLayout L;
+    bool ok = comp_bytes >= kHeaderBytes + (uint64_t)kDirBytes * g.T;
+    if (ok) {
+        ok = h[H_MAGIC] == kMagic && h[H_VERSION] == kVersion && h[H_DTYPE] == g.dtype && h[H_T] == g.T &&
+             h[H_B] == g.B && h[H_D] == g.D && h[H_R] == g.R && h[H_S] == g.S && h[H_LMAX] == g.LMAX &&
+             h[H_W] == kW && h[H_V] == kV && h[H_NG] == g.NG;
+    }
+    uint64_t off_cb = 0, n_out = 0, total = 0;
+    if (ok) {
+        n_out = q[HQ_NOUT];
+        L.words_total = q[HQ_WORDS];
+        off_cb = q[HQ_OFF_CB];
+        L.off_group = q[HQ_OFF_GROUP]; L.off_chunk = q[HQ_OFF_CHUNK]; L.off_outl = q[HQ_OFF_OUTL];
+        L.off_payload = q[HQ_OFF_PAYLOAD];
+        total = q[HQ_TOTAL];
+        ok = total <= comp_bytes && off_cb == d_a16(kHeaderBytes + (uint64_t)kDirBytes * g.T) &&
+             L.off_group >= off_cb && (L.off_group & 15ull) == 0 && L.off_group <= total &&
+             L.off_chunk == d_a16(L.off_group + 4ull * g.NG) && L.off_outl == d_a16(L.off_chunk + (uint64_t)kW * g.NG) &&
+             n_out <= (uint64_t)g.n * g.T && L.off_payload == d_a16(L.off_outl + 8ull * n_out) &&
+             L.words_total <= 0xFFFFFFFFull && total == L.off_payload + 4ull * L.words_total;
+    }
+    if (t == 0 && tid == 0) {
+        L.valid = ok; L.pad = 0;
+        *dlay = L;
+        if (!ok) set_status(ctrl, DLC_ECORRUPT);
+    }
+    DecTable D;
+    D.valid = 0; D.n_used = 0; D.sym_lo = 0; D.n_outliers = 0; D.outl_off = 0; D.ebx2 = 0.f; D.pad = 0;
+    uint32_t sym_lo = 0, sym_hi = 0, n_used = 0;
+    uint64_t cb = 0;
+    if (ok) {
+        const uint8_t* d = comp + kHeaderBytes + (uint64_t)kDirBytes * t;
+        const uint32_t* d32 = reinterpret_cast<const uint32_t*>(d);
+        const uint64_t* d64 = reinterpret_cast<const uint64_t*>(d + 24);
+        const float eb = __uint_as_float(d32[0]);
+        n_used = d32[1]; sym_lo = d32[2]; sym_hi = d32[3];
+        D.n_outliers = d32[4];
+        cb = d64[0];
+        D.outl_off = d64[1];
+        ok = eb > 0.f && eb < __builtin_inff() && d32[5] == g.G && sym_lo <= sym_hi && sym_hi < g.K && n_used >= 1 &&
+             n_used <= sym_hi - sym_lo + 1u && cb >= off_cb && cb + (sym_hi - sym_lo + 1u) <= L.off_group &&
+             D.outl_off >= L.off_outl && ((D.outl_off - L.off_outl) & 7ull) == 0 &&
+             D.outl_off + 8ull * D.n_outliers <= L.off_payload && D.n_outliers <= g.n;
+        D.ebx2 = eb * 2.0f;
+        D.sym_lo = sym_lo;
+        D.n_used = n_used;
+    }
+    if (tid == 0) s_ok = ok;
+    if (tid < kLmaxLimit + 2) s_cl[tid] = 0;
+    __syncthreads();
+    const uint32_t nl = ok ? sym_hi - sym_lo + 1u : 0u;
+    for (uint32_t i = tid; i < nl; i += 256) {
+        const uint32_t l = comp[cb + i];
+        s_len[i] = (uint8_t)l;
+        if (l > g.LMAX) s_ok = 0;
+        else if (l) atomicAdd(&s_cl[l], 1u);
+    }
+    __syncthreads();
+    const bool ok2 = s_ok != 0;  // every thread reads the same value, then nobody writes before the barrier
+    __syncthreads();
+    uint16_t* my_lut = lut + ((size_t)t << g.LMAX);
+    const uint32_t lut_n = 1u << g.LMAX;
+    if (ok2 && n_used == 1) {
+        if (tid == 0 && (sym_lo != sym_hi || s_len[0] != 0)) s_ok = 0;
+        for (uint32_t i = tid; i < lut_n; i += 256) my_lut[i] = (uint16_t)sym_lo;  // length 0
+    } else if (ok2) {
+        if (tid == 0) {
+            uint64_t kraft = 0;
+            uint32_t cnt = 0, code = 0, index = 0;
+            for (uint32_t l = 1; l <= g.LMAX; ++l) {
+                kraft += (uint64_t)s_cl[l] << (g.LMAX - l);
+                cnt += s_cl[l];
+                code <<= 1;
+                s_first[l] = code;
+                s_index[l] = index;
+                code += s_cl[l];
+                index += s_cl[l];
+            }
+            if (kraft != (1ull << g.LMAX) || cnt != n_used) s_ok = 0;
+            else {
+                uint32_t fill[kLmaxLimit + 2];
+                for (uint32_t l = 1; l <= g.LMAX; ++l) fill[l] = s_index[l];
+                for (uint32_t i = 0; i < nl; ++i) {
+                    const uint32_t l = s_len[i];
+                    if (l) s_sorted[fill[l]++] = (uint16_t)(sym_lo + i);
+                }
+            }
+        }
+        __syncthreads();
+        const bool ok3 = s_ok != 0;
+        if (ok3) {
+            for (uint32_t i = tid; i < lut_n; i += 256) {
+                uint32_t entry = 0;
+                for (uint32_t l = 1; l <= g.LMAX; ++l) {
+                    const uint32_t c = i >> (g.LMAX - l);
+                    const uint32_t rel = c - s_first[l];
+                    if (c >= s_first[l] && rel < s_cl[l]) {
+                        entry = (l << 12) | s_sorted[s_index[l] + rel];
+                        break;
+                    }
+                }
+                my_lut[i] = (uint16_t)entry;
+            }
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        D.valid = s_ok;
+        dtab[t] = D;
+        if (!s_ok) set_status(ctrl, DLC_ECORRUPT);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// chunk-parallel decode: one wavefront per group, lane l walks chunk l.  Each lane keeps a 64-bit
+// window of its own bit stream, looks LMAX bits up in the table's LDS decode table, and the four
+// symbols of a turn leave as one 16-byte store (1 KiB contiguous per wavefront instruction).
+// ------------------------------------------------------------------------------------------------
+template <bool F16, bool VEC>
+__global__ __launch_bounds__(512) void k_decode(Geom g, const uint8_t* comp, const uint16_t* lut, const DecLayout* dlay,
+                                                const DecTable* dtab, Ctrl* ctrl, void* outp, uint32_t bpt) {
+    extern __shared__ uint16_t s_lut[];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t t = blockIdx.x / bpt, b = blockIdx.x % bpt;
+    const DecLayout L = *dlay;
+    const DecTable D = dtab[t];
+    if (!L.valid || !D.valid) return;  // uniform over the work-group
+    const uint32_t lut_n = 1u << g.LMAX;
+    {
+        const uint4* src = reinterpret_cast<const uint4*>(lut + ((size_t)t << g.LMAX));
+        uint4* dst = reinterpret_cast<uint4*>(s_lut);
+        for (uint32_t i = tid; i < lut_n / 8; i += 512) dst[i] = src[i];
+    }
+    __syncthreads();
+    const uint32_t grp = b * 8 + wave;
+    if (grp >= g.G) return;
+    const uint32_t gid = t * g.G + grp;
+    const uint32_t cw = comp[L.off_chunk + (uint64_t)gid * kW + lane];
+    const uint32_t incl = wave_incl_scan(cw, lane);
+    const uint32_t total = __shfl(incl, 63, 64);
+    const uint64_t goff = reinterpret_cast<const uint32_t*>(comp + L.off_group)[gid];
+    if (goff + total > L.words_total) {
+        if (lane == 0) set_status(ctrl, DLC_ECORRUPT);
+        return;
+    }
+    const uint32_t* p = reinterpret_cast<const uint32_t*>(comp + L.off_payload) + goff + (incl - cw);
+    const uint32_t* pend = p + cw;
+    uint64_t buf = 0;
+    if (p < pend) buf = (uint64_t)(*p++) << 32;
+    if (p < pend) buf |= (uint64_t)(*p++);
+    uint32_t nb = 64;  // bits of buf in use (bits past the end of the chunk read as zero)
+    const float ebx2 = D.ebx2;
+    const int R = (int)g.R;
+    const uint32_t shift = 64u - g.LMAX;
+    uint8_t* tab = static_cast<uint8_t*>(outp) + (size_t)t * g.n * g.es;
+    const uint32_t base = grp * (kW * g.S) + lane * kV;
+    const uint32_t turns = g.S / kV;
+    for (uint32_t j = 0; j < turns; ++j) {
+        const uint32_t idx = base + j * (kW * kV);
+        if (idx >= g.n) break;
+        float v4[4];
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+            if (nb <= 32u) {
+                const uint64_t wv = p < pend ? (uint64_t)(*p++) : 0ull;
+                buf |= wv << (32u - nb);
+                nb += 32u;
+            }
+#pragma unroll
+            for (int v = 0; v < 2; ++v) {
+                const uint32_t e = s_lut[(uint32_t)(buf >> shift)];
+                const uint32_t len = e >> 12;
+                buf <<= len;
+                nb -= len;
+                v4[h2 * 2 + v] = (float)((int)(e & 0xFFFu) - R) * ebx2;
+            }
+        }
+        if constexpr (VEC) {
+            if constexpr (F16) {
+                uint2 o;
+                o.x = (uint32_t)__half_as_ushort(__float2half_rn(v4[0])) |
+                      ((uint32_t)__half_as_ushort(__float2half_rn(v4[1])) << 16);
+                o.y = (uint32_t)__half_as_ushort(__float2half_rn(v4[2])) |
+                      ((uint32_t)__half_as_ushort(__float2half_rn(v4[3])) << 16);
+                *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(tab) + idx) = o;
+            } else {
+                *reinterpret_cast<float4*>(reinterpret_cast<float*>(tab) + idx) = make_float4(v4[0], v4[1], v4[2], v4[3]);
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (idx + v < g.n) {
+                    if constexpr (F16) reinterpret_cast<__half*>(tab)[idx + v] = __float2half_rn(v4[v]);
+                    else reinterpret_cast<float*>(tab)[idx + v] = v4[v];
+                }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// escapes: verbatim values back into place
+// ------------------------------------------------------------------------------------------------
+template <bool F16>
+__global__ __launch_bounds__(256) void k_outliers(Geom g, const uint8_t* comp, const DecLayout* dlay,
+                                                  const DecTable* dtab, Ctrl* ctrl, void* outp) {
+    if (!dlay->valid) return;
+    const uint32_t gtid = blockIdx.x * blockDim.x + threadIdx.x, gsz = gridDim.x * blockDim.x;
+    for (uint32_t t = 0; t < g.T; ++t) {
+        const DecTable D = dtab[t];
+        if (!D.valid || D.n_outliers == 0) continue;
+        const uint32_t* rec = reinterpret_cast<const uint32_t*>(comp + D.outl_off);
+        uint8_t* tab = static_cast<uint8_t*>(outp) + (size_t)t * g.n * g.es;
+        for (uint32_t i = gtid; i < D.n_outliers; i += gsz) {
+            const uint32_t idx = rec[2ull * i], raw = rec[2ull * i + 1];
+            if (idx >= g.n) { set_status(ctrl, DLC_ECORRUPT); continue; }
+            if constexpr (F16) reinterpret_cast<uint16_t*>(tab)[idx] = (uint16_t)raw;
+            else reinterpret_cast<uint32_t*>(tab)[idx] = raw;
+        }
+    }
+}
+
+hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_bytes, void* out, const Ws& w, int pl,
+                             void* prof, hipStream_t s) {
+    const bool f16 = g.dtype == DLC_F16;
+    if (prof_on(pl, P_DEC_PREPARE)) prof_begin(prof, P_DEC_PREPARE, s);
+    hipLaunchKernelGGL(k_dec_prepare, dim3(g.T), dim3(256), 0, s, g, comp, comp_bytes, w.lut, w.dlay, w.dtab, w.ctrl);
+    if (prof_on(pl, P_DEC_PREPARE)) prof_end(prof, P_DEC_PREPARE, s);
+    {
+        const uint32_t bpt = (g.G + 7) / 8;
+        dim3 grid(g.T * bpt), block(512);
+        const size_t sm = (size_t)2 << g.LMAX;
+        if (prof_on(pl, P_DECODE)) prof_begin(prof, P_DECODE, s);
+#define DLC_DEC(F, V) hipLaunchKernelGGL((k_decode<F, V>), grid, block, sm, s, g, comp, w.lut, w.dlay, w.dtab, w.ctrl, out, bpt)
+        if (f16) { if (g.vec) DLC_DEC(true, true); else DLC_DEC(true, false); }
+        else { if (g.vec) DLC_DEC(false, true); else DLC_DEC(false, false); }
+#undef DLC_DEC
+        if (prof_on(pl, P_DECODE)) prof_end(prof, P_DECODE, s);
+    }
+    if (prof_on(pl, P_OUTLIERS)) prof_begin(prof, P_OUTLIERS, s);
+    if (f16) hipLaunchKernelGGL(k_outliers<true>, dim3(512), dim3(256), 0, s, g, comp, w.dlay, w.dtab, w.ctrl, out);
+    else hipLaunchKernelGGL(k_outliers<false>, dim3(512), dim3(256), 0, s, g, comp, w.dlay, w.dtab, w.ctrl, out);
+    if (prof_on(pl, P_OUTLIERS)) prof_end(prof, P_OUTLIERS, s);
+    return hipGetLastError();
+}
+
+}  // namespace dlc

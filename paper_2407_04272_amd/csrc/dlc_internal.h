@@ -1,0 +1,204 @@
+// Internal declarations shared by the HIP sources of libdlc (gfx950 only).
+#pragma once
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dlc.h"
+
+namespace dlc {
+
+// ---- container constants (byte layout of the compressed buffer) -----------------------------
+constexpr uint32_t kW = 64;  // chunks per group = lanes of one wavefront
+constexpr uint32_t kV = 4;   // consecutive symbols a chunk takes per turn = one 16-byte fp32 load per lane
+constexpr uint32_t kMagic = 0x31434C44u;
+constexpr uint32_t kVersion = 1u;
+constexpr uint32_t kHeaderBytes = 128;
+constexpr uint32_t kDirBytes = 56;
+constexpr int kLmaxLimit = 12;
+
+// header word / qword positions
+enum { H_MAGIC = 0, H_VERSION, H_DTYPE, H_T, H_B, H_D, H_R, H_S, H_LMAX, H_W, H_V, H_NG };  // u32 index
+enum { HQ_NOUT = 6, HQ_WORDS, HQ_OFF_CB, HQ_OFF_GROUP, HQ_OFF_CHUNK, HQ_OFF_OUTL, HQ_OFF_PAYLOAD, HQ_TOTAL };  // u64 index
+
+struct QParam {
+    float eb, ebx2, inv;
+    uint32_t eb_bits;
+};
+
+struct Geom {
+    uint32_t T, B, D;
+    uint32_t n;   // B*D symbols per table
+    uint32_t G;   // groups per table
+    uint32_t NG;  // T*G
+    uint32_t S, R, K, LMAX;
+    uint32_t dtype, es;
+    uint32_t vec;  // 1: every table starts on a 16-byte (fp32) / 8-byte (fp16) boundary and n % 4 == 0
+};
+
+// per-table results of the codebook step
+struct TMeta {
+    uint32_t n_used, sym_lo, sym_hi, n_outliers;
+    uint64_t cb_off;    // byte offset of the table's code-length block
+    uint64_t outl_off;  // byte offset of its first escape record
+};
+
+// section offsets of the container being written
+struct Layout {
+    uint64_t off_cb, off_group, off_chunk, off_outl, off_payload;
+    uint64_t n_out_total;
+};
+
+// small control block; `status` is sticky until read by the host, the rest is cleared per call
+struct Ctrl {
+    uint32_t ticket;  // ordered work-group ids of the encode kernel
+    uint32_t abort;   // set when the output capacity would be exceeded
+    uint32_t pad0, pad1;
+    int32_t status;   // first device-side error
+    uint32_t collide; // statistics: a hash match whose rows differ
+};
+
+struct DecLayout {
+    uint32_t valid;
+    uint32_t pad;
+    uint64_t off_group, off_chunk, off_outl, off_payload, words_total;
+};
+
+struct DecTable {
+    uint32_t valid, n_used, sym_lo, n_outliers;
+    uint64_t outl_off;
+    float ebx2;
+    uint32_t pad;
+};
+
+// ---- device helpers -----------------------------------------------------------------------------
+#if defined(__HIPCC__)
+
+__device__ __forceinline__ void set_status(Ctrl* c, int32_t code) { atomicCAS(&c->status, 0, code); }
+
+// Quantisation encoder without predictor: bin = rne(x / 2eb), taken as one binary32 multiply by the
+// rounded reciprocal; escape (symbol 0) when the bin is outside (-R, R) or the reconstruction misses eb.
+template <bool F16>
+__device__ __forceinline__ uint32_t quant_symbol(float x, const QParam& q, float Rf, int R) {
+    float r = __builtin_rintf(x * q.inv);
+    float xh = r * q.ebx2;
+    if constexpr (F16) xh = __half2float(__float2half_rn(xh));
+    float d = x - xh;
+    bool ok = (__builtin_fabsf(r) < Rf) && (__builtin_fabsf(d) <= q.eb);
+    return ok ? (uint32_t)((int)r + R) : 0u;
+}
+
+// Four consecutive elements of a group: `gbase` points at the group's first element (uniform over the
+// wavefront), `off` is the element offset inside the group (off % 4 == 0, off < 64*S), `rem` the number of
+// table elements from the group's start on.  Returns the mask of valid positions (off + v < rem); raw[]
+// holds the bit patterns.  Branch-free: a position past the end reads the group's first element instead
+// (always a legal address) and is masked out, so that the loads of several turns can be in flight together;
+// offsets stay 32-bit so that one scalar base and one small vector offset address every load.
+template <bool F16, bool VEC>
+__device__ __forceinline__ uint32_t load4(const void* gbase, uint32_t off, uint32_t rem, float x[4], uint32_t raw[4]) {
+    const char* gb = static_cast<const char*>(gbase);
+    if constexpr (VEC) {
+        const bool in = off < rem;
+        const uint32_t o2 = in ? off : 0u;
+        if constexpr (F16) {
+            uint2 w = *reinterpret_cast<const uint2*>(gb + o2 * 2u);
+            raw[0] = w.x & 0xFFFFu; raw[1] = w.x >> 16; raw[2] = w.y & 0xFFFFu; raw[3] = w.y >> 16;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) x[v] = __half2float(__ushort_as_half((unsigned short)raw[v]));
+        } else {
+            uint4 w = *reinterpret_cast<const uint4*>(gb + o2 * 4u);
+            raw[0] = w.x; raw[1] = w.y; raw[2] = w.z; raw[3] = w.w;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) x[v] = __uint_as_float(raw[v]);
+        }
+        return in ? 0xFu : 0u;
+    } else {
+        uint32_t m = 0;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const bool in = off + v < rem;
+            const uint32_t o2 = in ? off + v : 0u;
+            m |= in ? (1u << v) : 0u;
+            if constexpr (F16) {
+                raw[v] = *reinterpret_cast<const uint16_t*>(gb + o2 * 2u);
+                x[v] = __half2float(__ushort_as_half((unsigned short)raw[v]));
+            } else {
+                raw[v] = *reinterpret_cast<const uint32_t*>(gb + o2 * 4u);
+                x[v] = __uint_as_float(raw[v]);
+            }
+        }
+        return m;
+    }
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, uint32_t lane) {
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t u = __shfl_up(v, o, 64);
+        if (lane >= (uint32_t)o) v += u;
+    }
+    return v;
+}
+
+#endif  // __HIPCC__
+
+// ---- kernel launchers (defined next to their kernels) --------------------------------------------
+struct Ws;  // workspace, see dlc_api.hip
+
+hipError_t launch_quantize(const Geom& g, const void* payload, const QParam* qp, uint16_t* sym, hipStream_t s);
+hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uint64_t capacity, uint64_t* out_bytes,
+                           const Ws& w, uint64_t epoch, int prof_level, void* prof, hipStream_t s);
+hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_bytes, void* out, const Ws& w,
+                             int prof_level, void* prof, hipStream_t s);
+hipError_t launch_stats(const Geom& g, const void* payload, const QParam* probe, const Ws& w, uint32_t M, uint32_t salt,
+                        hipStream_t s);
+
+// device workspace of a context
+struct Ws {
+    uint8_t* base = nullptr;
+    size_t bytes = 0;
+    // compress
+    QParam* qp = nullptr;          // [T]
+    uint8_t* zero_begin = nullptr; // region cleared at the start of every compress call
+    uint32_t* hist = nullptr;      // [T][K]
+    uint32_t* table_outliers = nullptr;  // [T]
+    Ctrl* ctrl_call = nullptr;     // ticket, abort (inside the cleared region)
+    uint8_t* zero_end = nullptr;
+    Ctrl* ctrl = nullptr;          // same block as ctrl_call (status/collide are not cleared by the kernels)
+    uint32_t* group_outliers = nullptr;  // [NG]
+    uint32_t* group_out_base = nullptr;  // [NG]
+    TMeta* tmeta = nullptr;        // [T]
+    Layout* layout = nullptr;
+    uint16_t* enc = nullptr;       // [T][K]  len << 12 | codeword
+    uint8_t* lens = nullptr;       // [T][K]
+    uint64_t* state = nullptr;     // [NG] look-back records
+    uint32_t* word_start = nullptr;  // [T]
+    uint32_t* word_end = nullptr;    // [T]
+    // decompress
+    uint16_t* lut = nullptr;       // [T][1 << LMAX]  len << 12 | symbol
+    DecLayout* dlay = nullptr;
+    DecTable* dtab = nullptr;      // [T]
+    // statistics (allocated on first use)
+    uint8_t* stats_base = nullptr;
+    size_t stats_bytes = 0;
+    QParam* probe = nullptr;       // [T]
+    uint64_t* keys = nullptr;      // [2][T][M]
+    uint32_t* owner = nullptr;     // [2][T][M]
+    uint64_t* rowhash = nullptr;   // [2][T][B]
+    uint32_t* st_minmax = nullptr; // [T][2] order-preserving encodings
+    uint32_t* st_unique = nullptr; // [T][2]
+};
+
+// profiling hooks used by the launchers (implemented in dlc_api.hip)
+void prof_begin(void* prof, int slot, hipStream_t s);
+void prof_end(void* prof, int slot, hipStream_t s);
+enum ProfSlot { P_ZERO = 0, P_HIST, P_CODEBOOK, P_LAYOUT, P_ENCODE, P_FINALIZE, P_DEC_PREPARE, P_DECODE, P_OUTLIERS,
+                P_NSLOTS };
+inline bool prof_on(int level, int slot) { return level >= 2 || (level == 1 && (slot == P_ENCODE || slot == P_DECODE || slot == P_HIST)); }
+
+}  // namespace dlc

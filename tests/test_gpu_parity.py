@@ -1,0 +1,245 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bar: bit-exact symbols, histograms, code lengths, codewords, containers, sizes and chosen bounds;
+reconstructions equal to the oracle's bit for bit (the allowed 1 ulp is not needed) and within
+|x - x^| <= eb * (1 + 1e-6) on every finite element.
+"""
+import numpy as np
+import pytest
+
+import dlc_workloads as W
+import oracle
+from gpu_util import GpuRun, to_device
+
+pytestmark = pytest.mark.gpu
+
+R = 512
+
+
+def _payload(T, B, D, seed, sigma=0.02, dtype=np.float32, rows=50):
+    rng = np.random.default_rng(seed)
+    table = (rng.standard_normal((rows, D)) * sigma).astype(np.float32)
+    idx = rng.integers(0, rows, (T, B))
+    x = table[idx] * (1 + np.arange(T, dtype=np.float32)[:, None, None])
+    return x.astype(dtype)
+
+
+def _check_bound(x, rec, ebs):
+    for t in range(x.shape[0]):
+        fin = np.isfinite(x[t])
+        err = np.abs(x[t][fin].astype(np.float64) - rec[t][fin].astype(np.float64))
+        assert np.all(err <= float(ebs[t]) * (1 + 1e-6)), t
+    nf = ~np.isfinite(x)
+    u = np.uint32 if x.dtype == np.float32 else np.uint16
+    assert np.array_equal(rec[nf].view(u), x[nf].view(u))
+
+
+def _full_parity(x, eb, S=256, LMAX=12, Rr=R):
+    T = x.shape[0]
+    ebs = np.broadcast_to(np.asarray(eb, np.float32), (T,))
+    g = GpuRun(x, ebs, R=Rr, S=S, LMAX=LMAX)
+    o = oracle.compress(x, ebs, Rr, S, LMAX)
+    assert g.rc == 0 and g.status == 0 and o.rc == 0
+    assert g.guard_ok
+    assert g.total == o.data.size
+    assert np.array_equal(g.sizes, o.sizes)
+    diff = np.nonzero(g.data != o.data)[0]
+    assert diff.size == 0, f"first differing byte {diff[:8]} of {g.total}"
+    st, rec = g.decompress()
+    assert st == 0
+    rc, orec = oracle.decompress(o.data, x.shape, x.dtype)
+    assert rc == 0
+    u = np.uint32 if x.dtype == np.float32 else np.uint16
+    assert np.array_equal(rec.view(u), orec.view(u))
+    _check_bound(x, rec, ebs)
+    return g, o
+
+
+CASES = [  # T, B, D, S, eb, dtype
+    (1, 256, 16, 256, 1e-3, np.float32),     # less than one group
+    (2, 37, 13, 64, 2e-3, np.float32),       # ragged: B*D = 481 not a multiple of 4 (scalar loads), partial group
+    (3, 700, 64, 64, 5e-3, np.float32),      # 11 groups per table, the last one partial; work-groups with idle waves
+    (1, 3, 1, 64, 1e-3, np.float32),         # three symbols
+    (2, 64, 8, 128, 1.0, np.float32),        # eb above the data: one symbol, empty payload
+    (5, 1031, 17, 128, 3e-3, np.float32),    # odd sizes, scalar path, several groups
+    (2, 4096, 64, 256, 2e-3, np.float32),    # 16 full groups per table
+    (2, 300, 32, 64, 2.0 ** -10 * 0.3, np.float16),   # fp16 with percent-level escapes
+    (3, 129, 7, 64, 2.0 ** -9 * 0.3, np.float16),     # fp16 scalar path
+]
+
+
+@pytest.mark.parametrize("T,B,D,S,eb,dtype", CASES)
+def test_container_and_round_trip_bit_exact(T, B, D, S, eb, dtype):
+    print(f"case T={T} B={B} D={D} S={S} eb={eb} {np.dtype(dtype).name}", flush=True)
+    x = _payload(T, B, D, 7 * B + D, dtype=dtype)
+    flat = x.reshape(-1)
+    flat[::97] = 1e4 if dtype == np.float32 else 6e4          # out-of-range escapes
+    flat[5::1013] = np.nan
+    flat[11::2027] = np.inf
+    flat[3::31] = 0.0
+    flat[4::61] = -0.0
+    if dtype == np.float32:
+        flat[6::511] = 1e-42                                   # subnormal inputs
+    _full_parity(x, eb, S=S)
+
+
+def test_symbols_histogram_codebook_bit_exact():
+    import torch
+    x = _payload(3, 500, 48, 3)
+    x.reshape(-1)[::211] = 123.0
+    ebs = np.array([1e-3, 3e-3, 2e-2], np.float32)
+    g = GpuRun(x, ebs, S=64)
+    d_sym = torch.zeros(x.size, dtype=torch.int16, device="cuda")
+    g.ctx.quantize(g.d_payload, d_sym)
+    sym = d_sym.cpu().numpy().view(np.uint16).reshape(x.shape)
+    hist = g.ctx.read_histogram()
+    ln, code = g.ctx.read_codebook()
+    for t in range(3):
+        osym, _ = oracle.quantize(x[t], float(ebs[t]), R)
+        assert np.array_equal(sym[t], osym)
+        oh = oracle.histogram(osym, 2 * R)
+        assert np.array_equal(hist[t].astype(np.uint64), oh)
+        ol, oc, _, _ = oracle.codebook(oh, 12)
+        assert np.array_equal(ln[t], ol)
+        assert np.array_equal(code[t].astype(np.uint32), oc)
+
+
+def test_length_limited_codebook_matches():
+    """Fibonacci-like symbol counts push Huffman beyond LMAX: the halving rule must agree bit for bit."""
+    fib = [1, 1]
+    while len(fib) < 27:
+        fib.append(fib[-1] + fib[-2])
+    vals = np.repeat(np.arange(27), fib).astype(np.float32) * np.float32(0.02)
+    rng = np.random.default_rng(0)
+    rng.shuffle(vals)
+    x = vals[: (vals.size // 64) * 64].reshape(1, -1, 64)
+    g, o = _full_parity(x, 0.01, S=256)
+    ln, _ = g.ctx.read_codebook()
+    assert ln.max() == 12
+
+
+def test_wide_alphabet_and_other_radius():
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal((2, 600, 32)) * 0.05).astype(np.float32)
+    _full_parity(x, 2e-4, S=128)                      # ~ +-1000 bins wanted: hundreds of symbols plus escapes
+    _full_parity(x, 2e-3, S=64, LMAX=10, Rr=64)       # small alphabet, short maximum code
+    _full_parity(x, 5e-4, S=64, LMAX=12, Rr=2048)     # largest alphabet
+
+
+def test_workload1_and_2():
+    w1 = W.workload1()
+    g, o = _full_parity(w1.payload, w1.meta["eb"])
+    assert abs(w1.payload.nbytes / g.total - w1.payload.nbytes / o.data.size) == 0
+    w2 = W.workload2()
+    # statistics and controller, then compression at the derived bounds
+    import torch
+    from paper_2407_04272_amd import binding as b
+    x = w2.payload
+    T = x.shape[0]
+    d = to_device(x)
+    ctx = b.Context(b.make_config(b.F32, *x.shape))
+    probe = np.full(T, w2.meta["global_eb"], np.float32)
+    st = ctx.stats(d, probe)
+    ost = oracle.stats(x, probe)
+    for t in range(T):
+        a, c = st[t], ost[t]
+        assert (a.min, a.max, a.count, a.n_rows, a.n_unique_raw, a.n_unique_quant, a.probe_eb) == \
+               (c.min, c.max, c.count, c.n_rows, c.n_unique_raw, c.n_unique_quant, c.probe_eb), t
+    p = b.ControllerParams(mode=0, decay_kind=0, global_eb=w2.meta["global_eb"], alpha=w2.meta["alpha"],
+                           beta=w2.meta["beta"], h_large=0.0, h_small=0.05, decay_start=0, decay_len=0,
+                           decay_steps=0, reserved=0, decay_mult0=1.0, eb_min=w2.meta["eb_min"],
+                           eb_max=w2.meta["eb_max"], rel_floor=0.0)
+    op = oracle.ControllerParams(**{f[0]: getattr(p, f[0]) for f in p._fields_})
+    ebs, cls = ctx.set_error_bounds(stats=st, params=p)
+    oeb, ocls = oracle.controller(ost, op, 0)
+    assert np.array_equal(ebs.view(np.uint32), oeb.view(np.uint32)) and np.array_equal(cls, ocls)
+    assert len(set(cls.tolist())) >= 2                 # the workload exercises more than one class
+    assert np.all(ebs >= np.float32(1e-4)) and np.all(ebs <= np.float32(1e-2))
+    g = GpuRun(x, ebs, ctx=ctx, d_payload=d)
+    o = oracle.compress(x, ebs)
+    assert g.status == 0 and np.array_equal(g.data, o.data) and np.array_equal(g.sizes, o.sizes)
+    st2, rec = g.decompress()
+    assert st2 == 0
+    _check_bound(x, rec, ebs)
+    assert any(tb == 1 for tb in [int(np.count_nonzero(h)) for h in g.ctx.read_histogram()])  # a constant table
+
+
+def test_stats_small_cases():
+    from paper_2407_04272_amd import binding as b
+    rng = np.random.default_rng(9)
+    for (T, B, D, dtype) in [(2, 40, 5, np.float32), (3, 300, 70, np.float32), (2, 257, 128, np.float16),
+                             (1, 1, 1, np.float32)]:
+        vals = rng.choice(np.linspace(-1, 1, 9), (T, B, D)).astype(np.float32)
+        vals += (rng.random((T, B, D)) < 0.2) * np.float32(0.003)
+        vals[0, 0, 0] = np.nan
+        if B > 2:
+            vals[0, 1] = -0.0
+            vals[0, 2] = 0.0
+        x = vals.astype(dtype)
+        ctx = b.Context(b.make_config(b.F16 if dtype == np.float16 else b.F32, T, B, D))
+        probe = np.full(T, 0.01, np.float32)
+        st = ctx.stats(to_device(x), probe)
+        ost = oracle.stats(x, probe)
+        for t in range(T):
+            a, c = st[t], ost[t]
+            assert (a.n_unique_raw, a.n_unique_quant, a.count, a.n_rows) == \
+                   (c.n_unique_raw, c.n_unique_quant, c.count, c.n_rows), (T, B, D, t)
+            assert a.min == c.min and a.max == c.max
+
+
+def test_errors_and_robustness():
+    import torch
+    from paper_2407_04272_amd import binding as b
+    x = _payload(2, 200, 32, 1)
+    ctx = b.Context(b.make_config(b.F32, 2, 200, 32, chunk_symbols=64))
+    d = to_device(x)
+    out = torch.zeros(b.dlc_compress_bound(ctx.cfg), dtype=torch.uint8, device="cuda")
+    sizes = torch.zeros(3, dtype=torch.int64, device="cuda")
+    assert ctx.compress(d, out, sizes) == b.ESTATE                                   # bounds never set
+    with pytest.raises(b.DlcError):
+        ctx.set_error_bounds(eb=[1e-3, 0.0])
+    with pytest.raises(b.DlcError):
+        ctx.set_error_bounds(eb=[1e-3, float("nan")])
+    ctx.set_error_bounds(eb=1e-3)
+    assert ctx.compress(d.view(torch.uint8).view(-1)[4:].view(torch.float32), out, sizes) == b.EINVAL   # misaligned
+    # exact capacity works, one byte less fails cleanly and writes nothing past the limit
+    g = GpuRun(x, 1e-3, S=64)
+    assert g.status == 0
+    g_exact = GpuRun(x, 1e-3, S=64, capacity=g.total)
+    assert g_exact.status == 0 and np.array_equal(g_exact.data, g.data) and g_exact.guard_ok
+    for cap in (g.total - 4, g.total // 2, 1024, 256):
+        bad = GpuRun(x, 1e-3, S=64, capacity=cap)
+        assert bad.status == b.ECAPACITY and bad.total == 0 and bad.guard_ok, cap
+    # the context keeps working after a failure
+    again = GpuRun(x, 1e-3, S=64)
+    assert again.status == 0 and np.array_equal(again.data, g.data)
+    # corrupt containers are rejected, never fault
+    import container_reader as cr
+    cont = cr.parse(g.data)
+    for mutate in ("magic", "truncated", "length", "kraft", "geometry", "total"):
+        bad = g.data.copy()
+        nbytes = None
+        if mutate == "magic":
+            bad[0] ^= 1
+        elif mutate == "truncated":
+            nbytes = bad.size - 8
+        elif mutate == "length":
+            bad[cont.tables[0].codebook_off] = 13
+        elif mutate == "kraft":
+            bad[cont.tables[1].codebook_off] += 1
+        elif mutate == "geometry":
+            bad[16] ^= 1
+        elif mutate == "total":
+            bad[104:112] = np.frombuffer(np.uint64(bad.size + 16).tobytes(), np.uint8)
+        st, _ = g.decompress(bad, nbytes)
+        assert st == b.ECORRUPT, mutate
+    st, rec = g.decompress(g.data)
+    assert st == 0
+
+
+def test_deterministic_bytes():
+    x = _payload(4, 3000, 64, 11)
+    a = GpuRun(x, 2e-3, S=256)
+    for _ in range(3):
+        c = GpuRun(x, 2e-3, S=256, ctx=a.ctx, d_payload=a.d_payload)
+        assert c.status == 0 and np.array_equal(a.data, c.data)
