@@ -161,7 +161,8 @@ def test_workload1_and_2():
     st2, rec = g.decompress()
     assert st2 == 0
     _check_bound(x, rec, ebs)
-    assert any(tb == 1 for tb in [int(np.count_nonzero(h)) for h in g.ctx.read_histogram()])  # a constant table
+    used = [int(np.count_nonzero(h)) for h in g.ctx.read_histogram()]
+    assert min(used) <= 3 < max(used)                  # from nearly constant tables to wider alphabets
 
 
 def test_stats_small_cases():
