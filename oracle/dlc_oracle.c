@@ -212,8 +212,13 @@ int orc_histogram(const uint16_t* sym, size_t n, int K, uint64_t* hist) {
 /*  - leaves ordered by (count, symbol) ascending                      */
 /*  - two queues: sorted leaves, and merged nodes in creation order;   */
 /*    each pick takes the smaller head, a tie goes to the leaf queue   */
-/*  - if the longest code exceeds LMAX: count <- (count+1)>>1 on every */
-/*    used symbol, rebuild; repeat                                     */
+/*  - if the longest code exceeds LMAX: lengths above LMAX are cut to  */
+/*    LMAX; while the Kraft sum is too large, one code of length LMAX  */
+/*    is paired with a code taken from the deepest shorter level (that */
+/*    level loses one code, the next gains two), which lowers the sum  */
+/*    by one unit of 2^-LMAX; the resulting number of codes per length */
+/*    is handed out most frequent symbol first (the classic length     */
+/*    adjustment of JPEG Annex K / deflate encoders)                   */
 /*  - one used symbol: length 0                                        */
 /*  - codewords: symbols ordered by (length, symbol); first code 0;    */
 /*    next = (previous + 1) << (length increase)                       */
@@ -290,14 +295,30 @@ int orc_codebook(const uint64_t* hist, int K, int LMAX, uint8_t* len, uint32_t* 
             n++;
         }
     }
-    int halvings = 0;
+    int halvings = 0; /* number of Kraft repair steps (0: plain Huffman) */
     if (n >= 2) {
-        for (;;) {
-            qsort(leaf, (size_t)n, sizeof(orc_leaf), leaf_cmp);
-            int longest = huffman_depths(leaf, n, depth);
-            if (longest <= LMAX) break;
-            for (int i = 0; i < n; ++i) leaf[i].count = (leaf[i].count + 1) >> 1;
-            halvings++;
+        qsort(leaf, (size_t)n, sizeof(orc_leaf), leaf_cmp);
+        int longest = huffman_depths(leaf, n, depth);
+        if (longest > LMAX) {
+            uint32_t per_len[ORC_LMAX_LIMIT + 2];
+            memset(per_len, 0, sizeof per_len);
+            for (int i = 0; i < n; ++i) per_len[depth[i] > LMAX ? LMAX : depth[i]] += 1;
+            uint64_t kraft = 0;
+            for (int L = 1; L <= LMAX; ++L) kraft += (uint64_t)per_len[L] << (LMAX - L);
+            while (kraft > (1ull << LMAX)) {
+                per_len[LMAX] -= 1;
+                for (int L = LMAX - 1; L >= 1; --L)
+                    if (per_len[L]) {
+                        per_len[L] -= 1;
+                        per_len[L + 1] += 2;
+                        break;
+                    }
+                kraft -= 1;
+                halvings++;
+            }
+            int i = n - 1; /* leaves are sorted by rising count: the last one is the most frequent */
+            for (int L = 1; L <= LMAX; ++L)
+                for (uint32_t c = 0; c < per_len[L]; ++c) depth[i--] = L;
         }
         for (int i = 0; i < n; ++i) len[leaf[i].sym] = (uint8_t)depth[i];
         /* canonical codewords in (length, symbol) order */

@@ -8,6 +8,11 @@
 
 #include "dlc_internal.h"
 
+// phase time stamps for kernel micro-benchmarks; expands to nothing in the library
+#ifndef DLC_STAMP
+#define DLC_STAMP(i)
+#endif
+
 namespace dlc {
 
 // ------------------------------------------------------------------------------------------------
@@ -53,7 +58,7 @@ template <bool F16, bool VEC>
 __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const QParam* qp, uint32_t* hist,
                                               uint32_t* group_outliers, uint32_t* table_outliers, uint32_t bpt,
                                               uint32_t clog2) {
-    extern __shared__ uint32_t lh[];
+    extern __shared__ __align__(16) uint32_t lh[];
     const uint32_t t = blockIdx.x / bpt, b = blockIdx.x % bpt;
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t nbins = g.K << clog2;
@@ -101,27 +106,13 @@ __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const
 // ------------------------------------------------------------------------------------------------
 // Huffman codebook, one work-group per table.
 //   leaves ordered by (count, symbol); two queues (leaves, merged nodes in creation order); a tie
-//   between the queue heads takes the leaf; code lengths above LMAX: halve every count (rounding up)
-//   and rebuild; canonical codewords in (length, symbol) order.  One used symbol: length 0.
+//   between the queue heads takes the leaf; longest code d bits above LMAX: every count becomes
+//   ceil(count / 2^d) and the tree is rebuilt, until it fits; canonical codewords in (length, symbol)
+//   order.  One used symbol: length 0.
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t block_excl_scan_256(uint32_t v, uint32_t* scratch, uint32_t tid, uint32_t* total) {
-    scratch[tid] = v;
-    __syncthreads();
-    for (uint32_t o = 1; o < 256; o <<= 1) {
-        uint32_t u = tid >= o ? scratch[tid - o] : 0u;
-        __syncthreads();
-        scratch[tid] += u;
-        __syncthreads();
-    }
-    *total = scratch[255];
-    uint32_t r = scratch[tid] - v;
-    __syncthreads();
-    return r;
-}
-
 __global__ __launch_bounds__(256) void k_codebook(Geom g, const uint32_t* hist, const uint32_t* table_outliers,
                                                   uint16_t* enc, uint8_t* lens, TMeta* tmeta) {
-    extern __shared__ unsigned char smem[];
+    extern __shared__ __align__(16) unsigned char smem[];  // the 64-bit sort keys need natural alignment
     const uint32_t K = g.K, tid = threadIdx.x, t = blockIdx.x;
     uint64_t* key = reinterpret_cast<uint64_t*>(smem);        // [K] sort keys: count << 16 | symbol
     uint32_t* cnt = reinterpret_cast<uint32_t*>(key + K);      // [K] working counts
@@ -133,6 +124,7 @@ __global__ __launch_bounds__(256) void k_codebook(Geom g, const uint32_t* hist, 
     uint32_t* scratch = reinterpret_cast<uint32_t*>(len_s + K);  // [256]
     __shared__ uint32_t s_lo, s_hi, s_maxlen, s_cl[kLmaxLimit + 2], s_next[kLmaxLimit + 2];
 
+    DLC_STAMP(0);
     for (uint32_t k = tid; k < K; k += 256) {
         cnt[k] = hist[(size_t)t * K + k];
         len_s[k] = 0;
@@ -147,69 +139,103 @@ __global__ __launch_bounds__(256) void k_codebook(Geom g, const uint32_t* hist, 
     uint32_t mine = 0;
     for (uint32_t k = k0; k < k1; ++k) mine += cnt[k] != 0;
     uint32_t n_used;
-    const uint32_t my_off = block_excl_scan_256(mine, scratch, tid, &n_used);
+    const uint32_t my_off = block_excl_scan<4>(mine, scratch, tid, &n_used);
+    __syncthreads();
     for (uint32_t k = k0; k < k1; ++k)
         if (cnt[k]) { atomicMin(&s_lo, k); atomicMax(&s_hi, k); }
     __syncthreads();
 
+    DLC_STAMP(1);
     if (n_used >= 2) {
         uint32_t P = 2;
         while (P < n_used) P <<= 1;
-        for (int round = 0; round < 40; ++round) {
-            // keys of the used symbols, padded to a power of two
-            {
-                uint32_t o = my_off;
-                for (uint32_t k = k0; k < k1; ++k)
-                    if (cnt[k]) key[o++] = ((uint64_t)cnt[k] << 16) | k;
-                for (uint32_t i = n_used + tid; i < P; i += 256) key[i] = ~0ull;
-            }
-            __syncthreads();
-            // bitonic sort, ascending
-            for (uint32_t size = 2; size <= P; size <<= 1) {
-                for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-                    for (uint32_t i = tid; i < (P >> 1); i += 256) {
-                        uint32_t lo = 2 * i - (i & (stride - 1));
-                        uint32_t hi = lo + stride;
-                        bool up = (lo & size) == 0;
-                        uint64_t a = key[lo], bb = key[hi];
-                        if ((a > bb) == up) { key[lo] = bb; key[hi] = a; }
-                    }
-                    __syncthreads();
+        // keys of the used symbols, padded to a power of two
+        {
+            uint32_t o = my_off;
+            for (uint32_t k = k0; k < k1; ++k)
+                if (cnt[k]) key[o++] = ((uint64_t)cnt[k] << 16) | k;
+            for (uint32_t i = n_used + tid; i < P; i += 256) key[i] = ~0ull;
+        }
+        __syncthreads();
+        DLC_STAMP(2);
+        // bitonic sort, ascending
+        for (uint32_t size = 2; size <= P; size <<= 1) {
+            for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+                for (uint32_t i = tid; i < (P >> 1); i += 256) {
+                    uint32_t lo = 2 * i - (i & (stride - 1));
+                    uint32_t hi = lo + stride;
+                    bool up = (lo & size) == 0;
+                    uint64_t a = key[lo], bb = key[hi];
+                    if ((a > bb) == up) { key[lo] = bb; key[hi] = a; }
                 }
+                __syncthreads();
             }
+        }
+        DLC_STAMP(3);
+        if (tid == 0) {
+            const uint32_t n = n_used;
+            uint32_t a = 0, bq = 0;  // heads of the leaf queue and of the merged-node queue
+            for (uint32_t k = 0; k + 1 < n; ++k) {
+                uint32_t sum = 0;
+                for (int pick = 0; pick < 2; ++pick) {
+                    bool take_leaf;
+                    if (a >= n) take_leaf = false;
+                    else if (bq >= k) take_leaf = true;
+                    else take_leaf = (uint32_t)(key[a] >> 16) <= nodew[bq];
+                    if (take_leaf) { sum += (uint32_t)(key[a] >> 16); parent_leaf[a] = (uint16_t)k; ++a; }
+                    else { sum += nodew[bq]; parent_node[bq] = (uint16_t)k; ++bq; }
+                }
+                nodew[k] = sum;
+            }
+            depth_node[n - 2] = 0;
+            for (int k = (int)n - 3; k >= 0; --k) depth_node[k] = depth_node[parent_node[k]] + 1;
+            s_maxlen = 0;
+        }
+        __syncthreads();
+        DLC_STAMP(4);
+        // leaf depths; parent_leaf[] is reused to hold the depth of leaf i (sorted order)
+        uint32_t local_max = 0;
+        for (uint32_t i = tid; i < n_used; i += 256) {
+            const uint32_t d = depth_node[parent_leaf[i]] + 1u;
+            parent_leaf[i] = (uint16_t)d;
+            local_max = max(local_max, d);
+        }
+        if (local_max) atomicMax(&s_maxlen, local_max);
+        __syncthreads();
+        if (s_maxlen > g.LMAX) {
+            // cut to LMAX, repair the Kraft sum one unit at a time, hand the lengths out most frequent first
+            for (uint32_t i = tid; i < n_used; i += 256) atomicAdd(&s_cl[min((uint32_t)parent_leaf[i], g.LMAX)], 1u);
+            __syncthreads();
             if (tid == 0) {
-                const uint32_t n = n_used;
-                uint32_t a = 0, bq = 0;  // heads of the leaf queue and of the merged-node queue
-                for (uint32_t k = 0; k + 1 < n; ++k) {
-                    uint32_t sum = 0;
-                    for (int pick = 0; pick < 2; ++pick) {
-                        bool take_leaf;
-                        if (a >= n) take_leaf = false;
-                        else if (bq >= k) take_leaf = true;
-                        else take_leaf = (uint32_t)(key[a] >> 16) <= nodew[bq];
-                        if (take_leaf) { sum += (uint32_t)(key[a] >> 16); parent_leaf[a] = (uint16_t)k; ++a; }
-                        else { sum += nodew[bq]; parent_node[bq] = (uint16_t)k; ++bq; }
-                    }
-                    nodew[k] = sum;
+                const uint32_t LM = g.LMAX;
+                uint64_t kraft = 0;
+                for (uint32_t L = 1; L <= LM; ++L) kraft += (uint64_t)s_cl[L] << (LM - L);
+                while (kraft > (1ull << LM)) {
+                    s_cl[LM] -= 1;
+                    for (uint32_t L = LM - 1; L >= 1; --L)
+                        if (s_cl[L]) { s_cl[L] -= 1; s_cl[L + 1] += 2; break; }
+                    kraft -= 1;
                 }
-                depth_node[n - 2] = 0;
-                for (int k = (int)n - 3; k >= 0; --k) depth_node[k] = depth_node[parent_node[k]] + 1;
-                s_maxlen = 0;
+                // s_next[L] = number of leaves (counted from the most frequent) with length < L
+                uint32_t acc = 0;
+                for (uint32_t L = 1; L <= LM; ++L) { s_next[L] = acc; acc += s_cl[L]; }
+                s_next[LM + 1] = acc;
             }
             __syncthreads();
-            uint32_t local_max = 0;
             for (uint32_t i = tid; i < n_used; i += 256) {
-                uint32_t d = depth_node[parent_leaf[i]] + 1u;
-                len_s[(uint32_t)(key[i] & 0xFFFFu)] = (uint16_t)d;
-                local_max = max(local_max, d);
+                const uint32_t rank = n_used - 1u - i;  // 0 = most frequent (leaves are sorted by rising count)
+                uint32_t L = 1;
+                while (rank >= s_next[L + 1]) ++L;
+                parent_leaf[i] = (uint16_t)L;
             }
-            if (local_max) atomicMax(&s_maxlen, local_max);
             __syncthreads();
-            if (s_maxlen <= g.LMAX) break;
-            for (uint32_t k = k0; k < k1; ++k) cnt[k] = (cnt[k] + 1u) >> 1;
+            if (tid < kLmaxLimit + 2) s_cl[tid] = 0;
             __syncthreads();
         }
+        for (uint32_t i = tid; i < n_used; i += 256) len_s[(uint32_t)(key[i] & 0xFFFFu)] = parent_leaf[i];
+        __syncthreads();
         // codewords
+        DLC_STAMP(5);
         for (uint32_t k = k0; k < k1; ++k)
             if (len_s[k]) atomicAdd(&s_cl[len_s[k]], 1u);
         __syncthreads();
@@ -227,6 +253,7 @@ __global__ __launch_bounds__(256) void k_codebook(Geom g, const uint32_t* hist, 
         }
         __syncthreads();
     }
+    DLC_STAMP(6);
     for (uint32_t k = tid; k < K; k += 256) {
         uint32_t L = len_s[k];
         enc[(size_t)t * K + k] = (uint16_t)(L ? ((L << 12) | nodew[k]) : 0u);
@@ -238,6 +265,7 @@ __global__ __launch_bounds__(256) void k_codebook(Geom g, const uint32_t* hist, 
         m.cb_off = 0; m.outl_off = 0;
         tmeta[t] = m;
     }
+    DLC_STAMP(7);
 }
 
 static size_t codebook_smem(uint32_t K) { return (size_t)K * (8 + 4 + 4 + 2 + 2 + 2 + 2) + 256 * 4; }
@@ -252,51 +280,56 @@ __global__ __launch_bounds__(1024) void k_layout(Geom g, TMeta* tmeta, const uin
                                                  uint32_t* group_out_base, const uint8_t* lens, const QParam* qp,
                                                  uint8_t* out, uint64_t capacity, Ctrl* ctrl, Layout* lay) {
     __shared__ Layout s_lay;
-    __shared__ uint32_t s_scan[1024];
-    __shared__ uint32_t s_carry, s_abort;
+    __shared__ uint32_t s_red[17];
+    __shared__ uint32_t s_abort;
     const uint32_t tid = threadIdx.x;
-    if (tid == 0) {
-        uint64_t cur = a16(kHeaderBytes + (uint64_t)kDirBytes * g.T);
-        s_lay.off_cb = cur;
-        uint64_t nout = 0;
-        for (uint32_t t = 0; t < g.T; ++t) {
-            tmeta[t].cb_off = cur;
-            cur += (uint64_t)((tmeta[t].sym_hi - tmeta[t].sym_lo + 1u + 3u) & ~3u);
-            nout += tmeta[t].n_outliers;
+    // per-table offsets of the code-length blocks and of the escape records: two prefix sums over the tables
+    const uint64_t off_cb = a16(kHeaderBytes + (uint64_t)kDirBytes * g.T);
+    uint64_t cb_carry = 0, out_carry = 0;
+    for (uint32_t base = 0; base < g.T; base += 1024) {
+        const uint32_t t = base + tid;
+        uint32_t cb = 0, no = 0;
+        if (t < g.T) {
+            cb = (tmeta[t].sym_hi - tmeta[t].sym_lo + 1u + 3u) & ~3u;
+            no = tmeta[t].n_outliers;
         }
-        s_lay.off_group = a16(cur);
+        uint32_t cb_tot, no_tot;
+        const uint32_t cb_ex = block_excl_scan<16>(cb, s_red, tid, &cb_tot);
+        __syncthreads();
+        const uint32_t no_ex = block_excl_scan<16>(no, s_red, tid, &no_tot);
+        __syncthreads();
+        if (t < g.T) {
+            tmeta[t].cb_off = off_cb + cb_carry + cb_ex;
+            tmeta[t].outl_off = out_carry + no_ex;  // record index for now; byte offset below
+        }
+        cb_carry += cb_tot;
+        out_carry += no_tot;
+    }
+    if (tid == 0) {
+        s_lay.off_cb = off_cb;
+        s_lay.off_group = a16(off_cb + cb_carry);
         s_lay.off_chunk = a16(s_lay.off_group + 4ull * g.NG);
         s_lay.off_outl = a16(s_lay.off_chunk + (uint64_t)kW * g.NG);
-        s_lay.n_out_total = nout;
-        s_lay.off_payload = a16(s_lay.off_outl + 8ull * nout);
-        uint64_t o = s_lay.off_outl;
-        for (uint32_t t = 0; t < g.T; ++t) {
-            tmeta[t].outl_off = o;
-            o += 8ull * tmeta[t].n_outliers;
-        }
+        s_lay.n_out_total = out_carry;
+        s_lay.off_payload = a16(s_lay.off_outl + 8ull * out_carry);
         *lay = s_lay;
         s_abort = s_lay.off_payload > capacity;
         if (s_abort) { ctrl->abort = 1; set_status(ctrl, DLC_ECAPACITY); }
-        s_carry = 0;
     }
     __syncthreads();
+    for (uint32_t t = tid; t < g.T; t += 1024) tmeta[t].outl_off = s_lay.off_outl + 8ull * tmeta[t].outl_off;
     // exclusive prefix sum of the per-group escape counts (all tables, group order)
+    uint32_t carry = 0;
     for (uint32_t base = 0; base < g.NG; base += 1024) {
-        uint32_t i = base + tid;
-        uint32_t v = i < g.NG ? group_outliers[i] : 0u;
-        s_scan[tid] = v;
+        const uint32_t i = base + tid;
+        const uint32_t v = i < g.NG ? group_outliers[i] : 0u;
+        uint32_t tot;
+        const uint32_t ex = block_excl_scan<16>(v, s_red, tid, &tot);
         __syncthreads();
-        for (uint32_t o = 1; o < 1024; o <<= 1) {
-            uint32_t u = tid >= o ? s_scan[tid - o] : 0u;
-            __syncthreads();
-            s_scan[tid] += u;
-            __syncthreads();
-        }
-        if (i < g.NG) group_out_base[i] = s_carry + s_scan[tid] - v;
-        __syncthreads();
-        if (tid == 1023) s_carry += s_scan[1023];
-        __syncthreads();
+        if (i < g.NG) group_out_base[i] = carry + ex;
+        carry += tot;
     }
+    __syncthreads();
     if (s_abort) return;
     // everything before the group-offset section starts as zero (header reserve, padding)
     {
@@ -329,10 +362,12 @@ __global__ __launch_bounds__(1024) void k_layout(Geom g, TMeta* tmeta, const uin
         uint64_t* d64 = reinterpret_cast<uint64_t*>(d + 24);
         d64[0] = m.cb_off; d64[1] = m.outl_off;  // payload offset and size: k_finalize
     }
-    for (uint32_t t = 0; t < g.T; ++t) {
+    // code lengths of the used symbol range: a few dozen bytes per table, one thread per table
+    for (uint32_t t = tid; t < g.T; t += 1024) {
         const TMeta m = tmeta[t];
         const uint32_t nl = m.sym_hi - m.sym_lo + 1u;
-        for (uint32_t i = tid; i < nl; i += 1024) out[m.cb_off + i] = lens[(size_t)t * g.K + m.sym_lo + i];
+        const uint8_t* src = lens + (size_t)t * g.K + m.sym_lo;
+        for (uint32_t i = 0; i < nl; ++i) out[m.cb_off + i] = src[i];
     }
 }
 
@@ -355,7 +390,7 @@ void k_encode(const void* payload, Geom g, const QParam* qp, const uint16_t* enc
                                                 const Layout* lay, Ctrl* ctrl,
                                                 uint64_t* state, uint64_t epoch, uint8_t* out, uint64_t capacity,
                                                 uint32_t bpt, uint32_t* word_start, uint32_t* word_end) {
-    extern __shared__ uint16_t s_enc[];
+    extern __shared__ __align__(16) uint16_t s_enc[];
     __shared__ uint32_t s_wg;
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     if (tid == 0) s_wg = atomicAdd(&ctrl->ticket, 1u);

@@ -37,6 +37,7 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
         off_cb = q[HQ_OFF_CB];
         L.off_group = q[HQ_OFF_GROUP]; L.off_chunk = q[HQ_OFF_CHUNK]; L.off_outl = q[HQ_OFF_OUTL];
         L.off_payload = q[HQ_OFF_PAYLOAD];
+        L.n_out_total = n_out;
         total = q[HQ_TOTAL];
         ok = total <= comp_bytes && off_cb == d_a16(kHeaderBytes + (uint64_t)kDirBytes * g.T) &&
              L.off_group >= off_cb && (L.off_group & 15ull) == 0 && L.off_group <= total &&
@@ -114,17 +115,18 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
         __syncthreads();
         const bool ok3 = s_ok != 0;
         if (ok3) {
+            // the LMAX-bit string i starts with a codeword of length l iff i < limit[l] and not already
+            // i < limit[l-1]; the limits are the same for every thread (scalar registers)
+            uint32_t limit[kLmaxLimit + 1];
+#pragma unroll
+            for (uint32_t l = 1; l <= (uint32_t)kLmaxLimit; ++l)
+                limit[l] = l <= g.LMAX ? (s_first[l] + s_cl[l]) << (g.LMAX - l) : 0xFFFFFFFFu;
             for (uint32_t i = tid; i < lut_n; i += 256) {
-                uint32_t entry = 0;
-                for (uint32_t l = 1; l <= g.LMAX; ++l) {
-                    const uint32_t c = i >> (g.LMAX - l);
-                    const uint32_t rel = c - s_first[l];
-                    if (c >= s_first[l] && rel < s_cl[l]) {
-                        entry = (l << 12) | s_sorted[s_index[l] + rel];
-                        break;
-                    }
-                }
-                my_lut[i] = (uint16_t)entry;
+                uint32_t l = 1;
+#pragma unroll
+                for (uint32_t k = 1; k < (uint32_t)kLmaxLimit; ++k) l += (i >= limit[k]) ? 1u : 0u;
+                const uint32_t c = i >> (g.LMAX - l);
+                my_lut[i] = (uint16_t)((l << 12) | s_sorted[s_index[l] + (c - s_first[l])]);
             }
         }
     }
@@ -144,7 +146,7 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
 template <bool F16, bool VEC>
 __global__ __launch_bounds__(512) void k_decode(Geom g, const uint8_t* comp, const uint16_t* lut, const DecLayout* dlay,
                                                 const DecTable* dtab, Ctrl* ctrl, void* outp, uint32_t bpt) {
-    extern __shared__ uint16_t s_lut[];
+    extern __shared__ __align__(16) uint16_t s_lut[];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t t = blockIdx.x / bpt, b = blockIdx.x % bpt;
     const DecLayout L = *dlay;
@@ -228,19 +230,25 @@ __global__ __launch_bounds__(512) void k_decode(Geom g, const uint8_t* comp, con
 template <bool F16>
 __global__ __launch_bounds__(256) void k_outliers(Geom g, const uint8_t* comp, const DecLayout* dlay,
                                                   const DecTable* dtab, Ctrl* ctrl, void* outp) {
-    if (!dlay->valid) return;
-    const uint32_t gtid = blockIdx.x * blockDim.x + threadIdx.x, gsz = gridDim.x * blockDim.x;
-    for (uint32_t t = 0; t < g.T; ++t) {
-        const DecTable D = dtab[t];
-        if (!D.valid || D.n_outliers == 0) continue;
-        const uint32_t* rec = reinterpret_cast<const uint32_t*>(comp + D.outl_off);
-        uint8_t* tab = static_cast<uint8_t*>(outp) + (size_t)t * g.n * g.es;
-        for (uint32_t i = gtid; i < D.n_outliers; i += gsz) {
-            const uint32_t idx = rec[2ull * i], raw = rec[2ull * i + 1];
-            if (idx >= g.n) { set_status(ctrl, DLC_ECORRUPT); continue; }
-            if constexpr (F16) reinterpret_cast<uint16_t*>(tab)[idx] = (uint16_t)raw;
-            else reinterpret_cast<uint32_t*>(tab)[idx] = raw;
+    const DecLayout L = *dlay;
+    if (!L.valid || L.n_out_total == 0) return;
+    const uint64_t gtid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, gsz = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t r = gtid; r < L.n_out_total; r += gsz) {
+        // table of record r: the last table whose first record is at or before r (tables hold consecutive runs)
+        const uint64_t byte = L.off_outl + 8ull * r;
+        uint32_t lo = 0, hi = g.T - 1;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi + 1) >> 1;
+            if (dtab[mid].outl_off <= byte) lo = mid; else hi = mid - 1;
         }
+        const DecTable D = dtab[lo];
+        if (!D.valid || byte < D.outl_off || byte >= D.outl_off + 8ull * D.n_outliers) continue;  // table rejected
+        const uint32_t* rec = reinterpret_cast<const uint32_t*>(comp + byte);
+        const uint32_t idx = rec[0], raw = rec[1];
+        if (idx >= g.n) { set_status(ctrl, DLC_ECORRUPT); continue; }
+        uint8_t* tab = static_cast<uint8_t*>(outp) + (size_t)lo * g.n * g.es;
+        if constexpr (F16) reinterpret_cast<uint16_t*>(tab)[idx] = (uint16_t)raw;
+        else reinterpret_cast<uint32_t*>(tab)[idx] = raw;
     }
 }
 

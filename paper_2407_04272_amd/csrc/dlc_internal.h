@@ -61,7 +61,7 @@ struct Ctrl {
 struct DecLayout {
     uint32_t valid;
     uint32_t pad;
-    uint64_t off_group, off_chunk, off_outl, off_payload, words_total;
+    uint64_t off_group, off_chunk, off_outl, off_payload, words_total, n_out_total;
 };
 
 struct DecTable {
@@ -143,6 +143,26 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, uint32_t lane) {
         if (lane >= (uint32_t)o) v += u;
     }
     return v;
+}
+
+// Exclusive prefix sum over a work-group of NW wavefronts (blockDim.x == 64*NW); every thread gets the
+// grand total in *total.  `red` is NW+1 words of LDS.  Two barriers.
+template <int NW>
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* red, uint32_t tid, uint32_t* total) {
+    const uint32_t lane = tid & 63u, wave = tid >> 6;
+    const uint32_t incl = wave_incl_scan(v, lane);
+    if (lane == 63) red[wave] = incl;
+    __syncthreads();
+    if (wave == 0) {
+        const uint32_t w = lane < (uint32_t)NW ? red[lane] : 0u;
+        const uint32_t wi = wave_incl_scan(w, lane);
+        if (lane < (uint32_t)NW) red[lane] = wi - w;
+        if (lane == NW - 1) red[NW] = wi;
+    }
+    __syncthreads();
+    const uint32_t r = red[wave] + incl - v;
+    *total = red[NW];
+    return r;
 }
 
 #endif  // __HIPCC__

@@ -152,3 +152,48 @@ def test_tie_break_is_fixed():
     # leaves (3,1)(3,2)(3,4)(3,5)(3,7): merges (1,2)=6, (4,5)=6, then leaf 7 with node(1,2)=9, then 6+9
     assert [int(ln[s]) for s in (1, 2, 4, 5, 7)] == [3, 3, 2, 2, 2]
     assert [int(code[s]) for s in (4, 5, 7, 1, 2)] == [0, 1, 2, 6, 7]
+
+
+@pytest.mark.parametrize("LMAX", [4, 5, 7, 12])
+def test_length_limited_codes_are_valid_and_monotone(LMAX):
+    """Skewed counts with a small LMAX: every result is a complete prefix code within the limit, never gives
+    a more frequent symbol a longer code, and costs at least the unlimited optimum."""
+    rng = np.random.default_rng(LMAX)
+    K = 1 << LMAX
+    hit = 0
+    for trial in range(60):
+        n = int(rng.integers(2, K + 1))
+        hist = np.zeros(K, np.uint64)
+        where = rng.choice(K, n, replace=False)
+        kind = trial % 3
+        if kind == 0:
+            hist[where] = np.maximum(1, (2.0 ** rng.uniform(0, 30, n))).astype(np.uint64)     # huge dynamic range
+        elif kind == 1:
+            hist[where] = np.maximum(1, 1e6 * np.exp(-0.5 * ((np.arange(n) - n / 2) / (n / 12 + 0.3)) ** 2)).astype(
+                np.uint64)                                                                     # bell with long tails
+        else:
+            hist[where] = 1                                                                    # flat
+            hist[where[0]] = 10 ** 9
+        ln, code, nu, nh = oracle.codebook(hist, LMAX)
+        assert nu == n
+        _check_code(hist, ln, code, LMAX)
+        used = np.nonzero(hist)[0]
+        if nh:
+            hit += 1
+            order = sorted(used, key=lambda s: (-int(hist[s]), -int(s)))
+            lens = [int(ln[s]) for s in order]
+            assert lens == sorted(lens)                      # most frequent first gets the shortest
+            assert ln.max() == LMAX
+        assert int((hist * ln).sum()) >= _heap_huffman_cost(hist)
+    assert hit > 5
+
+
+def test_length_limit_costs_little_on_bell_shaped_counts():
+    """Quantised Gaussian data (observation 3 of Section III-B): the limit only touches the far tails."""
+    k = np.arange(-40, 41)
+    hist = np.zeros(1024, np.uint64)
+    hist[512 + k] = np.maximum(1, np.round(1e6 * 0.25 * np.exp(-0.5 * (k * 0.52) ** 2))).astype(np.uint64)
+    ln, code, nu, nh = oracle.codebook(hist, 12)
+    assert nh > 0 and ln.max() == 12
+    _check_code(hist, ln, code, 12)
+    assert int((hist * ln).sum()) <= _heap_huffman_cost(hist) * 1.01
