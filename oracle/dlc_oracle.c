@@ -41,8 +41,8 @@
 #define ORC_F16 1
 
 /* container constants (a reading: the paper gives no layout) */
-#define ORC_MAGIC 0x31434C44u /* "DLC1" */
-#define ORC_VERSION 1u
+#define ORC_MAGIC 0x32434C44u /* "DLC2" */
+#define ORC_VERSION 2u
 #define ORC_W 64u /* chunks per group */
 #define ORC_V 4u  /* consecutive symbols a chunk takes per turn */
 #define ORC_HEADER_BYTES 128u
@@ -500,32 +500,36 @@ int orc_controller(const orc_table_stats* st, int T, const orc_controller_params
 /* ------------------------------------------------------------------ */
 /* Container (a reading throughout; Section III-E only asks for one    */
 /* buffer holding all tables, chunked so that decoding is parallel,    */
-/* and Section III-A for size metadata).                               */
+/* with every write offset known before the write, and Section III-A   */
+/* for size metadata).                                                 */
 /*                                                                     */
 /* A table's n = B*D symbols (row-major) are cut into groups of W*S    */
 /* symbols.  Inside a group the W chunks take turns: chunk l gets      */
 /* symbols  g*W*S + j*W*V + l*V + v  for j = 0.., v = 0..V-1, in that  */
 /* order, as far as they are < n.  A chunk's codewords are packed      */
 /* MSB-first into little-endian 32-bit words (stream bit k is bit      */
-/* 31-(k%32) of word k/32) and zero-padded to a whole word.  Chunks    */
-/* are laid one after another: all chunks of group 0 of table 0, then  */
-/* group 1, ... then table 1, ...                                      */
+/* 31-(k%32) of word k/32) and zero-padded to a whole word.  A group   */
+/* occupies consecutive words: its W chunks in order, then one record  */
+/* of two words (index in table, raw bits) per escape of the group,    */
+/* in increasing index.  Groups follow one another: table 0 group 0,   */
+/* group 1, ... then table 1.  So every offset is a prefix sum over    */
+/* groups.                                                             */
 /*                                                                     */
 /* bytes   0..127  header (u32 magic, version, dtype, T, B, D, R, S,   */
 /*                 LMAX, W, V, n_groups_total; u64 n_outliers_total,   */
-/*                 payload_words_total, off_codebook, off_group,       */
-/*                 off_chunk, off_outlier, off_payload, total_bytes;   */
-/*                 16 zero bytes)                                      */
+/*                 payload_words_total, off_group, off_chunk,          */
+/*                 off_payload, off_codebook, total_bytes; 24 zero     */
+/*                 bytes)                                              */
 /* then T directory entries of 56 bytes (u32 eb bits, n_used, sym_lo,  */
-/*                 sym_hi, n_outliers, n_groups; u64 codebook_off,     */
-/*                 outlier_off, payload_word_off, payload_words)       */
-/* off_codebook    per table u8 length[sym_lo..sym_hi] (0 = unused),   */
-/*                 each block zero-padded to 4 bytes                   */
+/*                 sym_hi, n_outliers, n_groups; u64 codebook_off, 0,  */
+/*                 payload_word_off, payload_words)                    */
 /* off_group       u32 first word (relative to off_payload) per group  */
 /* off_chunk       u8 word count per chunk, W per group                */
-/* off_outlier     (u32 index in table, u32 raw bits) per escape,      */
-/*                 table by table, increasing index                    */
-/* off_payload     the words.  Every section starts 16-byte aligned.   */
+/* off_payload     the words (chunks and escape records)               */
+/* off_codebook    per table u8 length[sym_lo..sym_hi] (0 = unused),   */
+/*                 each block zero-padded to 4 bytes                   */
+/* Sections start 16-byte aligned; the first three have sizes that     */
+/* depend on the geometry alone.                                       */
 /* ------------------------------------------------------------------ */
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -564,12 +568,11 @@ size_t orc_compress_bound(int dtype, int T, int64_t B, int64_t D, int R, int S, 
     size_t G = (n + (size_t)ORC_W * S - 1) / ((size_t)ORC_W * S);
     size_t NG = G * (size_t)T;
     size_t off = align_up(ORC_HEADER_BYTES + (size_t)ORC_DIR_BYTES * T, 16);
-    off = align_up(off + (size_t)T * align_up(2 * (size_t)R, 4), 16);
     off = align_up(off + 4 * NG, 16);
     off = align_up(off + ORC_W * NG, 16);
-    off = align_up(off + 8 * n * T, 16);
     size_t words_per_chunk = ((size_t)S * LMAX + 31) / 32;
-    return off + 4 * words_per_chunk * ORC_W * NG;
+    off = align_up(off + 4 * words_per_chunk * ORC_W * NG + 8 * n * T, 16); /* every chunk full, every element an escape */
+    return off + (size_t)T * align_up(2 * (size_t)R, 4);
 }
 
 typedef struct {
@@ -581,7 +584,7 @@ typedef struct {
     uint32_t* out_raw;
     uint8_t* chunk_words; /* W per group */
     uint64_t* group_word; /* first word of each group, relative to the table */
-    uint32_t* words;
+    uint32_t* words;      /* chunks and escape records of all groups */
     uint64_t n_words;
 } orc_table_work;
 
@@ -646,7 +649,7 @@ int orc_compress(const void* payload, int dtype, int T, int64_t B, int64_t D, in
                 if (w->sym_lo < 0) w->sym_lo = k;
                 w->sym_hi = k;
             }
-        /* chunk sizes, offsets */
+        /* chunk sizes and group offsets: a group = its chunks' words, then two words per escape */
         w->chunk_words = (uint8_t*)calloc(G * ORC_W, 1);
         w->group_word = (uint64_t*)calloc(G, sizeof(uint64_t));
         uint64_t total_words = 0;
@@ -662,11 +665,14 @@ int orc_compress(const void* payload, int dtype, int T, int64_t B, int64_t D, in
                 w->chunk_words[g * ORC_W + l] = (uint8_t)nw;
                 total_words += nw;
             }
+            size_t lo = g * GS, hi = lo + GS < n ? lo + GS : n;
+            for (size_t i = lo; i < hi; ++i) total_words += 2 * (sym[i] == 0);
         }
         w->n_words = total_words;
         w->words = (uint32_t*)calloc(total_words ? total_words : 1, sizeof(uint32_t));
-        /* bit packing */
+        /* bit packing, then the group's escape records */
         uint64_t wpos = 0;
+        size_t o2 = 0;
         for (size_t g = 0; g < G; ++g) {
             for (uint32_t l = 0; l < ORC_W; ++l) {
                 uint64_t bit = 0; /* bit position inside the chunk */
@@ -683,6 +689,12 @@ int orc_compress(const void* payload, int dtype, int T, int64_t B, int64_t D, in
                 }
                 wpos += w->chunk_words[g * ORC_W + l];
             }
+            size_t hi = (g + 1) * GS < n ? (g + 1) * GS : n;
+            while (o2 < w->n_outliers && w->out_idx[o2] < hi) { /* out_idx is increasing */
+                w->words[wpos++] = w->out_idx[o2];
+                w->words[wpos++] = w->out_raw[o2];
+                o2++;
+            }
         }
     }
     free(sym);
@@ -690,23 +702,22 @@ int orc_compress(const void* payload, int dtype, int T, int64_t B, int64_t D, in
 
     /* layout */
     const size_t NG = G * (size_t)T;
-    size_t off_codebook = align_up(ORC_HEADER_BYTES + (size_t)ORC_DIR_BYTES * T, 16);
+    size_t off_group = align_up(ORC_HEADER_BYTES + (size_t)ORC_DIR_BYTES * T, 16);
+    size_t off_chunk = align_up(off_group + 4 * NG, 16);
+    size_t off_payload = align_up(off_chunk + ORC_W * NG, 16);
+    uint64_t n_out_total = 0, words_total = 0;
+    for (int t = 0; t < T; ++t) {
+        n_out_total += work[t].n_outliers;
+        words_total += work[t].n_words;
+    }
+    size_t off_codebook = align_up(off_payload + 4 * (size_t)words_total, 16);
     size_t cur = off_codebook;
     size_t* cb_off = (size_t*)malloc(sizeof(size_t) * (size_t)T);
     for (int t = 0; t < T; ++t) {
         cb_off[t] = cur;
         cur += align_up((size_t)(work[t].sym_hi - work[t].sym_lo + 1), 4);
     }
-    size_t off_group = align_up(cur, 16);
-    size_t off_chunk = align_up(off_group + 4 * NG, 16);
-    size_t off_outlier = align_up(off_chunk + ORC_W * NG, 16);
-    uint64_t n_out_total = 0, words_total = 0;
-    for (int t = 0; t < T; ++t) {
-        n_out_total += work[t].n_outliers;
-        words_total += work[t].n_words;
-    }
-    size_t off_payload = align_up(off_outlier + 8 * (size_t)n_out_total, 16);
-    size_t total = off_payload + 4 * (size_t)words_total;
+    size_t total = cur;
     if (words_total > 0xFFFFFFFFull) {
         free(cb_off);
         free_table_work(work, T);
@@ -718,7 +729,7 @@ int orc_compress(const void* payload, int dtype, int T, int64_t B, int64_t D, in
         out_bytes[0] = 0;
         return ORC_ECAPACITY;
     }
-    memset(out, 0, off_payload);
+    memset(out, 0, total);
     put32(out + 0, ORC_MAGIC);
     put32(out + 4, ORC_VERSION);
     put32(out + 8, (uint32_t)dtype);
@@ -733,13 +744,12 @@ int orc_compress(const void* payload, int dtype, int T, int64_t B, int64_t D, in
     put32(out + 44, (uint32_t)NG);
     put64(out + 48, n_out_total);
     put64(out + 56, words_total);
-    put64(out + 64, off_codebook);
-    put64(out + 72, off_group);
-    put64(out + 80, off_chunk);
-    put64(out + 88, off_outlier);
-    put64(out + 96, off_payload);
-    put64(out + 104, total);
-    uint64_t word_base = 0, out_base = 0;
+    put64(out + 64, off_group);
+    put64(out + 72, off_chunk);
+    put64(out + 80, off_payload);
+    put64(out + 88, off_codebook);
+    put64(out + 96, total);
+    uint64_t word_base = 0;
     for (int t = 0; t < T; ++t) {
         orc_table_work* w = &work[t];
         uint8_t* d = out + ORC_HEADER_BYTES + (size_t)ORC_DIR_BYTES * t;
@@ -752,23 +762,18 @@ int orc_compress(const void* payload, int dtype, int T, int64_t B, int64_t D, in
         put32(d + 16, w->n_outliers);
         put32(d + 20, (uint32_t)G);
         put64(d + 24, cb_off[t]);
-        put64(d + 32, off_outlier + 8 * out_base);
+        put64(d + 32, 0);
         put64(d + 40, word_base);
         put64(d + 48, w->n_words);
         memcpy(out + cb_off[t], w->len + w->sym_lo, (size_t)(w->sym_hi - w->sym_lo + 1));
         for (size_t g = 0; g < G; ++g)
             put32(out + off_group + 4 * ((size_t)t * G + g), (uint32_t)(word_base + w->group_word[g]));
         memcpy(out + off_chunk + ORC_W * (size_t)t * G, w->chunk_words, ORC_W * G);
-        for (uint32_t o = 0; o < w->n_outliers; ++o) {
-            put32(out + off_outlier + 8 * (out_base + o), w->out_idx[o]);
-            put32(out + off_outlier + 8 * (out_base + o) + 4, w->out_raw[o]);
-        }
         memcpy(out + off_payload + 4 * word_base, w->words, 4 * (size_t)w->n_words);
         /* bytes attributable to this table (size metadata of the pipeline's second stage) */
-        out_bytes[1 + t] = 4 * w->n_words + align_up((size_t)(w->sym_hi - w->sym_lo + 1), 4) + 8ull * w->n_outliers +
-                           (ORC_W + 4) * G + ORC_DIR_BYTES;
+        out_bytes[1 + t] = 4 * w->n_words + align_up((size_t)(w->sym_hi - w->sym_lo + 1), 4) + (ORC_W + 4) * G +
+                           ORC_DIR_BYTES;
         word_base += w->n_words;
-        out_base += w->n_outliers;
     }
     out_bytes[0] = total;
     free(cb_off);
@@ -806,17 +811,15 @@ int orc_decompress(const uint8_t* comp, size_t bytes, void* out, size_t out_capa
     const size_t G = (n + GS - 1) / GS;
     const size_t NG = G * (size_t)T;
     uint64_t n_out_total = q[0], words_total = q[1];
-    uint64_t off_codebook = q[2], off_group = q[3], off_chunk = q[4], off_outlier = q[5], off_payload = q[6],
-             total = q[7];
+    uint64_t off_group = q[2], off_chunk = q[3], off_payload = q[4], off_codebook = q[5], total = q[6];
     if (f[11] != NG) return ORC_ECORRUPT;
     if (total > bytes) return ORC_ECORRUPT;
-    if (off_codebook != align_up(ORC_HEADER_BYTES + (size_t)ORC_DIR_BYTES * T, 16)) return ORC_ECORRUPT;
-    if (off_group < off_codebook || off_group % 16 || off_group > total) return ORC_ECORRUPT;
+    if (off_group != align_up(ORC_HEADER_BYTES + (size_t)ORC_DIR_BYTES * T, 16)) return ORC_ECORRUPT;
     if (off_chunk != align_up(off_group + 4 * NG, 16)) return ORC_ECORRUPT;
-    if (off_outlier != align_up(off_chunk + ORC_W * NG, 16)) return ORC_ECORRUPT;
-    if (n_out_total > (uint64_t)n * T) return ORC_ECORRUPT;
-    if (off_payload != align_up(off_outlier + 8 * n_out_total, 16)) return ORC_ECORRUPT;
-    if (total != off_payload + 4 * words_total) return ORC_ECORRUPT;
+    if (off_payload != align_up(off_chunk + ORC_W * NG, 16)) return ORC_ECORRUPT;
+    if (words_total > 0xFFFFFFFFull || n_out_total > (uint64_t)n * T) return ORC_ECORRUPT;
+    if (off_codebook != align_up(off_payload + 4 * words_total, 16)) return ORC_ECORRUPT;
+    if (total < off_codebook) return ORC_ECORRUPT;
     if (!out || out_capacity_bytes < n * T * es) return ORC_ECAPACITY;
 
     for (int t = 0; t < T; ++t) {
@@ -826,12 +829,12 @@ int orc_decompress(const uint8_t* comp, size_t bytes, void* out, size_t out_capa
         memcpy(&eb, &ebbits, 4);
         uint32_t n_used = get32(d + 4), sym_lo = get32(d + 8), sym_hi = get32(d + 12);
         uint32_t n_outl = get32(d + 16);
-        uint64_t cb_off = get64(d + 24), outl_off = get64(d + 32);
+        uint64_t cb_off = get64(d + 24);
         if (!(eb > 0.0f) || isinf(eb)) return ORC_ECORRUPT;
         if (get32(d + 20) != G) return ORC_ECORRUPT;
         if (sym_lo > sym_hi || sym_hi >= (uint32_t)K || n_used < 1 || n_used > sym_hi - sym_lo + 1) return ORC_ECORRUPT;
-        if (cb_off < off_codebook || cb_off + (sym_hi - sym_lo + 1) > off_group) return ORC_ECORRUPT;
-        if (outl_off < off_outlier || outl_off + 8ull * n_outl > off_payload) return ORC_ECORRUPT;
+        if (cb_off < off_codebook || cb_off + (sym_hi - sym_lo + 1) > total) return ORC_ECORRUPT;
+        uint64_t seen_outl = 0;
         orc_qparam qp = make_qparam(eb);
 
         /* rebuild canonical code from lengths */
@@ -870,10 +873,13 @@ int orc_decompress(const uint8_t* comp, size_t bytes, void* out, size_t out_capa
         }
         uint8_t* tab_out = (uint8_t*)out + (size_t)t * n * es;
         for (size_t g = 0; g < G; ++g) {
-            uint64_t w0 = get32(comp + off_group + 4 * ((size_t)t * G + g));
+            size_t gi = (size_t)t * G + g;
+            uint64_t w0 = get32(comp + off_group + 4 * gi);
+            uint64_t w_end = gi + 1 < NG ? get32(comp + off_group + 4 * (gi + 1)) : words_total;
+            if (w_end < w0 || w_end > words_total) return ORC_ECORRUPT;
             for (uint32_t l = 0; l < ORC_W; ++l) {
-                uint32_t nw = comp[off_chunk + ORC_W * ((size_t)t * G + g) + l];
-                if (w0 + nw > words_total) return ORC_ECORRUPT;
+                uint32_t nw = comp[off_chunk + ORC_W * gi + l];
+                if (w0 + nw > w_end) return ORC_ECORRUPT;
                 const uint8_t* base = comp + off_payload + 4 * w0;
                 uint64_t bit = 0;
                 for (uint32_t k = 0; k < (uint32_t)S; ++k) {
@@ -905,14 +911,19 @@ int orc_decompress(const uint8_t* comp, size_t bytes, void* out, size_t out_capa
                 }
                 w0 += nw;
             }
+            /* the rest of the group's words are its escape records */
+            if ((w_end - w0) % 2) return ORC_ECORRUPT;
+            size_t lo = g * GS, hi = lo + GS < n ? lo + GS : n;
+            for (; w0 < w_end; w0 += 2) {
+                uint32_t idx = get32(comp + off_payload + 4 * w0);
+                uint32_t raw = get32(comp + off_payload + 4 * w0 + 4);
+                if (idx < lo || idx >= hi) return ORC_ECORRUPT;
+                if (dtype == ORC_F16) ((uint16_t*)tab_out)[idx] = (uint16_t)raw;
+                else ((uint32_t*)tab_out)[idx] = raw;
+                seen_outl++;
+            }
         }
-        for (uint32_t o = 0; o < n_outl; ++o) {
-            uint32_t idx = get32(comp + outl_off + 8ull * o);
-            uint32_t raw = get32(comp + outl_off + 8ull * o + 4);
-            if (idx >= n) return ORC_ECORRUPT;
-            if (dtype == ORC_F16) ((uint16_t*)tab_out)[idx] = (uint16_t)raw;
-            else ((uint32_t*)tab_out)[idx] = raw;
-        }
+        if (seen_outl != n_outl) return ORC_ECORRUPT;
     }
     return ORC_OK;
 }

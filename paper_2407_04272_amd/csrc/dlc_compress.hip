@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const
     const uint32_t t = blockIdx.x / bpt, b = blockIdx.x % bpt;
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t nbins = g.K << clog2;
-    for (uint32_t k = tid; k < nbins; k += 256) lh[k] = 0;
+    for (uint32_t k = tid; k < nbins + kW; k += 256) lh[k] = 0;
     __syncthreads();
     const QParam q = qp[t];
     const float Rf = (float)g.R;
@@ -74,17 +74,26 @@ __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const
         const uint8_t* gbase = tab + (size_t)gstart * g.es;
         const uint32_t rem = g.n - gstart;
         uint32_t nout = 0;
-#pragma unroll 4
-        for (uint32_t j = 0; j < turns; ++j) {
-            float x[4];
-            uint32_t raw[4];
-            const uint32_t valid = load4<F16, VEC>(gbase, lane * kV + j * (kW * kV), rem, x, raw);
+#ifndef DLC_EXP_HIST_BLK
+#define DLC_EXP_HIST_BLK 4
+#endif
+        constexpr uint32_t kBlk = DLC_EXP_HIST_BLK;  // turns whose loads are issued back to back (S/4 is a multiple)
+        for (uint32_t jb = 0; jb < turns; jb += kBlk) {
+            float x[kBlk][4];
+            uint32_t raw[kBlk][4];
+            uint32_t valid[kBlk];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                if ((valid >> v) & 1u) {
-                    const uint32_t c = quant_symbol<F16>(x[v], q, Rf, (int)g.R);
-                    atomicAdd(&lh[(c << clog2) + cm], 1u);
-                    nout += (c == 0u);
+            for (uint32_t u = 0; u < kBlk; ++u)
+                valid[u] = load4<F16, VEC>(gbase, lane * kV + (jb + u) * (kW * kV), rem, x[u], raw[u]);
+#pragma unroll
+            for (uint32_t u = 0; u < kBlk; ++u) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    // branch-free: a position past the end of the table counts into a scratch bin of its own lane
+                    const bool ok = (valid[u] >> v) & 1u;
+                    const uint32_t c = quant_symbol<F16>(x[u][v], q, Rf, (int)g.R);
+                    atomicAdd(&lh[ok ? (c << clog2) + cm : nbins + lane], 1u);
+                    nout += (ok && c == 0u) ? 1u : 0u;
                 }
             }
         }
@@ -605,16 +614,22 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         if (prof_on(pl, P_ZERO)) prof_end(prof, P_ZERO, s);
     }
     // histogram: up to 8 copies of each bin, 32 KiB of LDS at most
-    uint32_t clog2 = 3;
+#ifndef DLC_EXP_HIST_CLOG2
+#define DLC_EXP_HIST_CLOG2 3
+#endif
+    uint32_t clog2 = DLC_EXP_HIST_CLOG2;
     while (clog2 > 0 && ((size_t)g.K << clog2) * 4 > 32768) --clog2;
     const uint32_t waves_per_table = g.G;
     uint32_t bpt_h = (waves_per_table + 3) / 4;
     {
         // cap the grid at a few work-groups per CU; a work-group then loops over groups of its table
-        const uint32_t max_blocks = 256 * 8;
+#ifndef DLC_EXP_HIST_BLOCKS
+#define DLC_EXP_HIST_BLOCKS (256 * 8)
+#endif
+        const uint32_t max_blocks = DLC_EXP_HIST_BLOCKS;
         const uint32_t cap = std::max<uint32_t>(1, max_blocks / g.T);
         bpt_h = std::min(bpt_h, cap);
-        size_t sm = ((size_t)g.K << clog2) * 4;
+        size_t sm = ((size_t)g.K << clog2) * 4 + kW * 4;  // + one scratch bin per lane
         dim3 grid(g.T * bpt_h), block(256);
         if (prof_on(pl, P_HIST)) prof_begin(prof, P_HIST, s);
 #define DLC_HIST(F, V)                                                                                          \

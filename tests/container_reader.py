@@ -28,7 +28,7 @@ class Table:
     n_outliers: int
     n_groups: int
     codebook_off: int
-    outlier_off: int
+    reserved: int
     payload_word_off: int
     payload_words: int
     lengths: np.ndarray
@@ -46,11 +46,10 @@ class Container:
     n_groups_total: int
     n_outliers_total: int
     payload_words_total: int
-    off_codebook: int
     off_group: int
     off_chunk: int
-    off_outlier: int
     off_payload: int
+    off_codebook: int
     total_bytes: int
     tables: list
     group_off: np.ndarray
@@ -62,12 +61,12 @@ class Container:
 def parse(buf) -> Container:
     raw = bytes(buf)
     f = struct.unpack_from("<12I", raw, 0)
-    q = struct.unpack_from("<8Q", raw, 48)
-    assert f[0] == 0x31434C44 and f[1] == 1, "magic/version"
-    assert raw[112:128] == b"\0" * 16
+    q = struct.unpack_from("<7Q", raw, 48)
+    assert f[0] == 0x32434C44 and f[1] == 2, "magic/version"
+    assert raw[104:128] == b"\0" * 24
     dtype, T, B, D, R, S, LMAX, w, v, NG = f[2:12]
     assert (w, v) == (W, V)
-    n_out, n_words, off_cb, off_g, off_c, off_o, off_p, total = q
+    n_out, n_words, off_g, off_c, off_p, off_cb, total = q
     assert total == len(raw), (total, len(raw))
     tables = []
     for t in range(T):
@@ -78,48 +77,61 @@ def parse(buf) -> Container:
     group_off = np.frombuffer(raw, np.uint32, NG, off_g)
     chunk_words = np.frombuffer(raw, np.uint8, W * NG, off_c)
     words = np.frombuffer(raw, np.uint32, n_words, off_p)
-    return Container(dtype, T, B, D, R, S, LMAX, NG, n_out, n_words, off_cb, off_g, off_c, off_o, off_p, total,
+    return Container(dtype, T, B, D, R, S, LMAX, NG, n_out, n_words, off_g, off_c, off_p, off_cb, total,
                      tables, group_off, chunk_words, words, raw)
+
+
+def group_extent(c: Container, gi: int):
+    """(first word, number of chunk words, number of escape records) of global group gi."""
+    start = int(c.group_off[gi])
+    end = int(c.group_off[gi + 1]) if gi + 1 < c.n_groups_total else c.payload_words_total
+    cw = int(c.chunk_words[gi * W:(gi + 1) * W].astype(np.int64).sum())
+    assert end >= start + cw and (end - start - cw) % 2 == 0
+    return start, cw, (end - start - cw) // 2
 
 
 def check_layout(c: Container):
     """Sizes add up; every section sits where the format says; padding is zero."""
     n = c.B * c.D
     G = -(-n // (W * c.S))
-    assert c.n_groups_total == G * c.T
-    assert c.off_codebook == _a16(HEADER + DIRENT * c.T)
-    assert c.raw[HEADER + DIRENT * c.T:c.off_codebook] == b"\0" * (c.off_codebook - HEADER - DIRENT * c.T)
+    NG = G * c.T
+    assert c.n_groups_total == NG
+    e = HEADER + DIRENT * c.T
+    assert c.off_group == _a16(e) and c.raw[e:c.off_group] == b"\0" * (c.off_group - e)
+    e = c.off_group + 4 * NG
+    assert c.off_chunk == _a16(e) and c.raw[e:c.off_chunk] == b"\0" * (c.off_chunk - e)
+    assert c.off_payload == c.off_chunk + W * NG and c.off_payload % 16 == 0
+    e = c.off_payload + 4 * c.payload_words_total
+    assert c.off_codebook == _a16(e) and c.raw[e:c.off_codebook] == b"\0" * (c.off_codebook - e)
     cur = c.off_codebook
     words = 0
     outl = 0
     for t, tb in enumerate(c.tables):
-        assert tb.n_groups == G
+        assert tb.n_groups == G and tb.reserved == 0
         assert tb.codebook_off == cur
         nlen = tb.sym_hi - tb.sym_lo + 1
         pad = (nlen + 3) // 4 * 4
         assert c.raw[cur + nlen:cur + pad] == b"\0" * (pad - nlen)
         cur += pad
         assert tb.payload_word_off == words
+        assert tb.payload_word_off == int(c.group_off[t * G])
         words += tb.payload_words
-        assert tb.outlier_off == c.off_outlier + 8 * outl
+        n_esc = sum(group_extent(c, t * G + g)[2] for g in range(G))
+        assert n_esc == tb.n_outliers
         outl += tb.n_outliers
         if tb.n_used == 1:
-            assert tb.sym_lo == tb.sym_hi and tb.lengths[0] == 0 and tb.payload_words == 0
+            assert tb.sym_lo == tb.sym_hi and tb.lengths[0] == 0 and tb.payload_words == 2 * tb.n_outliers
         else:
             assert np.count_nonzero(tb.lengths) == tb.n_used and tb.lengths[0] and tb.lengths[-1]
-    assert c.off_group == _a16(cur) and c.raw[cur:c.off_group] == b"\0" * (c.off_group - cur)
-    e = c.off_group + 4 * c.n_groups_total
-    assert c.off_chunk == _a16(e) and c.raw[e:c.off_chunk] == b"\0" * (c.off_chunk - e)
-    assert c.off_outlier == c.off_chunk + W * c.n_groups_total
-    e = c.off_outlier + 8 * c.n_outliers_total
-    assert c.off_payload == _a16(e) and c.raw[e:c.off_payload] == b"\0" * (c.off_payload - e)
+    assert cur == c.total_bytes
     assert outl == c.n_outliers_total and words == c.payload_words_total
-    assert c.total_bytes == c.off_payload + 4 * c.payload_words_total
-    # group offsets are the exclusive prefix sum of the chunk word counts
-    per_group = c.chunk_words.reshape(-1, W).astype(np.int64).sum(1)
-    excl = np.concatenate([[0], np.cumsum(per_group)[:-1]]) if per_group.size else per_group
-    assert np.array_equal(c.group_off.astype(np.int64), excl)
-    assert per_group.sum() == c.payload_words_total
+    # group offsets are the exclusive prefix sum of (chunk words + two words per escape)
+    pos = 0
+    for gi in range(NG):
+        start, cw, ne = group_extent(c, gi)
+        assert start == pos
+        pos += cw + 2 * ne
+    assert pos == c.payload_words_total
 
 
 def _canonical(lengths, sym_lo, LMAX):
@@ -175,8 +187,17 @@ def decode_symbols(c: Container) -> np.ndarray:
 
 
 def outliers(c: Container):
+    """Per table: array of (index in table, raw bits), gathered from the groups' records in order."""
+    n = c.B * c.D
+    G = -(-n // (W * c.S))
     res = []
-    for tb in c.tables:
-        a = np.frombuffer(c.raw, np.uint32, 2 * tb.n_outliers, tb.outlier_off).reshape(-1, 2)
-        res.append(a)
+    for t in range(c.T):
+        recs = []
+        for g in range(G):
+            start, cw, ne = group_extent(c, t * G + g)
+            r = c.words[start + cw:start + cw + 2 * ne].reshape(-1, 2)
+            lo, hi = g * W * c.S, min(n, (g + 1) * W * c.S)
+            assert np.all((r[:, 0] >= lo) & (r[:, 0] < hi))
+            recs.append(r)
+        res.append(np.concatenate(recs) if recs else np.zeros((0, 2), np.uint32))
     return res
