@@ -40,8 +40,8 @@ void prof_end(void* p, int slot, hipStream_t s) {
     pr->recs.push_back({slot, pr->pending[slot], e});
 }
 
-static const char* kSlotNames[P_NSLOTS] = {"k_zero", "k_hist", "k_codebook", "k_layout", "k_encode", "k_finalize",
-                                           "k_dec_prepare", "k_decode", "k_outliers"};
+static const char* kSlotNames[P_NSLOTS] = {"k_zero", "k_hist", "k_codebook", "k_encode", "k_finalize",
+                                           "k_dec_prepare", "k_decode", "k_fused"};
 }  // namespace dlc
 
 using namespace dlc;
@@ -96,13 +96,11 @@ static size_t a16(size_t x) { return (x + 15) & ~size_t(15); }
 extern "C" size_t dlc_compress_bound(const dlc_config* cfg) {
     Geom g;
     if (!make_geom(cfg, &g)) return 0;
-    size_t off = a16(kHeaderBytes + (size_t)kDirBytes * g.T);
-    off = a16(off + (size_t)g.T * ((g.K + 3) & ~3u));
-    off = a16(off + 4 * (size_t)g.NG);
-    off = a16(off + (size_t)kW * g.NG);
-    off = a16(off + 8 * (size_t)g.n * g.T);
+    const FixedLayout F = fixed_layout(g);
     const size_t wpc = ((size_t)g.S * g.LMAX + 31) / 32;
-    return off + 4 * wpc * kW * g.NG;
+    // every chunk full, every element an escape, every symbol used
+    const size_t off_cb = a16(F.off_payload + 4 * wpc * kW * g.NG + 8 * (size_t)g.n * g.T);
+    return off_cb + (size_t)g.T * ((g.K + 3) & ~3u);
 }
 
 // carve the workspace; with base == nullptr only sizes are computed
@@ -114,19 +112,14 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
         return p;
     };
     uint8_t* qp = take(sizeof(QParam) * g.T);
-    // cleared per call: histograms, escape totals, first 16 bytes of the control block
+    // cleared per call: histograms, first 16 bytes of the control block
     size_t z0 = off;
     uint8_t* hist = base ? base + off : nullptr;
     off += (size_t)g.T * g.K * 4;
-    uint8_t* tout = base ? base + off : nullptr;
-    off += a16((size_t)g.T * 4);
     uint8_t* ctrl = base ? base + off : nullptr;
     size_t z1 = off + 16;
     off = a256(off + sizeof(Ctrl));
-    uint8_t* gout = take(4 * (size_t)g.NG);
-    uint8_t* gbase = take(4 * (size_t)g.NG);
     uint8_t* tmeta = take(sizeof(TMeta) * g.T);
-    uint8_t* lay = take(sizeof(Layout));
     uint8_t* enc = take(2 * (size_t)g.T * g.K);
     uint8_t* lens = take((size_t)g.T * g.K);
     uint8_t* state = take(8 * (size_t)g.NG);
@@ -139,9 +132,9 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
         w->base = base; w->bytes = off;
         w->qp = (QParam*)qp;
         w->zero_begin = base ? base + z0 : nullptr; w->zero_end = base ? base + z1 : nullptr;
-        w->hist = (uint32_t*)hist; w->table_outliers = (uint32_t*)tout; w->ctrl = (Ctrl*)ctrl; w->ctrl_call = (Ctrl*)ctrl;
-        w->group_outliers = (uint32_t*)gout; w->group_out_base = (uint32_t*)gbase; w->tmeta = (TMeta*)tmeta;
-        w->layout = (Layout*)lay; w->enc = (uint16_t*)enc; w->lens = lens; w->state = (uint64_t*)state;
+        w->hist = (uint32_t*)hist; w->ctrl = (Ctrl*)ctrl; w->ctrl_call = (Ctrl*)ctrl;
+        w->tmeta = (TMeta*)tmeta;
+        w->enc = (uint16_t*)enc; w->lens = lens; w->state = (uint64_t*)state;
         w->word_start = (uint32_t*)ws0; w->word_end = (uint32_t*)ws1; w->lut = (uint16_t*)lut;
         w->dlay = (DecLayout*)dlay; w->dtab = (DecTable*)dtab;
     }
@@ -280,7 +273,7 @@ extern "C" int dlc_compress(dlc_ctx* c, const void* d_payload, void* d_out, size
     if (!c || !aligned16(d_payload) || !aligned16(d_out) || !d_out_bytes || (((uintptr_t)d_out_bytes) & 7u))
         return DLC_EINVAL;
     if (!c->bounds_set) return DLC_ESTATE;
-    if (cap < kHeaderBytes) return DLC_ECAPACITY;
+    if (cap < fixed_layout(c->g).off_payload) return DLC_ECAPACITY;  // the fixed-size sections must fit
     c->epoch += 1;
     if (c->epoch >= (1ull << 30)) {  // look-back records carry a 30-bit call counter
         if (hipMemsetAsync(c->ws.state, 0, 8 * (size_t)c->g.NG, (hipStream_t)stream) != hipSuccess) return DLC_EHIP;

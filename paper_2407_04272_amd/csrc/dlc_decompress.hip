@@ -32,18 +32,15 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
     }
     uint64_t off_cb = 0, n_out = 0, total = 0;
     if (ok) {
+        const FixedLayout F = fixed_layout(g);
         n_out = q[HQ_NOUT];
         L.words_total = q[HQ_WORDS];
+        L.off_group = q[HQ_OFF_GROUP]; L.off_chunk = q[HQ_OFF_CHUNK]; L.off_payload = q[HQ_OFF_PAYLOAD];
         off_cb = q[HQ_OFF_CB];
-        L.off_group = q[HQ_OFF_GROUP]; L.off_chunk = q[HQ_OFF_CHUNK]; L.off_outl = q[HQ_OFF_OUTL];
-        L.off_payload = q[HQ_OFF_PAYLOAD];
-        L.n_out_total = n_out;
         total = q[HQ_TOTAL];
-        ok = total <= comp_bytes && off_cb == d_a16(kHeaderBytes + (uint64_t)kDirBytes * g.T) &&
-             L.off_group >= off_cb && (L.off_group & 15ull) == 0 && L.off_group <= total &&
-             L.off_chunk == d_a16(L.off_group + 4ull * g.NG) && L.off_outl == d_a16(L.off_chunk + (uint64_t)kW * g.NG) &&
-             n_out <= (uint64_t)g.n * g.T && L.off_payload == d_a16(L.off_outl + 8ull * n_out) &&
-             L.words_total <= 0xFFFFFFFFull && total == L.off_payload + 4ull * L.words_total;
+        ok = total <= comp_bytes && L.off_group == F.off_group && L.off_chunk == F.off_chunk &&
+             L.off_payload == F.off_payload && L.words_total <= 0xFFFFFFFFull && n_out <= (uint64_t)g.n * g.T &&
+             off_cb == d_a16(L.off_payload + 4ull * L.words_total) && total >= off_cb;
     }
     if (t == 0 && tid == 0) {
         L.valid = ok; L.pad = 0;
@@ -51,7 +48,7 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
         if (!ok) set_status(ctrl, DLC_ECORRUPT);
     }
     DecTable D;
-    D.valid = 0; D.n_used = 0; D.sym_lo = 0; D.n_outliers = 0; D.outl_off = 0; D.ebx2 = 0.f; D.pad = 0;
+    D.valid = 0; D.n_used = 0; D.sym_lo = 0; D.n_outliers = 0; D.ebx2 = 0.f; D.pad = 0;
     uint32_t sym_lo = 0, sym_hi = 0, n_used = 0;
     uint64_t cb = 0;
     if (ok) {
@@ -62,11 +59,9 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
         n_used = d32[1]; sym_lo = d32[2]; sym_hi = d32[3];
         D.n_outliers = d32[4];
         cb = d64[0];
-        D.outl_off = d64[1];
         ok = eb > 0.f && eb < __builtin_inff() && d32[5] == g.G && sym_lo <= sym_hi && sym_hi < g.K && n_used >= 1 &&
-             n_used <= sym_hi - sym_lo + 1u && cb >= off_cb && cb + (sym_hi - sym_lo + 1u) <= L.off_group &&
-             D.outl_off >= L.off_outl && ((D.outl_off - L.off_outl) & 7ull) == 0 &&
-             D.outl_off + 8ull * D.n_outliers <= L.off_payload && D.n_outliers <= g.n;
+             n_used <= sym_hi - sym_lo + 1u && cb >= off_cb && cb + (sym_hi - sym_lo + 1u) <= total &&
+             D.n_outliers <= g.n;
         D.ebx2 = eb * 2.0f;
         D.sym_lo = sym_lo;
         D.n_used = n_used;
@@ -165,11 +160,15 @@ __global__ __launch_bounds__(512) void k_decode(Geom g, const uint8_t* comp, con
     const uint32_t cw = comp[L.off_chunk + (uint64_t)gid * kW + lane];
     const uint32_t incl = wave_incl_scan(cw, lane);
     const uint32_t total = __shfl(incl, 63, 64);
-    const uint64_t goff = reinterpret_cast<const uint32_t*>(comp + L.off_group)[gid];
-    if (goff + total > L.words_total) {
+    const uint32_t* goffs = reinterpret_cast<const uint32_t*>(comp + L.off_group);
+    const uint64_t goff = goffs[gid];
+    const uint64_t gend = gid + 1 < g.NG ? (uint64_t)goffs[gid + 1] : L.words_total;
+    // the group's words: its chunks, then two words per escape
+    if (gend > L.words_total || goff + total > gend || ((gend - goff - total) & 1ull)) {
         if (lane == 0) set_status(ctrl, DLC_ECORRUPT);
         return;
     }
+    const uint32_t n_esc = (uint32_t)((gend - goff - total) >> 1);
     const uint32_t* p = reinterpret_cast<const uint32_t*>(comp + L.off_payload) + goff + (incl - cw);
     const uint32_t* pend = p + cw;
     uint64_t buf = 0;
@@ -222,33 +221,18 @@ __global__ __launch_bounds__(512) void k_decode(Geom g, const uint8_t* comp, con
                 }
         }
     }
-}
-
-// ------------------------------------------------------------------------------------------------
-// escapes: verbatim values back into place
-// ------------------------------------------------------------------------------------------------
-template <bool F16>
-__global__ __launch_bounds__(256) void k_outliers(Geom g, const uint8_t* comp, const DecLayout* dlay,
-                                                  const DecTable* dtab, Ctrl* ctrl, void* outp) {
-    const DecLayout L = *dlay;
-    if (!L.valid || L.n_out_total == 0) return;
-    const uint64_t gtid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, gsz = (uint64_t)gridDim.x * blockDim.x;
-    for (uint64_t r = gtid; r < L.n_out_total; r += gsz) {
-        // table of record r: the last table whose first record is at or before r (tables hold consecutive runs)
-        const uint64_t byte = L.off_outl + 8ull * r;
-        uint32_t lo = 0, hi = g.T - 1;
-        while (lo < hi) {
-            const uint32_t mid = (lo + hi + 1) >> 1;
-            if (dtab[mid].outl_off <= byte) lo = mid; else hi = mid - 1;
+    if (n_esc != 0u) {  // uniform over the wavefront: verbatim values over the decoded placeholders
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_s_waitcnt(0);  // the wavefront's own stores above are out before the overwrites below
+        const uint32_t* rec = reinterpret_cast<const uint32_t*>(comp + L.off_payload) + goff + total;
+        const uint32_t lo = grp * (kW * g.S);
+        const uint32_t hi = min(g.n, lo + kW * g.S);
+        for (uint32_t r = lane; r < n_esc; r += 64) {
+            const uint32_t idx = rec[2u * r], raw = rec[2u * r + 1];
+            if (idx < lo || idx >= hi) { set_status(ctrl, DLC_ECORRUPT); continue; }
+            if constexpr (F16) reinterpret_cast<uint16_t*>(tab)[idx] = (uint16_t)raw;
+            else reinterpret_cast<uint32_t*>(tab)[idx] = raw;
         }
-        const DecTable D = dtab[lo];
-        if (!D.valid || byte < D.outl_off || byte >= D.outl_off + 8ull * D.n_outliers) continue;  // table rejected
-        const uint32_t* rec = reinterpret_cast<const uint32_t*>(comp + byte);
-        const uint32_t idx = rec[0], raw = rec[1];
-        if (idx >= g.n) { set_status(ctrl, DLC_ECORRUPT); continue; }
-        uint8_t* tab = static_cast<uint8_t*>(outp) + (size_t)lo * g.n * g.es;
-        if constexpr (F16) reinterpret_cast<uint16_t*>(tab)[idx] = (uint16_t)raw;
-        else reinterpret_cast<uint32_t*>(tab)[idx] = raw;
     }
 }
 
@@ -269,10 +253,6 @@ hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_b
 #undef DLC_DEC
         if (prof_on(pl, P_DECODE)) prof_end(prof, P_DECODE, s);
     }
-    if (prof_on(pl, P_OUTLIERS)) prof_begin(prof, P_OUTLIERS, s);
-    if (f16) hipLaunchKernelGGL(k_outliers<true>, dim3(512), dim3(256), 0, s, g, comp, w.dlay, w.dtab, w.ctrl, out);
-    else hipLaunchKernelGGL(k_outliers<false>, dim3(512), dim3(256), 0, s, g, comp, w.dlay, w.dtab, w.ctrl, out);
-    if (prof_on(pl, P_OUTLIERS)) prof_end(prof, P_OUTLIERS, s);
     return hipGetLastError();
 }
 

@@ -11,15 +11,15 @@ namespace dlc {
 // ---- container constants (byte layout of the compressed buffer) -----------------------------
 constexpr uint32_t kW = 64;  // chunks per group = lanes of one wavefront
 constexpr uint32_t kV = 4;   // consecutive symbols a chunk takes per turn = one 16-byte fp32 load per lane
-constexpr uint32_t kMagic = 0x31434C44u;
-constexpr uint32_t kVersion = 1u;
+constexpr uint32_t kMagic = 0x32434C44u;  // "DLC2"
+constexpr uint32_t kVersion = 2u;
 constexpr uint32_t kHeaderBytes = 128;
 constexpr uint32_t kDirBytes = 56;
 constexpr int kLmaxLimit = 12;
 
 // header word / qword positions
 enum { H_MAGIC = 0, H_VERSION, H_DTYPE, H_T, H_B, H_D, H_R, H_S, H_LMAX, H_W, H_V, H_NG };  // u32 index
-enum { HQ_NOUT = 6, HQ_WORDS, HQ_OFF_CB, HQ_OFF_GROUP, HQ_OFF_CHUNK, HQ_OFF_OUTL, HQ_OFF_PAYLOAD, HQ_TOTAL };  // u64 index
+enum { HQ_NOUT = 6, HQ_WORDS, HQ_OFF_GROUP, HQ_OFF_CHUNK, HQ_OFF_PAYLOAD, HQ_OFF_CB, HQ_TOTAL };  // u64 index
 
 struct QParam {
     float eb, ebx2, inv;
@@ -39,15 +39,21 @@ struct Geom {
 // per-table results of the codebook step
 struct TMeta {
     uint32_t n_used, sym_lo, sym_hi, n_outliers;
-    uint64_t cb_off;    // byte offset of the table's code-length block
-    uint64_t outl_off;  // byte offset of its first escape record
+    uint64_t cb_off, outl_off;  // unused by the kernels; kept for the layout of the array
 };
 
-// section offsets of the container being written
-struct Layout {
-    uint64_t off_cb, off_group, off_chunk, off_outl, off_payload;
-    uint64_t n_out_total;
+// offsets of the container sections whose position depends on the geometry alone
+struct FixedLayout {
+    uint64_t off_group, off_chunk, off_payload;
 };
+
+inline __host__ __device__ FixedLayout fixed_layout(const Geom& g) {
+    FixedLayout F;
+    F.off_group = (kHeaderBytes + (uint64_t)kDirBytes * g.T + 15ull) & ~15ull;
+    F.off_chunk = (F.off_group + 4ull * g.NG + 15ull) & ~15ull;
+    F.off_payload = (F.off_chunk + (uint64_t)kW * g.NG + 15ull) & ~15ull;
+    return F;
+}
 
 // small control block; `status` is sticky until read by the host, the rest is cleared per call
 struct Ctrl {
@@ -61,12 +67,11 @@ struct Ctrl {
 struct DecLayout {
     uint32_t valid;
     uint32_t pad;
-    uint64_t off_group, off_chunk, off_outl, off_payload, words_total, n_out_total;
+    uint64_t off_group, off_chunk, off_payload, words_total;
 };
 
 struct DecTable {
     uint32_t valid, n_used, sym_lo, n_outliers;
-    uint64_t outl_off;
     float ebx2;
     uint32_t pad;
 };
@@ -186,14 +191,10 @@ struct Ws {
     QParam* qp = nullptr;          // [T]
     uint8_t* zero_begin = nullptr; // region cleared at the start of every compress call
     uint32_t* hist = nullptr;      // [T][K]
-    uint32_t* table_outliers = nullptr;  // [T]
     Ctrl* ctrl_call = nullptr;     // ticket, abort (inside the cleared region)
     uint8_t* zero_end = nullptr;
     Ctrl* ctrl = nullptr;          // same block as ctrl_call (status/collide are not cleared by the kernels)
-    uint32_t* group_outliers = nullptr;  // [NG]
-    uint32_t* group_out_base = nullptr;  // [NG]
     TMeta* tmeta = nullptr;        // [T]
-    Layout* layout = nullptr;
     uint16_t* enc = nullptr;       // [T][K]  len << 12 | codeword
     uint8_t* lens = nullptr;       // [T][K]
     uint64_t* state = nullptr;     // [NG] look-back records
@@ -217,8 +218,9 @@ struct Ws {
 // profiling hooks used by the launchers (implemented in dlc_api.hip)
 void prof_begin(void* prof, int slot, hipStream_t s);
 void prof_end(void* prof, int slot, hipStream_t s);
-enum ProfSlot { P_ZERO = 0, P_HIST, P_CODEBOOK, P_LAYOUT, P_ENCODE, P_FINALIZE, P_DEC_PREPARE, P_DECODE, P_OUTLIERS,
-                P_NSLOTS };
-inline bool prof_on(int level, int slot) { return level >= 2 || (level == 1 && (slot == P_ENCODE || slot == P_DECODE || slot == P_HIST)); }
+enum ProfSlot { P_ZERO = 0, P_HIST, P_CODEBOOK, P_ENCODE, P_FINALIZE, P_DEC_PREPARE, P_DECODE, P_FUSED, P_NSLOTS };
+inline bool prof_on(int level, int slot) {
+    return level >= 2 || (level == 1 && (slot == P_ENCODE || slot == P_DECODE || slot == P_HIST || slot == P_FUSED));
+}
 
 }  // namespace dlc

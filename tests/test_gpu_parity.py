@@ -231,7 +231,7 @@ def test_errors_and_robustness():
         elif mutate == "geometry":
             bad[16] ^= 1
         elif mutate == "total":
-            bad[104:112] = np.frombuffer(np.uint64(bad.size + 16).tobytes(), np.uint8)
+            bad[96:104] = np.frombuffer(np.uint64(bad.size + 16).tobytes(), np.uint8)
         st, _ = g.decompress(bad, nbytes)
         assert st == b.ECORRUPT, mutate
     st, rec = g.decompress(g.data)
