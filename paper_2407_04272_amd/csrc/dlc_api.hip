@@ -10,6 +10,7 @@
 
 namespace dlc {
 hipError_t compress_set_attributes();
+hipError_t decompress_set_attributes();
 
 struct Prof {
     int level = 0;
@@ -162,7 +163,11 @@ extern "C" int dlc_create(dlc_ctx** out, const dlc_config* cfg) {
     if (hipMalloc((void**)&base, bytes) != hipSuccess) { (void)hipGetLastError(); delete c; return DLC_ENOMEM; }
     if (hipMemset(base, 0, bytes) != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }
     carve(g, base, &c->ws);
-    if (compress_set_attributes() != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }
+    if (compress_set_attributes() != hipSuccess || decompress_set_attributes() != hipSuccess) {
+        (void)hipFree(base);
+        delete c;
+        return DLC_EHIP;
+    }
     if (hipHostMalloc((void**)&c->pin, sizeof(QParam) * g.T * dlc_ctx::kRing, hipHostMallocDefault) != hipSuccess) {
         (void)hipGetLastError();
         (void)hipFree(base);

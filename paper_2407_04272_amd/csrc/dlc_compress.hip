@@ -54,7 +54,10 @@ hipError_t launch_quantize(const Geom& g, const void* payload, const QParam* qp,
 //   LDS : K << clog2 counters; a lane adds into copy (lane & (C-1)) of its bin so that the few hot
 //         bins of a bell-shaped distribution spread over C banks instead of serialising on one address
 // ------------------------------------------------------------------------------------------------
-constexpr uint32_t kHistBlk = 4;  // turns whose loads are issued back to back (S/4 is a multiple)
+#ifndef DLC_EXP_HIST_BLK
+#define DLC_EXP_HIST_BLK 4
+#endif
+constexpr uint32_t kHistBlk = DLC_EXP_HIST_BLK;  // turns whose loads are issued back to back (S/4 is a multiple)
 
 // FULL: every position of the group is inside the table (no masking at all)
 template <bool F16, bool VEC, bool FULL>
@@ -72,7 +75,11 @@ __device__ __forceinline__ void hist_group(const uint8_t* gbase, uint32_t rem, u
         for (uint32_t u = 0; u < kHistBlk; ++u) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
+#ifdef DLC_EXP_HIST_NOCOMPUTE
+                const uint32_t c = raw[u][v] & 1023u;
+#else
                 const uint32_t c = quant_symbol<F16>(x[u][v], q, Rf, R);
+#endif
                 uint32_t byte = (c << (clog2 + 2u)) + cm4;
                 // branch-free: a position past the end of the table counts into a scratch bin of its own lane
                 if constexpr (!FULL) byte = ((valid[u] >> v) & 1u) ? byte : trash;
@@ -275,6 +282,9 @@ __device__ __forceinline__ void codebook_build(const Geom& g, const uint32_t* hi
     }
     if (tid == 0) {
         TMeta m;
+        // an empty histogram cannot come out of the histogram kernel (every table has an element); should it
+        // happen anyway, the symbol range must still be a valid one for the kernels that size things from it
+        if (n_used == 0) { sh.lo = 0; sh.hi = 0; }
         m.n_used = n_used; m.sym_lo = sh.lo; m.sym_hi = sh.hi; m.n_outliers = hist_t[0];  // symbol 0 = escape
         m.cb_off = 0; m.outl_off = 0;
         *tmeta_t = m;
@@ -501,7 +511,12 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
     uint64_t cb_total = 0;
     for (uint32_t base = 0; base < g.T; base += 1024) {
         const uint32_t t = base + tid;
-        uint32_t cb = t < g.T ? (tmeta[t].sym_hi - tmeta[t].sym_lo + 1u + 3u) & ~3u : 0u;
+        uint32_t cb = 0;
+        if (t < g.T) {
+            uint32_t lo = tmeta[t].sym_lo, hi = tmeta[t].sym_hi;
+            if (lo > hi || hi >= g.K) { lo = 0; hi = 0; }
+            cb = (hi - lo + 1u + 3u) & ~3u;
+        }
         uint32_t tot;
         (void)block_excl_scan<16>(cb, s_red, tid, &tot);
         __syncthreads();
@@ -523,6 +538,7 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
         uint32_t cb = 0, no = 0;
         if (t < g.T) {
             m = tmeta[t];
+            if (m.sym_lo > m.sym_hi || m.sym_hi >= g.K) { m.sym_lo = 0; m.sym_hi = 0; }  // never index outside lens[]
             cb = (m.sym_hi - m.sym_lo + 1u + 3u) & ~3u;
             no = m.n_outliers;
         }
@@ -599,12 +615,18 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         if (prof_on(pl, P_ZERO)) prof_end(prof, P_ZERO, s);
     }
     // histogram: up to 8 copies of each bin, 32 KiB of LDS at most
-    uint32_t clog2 = 3;
+#ifndef DLC_EXP_HIST_CLOG2
+#define DLC_EXP_HIST_CLOG2 3
+#endif
+    uint32_t clog2 = DLC_EXP_HIST_CLOG2;
     while (clog2 > 0 && ((size_t)g.K << clog2) * 4 > 32768) --clog2;
     uint32_t bpt_h = (g.G + 3) / 4;
     {
         // cap the grid at a few work-groups per CU; a work-group then loops over groups of its table
-        const uint32_t max_blocks = 256 * 8;
+#ifndef DLC_EXP_HIST_BLOCKS
+#define DLC_EXP_HIST_BLOCKS (256 * 8)
+#endif
+        const uint32_t max_blocks = DLC_EXP_HIST_BLOCKS;
         const uint32_t cap = std::max<uint32_t>(1, max_blocks / g.T);
         bpt_h = std::min(bpt_h, cap);
         size_t sm = ((size_t)g.K << clog2) * 4 + kW * 4;  // + one scratch bin per lane

@@ -137,12 +137,20 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
 // chunk-parallel decode: one wavefront per group, lane l walks chunk l.  Each lane keeps a 64-bit
 // window of its own bit stream, looks LMAX bits up in the table's LDS decode table, and the four
 // symbols of a turn leave as one 16-byte store (1 KiB contiguous per wavefront instruction).
+//
+// The bit stream words reach the lanes through LDS: every lane copies the next kWin words of its chunk
+// into column `lane` of a [kWin][64] staging array of its wavefront (bank = lane, so the lanes never
+// collide whatever word each of them is at) and refills its window from there.  The decode loop then
+// holds no global load, so nothing in it ever waits for memory: the stores just stream out.
 // ------------------------------------------------------------------------------------------------
+constexpr uint32_t kWin = 32;            // staged words per lane
+constexpr uint32_t kDecWaves = 8;        // wavefronts per work-group
+
 template <bool F16, bool VEC>
 __global__ __launch_bounds__(512) void k_decode(Geom g, const uint8_t* comp, const uint16_t* lut, const DecLayout* dlay,
                                                 const DecTable* dtab, Ctrl* ctrl, void* outp, uint32_t bpt) {
-    extern __shared__ __align__(16) uint16_t s_lut[];
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    extern __shared__ __align__(16) uint16_t s_lut[];  // [1 << LMAX] decode table, then kDecWaves staging arrays
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t t = blockIdx.x / bpt, b = blockIdx.x % bpt;
     const DecLayout L = *dlay;
     const DecTable D = dtab[t];
@@ -154,8 +162,9 @@ __global__ __launch_bounds__(512) void k_decode(Geom g, const uint8_t* comp, con
         for (uint32_t i = tid; i < lut_n / 8; i += 512) dst[i] = src[i];
     }
     __syncthreads();
-    const uint32_t grp = b * 8 + wave;
-    if (grp >= g.G) return;
+    const uint32_t grp = b * kDecWaves + wave;
+    if (grp >= g.G) return;  // whole wavefront; no barrier follows
+    uint32_t* stage = reinterpret_cast<uint32_t*>(s_lut + lut_n) + wave * (kWin * kW) + lane;  // my column
     const uint32_t gid = t * g.G + grp;
     const uint32_t cw = comp[L.off_chunk + (uint64_t)gid * kW + lane];
     const uint32_t incl = wave_incl_scan(cw, lane);
@@ -169,11 +178,25 @@ __global__ __launch_bounds__(512) void k_decode(Geom g, const uint8_t* comp, con
         return;
     }
     const uint32_t n_esc = (uint32_t)((gend - goff - total) >> 1);
-    const uint32_t* p = reinterpret_cast<const uint32_t*>(comp + L.off_payload) + goff + (incl - cw);
-    const uint32_t* pend = p + cw;
-    uint64_t buf = 0;
-    if (p < pend) buf = (uint64_t)(*p++) << 32;
-    if (p < pend) buf |= (uint64_t)(*p++);
+    const uint32_t* chunk = reinterpret_cast<const uint32_t*>(comp + L.off_payload) + goff + (incl - cw);
+    uint32_t taken = 0;   // words of the chunk already moved into buf
+    uint32_t wbase = 0;   // chunk word index of staging row 0
+    // stage words [wbase, wbase + kWin) of my chunk (zero past its end).  Branch-free, all loads in flight
+    // together: an index past the end reads the chunk's last word instead (an empty chunk reads the word at
+    // its position, which still lies inside the container: code-length blocks follow the payload) and is
+    // masked to zero.
+    const uint32_t last = cw ? cw - 1u : 0u;
+    auto restage = [&]() {
+        wbase = taken;
+        uint32_t w[kWin];
+#pragma unroll
+        for (uint32_t k = 0; k < kWin; ++k) w[k] = chunk[min(wbase + k, last)];
+#pragma unroll
+        for (uint32_t k = 0; k < kWin; ++k) stage[k * kW] = wbase + k < cw ? w[k] : 0u;
+    };
+    restage();
+    uint64_t buf = ((uint64_t)stage[0] << 32) | stage[kW];
+    taken = 2;
     uint32_t nb = 64;  // bits of buf in use (bits past the end of the chunk read as zero)
     const float ebx2 = D.ebx2;
     const int R = (int)g.R;
@@ -183,42 +206,47 @@ __global__ __launch_bounds__(512) void k_decode(Geom g, const uint8_t* comp, con
     const uint32_t turns = g.S / kV;
     for (uint32_t j = 0; j < turns; ++j) {
         const uint32_t idx = base + j * (kW * kV);
-        if (idx >= g.n) break;
-        float v4[4];
+        // a turn takes at most two more words; restage (whole wavefront) when a lane could run off its rows
+        if (__ballot(taken + 2u > wbase + kWin && taken < cw) != 0ull) restage();
+        if (idx < g.n) {
+            float v4[4];
 #pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-            if (nb <= 32u) {
-                const uint64_t wv = p < pend ? (uint64_t)(*p++) : 0ull;
-                buf |= wv << (32u - nb);
-                nb += 32u;
-            }
-#pragma unroll
-            for (int v = 0; v < 2; ++v) {
-                const uint32_t e = s_lut[(uint32_t)(buf >> shift)];
-                const uint32_t len = e >> 12;
-                buf <<= len;
-                nb -= len;
-                v4[h2 * 2 + v] = (float)((int)(e & 0xFFFu) - R) * ebx2;
-            }
-        }
-        if constexpr (VEC) {
-            if constexpr (F16) {
-                uint2 o;
-                o.x = (uint32_t)__half_as_ushort(__float2half_rn(v4[0])) |
-                      ((uint32_t)__half_as_ushort(__float2half_rn(v4[1])) << 16);
-                o.y = (uint32_t)__half_as_ushort(__float2half_rn(v4[2])) |
-                      ((uint32_t)__half_as_ushort(__float2half_rn(v4[3])) << 16);
-                *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(tab) + idx) = o;
-            } else {
-                *reinterpret_cast<float4*>(reinterpret_cast<float*>(tab) + idx) = make_float4(v4[0], v4[1], v4[2], v4[3]);
-            }
-        } else {
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-                if (idx + v < g.n) {
-                    if constexpr (F16) reinterpret_cast<__half*>(tab)[idx + v] = __float2half_rn(v4[v]);
-                    else reinterpret_cast<float*>(tab)[idx + v] = v4[v];
+            for (int h2 = 0; h2 < 2; ++h2) {
+                if (nb <= 32u) {
+                    const uint32_t k = taken - wbase;  // < kWin by the restage rule (rows past the chunk's end are zero)
+                    buf |= (uint64_t)stage[(k < kWin ? k : kWin - 1u) * kW] << (32u - nb);
+                    nb += 32u;
+                    ++taken;
                 }
+#pragma unroll
+                for (int v = 0; v < 2; ++v) {
+                    const uint32_t e = s_lut[(uint32_t)(buf >> shift)];
+                    const uint32_t len = e >> 12;
+                    buf <<= len;
+                    nb -= len;
+                    v4[h2 * 2 + v] = (float)((int)(e & 0xFFFu) - R) * ebx2;
+                }
+            }
+            if constexpr (VEC) {
+                if constexpr (F16) {
+                    uint2 o;
+                    o.x = (uint32_t)__half_as_ushort(__float2half_rn(v4[0])) |
+                          ((uint32_t)__half_as_ushort(__float2half_rn(v4[1])) << 16);
+                    o.y = (uint32_t)__half_as_ushort(__float2half_rn(v4[2])) |
+                          ((uint32_t)__half_as_ushort(__float2half_rn(v4[3])) << 16);
+                    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(tab) + idx) = o;
+                } else {
+                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(tab) + idx) =
+                        make_float4(v4[0], v4[1], v4[2], v4[3]);
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (idx + v < g.n) {
+                        if constexpr (F16) reinterpret_cast<__half*>(tab)[idx + v] = __float2half_rn(v4[v]);
+                        else reinterpret_cast<float*>(tab)[idx + v] = v4[v];
+                    }
+            }
         }
     }
     if (n_esc != 0u) {  // uniform over the wavefront: verbatim values over the decoded placeholders
@@ -243,9 +271,9 @@ hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_b
     hipLaunchKernelGGL(k_dec_prepare, dim3(g.T), dim3(256), 0, s, g, comp, comp_bytes, w.lut, w.dlay, w.dtab, w.ctrl);
     if (prof_on(pl, P_DEC_PREPARE)) prof_end(prof, P_DEC_PREPARE, s);
     {
-        const uint32_t bpt = (g.G + 7) / 8;
-        dim3 grid(g.T * bpt), block(512);
-        const size_t sm = (size_t)2 << g.LMAX;
+        const uint32_t bpt = (g.G + kDecWaves - 1) / kDecWaves;
+        dim3 grid(g.T * bpt), block(64 * kDecWaves);
+        const size_t sm = ((size_t)2 << g.LMAX) + (size_t)kDecWaves * kWin * kW * 4;
         if (prof_on(pl, P_DECODE)) prof_begin(prof, P_DECODE, s);
 #define DLC_DEC(F, V) hipLaunchKernelGGL((k_decode<F, V>), grid, block, sm, s, g, comp, w.lut, w.dlay, w.dtab, w.ctrl, out, bpt)
         if (f16) { if (g.vec) DLC_DEC(true, true); else DLC_DEC(true, false); }
@@ -254,6 +282,22 @@ hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_b
         if (prof_on(pl, P_DECODE)) prof_end(prof, P_DECODE, s);
     }
     return hipGetLastError();
+}
+
+hipError_t decompress_set_attributes() {
+    const int bytes = (2 << kLmaxLimit) + (int)(kDecWaves * kWin * kW * 4);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_decode<false, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_decode<false, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_decode<true, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_decode<true, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    return e;
 }
 
 }  // namespace dlc
