@@ -41,7 +41,7 @@ void prof_end(void* p, int slot, hipStream_t s) {
     pr->recs.push_back({slot, pr->pending[slot], e});
 }
 
-static const char* kSlotNames[P_NSLOTS] = {"k_zero", "k_hist", "k_codebook", "k_encode", "k_finalize",
+static const char* kSlotNames[P_NSLOTS] = {"k_hist", "k_codebook", "k_encode", "k_finalize",
                                            "k_dec_prepare", "k_decode", "k_fused"};
 }  // namespace dlc
 
@@ -113,13 +113,9 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
         return p;
     };
     uint8_t* qp = take(sizeof(QParam) * g.T);
-    // cleared per call: histograms, first 16 bytes of the control block
-    size_t z0 = off;
-    uint8_t* hist = base ? base + off : nullptr;
-    off += (size_t)g.T * g.K * 4;
-    uint8_t* ctrl = base ? base + off : nullptr;
-    size_t z1 = off + 16;
-    off = a256(off + sizeof(Ctrl));
+    uint8_t* hist = take((size_t)g.T * g.K * 4);
+    uint8_t* hview = take((size_t)g.T * g.K * 4);
+    uint8_t* ctrl = take(sizeof(Ctrl));
     uint8_t* tmeta = take(sizeof(TMeta) * g.T);
     uint8_t* enc = take(2 * (size_t)g.T * g.K);
     uint8_t* lens = take((size_t)g.T * g.K);
@@ -132,8 +128,7 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
     if (w) {
         w->base = base; w->bytes = off;
         w->qp = (QParam*)qp;
-        w->zero_begin = base ? base + z0 : nullptr; w->zero_end = base ? base + z1 : nullptr;
-        w->hist = (uint32_t*)hist; w->ctrl = (Ctrl*)ctrl; w->ctrl_call = (Ctrl*)ctrl;
+        w->hist = (uint32_t*)hist; w->hist_view = (uint32_t*)hview; w->ctrl = (Ctrl*)ctrl;
         w->tmeta = (TMeta*)tmeta;
         w->enc = (uint16_t*)enc; w->lens = lens; w->state = (uint64_t*)state;
         w->word_start = (uint32_t*)ws0; w->word_end = (uint32_t*)ws1; w->lut = (uint16_t*)lut;
@@ -389,7 +384,8 @@ extern "C" int dlc_quantize(dlc_ctx* c, const void* d_payload, uint16_t* d_sym, 
 extern "C" int dlc_read_histogram(dlc_ctx* c, uint32_t* h_hist, void* stream) {
     if (!c || !h_hist) return DLC_EINVAL;
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return DLC_EHIP;
-    return hipMemcpy(h_hist, c->ws.hist, 4ull * c->g.T * c->g.K, hipMemcpyDeviceToHost) == hipSuccess ? DLC_OK : DLC_EHIP;
+    return hipMemcpy(h_hist, c->ws.hist_view, 4ull * c->g.T * c->g.K, hipMemcpyDeviceToHost) == hipSuccess ? DLC_OK
+                                                                                                            : DLC_EHIP;
 }
 
 extern "C" int dlc_read_codebook(dlc_ctx* c, uint8_t* h_len, uint16_t* h_code, void* stream) {

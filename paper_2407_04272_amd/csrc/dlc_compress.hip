@@ -51,19 +51,28 @@ hipError_t launch_quantize(const Geom& g, const void* payload, const QParam* qp,
 // ------------------------------------------------------------------------------------------------
 // quantise + LDS-privatised histogram
 //   grid: T * bpt work-groups of 4 wavefronts; a work-group stays inside one table
-//   LDS : K << clog2 counters; a lane adds into copy (lane & (C-1)) of its bin so that the few hot
-//         bins of a bell-shaped distribution spread over C banks instead of serialising on one address
+//   LDS : LDS atomics with 64 scattered addresses cost one pass per lane that shares a bank, and that -- not
+//         HBM, not the ALU -- bounds this kernel.  So the bins around the centre of the alphabet (where a
+//         bell-shaped distribution puts almost everything) get 32 copies each, copy = lane & 31: the bank of
+//         an update is then the lane's own, whatever its symbol, and a wavefront's 64 updates take the minimum
+//         of two passes.  Symbols outside that window go to a single-copy array (rare), positions past the end
+//         of the table to a scratch word per lane.
+//         layout in words: window [kHistWin][32] | overflow [K] | scratch [64]
 // ------------------------------------------------------------------------------------------------
-#ifndef DLC_EXP_HIST_BLK
-#define DLC_EXP_HIST_BLK 4
-#endif
-constexpr uint32_t kHistBlk = DLC_EXP_HIST_BLK;  // turns whose loads are issued back to back (S/4 is a multiple)
+constexpr uint32_t kHistBlk = 4;    // turns whose loads are issued back to back (S/4 is a multiple)
+constexpr uint32_t kHistWin = 256;  // bins with private copies (all of them when K <= 256)
+constexpr uint32_t kHistCopies = 32;
+
+struct HistLds {
+    uint32_t win_bins, win_lo;   // window = symbols [win_lo, win_lo + win_bins)
+    uint32_t ovf_byte, trash_byte;  // byte offsets of the overflow array and of this lane's scratch word
+};
 
 // FULL: every position of the group is inside the table (no masking at all)
 template <bool F16, bool VEC, bool FULL>
 __device__ __forceinline__ void hist_group(const uint8_t* gbase, uint32_t rem, uint32_t turns, uint32_t lane,
-                                           const QParam& q, float Rf, int R, uint32_t* lh, uint32_t clog2, uint32_t cm4,
-                                           uint32_t trash) {
+                                           const QParam& q, float Rf, int R, uint32_t* lh, const HistLds& H) {
+    const uint32_t copy4 = (lane & (kHistCopies - 1u)) * 4u;
     for (uint32_t jb = 0; jb < turns; jb += kHistBlk) {
         float x[kHistBlk][4];
         uint32_t raw[kHistBlk][4];
@@ -75,47 +84,55 @@ __device__ __forceinline__ void hist_group(const uint8_t* gbase, uint32_t rem, u
         for (uint32_t u = 0; u < kHistBlk; ++u) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-#ifdef DLC_EXP_HIST_NOCOMPUTE
-                const uint32_t c = raw[u][v] & 1023u;
-#else
                 const uint32_t c = quant_symbol<F16>(x[u][v], q, Rf, R);
-#endif
-                uint32_t byte = (c << (clog2 + 2u)) + cm4;
-                // branch-free: a position past the end of the table counts into a scratch bin of its own lane
-                if constexpr (!FULL) byte = ((valid[u] >> v) & 1u) ? byte : trash;
+                const uint32_t w = c - H.win_lo;  // wraps for symbols below the window
+                uint32_t byte = w < H.win_bins ? w * (kHistCopies * 4u) + copy4 : H.ovf_byte + c * 4u;
+                if constexpr (!FULL) byte = ((valid[u] >> v) & 1u) ? byte : H.trash_byte;
                 atomicAdd(reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(lh) + byte), 1u);
             }
         }
     }
 }
 
+__host__ __device__ inline uint32_t hist_win_bins(uint32_t K) { return K < kHistWin ? K : kHistWin; }
+__host__ __device__ inline size_t hist_lds_bytes(uint32_t K) { return ((size_t)hist_win_bins(K) * kHistCopies + K + kW) * 4; }
+
 template <bool F16, bool VEC>
 __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const QParam* qp, uint32_t* hist,
-                                              uint32_t bpt, uint32_t clog2) {
+                                              uint32_t bpt) {
     extern __shared__ __align__(16) uint32_t lh[];
     const uint32_t t = blockIdx.x / bpt, b = blockIdx.x % bpt;
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t nbins = g.K << clog2;
-    for (uint32_t k = tid; k < nbins + kW; k += 256) lh[k] = 0;
+    HistLds H;
+    H.win_bins = hist_win_bins(g.K);
+    H.win_lo = g.R - H.win_bins / 2u;  // symbol R is the bin of value 0
+    const uint32_t n_words = H.win_bins * kHistCopies + g.K + kW;
+    H.ovf_byte = H.win_bins * kHistCopies * 4u;
+    H.trash_byte = (H.win_bins * kHistCopies + g.K + lane) * 4u;
+    for (uint32_t k = tid; k < n_words; k += 256) lh[k] = 0;
     __syncthreads();
     const QParam q = qp[t];
     const float Rf = (float)g.R;
-    const uint32_t cm4 = (lane & ((1u << clog2) - 1u)) * 4u;
-    const uint32_t trash = (nbins + lane) * 4u;
     const uint8_t* tab = static_cast<const uint8_t*>(payload) + (size_t)t * g.n * g.es;
     const uint32_t turns = g.S / kV;
     for (uint32_t grp = b * 4 + wave; grp < g.G; grp += bpt * 4) {
         const uint32_t gstart = grp * (kW * g.S);
         const uint8_t* gbase = tab + (size_t)gstart * g.es;
         const uint32_t rem = g.n - gstart;
-        if (rem >= kW * g.S) hist_group<F16, VEC, true>(gbase, rem, turns, lane, q, Rf, (int)g.R, lh, clog2, cm4, trash);
-        else hist_group<F16, VEC, false>(gbase, rem, turns, lane, q, Rf, (int)g.R, lh, clog2, cm4, trash);
+        if (rem >= kW * g.S) hist_group<F16, VEC, true>(gbase, rem, turns, lane, q, Rf, (int)g.R, lh, H);
+        else hist_group<F16, VEC, false>(gbase, rem, turns, lane, q, Rf, (int)g.R, lh, H);
     }
     __syncthreads();
-    const uint32_t C = 1u << clog2;
+    // merge: window bins (sum of the copies, skewed start so that the threads of a wavefront read different
+    // banks) plus the overflow array
+    const uint32_t* ovf = lh + H.win_bins * kHistCopies;
     for (uint32_t k = tid; k < g.K; k += 256) {
-        uint32_t s = 0;
-        for (uint32_t c = 0; c < C; ++c) s += lh[(k << clog2) + c];
+        uint32_t s = ovf[k];
+        const uint32_t w = k - H.win_lo;
+        if (w < H.win_bins) {
+            const uint32_t* row = lh + w * kHistCopies;
+            for (uint32_t c = 0; c < kHistCopies; ++c) s += row[(c + tid) & (kHistCopies - 1u)];
+        }
         if (s) atomicAdd(&hist[(size_t)t * g.K + k], s);
     }
 }
@@ -135,8 +152,10 @@ struct CodebookShared {
     uint32_t lo, hi, maxlen, cl[kLmaxLimit + 2], next[kLmaxLimit + 2];
 };
 
-__device__ __forceinline__ void codebook_build(const Geom& g, const uint32_t* hist_t, uint16_t* enc_t, uint8_t* lens_t,
-                                               TMeta* tmeta_t, unsigned char* smem, CodebookShared& sh, uint32_t tid) {
+// hist_t is read, copied to hist_view_t (inspection) and cleared, so that the next call starts from zero counts.
+__device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, uint32_t* hist_view_t, uint16_t* enc_t,
+                                               uint8_t* lens_t, TMeta* tmeta_t, unsigned char* smem, CodebookShared& sh,
+                                               uint32_t tid) {
     const uint32_t K = g.K;
     uint64_t* key = reinterpret_cast<uint64_t*>(smem);        // [K] sort keys: count << 16 | symbol
     uint32_t* cnt = reinterpret_cast<uint32_t*>(key + K);      // [K] counts
@@ -149,7 +168,10 @@ __device__ __forceinline__ void codebook_build(const Geom& g, const uint32_t* hi
 
     DLC_STAMP(0);
     for (uint32_t k = tid; k < K; k += 256) {
-        cnt[k] = hist_t[k];
+        const uint32_t h = hist_t[k];
+        cnt[k] = h;
+        hist_view_t[k] = h;
+        hist_t[k] = 0;
         len_s[k] = 0;
     }
     if (tid == 0) { sh.lo = 0xFFFFFFFFu; sh.hi = 0; sh.maxlen = 0; }
@@ -285,7 +307,7 @@ __device__ __forceinline__ void codebook_build(const Geom& g, const uint32_t* hi
         // an empty histogram cannot come out of the histogram kernel (every table has an element); should it
         // happen anyway, the symbol range must still be a valid one for the kernels that size things from it
         if (n_used == 0) { sh.lo = 0; sh.hi = 0; }
-        m.n_used = n_used; m.sym_lo = sh.lo; m.sym_hi = sh.hi; m.n_outliers = hist_t[0];  // symbol 0 = escape
+        m.n_used = n_used; m.sym_lo = sh.lo; m.sym_hi = sh.hi; m.n_outliers = cnt[0];  // symbol 0 = escape
         m.cb_off = 0; m.outl_off = 0;
         *tmeta_t = m;
     }
@@ -293,13 +315,13 @@ __device__ __forceinline__ void codebook_build(const Geom& g, const uint32_t* hi
     DLC_STAMP(7);
 }
 
-__global__ __launch_bounds__(256) void k_codebook(Geom g, const uint32_t* hist, uint16_t* enc, uint8_t* lens,
-                                                  TMeta* tmeta) {
+__global__ __launch_bounds__(256) void k_codebook(Geom g, uint32_t* hist, uint32_t* hist_view, uint16_t* enc,
+                                                  uint8_t* lens, TMeta* tmeta) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ CodebookShared sh;
     const uint32_t t = blockIdx.x;
-    codebook_build(g, hist + (size_t)t * g.K, enc + (size_t)t * g.K, lens + (size_t)t * g.K, tmeta + t, smem, sh,
-                   threadIdx.x);
+    codebook_build(g, hist + (size_t)t * g.K, hist_view + (size_t)t * g.K, enc + (size_t)t * g.K,
+                   lens + (size_t)t * g.K, tmeta + t, smem, sh, threadIdx.x);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -493,98 +515,99 @@ void k_encode(const void* payload, Geom g, FixedLayout F, const QParam* qp, cons
 }
 
 // ------------------------------------------------------------------------------------------------
-// finalize: code-length blocks behind the payload, header, directory, padding, size metadata.
-//   one work-group of 1024 threads
+// finalize: code-length blocks behind the payload, header, directory, padding, size metadata; clears the
+// per-call control words for the next call.  One work-group of 1024 threads.
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint64_t a16(uint64_t x) { return (x + 15ull) & ~15ull; }
 
-__global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const TMeta* tmeta, const uint8_t* lens,
+__global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const TMeta* tmeta, const uint8_t* __restrict__ lens,
                                                    const QParam* qp, Ctrl* ctrl, const uint32_t* word_start,
                                                    const uint32_t* word_end, uint8_t* __restrict__ out, uint64_t capacity,
                                                    uint64_t* out_bytes) {
     __shared__ uint32_t s_red[17];
     __shared__ uint32_t s_abort;
+    __shared__ uint32_t s_cb[1025];   // start of each table's block, relative to the pass's first block
+    __shared__ uint32_t s_lo[1024], s_nl[1024];
     const uint32_t tid = threadIdx.x;
     const uint64_t words = word_end[g.T - 1];
     const uint64_t off_cb = a16(F.off_payload + 4ull * words);
-    // total size: sum of the code-length blocks over the tables
-    uint64_t cb_total = 0;
-    for (uint32_t base = 0; base < g.T; base += 1024) {
-        const uint32_t t = base + tid;
-        uint32_t cb = 0;
-        if (t < g.T) {
-            uint32_t lo = tmeta[t].sym_lo, hi = tmeta[t].sym_hi;
-            if (lo > hi || hi >= g.K) { lo = 0; hi = 0; }
-            cb = (hi - lo + 1u + 3u) & ~3u;
-        }
-        uint32_t tot;
-        (void)block_excl_scan<16>(cb, s_red, tid, &tot);
-        __syncthreads();
-        cb_total += tot;
-    }
-    if (tid == 0) {
-        s_abort = ctrl->abort != 0 || off_cb + cb_total > capacity;
-        if (s_abort && ctrl->abort == 0) { ctrl->abort = 1; set_status(ctrl, DLC_ECAPACITY); }
-    }
-    __syncthreads();
-    if (s_abort) {
-        for (uint32_t t = tid; t < g.T + 1; t += 1024) out_bytes[t] = 0;
-        return;
-    }
+    const bool aborted = ctrl->abort != 0;
     uint64_t cb_carry = 0, nout_carry = 0;
     for (uint32_t base = 0; base < g.T; base += 1024) {
         const uint32_t t = base + tid;
         TMeta m;
-        uint32_t cb = 0, no = 0;
+        uint32_t cb = 0, no = 0, nl = 0;
         if (t < g.T) {
             m = tmeta[t];
             if (m.sym_lo > m.sym_hi || m.sym_hi >= g.K) { m.sym_lo = 0; m.sym_hi = 0; }  // never index outside lens[]
-            cb = (m.sym_hi - m.sym_lo + 1u + 3u) & ~3u;
+            nl = m.sym_hi - m.sym_lo + 1u;
+            cb = (nl + 3u) & ~3u;
             no = m.n_outliers;
         }
         uint32_t cb_tot, no_tot;
         const uint32_t cb_ex = block_excl_scan<16>(cb, s_red, tid, &cb_tot);
         __syncthreads();
         (void)block_excl_scan<16>(no, s_red, tid, &no_tot);
+        s_cb[tid] = cb_ex;
+        s_lo[tid] = m.sym_lo;
+        s_nl[tid] = nl;
+        if (tid == 0) {
+            s_cb[1024] = cb_tot;
+            // the code-length blocks are the last thing in the container: the capacity check of this pass
+            s_abort = aborted || off_cb + cb_carry + cb_tot > capacity;
+        }
         __syncthreads();
+        if (s_abort) break;  // uniform
+        const uint32_t nt = min(1024u, g.T - base);
+        // the pass's blocks, byte by byte: binary search for the table of byte j
+        for (uint32_t j = tid; j < cb_tot; j += 1024) {
+            uint32_t lo = 0, hi = nt - 1u;
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi + 1u) >> 1;
+                if (s_cb[mid] <= j) lo = mid; else hi = mid - 1u;
+            }
+            const uint32_t i = j - s_cb[lo];
+            out[off_cb + cb_carry + j] = i < s_nl[lo] ? lens[(size_t)(base + lo) * g.K + s_lo[lo] + i] : (uint8_t)0;
+        }
         if (t < g.T) {
-            const uint64_t my_cb = off_cb + cb_carry + cb_ex;
             const uint64_t w0 = word_start[t], w1 = word_end[t];
             uint8_t* d = out + kHeaderBytes + (uint64_t)kDirBytes * t;
             uint32_t* d32 = reinterpret_cast<uint32_t*>(d);
             d32[0] = qp[t].eb_bits; d32[1] = m.n_used; d32[2] = m.sym_lo; d32[3] = m.sym_hi; d32[4] = m.n_outliers;
             d32[5] = g.G;
             uint64_t* d64 = reinterpret_cast<uint64_t*>(d + 24);
-            d64[0] = my_cb; d64[1] = 0; d64[2] = w0; d64[3] = w1 - w0;
-            // code lengths of the used symbol range, zero-padded to 4 bytes: a few dozen bytes per table
-            const uint32_t nl = m.sym_hi - m.sym_lo + 1u;
-            const uint8_t* __restrict__ src = lens + (size_t)t * g.K + m.sym_lo;
-            for (uint32_t i = 0; i < cb; ++i) out[my_cb + i] = i < nl ? src[i] : (uint8_t)0;
+            d64[0] = off_cb + cb_carry + cb_ex; d64[1] = 0; d64[2] = w0; d64[3] = w1 - w0;
             out_bytes[1 + t] = 4ull * (w1 - w0) + cb + (uint64_t)(kW + 4u) * g.G + kDirBytes;
         }
         cb_carry += cb_tot;
         nout_carry += no_tot;
+        __syncthreads();
     }
-    // padding between sections
-    {
+    if (s_abort) {
+        if (tid == 0 && !aborted) set_status(ctrl, DLC_ECAPACITY);
+        for (uint32_t t = tid; t < g.T + 1; t += 1024) out_bytes[t] = 0;
+    } else {
+        // padding between sections
         const uint64_t e0 = kHeaderBytes + (uint64_t)kDirBytes * g.T;
         for (uint64_t i = e0 + tid; i < F.off_group; i += 1024) out[i] = 0;
         const uint64_t e1 = F.off_group + 4ull * g.NG;
         for (uint64_t i = e1 + tid; i < F.off_chunk; i += 1024) out[i] = 0;
         const uint64_t e2 = F.off_payload + 4ull * words;
         for (uint64_t i = e2 + tid; i < off_cb; i += 1024) out[i] = 0;
+        if (tid == 0) {
+            uint32_t* h = reinterpret_cast<uint32_t*>(out);
+            h[H_MAGIC] = kMagic; h[H_VERSION] = kVersion; h[H_DTYPE] = g.dtype; h[H_T] = g.T; h[H_B] = g.B; h[H_D] = g.D;
+            h[H_R] = g.R; h[H_S] = g.S; h[H_LMAX] = g.LMAX; h[H_W] = kW; h[H_V] = kV; h[H_NG] = g.NG;
+            uint64_t* q = reinterpret_cast<uint64_t*>(out);
+            q[HQ_NOUT] = nout_carry; q[HQ_WORDS] = words; q[HQ_OFF_GROUP] = F.off_group; q[HQ_OFF_CHUNK] = F.off_chunk;
+            q[HQ_OFF_PAYLOAD] = F.off_payload; q[HQ_OFF_CB] = off_cb;
+            const uint64_t total = off_cb + cb_carry;
+            q[HQ_TOTAL] = total; q[HQ_TOTAL + 1] = 0; q[HQ_TOTAL + 2] = 0; q[HQ_TOTAL + 3] = 0;
+            out_bytes[0] = total;
+        }
     }
-    if (tid == 0) {
-        uint32_t* h = reinterpret_cast<uint32_t*>(out);
-        h[H_MAGIC] = kMagic; h[H_VERSION] = kVersion; h[H_DTYPE] = g.dtype; h[H_T] = g.T; h[H_B] = g.B; h[H_D] = g.D;
-        h[H_R] = g.R; h[H_S] = g.S; h[H_LMAX] = g.LMAX; h[H_W] = kW; h[H_V] = kV; h[H_NG] = g.NG;
-        uint64_t* q = reinterpret_cast<uint64_t*>(out);
-        q[HQ_NOUT] = nout_carry; q[HQ_WORDS] = words; q[HQ_OFF_GROUP] = F.off_group; q[HQ_OFF_CHUNK] = F.off_chunk;
-        q[HQ_OFF_PAYLOAD] = F.off_payload; q[HQ_OFF_CB] = off_cb;
-        const uint64_t total = off_cb + cb_total;
-        q[HQ_TOTAL] = total; q[HQ_TOTAL + 1] = 0; q[HQ_TOTAL + 2] = 0; q[HQ_TOTAL + 3] = 0;
-        out_bytes[0] = total;
-    }
+    // the next call starts with ticket 0 and no abort (the histograms were cleared by the codebook step)
+    if (tid == 0) { ctrl->ticket = 0; ctrl->abort = 0; }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -606,40 +629,25 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
                            const Ws& w, uint64_t epoch, int pl, void* prof, hipStream_t s) {
     const bool f16 = g.dtype == DLC_F16;
     const FixedLayout F = fixed_layout(g);
-    // clear histograms, ticket and abort flag
-    {
-        const size_t n16 = (size_t)(w.zero_end - w.zero_begin) / 16;
-        if (prof_on(pl, P_ZERO)) prof_begin(prof, P_ZERO, s);
-        hipLaunchKernelGGL(k_zero, dim3((unsigned)std::min<size_t>((n16 + 255) / 256, 1024)), dim3(256), 0, s,
-                           reinterpret_cast<uint4*>(w.zero_begin), n16);
-        if (prof_on(pl, P_ZERO)) prof_end(prof, P_ZERO, s);
-    }
-    // histogram: up to 8 copies of each bin, 32 KiB of LDS at most
-#ifndef DLC_EXP_HIST_CLOG2
-#define DLC_EXP_HIST_CLOG2 3
-#endif
-    uint32_t clog2 = DLC_EXP_HIST_CLOG2;
-    while (clog2 > 0 && ((size_t)g.K << clog2) * 4 > 32768) --clog2;
+    // histogram
     uint32_t bpt_h = (g.G + 3) / 4;
     {
         // cap the grid at a few work-groups per CU; a work-group then loops over groups of its table
-#ifndef DLC_EXP_HIST_BLOCKS
-#define DLC_EXP_HIST_BLOCKS (256 * 8)
-#endif
-        const uint32_t max_blocks = DLC_EXP_HIST_BLOCKS;
+        const uint32_t max_blocks = 256 * 8;
         const uint32_t cap = std::max<uint32_t>(1, max_blocks / g.T);
         bpt_h = std::min(bpt_h, cap);
-        size_t sm = ((size_t)g.K << clog2) * 4 + kW * 4;  // + one scratch bin per lane
+        const size_t sm = hist_lds_bytes(g.K);
         dim3 grid(g.T * bpt_h), block(256);
         if (prof_on(pl, P_HIST)) prof_begin(prof, P_HIST, s);
-#define DLC_HIST(FF, V) hipLaunchKernelGGL((k_hist<FF, V>), grid, block, sm, s, payload, g, w.qp, w.hist, bpt_h, clog2)
+#define DLC_HIST(FF, V) hipLaunchKernelGGL((k_hist<FF, V>), grid, block, sm, s, payload, g, w.qp, w.hist, bpt_h)
         if (f16) { if (g.vec) DLC_HIST(true, true); else DLC_HIST(true, false); }
         else { if (g.vec) DLC_HIST(false, true); else DLC_HIST(false, false); }
 #undef DLC_HIST
         if (prof_on(pl, P_HIST)) prof_end(prof, P_HIST, s);
     }
     if (prof_on(pl, P_CODEBOOK)) prof_begin(prof, P_CODEBOOK, s);
-    hipLaunchKernelGGL(k_codebook, dim3(g.T), dim3(256), codebook_smem(g.K), s, g, w.hist, w.enc, w.lens, w.tmeta);
+    hipLaunchKernelGGL(k_codebook, dim3(g.T), dim3(256), codebook_smem(g.K), s, g, w.hist, w.hist_view, w.enc, w.lens,
+                       w.tmeta);
     if (prof_on(pl, P_CODEBOOK)) prof_end(prof, P_CODEBOOK, s);
     {
         const uint32_t bpt = (g.G + 3) / 4;

@@ -189,11 +189,9 @@ struct Ws {
     size_t bytes = 0;
     // compress
     QParam* qp = nullptr;          // [T]
-    uint8_t* zero_begin = nullptr; // region cleared at the start of every compress call
-    uint32_t* hist = nullptr;      // [T][K]
-    Ctrl* ctrl_call = nullptr;     // ticket, abort (inside the cleared region)
-    uint8_t* zero_end = nullptr;
-    Ctrl* ctrl = nullptr;          // same block as ctrl_call (status/collide are not cleared by the kernels)
+    uint32_t* hist = nullptr;      // [T][K] zero between calls
+    uint32_t* hist_view = nullptr; // [T][K] copy of the last call's histogram (inspection)
+    Ctrl* ctrl = nullptr;          // ticket and abort are zero between calls
     TMeta* tmeta = nullptr;        // [T]
     uint16_t* enc = nullptr;       // [T][K]  len << 12 | codeword
     uint8_t* lens = nullptr;       // [T][K]
@@ -218,7 +216,7 @@ struct Ws {
 // profiling hooks used by the launchers (implemented in dlc_api.hip)
 void prof_begin(void* prof, int slot, hipStream_t s);
 void prof_end(void* prof, int slot, hipStream_t s);
-enum ProfSlot { P_ZERO = 0, P_HIST, P_CODEBOOK, P_ENCODE, P_FINALIZE, P_DEC_PREPARE, P_DECODE, P_FUSED, P_NSLOTS };
+enum ProfSlot { P_HIST = 0, P_CODEBOOK, P_ENCODE, P_FINALIZE, P_DEC_PREPARE, P_DECODE, P_FUSED, P_NSLOTS };
 inline bool prof_on(int level, int slot) {
     return level >= 2 || (level == 1 && (slot == P_ENCODE || slot == P_DECODE || slot == P_HIST || slot == P_FUSED));
 }
