@@ -56,8 +56,12 @@ typedef struct {
     int32_t radius;        /* R: power of two in [8, 2048]; alphabet 2R, symbol 0 = verbatim escape */
     int32_t chunk_symbols; /* S: symbols per chunk, one of 64, 128, 256 */
     int32_t max_code_len;  /* LMAX <= 12, 2^LMAX >= 2R */
-    int32_t reserved;      /* 0 */
+    int32_t flags;         /* 0, or DLC_FLAG_* */
 } dlc_config;
+
+/* dlc_config.flags: compress with separate histogram, codebook and encode kernels (the payload is read twice)
+ * instead of the fused kernel that reads it once.  Both produce the same bytes. */
+enum { DLC_FLAG_TWO_PASS = 1 };
 
 /* Per-table statistics of a sampled batch: what Eq. 1 needs, plus the value range. */
 typedef struct {

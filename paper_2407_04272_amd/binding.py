@@ -22,7 +22,7 @@ DECAY_NONE, DECAY_STEPWISE, DECAY_DROP = 0, 1, 2
 class Config(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("num_tables", C.c_int32), ("batch", C.c_int64), ("dim", C.c_int64),
                 ("radius", C.c_int32), ("chunk_symbols", C.c_int32), ("max_code_len", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("flags", C.c_int32)]
 
 
 class TableStats(C.Structure):
@@ -92,8 +92,11 @@ def _check(status, where):
         raise DlcError(status, where)
 
 
-def make_config(dtype, T, B, D, radius=512, chunk_symbols=256, max_code_len=12) -> Config:
-    return Config(dtype, T, B, D, radius, chunk_symbols, max_code_len, 0)
+FLAG_TWO_PASS = 1
+
+
+def make_config(dtype, T, B, D, radius=512, chunk_symbols=256, max_code_len=12, flags=0) -> Config:
+    return Config(dtype, T, B, D, radius, chunk_symbols, max_code_len, flags)
 
 
 def dlc_compress_bound(cfg: Config) -> int:

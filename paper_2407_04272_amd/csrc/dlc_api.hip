@@ -79,7 +79,7 @@ static bool make_geom(const dlc_config* c, Geom* g) {
     if (L < 1 || L > kLmaxLimit || (1 << L) < 2 * R) return false;
     const int S = c->chunk_symbols;
     if (S != 64 && S != 128 && S != 256) return false;
-    if (c->reserved != 0) return false;
+    if (c->flags & ~(int32_t)DLC_FLAG_TWO_PASS) return false;
     const uint64_t GS = (uint64_t)kW * S;
     const uint64_t G = (n + GS - 1) / GS;
     const uint64_t NG = G * (uint64_t)c->num_tables;
@@ -122,6 +122,8 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
     uint8_t* state = take(8 * (size_t)g.NG);
     uint8_t* ws0 = take(4 * (size_t)g.T);
     uint8_t* ws1 = take(4 * (size_t)g.T);
+    uint8_t* arrive = take(4 * (size_t)g.T);
+    uint8_t* ready = take(8 * (size_t)g.T);
     uint8_t* lut = take(((size_t)g.T << g.LMAX) * 2);
     uint8_t* dlay = take(sizeof(DecLayout));
     uint8_t* dtab = take(sizeof(DecTable) * g.T);
@@ -132,6 +134,7 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
         w->tmeta = (TMeta*)tmeta;
         w->enc = (uint16_t*)enc; w->lens = lens; w->state = (uint64_t*)state;
         w->word_start = (uint32_t*)ws0; w->word_end = (uint32_t*)ws1; w->lut = (uint16_t*)lut;
+        w->arrive = (uint32_t*)arrive; w->ready = (uint64_t*)ready;
         w->dlay = (DecLayout*)dlay; w->dtab = (DecTable*)dtab;
     }
     return off;
@@ -158,7 +161,9 @@ extern "C" int dlc_create(dlc_ctx** out, const dlc_config* cfg) {
     if (hipMalloc((void**)&base, bytes) != hipSuccess) { (void)hipGetLastError(); delete c; return DLC_ENOMEM; }
     if (hipMemset(base, 0, bytes) != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }
     carve(g, base, &c->ws);
-    if (compress_set_attributes() != hipSuccess || decompress_set_attributes() != hipSuccess) {
+    if (compress_set_attributes() != hipSuccess || decompress_set_attributes() != hipSuccess ||
+        (!(cfg->flags & DLC_FLAG_TWO_PASS) && fused_plan(g, &c->ws.fused_grid) != hipSuccess)) {
+        (void)hipGetLastError();
         (void)hipFree(base);
         delete c;
         return DLC_EHIP;

@@ -1,0 +1,470 @@
+// Device-side building blocks shared by the compression kernels of libdlc (gfx950 only): the LDS histogram
+// layout, the Huffman codebook builder, the look-back scan over groups and the bit-stream writer.
+#pragma once
+#include "dlc_internal.h"
+
+// phase time stamps for kernel micro-benchmarks; expands to nothing in the library
+#ifndef DLC_STAMP
+#define DLC_STAMP(i)
+#endif
+
+namespace dlc {
+
+// ------------------------------------------------------------------------------------------------
+// LDS-privatised histogram of one work-group.
+//   LDS atomics with 64 scattered addresses cost one pass per lane that shares a bank, and that -- not
+//   HBM, not the ALU -- bounds the counting.  So the bins around the centre of the alphabet (where a
+//   bell-shaped distribution puts almost everything) get 32 copies each, copy = lane & 31: the bank of
+//   an update is then the lane's own, whatever its symbol, and a wavefront's 64 updates take the minimum
+//   of two passes.  Symbols outside that window go to a single-copy array (rare), positions past the end
+//   of the table to a scratch word per lane.
+//   layout in words: window [kHistWin][32] | overflow [K] | scratch [64]
+// ------------------------------------------------------------------------------------------------
+constexpr uint32_t kHistBlk = 4;    // turns whose loads are issued back to back (S/4 is a multiple)
+constexpr uint32_t kHistWin = 256;  // bins with private copies (all of them when K <= 256)
+constexpr uint32_t kHistCopies = 32;
+
+struct HistLds {
+    uint32_t win_bins, win_lo;   // window = symbols [win_lo, win_lo + win_bins)
+    uint32_t ovf_byte, trash_byte;  // byte offsets of the overflow array and of this lane's scratch word
+};
+
+// FULL: every position of the group is inside the table (no masking at all)
+template <bool F16, bool VEC, bool FULL>
+__device__ __forceinline__ void hist_group(const uint8_t* gbase, uint32_t rem, uint32_t turns, uint32_t lane,
+                                           const QParam& q, float Rf, int R, uint32_t* lh, const HistLds& H) {
+    const uint32_t copy4 = (lane & (kHistCopies - 1u)) * 4u;
+    for (uint32_t jb = 0; jb < turns; jb += kHistBlk) {
+        float x[kHistBlk][4];
+        uint32_t raw[kHistBlk][4];
+        uint32_t valid[kHistBlk];
+#pragma unroll
+        for (uint32_t u = 0; u < kHistBlk; ++u)
+            valid[u] = load4<F16, VEC>(gbase, lane * kV + (jb + u) * (kW * kV), FULL ? 0xFFFFFFFFu : rem, x[u], raw[u]);
+#pragma unroll
+        for (uint32_t u = 0; u < kHistBlk; ++u) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const uint32_t c = quant_symbol<F16>(x[u][v], q, Rf, R);
+                const uint32_t w = c - H.win_lo;  // wraps for symbols below the window
+                uint32_t byte = w < H.win_bins ? w * (kHistCopies * 4u) + copy4 : H.ovf_byte + c * 4u;
+                if constexpr (!FULL) byte = ((valid[u] >> v) & 1u) ? byte : H.trash_byte;
+                atomicAdd(reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(lh) + byte), 1u);
+            }
+        }
+    }
+}
+
+__host__ __device__ inline uint32_t hist_win_bins(uint32_t K) { return K < kHistWin ? K : kHistWin; }
+__host__ __device__ inline size_t hist_lds_bytes(uint32_t K) { return ((size_t)hist_win_bins(K) * kHistCopies + K + kW) * 4; }
+
+// ------------------------------------------------------------------------------------------------
+// Huffman codebook of one table, built by one work-group of 256 threads from the table's histogram.
+//   leaves ordered by (count, symbol); two queues (leaves, merged nodes in creation order); a tie
+//   between the queue heads takes the leaf; longest code above LMAX: lengths are cut to LMAX, the
+//   Kraft sum is repaired one unit at a time (a code of length LMAX pairs up with a code taken from
+//   the deepest shorter level) and the resulting lengths are handed out most frequent symbol first;
+//   canonical codewords in (length, symbol) order.  One used symbol: length 0.
+//   smem: codebook_smem(K) bytes, 16-byte aligned.  Ends with a barrier; results are in global memory.
+// ------------------------------------------------------------------------------------------------
+__host__ __device__ constexpr size_t codebook_smem(uint32_t K) { return (size_t)K * (8 + 4 + 4 + 2 + 2 + 2 + 2) + 64 * 4; }
+
+struct CodebookShared {
+    uint32_t lo, hi, maxlen, codes_done, cl[kLmaxLimit + 2], next[kLmaxLimit + 2];
+};
+
+__device__ __forceinline__ uint32_t lane_get(uint32_t v, uint32_t l) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)__builtin_amdgcn_readfirstlane((int)(l & 63u)));
+}
+__device__ __forceinline__ uint32_t lane_put(uint32_t vec, uint32_t l, uint32_t val, uint32_t lane) {
+    return lane == l ? val : vec;
+}
+
+// The whole tree of a table with at most 64 used symbols, built by one wavefront without touching memory:
+// lane i holds used symbol i (symbol order) on entry.  Leaves and merged nodes live one per lane; the merge
+// loop runs on wavefront-uniform values (lane reads and writes); depths come from pointer jumping.
+// Lengths above LM are limited as described above.  Returns the code length of the leaf at sorted position
+// `lane` (rising count, then symbol) and that leaf's symbol in *sorted_sym.  2 <= n <= 64.
+__device__ __forceinline__ uint32_t wave_huffman_lengths(uint32_t n, uint32_t LM, uint32_t sym, uint32_t cnt, uint32_t lane,
+                                                         uint32_t* sorted_sym) {
+    const uint32_t kInf = 0xFFFFFFFFu;
+    // position in (count, symbol) order
+    uint32_t rank = 0;
+    for (uint32_t j = 0; j < n; ++j) {
+        const uint32_t cj = lane_get(cnt, j);
+        rank += (cj < cnt || (cj == cnt && j < lane)) ? 1u : 0u;
+    }
+    if (lane >= n) rank = lane;  // idle lanes keep their place
+    // the sorted sequence: lane r takes the values of the lane whose rank is r (inverse permutation by search)
+    uint32_t src = lane;
+    for (uint32_t j = 0; j < n; ++j) {
+        const uint32_t rj = lane_get(rank, j);
+        src = (rj == lane) ? j : src;
+    }
+    const uint32_t s_sym = __shfl(sym, src, 64), s_cnt = lane < n ? __shfl(cnt, src, 64) : kInf;
+    // two-queue merge; a tie between the heads takes the leaf
+    uint32_t vw = s_cnt, vn = kInf, vpl = 0, vpn = 0;
+    uint32_t a = 0, bq = 0;
+    for (uint32_t k = 0; k + 1 < n; ++k) {
+        const uint32_t l0 = a < n ? lane_get(vw, a) : kInf, l1 = a + 1 < n ? lane_get(vw, a + 1) : kInf;
+        const uint32_t n0 = bq < k ? lane_get(vn, bq) : kInf, n1 = bq + 1 < k ? lane_get(vn, bq + 1) : kInf;
+        const bool f_leaf = l0 <= n0;
+        const uint32_t s1 = f_leaf ? l0 : n0;
+        const uint32_t c_l = f_leaf ? l1 : l0, c_n = f_leaf ? n0 : n1;
+        const bool s_leaf = c_l <= c_n;
+        const uint32_t s2 = s_leaf ? c_l : c_n;
+        if (f_leaf) { vpl = lane_put(vpl, a, k, lane); ++a; } else { vpn = lane_put(vpn, bq, k, lane); ++bq; }
+        if (s_leaf) { vpl = lane_put(vpl, a, k, lane); ++a; } else { vpn = lane_put(vpn, bq, k, lane); ++bq; }
+        vn = lane_put(vn, k, s1 + s2, lane);
+    }
+    // depth of every merged node (lane k = node k, the root is node n-2)
+    const uint32_t root = n - 2u;
+    uint32_t p = (lane < root) ? vpn : lane;
+    uint32_t d = (lane < root) ? 1u : 0u;
+#pragma unroll
+    for (int r = 0; r < 6; ++r) {
+        const uint32_t dd = __shfl(d, p, 64), pp = __shfl(p, p, 64);
+        d += dd;
+        p = pp;
+    }
+    uint32_t len = lane < n ? __shfl(d, vpl, 64) + 1u : 0u;
+    uint32_t m = len;
+    for (int o = 32; o > 0; o >>= 1) m = max(m, (uint32_t)__shfl_xor(m, o, 64));
+    if (m > LM) {
+        // cut to LM, then repair the Kraft sum: a code of length LM pairs up with a code taken from the deepest
+        // shorter level, one unit at a time.  Lane L of clv holds the number of codes of length L.
+        const uint32_t lc = min(len, LM);
+        uint32_t clv = 0;
+        uint64_t kraft = 0;  // in units of 2^-LM
+        for (uint32_t L = 1; L <= LM; ++L) {
+            const uint32_t c = (uint32_t)__popcll(__ballot(lane < n && lc == L));
+            clv = lane_put(clv, L, c, lane);
+            kraft += (uint64_t)c << (LM - L);
+        }
+        while (kraft > (1ull << LM) && lane_get(clv, LM) > 0u) {
+            const uint64_t shorter = __ballot(clv > 0u && lane >= 1u && lane < LM);
+            clv = lane_put(clv, LM, lane_get(clv, LM) - 1u, lane);
+            if (shorter) {
+                const uint32_t Ld = 63u - (uint32_t)__builtin_clzll(shorter);
+                clv = lane_put(clv, Ld, lane_get(clv, Ld) - 1u, lane);
+                clv = lane_put(clv, Ld + 1u, lane_get(clv, Ld + 1u) + 2u, lane);
+            }
+            kraft -= 1;
+        }
+        // lengths are handed out most frequent leaf first (the leaves are sorted by rising count)
+        const uint32_t rank = n - 1u - lane;
+        uint32_t acc = 0, nl = 1;
+        for (uint32_t L = 1; L < LM; ++L) {
+            acc += lane_get(clv, L);  // leaves with a length of at most L
+            nl += (rank >= acc) ? 1u : 0u;
+        }
+        len = lane < n ? nl : 0u;
+    }
+    *sorted_sym = s_sym;
+    return len;  // of the leaf at sorted position `lane`
+}
+
+// hist_t is read, copied to hist_view_t (inspection) and cleared, so that the next call starts from zero counts.
+// enc_t is written with device-scope stores: other work-groups of a running kernel may read it once they have
+// seen the caller's completion flag.
+__device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, uint32_t* hist_view_t, uint16_t* enc_t,
+                                               uint8_t* lens_t, TMeta* tmeta_t, unsigned char* smem, CodebookShared& sh,
+                                               uint32_t tid) {
+    const uint32_t K = g.K;
+    uint64_t* key = reinterpret_cast<uint64_t*>(smem);        // [K] sort keys: count << 16 | symbol
+    uint32_t* cnt = reinterpret_cast<uint32_t*>(key + K);      // [K] counts
+    uint32_t* nodew = cnt + K;                                 // [K] merged-node weights, later codewords
+    uint16_t* parent_leaf = reinterpret_cast<uint16_t*>(nodew + K);  // [K] parent of a leaf, later its length
+    uint16_t* parent_node = parent_leaf + K;                   // [K]
+    uint16_t* depth_node = parent_node + K;                    // [K]
+    uint16_t* len_s = depth_node + K;                          // [K] code length per symbol
+    uint32_t* scratch = reinterpret_cast<uint32_t*>(len_s + K);  // [64]
+    const uint32_t lane = tid & 63u, wave = tid >> 6;
+
+    DLC_STAMP(0);
+    // each thread owns `per` consecutive symbols
+    const uint32_t per = (K + 255) / 256;
+    const uint32_t k0 = tid * per, k1 = min(K, k0 + per);
+    uint32_t mine = 0;
+    for (uint32_t k = k0; k < k1; ++k) {
+        // the counts were added by device-scope atomics of other work-groups, possibly on other dies
+        const uint32_t h = __hip_atomic_load(&hist_t[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        cnt[k] = h;
+        hist_view_t[k] = h;
+        __hip_atomic_store(&hist_t[k], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        len_s[k] = 0;
+        mine += h != 0;
+    }
+    if (tid == 0) { sh.maxlen = 0; sh.codes_done = 0; }
+    if (tid < kLmaxLimit + 2) sh.cl[tid] = 0;
+    // compaction offsets of the used symbols (symbol order); the barriers inside also publish cnt[]
+    uint32_t n_used;
+    const uint32_t my_off = block_excl_scan<4>(mine, scratch, tid, &n_used);
+    {
+        uint32_t o = my_off;
+        for (uint32_t k = k0; k < k1; ++k)
+            if (cnt[k]) key[o++] = ((uint64_t)cnt[k] << 16) | k;
+    }
+    __syncthreads();
+    // first and last used symbol: the ends of the compacted list
+    const uint32_t sym_lo = n_used ? (uint32_t)(key[0] & 0xFFFFu) : 0u;
+    const uint32_t sym_hi = n_used ? (uint32_t)(key[n_used - 1] & 0xFFFFu) : 0u;
+
+    DLC_STAMP(1);
+    if (n_used >= 2 && n_used <= 64) {
+        if (wave == 0) {
+            const uint64_t kv = lane < n_used ? key[lane] : ~0ull;
+            uint32_t s_sym;
+            const uint32_t len = wave_huffman_lengths(n_used, g.LMAX, (uint32_t)(kv & 0xFFFFu), (uint32_t)(kv >> 16), lane,
+                                                      &s_sym);
+            // canonical codewords: first code of each length, then the rank among the symbols of that length
+            uint32_t code = 0, first = 0;
+            for (uint32_t L = 1; L <= g.LMAX; ++L) {
+                code <<= 1;
+                first = (len == L) ? code : first;
+                code += (uint32_t)__popcll(__ballot(len == L));
+            }
+            uint32_t r = 0;
+            for (uint32_t j = 0; j < n_used; ++j) {
+                const uint32_t lj = lane_get(len, j), sj = lane_get(s_sym, j);
+                r += (lj == len && sj < s_sym) ? 1u : 0u;
+            }
+            if (lane < n_used) { len_s[s_sym] = (uint16_t)len; nodew[s_sym] = first + r; }
+            if (lane == 0) sh.codes_done = 1;
+        }
+        __syncthreads();
+    } else if (n_used > 64) {
+        uint32_t P = 2;
+        while (P < n_used) P <<= 1;
+        for (uint32_t i = n_used + tid; i < P; i += 256) key[i] = ~0ull;  // pad to a power of two
+        __syncthreads();
+        DLC_STAMP(2);
+        // bitonic sort, ascending
+        for (uint32_t size = 2; size <= P; size <<= 1) {
+            for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+                for (uint32_t i = tid; i < (P >> 1); i += 256) {
+                    uint32_t lo = 2 * i - (i & (stride - 1));
+                    uint32_t hi = lo + stride;
+                    bool up = (lo & size) == 0;
+                    uint64_t a = key[lo], bb = key[hi];
+                    if ((a > bb) == up) { key[lo] = bb; key[hi] = a; }
+                }
+                __syncthreads();
+            }
+        }
+        DLC_STAMP(3);
+        if (tid == 0) {
+            const uint32_t n = n_used;
+            uint32_t a = 0, bq = 0;  // heads of the leaf queue and of the merged-node queue
+            for (uint32_t k = 0; k + 1 < n; ++k) {
+                uint32_t sum = 0;
+                for (int pick = 0; pick < 2; ++pick) {
+                    bool take_leaf;
+                    if (a >= n) take_leaf = false;
+                    else if (bq >= k) take_leaf = true;
+                    else take_leaf = (uint32_t)(key[a] >> 16) <= nodew[bq];
+                    if (take_leaf) { sum += (uint32_t)(key[a] >> 16); parent_leaf[a] = (uint16_t)k; ++a; }
+                    else { sum += nodew[bq]; parent_node[bq] = (uint16_t)k; ++bq; }
+                }
+                nodew[k] = sum;
+            }
+            depth_node[n - 2] = 0;
+            for (int k = (int)n - 3; k >= 0; --k) depth_node[k] = depth_node[parent_node[k]] + 1;
+        }
+        __syncthreads();
+        DLC_STAMP(4);
+        // leaf depths; parent_leaf[] is reused to hold the depth of leaf i (sorted order)
+        uint32_t local_max = 0;
+        for (uint32_t i = tid; i < n_used; i += 256) {
+            const uint32_t d = depth_node[parent_leaf[i]] + 1u;
+            parent_leaf[i] = (uint16_t)d;
+            local_max = max(local_max, d);
+        }
+        if (local_max) atomicMax(&sh.maxlen, local_max);
+        __syncthreads();
+    }
+    if (n_used >= 2) {
+        if (sh.maxlen > g.LMAX) {
+            for (uint32_t i = tid; i < n_used; i += 256) atomicAdd(&sh.cl[min((uint32_t)parent_leaf[i], g.LMAX)], 1u);
+            __syncthreads();
+            if (tid == 0) {
+                const uint32_t LM = g.LMAX;
+                uint64_t kraft = 0;
+                for (uint32_t L = 1; L <= LM; ++L) kraft += (uint64_t)sh.cl[L] << (LM - L);
+                while (kraft > (1ull << LM) && sh.cl[LM] > 0) {
+                    sh.cl[LM] -= 1;
+                    for (uint32_t L = LM - 1; L >= 1; --L)
+                        if (sh.cl[L]) { sh.cl[L] -= 1; sh.cl[L + 1] += 2; break; }
+                    kraft -= 1;
+                }
+                // next[L] = number of leaves (counted from the most frequent) with length < L
+                uint32_t acc = 0;
+                for (uint32_t L = 1; L <= LM; ++L) { sh.next[L] = acc; acc += sh.cl[L]; }
+                sh.next[LM + 1] = acc;
+            }
+            __syncthreads();
+            for (uint32_t i = tid; i < n_used; i += 256) {
+                const uint32_t rank = n_used - 1u - i;  // 0 = most frequent (leaves are sorted by rising count)
+                uint32_t L = 1;
+                while (L < g.LMAX && rank >= sh.next[L + 1]) ++L;
+                parent_leaf[i] = (uint16_t)L;
+            }
+            __syncthreads();
+            if (tid < kLmaxLimit + 2) sh.cl[tid] = 0;
+            __syncthreads();
+        }
+        if (!sh.codes_done) {  // uniform
+            for (uint32_t i = tid; i < n_used; i += 256) len_s[(uint32_t)(key[i] & 0xFFFFu)] = parent_leaf[i];
+            __syncthreads();
+            // codewords
+            DLC_STAMP(5);
+            for (uint32_t k = k0; k < k1; ++k)
+                if (len_s[k]) atomicAdd(&sh.cl[len_s[k]], 1u);
+            __syncthreads();
+            if (tid == 0) {
+                uint32_t code = 0;
+                for (uint32_t L = 1; L <= g.LMAX; ++L) {
+                    code <<= 1;
+                    sh.next[L] = code;
+                    code += sh.cl[L];
+                }
+                for (uint32_t k = sym_lo; k <= sym_hi; ++k) {
+                    uint32_t L = len_s[k];
+                    if (L) nodew[k] = sh.next[L]++;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    DLC_STAMP(6);
+    for (uint32_t k = k0; k < k1; ++k) {
+        uint32_t L = len_s[k];
+        __hip_atomic_store(&enc_t[k], (uint16_t)(L ? ((L << 12) | nodew[k]) : 0u), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+        lens_t[k] = (uint8_t)L;
+    }
+    if (tid == 0) {
+        TMeta m;
+        // an empty histogram cannot come out of the histogram step (every table has an element); should it
+        // happen anyway, the symbol range is still a valid one for the kernels that size things from it
+        m.n_used = n_used; m.sym_lo = sym_lo; m.sym_hi = sym_hi; m.n_outliers = cnt[0];  // symbol 0 = escape
+        m.cb_off = 0; m.outl_off = 0;
+        *tmeta_t = m;
+    }
+    __syncthreads();
+    DLC_STAMP(7);
+}
+
+// LDS of the fused kernel: the histogram, later the codebook builder's scratch, share the front; the table's
+// packed (length, codeword) entries plus one empty entry sit behind.
+__host__ __device__ inline size_t fused_region0(uint32_t K) {
+    const size_t a = hist_lds_bytes(K), b = codebook_smem(K);
+    return ((a > b ? a : b) + 15) & ~size_t(15);
+}
+__host__ __device__ inline size_t fused_lds_bytes(uint32_t K) { return fused_region0(K) + (((size_t)K + 1) * 2 + 15 & ~size_t(15)); }
+
+// ------------------------------------------------------------------------------------------------
+// offsets of the groups' words: single-pass look-back over per-group records
+// ------------------------------------------------------------------------------------------------
+constexpr uint32_t kFlagAgg = 1, kFlagPrefix = 2;
+constexpr uint32_t kSpinLimit = 1u << 22;
+
+// exclusive prefix of `total` over all groups before gid; publishes this group's records.  All lanes call.
+__device__ __forceinline__ uint32_t group_scan(uint64_t* state, uint64_t epoch, uint32_t gid, uint32_t total,
+                                               uint32_t lane, Ctrl* ctrl, bool* dead) {
+    const uint64_t tag = epoch << 34;
+    if (lane == 0)
+        __hip_atomic_store(&state[gid], tag | ((uint64_t)(gid == 0 ? kFlagPrefix : kFlagAgg) << 32) | total,
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t excl = 0;
+    if (gid > 0) {
+        int64_t pos = (int64_t)gid - 1;
+        uint32_t spins = 0;
+        for (;;) {
+            const int64_t my = pos - (int64_t)lane;
+            uint64_t sv;
+            uint32_t flag;
+            for (;;) {
+                sv = my >= 0 ? __hip_atomic_load(&state[my], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                             : (tag | ((uint64_t)kFlagPrefix << 32));
+                flag = (sv >> 34) == epoch ? (uint32_t)(sv >> 32) & 3u : 0u;
+                if (__ballot(flag == 0u) == 0ull) break;
+                if (++spins > kSpinLimit) break;  // never expected; the bound only guarantees termination
+                __builtin_amdgcn_s_sleep(2);
+            }
+            if (spins > kSpinLimit) {
+                if (lane == 0) { set_status(ctrl, DLC_ESTATE); ctrl->abort = 1; }
+                *dead = true;
+                break;
+            }
+            const uint64_t pm = __ballot(flag == kFlagPrefix);
+            if (pm) {
+                const uint32_t first = (uint32_t)__ffsll((unsigned long long)pm) - 1u;
+                excl += wave_sum(lane <= first ? (uint32_t)sv : 0u);
+                break;
+            }
+            excl += wave_sum((uint32_t)sv);
+            pos -= 64;
+        }
+        if (lane == 0)
+            __hip_atomic_store(&state[gid], tag | ((uint64_t)kFlagPrefix << 32) | (uint32_t)(excl + total),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    return excl;
+}
+
+// walk 2 and everything after the group's offset is known.  pk[] holds S/2 words of two (len<<12|code) each.
+template <int S, bool F16, bool VEC>
+__device__ __forceinline__ void emit_group(const uint32_t (&pk)[S / 2], uint32_t nw, uint32_t lane_off, uint32_t excl,
+                                           uint32_t chunk_total, uint32_t n_esc, uint32_t gid, uint32_t lane,
+                                           const uint8_t* gbase, uint32_t gstart, uint32_t rem, const QParam& q, float Rf,
+                                           int R, const FixedLayout& F, uint8_t* out) {
+    out[F.off_chunk + (uint64_t)gid * kW + lane] = (uint8_t)nw;
+    if (lane == 0) reinterpret_cast<uint32_t*>(out + F.off_group)[gid] = excl;
+    uint32_t* gw = reinterpret_cast<uint32_t*>(out + F.off_payload) + excl;
+    uint32_t* p = gw + lane_off;
+    uint64_t acc = 0;
+    uint32_t nb = 0;
+#pragma clang loop unroll(full)
+    for (int i = 0; i < S / 2; ++i) {
+        const uint32_t w = pk[i];
+        const uint32_t l0 = (w >> 12) & 0xFu, l1 = w >> 28;
+        acc = (acc << l0) | (w & 0xFFFu);
+        acc = (acc << l1) | ((w >> 16) & 0xFFFu);
+        nb += l0 + l1;
+        if (nb >= 32u) {
+            nb -= 32u;
+            *p++ = (uint32_t)(acc >> nb);
+        }
+        if ((i & 3) == 3) __builtin_amdgcn_sched_barrier(0);  // do not unpack far ahead of the serial chain
+    }
+    if (nb) *p = (uint32_t)(acc << (32u - nb));
+    if (n_esc != 0u) {  // uniform over the wavefront
+        uint32_t* rec = gw + chunk_total;
+        uint32_t opos = 0;
+        for (uint32_t j = 0; j < (uint32_t)S / kV; ++j) {
+            const uint32_t off = lane * kV + j * (kW * kV);
+            float x[4];
+            uint32_t raw[4];
+            const uint32_t valid = load4<F16, VEC>(gbase, off, rem, x, raw);
+            uint32_t esc = 0;
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                esc |= (((valid >> v) & 1u) && quant_symbol<F16>(x[v], q, Rf, R) == 0u) ? (1u << v) : 0u;
+            if (__ballot(esc != 0u) == 0ull) continue;
+            const uint32_t cnt = __popc(esc);
+            const uint32_t incl = wave_incl_scan(cnt, lane);
+            uint32_t r = opos + incl - cnt;
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if ((esc >> v) & 1u) {
+                    rec[2u * r] = gstart + off + v;
+                    rec[2u * r + 1] = raw[v];
+                    ++r;
+                }
+            opos += __shfl(incl, 63, 64);
+        }
+    }
+}
+
+}  // namespace dlc

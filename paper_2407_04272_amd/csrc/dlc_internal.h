@@ -178,6 +178,7 @@ struct Ws;  // workspace, see dlc_api.hip
 hipError_t launch_quantize(const Geom& g, const void* payload, const QParam* qp, uint16_t* sym, hipStream_t s);
 hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uint64_t capacity, uint64_t* out_bytes,
                            const Ws& w, uint64_t epoch, int prof_level, void* prof, hipStream_t s);
+hipError_t fused_plan(const Geom& g, uint32_t* grid_out);
 hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_bytes, void* out, const Ws& w,
                              int prof_level, void* prof, hipStream_t s);
 hipError_t launch_stats(const Geom& g, const void* payload, const QParam* probe, const Ws& w, uint32_t M, uint32_t salt,
@@ -198,6 +199,9 @@ struct Ws {
     uint64_t* state = nullptr;     // [NG] look-back records
     uint32_t* word_start = nullptr;  // [T]
     uint32_t* word_end = nullptr;    // [T]
+    uint32_t* arrive = nullptr;    // [T] items of a table that have added their counts (fused kernel); zero between calls
+    uint64_t* ready = nullptr;     // [T] call counter of the call whose codebook of the table is complete
+    uint32_t fused_grid = 0;       // work-groups of the fused kernel; 0 = separate histogram / codebook / encode kernels
     // decompress
     uint16_t* lut = nullptr;       // [T][1 << LMAX]  len << 12 | symbol
     DecLayout* dlay = nullptr;
