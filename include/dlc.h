@@ -59,9 +59,10 @@ typedef struct {
     int32_t flags;         /* 0, or DLC_FLAG_* */
 } dlc_config;
 
-/* dlc_config.flags: compress with separate histogram, codebook and encode kernels (the payload is read twice)
- * instead of the fused kernel that reads it once.  Both produce the same bytes. */
-enum { DLC_FLAG_TWO_PASS = 1 };
+/* dlc_config.flags: compress with the fused persistent kernel, which reads the payload once and builds each
+ * table's codebook inside the kernel, instead of the separate histogram, codebook and encode kernels.  Both
+ * produce the same bytes; on MI355X the separate kernels are the faster choice (the default). */
+enum { DLC_FLAG_FUSED = 1 };
 
 /* Per-table statistics of a sampled batch: what Eq. 1 needs, plus the value range. */
 typedef struct {

@@ -92,7 +92,7 @@ def _check(status, where):
         raise DlcError(status, where)
 
 
-FLAG_TWO_PASS = 1
+FLAG_FUSED = 1
 
 
 def make_config(dtype, T, B, D, radius=512, chunk_symbols=256, max_code_len=12, flags=0) -> Config:

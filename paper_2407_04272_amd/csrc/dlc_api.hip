@@ -79,7 +79,7 @@ static bool make_geom(const dlc_config* c, Geom* g) {
     if (L < 1 || L > kLmaxLimit || (1 << L) < 2 * R) return false;
     const int S = c->chunk_symbols;
     if (S != 64 && S != 128 && S != 256) return false;
-    if (c->flags & ~(int32_t)DLC_FLAG_TWO_PASS) return false;
+    if (c->flags & ~(int32_t)DLC_FLAG_FUSED) return false;
     const uint64_t GS = (uint64_t)kW * S;
     const uint64_t G = (n + GS - 1) / GS;
     const uint64_t NG = G * (uint64_t)c->num_tables;
@@ -162,7 +162,7 @@ extern "C" int dlc_create(dlc_ctx** out, const dlc_config* cfg) {
     if (hipMemset(base, 0, bytes) != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }
     carve(g, base, &c->ws);
     if (compress_set_attributes() != hipSuccess || decompress_set_attributes() != hipSuccess ||
-        (!(cfg->flags & DLC_FLAG_TWO_PASS) && fused_plan(g, &c->ws.fused_grid) != hipSuccess)) {
+        ((cfg->flags & DLC_FLAG_FUSED) && fused_plan(g, &c->ws.fused_grid) != hipSuccess)) {
         (void)hipGetLastError();
         (void)hipFree(base);
         delete c;

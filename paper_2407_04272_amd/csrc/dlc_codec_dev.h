@@ -11,52 +11,21 @@
 namespace dlc {
 
 // ------------------------------------------------------------------------------------------------
-// LDS-privatised histogram of one work-group.
-//   LDS atomics with 64 scattered addresses cost one pass per lane that shares a bank, and that -- not
-//   HBM, not the ALU -- bounds the counting.  So the bins around the centre of the alphabet (where a
-//   bell-shaped distribution puts almost everything) get 32 copies each, copy = lane & 31: the bank of
-//   an update is then the lane's own, whatever its symbol, and a wavefront's 64 updates take the minimum
-//   of two passes.  Symbols outside that window go to a single-copy array (rare), positions past the end
-//   of the table to a scratch word per lane.
-//   layout in words: window [kHistWin][32] | overflow [K] | scratch [64]
+// The symbol window of the histogram kernel.  Almost every element of a bell-shaped table falls into a few bins
+// around zero, so the kernel counts window indices: index v in [0, 255) stands for symbol win_lo + v, index 255
+// for everything else (an escape, a symbol outside the window).  Window rows have kWinCopies copies each
+// (copy = lane mod kWinCopies), so a wavefront's 64 updates spread over the LDS banks whatever the symbols are;
+// the rare index 255 is counted exactly, by symbol, in a single-copy array.
 // ------------------------------------------------------------------------------------------------
-constexpr uint32_t kHistBlk = 4;    // turns whose loads are issued back to back (S/4 is a multiple)
-constexpr uint32_t kHistWin = 256;  // bins with private copies (all of them when K <= 256)
-constexpr uint32_t kHistCopies = 32;
+constexpr uint32_t kWinBins = 255;
+constexpr uint32_t kWinCopies = 16;
+__host__ __device__ inline uint32_t win_lo_of(uint32_t R) { return R > kWinBins / 2u ? R - kWinBins / 2u : 0u; }
+// LDS of the histogram kernel in words: window [kWinBins + 1][kWinCopies] | exact counts [K] | scratch [64]
+__host__ __device__ inline size_t hist_lds_bytes(uint32_t K) { return ((size_t)(kWinBins + 1) * kWinCopies + K + kW) * 4; }
 
-struct HistLds {
-    uint32_t win_bins, win_lo;   // window = symbols [win_lo, win_lo + win_bins)
-    uint32_t ovf_byte, trash_byte;  // byte offsets of the overflow array and of this lane's scratch word
-};
-
-// FULL: every position of the group is inside the table (no masking at all)
-template <bool F16, bool VEC, bool FULL>
-__device__ __forceinline__ void hist_group(const uint8_t* gbase, uint32_t rem, uint32_t turns, uint32_t lane,
-                                           const QParam& q, float Rf, int R, uint32_t* lh, const HistLds& H) {
-    const uint32_t copy4 = (lane & (kHistCopies - 1u)) * 4u;
-    for (uint32_t jb = 0; jb < turns; jb += kHistBlk) {
-        float x[kHistBlk][4];
-        uint32_t raw[kHistBlk][4];
-        uint32_t valid[kHistBlk];
-#pragma unroll
-        for (uint32_t u = 0; u < kHistBlk; ++u)
-            valid[u] = load4<F16, VEC>(gbase, lane * kV + (jb + u) * (kW * kV), FULL ? 0xFFFFFFFFu : rem, x[u], raw[u]);
-#pragma unroll
-        for (uint32_t u = 0; u < kHistBlk; ++u) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const uint32_t c = quant_symbol<F16>(x[u][v], q, Rf, R);
-                const uint32_t w = c - H.win_lo;  // wraps for symbols below the window
-                uint32_t byte = w < H.win_bins ? w * (kHistCopies * 4u) + copy4 : H.ovf_byte + c * 4u;
-                if constexpr (!FULL) byte = ((valid[u] >> v) & 1u) ? byte : H.trash_byte;
-                atomicAdd(reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(lh) + byte), 1u);
-            }
-        }
-    }
-}
-
+// legacy helpers of the fused kernel's own histogram layout
+constexpr uint32_t kHistWin = 256;
 __host__ __device__ inline uint32_t hist_win_bins(uint32_t K) { return K < kHistWin ? K : kHistWin; }
-__host__ __device__ inline size_t hist_lds_bytes(uint32_t K) { return ((size_t)hist_win_bins(K) * kHistCopies + K + kW) * 4; }
 
 // ------------------------------------------------------------------------------------------------
 // Huffman codebook of one table, built by one work-group of 256 threads from the table's histogram.
@@ -355,13 +324,23 @@ __device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, 
     DLC_STAMP(7);
 }
 
-// LDS of the fused kernel: the histogram, later the codebook builder's scratch, share the front; the table's
-// packed (length, codeword) entries plus one empty entry sit behind.
-__host__ __device__ inline size_t fused_region0(uint32_t K) {
-    const size_t a = hist_lds_bytes(K), b = codebook_smem(K);
-    return ((a > b ? a : b) + 15) & ~size_t(15);
+// LDS of the fused kernel, in bytes from the start of its dynamic LDS (alphabets of up to kFusedMaxK symbols):
+//   [0, kFusedTab)             code lengths of the table's symbols, u16[K+1]  (index = symbol; entry 0 is empty and
+//                              stands for a position past the end of the table, entry K is the escape)
+//   [kFusedTab, 2*kFusedTab)   codewords, same indexing
+//   [2*kFusedTab, ...)         the work-group's histogram, later the codebook builder's scratch
+//   histogram in words: window [win_bins + 1][kFusedCopies] (the last row counts everything outside the window)
+//                       | single-copy counts [K] | scratch [64]
+constexpr uint32_t kFusedMaxK = 1024;
+constexpr uint32_t kFusedTab = (kFusedMaxK + 1) * 2 + 14;  // 2064: a 16-byte multiple
+constexpr uint32_t kFusedCopies = 16;
+__host__ __device__ inline size_t fused_hist_bytes(uint32_t K) {
+    return ((size_t)(hist_win_bins(K) + 1) * kFusedCopies + K + kW) * 4;
 }
-__host__ __device__ inline size_t fused_lds_bytes(uint32_t K) { return fused_region0(K) + (((size_t)K + 1) * 2 + 15 & ~size_t(15)); }
+__host__ __device__ inline size_t fused_lds_bytes(uint32_t K) {
+    const size_t a = fused_hist_bytes(K), b = codebook_smem(K);
+    return 2 * (size_t)kFusedTab + (((a > b ? a : b) + 15) & ~size_t(15));
+}
 
 // ------------------------------------------------------------------------------------------------
 // offsets of the groups' words: single-pass look-back over per-group records
@@ -413,6 +392,89 @@ __device__ __forceinline__ uint32_t group_scan(uint64_t* state, uint64_t epoch, 
     return excl;
 }
 
+// The same scan with one record per work-group and 256 records per look-back step (four per lane): the chain
+// of "wait for a predecessor's prefix" steps across the work-groups that run at the same time is what bounds a
+// streaming kernel that places its output by this scan, so the records are few and the steps wide.
+// Called by one whole wavefront; returns the exclusive prefix of `total` over the work-groups before `wg`.
+__device__ __forceinline__ uint32_t wg_scan(uint64_t* state, uint64_t epoch, uint32_t wg, uint32_t total, uint32_t lane,
+                                            Ctrl* ctrl, bool* dead) {
+    const uint64_t tag = epoch << 34;
+    if (lane == 0)
+        __hip_atomic_store(&state[wg], tag | ((uint64_t)(wg == 0 ? kFlagPrefix : kFlagAgg) << 32) | total,
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t excl = 0;
+    if (wg > 0) {
+        int64_t pos = (int64_t)wg - 1;  // nearest record not yet added
+        uint32_t spins = 0;
+        for (;;) {
+            // this lane's four records, nearest first; before the first work-group: an empty prefix
+            uint32_t sum = 0;       // values up to and including the lane's first prefix record (or all four)
+            bool has_p = false;     // there is a prefix record among them
+            bool hole = false;      // an unpublished record comes before it
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int64_t my = pos - (int64_t)(lane * 4u + (uint32_t)k);
+                const uint64_t sv = my >= 0 ? __hip_atomic_load(&state[my], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                            : (tag | ((uint64_t)kFlagPrefix << 32));
+                const uint32_t flag = (sv >> 34) == epoch ? (uint32_t)(sv >> 32) & 3u : 0u;
+                if (!has_p) {
+                    hole = hole || flag == 0u;
+                    sum += flag != 0u ? (uint32_t)sv : 0u;
+                    has_p = flag == kFlagPrefix;
+                }
+            }
+            const uint64_t pm = __ballot(has_p);
+            const uint32_t first = pm ? (uint32_t)__ffsll((unsigned long long)pm) - 1u : 64u;  // lane of the nearest prefix
+            if (__ballot(hole && lane <= first) != 0ull) {  // something nearer than that prefix is not published yet
+                if (++spins > kSpinLimit) {  // never expected; the bound only guarantees termination
+                    if (lane == 0) { set_status(ctrl, DLC_ESTATE); ctrl->abort = 1; }
+                    *dead = true;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+                continue;
+            }
+            excl += wave_sum(lane <= first ? sum : 0u);
+            if (pm) break;
+            pos -= 256;
+        }
+        if (lane == 0)
+            __hip_atomic_store(&state[wg], tag | ((uint64_t)kFlagPrefix << 32) | (uint32_t)(excl + total),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    return excl;
+}
+
+// escape records of one group, in increasing element index, behind its chunk words: the group's elements are
+// read and quantised once more in a rolled loop (rare for fp32)
+template <int S, bool F16, bool VEC>
+__device__ __forceinline__ void emit_escapes(uint32_t* rec, uint32_t lane, const uint8_t* gbase, uint32_t gstart,
+                                             uint32_t rem, const QParam& q, float Rf, int R) {
+    uint32_t opos = 0;
+    for (uint32_t j = 0; j < (uint32_t)S / kV; ++j) {
+        const uint32_t off = lane * kV + j * (kW * kV);
+        float x[4];
+        uint32_t raw[4];
+        const uint32_t valid = load4<F16, VEC>(gbase, off, rem, x, raw);
+        uint32_t esc = 0;
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            esc |= (((valid >> v) & 1u) && quant_symbol<F16>(x[v], q, Rf, R) == 0u) ? (1u << v) : 0u;
+        if (__ballot(esc != 0u) == 0ull) continue;
+        const uint32_t cnt = __popc(esc);
+        const uint32_t incl = wave_incl_scan(cnt, lane);
+        uint32_t r = opos + incl - cnt;
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            if ((esc >> v) & 1u) {
+                rec[2u * r] = gstart + off + v;
+                rec[2u * r + 1] = raw[v];
+                ++r;
+            }
+        opos += __shfl(incl, 63, 64);
+    }
+}
+
 // walk 2 and everything after the group's offset is known.  pk[] holds S/2 words of two (len<<12|code) each.
 template <int S, bool F16, bool VEC>
 __device__ __forceinline__ void emit_group(const uint32_t (&pk)[S / 2], uint32_t nw, uint32_t lane_off, uint32_t excl,
@@ -439,32 +501,8 @@ __device__ __forceinline__ void emit_group(const uint32_t (&pk)[S / 2], uint32_t
         if ((i & 3) == 3) __builtin_amdgcn_sched_barrier(0);  // do not unpack far ahead of the serial chain
     }
     if (nb) *p = (uint32_t)(acc << (32u - nb));
-    if (n_esc != 0u) {  // uniform over the wavefront
-        uint32_t* rec = gw + chunk_total;
-        uint32_t opos = 0;
-        for (uint32_t j = 0; j < (uint32_t)S / kV; ++j) {
-            const uint32_t off = lane * kV + j * (kW * kV);
-            float x[4];
-            uint32_t raw[4];
-            const uint32_t valid = load4<F16, VEC>(gbase, off, rem, x, raw);
-            uint32_t esc = 0;
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-                esc |= (((valid >> v) & 1u) && quant_symbol<F16>(x[v], q, Rf, R) == 0u) ? (1u << v) : 0u;
-            if (__ballot(esc != 0u) == 0ull) continue;
-            const uint32_t cnt = __popc(esc);
-            const uint32_t incl = wave_incl_scan(cnt, lane);
-            uint32_t r = opos + incl - cnt;
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-                if ((esc >> v) & 1u) {
-                    rec[2u * r] = gstart + off + v;
-                    rec[2u * r + 1] = raw[v];
-                    ++r;
-                }
-            opos += __shfl(incl, 63, 64);
-        }
-    }
+    if (n_esc != 0u)  // uniform over the wavefront
+        emit_escapes<S, F16, VEC>(gw + chunk_total, lane, gbase, gstart, rem, q, Rf, R);
 }
 
 }  // namespace dlc

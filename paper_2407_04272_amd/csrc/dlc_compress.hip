@@ -53,23 +53,90 @@ hipError_t launch_quantize(const Geom& g, const void* payload, const QParam* qp,
 }
 
 // ------------------------------------------------------------------------------------------------
-// quantise + LDS-privatised histogram
-//   grid: T * bpt work-groups of 4 wavefronts; a work-group stays inside one table and merges its LDS
-//   histogram into the table's global one at the end
+// quantise + histogram
+//   grid: T * bpt work-groups of 4 wavefronts; a work-group stays inside one table, counts into its LDS
+//   histogram and merges that into the table's global one at the end.
 // ------------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
+__device__ __forceinline__ void lds_count(uint32_t addr) {
+    __hip_atomic_fetch_add(reinterpret_cast<lds_u32*>(addr), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+struct HistC {
+    int ubias;          // window index of bin 0
+    uint32_t win_lo;    // symbol of window index 0
+    uint32_t lanebase;  // LDS address of this lane's copy of window row 0
+    uint32_t exact;     // LDS address of the exact counts
+};
+
+constexpr uint32_t kEscW = 0x80000000u;  // no bin has this window index (bins below the window wrap to just under 2^32)
+constexpr uint32_t kHistBlk = 4;  // turns whose loads are issued back to back (S/4 is a multiple)
+
+// FULL: every position of the group is inside the table (no masking at all)
+template <bool F16, bool VEC, bool FULL>
+__device__ __forceinline__ void hist_group(const uint8_t* gbase, uint32_t rem, uint32_t turns, uint32_t lane,
+                                           const QParam& q, float Rf, const HistC& H) {
+    for (uint32_t jb = 0; jb < turns; jb += kHistBlk) {
+        float x[kHistBlk][4];
+        uint32_t raw[kHistBlk][4];
+        uint32_t valid[kHistBlk];
+#pragma unroll
+        for (uint32_t u = 0; u < kHistBlk; ++u)
+            valid[u] = load4<F16, VEC>(gbase, lane * kV + (jb + u) * (kW * kV), FULL ? 0xFFFFFFFFu : rem, x[u], raw[u]);
+#pragma unroll
+        for (uint32_t u = 0; u < kHistBlk; ++u) {
+            uint32_t w[4], sl[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                // the quantiser (same arithmetic as quant_symbol), result as a window index; kEscW for an escape
+                const float xv = x[u][v];
+                const float r = __builtin_rintf(xv * q.inv);
+                float xh = r * q.ebx2;
+                if constexpr (F16) xh = __half2float(__float2half_rn(xh));
+                const float d = xv - xh;
+                const bool ok = (__builtin_fabsf(r) < Rf) & (__builtin_fabsf(d) <= q.eb);  // no short circuit: no branches
+                w[v] = ok ? (uint32_t)((int)r + H.ubias) : kEscW;
+                sl[v] = min(w[v], kWinBins);
+                if constexpr (FULL) {
+                    lds_count(sl[v] * (kWinCopies * 4u) + H.lanebase);
+                } else {
+                    const bool in = (valid[u] >> v) & 1u;
+                    if (in) lds_count(sl[v] * (kWinCopies * 4u) + H.lanebase);
+                    else sl[v] = kWinBins;
+                }
+            }
+            // index 255 is rare: count those elements exactly, by symbol (0 = escape)
+            if (__ballot(max(max(sl[0], sl[1]), max(sl[2], sl[3])) == kWinBins) != 0ull) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const bool in = FULL || ((valid[u] >> v) & 1u);
+                    if (in && sl[v] == kWinBins) {
+                        const uint32_t c = w[v] == kEscW ? 0u : w[v] + H.win_lo;
+                        lds_count(H.exact + c * 4u);
+                    }
+                }
+            }
+        }
+    }
+}
+
 template <bool F16, bool VEC>
 __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const QParam* qp, uint32_t* hist,
                                               uint32_t bpt) {
     extern __shared__ __align__(16) uint32_t lh[];
     const uint32_t t = blockIdx.x / bpt, b = blockIdx.x % bpt;
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    HistLds H;
-    H.win_bins = hist_win_bins(g.K);
-    H.win_lo = g.R - H.win_bins / 2u;  // symbol R is the bin of value 0
-    const uint32_t n_words = H.win_bins * kHistCopies + g.K + kW;
-    H.ovf_byte = H.win_bins * kHistCopies * 4u;
-    H.trash_byte = (H.win_bins * kHistCopies + g.K + lane) * 4u;
-    for (uint32_t k = tid; k < n_words; k += 256) lh[k] = 0;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lh;
+    HistC H;
+    H.win_lo = win_lo_of(g.R);
+    H.ubias = (int)(g.R - H.win_lo);
+    H.lanebase = lds0 + (lane & (kWinCopies - 1u)) * 4u;
+    H.exact = lds0 + (kWinBins + 1u) * kWinCopies * 4u;
+    const uint32_t n_words = (kWinBins + 1u) * kWinCopies + g.K + kW;
+    {
+        uint4* z = reinterpret_cast<uint4*>(lh);
+        for (uint32_t k = tid; k < (n_words + 3u) / 4u; k += 256) z[k] = make_uint4(0, 0, 0, 0);
+    }
     __syncthreads();
     const QParam q = qp[t];
     const float Rf = (float)g.R;
@@ -79,19 +146,19 @@ __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const
         const uint32_t gstart = grp * (kW * g.S);
         const uint8_t* gbase = tab + (size_t)gstart * g.es;
         const uint32_t rem = g.n - gstart;
-        if (rem >= kW * g.S) hist_group<F16, VEC, true>(gbase, rem, turns, lane, q, Rf, (int)g.R, lh, H);
-        else hist_group<F16, VEC, false>(gbase, rem, turns, lane, q, Rf, (int)g.R, lh, H);
+        if (rem >= kW * g.S) hist_group<F16, VEC, true>(gbase, rem, turns, lane, q, Rf, H);
+        else hist_group<F16, VEC, false>(gbase, rem, turns, lane, q, Rf, H);
     }
     __syncthreads();
-    // merge: window bins (sum of the copies, skewed start so that the threads of a wavefront read different
-    // banks) plus the overflow array
-    const uint32_t* ovf = lh + H.win_bins * kHistCopies;
+    // merge: the window rows (sum of the copies, skewed start so that the threads of a wavefront read different
+    // banks) plus the exact counts
+    const uint32_t* exact = lh + (kWinBins + 1u) * kWinCopies;
     for (uint32_t k = tid; k < g.K; k += 256) {
-        uint32_t s = ovf[k];
+        uint32_t s = exact[k];
         const uint32_t w = k - H.win_lo;
-        if (w < H.win_bins) {
-            const uint32_t* row = lh + w * kHistCopies;
-            for (uint32_t c = 0; c < kHistCopies; ++c) s += row[(c + tid) & (kHistCopies - 1u)];
+        if (w < kWinBins) {
+            const uint32_t* row = lh + w * kWinCopies;
+            for (uint32_t c = 0; c < kWinCopies; ++c) s += row[(c + tid) & (kWinCopies - 1u)];
         }
         if (s) atomicAdd(&hist[(size_t)t * g.K + k], s);
     }

@@ -1,5 +1,7 @@
 // Host side of the fused compress kernel: which instantiation, how large a grid, the launch.
 #include <algorithm>
+#include <cstdio>
+#include <cstdlib>
 
 #include "dlc_codec_dev.h"
 
@@ -22,6 +24,7 @@ static const void* fused_kernel(const Geom& g) {
 // would not all be resident together with room to spare (its progress argument needs that).
 hipError_t fused_plan(const Geom& g, uint32_t* grid_out) {
     *grid_out = 0;
+    if (g.K > kFusedMaxK) return hipSuccess;  // its LDS code tables are sized for alphabets up to that
     const void* fn = fused_kernel(g);
     const size_t sm = fused_lds_bytes(g.K);
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
@@ -32,6 +35,7 @@ hipError_t fused_plan(const Geom& g, uint32_t* grid_out) {
     if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
     const uint64_t resident = (uint64_t)std::max(per_cu, 0) * (uint64_t)std::max(cus, 0);
     const uint64_t bpt = (g.G + 3) / 4, n_items = bpt * g.T;
+    if (getenv("DLC_DEBUG_PLAN")) fprintf(stderr, "fused_plan: per_cu %d cus %d lds %zu bpt %llu items %llu\n", per_cu, cus, sm, (unsigned long long)bpt, (unsigned long long)n_items);
     if (resident < 2 * bpt) return hipSuccess;
     *grid_out = (uint32_t)std::min<uint64_t>(resident, n_items);
     return hipSuccess;
