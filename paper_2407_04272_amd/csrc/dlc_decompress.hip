@@ -85,25 +85,37 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
         if (tid == 0 && (sym_lo != sym_hi || s_len[0] != 0)) s_ok = 0;
         for (uint32_t i = tid; i < lut_n; i += 256) my_lut[i] = (uint16_t)sym_lo;  // length 0
     } else if (ok2) {
-        if (tid == 0) {
+        if (tid < 64) {
+            // first wavefront: every lane derives the same per-length tables, then the symbols are put in
+            // (length, symbol) order, 64 at a time: a symbol's place is the number of symbols of its length before it
+            const uint32_t lane = tid;
             uint64_t kraft = 0;
             uint32_t cnt = 0, code = 0, index = 0;
-            for (uint32_t l = 1; l <= g.LMAX; ++l) {
-                kraft += (uint64_t)s_cl[l] << (g.LMAX - l);
-                cnt += s_cl[l];
+            uint32_t fill[kLmaxLimit + 1];
+#pragma unroll
+            for (uint32_t l = 1; l <= (uint32_t)kLmaxLimit; ++l) {
+                const uint32_t c = l <= g.LMAX ? s_cl[l] : 0u;
+                kraft += l <= g.LMAX ? (uint64_t)c << (g.LMAX - l) : 0ull;
+                cnt += c;
                 code <<= 1;
-                s_first[l] = code;
-                s_index[l] = index;
-                code += s_cl[l];
-                index += s_cl[l];
+                if (lane == 0) { s_first[l] = code; s_index[l] = index; }
+                fill[l] = index;
+                code += c;
+                index += c;
             }
-            if (kraft != (1ull << g.LMAX) || cnt != n_used) s_ok = 0;
-            else {
-                uint32_t fill[kLmaxLimit + 2];
-                for (uint32_t l = 1; l <= g.LMAX; ++l) fill[l] = s_index[l];
-                for (uint32_t i = 0; i < nl; ++i) {
-                    const uint32_t l = s_len[i];
-                    if (l) s_sorted[fill[l]++] = (uint16_t)(sym_lo + i);
+            if (kraft != (1ull << g.LMAX) || cnt != n_used) {
+                if (lane == 0) s_ok = 0;
+            } else {
+                const uint64_t below = (1ull << lane) - 1ull;
+                for (uint32_t base = 0; base < nl; base += 64) {
+                    const uint32_t i = base + lane;
+                    const uint32_t L = i < nl ? s_len[i] : 0u;
+#pragma unroll
+                    for (uint32_t l = 1; l <= (uint32_t)kLmaxLimit; ++l) {
+                        const uint64_t m = __ballot(L == l);
+                        if (L == l) s_sorted[fill[l] + (uint32_t)__popcll(m & below)] = (uint16_t)(sym_lo + i);
+                        fill[l] += (uint32_t)__popcll(m);
+                    }
                 }
             }
         }
