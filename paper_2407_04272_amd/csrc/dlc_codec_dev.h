@@ -20,8 +20,8 @@ namespace dlc {
 constexpr uint32_t kWinBins = 255;
 constexpr uint32_t kWinCopies = 16;
 __host__ __device__ inline uint32_t win_lo_of(uint32_t R) { return R > kWinBins / 2u ? R - kWinBins / 2u : 0u; }
-// LDS of the histogram kernel in words: window [kWinBins + 1][kWinCopies] | exact counts [K] | scratch [64]
-__host__ __device__ inline size_t hist_lds_bytes(uint32_t K) { return ((size_t)(kWinBins + 1) * kWinCopies + K + kW) * 4; }
+// LDS of the histogram kernel in words: window [kWinBins + 1][kWinCopies] | exact counts [K]
+__host__ __device__ inline size_t hist_lds_bytes(uint32_t K) { return (((size_t)(kWinBins + 1) * kWinCopies + K) * 4 + 15) & ~size_t(15); }
 
 // legacy helpers of the fused kernel's own histogram layout
 constexpr uint32_t kHistWin = 256;

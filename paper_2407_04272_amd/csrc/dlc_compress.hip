@@ -69,62 +69,65 @@ struct HistC {
     uint32_t exact;     // LDS address of the exact counts
 };
 
-constexpr uint32_t kEscW = 0x80000000u;  // no bin has this window index (bins below the window wrap to just under 2^32)
-constexpr uint32_t kHistBlk = 4;  // turns whose loads are issued back to back (S/4 is a multiple)
+// hook for micro-benchmarks (counting switched off); the library counts
+#ifndef DLC_HIST_COUNT
+#define DLC_HIST_COUNT(addr) lds_count(addr)
+#endif
 
-// FULL: every position of the group is inside the table (no masking at all)
+constexpr uint32_t kEscW = 0x80000000u;  // no bin has this window index (bins below the window wrap to just under 2^32)
+constexpr uint32_t kHistBlk = 4;  // units whose loads are issued back to back
+
+// One block of kHistBlk units of one table; a unit is 256 consecutive elements (one 16-byte load per lane).
+// `rem` = elements of the table from the block's first element on, `n_units` = units of the block that are this
+// wavefront's.  FULL: all kHistBlk units are, and all their elements are inside the table (no masking at all).
 template <bool F16, bool VEC, bool FULL>
-__device__ __forceinline__ void hist_group(const uint8_t* gbase, uint32_t rem, uint32_t turns, uint32_t lane,
-                                           const QParam& q, float Rf, const HistC& H) {
-    for (uint32_t jb = 0; jb < turns; jb += kHistBlk) {
-        float x[kHistBlk][4];
-        uint32_t raw[kHistBlk][4];
-        uint32_t valid[kHistBlk];
+__device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, uint32_t n_units, uint32_t lane, const QParam& q,
+                                           float Rf, const HistC& H) {
+    float x[kHistBlk][4];
+    uint32_t raw[kHistBlk][4];
+    uint32_t valid[kHistBlk];
 #pragma unroll
-        for (uint32_t u = 0; u < kHistBlk; ++u)
-            valid[u] = load4<F16, VEC>(gbase, lane * kV + (jb + u) * (kW * kV), FULL ? 0xFFFFFFFFu : rem, x[u], raw[u]);
+    for (uint32_t u = 0; u < kHistBlk; ++u) {
+        const uint32_t lim = FULL ? 0xFFFFFFFFu : (u < n_units ? rem : 0u);
+        valid[u] = load4<F16, VEC>(base, lane * kV + u * (kW * kV), lim, x[u], raw[u]);
+    }
 #pragma unroll
-        for (uint32_t u = 0; u < kHistBlk; ++u) {
-            uint32_t w[4], sl[4];
+    for (uint32_t u = 0; u < kHistBlk; ++u) {
+        uint32_t w[4], sl[4];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                // the quantiser (same arithmetic as quant_symbol), result as a window index; kEscW for an escape
-                const float xv = x[u][v];
-                const float r = __builtin_rintf(xv * q.inv);
-                float xh = r * q.ebx2;
-                if constexpr (F16) xh = __half2float(__float2half_rn(xh));
-                const float d = xv - xh;
-                const bool ok = (__builtin_fabsf(r) < Rf) & (__builtin_fabsf(d) <= q.eb);  // no short circuit: no branches
-                w[v] = ok ? (uint32_t)((int)r + H.ubias) : kEscW;
-                sl[v] = min(w[v], kWinBins);
-                if constexpr (FULL) {
-                    lds_count(sl[v] * (kWinCopies * 4u) + H.lanebase);
-                } else {
-                    const bool in = (valid[u] >> v) & 1u;
-                    if (in) lds_count(sl[v] * (kWinCopies * 4u) + H.lanebase);
-                    else sl[v] = kWinBins;
-                }
+        for (int v = 0; v < 4; ++v) {
+            // the quantiser (same arithmetic as quant_symbol), result as a window index; kEscW for an escape
+            const float xv = x[u][v];
+            const float r = __builtin_rintf(xv * q.inv);
+            float xh = r * q.ebx2;
+            if constexpr (F16) xh = __half2float(__float2half_rn(xh));
+            const float d = xv - xh;
+            const bool ok = (__builtin_fabsf(r) < Rf) & (__builtin_fabsf(d) <= q.eb);  // no short circuit: no branches
+            w[v] = ok ? (uint32_t)((int)r + H.ubias) : kEscW;
+            sl[v] = min(w[v], kWinBins);
+            if constexpr (FULL) {
+                DLC_HIST_COUNT(sl[v] * (kWinCopies * 4u) + H.lanebase);
+            } else {
+                if ((valid[u] >> v) & 1u) DLC_HIST_COUNT(sl[v] * (kWinCopies * 4u) + H.lanebase);
+                else sl[v] = 0;
             }
-            // index 255 is rare: count those elements exactly, by symbol (0 = escape)
-            if (__ballot(max(max(sl[0], sl[1]), max(sl[2], sl[3])) == kWinBins) != 0ull) {
+        }
+        // index 255 is rare: count those elements exactly, by symbol (0 = escape)
+        if (__ballot(max(max(sl[0], sl[1]), max(sl[2], sl[3])) == kWinBins) != 0ull) {
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const bool in = FULL || ((valid[u] >> v) & 1u);
-                    if (in && sl[v] == kWinBins) {
-                        const uint32_t c = w[v] == kEscW ? 0u : w[v] + H.win_lo;
-                        lds_count(H.exact + c * 4u);
-                    }
-                }
-            }
+            for (int v = 0; v < 4; ++v)
+                if (sl[v] == kWinBins) lds_count(H.exact + (w[v] == kEscW ? 0u : w[v] + H.win_lo) * 4u);
         }
     }
 }
 
+// The payload is cut into units of 256 elements, U per table, and every wavefront of the grid gets the same
+// number of consecutive units (table after table), so that all of them finish together whatever the shape is.
+// A work-group whose units touch several tables handles them one table at a time.
 template <bool F16, bool VEC>
 __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const QParam* qp, uint32_t* hist,
-                                              uint32_t bpt) {
+                                              uint32_t U, uint32_t units_per_wave) {
     extern __shared__ __align__(16) uint32_t lh[];
-    const uint32_t t = blockIdx.x / bpt, b = blockIdx.x % bpt;
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t lds0 = (uint32_t)(uintptr_t)lh;
     HistC H;
@@ -132,35 +135,52 @@ __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const
     H.ubias = (int)(g.R - H.win_lo);
     H.lanebase = lds0 + (lane & (kWinCopies - 1u)) * 4u;
     H.exact = lds0 + (kWinBins + 1u) * kWinCopies * 4u;
-    const uint32_t n_words = (kWinBins + 1u) * kWinCopies + g.K + kW;
-    {
-        uint4* z = reinterpret_cast<uint4*>(lh);
-        for (uint32_t k = tid; k < (n_words + 3u) / 4u; k += 256) z[k] = make_uint4(0, 0, 0, 0);
-    }
-    __syncthreads();
-    const QParam q = qp[t];
+    const uint32_t n_words = (kWinBins + 1u) * kWinCopies + g.K;
     const float Rf = (float)g.R;
-    const uint8_t* tab = static_cast<const uint8_t*>(payload) + (size_t)t * g.n * g.es;
-    const uint32_t turns = g.S / kV;
-    for (uint32_t grp = b * 4 + wave; grp < g.G; grp += bpt * 4) {
-        const uint32_t gstart = grp * (kW * g.S);
-        const uint8_t* gbase = tab + (size_t)gstart * g.es;
-        const uint32_t rem = g.n - gstart;
-        if (rem >= kW * g.S) hist_group<F16, VEC, true>(gbase, rem, turns, lane, q, Rf, H);
-        else hist_group<F16, VEC, false>(gbase, rem, turns, lane, q, Rf, H);
-    }
-    __syncthreads();
-    // merge: the window rows (sum of the copies, skewed start so that the threads of a wavefront read different
-    // banks) plus the exact counts
-    const uint32_t* exact = lh + (kWinBins + 1u) * kWinCopies;
-    for (uint32_t k = tid; k < g.K; k += 256) {
-        uint32_t s = exact[k];
-        const uint32_t w = k - H.win_lo;
-        if (w < kWinBins) {
-            const uint32_t* row = lh + w * kWinCopies;
-            for (uint32_t c = 0; c < kWinCopies; ++c) s += row[(c + tid) & (kWinCopies - 1u)];
+    const uint64_t total_units = (uint64_t)g.T * U;
+    // this wavefront's units [w0, w1) and the work-group's [g0, g1), as global unit numbers
+    const uint64_t g0 = (uint64_t)blockIdx.x * 4u * units_per_wave;
+    const uint64_t g1 = min(total_units, g0 + 4ull * units_per_wave);
+    const uint64_t w0 = min(total_units, g0 + (uint64_t)wave * units_per_wave), w1 = min(total_units, w0 + units_per_wave);
+    if (g0 >= g1) return;  // uniform
+    const uint32_t t_first = (uint32_t)(g0 / U), t_last = (uint32_t)((g1 - 1) / U);
+    for (uint32_t t = t_first; t <= t_last; ++t) {
+        {
+            uint4* z = reinterpret_cast<uint4*>(lh);
+            for (uint32_t k = tid; k < (n_words + 3u) / 4u; k += 256) z[k] = make_uint4(0, 0, 0, 0);
         }
-        if (s) atomicAdd(&hist[(size_t)t * g.K + k], s);
+        __syncthreads();
+        const QParam q = qp[t];
+        const uint8_t* tab = static_cast<const uint8_t*>(payload) + (size_t)t * g.n * g.es;
+        // my units inside table t
+        const uint64_t t0 = (uint64_t)t * U, t1 = t0 + U;
+        const uint64_t a = max(w0, t0), b = min(w1, t1);
+        if (a < b) {
+            uint32_t u = (uint32_t)(a - t0);
+            const uint32_t ue = (uint32_t)(b - t0);
+            for (; u < ue; u += kHistBlk) {
+                const uint32_t first = u * (kW * kV);  // element of the table
+                const uint8_t* base = tab + (size_t)first * g.es;
+                const uint32_t rem = g.n - first;
+                const uint32_t n_units = min(kHistBlk, ue - u);
+                if (n_units == kHistBlk && rem >= kHistBlk * kW * kV) hist_block<F16, VEC, true>(base, rem, n_units, lane, q, Rf, H);
+                else hist_block<F16, VEC, false>(base, rem, n_units, lane, q, Rf, H);
+            }
+        }
+        __syncthreads();
+        // merge: the window rows (sum of the copies, skewed start so that the threads of a wavefront read different
+        // banks) plus the exact counts
+        const uint32_t* exact = lh + (kWinBins + 1u) * kWinCopies;
+        for (uint32_t k = tid; k < g.K; k += 256) {
+            uint32_t s = exact[k];
+            const uint32_t w = k - H.win_lo;
+            if (w < kWinBins) {
+                const uint32_t* row = lh + w * kWinCopies;
+                for (uint32_t c = 0; c < kWinCopies; ++c) s += row[(c + tid) & (kWinCopies - 1u)];
+            }
+            if (s) atomicAdd(&hist[(size_t)t * g.K + k], s);
+        }
+        __syncthreads();
     }
 }
 
@@ -285,16 +305,17 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         return hipGetLastError();
     }
     // histogram
-    uint32_t bpt_h = (g.G + 3) / 4;
     {
-        // cap the grid at a few work-groups per CU; a work-group then loops over groups of its table
-        const uint32_t max_blocks = 256 * 8;
-        const uint32_t cap = std::max<uint32_t>(1, max_blocks / g.T);
-        bpt_h = std::min(bpt_h, cap);
+        // equal shares of 16 units (16 KiB of fp32) per wavefront: measured best on MI355X, a little ahead of one
+        // share per resident wavefront
+        const uint32_t U = (g.n + kW * kV - 1) / (kW * kV);
+        const uint64_t total_units = (uint64_t)g.T * U;
+        const uint32_t units_per_wave = 4 * kHistBlk;
+        const uint32_t grid_n = (uint32_t)((total_units + 4ull * units_per_wave - 1) / (4ull * units_per_wave));
         const size_t sm = hist_lds_bytes(g.K);
-        dim3 grid(g.T * bpt_h), block(256);
+        dim3 grid(grid_n), block(256);
         if (prof_on(pl, P_HIST)) prof_begin(prof, P_HIST, s);
-#define DLC_HIST(FF, V) hipLaunchKernelGGL((k_hist<FF, V>), grid, block, sm, s, payload, g, w.qp, w.hist, bpt_h)
+#define DLC_HIST(FF, V) hipLaunchKernelGGL((k_hist<FF, V>), grid, block, sm, s, payload, g, w.qp, w.hist, U, units_per_wave)
         if (f16) { if (g.vec) DLC_HIST(true, true); else DLC_HIST(true, false); }
         else { if (g.vec) DLC_HIST(false, true); else DLC_HIST(false, false); }
 #undef DLC_HIST

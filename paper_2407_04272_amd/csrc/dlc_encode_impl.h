@@ -57,23 +57,32 @@ void k_encode(const void* payload, Geom g, FixedLayout F, const QParam* qp, cons
     uint32_t pk[S / 2];
     uint32_t bits = 0;
     uint32_t n_esc = 0;  // escapes of the whole group (a scalar: counted from the comparison masks)
-    constexpr int kBlk = 8;  // turns whose loads are in flight together (8 x 16 B per lane)
+    constexpr int kBlk = 8;  // turns per block (8 x 16 B per lane); the next block's loads are issued before this one is used
+    constexpr int kNBlk = S / 4 / kBlk;
     if (active) {
+        float x[2][kBlk][4];
+        uint32_t raw[2][kBlk][4];
+        uint32_t valid[2][kBlk];
 #pragma clang loop unroll(full)
-        for (int jb = 0; jb < S / 4; jb += kBlk) {
-            float x[kBlk][4];
-            uint32_t raw[kBlk][4];
-            uint32_t valid[kBlk];
+        for (int u = 0; u < kBlk; ++u)
+            valid[0][u] = load4<F16, VEC>(gbase, lane * kV + (uint32_t)u * (kW * kV), rem, x[0][u], raw[0][u]);
 #pragma clang loop unroll(full)
-            for (int u = 0; u < kBlk; ++u)
-                valid[u] = load4<F16, VEC>(gbase, lane * kV + (uint32_t)(jb + u) * (kW * kV), rem, x[u], raw[u]);
+        for (int ib = 0; ib < kNBlk; ++ib) {
+            const int cur = ib & 1, nxt = cur ^ 1;
+            if (ib + 1 < kNBlk) {
+#pragma clang loop unroll(full)
+                for (int u = 0; u < kBlk; ++u)
+                    valid[nxt][u] = load4<F16, VEC>(gbase, lane * kV + (uint32_t)((ib + 1) * kBlk + u) * (kW * kV), rem, x[nxt][u],
+                                                    raw[nxt][u]);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // the loads above stay above, the work below stays below
 #pragma clang loop unroll(full)
             for (int u = 0; u < kBlk; ++u) {
                 uint32_t e[4];
 #pragma clang loop unroll(full)
                 for (int v = 0; v < 4; ++v) {
-                    const uint32_t c = quant_symbol<F16>(x[u][v], q, Rf, (int)g.R);
-                    const bool ok = (valid[u] >> v) & 1u;
+                    const uint32_t c = quant_symbol<F16>(x[cur][u][v], q, Rf, (int)g.R);
+                    const bool ok = (valid[cur][u] >> v) & 1u;
                     // unconditional table read, masked afterwards: a position past the end contributes no bits
                     e[v] = (uint32_t)s_enc[c] & (0u - (uint32_t)ok);
                     n_esc += (uint32_t)__popcll(__ballot(ok && c == 0u));
@@ -82,11 +91,11 @@ void k_encode(const void* payload, Geom g, FixedLayout F, const QParam* qp, cons
                 // opaque to the optimiser: otherwise it keeps length and codeword of every symbol in registers of
                 // their own instead of the packed words
                 asm volatile("" : "+v"(w0), "+v"(w1));
-                pk[2 * (jb + u)] = w0;
-                pk[2 * (jb + u) + 1] = w1;
+                pk[2 * (ib * kBlk + u)] = w0;
+                pk[2 * (ib * kBlk + u) + 1] = w1;
                 bits += ((w0 >> 12) & 0xFu) + (w0 >> 28) + ((w1 >> 12) & 0xFu) + (w1 >> 28);
             }
-            __builtin_amdgcn_sched_barrier(0);  // keep the next block's loads from being hoisted above this one
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     DLC_ESTAMP(2);

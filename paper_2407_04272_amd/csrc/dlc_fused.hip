@@ -1,7 +1,5 @@
 // Host side of the fused compress kernel: which instantiation, how large a grid, the launch.
 #include <algorithm>
-#include <cstdio>
-#include <cstdlib>
 
 #include "dlc_codec_dev.h"
 
@@ -35,7 +33,6 @@ hipError_t fused_plan(const Geom& g, uint32_t* grid_out) {
     if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
     const uint64_t resident = (uint64_t)std::max(per_cu, 0) * (uint64_t)std::max(cus, 0);
     const uint64_t bpt = (g.G + 3) / 4, n_items = bpt * g.T;
-    if (getenv("DLC_DEBUG_PLAN")) fprintf(stderr, "fused_plan: per_cu %d cus %d lds %zu bpt %llu items %llu\n", per_cu, cus, sm, (unsigned long long)bpt, (unsigned long long)n_items);
     if (resident < 2 * bpt) return hipSuccess;
     *grid_out = (uint32_t)std::min<uint64_t>(resident, n_items);
     return hipSuccess;
