@@ -17,14 +17,14 @@ def to_device(x: np.ndarray):
 class GpuRun:
     """compress + decompress of one payload on cuda:0; everything copied back to numpy."""
 
-    def __init__(self, payload, eb, R=512, S=256, LMAX=12, capacity=None, ctx=None, d_payload=None):
+    def __init__(self, payload, eb, R=512, S=256, LMAX=12, capacity=None, ctx=None, d_payload=None, flags=0):
         import torch
         from paper_2407_04272_amd import binding as b
         if d_payload is None:
             d_payload = to_device(payload)
         T, B, D = d_payload.shape
         dt = b.F16 if d_payload.dtype == torch.float16 else b.F32
-        self.cfg = b.make_config(dt, T, B, D, R, S, LMAX)
+        self.cfg = b.make_config(dt, T, B, D, R, S, LMAX, flags)
         self.ctx = ctx if ctx is not None else b.Context(self.cfg)
         self.d_payload = d_payload
         bound = b.dlc_compress_bound(self.cfg)
