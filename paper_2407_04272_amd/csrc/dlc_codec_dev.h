@@ -343,59 +343,16 @@ __host__ __device__ inline size_t fused_lds_bytes(uint32_t K) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// offsets of the groups' words: single-pass look-back over per-group records
+// offsets of the output: single-pass look-back scan
 // ------------------------------------------------------------------------------------------------
 constexpr uint32_t kFlagAgg = 1, kFlagPrefix = 2;
 constexpr uint32_t kSpinLimit = 1u << 22;
 
-// exclusive prefix of `total` over all groups before gid; publishes this group's records.  All lanes call.
-__device__ __forceinline__ uint32_t group_scan(uint64_t* state, uint64_t epoch, uint32_t gid, uint32_t total,
-                                               uint32_t lane, Ctrl* ctrl, bool* dead) {
-    const uint64_t tag = epoch << 34;
-    if (lane == 0)
-        __hip_atomic_store(&state[gid], tag | ((uint64_t)(gid == 0 ? kFlagPrefix : kFlagAgg) << 32) | total,
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    uint32_t excl = 0;
-    if (gid > 0) {
-        int64_t pos = (int64_t)gid - 1;
-        uint32_t spins = 0;
-        for (;;) {
-            const int64_t my = pos - (int64_t)lane;
-            uint64_t sv;
-            uint32_t flag;
-            for (;;) {
-                sv = my >= 0 ? __hip_atomic_load(&state[my], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                             : (tag | ((uint64_t)kFlagPrefix << 32));
-                flag = (sv >> 34) == epoch ? (uint32_t)(sv >> 32) & 3u : 0u;
-                if (__ballot(flag == 0u) == 0ull) break;
-                if (++spins > kSpinLimit) break;  // never expected; the bound only guarantees termination
-                __builtin_amdgcn_s_sleep(2);
-            }
-            if (spins > kSpinLimit) {
-                if (lane == 0) { set_status(ctrl, DLC_ESTATE); ctrl->abort = 1; }
-                *dead = true;
-                break;
-            }
-            const uint64_t pm = __ballot(flag == kFlagPrefix);
-            if (pm) {
-                const uint32_t first = (uint32_t)__ffsll((unsigned long long)pm) - 1u;
-                excl += wave_sum(lane <= first ? (uint32_t)sv : 0u);
-                break;
-            }
-            excl += wave_sum((uint32_t)sv);
-            pos -= 64;
-        }
-        if (lane == 0)
-            __hip_atomic_store(&state[gid], tag | ((uint64_t)kFlagPrefix << 32) | (uint32_t)(excl + total),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    return excl;
-}
-
-// The same scan with one record per work-group and 256 records per look-back step (four per lane): the chain
-// of "wait for a predecessor's prefix" steps across the work-groups that run at the same time is what bounds a
-// streaming kernel that places its output by this scan, so the records are few and the steps wide.
-// Called by one whole wavefront; returns the exclusive prefix of `total` over the work-groups before `wg`.
+// Exclusive prefix of `total` over the work-groups before `wg`: single-pass look-back over one record per
+// work-group, 256 records per step (four per lane).  The chain of "wait for a predecessor's prefix" steps across
+// the work-groups that run at the same time is what bounds a streaming kernel that places its output by such a
+// scan, so the records are few and the steps wide.  Publishes this work-group's records.  Called by one whole
+// wavefront.
 __device__ __forceinline__ uint32_t wg_scan(uint64_t* state, uint64_t epoch, uint32_t wg, uint32_t total, uint32_t lane,
                                             Ctrl* ctrl, bool* dead) {
     const uint64_t tag = epoch << 34;

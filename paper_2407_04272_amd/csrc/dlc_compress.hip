@@ -20,15 +20,6 @@ hipError_t launch_fused(const Geom& g, const FixedLayout& F, const void* payload
                         uint64_t capacity, hipStream_t s);
 
 // ------------------------------------------------------------------------------------------------
-// clear the per-call part of the workspace
-// ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_zero(uint4* p, size_t n16) {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
-}
-
-// ------------------------------------------------------------------------------------------------
 // quantiser alone (inspection entry point)
 // ------------------------------------------------------------------------------------------------
 template <bool F16>

@@ -237,7 +237,7 @@ __device__ __forceinline__ void fused_phase_a(const FusedEnv& E, const FusedA& A
 // phase B of one item: waits for the table's codebook.  Called by all threads (has barriers).
 template <int S, bool F16, bool VEC>
 __device__ __forceinline__ void fused_phase_b(const FusedEnv& E, const FusedItem& I, uint32_t (&pk)[S / 2], uint32_t* s_go,
-                                              uint32_t tid, uint32_t lane) {
+                                              uint32_t* s_tot, uint32_t tid, uint32_t lane, uint32_t wave) {
     const Geom& g = E.g;
 #ifdef DLC_EXP_STAMPS
     const uint32_t item = I.t * E.bpt + I.grp / 4;
@@ -269,8 +269,8 @@ __device__ __forceinline__ void fused_phase_b(const FusedEnv& E, const FusedItem
     }
     __syncthreads();
     DLC_FSTAMP(9);
+    uint32_t bits = 0;
     if (I.active) {
-        uint32_t bits = 0;
         constexpr int kB = 8;  // pairs whose table reads are in flight together
 #pragma clang loop unroll(full)
         for (int ib = 0; ib < S / 2; ib += kB) {
@@ -293,12 +293,25 @@ __device__ __forceinline__ void fused_phase_b(const FusedEnv& E, const FusedItem
             __builtin_amdgcn_sched_barrier(0);
         }
         DLC_FSTAMP(10);
-        const uint32_t nw = (bits + 31u) >> 5;
-        const uint32_t incl = wave_incl_scan(nw, lane);
-        const uint32_t lane_off = incl - nw;
-        const uint32_t chunk_total = __shfl(incl, 63, 64);
-        const uint32_t total = chunk_total + 2u * I.n_esc;
-        const uint32_t excl = group_scan(E.state, E.epoch, I.gid, total, lane, E.ctrl, &dead);
+    }
+    const uint32_t nw = (bits + 31u) >> 5;
+    const uint32_t incl = wave_incl_scan(nw, lane);
+    const uint32_t lane_off = incl - nw;
+    const uint32_t chunk_total = __shfl(incl, 63, 64);
+    const uint32_t total = chunk_total + 2u * I.n_esc;  // 0 for an idle wavefront
+    // offsets: one scan record per item; the wavefronts' totals are joined through LDS
+    if (lane == 0) s_tot[wave] = total;
+    __syncthreads();
+    if (wave == 0) {
+        const uint32_t e = wg_scan(E.state, E.epoch, I.t * E.bpt + I.grp / 4u, s_tot[0] + s_tot[1] + s_tot[2] + s_tot[3], lane,
+                                   E.ctrl, &dead);
+        if (lane == 0) { s_tot[4] = e; s_tot[5] = dead ? 1u : 0u; }
+    }
+    __syncthreads();
+    if (I.active) {
+        dead = s_tot[5] != 0u;
+        uint32_t excl = s_tot[4];
+        for (uint32_t k = 0; k < wave; ++k) excl += s_tot[k];
         DLC_FSTAMP(11);
         if (E.F.off_payload + 4ull * ((uint64_t)excl + total) > E.capacity) {
             if (!dead && lane == 0) { set_status(E.ctrl, DLC_ECAPACITY); E.ctrl->abort = 1; }
@@ -344,7 +357,7 @@ void k_fused(const void* payload, Geom g, FixedLayout F, const QParam* qp, uint3
              uint32_t* word_end) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ CodebookShared sh;
-    __shared__ uint32_t s_item, s_last, s_go;
+    __shared__ uint32_t s_item, s_last, s_go, s_tot[6];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;  // LDS address of the dynamic part
     FusedEnv E;
@@ -382,7 +395,7 @@ void k_fused(const void* payload, Geom g, FixedLayout F, const QParam* qp, uint3
             const uint32_t item = __builtin_amdgcn_readfirstlane(s_item);
             if (item >= n_items) break;
             fused_phase_a<S, F16, VEC>(E, A, item, I, pk, sh, &s_last, tid, lane, wave);
-            fused_phase_b<S, F16, VEC>(E, I, pk, &s_go, tid, lane);
+            fused_phase_b<S, F16, VEC>(E, I, pk, &s_go, s_tot, tid, lane, wave);
         }
     }
 }
