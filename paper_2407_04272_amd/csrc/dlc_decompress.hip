@@ -239,17 +239,20 @@ __global__ __launch_bounds__(512) void k_decode(Geom g, const uint8_t* comp, con
                     v4[h2 * 2 + v] = (float)((int)(e & 0xFFFu) - R) * ebx2;
                 }
             }
+            // streaming stores: the output is written once and is larger than the caches
             if constexpr (VEC) {
                 if constexpr (F16) {
-                    uint2 o;
+                    typedef uint32_t u2v __attribute__((ext_vector_type(2)));
+                    u2v o;
                     o.x = (uint32_t)__half_as_ushort(__float2half_rn(v4[0])) |
                           ((uint32_t)__half_as_ushort(__float2half_rn(v4[1])) << 16);
                     o.y = (uint32_t)__half_as_ushort(__float2half_rn(v4[2])) |
                           ((uint32_t)__half_as_ushort(__float2half_rn(v4[3])) << 16);
-                    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(tab) + idx) = o;
+                    __builtin_nontemporal_store(o, reinterpret_cast<u2v*>(reinterpret_cast<uint16_t*>(tab) + idx));
                 } else {
-                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(tab) + idx) =
-                        make_float4(v4[0], v4[1], v4[2], v4[3]);
+                    typedef float f4v __attribute__((ext_vector_type(4)));
+                    f4v o4 = {v4[0], v4[1], v4[2], v4[3]};
+                    __builtin_nontemporal_store(o4, reinterpret_cast<f4v*>(reinterpret_cast<float*>(tab) + idx));
                 }
             } else {
 #pragma unroll

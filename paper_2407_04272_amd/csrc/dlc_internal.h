@@ -105,13 +105,17 @@ __device__ __forceinline__ uint32_t load4(const void* gbase, uint32_t off, uint3
     if constexpr (VEC) {
         const bool in = off < rem;
         const uint32_t o2 = in ? off : 0u;
+        // streaming loads: the payload is read once per kernel and is larger than the caches, so it is kept from
+        // displacing what the caches hold (measured: the histogram kernel 150 -> 88 us inside the compress/decompress loop)
         if constexpr (F16) {
-            uint2 w = *reinterpret_cast<const uint2*>(gb + o2 * 2u);
+            typedef uint32_t u2v __attribute__((ext_vector_type(2)));
+            const u2v w = __builtin_nontemporal_load(reinterpret_cast<const u2v*>(gb + o2 * 2u));
             raw[0] = w.x & 0xFFFFu; raw[1] = w.x >> 16; raw[2] = w.y & 0xFFFFu; raw[3] = w.y >> 16;
 #pragma unroll
             for (int v = 0; v < 4; ++v) x[v] = __half2float(__ushort_as_half((unsigned short)raw[v]));
         } else {
-            uint4 w = *reinterpret_cast<const uint4*>(gb + o2 * 4u);
+            typedef uint32_t u4v __attribute__((ext_vector_type(4)));
+            const u4v w = __builtin_nontemporal_load(reinterpret_cast<const u4v*>(gb + o2 * 4u));
             raw[0] = w.x; raw[1] = w.y; raw[2] = w.z; raw[3] = w.w;
 #pragma unroll
             for (int v = 0; v < 4; ++v) x[v] = __uint_as_float(raw[v]);
@@ -125,10 +129,10 @@ __device__ __forceinline__ uint32_t load4(const void* gbase, uint32_t off, uint3
             const uint32_t o2 = in ? off + v : 0u;
             m |= in ? (1u << v) : 0u;
             if constexpr (F16) {
-                raw[v] = *reinterpret_cast<const uint16_t*>(gb + o2 * 2u);
+                raw[v] = __builtin_nontemporal_load(reinterpret_cast<const uint16_t*>(gb + o2 * 2u));
                 x[v] = __half2float(__ushort_as_half((unsigned short)raw[v]));
             } else {
-                raw[v] = *reinterpret_cast<const uint32_t*>(gb + o2 * 4u);
+                raw[v] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(gb + o2 * 4u));
                 x[v] = __uint_as_float(raw[v]);
             }
         }
