@@ -402,6 +402,83 @@ __device__ __forceinline__ uint32_t wg_scan(uint64_t* state, uint64_t epoch, uin
     return excl;
 }
 
+// The same look-back in steps that can be spread through other work: issue() starts the loads of one step,
+// consume() uses them.  Between the two the caller does something else, so the latency of the records (they
+// live in device-coherent memory, a few hundred nanoseconds away) costs nothing.  The caller has published its
+// own aggregate record before the first step (publish_aggregate) and publishes the prefix when done.
+struct LookBack {
+    int64_t pos;      // nearest record not yet added
+    uint32_t excl;    // sum so far
+    uint32_t spins;
+    bool done, failed, pending;
+    uint64_t sv[4];
+};
+
+__device__ __forceinline__ void lb_publish_aggregate(uint64_t* state, uint64_t epoch, uint32_t wg, uint32_t total, uint32_t lane) {
+    if (lane == 0)
+        __hip_atomic_store(&state[wg], (epoch << 34) | ((uint64_t)(wg == 0 ? kFlagPrefix : kFlagAgg) << 32) | total,
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void lb_init(LookBack& L, uint32_t wg) {
+    L.pos = (int64_t)wg - 1;
+    L.excl = 0;
+    L.spins = 0;
+    L.done = wg == 0;
+    L.failed = false;
+    L.pending = false;
+}
+__device__ __forceinline__ void lb_issue(LookBack& L, const uint64_t* state, uint64_t epoch, uint32_t lane) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int64_t my = L.pos - (int64_t)(lane * 4u + (uint32_t)k);
+        L.sv[k] = my >= 0 ? __hip_atomic_load(&state[my], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                          : ((epoch << 34) | ((uint64_t)kFlagPrefix << 32));  // before the first work-group: an empty prefix
+    }
+    L.pending = true;
+}
+// true if the step made progress (false: a record nearer than the nearest prefix is not published yet)
+__device__ __forceinline__ bool lb_consume(LookBack& L, uint64_t epoch, uint32_t lane) {
+    uint32_t sum = 0;    // values up to and including the lane's first prefix record (or all four)
+    bool has_p = false;  // there is a prefix record among them
+    bool hole = false;   // an unpublished record comes before it
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint64_t sv = L.sv[k];
+        const uint32_t flag = (sv >> 34) == epoch ? (uint32_t)(sv >> 32) & 3u : 0u;
+        if (!has_p) {
+            hole = hole || flag == 0u;
+            sum += flag != 0u ? (uint32_t)sv : 0u;
+            has_p = flag == kFlagPrefix;
+        }
+    }
+    L.pending = false;
+    const uint64_t pm = __ballot(has_p);
+    const uint32_t first = pm ? (uint32_t)__ffsll((unsigned long long)pm) - 1u : 64u;  // lane of the nearest prefix
+    if (__ballot(hole && lane <= first) != 0ull) return false;
+    L.excl += wave_sum(lane <= first ? sum : 0u);
+    if (pm) L.done = true;
+    else L.pos -= 256;
+    return true;
+}
+// runs the remaining steps to the end (bounded) and publishes the prefix record
+__device__ __forceinline__ void lb_finish(LookBack& L, uint64_t* state, uint64_t epoch, uint32_t wg, uint32_t total, uint32_t lane,
+                                          Ctrl* ctrl) {
+    while (!L.done && !L.failed) {
+        if (!L.pending) lb_issue(L, state, epoch, lane);
+        if (!lb_consume(L, epoch, lane)) {
+            if (++L.spins > kSpinLimit) {  // never expected; the bound only guarantees termination
+                if (lane == 0) { set_status(ctrl, DLC_ESTATE); ctrl->abort = 1; }
+                L.failed = true;
+            } else {
+                __builtin_amdgcn_s_sleep(1);
+            }
+        }
+    }
+    if (wg > 0 && !L.failed && lane == 0)
+        __hip_atomic_store(&state[wg], (epoch << 34) | ((uint64_t)kFlagPrefix << 32) | (uint32_t)(L.excl + total),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // escape records of one group, in increasing element index, behind its chunk words: the group's elements are
 // read and quantised once more in a rolled loop (rare for fp32)
 template <int S, bool F16, bool VEC>

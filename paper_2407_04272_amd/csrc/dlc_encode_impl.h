@@ -18,46 +18,88 @@ namespace dlc {
 
 // ------------------------------------------------------------------------------------------------
 // bit-packed encode.
-//   walk 1: load, quantise, look the (length, codeword) pairs up in LDS, keep them packed in registers,
-//           sum the chunk's bits, count the escapes
+//   walk 1: load, quantise to a window index (one byte: 0..254 = symbol win_lo + index, 255 = everything else),
+//           keep the indices in registers four to a word, look up the code length of each in LDS and sum the
+//           chunk's bits.  Index 255 is rare (an escape, a symbol outside the window, a position past the end of
+//           the table): its element is looked at exactly, with the code from the full table; escapes are counted.
 //   scan  : chunk word counts inside the wavefront; the wavefronts' totals (chunk words + two words per
 //           escape) are joined per work-group, and the work-groups' totals across the grid by a single-pass
 //           look-back (ordered work-group ids: a work-group only ever waits for work-groups that started
 //           earlier)
-//   walk 2: shift the kept pairs into a 64-bit accumulator, store whole words at the chunk's offset
-//   escapes (rare for fp32): a group that has any walks its elements once more in a rolled loop and
-//           writes its records, in increasing element index, behind its chunk words
+//   walk 2: look up length and codeword of the kept indices (index 255: the element itself once more), join the
+//           two codes of a pair, shift into a 64-bit accumulator, store whole words at the chunk's offset
+//   escapes: a group that has any walks its elements once more in a rolled loop and writes its records, in
+//           increasing element index, behind its chunk words
+// Keeping bytes instead of (length, codeword) entries halves the registers a wavefront holds between the walks,
+// which doubles the wavefronts per SIMD: the kernel is bound by latency (global scan, table look-ups, stores),
+// not by arithmetic.
 // ------------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) uint16_t lds_u16;
+__device__ __forceinline__ uint32_t lds_read16(uint32_t addr, uint32_t byte_off) {
+    return *reinterpret_cast<lds_u16*>(reinterpret_cast<__attribute__((address_space(3))) unsigned char*>(addr) + byte_off);
+}
+
+constexpr uint32_t kEncEscW = 0x80000000u;  // no bin has this window index (bins below the window wrap to just under 2^32)
+
+// (length << 12 | codeword) of the element at `off` of the group, quantised again; *is_escape says whether it is one
+template <bool F16>
+__device__ __forceinline__ uint32_t entry_of_element(const uint8_t* gbase, uint32_t off, const QParam& q, float Rf, int R,
+                                                     const uint16_t* enc_t, uint32_t* is_escape) {
+    float x;
+    if constexpr (F16) x = __half2float(__ushort_as_half(reinterpret_cast<const unsigned short*>(gbase)[off]));
+    else x = reinterpret_cast<const float*>(gbase)[off];
+    const uint32_t sym = quant_symbol<F16>(x, q, Rf, R);
+    *is_escape = sym == 0u ? 1u : 0u;
+    return enc_t[sym];
+}
+
+__device__ __forceinline__ bool has_ff_byte(uint32_t m) {
+    return ((m & 0xFFu) == 0xFFu) | ((m & 0xFF00u) == 0xFF00u) | ((m & 0xFF0000u) == 0xFF0000u) | (m >= 0xFF000000u);
+}
+
 template <int S, bool F16, bool VEC>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(S == 256 ? 2 : (S == 128 ? 3 : 5))))
-void k_encode(const void* payload, Geom g, FixedLayout F, const QParam* qp, const uint16_t* enc, Ctrl* ctrl,
-              uint64_t* state, uint64_t epoch, uint8_t* out, uint64_t capacity, uint32_t bpt, uint32_t* word_start,
-              uint32_t* word_end) {
-    extern __shared__ __align__(16) uint16_t s_enc[];
-    __shared__ uint32_t s_wg, s_tot[4], s_excl, s_dead;
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(S == 256 ? 4 : 5)))
+void k_encode(const void* payload, Geom g, FixedLayout F, const QParam* qp, const uint16_t* enc, const TMeta* tmeta,
+              Ctrl* ctrl, uint64_t* state, uint64_t epoch, uint8_t* out, uint64_t capacity, uint32_t bpt,
+              uint32_t* word_start, uint32_t* word_end) {
+    __shared__ __align__(16) uint16_t s_len[256], s_code[256];  // by window index; entry 255 is empty
+    __shared__ uint32_t s_wg, s_tot[4], s_ct[4], s_excl, s_dead;
+    constexpr uint32_t kStageWords = 8u * (uint32_t)S;  // LDS staging per wavefront: room for a group of up to 4 bits per symbol
+    __shared__ __align__(16) uint32_t s_stage[4 * kStageWords];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     if (tid == 0) s_wg = atomicAdd(&ctrl->ticket, 1u);
     __syncthreads();
     const uint32_t wg = __builtin_amdgcn_readfirstlane(s_wg);
     const uint32_t t = wg / bpt, b = wg % bpt;
     DLC_ESTAMP(0);
-    for (uint32_t k = tid; k < g.K; k += 256) s_enc[k] = enc[(size_t)t * g.K + k];
+    const uint32_t win_lo = win_lo_of(g.R);
+    const uint16_t* enc_t = enc + (size_t)t * g.K;
+    {
+        const uint32_t c = win_lo + tid;
+        const uint32_t e = (tid < kWinBins && c < g.K) ? enc_t[c] : 0u;
+        s_len[tid] = (uint16_t)(e >> 12);
+        s_code[tid] = (uint16_t)(e & 0xFFFu);
+    }
     __syncthreads();
     const uint32_t grp = b * 4 + wave;
     const bool active = grp < g.G;  // uniform over the wavefront; an idle wavefront only takes part in the barriers
     const uint32_t gid = t * g.G + (active ? grp : 0u);
     const QParam q = qp[t];
     const float Rf = (float)g.R;
+    const int ubias = (int)(g.R - win_lo);
     const uint8_t* tab = static_cast<const uint8_t*>(payload) + (size_t)t * g.n * g.es;
     const uint32_t gstart = grp * (kW * (uint32_t)S);
     const uint8_t* gbase = tab + (size_t)gstart * g.es;
     const uint32_t rem = active ? g.n - gstart : 0u;
+    // can index 255 occur in this group at all?  (an escape, a symbol outside the window, a ragged last group)
+    const TMeta tm = tmeta[t];
+    const bool plain = tm.n_outliers == 0u && tm.sym_lo >= win_lo && tm.sym_hi < win_lo + kWinBins && rem >= kW * (uint32_t)S;
+    const uint32_t a_len = (uint32_t)(uintptr_t)s_len, d_code = (uint32_t)(uintptr_t)s_code - a_len;
 
     DLC_ESTAMP(1);
-    uint32_t pk[S / 2];
-    uint32_t bits = 0;
-    uint32_t n_esc = 0;  // escapes of the whole group (a scalar: counted from the comparison masks)
-    constexpr int kBlk = 8;  // turns per block (8 x 16 B per lane); the next block's loads are issued before this one is used
+    uint32_t ix[S / 4];  // window indices, four to a word, in element order
+    uint32_t bits = 0, my_esc = 0;
+    constexpr int kBlk = 4;  // turns per block (16 B per lane each); the next block's loads are issued before this one is used
     constexpr int kNBlk = S / 4 / kBlk;
     if (active) {
         float x[2][kBlk][4];
@@ -78,69 +120,167 @@ void k_encode(const void* payload, Geom g, FixedLayout F, const QParam* qp, cons
             __builtin_amdgcn_sched_barrier(0);  // the loads above stay above, the work below stays below
 #pragma clang loop unroll(full)
             for (int u = 0; u < kBlk; ++u) {
-                uint32_t e[4];
+                uint32_t w[4], sl[4];
 #pragma clang loop unroll(full)
                 for (int v = 0; v < 4; ++v) {
-                    const uint32_t c = quant_symbol<F16>(x[cur][u][v], q, Rf, (int)g.R);
-                    const bool ok = (valid[cur][u] >> v) & 1u;
-                    // unconditional table read, masked afterwards: a position past the end contributes no bits
-                    e[v] = (uint32_t)s_enc[c] & (0u - (uint32_t)ok);
-                    n_esc += (uint32_t)__popcll(__ballot(ok && c == 0u));
+                    // the quantiser (same arithmetic as quant_symbol), result as a window index
+                    const float xv = x[cur][u][v];
+                    const float r = __builtin_rintf(xv * q.inv);
+                    float xh = r * q.ebx2;
+                    if constexpr (F16) xh = __half2float(__float2half_rn(xh));
+                    const float d = xv - xh;
+                    const bool ok = (__builtin_fabsf(r) < Rf) & (__builtin_fabsf(d) <= q.eb);  // no short circuit: no branches
+                    w[v] = ok ? (uint32_t)((int)r + ubias) : kEncEscW;
+                    sl[v] = min(w[v], kWinBins);
+                    if (!plain) sl[v] = ((valid[cur][u] >> v) & 1u) ? sl[v] : kWinBins;  // past the end: looked at below, adds nothing
+                    bits += lds_read16(a_len + sl[v] * 2u, 0);
                 }
-                uint32_t w0 = e[0] | (e[1] << 16), w1 = e[2] | (e[3] << 16);
-                // opaque to the optimiser: otherwise it keeps length and codeword of every symbol in registers of
-                // their own instead of the packed words
-                asm volatile("" : "+v"(w0), "+v"(w1));
-                pk[2 * (ib * kBlk + u)] = w0;
-                pk[2 * (ib * kBlk + u) + 1] = w1;
-                bits += ((w0 >> 12) & 0xFu) + (w0 >> 28) + ((w1 >> 12) & 0xFu) + (w1 >> 28);
+                if (!plain && __ballot(max(max(sl[0], sl[1]), max(sl[2], sl[3])) == kWinBins) != 0ull) {
+#pragma clang loop unroll(full)
+                    for (int v = 0; v < 4; ++v)
+                        if (sl[v] == kWinBins && ((valid[cur][u] >> v) & 1u)) {
+                            const uint32_t sym = w[v] == kEncEscW ? 0u : w[v] + win_lo;
+                            bits += (uint32_t)enc_t[sym] >> 12;
+                            my_esc += sym == 0u ? 1u : 0u;
+                        }
+                }
+                uint32_t p4 = sl[0] | (sl[1] << 8) | (sl[2] << 16) | (sl[3] << 24);
+                asm volatile("" : "+v"(p4));  // keep the indices packed
+                ix[ib * kBlk + u] = p4;
             }
             __builtin_amdgcn_sched_barrier(0);
         }
     }
     DLC_ESTAMP(2);
+    const uint32_t n_esc = (plain || !active) ? 0u : wave_sum(my_esc);
     const uint32_t nw = (bits + 31u) >> 5;
     const uint32_t incl = wave_incl_scan(nw, lane);
     const uint32_t lane_off = incl - nw;
     const uint32_t chunk_total = __shfl(incl, 63, 64);
     const uint32_t total = chunk_total + 2u * n_esc;  // 0 for an idle wavefront
 
-    // offsets: one scan record per work-group; the wavefronts' totals are joined through LDS
+    // offsets: one scan record per work-group; the wavefronts' totals are joined through LDS.  The look-back over
+    // the records of earlier work-groups is done by the first wavefront, a step at a time, in between its emit
+    // work: walk 2 writes into an LDS staging buffer, which needs no global offset yet, and the words are copied to
+    // their place (coalesced) once the offset is known.  A work-group with a group too large for the staging
+    // buffer waits for its offset first and emits straight to memory.
+    if (lane == 0) { s_tot[wave] = total; s_ct[wave] = chunk_total; }
+    __syncthreads();
+    const uint32_t wg_total = s_tot[0] + s_tot[1] + s_tot[2] + s_tot[3];
+    const bool staged = max(max(s_ct[0], s_ct[1]), max(s_ct[2], s_ct[3])) <= kStageWords;  // uniform over the work-group
+    LookBack L;
+    lb_init(L, wg);
+    if (wave == 0) lb_publish_aggregate(state, epoch, wg, wg_total, lane);
+    if (!staged) {
+        if (wave == 0) {
+            lb_finish(L, state, epoch, wg, wg_total, lane, ctrl);
+            if (lane == 0) { s_excl = L.excl; s_dead = L.failed ? 1u : 0u; }
+        }
+        __syncthreads();
+    }
+    uint32_t excl = 0;
     bool dead = false;  // nothing may be written to the container
-    if (lane == 0) s_tot[wave] = total;
-    __syncthreads();
-    if (wave == 0) {
-        const uint32_t e = wg_scan(state, epoch, wg, s_tot[0] + s_tot[1] + s_tot[2] + s_tot[3], lane, ctrl, &dead);
-        if (lane == 0) { s_excl = e; s_dead = dead ? 1u : 0u; }
+    if (!staged) {
+        dead = s_dead != 0u;
+        excl = s_excl;
+        for (uint32_t k = 0; k < wave; ++k) excl += s_tot[k];
+        if (F.off_payload + 4ull * ((uint64_t)excl + total) > capacity) {
+            if (active && !dead && lane == 0) { set_status(ctrl, DLC_ECAPACITY); ctrl->abort = 1; }
+            dead = true;
+        }
     }
-    __syncthreads();
-    if (!active) return;
-    dead = s_dead != 0u;
-    uint32_t excl = s_excl;
-    for (uint32_t k = 0; k < wave; ++k) excl += s_tot[k];
     DLC_ESTAMP(3);
-    if (F.off_payload + 4ull * ((uint64_t)excl + total) > capacity) {
-        if (!dead && lane == 0) { set_status(ctrl, DLC_ECAPACITY); ctrl->abort = 1; }
-        dead = true;
+    uint32_t* const stage = s_stage + wave * kStageWords;
+    if (active && !(dead && !staged)) {
+        uint32_t* p = staged ? stage + lane_off : reinterpret_cast<uint32_t*>(out + F.off_payload) + excl + lane_off;
+        uint64_t acc = 0;
+        uint32_t nb = 0;
+        constexpr int kB2 = 4;  // words of indices whose table reads are in flight together
+#pragma clang loop unroll(full)
+        for (int jb = 0; jb < S / 4; jb += kB2) {
+            if (staged && wave == 0 && !L.done && (jb % 8) == 0) {  // uniform: one look-back step per eight words
+                if (L.pending) (void)lb_consume(L, epoch, lane);
+                if (!L.done) lb_issue(L, state, epoch, lane);
+            }
+            uint32_t l[kB2][4], c[kB2][4];
+#pragma clang loop unroll(full)
+            for (int u = 0; u < kB2; ++u) {
+                uint32_t m = ix[jb + u];
+                asm volatile("" : "+v"(m));  // unpack here, not where the word was made
+#pragma clang loop unroll(full)
+                for (int v = 0; v < 4; ++v) {
+                    const uint32_t a = a_len + (((m >> (8 * v)) & 0xFFu) << 1);
+                    l[u][v] = lds_read16(a, 0);
+                    c[u][v] = lds_read16(a, d_code);
+                }
+                if (!plain && __ballot(has_ff_byte(m)) != 0ull) {  // uniform over the wavefront
+#pragma clang loop unroll(full)
+                    for (int v = 0; v < 4; ++v) {
+                        const uint32_t off = lane * kV + (uint32_t)(jb + u) * (kW * kV) + (uint32_t)v;
+                        if (((m >> (8 * v)) & 0xFFu) == 0xFFu && off < rem) {
+                            uint32_t esc;
+                            const uint32_t e = entry_of_element<F16>(gbase, off, q, Rf, (int)g.R, enc_t, &esc);
+                            l[u][v] = e >> 12;
+                            c[u][v] = e & 0xFFFu;
+                        }
+                    }
+                }
+            }
+#pragma clang loop unroll(full)
+            for (int u = 0; u < kB2; ++u)
+#pragma clang loop unroll(full)
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t len = l[u][2 * h] + l[u][2 * h + 1];  // a pair: at most 24 bits
+                    acc = (acc << len) | ((c[u][2 * h] << l[u][2 * h + 1]) | c[u][2 * h + 1]);
+                    nb += len;
+                    if (nb >= 32u) {
+                        nb -= 32u;
+                        *p++ = (uint32_t)(acc >> nb);
+                    }
+                }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (nb) *p = (uint32_t)(acc << (32u - nb));
     }
+    DLC_ESTAMP(4);
+    if (staged) {
+        if (wave == 0) {
+            lb_finish(L, state, epoch, wg, wg_total, lane, ctrl);
+            if (lane == 0) { s_excl = L.excl; s_dead = L.failed ? 1u : 0u; }
+        }
+        __syncthreads();  // also: the staging buffers are complete
+        dead = s_dead != 0u;
+        excl = s_excl;
+        for (uint32_t k = 0; k < wave; ++k) excl += s_tot[k];
+        if (F.off_payload + 4ull * ((uint64_t)excl + total) > capacity) {
+            if (active && !dead && lane == 0) { set_status(ctrl, DLC_ECAPACITY); ctrl->abort = 1; }
+            dead = true;
+        }
+    }
+    if (!active) return;
     if (lane == 0) {
         if (grp == 0) word_start[t] = excl;
         if (grp == g.G - 1) word_end[t] = excl + total;
     }
     if (dead) return;
-    emit_group<S, F16, VEC>(pk, nw, lane_off, excl, chunk_total, n_esc, gid, lane, gbase, gstart, rem, q, Rf, (int)g.R, F,
-                            out);
-    DLC_ESTAMP(4);
+    out[F.off_chunk + (uint64_t)gid * kW + lane] = (uint8_t)nw;
+    if (lane == 0) reinterpret_cast<uint32_t*>(out + F.off_group)[gid] = excl;
+    uint32_t* gw = reinterpret_cast<uint32_t*>(out + F.off_payload) + excl;
+    if (staged)
+        for (uint32_t k = lane; k < chunk_total; k += 64) gw[k] = stage[k];
+    DLC_ESTAMP(5);
+    if (n_esc != 0u)  // uniform over the wavefront
+        emit_escapes<S, F16, VEC>(gw + chunk_total, lane, gbase, gstart, rem, q, Rf, (int)g.R);
 }
 
 void DLC_CAT(launch_encode_, DLC_S)(const Geom& g, const FixedLayout& F, const void* payload, const Ws& w, uint64_t epoch,
                                     uint8_t* out, uint64_t capacity, uint32_t bpt, hipStream_t s) {
     constexpr int S = DLC_S;
     dim3 grid(g.T * bpt), block(256);
-    const size_t sm = (size_t)g.K * 2;
+    const size_t sm = 0;
     const bool f16 = g.dtype == DLC_F16;
 #define DLC_ENC(FF, V)                                                                                          \
-    hipLaunchKernelGGL((k_encode<S, FF, V>), grid, block, sm, s, payload, g, F, w.qp, w.enc, w.ctrl, w.state, epoch, \
+    hipLaunchKernelGGL((k_encode<S, FF, V>), grid, block, sm, s, payload, g, F, w.qp, w.enc, w.tmeta, w.ctrl, w.state, epoch, \
                        out, capacity, bpt, w.word_start, w.word_end)
     if (f16) { if (g.vec) DLC_ENC(true, true); else DLC_ENC(true, false); }
     else { if (g.vec) DLC_ENC(false, true); else DLC_ENC(false, false); }
