@@ -122,6 +122,7 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
     uint8_t* state = take(8 * (size_t)g.NG);
     uint8_t* ws0 = take(4 * (size_t)g.T);
     uint8_t* ws1 = take(4 * (size_t)g.T);
+    uint8_t* plane = take((size_t)g.NG * kW * g.S);
     uint8_t* arrive = take(4 * (size_t)g.T);
     uint8_t* ready = take(8 * (size_t)g.T);
     uint8_t* lut = take(((size_t)g.T << g.LMAX) * 2);
@@ -134,7 +135,7 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
         w->tmeta = (TMeta*)tmeta;
         w->enc = (uint16_t*)enc; w->lens = lens; w->state = (uint64_t*)state;
         w->word_start = (uint32_t*)ws0; w->word_end = (uint32_t*)ws1; w->lut = (uint16_t*)lut;
-        w->arrive = (uint32_t*)arrive; w->ready = (uint64_t*)ready;
+        w->arrive = (uint32_t*)arrive; w->ready = (uint64_t*)ready; w->sym_plane = plane;
         w->dlay = (DecLayout*)dlay; w->dtab = (DecTable*)dtab;
     }
     return off;

@@ -11,15 +11,21 @@
 namespace dlc {
 
 // ------------------------------------------------------------------------------------------------
-// The symbol window of the histogram kernel.  Almost every element of a bell-shaped table falls into a few bins
-// around zero, so the kernel counts window indices: index v in [0, 255) stands for symbol win_lo + v, index 255
-// for everything else (an escape, a symbol outside the window).  Window rows have kWinCopies copies each
-// (copy = lane mod kWinCopies), so a wavefront's 64 updates spread over the LDS banks whatever the symbols are;
-// the rare index 255 is counted exactly, by symbol, in a single-copy array.
+// The symbol window.  Almost every element of a bell-shaped table falls into a few bins around zero, so the
+// streaming kernels work on window indices: index v in [0, 255) stands for symbol win_lo + v, index 255 for
+// everything else (an escape, a symbol outside the window, a position past the end of the table).
+//   - the histogram kernel counts window indices in LDS with kWinCopies copies per row (copy = lane mod
+//     kWinCopies, so a wavefront's 64 updates spread over the banks whatever the symbols are) and hands the
+//     indices on as one byte per element (the symbol plane); the rare index 255 is counted exactly by symbol
+//   - the encode kernel looks window indices up in a 256-entry LDS table and goes back to the element itself
+//     only for index 255
 // ------------------------------------------------------------------------------------------------
 constexpr uint32_t kWinBins = 255;
 constexpr uint32_t kWinCopies = 16;
 __host__ __device__ inline uint32_t win_lo_of(uint32_t R) { return R > kWinBins / 2u ? R - kWinBins / 2u : 0u; }
+// The symbol plane: the window index of every element, one byte each, in element order; a table's part is padded to
+// whole groups (and the last unit of a table is always written whole), so that every group has its 64*S bytes.
+__host__ __device__ inline size_t plane_stride(const Geom& g) { return (size_t)g.G * kW * g.S; }
 // LDS of the histogram kernel in words: window [kWinBins + 1][kWinCopies] | exact counts [K]
 __host__ __device__ inline size_t hist_lds_bytes(uint32_t K) { return (((size_t)(kWinBins + 1) * kWinCopies + K) * 4 + 15) & ~size_t(15); }
 

@@ -66,6 +66,7 @@ struct HistC {
 #endif
 
 constexpr uint32_t kEscW = 0x80000000u;  // no bin has this window index (bins below the window wrap to just under 2^32)
+constexpr uint32_t kPastEnd = 0x80000001u;  // nor this one: a position past the end of the table
 constexpr uint32_t kHistBlk = 4;  // units whose loads are issued back to back
 
 // One block of kHistBlk units of one table; a unit is 256 consecutive elements (one 16-byte load per lane).
@@ -73,7 +74,7 @@ constexpr uint32_t kHistBlk = 4;  // units whose loads are issued back to back
 // wavefront's.  FULL: all kHistBlk units are, and all their elements are inside the table (no masking at all).
 template <bool F16, bool VEC, bool FULL>
 __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, uint32_t n_units, uint32_t lane, const QParam& q,
-                                           float Rf, const HistC& H) {
+                                           float Rf, const HistC& H, uint32_t* plane) {
     float x[kHistBlk][4];
     uint32_t raw[kHistBlk][4];
     uint32_t valid[kHistBlk];
@@ -100,15 +101,17 @@ __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, ui
                 DLC_HIST_COUNT(sl[v] * (kWinCopies * 4u) + H.lanebase);
             } else {
                 if ((valid[u] >> v) & 1u) DLC_HIST_COUNT(sl[v] * (kWinCopies * 4u) + H.lanebase);
-                else sl[v] = 0;
+                else { sl[v] = kWinBins; w[v] = kPastEnd; }
             }
         }
         // index 255 is rare: count those elements exactly, by symbol (0 = escape)
         if (__ballot(max(max(sl[0], sl[1]), max(sl[2], sl[3])) == kWinBins) != 0ull) {
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-                if (sl[v] == kWinBins) lds_count(H.exact + (w[v] == kEscW ? 0u : w[v] + H.win_lo) * 4u);
+                if (sl[v] == kWinBins && w[v] != kPastEnd) lds_count(H.exact + (w[v] == kEscW ? 0u : w[v] + H.win_lo) * 4u);
         }
+        // the window indices of these four elements, for the encode kernel (a unit of this wavefront only)
+        if (FULL || u < n_units) plane[u * kW + lane] = sl[0] | (sl[1] << 8) | (sl[2] << 16) | (sl[3] << 24);
     }
 }
 
@@ -117,7 +120,7 @@ __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, ui
 // A work-group whose units touch several tables handles them one table at a time.
 template <bool F16, bool VEC>
 __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const QParam* qp, uint32_t* hist,
-                                              uint32_t U, uint32_t units_per_wave) {
+                                              uint8_t* sym_plane, uint32_t U, uint32_t units_per_wave) {
     extern __shared__ __align__(16) uint32_t lh[];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t lds0 = (uint32_t)(uintptr_t)lh;
@@ -154,8 +157,9 @@ __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const
                 const uint8_t* base = tab + (size_t)first * g.es;
                 const uint32_t rem = g.n - first;
                 const uint32_t n_units = min(kHistBlk, ue - u);
-                if (n_units == kHistBlk && rem >= kHistBlk * kW * kV) hist_block<F16, VEC, true>(base, rem, n_units, lane, q, Rf, H);
-                else hist_block<F16, VEC, false>(base, rem, n_units, lane, q, Rf, H);
+                uint32_t* plane = reinterpret_cast<uint32_t*>(sym_plane + (size_t)t * plane_stride(g) + first);
+                if (n_units == kHistBlk && rem >= kHistBlk * kW * kV) hist_block<F16, VEC, true>(base, rem, n_units, lane, q, Rf, H, plane);
+                else hist_block<F16, VEC, false>(base, rem, n_units, lane, q, Rf, H, plane);
             }
         }
         __syncthreads();
@@ -306,7 +310,7 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         const size_t sm = hist_lds_bytes(g.K);
         dim3 grid(grid_n), block(256);
         if (prof_on(pl, P_HIST)) prof_begin(prof, P_HIST, s);
-#define DLC_HIST(FF, V) hipLaunchKernelGGL((k_hist<FF, V>), grid, block, sm, s, payload, g, w.qp, w.hist, U, units_per_wave)
+#define DLC_HIST(FF, V) hipLaunchKernelGGL((k_hist<FF, V>), grid, block, sm, s, payload, g, w.qp, w.hist, w.sym_plane, U, units_per_wave)
         if (f16) { if (g.vec) DLC_HIST(true, true); else DLC_HIST(true, false); }
         else { if (g.vec) DLC_HIST(false, true); else DLC_HIST(false, false); }
 #undef DLC_HIST

@@ -18,10 +18,11 @@ namespace dlc {
 
 // ------------------------------------------------------------------------------------------------
 // bit-packed encode.
-//   walk 1: load, quantise to a window index (one byte: 0..254 = symbol win_lo + index, 255 = everything else),
-//           keep the indices in registers four to a word, look up the code length of each in LDS and sum the
-//           chunk's bits.  Index 255 is rare (an escape, a symbol outside the window, a position past the end of
-//           the table): its element is looked at exactly, with the code from the full table; escapes are counted.
+//   walk 1: read the group's window indices from the symbol plane the histogram kernel has written (one byte per
+//           element: 0..254 = symbol win_lo + index, 255 = everything else), keep them in registers four to a
+//           word, look up the code length of each in LDS and sum the chunk's bits.  Index 255 is rare (an escape,
+//           a symbol outside the window, a position past the end of the table): its element is quantised again,
+//           with the code from the full table; escapes are counted.
 //   scan  : chunk word counts inside the wavefront; the wavefronts' totals (chunk words + two words per
 //           escape) are joined per work-group, and the work-groups' totals across the grid by a single-pass
 //           look-back (ordered work-group ids: a work-group only ever waits for work-groups that started
@@ -39,7 +40,6 @@ __device__ __forceinline__ uint32_t lds_read16(uint32_t addr, uint32_t byte_off)
     return *reinterpret_cast<lds_u16*>(reinterpret_cast<__attribute__((address_space(3))) unsigned char*>(addr) + byte_off);
 }
 
-constexpr uint32_t kEncEscW = 0x80000000u;  // no bin has this window index (bins below the window wrap to just under 2^32)
 
 // (length << 12 | codeword) of the element at `off` of the group, quantised again; *is_escape says whether it is one
 template <bool F16>
@@ -59,8 +59,8 @@ __device__ __forceinline__ bool has_ff_byte(uint32_t m) {
 
 template <int S, bool F16, bool VEC>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(S == 256 ? 4 : 5)))
-void k_encode(const void* payload, Geom g, FixedLayout F, const QParam* qp, const uint16_t* enc, const TMeta* tmeta,
-              Ctrl* ctrl, uint64_t* state, uint64_t epoch, uint8_t* out, uint64_t capacity, uint32_t bpt,
+void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout F, const QParam* qp, const uint16_t* enc,
+              const TMeta* tmeta, Ctrl* ctrl, uint64_t* state, uint64_t epoch, uint8_t* out, uint64_t capacity, uint32_t bpt,
               uint32_t* word_start, uint32_t* word_end) {
     __shared__ __align__(16) uint16_t s_len[256], s_code[256];  // by window index; entry 255 is empty
     __shared__ uint32_t s_wg, s_tot[4], s_ct[4], s_excl, s_dead;
@@ -86,7 +86,6 @@ void k_encode(const void* payload, Geom g, FixedLayout F, const QParam* qp, cons
     const uint32_t gid = t * g.G + (active ? grp : 0u);
     const QParam q = qp[t];
     const float Rf = (float)g.R;
-    const int ubias = (int)(g.R - win_lo);
     const uint8_t* tab = static_cast<const uint8_t*>(payload) + (size_t)t * g.n * g.es;
     const uint32_t gstart = grp * (kW * (uint32_t)S);
     const uint8_t* gbase = tab + (size_t)gstart * g.es;
@@ -99,56 +98,47 @@ void k_encode(const void* payload, Geom g, FixedLayout F, const QParam* qp, cons
     DLC_ESTAMP(1);
     uint32_t ix[S / 4];  // window indices, four to a word, in element order
     uint32_t bits = 0, my_esc = 0;
-    constexpr int kBlk = 4;  // turns per block (16 B per lane each); the next block's loads are issued before this one is used
-    constexpr int kNBlk = S / 4 / kBlk;
     if (active) {
-        float x[2][kBlk][4];
-        uint32_t raw[2][kBlk][4];
-        uint32_t valid[2][kBlk];
+        const uint32_t* plane = reinterpret_cast<const uint32_t*>(sym_plane + (size_t)t * plane_stride(g) + gstart);
+        const bool ragged = rem < kW * (uint32_t)S;  // uniform: the table ends inside this group
 #pragma clang loop unroll(full)
-        for (int u = 0; u < kBlk; ++u)
-            valid[0][u] = load4<F16, VEC>(gbase, lane * kV + (uint32_t)u * (kW * kV), rem, x[0][u], raw[0][u]);
+        for (int j = 0; j < S / 4; ++j) ix[j] = plane[(uint32_t)j * kW + lane];
+        constexpr int kB1 = 8;  // words whose table reads are in flight together
 #pragma clang loop unroll(full)
-        for (int ib = 0; ib < kNBlk; ++ib) {
-            const int cur = ib & 1, nxt = cur ^ 1;
-            if (ib + 1 < kNBlk) {
+        for (int jb = 0; jb < S / 4; jb += kB1) {
+            if (ragged) {  // whatever the plane holds past the end of the table does not count
 #pragma clang loop unroll(full)
-                for (int u = 0; u < kBlk; ++u)
-                    valid[nxt][u] = load4<F16, VEC>(gbase, lane * kV + (uint32_t)((ib + 1) * kBlk + u) * (kW * kV), rem, x[nxt][u],
-                                                    raw[nxt][u]);
-            }
-            __builtin_amdgcn_sched_barrier(0);  // the loads above stay above, the work below stays below
+                for (int u = 0; u < kB1; ++u) {
+                    const uint32_t off = lane * kV + (uint32_t)(jb + u) * (kW * kV);
+                    uint32_t m = ix[jb + u];
 #pragma clang loop unroll(full)
-            for (int u = 0; u < kBlk; ++u) {
-                uint32_t w[4], sl[4];
-#pragma clang loop unroll(full)
-                for (int v = 0; v < 4; ++v) {
-                    // the quantiser (same arithmetic as quant_symbol), result as a window index
-                    const float xv = x[cur][u][v];
-                    const float r = __builtin_rintf(xv * q.inv);
-                    float xh = r * q.ebx2;
-                    if constexpr (F16) xh = __half2float(__float2half_rn(xh));
-                    const float d = xv - xh;
-                    const bool ok = (__builtin_fabsf(r) < Rf) & (__builtin_fabsf(d) <= q.eb);  // no short circuit: no branches
-                    w[v] = ok ? (uint32_t)((int)r + ubias) : kEncEscW;
-                    sl[v] = min(w[v], kWinBins);
-                    if (!plain) sl[v] = ((valid[cur][u] >> v) & 1u) ? sl[v] : kWinBins;  // past the end: looked at below, adds nothing
-                    bits += lds_read16(a_len + sl[v] * 2u, 0);
+                    for (int v = 0; v < 4; ++v) m |= (off + (uint32_t)v < rem) ? 0u : (0xFFu << (8 * v));
+                    ix[jb + u] = m;
                 }
-                if (!plain && __ballot(max(max(sl[0], sl[1]), max(sl[2], sl[3])) == kWinBins) != 0ull) {
+            }
+            uint32_t l[kB1][4];
 #pragma clang loop unroll(full)
-                    for (int v = 0; v < 4; ++v)
-                        if (sl[v] == kWinBins && ((valid[cur][u] >> v) & 1u)) {
-                            const uint32_t sym = w[v] == kEncEscW ? 0u : w[v] + win_lo;
-                            bits += (uint32_t)enc_t[sym] >> 12;
-                            my_esc += sym == 0u ? 1u : 0u;
+            for (int u = 0; u < kB1; ++u)
+#pragma clang loop unroll(full)
+                for (int v = 0; v < 4; ++v) l[u][v] = lds_read16(a_len + (((ix[jb + u] >> (8 * v)) & 0xFFu) << 1), 0);
+#pragma clang loop unroll(full)
+            for (int u = 0; u < kB1; ++u) bits += l[u][0] + l[u][1] + l[u][2] + l[u][3];
+            if (!plain) {  // uniform over the wavefront
+#pragma clang loop unroll(full)
+                for (int u = 0; u < kB1; ++u) {
+                    const uint32_t m = ix[jb + u];
+                    if (__ballot(has_ff_byte(m)) == 0ull) continue;
+#pragma clang loop unroll(full)
+                    for (int v = 0; v < 4; ++v) {
+                        const uint32_t off = lane * kV + (uint32_t)(jb + u) * (kW * kV) + (uint32_t)v;
+                        if (((m >> (8 * v)) & 0xFFu) == 0xFFu && off < rem) {
+                            uint32_t esc;
+                            bits += entry_of_element<F16>(gbase, off, q, Rf, (int)g.R, enc_t, &esc) >> 12;
+                            my_esc += esc;
                         }
+                    }
                 }
-                uint32_t p4 = sl[0] | (sl[1] << 8) | (sl[2] << 16) | (sl[3] << 24);
-                asm volatile("" : "+v"(p4));  // keep the indices packed
-                ix[ib * kBlk + u] = p4;
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
     }
     DLC_ESTAMP(2);
@@ -280,7 +270,7 @@ void DLC_CAT(launch_encode_, DLC_S)(const Geom& g, const FixedLayout& F, const v
     const size_t sm = 0;
     const bool f16 = g.dtype == DLC_F16;
 #define DLC_ENC(FF, V)                                                                                          \
-    hipLaunchKernelGGL((k_encode<S, FF, V>), grid, block, sm, s, payload, g, F, w.qp, w.enc, w.tmeta, w.ctrl, w.state, epoch, \
+    hipLaunchKernelGGL((k_encode<S, FF, V>), grid, block, sm, s, payload, w.sym_plane, g, F, w.qp, w.enc, w.tmeta, w.ctrl, w.state, epoch, \
                        out, capacity, bpt, w.word_start, w.word_end)
     if (f16) { if (g.vec) DLC_ENC(true, true); else DLC_ENC(true, false); }
     else { if (g.vec) DLC_ENC(false, true); else DLC_ENC(false, false); }

@@ -203,6 +203,7 @@ struct Ws {
     uint64_t* state = nullptr;     // [NG] look-back records
     uint32_t* word_start = nullptr;  // [T]
     uint32_t* word_end = nullptr;    // [T]
+    uint8_t* sym_plane = nullptr;  // [T][G*64*S] window index of every element (255: see the element itself)
     uint32_t* arrive = nullptr;    // [T] items of a table that have added their counts (fused kernel); zero between calls
     uint64_t* ready = nullptr;     // [T] call counter of the call whose codebook of the table is complete
     uint32_t fused_grid = 0;       // work-groups of the fused kernel; 0 = separate histogram / codebook / encode kernels
