@@ -121,7 +121,8 @@ int dlc_stats(dlc_ctx* ctx, const void* d_payload, const float* h_probe_eb, dlc_
  *                     times the iteration multiplier, clamp, floor; rounded once to fp32 and written to
  *                     h_eb_inout (T, HOST) and, if given, the classes to h_class_out (T, HOST).
  * The bounds are then copied to the context's device memory on `stream` (ordered before later compress calls
- * on that stream).  Every bound must be finite and > 0.
+ * on that stream); a set of bounds equal to the one last copied on the same stream is not copied again.
+ * Every bound must be finite and > 0.
  */
 int dlc_set_error_bounds(dlc_ctx* ctx, const dlc_table_stats* h_stats, const dlc_controller_params* params,
                          const int32_t* h_class_override, int64_t iteration, float* h_eb_inout,
@@ -165,7 +166,8 @@ int dlc_read_codebook(dlc_ctx* ctx, uint8_t* h_len, uint16_t* h_code, void* stre
 
 /*
  * Kernel timing with HIP events on the caller's stream.
- *   dlc_profile_enable  level 0 off; 1 = the two dominant kernels (encode, decode); 2 = every kernel
+ *   dlc_profile_enable  level 0 off; 1 = the dominant kernel of each direction (encode or fused, decode); 2 = every
+ *                       kernel.  Each timed kernel costs two event records per call (a few microseconds).
  *   dlc_profile_read    synchronises, returns the number of kernel slots; for slot i < max_slots:
  *                       names[i] (static string), total_ms[i], launches[i]; then resets the counters
  */

@@ -62,6 +62,9 @@ struct dlc_ctx {
     hipEvent_t pin_ev[kRing] = {};
     bool pin_used[kRing] = {};
     int pin_next = 0;
+    // what the device holds: an unchanged set of bounds on the same stream is not uploaded again
+    std::vector<float> eb_on_device;
+    void* eb_stream = nullptr;
 };
 
 static size_t a256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -259,6 +262,9 @@ extern "C" int dlc_set_error_bounds(dlc_ctx* c, const dlc_table_stats* st, const
     }
     for (uint32_t t = 0; t < T; ++t)
         if (!good_eb(eb[t])) return DLC_EINVAL;
+    if (c->bounds_set && c->eb_stream == stream && c->eb_on_device.size() == T &&
+        memcmp(c->eb_on_device.data(), eb, sizeof(float) * T) == 0)
+        return DLC_OK;
     const int slot = c->pin_next;
     c->pin_next = (slot + 1) % dlc_ctx::kRing;
     if (c->pin_used[slot] && hipEventSynchronize(c->pin_ev[slot]) != hipSuccess) return DLC_EHIP;  // copy 16 calls ago
@@ -269,6 +275,8 @@ extern "C" int dlc_set_error_bounds(dlc_ctx* c, const dlc_table_stats* st, const
     if (hipEventRecord(c->pin_ev[slot], (hipStream_t)stream) != hipSuccess) return DLC_EHIP;
     c->pin_used[slot] = true;
     c->bounds_set = true;
+    c->eb_on_device.assign(eb, eb + T);
+    c->eb_stream = stream;
     return DLC_OK;
 }
 

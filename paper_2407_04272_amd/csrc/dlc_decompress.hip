@@ -155,11 +155,17 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
 // collide whatever word each of them is at) and refills its window from there.  The decode loop then
 // holds no global load, so nothing in it ever waits for memory: the stores just stream out.
 // ------------------------------------------------------------------------------------------------
-constexpr uint32_t kWin = 32;            // staged words per lane
-constexpr uint32_t kDecWaves = 8;        // wavefronts per work-group
+#ifndef DLC_DEC_WIN
+#define DLC_DEC_WIN 32
+#endif
+#ifndef DLC_DEC_WAVES
+#define DLC_DEC_WAVES 8
+#endif
+constexpr uint32_t kWin = DLC_DEC_WIN;            // staged words per lane
+constexpr uint32_t kDecWaves = DLC_DEC_WAVES;        // wavefronts per work-group
 
 template <bool F16, bool VEC>
-__global__ __launch_bounds__(512) void k_decode(Geom g, const uint8_t* comp, const uint16_t* lut, const DecLayout* dlay,
+__global__ __launch_bounds__(64 * DLC_DEC_WAVES) void k_decode(Geom g, const uint8_t* comp, const uint16_t* lut, const DecLayout* dlay,
                                                 const DecTable* dtab, Ctrl* ctrl, void* outp, uint32_t bpt) {
     extern __shared__ __align__(16) uint16_t s_lut[];  // [1 << LMAX] decode table, then kDecWaves staging arrays
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -171,7 +177,7 @@ __global__ __launch_bounds__(512) void k_decode(Geom g, const uint8_t* comp, con
     {
         const uint4* src = reinterpret_cast<const uint4*>(lut + ((size_t)t << g.LMAX));
         uint4* dst = reinterpret_cast<uint4*>(s_lut);
-        for (uint32_t i = tid; i < lut_n / 8; i += 512) dst[i] = src[i];
+        for (uint32_t i = tid; i < lut_n / 8; i += 64 * kDecWaves) dst[i] = src[i];
     }
     __syncthreads();
     const uint32_t grp = b * kDecWaves + wave;

@@ -227,7 +227,7 @@ void prof_begin(void* prof, int slot, hipStream_t s);
 void prof_end(void* prof, int slot, hipStream_t s);
 enum ProfSlot { P_HIST = 0, P_CODEBOOK, P_ENCODE, P_FINALIZE, P_DEC_PREPARE, P_DECODE, P_FUSED, P_NSLOTS };
 inline bool prof_on(int level, int slot) {
-    return level >= 2 || (level == 1 && (slot == P_ENCODE || slot == P_DECODE || slot == P_HIST || slot == P_FUSED));
+    return level >= 2 || (level == 1 && (slot == P_ENCODE || slot == P_DECODE || slot == P_FUSED));
 }
 
 }  // namespace dlc
