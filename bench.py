@@ -152,7 +152,7 @@ def main():
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     # HBM bytes per launch of the dominant kernel, from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
     # profiles/cfg3_hbm_traffic_pmc.txt (they cannot be collected from inside this process); known for this workload only
-    measured_traffic = {"k_encode": 600.1e6, "k_hist": 537.5e6, "k_decode": 598.8e6}
+    measured_traffic = {"k_encode": 235.2e6, "k_hist": 671.8e6, "k_decode": 597.4e6}
     traffic = measured_traffic.get(dom) if (args.workload == "cfg3" and args.chunk_symbols == 256) else None
     result = {
         "metric": "compress+decompress round-trip GB/s of uncompressed fp32 payload, 1 MI355X",
