@@ -14,6 +14,10 @@ extern "C" void dlc_debug_stamps(long long* out) { (void)hipMemcpyFromSymbol(out
 #define DLC_ESTAMP(i)
 #endif
 
+#ifndef DLC_ENC_WAVES  // wavefronts per SIMD the register allocation aims at
+#define DLC_ENC_WAVES(S) ((S) == 128 ? 3 : 4)
+#endif
+
 namespace dlc {
 
 // ------------------------------------------------------------------------------------------------
@@ -58,7 +62,7 @@ __device__ __forceinline__ bool has_ff_byte(uint32_t m) {
 }
 
 template <int S, bool F16, bool VEC>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(S == 256 ? 4 : 5)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DLC_ENC_WAVES(S))))
 void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout F, const QParam* qp, const uint16_t* enc,
               const TMeta* tmeta, Ctrl* ctrl, uint64_t* state, uint64_t epoch, uint8_t* out, uint64_t capacity, uint32_t bpt,
               uint32_t* word_start, uint32_t* word_end) {
