@@ -9,6 +9,10 @@
 
 #include "dlc_internal.h"
 
+#ifndef DLC_STATS_BLOCKS
+#define DLC_STATS_BLOCKS 32
+#endif
+
 namespace dlc {
 
 __device__ __forceinline__ uint64_t mix64(uint64_t z) {
@@ -148,7 +152,9 @@ __global__ __launch_bounds__(256) void k_stats_verify(const void* payload, Geom 
 
 hipError_t launch_stats(const Geom& g, const void* payload, const QParam* probe, const Ws& w, uint32_t M, uint32_t salt,
                         hipStream_t s) {
-    const uint32_t blocks_x = std::min<uint32_t>((g.B + 3) / 4, 2048);
+    // few, long-running work-groups per table: every wavefront ends with atomics on its table's two range words and two
+    // counters, and a wavefront per row made those same-address atomics the whole cost of the reduction
+    const uint32_t blocks_x = std::min<uint32_t>((g.B + 3) / 4, DLC_STATS_BLOCKS);
     const uint32_t rows_grid = blocks_x * 4;
     dim3 grid(blocks_x, g.T), block(256);
     if (g.dtype == DLC_F16) {
