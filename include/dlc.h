@@ -23,6 +23,26 @@
  *  - a context is not thread-safe; calls that share a context must be issued
  *    on one stream (or be ordered by the caller).
  */
+/*
+ * The container (little-endian; what dlc_compress writes and dlc_decompress reads)
+ *
+ *   header, 128 bytes   u32 magic "DLC2", version 2, dtype, T, B, D, R, S, LMAX, 64 (chunks per group), 4 (symbols a
+ *                       chunk takes per turn), NG (groups in all);  then from byte 48, u64: escapes in all, payload words
+ *                       in all, byte offsets of the group table, the chunk table, the payload, the code-length blocks, and
+ *                       the total size;  24 zero bytes
+ *   directory           T entries of 56 bytes: u32 bound (fp32 bits), used symbols, lowest and highest used symbol, escapes,
+ *                       groups;  u64 byte offset of the table's code lengths, 0, first payload word, payload words
+ *   group table         u32 first payload word of every group               (each section starts on a 16-byte boundary)
+ *   chunk table         u8 words of every chunk, 64 per group
+ *   payload             group after group: its 64 chunks (codewords most significant bit first in 32-bit words, each chunk
+ *                       padded to a word), then its escape records (u32 element index in the table, u32 raw bits), by index
+ *   code lengths        per table u8 length of every symbol from the lowest to the highest used one, padded to 4 bytes;
+ *                       codewords are canonical: ordered by (length, symbol)
+ *
+ * A table's B*D elements are cut into groups of 64*S; chunk l of group g holds the elements
+ * g*64*S + j*256 + l*4 + v  (j < S/4, v < 4) in that order.  Symbol 0 is the escape, symbol c > 0 stands for the value
+ * (c - R) * 2 * bound.
+ */
 #ifndef DLC_H
 #define DLC_H
 
