@@ -44,7 +44,10 @@ __device__ __forceinline__ float elem_at(const uint8_t* tab, uint32_t i, uint32_
     }
 }
 
-// pass 1: one wavefront per row (grid-stride over the rows of a table)
+constexpr uint32_t kRowsPer = 4;  // rows a wavefront works on at a time: their loads and their set operations overlap
+
+// pass 1: a wavefront takes kRowsPer rows at a time (grid-stride over the rows of a table); all lanes hash the
+// rows' elements, then lane 2k+s puts row k into set s (0: raw rows, 1: quantised rows)
 template <bool F16>
 __global__ __launch_bounds__(256) void k_stats_hash(const void* payload, Geom g, const QParam* probe, uint32_t M,
                                                     uint32_t salt, uint64_t* keys, uint32_t* owner, uint64_t* rowhash,
@@ -56,26 +59,39 @@ __global__ __launch_bounds__(256) void k_stats_hash(const void* payload, Geom g,
     const float Rf = (float)g.R;
     const uint8_t* tab = static_cast<const uint8_t*>(payload) + (size_t)t * g.n * g.es;
     uint32_t mn = 0xFFFFFFFFu, mx = 0u;
-    for (uint32_t row = wave_global; row < g.B; row += rows_grid) {
-        uint64_t hr = 0, hq = 0;
+    for (uint32_t row0 = wave_global * kRowsPer; row0 < g.B; row0 += rows_grid * kRowsPer) {
+        uint64_t hr[kRowsPer], hq[kRowsPer];
+#pragma unroll
+        for (uint32_t k = 0; k < kRowsPer; ++k) { hr[k] = 0; hq[k] = 0; }
         for (uint32_t e = lane; e < g.D; e += 64) {
-            uint32_t raw;
-            const float x = elem_at<F16>(tab, row * g.D + e, raw);
-            if (__builtin_fabsf(x) < __builtin_inff()) {
-                const uint32_t o = ord_enc(x);
-                mn = min(mn, o);
-                mx = max(mx, o);
-            }
-            const uint32_t c = quant_symbol<F16>(x, q, Rf, (int)g.R);
+            uint32_t raw[kRowsPer];
+            float x[kRowsPer];
+#pragma unroll
+            for (uint32_t k = 0; k < kRowsPer; ++k)  // a row past the end reads the last row instead; it is not used
+                x[k] = elem_at<F16>(tab, min(row0 + k, g.B - 1u) * g.D + e, raw[k]);
             const uint64_t pos = (uint64_t)(e + 1u) * 0x9E3779B97F4A7C15ull + salt;
-            hr += mix64((uint64_t)raw + pos);
-            hq += mix64((uint64_t)c + pos);
+#pragma unroll
+            for (uint32_t k = 0; k < kRowsPer; ++k) {
+                if (row0 + k < g.B && __builtin_fabsf(x[k]) < __builtin_inff()) {
+                    const uint32_t o = ord_enc(x[k]);
+                    mn = min(mn, o);
+                    mx = max(mx, o);
+                }
+                const uint32_t c = quant_symbol<F16>(x[k], q, Rf, (int)g.R);
+                hr[k] += mix64((uint64_t)raw[k] + pos);
+                hq[k] += mix64((uint64_t)c + pos);
+            }
         }
-        hr = mix64(wave_sum64(hr)) | 1ull;  // never 0: 0 marks an empty slot
-        hq = mix64(wave_sum64(hq)) | 1ull;
-        if (lane < 2) {
-            const uint64_t hsh = lane == 0 ? hr : hq;
-            const size_t set = (size_t)lane * g.T + t;
+        uint64_t hsh = 0;
+#pragma unroll
+        for (uint32_t k = 0; k < kRowsPer; ++k) {
+            const uint64_t a = mix64(wave_sum64(hr[k])) | 1ull;  // never 0: 0 marks an empty slot
+            const uint64_t b = mix64(wave_sum64(hq[k])) | 1ull;
+            if ((lane >> 1) == k) hsh = (lane & 1u) ? b : a;
+        }
+        const uint32_t row = row0 + (lane >> 1);
+        if (lane < 2 * kRowsPer && row < g.B) {
+            const size_t set = (size_t)(lane & 1u) * g.T + t;
             rowhash[set * g.B + row] = hsh;
             uint64_t* kk = keys + set * M;
             uint32_t* oo = owner + set * M;
@@ -101,7 +117,8 @@ __global__ __launch_bounds__(256) void k_stats_hash(const void* payload, Geom g,
     }
 }
 
-// pass 2: a row is distinct iff it owns its slot; every other row must equal the owner
+// pass 2: a row is distinct iff it owns its slot; every other row must equal the owner.  Lane 2k+s looks row k up
+// in set s; the comparisons of all rows that need one are then done together (their loads overlap).
 template <bool F16>
 __global__ __launch_bounds__(256) void k_stats_verify(const void* payload, Geom g, const QParam* probe, uint32_t M,
                                                       const uint64_t* keys, const uint32_t* owner,
@@ -114,35 +131,53 @@ __global__ __launch_bounds__(256) void k_stats_verify(const void* payload, Geom 
     const float Rf = (float)g.R;
     const uint8_t* tab = static_cast<const uint8_t*>(payload) + (size_t)t * g.n * g.es;
     uint32_t n_raw = 0, n_quant = 0;
-    for (uint32_t row = wave_global; row < g.B; row += rows_grid) {
-        for (uint32_t set_i = 0; set_i < 2; ++set_i) {
-            const size_t set = (size_t)set_i * g.T + t;
-            const uint64_t hsh = rowhash[set * g.B + row];
-            const uint64_t* kk = keys + set * M;
-            uint32_t pos = (uint32_t)(hsh >> 20) & (M - 1u);
-            uint32_t own = 0xFFFFFFFFu;
-            for (uint32_t probe_n = 0; probe_n < M; ++probe_n) {
-                if (kk[pos] == hsh) { own = owner[set * M + pos]; break; }
-                pos = (pos + 1u) & (M - 1u);
+    for (uint32_t row0 = wave_global * kRowsPer; row0 < g.B; row0 += rows_grid * kRowsPer) {
+        // look-ups
+        uint32_t own = 0xFFFFFFFFu;
+        {
+            const uint32_t row = row0 + (lane >> 1);
+            if (lane < 2 * kRowsPer && row < g.B) {
+                const size_t set = (size_t)(lane & 1u) * g.T + t;
+                const uint64_t hsh = rowhash[set * g.B + row];
+                const uint64_t* kk = keys + set * M;
+                uint32_t pos = (uint32_t)(hsh >> 20) & (M - 1u);
+                for (uint32_t probe_n = 0; probe_n < M; ++probe_n) {
+                    if (kk[pos] == hsh) { own = owner[set * M + pos]; break; }
+                    pos = (pos + 1u) & (M - 1u);
+                }
             }
-            if (own == row) {
-                if (set_i == 0) ++n_raw; else ++n_quant;
-                continue;
-            }
-            if (own >= g.B) {  // the set was too small or was not filled: an internal error
-                if (lane == 0) set_status(ctrl, DLC_ESTATE);
-                continue;
-            }
-            bool differ = false;
-            for (uint32_t e = lane; e < g.D; e += 64) {
-                uint32_t ra, rb;
-                const float xa = elem_at<F16>(tab, row * g.D + e, ra);
-                const float xb = elem_at<F16>(tab, own * g.D + e, rb);
-                if (set_i == 0) differ |= ra != rb;
-                else differ |= quant_symbol<F16>(xa, q, Rf, (int)g.R) != quant_symbol<F16>(xb, q, Rf, (int)g.R);
-            }
-            if (__ballot(differ) != 0ull && lane == 0) atomicAdd(&ctrl->collide, 1u);
         }
+        uint32_t ownk[2 * kRowsPer];
+        bool need[2 * kRowsPer];
+#pragma unroll
+        for (uint32_t c = 0; c < 2 * kRowsPer; ++c) {
+            ownk[c] = __shfl(own, c, 64);
+            const uint32_t row = row0 + (c >> 1);
+            need[c] = false;
+            if (row < g.B) {
+                if (ownk[c] == row) {
+                    if (c & 1u) ++n_quant; else ++n_raw;
+                } else if (ownk[c] >= g.B) {  // the set was too small or was not filled: an internal error
+                    if (lane == 0) set_status(ctrl, DLC_ESTATE);
+                } else {
+                    need[c] = true;
+                }
+            }
+        }
+        // comparisons (uniform conditions: every lane holds the same ownk[] and need[])
+        bool differ = false;
+        for (uint32_t e = lane; e < g.D; e += 64) {
+#pragma unroll
+            for (uint32_t c = 0; c < 2 * kRowsPer; ++c) {
+                if (!need[c]) continue;
+                uint32_t ra, rb;
+                const float xa = elem_at<F16>(tab, (row0 + (c >> 1)) * g.D + e, ra);
+                const float xb = elem_at<F16>(tab, ownk[c] * g.D + e, rb);
+                if (c & 1u) differ |= quant_symbol<F16>(xa, q, Rf, (int)g.R) != quant_symbol<F16>(xb, q, Rf, (int)g.R);
+                else differ |= ra != rb;
+            }
+        }
+        if (__ballot(differ) != 0ull && lane == 0) atomicAdd(&ctrl->collide, 1u);
     }
     if (lane == 0) {
         if (n_raw) atomicAdd(&unique[2 * t], n_raw);
@@ -154,7 +189,7 @@ hipError_t launch_stats(const Geom& g, const void* payload, const QParam* probe,
                         hipStream_t s) {
     // few, long-running work-groups per table: every wavefront ends with atomics on its table's two range words and two
     // counters, and a wavefront per row made those same-address atomics the whole cost of the reduction
-    const uint32_t blocks_x = std::min<uint32_t>((g.B + 3) / 4, DLC_STATS_BLOCKS);
+    const uint32_t blocks_x = std::min<uint32_t>((g.B + 4 * kRowsPer - 1) / (4 * kRowsPer), DLC_STATS_BLOCKS);
     const uint32_t rows_grid = blocks_x * 4;
     dim3 grid(blocks_x, g.T), block(256);
     if (g.dtype == DLC_F16) {
