@@ -74,6 +74,8 @@ def lib():
         L.orc_compress_bound.argtypes = [C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int]
         L.orc_compress.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int,
                                    C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.orc_compress_carried.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int,
+                                           C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
         L.orc_decompress.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p]
         _lib = L
     return _lib
@@ -180,9 +182,13 @@ class Compressed:
     data: np.ndarray      # u8, exactly total_bytes long
     sizes: np.ndarray     # u64[1+T]: total, then bytes attributable to each table
     rc: int
+    hist: np.ndarray | None = None   # u64[T, K] symbol counts of this payload (compress(..., want_hist=True))
 
 
-def compress(payload: np.ndarray, eb, R: int = 512, S: int = 256, LMAX: int = 12, capacity: int | None = None):
+def compress(payload: np.ndarray, eb, R: int = 512, S: int = 256, LMAX: int = 12, capacity: int | None = None,
+             carry_hist: np.ndarray | None = None, want_hist: bool = False):
+    """carry_hist (u64[T, 2R]): code with the codebook of these counts (an earlier payload's) instead of the payload's
+    own; want_hist: also return this payload's counts, which is what the next call is given."""
     payload = np.ascontiguousarray(payload)
     T, B, D = payload.shape
     dt = _dtype_code(payload)
@@ -192,9 +198,20 @@ def compress(payload: np.ndarray, eb, R: int = 512, S: int = 256, LMAX: int = 12
         raise ValueError("bad geometry")
     out = np.zeros(max(cap, 1), np.uint8)
     sizes = np.zeros(1 + T, np.uint64)
-    rc = lib().orc_compress(_ptr(payload), dt, T, B, D, R, S, LMAX, _ptr(ebs), _ptr(out), cap, _ptr(sizes))
+    if carry_hist is None and not want_hist:
+        rc = lib().orc_compress(_ptr(payload), dt, T, B, D, R, S, LMAX, _ptr(ebs), _ptr(out), cap, _ptr(sizes))
+        hist = None
+    else:
+        ch = None
+        if carry_hist is not None:
+            ch = np.ascontiguousarray(carry_hist, np.uint64)
+            if ch.shape != (T, 2 * R):
+                raise ValueError("carry_hist must be [T, 2R]")
+        hist = np.zeros((T, 2 * R), np.uint64) if want_hist else None
+        rc = lib().orc_compress_carried(_ptr(payload), dt, T, B, D, R, S, LMAX, _ptr(ebs), _ptr(out), cap, _ptr(sizes),
+                                        _ptr(ch) if ch is not None else None, _ptr(hist) if hist is not None else None)
     n = int(sizes[0]) if rc == OK else 0
-    return Compressed(out[:n].copy(), sizes, rc)
+    return Compressed(out[:n].copy(), sizes, rc, hist)
 
 
 def decompress(data: np.ndarray, shape, dtype, want_symbols: bool = False):

@@ -600,8 +600,20 @@ static void free_table_work(orc_table_work* w, int T) {
     free(w);
 }
 
-int orc_compress(const void* payload, int dtype, int T, int64_t B, int64_t D, int R, int S, int LMAX,
-                 const float* eb, uint8_t* out, size_t capacity, uint64_t* out_bytes /* 1 + T */) {
+/*
+ * carry_hist (optional, T*K counts): code table t with the Huffman codebook of carry_hist[t] -- the symbol counts of
+ * an EARLIER payload -- instead of its own (the value distributions change little between training iterations,
+ * Section IV-E, so the previous iteration's codebook fits the next one).  Readings, the paper being silent:
+ *   - the count of symbol 0 (the escape) is raised by one before the codebook is built, so that an escape can always
+ *     be coded;
+ *   - a symbol the carried counts do not contain is stored as an escape (symbol 0 in the stream plus a record with
+ *     the raw value), so the bound holds for any payload.
+ * hist_out (optional, T*K): the symbol counts of THIS payload (before that substitution), i.e. what the next call
+ * would be given as carry_hist.
+ */
+static int compress_impl(const void* payload, int dtype, int T, int64_t B, int64_t D, int R, int S, int LMAX,
+                         const float* eb, uint8_t* out, size_t capacity, uint64_t* out_bytes /* 1 + T */,
+                         const uint64_t* carry_hist, uint64_t* hist_out) {
     int rc = check_geometry(dtype, T, B, D, R, S, LMAX);
     if (rc != ORC_OK) return rc;
     if (!payload || !eb || !out || !out_bytes) return ORC_EINVAL;
@@ -628,6 +640,22 @@ int orc_compress(const void* payload, int dtype, int T, int64_t B, int64_t D, in
         const uint8_t* tab = (const uint8_t*)payload + (size_t)t * n * es;
         /* quantise, collect escapes in index order */
         orc_quantize(tab, dtype, n, eb[t], R, sym, NULL);
+        /* histogram and codebook */
+        orc_histogram(sym, n, K, hist);
+        if (hist_out) memcpy(hist_out + (size_t)t * K, hist, sizeof(uint64_t) * (size_t)K);
+        if (carry_hist) {
+            memcpy(hist, carry_hist + (size_t)t * K, sizeof(uint64_t) * (size_t)K);
+            hist[0] += 1;
+            for (size_t i = 0; i < n; ++i)
+                if (hist[sym[i]] == 0) sym[i] = 0; /* no code for it: an escape */
+        }
+        orc_codebook(hist, K, LMAX, w->len, w->code, &w->n_used, NULL);
+        w->sym_lo = -1;
+        for (int k = 0; k < K; ++k)
+            if (hist[k]) {
+                if (w->sym_lo < 0) w->sym_lo = k;
+                w->sym_hi = k;
+            }
         size_t n_out = 0;
         for (size_t i = 0; i < n; ++i) n_out += sym[i] == 0;
         w->n_outliers = (uint32_t)n_out;
@@ -639,15 +667,6 @@ int orc_compress(const void* payload, int dtype, int T, int64_t B, int64_t D, in
                 w->out_idx[o] = (uint32_t)i;
                 w->out_raw[o] = load_raw(tab, dtype, i);
                 o++;
-            }
-        /* histogram and codebook */
-        orc_histogram(sym, n, K, hist);
-        orc_codebook(hist, K, LMAX, w->len, w->code, &w->n_used, NULL);
-        w->sym_lo = -1;
-        for (int k = 0; k < K; ++k)
-            if (hist[k]) {
-                if (w->sym_lo < 0) w->sym_lo = k;
-                w->sym_hi = k;
             }
         /* chunk sizes and group offsets: a group = its chunks' words, then two words per escape */
         w->chunk_words = (uint8_t*)calloc(G * ORC_W, 1);
@@ -779,6 +798,17 @@ int orc_compress(const void* payload, int dtype, int T, int64_t B, int64_t D, in
     free(cb_off);
     free_table_work(work, T);
     return ORC_OK;
+}
+
+int orc_compress(const void* payload, int dtype, int T, int64_t B, int64_t D, int R, int S, int LMAX,
+                 const float* eb, uint8_t* out, size_t capacity, uint64_t* out_bytes /* 1 + T */) {
+    return compress_impl(payload, dtype, T, B, D, R, S, LMAX, eb, out, capacity, out_bytes, NULL, NULL);
+}
+
+int orc_compress_carried(const void* payload, int dtype, int T, int64_t B, int64_t D, int R, int S, int LMAX,
+                         const float* eb, uint8_t* out, size_t capacity, uint64_t* out_bytes /* 1 + T */,
+                         const uint64_t* carry_hist /* T*K or NULL */, uint64_t* hist_out /* T*K or NULL */) {
+    return compress_impl(payload, dtype, T, B, D, R, S, LMAX, eb, out, capacity, out_bytes, carry_hist, hist_out);
 }
 
 /* ------------------------------------------------------------------ */
