@@ -82,7 +82,19 @@ typedef struct {
 /* dlc_config.flags: compress with the fused persistent kernel, which reads the payload once and builds each
  * table's codebook inside the kernel, instead of the separate histogram, codebook and encode kernels.  Both
  * produce the same bytes; on MI355X the separate kernels are the faster choice (the default). */
-enum { DLC_FLAG_FUSED = 1 };
+enum { DLC_FLAG_FUSED = 1, DLC_FLAG_CARRY_CODEBOOK = 2 };
+
+/* DLC_FLAG_CARRY_CODEBOOK: dlc_compress codes each table with the Huffman codebook built from the payload of the
+ * PREVIOUS dlc_compress call on this context instead of from its own payload (Section IV-E: the value distributions
+ * of the lookups change little from iteration to iteration).  The payload is then read once instead of twice.
+ *   - The first call on a context, and the first call after dlc_set_error_bounds changed a bound, build their
+ *     codebook from their own payload as without the flag (same bytes as without the flag).
+ *   - A carried codebook is the Huffman codebook of the previous call's symbol counts with the count of symbol 0
+ *     (the escape) raised by one, so that an escape can always be coded.
+ *   - A symbol the carried codebook has no code for is stored as an escape (raw value), so the error bound holds
+ *     for any payload; a payload unlike the previous one costs compression ratio, never correctness.
+ *   - The container format is unchanged; dlc_decompress needs no flag.
+ * Cannot be combined with DLC_FLAG_FUSED. */
 
 /* Per-table statistics of a sampled batch: what Eq. 1 needs, plus the value range. */
 typedef struct {

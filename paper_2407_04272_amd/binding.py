@@ -93,6 +93,7 @@ def _check(status, where):
 
 
 FLAG_FUSED = 1
+FLAG_CARRY_CODEBOOK = 2
 
 
 def make_config(dtype, T, B, D, radius=512, chunk_symbols=256, max_code_len=12, flags=0) -> Config:

@@ -42,7 +42,7 @@ void prof_end(void* p, int slot, hipStream_t s) {
 }
 
 static const char* kSlotNames[P_NSLOTS] = {"k_hist", "k_codebook", "k_encode", "k_finalize",
-                                           "k_dec_prepare", "k_decode", "k_fused"};
+                                           "k_dec_prepare", "k_decode", "k_fused", "k_encode_carry"};
 }  // namespace dlc
 
 using namespace dlc;
@@ -65,6 +65,8 @@ struct dlc_ctx {
     // what the device holds: an unchanged set of bounds on the same stream is not uploaded again
     std::vector<float> eb_on_device;
     void* eb_stream = nullptr;
+    // single-pass path: the device holds a codebook built from the previous call's payload under the current bounds
+    bool carry_ready = false;
 };
 
 static size_t a256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -82,7 +84,8 @@ static bool make_geom(const dlc_config* c, Geom* g) {
     if (L < 1 || L > kLmaxLimit || (1 << L) < 2 * R) return false;
     const int S = c->chunk_symbols;
     if (S != 64 && S != 128 && S != 256) return false;
-    if (c->flags & ~(int32_t)DLC_FLAG_FUSED) return false;
+    if (c->flags & ~(int32_t)(DLC_FLAG_FUSED | DLC_FLAG_CARRY_CODEBOOK)) return false;
+    if ((c->flags & DLC_FLAG_FUSED) && (c->flags & DLC_FLAG_CARRY_CODEBOOK)) return false;
     const uint64_t GS = (uint64_t)kW * S;
     const uint64_t G = (n + GS - 1) / GS;
     const uint64_t NG = G * (uint64_t)c->num_tables;
@@ -128,6 +131,7 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
     uint8_t* plane = take((size_t)g.NG * kW * g.S);
     uint8_t* arrive = take(4 * (size_t)g.T);
     uint8_t* ready = take(8 * (size_t)g.T);
+    uint8_t* escc = take(4 * (size_t)g.T);
     uint8_t* lut = take(((size_t)g.T << g.LMAX) * 2);
     uint8_t* dlay = take(sizeof(DecLayout));
     uint8_t* dtab = take(sizeof(DecTable) * g.T);
@@ -139,6 +143,7 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
         w->enc = (uint16_t*)enc; w->lens = lens; w->state = (uint64_t*)state;
         w->word_start = (uint32_t*)ws0; w->word_end = (uint32_t*)ws1; w->lut = (uint16_t*)lut;
         w->arrive = (uint32_t*)arrive; w->ready = (uint64_t*)ready; w->sym_plane = plane;
+        w->esc_count = (uint32_t*)escc;
         w->dlay = (DecLayout*)dlay; w->dtab = (DecTable*)dtab;
     }
     return off;
@@ -165,6 +170,7 @@ extern "C" int dlc_create(dlc_ctx** out, const dlc_config* cfg) {
     if (hipMalloc((void**)&base, bytes) != hipSuccess) { (void)hipGetLastError(); delete c; return DLC_ENOMEM; }
     if (hipMemset(base, 0, bytes) != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }
     carve(g, base, &c->ws);
+    c->ws.carry = (cfg->flags & DLC_FLAG_CARRY_CODEBOOK) ? 1u : 0u;
     if (compress_set_attributes() != hipSuccess || decompress_set_attributes() != hipSuccess ||
         ((cfg->flags & DLC_FLAG_FUSED) && fused_plan(g, &c->ws.fused_grid) != hipSuccess)) {
         (void)hipGetLastError();
@@ -276,6 +282,7 @@ extern "C" int dlc_set_error_bounds(dlc_ctx* c, const dlc_table_stats* st, const
     c->pin_used[slot] = true;
     c->bounds_set = true;
     c->eb_on_device.assign(eb, eb + T);
+    c->carry_ready = false;  // new bounds, new symbol distribution: the next call builds its own codebook
     c->eb_stream = stream;
     return DLC_OK;
 }
@@ -293,8 +300,9 @@ extern "C" int dlc_compress(dlc_ctx* c, const void* d_payload, void* d_out, size
         if (hipMemsetAsync(c->ws.state, 0, 8 * (size_t)c->g.NG, (hipStream_t)stream) != hipSuccess) return DLC_EHIP;
         c->epoch = 1;
     }
-    hipError_t e = launch_compress(c->g, d_payload, (uint8_t*)d_out, cap, d_out_bytes, c->ws, c->epoch, c->prof.level,
-                                   &c->prof, (hipStream_t)stream);
+    hipError_t e = launch_compress(c->g, d_payload, (uint8_t*)d_out, cap, d_out_bytes, c->ws, c->epoch, c->carry_ready,
+                                   c->prof.level, &c->prof, (hipStream_t)stream);
+    c->carry_ready = e == hipSuccess && c->ws.carry != 0;
     return e == hipSuccess ? DLC_OK : DLC_EHIP;
 }
 

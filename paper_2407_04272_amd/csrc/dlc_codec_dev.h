@@ -144,7 +144,7 @@ __device__ __forceinline__ uint32_t wave_huffman_lengths(uint32_t n, uint32_t LM
 // seen the caller's completion flag.
 __device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, uint32_t* hist_view_t, uint16_t* enc_t,
                                                uint8_t* lens_t, TMeta* tmeta_t, unsigned char* smem, CodebookShared& sh,
-                                               uint32_t tid) {
+                                               uint32_t tid, uint32_t carry = 0) {
     const uint32_t K = g.K;
     uint64_t* key = reinterpret_cast<uint64_t*>(smem);        // [K] sort keys: count << 16 | symbol
     uint32_t* cnt = reinterpret_cast<uint32_t*>(key + K);      // [K] counts
@@ -164,11 +164,14 @@ __device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, 
     for (uint32_t k = k0; k < k1; ++k) {
         // the counts were added by device-scope atomics of other work-groups, possibly on other dies
         const uint32_t h = __hip_atomic_load(&hist_t[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        cnt[k] = h;
-        hist_view_t[k] = h;
-        __hip_atomic_store(&hist_t[k], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // a codebook that is carried to the next call always has a code for the escape symbol
+        cnt[k] = h + ((carry != 0u && k == 0u) ? 1u : 0u);
+        if (hist_t != hist_view_t) {  // (the copy itself can be the source: it is left as it is)
+            hist_view_t[k] = h;
+            __hip_atomic_store(&hist_t[k], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         len_s[k] = 0;
-        mine += h != 0;
+        mine += cnt[k] != 0;
     }
     if (tid == 0) { sh.maxlen = 0; sh.codes_done = 0; }
     if (tid < kLmaxLimit + 2) sh.cl[tid] = 0;

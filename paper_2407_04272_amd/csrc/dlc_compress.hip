@@ -16,6 +16,12 @@ void launch_encode_128(const Geom& g, const FixedLayout& F, const void* payload,
                        uint64_t capacity, uint32_t bpt, hipStream_t s);
 void launch_encode_256(const Geom& g, const FixedLayout& F, const void* payload, const Ws& w, uint64_t epoch, uint8_t* out,
                        uint64_t capacity, uint32_t bpt, hipStream_t s);
+void launch_encode_carry_64(const Geom& g, const FixedLayout& F, const void* payload, const Ws& w, uint64_t epoch, uint8_t* out,
+                            uint64_t capacity, uint32_t bpt, hipStream_t s);
+void launch_encode_carry_128(const Geom& g, const FixedLayout& F, const void* payload, const Ws& w, uint64_t epoch, uint8_t* out,
+                             uint64_t capacity, uint32_t bpt, hipStream_t s);
+void launch_encode_carry_256(const Geom& g, const FixedLayout& F, const void* payload, const Ws& w, uint64_t epoch, uint8_t* out,
+                             uint64_t capacity, uint32_t bpt, hipStream_t s);
 hipError_t launch_fused(const Geom& g, const FixedLayout& F, const void* payload, const Ws& w, uint64_t epoch, uint8_t* out,
                         uint64_t capacity, hipStream_t s);
 
@@ -179,13 +185,14 @@ __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const
     }
 }
 
+// carry != 0: the codebook is for the next call (the escape symbol gets a code whether it occurred or not)
 __global__ __launch_bounds__(256) void k_codebook(Geom g, uint32_t* hist, uint32_t* hist_view, uint16_t* enc,
-                                                  uint8_t* lens, TMeta* tmeta) {
+                                                  uint8_t* lens, TMeta* tmeta, uint32_t carry) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ CodebookShared sh;
     const uint32_t t = blockIdx.x;
     codebook_build(g, hist + (size_t)t * g.K, hist_view + (size_t)t * g.K, enc + (size_t)t * g.K,
-                   lens + (size_t)t * g.K, tmeta + t, smem, sh, threadIdx.x);
+                   lens + (size_t)t * g.K, tmeta + t, smem, sh, threadIdx.x, carry);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -197,7 +204,7 @@ __device__ __forceinline__ uint64_t a16(uint64_t x) { return (x + 15ull) & ~15ul
 __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const TMeta* tmeta, const uint8_t* __restrict__ lens,
                                                    const QParam* qp, Ctrl* ctrl, const uint32_t* word_start,
                                                    const uint32_t* word_end, uint8_t* __restrict__ out, uint64_t capacity,
-                                                   uint64_t* out_bytes) {
+                                                   uint64_t* out_bytes, uint32_t* esc_count) {
     __shared__ uint32_t s_red[17];
     __shared__ uint32_t s_abort;
     __shared__ uint32_t s_cb[1025];   // start of each table's block, relative to the pass's first block
@@ -213,6 +220,10 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
         uint32_t cb = 0, no = 0, nl = 0;
         if (t < g.T) {
             m = tmeta[t];
+            if (esc_count) {  // single-pass path: the codebook is older than the payload, the escapes were counted by the encode kernel
+                m.n_outliers = esc_count[t];
+                esc_count[t] = 0;
+            }
             if (m.sym_lo > m.sym_hi || m.sym_hi >= g.K) { m.sym_lo = 0; m.sym_hi = 0; }  // never index outside lens[]
             nl = m.sym_hi - m.sym_lo + 1u;
             cb = (nl + 3u) & ~3u;
@@ -285,9 +296,29 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
 }
 
 hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uint64_t capacity, uint64_t* out_bytes,
-                           const Ws& w, uint64_t epoch, int pl, void* prof, hipStream_t s) {
+                           const Ws& w, uint64_t epoch, bool carry_ready, int pl, void* prof, hipStream_t s) {
     const bool f16 = g.dtype == DLC_F16;
     const FixedLayout F = fixed_layout(g);
+    if (w.carry != 0 && carry_ready) {
+        // single pass: encode with the codebook of the previous call, then build the next one from this call's counts
+        const uint32_t bpt = (g.G + 3) / 4;
+        if (prof_on(pl, P_CARRY)) prof_begin(prof, P_CARRY, s);
+        switch (g.S) {
+            case 64: launch_encode_carry_64(g, F, payload, w, epoch, out, capacity, bpt, s); break;
+            case 128: launch_encode_carry_128(g, F, payload, w, epoch, out, capacity, bpt, s); break;
+            default: launch_encode_carry_256(g, F, payload, w, epoch, out, capacity, bpt, s); break;
+        }
+        if (prof_on(pl, P_CARRY)) prof_end(prof, P_CARRY, s);
+        if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
+        hipLaunchKernelGGL(k_finalize, dim3(1), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
+                           w.word_end, out, capacity, out_bytes, w.esc_count);
+        if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
+        if (prof_on(pl, P_CODEBOOK)) prof_begin(prof, P_CODEBOOK, s);
+        hipLaunchKernelGGL(k_codebook, dim3(g.T), dim3(256), codebook_smem(g.K), s, g, w.hist, w.hist_view, w.enc, w.lens,
+                           w.tmeta, 1u);
+        if (prof_on(pl, P_CODEBOOK)) prof_end(prof, P_CODEBOOK, s);
+        return hipGetLastError();
+    }
     if (w.fused_grid != 0) {
         if (prof_on(pl, P_FUSED)) prof_begin(prof, P_FUSED, s);
         hipError_t e = launch_fused(g, F, payload, w, epoch, out, capacity, s);
@@ -295,7 +326,7 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         if (e != hipSuccess) return e;
         if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
         hipLaunchKernelGGL(k_finalize, dim3(1), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
-                           w.word_end, out, capacity, out_bytes);
+                           w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr);
         if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
         return hipGetLastError();
     }
@@ -318,7 +349,7 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
     }
     if (prof_on(pl, P_CODEBOOK)) prof_begin(prof, P_CODEBOOK, s);
     hipLaunchKernelGGL(k_codebook, dim3(g.T), dim3(256), codebook_smem(g.K), s, g, w.hist, w.hist_view, w.enc, w.lens,
-                       w.tmeta);
+                       w.tmeta, 0u);
     if (prof_on(pl, P_CODEBOOK)) prof_end(prof, P_CODEBOOK, s);
     {
         const uint32_t bpt = (g.G + 3) / 4;
@@ -332,8 +363,11 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
     }
     if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
     hipLaunchKernelGGL(k_finalize, dim3(1), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
-                       w.word_end, out, capacity, out_bytes);
+                       w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr);
     if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
+    if (w.carry != 0)  // the codebook the next call will use: this call's counts (kept as the copy), escape symbol included
+        hipLaunchKernelGGL(k_codebook, dim3(g.T), dim3(256), codebook_smem(g.K), s, g, w.hist_view, w.hist_view, w.enc,
+                           w.lens, w.tmeta, 1u);
     return hipGetLastError();
 }
 

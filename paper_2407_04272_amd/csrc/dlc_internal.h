@@ -181,7 +181,7 @@ struct Ws;  // workspace, see dlc_api.hip
 
 hipError_t launch_quantize(const Geom& g, const void* payload, const QParam* qp, uint16_t* sym, hipStream_t s);
 hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uint64_t capacity, uint64_t* out_bytes,
-                           const Ws& w, uint64_t epoch, int prof_level, void* prof, hipStream_t s);
+                           const Ws& w, uint64_t epoch, bool carry_ready, int prof_level, void* prof, hipStream_t s);
 hipError_t fused_plan(const Geom& g, uint32_t* grid_out);
 hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_bytes, void* out, const Ws& w,
                              int prof_level, void* prof, hipStream_t s);
@@ -207,6 +207,8 @@ struct Ws {
     uint32_t* arrive = nullptr;    // [T] items of a table that have added their counts (fused kernel); zero between calls
     uint64_t* ready = nullptr;     // [T] call counter of the call whose codebook of the table is complete
     uint32_t fused_grid = 0;       // work-groups of the fused kernel; 0 = separate histogram / codebook / encode kernels
+    uint32_t* esc_count = nullptr; // [T] escapes of the call (single-pass path); zero between calls
+    uint32_t carry = 0;            // 1: the codebook is carried from call to call (single-pass path)
     // decompress
     uint16_t* lut = nullptr;       // [T][1 << LMAX]  len << 12 | symbol
     DecLayout* dlay = nullptr;
@@ -225,9 +227,9 @@ struct Ws {
 // profiling hooks used by the launchers (implemented in dlc_api.hip)
 void prof_begin(void* prof, int slot, hipStream_t s);
 void prof_end(void* prof, int slot, hipStream_t s);
-enum ProfSlot { P_HIST = 0, P_CODEBOOK, P_ENCODE, P_FINALIZE, P_DEC_PREPARE, P_DECODE, P_FUSED, P_NSLOTS };
+enum ProfSlot { P_HIST = 0, P_CODEBOOK, P_ENCODE, P_FINALIZE, P_DEC_PREPARE, P_DECODE, P_FUSED, P_CARRY, P_NSLOTS };
 inline bool prof_on(int level, int slot) {
-    return level >= 2 || (level == 1 && (slot == P_ENCODE || slot == P_DECODE || slot == P_FUSED));
+    return level >= 2 || (level == 1 && (slot == P_ENCODE || slot == P_DECODE || slot == P_FUSED || slot == P_CARRY));
 }
 
 }  // namespace dlc

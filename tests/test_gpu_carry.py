@@ -1,0 +1,181 @@
+"""GPU parity of the carried-codebook path (DLC_FLAG_CARRY_CODEBOOK): a sequence of payloads through one context
+against the same sequence through the oracle, container by container, byte for byte.
+
+The oracle chain is its own: call k is given the counts the oracle itself reported for call k-1; nothing the GPU
+produced goes into it.
+"""
+import numpy as np
+import pytest
+
+import dlc_workloads as W
+import oracle
+from gpu_util import to_device
+
+pytestmark = pytest.mark.gpu
+
+R = 512
+
+
+def _batch(T, B, D, seed, sigma=0.02, dtype=np.float32, rows=80, shift=0.0):
+    rng = np.random.default_rng(seed)
+    table = (rng.standard_normal((rows, D)) * sigma + shift).astype(np.float32)
+    idx = rng.integers(0, rows, (T, B))
+    x = table[idx] * (1 + np.arange(T, dtype=np.float32)[:, None, None])
+    return x.astype(dtype)
+
+
+class _Chain:
+    """one context with the flag; compress() returns (container bytes, sizes, reconstruction)"""
+
+    def __init__(self, shape, dtype, S, Rr=R, LMAX=12):
+        import torch
+        from paper_2407_04272_amd import binding as b
+        self.b = b
+        T, B, D = shape
+        dt = b.F16 if np.dtype(dtype) == np.float16 else b.F32
+        self.cfg = b.make_config(dt, T, B, D, Rr, S, LMAX, b.FLAG_CARRY_CODEBOOK)
+        self.ctx = b.Context(self.cfg)
+        self.cap = b.dlc_compress_bound(self.cfg)
+        self.d_out = torch.zeros(self.cap + 64, dtype=torch.uint8, device="cuda")
+        self.d_sizes = torch.zeros(1 + T, dtype=torch.int64, device="cuda")
+
+    def compress(self, x, ebs):
+        import torch
+        d = to_device(x)
+        self.ctx.set_error_bounds(eb=ebs)
+        self.d_out.fill_(0xA5)
+        assert self.ctx.compress(d, self.d_out, self.d_sizes, capacity=self.cap) == 0
+        assert self.ctx.sync_status() == 0
+        sizes = self.d_sizes.cpu().numpy().astype(np.uint64)
+        total = int(sizes[0])
+        out = self.d_out.cpu().numpy()
+        assert np.all(out[self.cap:] == 0xA5)
+        rec = torch.full_like(d, 7.0)
+        assert self.ctx.decompress(self.d_out, total, rec) == 0
+        assert self.ctx.sync_status() == 0
+        return out[:total].copy(), sizes, rec.cpu().numpy()
+
+
+def _same(g, o, x, what):
+    data, sizes, rec = g
+    assert o.rc == 0, what
+    assert data.size == o.data.size, (what, data.size, o.data.size)
+    diff = np.nonzero(data != o.data)[0]
+    assert diff.size == 0, f"{what}: first differing byte {diff[:8]} of {data.size}"
+    assert np.array_equal(sizes, o.sizes), what
+    rc, orec = oracle.decompress(o.data, x.shape, x.dtype)
+    assert rc == 0
+    u = np.uint32 if x.dtype == np.float32 else np.uint16
+    assert np.array_equal(rec.view(u), orec.view(u)), what
+
+
+CASES = [  # T, B, D, S, eb, dtype
+    (1, 256, 16, 256, 1e-3, np.float32),     # less than one group
+    (2, 37, 13, 64, 2e-3, np.float32),       # ragged: B*D = 481 not a multiple of 4 (scalar loads), partial group
+    (3, 1000, 50, 256, 2e-3, np.float32),    # several groups and a partial last one
+    (5, 700, 48, 128, 1e-3, np.float32),
+    (2, 2048, 64, 64, 5e-4, np.float32),     # long codes: chunks that do not fit their LDS words are walked twice
+    (3, 900, 40, 256, 4e-3, np.float16),     # half precision: many escapes (records written by the second walk)
+    (2, 512, 32, 128, 2e-3, np.float16),
+]
+
+
+@pytest.mark.parametrize("T,B,D,S,eb,dtype", CASES)
+def test_chain_matches_the_oracle(T, B, D, S, eb, dtype):
+    print("carried chain", T, B, D, S, eb, np.dtype(dtype).name, flush=True)
+    ebs = (np.float32(eb) * (1 + np.arange(T, dtype=np.float32))).astype(np.float32)
+    ch = _Chain((T, B, D), dtype, S)
+    prev = None
+    for k in range(4):
+        x = _batch(T, B, D, 100 * k + B + D, dtype=dtype)
+        if k == 2:
+            x.reshape(-1)[::211] = 1e4 if dtype == np.float32 else 6e4     # true escapes
+            x.reshape(-1)[5] = np.nan
+        if k == 3:
+            x.reshape(-1)[::2999] = -3e4                                   # a few per group: records kept on the way
+        g = ch.compress(x, ebs)
+        o = oracle.compress(x, ebs, R, S, 12, carry_hist=prev, want_hist=True)
+        _same(g, o, x, f"call {k}")
+        prev = o.hist
+
+
+def test_new_bounds_start_a_new_chain():
+    T, B, D, S = 3, 600, 32, 128
+    ch = _Chain((T, B, D), np.float32, S)
+    e1 = np.full(T, 2e-3, np.float32)
+    e2 = np.full(T, 1e-3, np.float32)
+    x0, x1, x2, x3 = (_batch(T, B, D, s) for s in (1, 2, 3, 4))
+    o0 = oracle.compress(x0, e1, R, S, 12, want_hist=True)
+    _same(ch.compress(x0, e1), o0, x0, "first call")
+    o1 = oracle.compress(x1, e1, R, S, 12, carry_hist=o0.hist, want_hist=True)
+    _same(ch.compress(x1, e1), o1, x1, "carried")
+    # a changed bound: the symbols mean something else now, the call builds its own codebook
+    o2 = oracle.compress(x2, e2, R, S, 12, want_hist=True)
+    _same(ch.compress(x2, e2), o2, x2, "after new bounds")
+    o3 = oracle.compress(x3, e2, R, S, 12, carry_hist=o2.hist, want_hist=True)
+    _same(ch.compress(x3, e2), o3, x3, "carried again")
+
+
+def test_payload_unlike_the_previous_one():
+    """Nothing of the new payload has a code: every element becomes an escape, bit-exact and still in order."""
+    T, B, D, S = 2, 300, 16, 64
+    ch = _Chain((T, B, D), np.float32, S)
+    ebs = np.full(T, 1e-3, np.float32)
+    x0 = _batch(T, B, D, 7)
+    x1 = _batch(T, B, D, 8, shift=0.3)
+    o0 = oracle.compress(x0, ebs, R, S, 12, want_hist=True)
+    _same(ch.compress(x0, ebs), o0, x0, "first")
+    o1 = oracle.compress(x1, ebs, R, S, 12, carry_hist=o0.hist, want_hist=True)
+    g1 = ch.compress(x1, ebs)
+    _same(g1, o1, x1, "all escapes")
+    assert np.array_equal(g1[2].view(np.uint32), x1.view(np.uint32))
+    # and back to ordinary data: the counts of the all-escape call carry nothing but the escape
+    x2 = _batch(T, B, D, 9)
+    o2 = oracle.compress(x2, ebs, R, S, 12, carry_hist=o1.hist, want_hist=True)
+    _same(ch.compress(x2, ebs), o2, x2, "after all escapes")
+
+
+def test_small_alphabet_and_constant_table():
+    T, B, D, S = 2, 256, 16, 64
+    ch = _Chain((T, B, D), np.float32, S, Rr=64, LMAX=8)
+    ebs = np.array([1e-3, 1.0], np.float32)            # table 1: one symbol
+    prev = None
+    for k in range(3):
+        x = _batch(T, B, D, 20 + k)
+        g = ch.compress(x, ebs)
+        o = oracle.compress(x, ebs, 64, S, 8, carry_hist=prev, want_hist=True)
+        _same(g, o, x, f"call {k}")
+        prev = o.hist
+
+
+def test_workload3_consecutive_iterations_full_size():
+    """The benchmark shape: iteration i+1 coded with iteration i's codebook, byte for byte against the oracle."""
+    import torch
+    from paper_2407_04272_amd import binding as b
+    print("workload 5 forward payloads, 128 x 8192 x 128, two iterations", flush=True)
+    gen = W.Workload5(device="cuda")
+    f0 = gen.step()[0].clone()
+    f1 = gen.step()[0].clone()
+    T, B, D = f0.shape
+    lo = f0.amin(dim=(1, 2)).cpu().numpy()
+    hi = f0.amax(dim=(1, 2)).cpu().numpy()
+    ebs = (0.03 * (hi - lo)).astype(np.float32)
+    ctx = b.Context(b.make_config(b.F32, T, B, D, chunk_symbols=256, flags=b.FLAG_CARRY_CODEBOOK))
+    ctx.set_error_bounds(eb=ebs)
+    out = torch.zeros(f0.numel() * 4, dtype=torch.uint8, device="cuda")
+    sizes = torch.zeros(1 + T, dtype=torch.int64, device="cuda")
+    prev = None
+    for k, d in enumerate((f0, f1)):
+        assert ctx.compress(d, out, sizes) == 0 and ctx.sync_status() == 0
+        total = int(sizes[0].item())
+        data = out[:total].cpu().numpy()
+        rec = torch.empty_like(d)
+        assert ctx.decompress(out, total, rec) == 0 and ctx.sync_status() == 0
+        x = d.cpu().numpy()
+        print("oracle, iteration", k, flush=True)
+        o = oracle.compress(x, ebs, carry_hist=prev, want_hist=True)
+        assert o.rc == 0 and o.data.size == data.size and np.array_equal(o.data, data), k
+        assert np.array_equal(o.sizes, sizes.cpu().numpy().astype(np.uint64))
+        err = (d.double() - rec.double()).abs().amax(dim=(1, 2)).cpu().numpy()
+        assert np.all(err <= ebs.astype(np.float64) * (1 + 1e-6))
+        prev = o.hist
