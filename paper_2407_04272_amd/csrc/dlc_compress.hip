@@ -197,7 +197,9 @@ __global__ __launch_bounds__(256) void k_codebook(Geom g, uint32_t* hist, uint32
 
 // ------------------------------------------------------------------------------------------------
 // finalize: code-length blocks behind the payload, header, directory, padding, size metadata; clears the
-// per-call control words for the next call.  One work-group of 1024 threads.
+// per-call control words for the next call.  Work-groups of 1024 threads: every work-group works out where the
+// code-length blocks go (a scan over the tables) and writes the blocks of its share of the tables, a wavefront
+// per table; the first work-group also writes everything else.
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint64_t a16(uint64_t x) { return (x + 15ull) & ~15ull; }
 
@@ -209,10 +211,13 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
     __shared__ uint32_t s_abort;
     __shared__ uint32_t s_cb[1025];   // start of each table's block, relative to the pass's first block
     __shared__ uint32_t s_lo[1024], s_nl[1024];
-    const uint32_t tid = threadIdx.x;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const bool first = blockIdx.x == 0;
     const uint64_t words = word_end[g.T - 1];
     const uint64_t off_cb = a16(F.off_payload + 4ull * words);
-    const bool aborted = ctrl->abort != 0;
+    // (only the first work-group looks at the abort flag, which it clears at the end; the others are kept inside the
+    // output by the capacity test alone)
+    const bool aborted = first && ctrl->abort != 0;
     uint64_t cb_carry = 0, nout_carry = 0;
     for (uint32_t base = 0; base < g.T; base += 1024) {
         const uint32_t t = base + tid;
@@ -220,7 +225,7 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
         uint32_t cb = 0, no = 0, nl = 0;
         if (t < g.T) {
             m = tmeta[t];
-            if (esc_count) {  // single-pass path: the codebook is older than the payload, the escapes were counted by the encode kernel
+            if (first && esc_count) {  // single-pass path: the codebook is older than the payload, the escapes were counted by the encode kernel
                 m.n_outliers = esc_count[t];
                 esc_count[t] = 0;
             }
@@ -244,17 +249,23 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
         __syncthreads();
         if (s_abort) break;  // uniform
         const uint32_t nt = min(1024u, g.T - base);
-        // the pass's blocks, byte by byte: binary search for the table of byte j
-        for (uint32_t j = tid; j < cb_tot; j += 1024) {
-            uint32_t lo = 0, hi = nt - 1u;
-            while (lo < hi) {
-                const uint32_t mid = (lo + hi + 1u) >> 1;
-                if (s_cb[mid] <= j) lo = mid; else hi = mid - 1u;
+        // the blocks of this work-group's tables, a wavefront per table, four bytes per lane (the blocks start on
+        // 4-byte boundaries and are padded to them)
+        for (uint32_t lt = blockIdx.x * 16u + wave; lt < nt; lt += gridDim.x * 16u) {
+            const uint32_t n_l = s_nl[lt];
+            const uint8_t* src = lens + (size_t)(base + lt) * g.K + s_lo[lt];
+            uint32_t* dst = reinterpret_cast<uint32_t*>(out + off_cb + cb_carry + s_cb[lt]);
+            for (uint32_t wd = lane; wd < (n_l + 3u) / 4u; wd += 64) {
+                uint32_t v = 0;
+#pragma unroll
+                for (uint32_t b = 0; b < 4; ++b) {
+                    const uint32_t i = wd * 4u + b;
+                    v |= (i < n_l ? (uint32_t)src[i] : 0u) << (8u * b);
+                }
+                dst[wd] = v;
             }
-            const uint32_t i = j - s_cb[lo];
-            out[off_cb + cb_carry + j] = i < s_nl[lo] ? lens[(size_t)(base + lo) * g.K + s_lo[lo] + i] : (uint8_t)0;
         }
-        if (t < g.T) {
+        if (first && t < g.T) {
             const uint64_t w0 = word_start[t], w1 = word_end[t];
             uint8_t* d = out + kHeaderBytes + (uint64_t)kDirBytes * t;
             uint32_t* d32 = reinterpret_cast<uint32_t*>(d);
@@ -268,9 +279,12 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
         nout_carry += no_tot;
         __syncthreads();
     }
+    if (!first) return;
     if (s_abort) {
         if (tid == 0 && !aborted) set_status(ctrl, DLC_ECAPACITY);
         for (uint32_t t = tid; t < g.T + 1; t += 1024) out_bytes[t] = 0;
+        if (esc_count)  // whatever the passes after the failing one have not cleared
+            for (uint32_t t = tid; t < g.T; t += 1024) esc_count[t] = 0;
     } else {
         // padding between sections
         const uint64_t e0 = kHeaderBytes + (uint64_t)kDirBytes * g.T;
@@ -295,6 +309,9 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
     if (tid == 0) { ctrl->ticket = 0; ctrl->abort = 0; }
 }
 
+// work-groups of the finalize kernel: a wavefront per table, sixteen wavefronts per work-group
+static inline uint32_t finalize_grid(const Geom& g) { return std::min<uint32_t>((std::min<uint32_t>(g.T, 1024u) + 15u) / 16u, 64u); }
+
 hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uint64_t capacity, uint64_t* out_bytes,
                            const Ws& w, uint64_t epoch, bool carry_ready, int pl, void* prof, hipStream_t s) {
     const bool f16 = g.dtype == DLC_F16;
@@ -310,7 +327,7 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         }
         if (prof_on(pl, P_CARRY)) prof_end(prof, P_CARRY, s);
         if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
-        hipLaunchKernelGGL(k_finalize, dim3(1), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
+        hipLaunchKernelGGL(k_finalize, dim3(finalize_grid(g)), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
                            w.word_end, out, capacity, out_bytes, w.esc_count);
         if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
         if (prof_on(pl, P_CODEBOOK)) prof_begin(prof, P_CODEBOOK, s);
@@ -325,7 +342,7 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         if (prof_on(pl, P_FUSED)) prof_end(prof, P_FUSED, s);
         if (e != hipSuccess) return e;
         if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
-        hipLaunchKernelGGL(k_finalize, dim3(1), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
+        hipLaunchKernelGGL(k_finalize, dim3(finalize_grid(g)), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
                            w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr);
         if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
         return hipGetLastError();
@@ -362,7 +379,7 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         if (prof_on(pl, P_ENCODE)) prof_end(prof, P_ENCODE, s);
     }
     if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
-    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
+    hipLaunchKernelGGL(k_finalize, dim3(finalize_grid(g)), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
                        w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr);
     if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
     if (w.carry != 0)  // the codebook the next call will use: this call's counts (kept as the copy), escape symbol included
