@@ -351,10 +351,45 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
     if (lane == 0) s_tot[wave] = total;
     __syncthreads();  // also: every wavefront of the work-group has finished counting
     const uint32_t wg_total = s_tot[0] + s_tot[1] + s_tot[2] + s_tot[3];
+    // The look-back over the records of earlier work-groups (first wavefront) takes a while: a work-group waits for
+    // the slowest of those that started before it.  Meanwhile every wavefront already fetches its group's words
+    // from the LDS columns, in output order, into registers; once the offset is known they only need storing.
+    //   word i of the group belongs to the last non-empty chunk that starts at or before i.  Segment by segment
+    //   of 64 words: the chunks that start inside the segment put (start << 8 | chunk) at their start's place
+    //   in a 64-word scratch, and a running maximum spreads it over the words that follow (what the scratch
+    //   still holds from earlier segments is smaller than the value carried in, so it never needs clearing).
+    LookBack L;
+    lb_init(L, wg);
+    if (wave == 0) lb_publish_aggregate(state, epoch, wg, wg_total, lane);
+    uint32_t wb[CAP];
+    if (active && !spilled) {
+        uint32_t* const heads = s_heads + wave * kW;
+        heads[lane] = 0u;
+        const uint32_t mine = (lane_off << 8) | lane;
+        uint32_t carry = 0u;
+#pragma unroll
+        for (uint32_t seg = 0; seg < CAP; ++seg) {
+            const uint32_t base = seg * 64u;
+            wb[seg] = 0u;
+            if (base < chunk_total) {  // uniform
+                if (nw != 0u && lane_off - base < 64u) heads[lane_off - base] = mine;
+                __builtin_amdgcn_wave_barrier();
+                uint32_t v = max(heads[lane], carry);
+                __builtin_amdgcn_wave_barrier();
+                v = wave_incl_max(v);
+                carry = (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+                const uint32_t c = v & 0xFFu, k = base + lane - (v >> 8);
+                if (base + lane < chunk_total) wb[seg] = stage[k * 65u + c];
+            }
+            if (wave == 0 && !L.done && (seg % 4u) == 3u) {  // uniform: one look-back step per four segments
+                if (L.pending) (void)lb_consume(L, epoch, lane);
+                if (!L.done) lb_issue(L, state, epoch, lane);
+            }
+        }
+    }
     if (wave == 0) {
-        bool failed = false;
-        const uint32_t ex = wg_scan(state, epoch, wg, wg_total, lane, ctrl, &failed);
-        if (lane == 0) { s_excl = ex; s_dead = failed ? 1u : 0u; }
+        lb_finish(L, state, epoch, wg, wg_total, lane, ctrl);
+        if (lane == 0) { s_excl = L.excl; s_dead = L.failed ? 1u : 0u; }
     }
     // this call's histogram, for the next call's codebook: the window rows (sum of the copies, skewed start so that
     // the threads of a wavefront read different banks); everything else went to memory directly
@@ -385,24 +420,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
     if (lane == 0) reinterpret_cast<uint32_t*>(out + F.off_group)[gid] = excl;
     uint32_t* gw = reinterpret_cast<uint32_t*>(out + F.off_payload) + excl;
     if (!spilled) {
-        // word i of the group belongs to the last non-empty chunk that starts at or before i.  Segment by segment
-        // of 64 words: the chunks that start inside the segment put (start << 8 | chunk) at their start's place
-        // in a 64-word scratch, and a running maximum spreads it over the words that follow (what the scratch
-        // still holds from earlier segments is smaller than the value carried in, so it never needs clearing).
-        uint32_t* const heads = s_heads + wave * kW;
-        heads[lane] = 0u;
-        const uint32_t mine = (lane_off << 8) | lane;
-        uint32_t carry = 0u;
-        for (uint32_t base = 0; base < chunk_total; base += 64) {
-            if (nw != 0u && lane_off - base < 64u) heads[lane_off - base] = mine;
-            __builtin_amdgcn_wave_barrier();
-            uint32_t v = max(heads[lane], carry);
-            __builtin_amdgcn_wave_barrier();
-            v = wave_incl_max(v);
-            carry = (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
-            const uint32_t c = v & 0xFFu, k = base + lane - (v >> 8);
-            if (base + lane < chunk_total) gw[base + lane] = stage[k * 65u + c];
-        }
+#pragma unroll
+        for (uint32_t seg = 0; seg < CAP; ++seg)
+            if (seg * 64u + lane < chunk_total) gw[seg * 64u + lane] = wb[seg];
     } else {
         // walk again, straight to memory now that the chunk's place is known (the group's elements are read again)
         uint64_t acc2 = 0;
