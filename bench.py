@@ -21,6 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+CARRY_TRAFFIC = 590.7e6  # HBM bytes per launch of the single-pass kernel on cfg3, from the counter runs
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
 
@@ -33,6 +34,9 @@ def main():
     ap.add_argument("--chunk-symbols", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-level", type=int, default=1)
+    ap.add_argument("--carry-codebook", action="store_true",
+                    help="time the single-pass path (DLC_FLAG_CARRY_CODEBOOK: each step is coded with the codebook built "
+                         "from the previous step's payload) instead of the default two-pass path")
     ap.add_argument("--copy-reference", action="store_true",
                     help="also run three plain device copies of the payload (the known-size kernel that HBM counters are scaled by)")
     args = ap.parse_args()
@@ -56,7 +60,8 @@ def main():
     d = w.payload
     T, B, D = d.shape
     payload_bytes = d.numel() * 4
-    ctx = b.Context(b.make_config(b.F32, T, B, D, chunk_symbols=args.chunk_symbols))
+    flags = b.FLAG_CARRY_CODEBOOK if args.carry_codebook else 0
+    ctx = b.Context(b.make_config(b.F32, T, B, D, chunk_symbols=args.chunk_symbols, flags=flags))
 
     # offline analysis (Section III-A): statistics -> table classes; timed on its own
     probe_first = np.full(T, 1e-3, np.float32)
@@ -152,7 +157,7 @@ def main():
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     # HBM bytes per launch of the dominant kernel, from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
     # profiles/cfg3_hbm_traffic_pmc.txt (they cannot be collected from inside this process); known for this workload only
-    measured_traffic = {"k_encode": 235.2e6, "k_hist": 671.8e6, "k_decode": 597.4e6}
+    measured_traffic = {"k_encode": 235.2e6, "k_hist": 671.8e6, "k_decode": 597.4e6, "k_encode_carry": CARRY_TRAFFIC}
     traffic = measured_traffic.get(dom) if (args.workload == "cfg3" and args.chunk_symbols == 256) else None
     result = {
         "metric": "compress+decompress round-trip GB/s of uncompressed fp32 payload, 1 MI355X",
@@ -161,7 +166,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {T} tables x {B} lookups x dim {D} fp32 ({payload_bytes >> 20} MiB), "
                                "Zipf(1.05) single-hot, N(0,sigma_t), table-wise range-relative bounds 0.03",
-                   "chunk_symbols": args.chunk_symbols, "radius": 512, "max_code_len": 12},
+                   "chunk_symbols": args.chunk_symbols, "radius": 512, "max_code_len": 12,
+                   "codebook": "carried from the previous step" if args.carry_codebook else "built from the step's own payload"},
         "compression_ratio": round(cr, 3),
         "compress_GBps": round(payload_bytes / comp_ms / 1e6, 2), "compress_ms": round(comp_ms, 4),
         "decompress_GBps": round(payload_bytes / dec_ms / 1e6, 2), "decompress_ms": round(dec_ms, 4),
@@ -174,11 +180,40 @@ def main():
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
     }
 
+    if not args.carry_codebook:
+        # for information: the same workload through the single-pass path (not part of `value`)
+        ctx2 = b.Context(b.make_config(b.F32, T, B, D, chunk_symbols=args.chunk_symbols, flags=b.FLAG_CARRY_CODEBOOK))
+        ctx2.set_error_bounds(eb=ebs)
+        for _ in range(3):
+            ctx2.compress(d, out, sizes)
+        assert ctx2.sync_status() == 0
+        total2 = int(sizes[0].item())
+        comp2_ms = timed(lambda: ctx2.compress(d, out, sizes), n_dir)
+
+        def step2():
+            ctx2.compress(d, out, sizes)
+            ctx2.decompress(out, out.numel(), rec)
+        rt2_ms = timed(step2, n_dir)
+        assert ctx2.sync_status() == 0
+        result["carried_codebook"] = {"compress_ms": round(comp2_ms, 4),
+                                      "compress_GBps": round(payload_bytes / comp2_ms / 1e6, 2),
+                                      "round_trip_GBps": round(payload_bytes / rt2_ms / 1e6, 2),
+                                      "compression_ratio": round(payload_bytes / total2, 3),
+                                      "note": "each call coded with the codebook of the previous call's payload "
+                                              "(here the same payload); see --carry-codebook"}
+        del ctx2
+        # leave the default path's container in `out` for the comparison below
+        ctx.compress(d, out, sizes)
+        assert ctx.sync_status() == 0
+
     if not args.no_cpu_baseline:
         import oracle
         x = d.cpu().numpy()
+        carry = None
+        if args.carry_codebook:  # the steady state of the chain: the counts of the same payload
+            carry = oracle.compress(x, ebs, want_hist=True).hist
         t0 = time.perf_counter()
-        o = oracle.compress(x, ebs)
+        o = oracle.compress(x, ebs, carry_hist=carry)
         tc = time.perf_counter() - t0
         t0 = time.perf_counter()
         rc, orec = oracle.decompress(o.data, x.shape, np.float32)
