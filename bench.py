@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--carry-codebook", action="store_true",
                     help="time the single-pass path (DLC_FLAG_CARRY_CODEBOOK: each step is coded with the codebook built "
                          "from the previous step's payload) instead of the default two-pass path")
+    ap.add_argument("--all-workloads", action="store_true",
+                    help="also measure the five synthetic workloads one after the other (adds a 'workloads' list to the "
+                         "JSON line; takes about a minute more, mostly the oracle)")
     ap.add_argument("--copy-reference", action="store_true",
                     help="also run three plain device copies of the payload (the known-size kernel that HBM counters are scaled by)")
     args = ap.parse_args()
@@ -225,7 +228,122 @@ def main():
                                   "compress_GBps": round(payload_bytes / tc / 1e9, 4),
                                   "decompress_GBps": round(payload_bytes / td / 1e9, 4),
                                   "container_identical_to_gpu": same}
+    if args.all_workloads:
+        del d, rec, out
+        torch.cuda.empty_cache()
+        result["workloads"] = all_workloads(b, torch, np, W, dev, args.chunk_symbols, not args.no_cpu_baseline)
     print(json.dumps(result))
+
+
+def _measure(b, torch, np, name, d, ebs, S, with_oracle):
+    """compress / decompress of one payload at the given bounds: both paths on the GPU, the oracle beside them."""
+    T, B, D = d.shape
+    f16 = d.dtype == torch.float16
+    nbytes = d.numel() * d.element_size()
+    out = torch.zeros(max(nbytes, 1 << 20), dtype=torch.uint8, device=d.device)
+    sizes = torch.zeros(1 + T, dtype=torch.int64, device=d.device)
+    rec = torch.empty_like(d)
+    row = {"workload": name, "shape": [T, B, D], "dtype": "f16" if f16 else "f32", "payload_MiB": round(nbytes / 2 ** 20, 3)}
+
+    def timed(fn, n=20):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(3):
+            fn()
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    for key, flags in (("", 0), ("carried_", b.FLAG_CARRY_CODEBOOK)):
+        ctx = b.Context(b.make_config(b.F16 if f16 else b.F32, T, B, D, chunk_symbols=S, flags=flags))
+        ctx.set_error_bounds(eb=ebs)
+        c_ms = timed(lambda: ctx.compress(d, out, sizes))
+        assert ctx.sync_status() == 0
+        total = int(sizes[0].item())
+        cr = nbytes / total
+        algo = nbytes * (1.0 + 1.0 / cr)
+        row[key + "compression_ratio"] = round(cr, 3)
+        row[key + "compress_GBps"] = round(nbytes / c_ms / 1e6, 2)
+        row[key + "compress_roofline_frac"] = round(algo / (c_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+        if not key:
+            d_ms = timed(lambda: ctx.decompress(out, total, rec))
+            assert ctx.sync_status() == 0
+            row["decompress_GBps"] = round(nbytes / d_ms / 1e6, 2)
+            row["decompress_roofline_frac"] = round(algo / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+            eb_t = torch.from_numpy(np.asarray(ebs, np.float64)).to(d.device).view(T, 1, 1)
+            fin = torch.isfinite(d)
+            err = torch.where(fin, (d.double() - rec.double()).abs(), torch.zeros((), dtype=torch.float64, device=d.device))
+            row["bound_held"] = bool((err <= eb_t * (1 + 1e-6)).all())
+            data = out[:total].cpu().numpy()
+        del ctx
+    if with_oracle:
+        import oracle
+        x = d.cpu().numpy()
+        t0 = time.perf_counter()
+        o = oracle.compress(x, ebs, S=S)
+        tc = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        rc, _ = oracle.decompress(o.data, x.shape, x.dtype)
+        td = time.perf_counter() - t0
+        row["oracle_GBps"] = round(nbytes / (tc + td) / 1e9, 4)
+        row["container_identical_to_oracle"] = bool(o.rc == 0 and rc == 0 and o.data.size == data.size
+                                                     and np.array_equal(o.data, data))
+    return row
+
+
+def all_workloads(b, torch, np, W, dev, S, with_oracle):
+    rows = []
+
+    def bounds(d, meta, mode, probe_frac=None, probe_abs=None, iteration=0, decay=False, rel_floor=0.0, clamp=(0.0, 0.0)):
+        T = d.shape[0]
+        ctx = b.Context(b.make_config(b.F16 if d.dtype == torch.float16 else b.F32, *d.shape, chunk_symbols=S))
+        if probe_abs is not None:
+            probe = np.full(T, probe_abs, np.float32)
+        else:
+            lo = d.float().amin(dim=(1, 2)).cpu().numpy()
+            hi = d.float().amax(dim=(1, 2)).cpu().numpy()
+            probe = (probe_frac * (hi - lo)).astype(np.float32)
+        st = ctx.stats(d, probe)
+        p = b.ControllerParams(mode=mode, decay_kind=b.DECAY_STEPWISE if decay else b.DECAY_NONE,
+                               global_eb=meta["global_eb"], alpha=meta["alpha"], beta=meta["beta"], h_large=0.0,
+                               h_small=0.05, decay_start=0, decay_len=100 if decay else 0, decay_steps=5 if decay else 0,
+                               reserved=0, decay_mult0=2.0 if decay else 1.0, eb_min=clamp[0], eb_max=clamp[1],
+                               rel_floor=rel_floor)
+        ebs, _ = ctx.set_error_bounds(stats=st, params=p, iteration=iteration)
+        return ebs
+
+    w = W.workload1()
+    d = torch.from_numpy(w.payload).to(dev)
+    rows.append(_measure(b, torch, np, "1: 1 table, 256 lookups x 16, absolute bound 1e-3", d,
+                         np.full(1, w.meta["eb"], np.float32), S, with_oracle))
+    w = W.workload2()
+    d = torch.from_numpy(w.payload).to(dev)
+    ebs = bounds(d, w.meta, 0, probe_abs=w.meta["global_eb"], clamp=(w.meta["eb_min"], w.meta["eb_max"]))
+    rows.append(_measure(b, torch, np, "2: 26 tables x 4096 x 64, controller with absolute bounds", d, ebs, S, with_oracle))
+    w = W.workload3(device=dev)
+    ebs = bounds(w.payload, w.meta, 1, probe_frac=0.03)
+    rows.append(_measure(b, torch, np, "3: 128 x 8192 x 128, range-relative 0.03", w.payload, ebs, S, with_oracle))
+    del w
+    torch.cuda.empty_cache()
+    w = W.workload4(device=dev)
+    ebs = bounds(w.payload, w.meta, 1, probe_frac=0.03)
+    rows.append(_measure(b, torch, np, "4: 64 x 16384 x 128 multi-hot, fp32", w.payload, ebs, S, with_oracle))
+    h = w.meta["payload_f16"]
+    ebs = bounds(h, w.meta, 1, probe_frac=0.03, rel_floor=w.meta["rel_floor_f16"])
+    rows.append(_measure(b, torch, np, "4: the same sums in fp16, floor 2^-10 of the range", h, ebs, S, with_oracle))
+    del w, h
+    torch.cuda.empty_cache()
+    gen = W.Workload5(device=dev)
+    fwd, bwd = gen.step()
+    fwd, bwd = fwd.clone(), bwd.clone()
+    for it, tag in ((0, "iteration 0 (bound x2)"), (100, "iteration 100 (bound x1)")):
+        ebs = bounds(fwd, gen.meta, 1, probe_frac=0.03, iteration=it, decay=True)
+        rows.append(_measure(b, torch, np, "5: forward payload, " + tag, fwd, ebs, S, with_oracle))
+    ebs = bounds(bwd, gen.meta, 1, probe_abs=1e-5, iteration=100, decay=True)
+    rows.append(_measure(b, torch, np, "5: backward payload N(0, 1e-4)", bwd, ebs, S, with_oracle))
+    return rows
 
 
 if __name__ == "__main__":

@@ -116,7 +116,7 @@ __device__ __forceinline__ void carry_block(const CarryEnv& E, const float (&x)[
             const float xv = x[u][v];
             const float r = __builtin_rintf(xv * E.q.inv);
             float xh = r * E.q.ebx2;
-            if constexpr (F16) xh = __half2float(__float2half_rn(xh));
+            if constexpr (F16) xh = __half2float(half_rne(xh));
             const float d = xv - xh;
             const bool ok = __builtin_fabsf(d) <= E.q.eb;
             const float t = __builtin_amdgcn_fmed3f(__builtin_fmaf(r, 4.0f, E.bias4), 0.0f, 1024.0f);  // exact: small integers

@@ -98,7 +98,7 @@ __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, ui
             const float xv = x[u][v];
             const float r = __builtin_rintf(xv * q.inv);
             float xh = r * q.ebx2;
-            if constexpr (F16) xh = __half2float(__float2half_rn(xh));
+            if constexpr (F16) xh = __half2float(half_rne(xh));
             const float d = xv - xh;
             const bool ok = (__builtin_fabsf(r) < Rf) & (__builtin_fabsf(d) <= q.eb);  // no short circuit: no branches
             w[v] = ok ? (uint32_t)((int)r + H.ubias) : kEscW;

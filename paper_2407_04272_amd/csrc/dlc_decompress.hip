@@ -250,10 +250,10 @@ __global__ __launch_bounds__(64 * DLC_DEC_WAVES) void k_decode(Geom g, const uin
                 if constexpr (F16) {
                     typedef uint32_t u2v __attribute__((ext_vector_type(2)));
                     u2v o;
-                    o.x = (uint32_t)__half_as_ushort(__float2half_rn(v4[0])) |
-                          ((uint32_t)__half_as_ushort(__float2half_rn(v4[1])) << 16);
-                    o.y = (uint32_t)__half_as_ushort(__float2half_rn(v4[2])) |
-                          ((uint32_t)__half_as_ushort(__float2half_rn(v4[3])) << 16);
+                    o.x = (uint32_t)__half_as_ushort(half_rne(v4[0])) |
+                          ((uint32_t)__half_as_ushort(half_rne(v4[1])) << 16);
+                    o.y = (uint32_t)__half_as_ushort(half_rne(v4[2])) |
+                          ((uint32_t)__half_as_ushort(half_rne(v4[3])) << 16);
                     __builtin_nontemporal_store(o, reinterpret_cast<u2v*>(reinterpret_cast<uint16_t*>(tab) + idx));
                 } else {
                     typedef float f4v __attribute__((ext_vector_type(4)));
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(64 * DLC_DEC_WAVES) void k_decode(Geom g, const uin
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
                     if (idx + v < g.n) {
-                        if constexpr (F16) reinterpret_cast<__half*>(tab)[idx + v] = __float2half_rn(v4[v]);
+                        if constexpr (F16) reinterpret_cast<__half*>(tab)[idx + v] = half_rne(v4[v]);
                         else reinterpret_cast<float*>(tab)[idx + v] = v4[v];
                     }
             }

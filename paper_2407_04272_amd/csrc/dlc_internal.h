@@ -81,13 +81,22 @@ struct DecTable {
 
 __device__ __forceinline__ void set_status(Ctrl* c, int32_t code) { atomicCAS(&c->status, 0, code); }
 
+// binary32 -> binary16, round to nearest even, of a value that is already a rounded binary32 number.  The value is
+// pinned in a register first: handed a product directly, the compiler merges the multiply and the conversion into
+// one mixed-precision instruction (v_fma_mixlo_f16), which rounds once, from the exact product, instead of twice,
+// and that differs from "binary32 product, then binary16" whenever the binary32 product lands on a binary16 tie.
+__device__ __forceinline__ __half half_rne(float v) {
+    asm("" : "+v"(v));
+    return __float2half_rn(v);
+}
+
 // Quantisation encoder without predictor: bin = rne(x / 2eb), taken as one binary32 multiply by the
 // rounded reciprocal; escape (symbol 0) when the bin is outside (-R, R) or the reconstruction misses eb.
 template <bool F16>
 __device__ __forceinline__ uint32_t quant_symbol(float x, const QParam& q, float Rf, int R) {
     float r = __builtin_rintf(x * q.inv);
     float xh = r * q.ebx2;
-    if constexpr (F16) xh = __half2float(__float2half_rn(xh));
+    if constexpr (F16) xh = __half2float(half_rne(xh));
     float d = x - xh;
     bool ok = (__builtin_fabsf(r) < Rf) && (__builtin_fabsf(d) <= q.eb);
     return ok ? (uint32_t)((int)r + R) : 0u;

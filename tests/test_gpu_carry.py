@@ -179,3 +179,15 @@ def test_workload3_consecutive_iterations_full_size():
         err = (d.double() - rec.double()).abs().amax(dim=(1, 2)).cpu().numpy()
         assert np.all(err <= ebs.astype(np.float64) * (1 + 1e-6))
         prev = o.hist
+
+
+def test_f16_ties_on_the_single_pass_path():
+    from test_oracle_quantizer import half_tie_payload
+    x, ebs = half_tie_payload()
+    ch = _Chain(x.shape, np.float16, 128)
+    prev = None
+    for k in range(2):
+        g = ch.compress(x, ebs)
+        o = oracle.compress(x, ebs, R, 128, 12, carry_hist=prev, want_hist=True)
+        _same(g, o, x, f"call {k}")
+        prev = o.hist

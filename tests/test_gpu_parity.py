@@ -262,3 +262,12 @@ def test_deterministic_bytes():
     for _ in range(3):
         c = GpuRun(x, 2e-3, S=256, ctx=a.ctx, d_payload=a.d_payload)
         assert c.status == 0 and np.array_equal(a.data, c.data)
+
+
+def test_f16_bin_centres_on_binary16_ties():
+    """Bounds for which a bin centre, as a binary32 product, lands exactly between two binary16 numbers: the
+    reconstruction must be rounded in two steps (binary32, then binary16), not by one fused multiply-convert."""
+    from test_oracle_quantizer import half_tie_payload
+    x, ebs = half_tie_payload()
+    _full_parity(x, ebs, S=64)
+    _full_parity(x, ebs, S=256)

@@ -140,3 +140,46 @@ def test_bound_holds_on_every_element_f16(rel):
     assert np.array_equal(rec[~esc].view(np.uint16), want.view(np.uint16))
     # half precision rounding of the reconstruction makes bin-edge escapes a visible fraction
     assert 0 < esc.mean() < 0.5
+
+
+# bounds (binary32 bit patterns) for which some bin centre r * 2eb, rounded to binary32, lands exactly half way between
+# two binary16 numbers while the exact product does not: rounding the product to binary16 in one step (what a fused
+# multiply-convert instruction does) gives another reconstruction than binary32-then-binary16
+TIE_BOUNDS = [1037035110, 994589847, 1009301586, 1050593819, 982489498]
+
+
+def half_tie_payload():
+    """every finite binary16 value in [-2, 2], one table per bound"""
+    pos = np.arange(0, 0x4001, dtype=np.uint16)
+    vals = np.concatenate([pos, pos | np.uint16(0x8000)]).view(np.float16)
+    n = 514 * 64
+    x = np.zeros((len(TIE_BOUNDS), n), np.float16)
+    x[:, :vals.size] = vals
+    ebs = np.array(TIE_BOUNDS, np.uint32).view(np.float32)
+    return x.reshape(len(TIE_BOUNDS), 514, 64), ebs
+
+
+def test_f16_reconstruction_is_rounded_twice():
+    """Section III-D fixes no number format; the reading taken is: bin centre as a binary32 product, then rounded to
+    binary16 (ties to even).  The oracle must follow it where the one-step rounding differs, and the symbol decision
+    (inside the bound or escape) must be the one that reading gives."""
+    x, ebs = half_tie_payload()
+    differ = 0
+    for t, eb in enumerate(ebs):
+        sym, rec = oracle.quantize(x[t:t + 1], float(eb), R)
+        xs = x[t].reshape(-1).astype(np.float32)
+        ebx2 = np.float32(eb * np.float32(2))
+        inv = np.float32(1.0 / np.float64(ebx2))
+        r = np.rint((xs * inv).astype(np.float32)).astype(np.float32)
+        two = (r * ebx2).astype(np.float32).astype(np.float16)                       # the reading
+        one = (r.astype(np.float64) * np.float64(ebx2)).astype(np.float16)           # a fused multiply-convert
+        ok = (np.abs(r) < R) & (np.abs(xs - two.astype(np.float32)) <= eb)
+        want = np.where(ok, r.astype(np.int32) + R, 0).astype(np.uint16)
+        assert np.array_equal(sym.reshape(-1), want)
+        got = rec.reshape(-1)
+        ri = (want.astype(np.int32) - R).astype(np.float32)      # what the decoder sees (bin 0 gives +0.0)
+        two_dec = (ri * ebx2).astype(np.float32).astype(np.float16)
+        assert np.array_equal(got[ok].view(np.uint16), two_dec[ok].view(np.uint16))
+        ok1 = (np.abs(r) < R) & (np.abs(xs - one.astype(np.float32)) <= eb)
+        differ += int(np.count_nonzero(ok != ok1))
+    assert differ > 0          # the case separates the two definitions
