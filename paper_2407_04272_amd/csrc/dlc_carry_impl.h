@@ -93,7 +93,7 @@ struct CarryEnv {
     const uint16_t* enc_t;
     uint32_t* hist_t;
     uint32_t gstart;       // index of the group's first element in the table
-    uint32_t* recs;        // LDS: the wavefront's escape records found on the way (fp32 only), kCarryRecs at most
+    uint32_t* recs;        // LDS: the wavefront's escape records found on the way, kCarryRecs at most
 };
 
 // One block of kCarryBlk units already loaded: quantise, count, look up, append.
@@ -164,9 +164,10 @@ __device__ __forceinline__ void carry_block(const CarryEnv& E, const float (&x)[
                 }
                 e[v] = ((ent >> 12) << 16) | (ent & 0xFFFu);
             }
-            if constexpr (FIRST && !F16) {
+            if constexpr (FIRST) {
                 // the records of these escapes, in element order (the walk meets the elements of a group in
-                // increasing index: turn, lane, position); kept while they fit
+                // increasing index: turn, lane, position); kept while they fit.  The raw bits are read from the
+                // payload again (half precision: the float in hand need not convert back to the same bits).
                 const uint32_t cnt = __popc(em);
                 const uint32_t incl = wave_incl_scan(cnt, E.lane);
                 uint32_t r = nrec + incl - cnt;
@@ -174,8 +175,10 @@ __device__ __forceinline__ void carry_block(const CarryEnv& E, const float (&x)[
                 for (int v = 0; v < 4; ++v)
                     if ((em >> v) & 1u) {
                         if (r < kCarryRecs) {
-                            E.recs[2u * r] = E.gstart + E.lane * kV + (jb + u) * (kW * kV) + (uint32_t)v;
-                            E.recs[2u * r + 1] = __float_as_uint(x[u][v]);
+                            const uint32_t off = E.lane * kV + (jb + u) * (kW * kV) + (uint32_t)v;
+                            E.recs[2u * r] = E.gstart + off;
+                            if constexpr (F16) E.recs[2u * r + 1] = reinterpret_cast<const uint16_t*>(E.gbase)[off];
+                            else E.recs[2u * r + 1] = reinterpret_cast<const uint32_t*>(E.gbase)[off];
                         }
                         ++r;
                     }
@@ -439,7 +442,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
 #endif
     if (n_esc != 0u) {  // uniform over the wavefront
         uint32_t* rec = gw + chunk_total;
-        if (!F16 && n_esc <= kCarryRecs) {  // the records were kept on the way
+        if (n_esc <= kCarryRecs) {  // the records were kept on the way
             for (uint32_t k = lane; k < 2u * n_esc; k += 64) rec[k] = E.recs[k];
         } else {
             carry_emit_escapes<S, F16, VEC>(rec, lane, gbase, gstart, rem, q, Rf, (int)g.R, enc_t);

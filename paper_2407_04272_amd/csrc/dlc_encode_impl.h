@@ -33,8 +33,9 @@ namespace dlc {
 //           earlier)
 //   walk 2: look up length and codeword of the kept indices (index 255: the element itself once more), join the
 //           two codes of a pair, shift into a 64-bit accumulator, store whole words at the chunk's offset
-//   escapes: a group that has any walks its elements once more in a rolled loop and writes its records, in
-//           increasing element index, behind its chunk words
+//   escapes: their records (element index, raw bits; in increasing element index, behind the group's chunk words)
+//           are collected in LDS during walk 1, up to 32 per group; a group with more walks its elements once
+//           more in a rolled loop
 // Keeping bytes instead of (length, codeword) entries halves the registers a wavefront holds between the walks,
 // which doubles the wavefronts per SIMD: the kernel is bound by latency (global scan, table look-ups, stores),
 // not by arithmetic.
@@ -70,6 +71,8 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
     __shared__ uint32_t s_wg, s_tot[4], s_ct[4], s_excl, s_dead;
     constexpr uint32_t kStageWords = 8u * (uint32_t)S;  // LDS staging per wavefront: room for a group of up to 4 bits per symbol
     __shared__ __align__(16) uint32_t s_stage[4 * kStageWords];
+    constexpr uint32_t kEncRecs = 32;  // escape records a wavefront keeps in LDS; a group with more walks its elements again
+    __shared__ uint32_t s_recs[4 * 2 * kEncRecs];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     if (tid == 0) s_wg = atomicAdd(&ctrl->ticket, 1u);
     __syncthreads();
@@ -101,7 +104,8 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
 
     DLC_ESTAMP(1);
     uint32_t ix[S / 4];  // window indices, four to a word, in element order
-    uint32_t bits = 0, my_esc = 0;
+    uint32_t bits = 0, my_esc = 0, nrec = 0;
+    uint32_t* const recs = s_recs + wave * (2u * kEncRecs);
     if (active) {
         const uint32_t* plane = reinterpret_cast<const uint32_t*>(sym_plane + (size_t)t * plane_stride(g) + gstart);
         const bool ragged = rem < kW * (uint32_t)S;  // uniform: the table ends inside this group
@@ -132,6 +136,7 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
                 for (int u = 0; u < kB1; ++u) {
                     const uint32_t m = ix[jb + u];
                     if (__ballot(has_ff_byte(m)) == 0ull) continue;
+                    uint32_t em = 0;  // which of the four are escapes
 #pragma clang loop unroll(full)
                     for (int v = 0; v < 4; ++v) {
                         const uint32_t off = lane * kV + (uint32_t)(jb + u) * (kW * kV) + (uint32_t)v;
@@ -139,7 +144,27 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
                             uint32_t esc;
                             bits += entry_of_element<F16>(gbase, off, q, Rf, (int)g.R, enc_t, &esc) >> 12;
                             my_esc += esc;
+                            em |= esc << v;
                         }
+                    }
+                    // the records of these escapes, in element order (the walk meets the elements of a group in
+                    // increasing index: turn, lane, position); kept in LDS while they fit
+                    if (__ballot(em != 0u) != 0ull) {
+                        const uint32_t cnt = __popc(em);
+                        const uint32_t incl = wave_incl_scan(cnt, lane);
+                        uint32_t r = nrec + incl - cnt;
+#pragma clang loop unroll(full)
+                        for (int v = 0; v < 4; ++v)
+                            if ((em >> v) & 1u) {
+                                if (r < kEncRecs) {
+                                    const uint32_t off = lane * kV + (uint32_t)(jb + u) * (kW * kV) + (uint32_t)v;
+                                    recs[2u * r] = gstart + off;
+                                    if constexpr (F16) recs[2u * r + 1] = reinterpret_cast<const uint16_t*>(gbase)[off];
+                                    else recs[2u * r + 1] = reinterpret_cast<const uint32_t*>(gbase)[off];
+                                }
+                                ++r;
+                            }
+                        nrec += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
                     }
                 }
             }
@@ -263,8 +288,14 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
     if (staged)
         for (uint32_t k = lane; k < chunk_total; k += 64) gw[k] = stage[k];
     DLC_ESTAMP(5);
-    if (n_esc != 0u)  // uniform over the wavefront
-        emit_escapes<S, F16, VEC>(gw + chunk_total, lane, gbase, gstart, rem, q, Rf, (int)g.R);
+    if (n_esc != 0u) {  // uniform over the wavefront
+        uint32_t* rec = gw + chunk_total;
+        if (n_esc <= kEncRecs) {  // the records were kept on the way
+            for (uint32_t k = lane; k < 2u * n_esc; k += 64) rec[k] = recs[k];
+        } else {
+            emit_escapes<S, F16, VEC>(rec, lane, gbase, gstart, rem, q, Rf, (int)g.R);
+        }
+    }
 }
 
 void DLC_CAT(launch_encode_, DLC_S)(const Geom& g, const FixedLayout& F, const void* payload, const Ws& w, uint64_t epoch,
