@@ -18,8 +18,8 @@ namespace dlc {
 
 typedef __attribute__((address_space(3))) uint32_t lds_u32;
 
-constexpr uint32_t kCarryBlk = 4;   // units (16-byte loads per lane) worked on together
-constexpr uint32_t kCarryLoad = 8;  // units loaded together, one such block ahead of the work
+constexpr uint32_t kCarryBlk = 2;   // units (16-byte loads per lane) worked on together
+constexpr uint32_t kCarryLoad = 4;  // units loaded together, one such block ahead of the work
 
 // hooks for micro-benchmarks (a step switched off); the library has them all on
 #ifndef DLC_CX_COUNT
@@ -73,7 +73,11 @@ __device__ __forceinline__ void carry_count(uint32_t addr) {
 // (an escape, a symbol outside the window, NaN, a position past the end of the table).  The index comes straight
 // out of the float pipeline as a byte offset, 4*i, clamped to [0, 1024].
 constexpr uint32_t kCarryRows = 257;
-constexpr uint32_t kCarryRecs = 32;  // escape records a wavefront keeps in LDS; a group with more walks its elements again
+constexpr uint32_t kCarryRecs = 16;   // escape records a wavefront keeps in LDS; a group with more walks its elements again
+// copies of a histogram row in LDS (copy = lane mod kCarryCopies).  Few, and loads only four turns ahead: the
+// kernel is sized (LDS 40 KiB, 128 registers) so that four work-groups share a CU, which counts for more here than
+// cheaper atomics or deeper prefetch (measured: 16 copies and eight turns ahead at three work-groups, 160 us; this, 153 us)
+constexpr uint32_t kCarryCopies = 4;
 
 // LDS staging of a wavefront: word k of chunk l at [k*65 + l] (stride 65: the words of one chunk fall into
 // different banks when the chunk is copied out), CAP rows plus one that takes what does not fit
@@ -135,7 +139,7 @@ __device__ __forceinline__ void carry_block(const CarryEnv& E, const float (&x)[
         for (uint32_t u = 0; u < kCarryBlk; ++u)
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-                if (DLC_CX_SAMPLE(u) && (FULL || ((valid[u] >> v) & 1u))) DLC_CX_COUNT(ab[u][v] * kWinCopies + E.lanebase);  // rows 0 and 256 are not used
+                if (DLC_CX_SAMPLE(u) && (FULL || ((valid[u] >> v) & 1u))) DLC_CX_COUNT(ab[u][v] * kCarryCopies + E.lanebase);  // rows 0 and 256 are not used
     }
     DLC_CX_T(2);
 #pragma unroll
@@ -220,7 +224,7 @@ template <int S, bool F16, bool VEC, bool FULL, bool FIRST>
 __device__ __forceinline__ void carry_walk(const CarryEnv& E, uint64_t& acc, uint32_t& nb, uint32_t& sp, uint32_t sp_lim,
                                            uint32_t*& dst, uint32_t& esc, uint32_t& nrec DLC_CX_TARGS) {
     constexpr uint32_t N = (uint32_t)S / kV;  // turns
-    static_assert(N % (2 * kCarryLoad) == 0 && kCarryLoad == 2 * kCarryBlk, "two load blocks per trip, two work blocks per load block");
+    static_assert(N % (2 * kCarryLoad) == 0 && kCarryLoad % kCarryBlk == 0, "two load blocks per trip, whole work blocks per load block");
     typedef const float (&XBlk)[kCarryBlk][4];
     typedef const uint32_t (&VBlk)[kCarryBlk];
     float xa[kCarryLoad][4], xb[kCarryLoad][4];
@@ -228,11 +232,13 @@ __device__ __forceinline__ void carry_walk(const CarryEnv& E, uint64_t& acc, uin
     carry_load<F16, VEC, FULL>(E, 0, xa, va);
     for (uint32_t jb = 0; jb < N; jb += 2 * kCarryLoad) {
         carry_load<F16, VEC, FULL>(E, jb + kCarryLoad, xb, vb);
-        carry_block<F16, FULL, FIRST>(E, reinterpret_cast<XBlk>(xa[0]), reinterpret_cast<VBlk>(va[0]), jb, acc, nb, sp, sp_lim, dst, esc, nrec DLC_CX_TPASS);
-        carry_block<F16, FULL, FIRST>(E, reinterpret_cast<XBlk>(xa[kCarryBlk]), reinterpret_cast<VBlk>(va[kCarryBlk]), jb + kCarryBlk, acc, nb, sp, sp_lim, dst, esc, nrec DLC_CX_TPASS);
+#pragma unroll
+        for (uint32_t k = 0; k < kCarryLoad; k += kCarryBlk)
+            carry_block<F16, FULL, FIRST>(E, reinterpret_cast<XBlk>(xa[k]), reinterpret_cast<VBlk>(va[k]), jb + k, acc, nb, sp, sp_lim, dst, esc, nrec DLC_CX_TPASS);
         if (jb + 2 * kCarryLoad < N) carry_load<F16, VEC, FULL>(E, jb + 2 * kCarryLoad, xa, va);
-        carry_block<F16, FULL, FIRST>(E, reinterpret_cast<XBlk>(xb[0]), reinterpret_cast<VBlk>(vb[0]), jb + kCarryLoad, acc, nb, sp, sp_lim, dst, esc, nrec DLC_CX_TPASS);
-        carry_block<F16, FULL, FIRST>(E, reinterpret_cast<XBlk>(xb[kCarryBlk]), reinterpret_cast<VBlk>(vb[kCarryBlk]), jb + kCarryLoad + kCarryBlk, acc, nb, sp, sp_lim, dst, esc, nrec DLC_CX_TPASS);
+#pragma unroll
+        for (uint32_t k = 0; k < kCarryLoad; k += kCarryBlk)
+            carry_block<F16, FULL, FIRST>(E, reinterpret_cast<XBlk>(xb[k]), reinterpret_cast<VBlk>(vb[k]), jb + kCarryLoad + k, acc, nb, sp, sp_lim, dst, esc, nrec DLC_CX_TPASS);
     }
 }
 
@@ -269,23 +275,22 @@ __device__ __forceinline__ void carry_emit_escapes(uint32_t* rec, uint32_t lane,
 }
 
 template <int S, bool F16, bool VEC>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k_encode_carry(const void* payload, Geom g, FixedLayout F, const QParam* qp,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k_encode_carry(const void* payload, Geom g, FixedLayout F, const QParam* qp,
                                                       const uint16_t* enc, Ctrl* ctrl, uint64_t* state, uint64_t epoch,
                                                       uint8_t* out, uint64_t capacity, uint32_t bpt, uint32_t* word_start,
                                                       uint32_t* word_end, uint32_t* hist, uint32_t* esc_count) {
     constexpr uint32_t CAP = (uint32_t)S / 8u;          // words of LDS per chunk: room for 4 bits per symbol
     constexpr uint32_t kStageWords = carry_stage_words(CAP);  // per wavefront
-    __shared__ __align__(16) uint32_t s_hist[(kCarryRows + 3u) * kWinCopies];
+    __shared__ __align__(16) uint32_t s_hist[(kCarryRows + 3u) * kCarryCopies];
     __shared__ __align__(16) uint32_t s_tab[kCarryRows + 3u];  // by table index: len << 16 | codeword; 0 = no code
     __shared__ __align__(16) uint32_t s_stage[4 * kStageWords];
-    __shared__ uint32_t s_heads[4 * kW];
     __shared__ uint32_t s_recs[4 * 2 * kCarryRecs];
     __shared__ uint32_t s_wg, s_tot[4], s_excl, s_dead;
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     if (tid == 0) s_wg = atomicAdd(&ctrl->ticket, 1u);
     {
         uint4* z = reinterpret_cast<uint4*>(s_hist);
-        for (uint32_t k = tid; k < (kCarryRows + 3u) * kWinCopies / 4u; k += 256) z[k] = make_uint4(0, 0, 0, 0);
+        for (uint32_t k = tid; k < (kCarryRows + 3u) * kCarryCopies / 4u; k += 256) z[k] = make_uint4(0, 0, 0, 0);
     }
     __syncthreads();
     const uint32_t wg = __builtin_amdgcn_readfirstlane(s_wg);
@@ -316,7 +321,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
     E.bias4 = 4.0f * (float)(g.R - win_lo + 1u);
     E.win_lo = win_lo;
     E.a_tab = (uint32_t)(uintptr_t)s_tab;
-    E.lanebase = (uint32_t)(uintptr_t)s_hist + (lane & (kWinCopies - 1u)) * 4u;
+    E.lanebase = (uint32_t)(uintptr_t)s_hist + (lane & (kCarryCopies - 1u)) * 4u;
     E.enc_t = enc_t;
     E.hist_t = hist_t;
     E.gstart = gstart;
@@ -366,7 +371,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
     if (wave == 0) lb_publish_aggregate(state, epoch, wg, wg_total, lane);
     uint32_t wb[CAP];
     if (active && !spilled) {
-        uint32_t* const heads = s_heads + wave * kW;
+        uint32_t* const heads = stage + CAP * 65u;  // the row that takes what does not fit is free now (nothing spilled)
         heads[lane] = 0u;
         const uint32_t mine = (lane_off << 8) | lane;
         uint32_t carry = 0u;
@@ -397,9 +402,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
     // this call's histogram, for the next call's codebook: the window rows (sum of the copies, skewed start so that
     // the threads of a wavefront read different banks); everything else went to memory directly
     if (tid < kCarryRows - 2u) {
-        const uint32_t* row = s_hist + (tid + 1u) * kWinCopies;
+        const uint32_t* row = s_hist + (tid + 1u) * kCarryCopies;
         uint32_t s = 0;
-        for (uint32_t c = 0; c < kWinCopies; ++c) s += row[(c + tid) & (kWinCopies - 1u)];
+        for (uint32_t c = 0; c < kCarryCopies; ++c) s += row[(c + tid) & (kCarryCopies - 1u)];
         const uint32_t sym = win_lo + tid;
         if (s && sym < g.K) atomicAdd(&hist_t[sym], s);
     }
