@@ -107,7 +107,14 @@ typedef struct {
 } dlc_table_stats;
 
 enum { DLC_CLASS_SMALL = 0, DLC_CLASS_MEDIUM = 1, DLC_CLASS_LARGE = 2 };
-enum { DLC_DECAY_NONE = 0, DLC_DECAY_STEPWISE = 1, DLC_DECAY_DROP = 2 };
+/* Iteration-wise schedules (Section III-C names logarithmic and stepwise decay functions and gives only their end
+ * points: mult0 x base at the start of the initial phase, base after it).  With u = (i - decay_start) / decay_len:
+ *   STEPWISE  mult0 - (mult0 - 1) * floor(u * steps) / steps       (the paper's default)
+ *   DROP      mult0 during the phase, 1 after it                    ("Drop_kx")
+ *   LINEAR    mult0 - (mult0 - 1) * u
+ *   LOG       mult0 - (mult0 - 1) * log(1 + (i - decay_start)) / log(1 + decay_len)   (fast at first, then slow)
+ * All are mult0 before the phase and 1 from its end on; computed in double. */
+enum { DLC_DECAY_NONE = 0, DLC_DECAY_STEPWISE = 1, DLC_DECAY_DROP = 2, DLC_DECAY_LINEAR = 3, DLC_DECAY_LOG = 4 };
 
 /* Hyper-parameters of Algorithm 1. */
 typedef struct {
@@ -191,6 +198,8 @@ int dlc_sync_status(dlc_ctx* ctx, void* stream);
  *   dlc_quantize       symbols (uint16, DEVICE, T*B*D) of d_payload at the current bounds -- the quantiser alone
  *   dlc_read_histogram the code histogram (uint32[T][2R], HOST) left by the last dlc_compress
  *   dlc_read_codebook  code lengths (uint8[T][2R]) and codewords (uint16[T][2R]) left by the last dlc_compress
+ * With DLC_FLAG_CARRY_CODEBOOK the histogram is still that of the last call's payload, and the codebook is the one
+ * built from it for the NEXT call (escape count raised by one), not the one the last call's container was coded with.
  */
 int dlc_quantize(dlc_ctx* ctx, const void* d_payload, uint16_t* d_symbols, void* stream);
 int dlc_read_histogram(dlc_ctx* ctx, uint32_t* h_hist, void* stream);

@@ -463,6 +463,11 @@ double orc_decay_multiplier(const orc_controller_params* p, int64_t i) {
     if (i >= p->decay_start + p->decay_len) return 1.0;
     if (p->decay_kind == 2) return p->decay_mult0;
     if (i < p->decay_start) return p->decay_mult0;
+    if (p->decay_kind == 3) /* linear */
+        return p->decay_mult0 - (p->decay_mult0 - 1.0) * (double)(i - p->decay_start) / (double)p->decay_len;
+    if (p->decay_kind == 4) /* logarithmic: fast at first, then slow */
+        return p->decay_mult0 -
+               (p->decay_mult0 - 1.0) * (log(1.0 + (double)(i - p->decay_start)) / log(1.0 + (double)p->decay_len));
     int64_t Ks = p->decay_steps;
     if (Ks < 1) return 1.0;
     int64_t s = ((i - p->decay_start) * Ks) / p->decay_len;

@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libdlc.so")
 F32, F16 = 0, 1
 OK, EINVAL, ENOMEM, ECAPACITY, ECORRUPT, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6
 CLASS_SMALL, CLASS_MEDIUM, CLASS_LARGE = 0, 1, 2
-DECAY_NONE, DECAY_STEPWISE, DECAY_DROP = 0, 1, 2
+DECAY_NONE, DECAY_STEPWISE, DECAY_DROP, DECAY_LINEAR, DECAY_LOG = 0, 1, 2, 3, 4
 
 
 class Config(C.Structure):

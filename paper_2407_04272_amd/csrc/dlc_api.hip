@@ -229,6 +229,11 @@ static double iteration_multiplier(const dlc_controller_params* p, int64_t i) {
     const int64_t end = p->decay_start + p->decay_len;
     if (i >= end) return 1.0;
     if (p->decay_kind == DLC_DECAY_DROP || i < p->decay_start) return p->decay_mult0;
+    if (p->decay_kind == DLC_DECAY_LINEAR)
+        return p->decay_mult0 - (p->decay_mult0 - 1.0) * (double)(i - p->decay_start) / (double)p->decay_len;
+    if (p->decay_kind == DLC_DECAY_LOG)
+        return p->decay_mult0 -
+               (p->decay_mult0 - 1.0) * (std::log(1.0 + (double)(i - p->decay_start)) / std::log(1.0 + (double)p->decay_len));
     const int64_t steps = p->decay_steps;
     if (steps < 1) return 1.0;
     int64_t s = ((i - p->decay_start) * steps) / p->decay_len;
@@ -243,7 +248,7 @@ extern "C" int dlc_set_error_bounds(dlc_ctx* c, const dlc_table_stats* st, const
     const uint32_t T = c->g.T;
     if (st) {
         if (!p) return DLC_EINVAL;
-        if (p->decay_kind < DLC_DECAY_NONE || p->decay_kind > DLC_DECAY_DROP || (p->mode != 0 && p->mode != 1))
+        if (p->decay_kind < DLC_DECAY_NONE || p->decay_kind > DLC_DECAY_LOG || (p->mode != 0 && p->mode != 1))
             return DLC_EINVAL;
         const double mult = iteration_multiplier(p, iteration);
         for (uint32_t t = 0; t < T; ++t) {

@@ -271,3 +271,27 @@ def test_f16_bin_centres_on_binary16_ties():
     x, ebs = half_tie_payload()
     _full_parity(x, ebs, S=64)
     _full_parity(x, ebs, S=256)
+
+
+def test_every_schedule_gives_the_oracles_bounds():
+    """dlc_set_error_bounds against the oracle's controller, bit for bit, over a whole run for every decay kind."""
+    from paper_2407_04272_amd import binding as b
+    x = _payload(5, 256, 16, 3)
+    x[1, 128:] = x[1, :128]                     # duplicate rows
+    x[2] = np.round(x[2] * 200) / 200           # rows that merge once quantised: another class
+    d = to_device(x)
+    ctx = b.Context(b.make_config(b.F32, *x.shape))
+    probe = np.full(5, 1e-3, np.float32)
+    st = ctx.stats(d, probe)
+    ost = oracle.stats(x, probe)
+    for kind in (b.DECAY_NONE, b.DECAY_STEPWISE, b.DECAY_DROP, b.DECAY_LINEAR, b.DECAY_LOG):
+        for mode in (0, 1):
+            p = b.ControllerParams(mode=mode, decay_kind=kind, global_eb=0.02, alpha=5.0 / 3.0, beta=3.0, h_large=0.0,
+                                   h_small=0.05, decay_start=7, decay_len=61, decay_steps=5, reserved=0, decay_mult0=2.5,
+                                   eb_min=0.0, eb_max=0.0, rel_floor=0.0)
+            op = oracle.ControllerParams(**{f[0]: getattr(p, f[0]) for f in p._fields_})
+            for it in range(0, 90):
+                ebs, cls = ctx.set_error_bounds(stats=st, params=p, iteration=it)
+                oeb, ocls = oracle.controller(ost, op, it)
+                assert np.array_equal(ebs.view(np.uint32), oeb.view(np.uint32)), (kind, mode, it)
+                assert np.array_equal(cls, ocls)

@@ -178,6 +178,27 @@ def test_drop_schedule():
     assert m[:40] == [3.0] * 40 and m[40:] == [1.0] * 40
 
 
+def test_linear_and_logarithmic_schedules():
+    """The paper names a logarithmic decay next to the stepwise one and fixes only the end points (k x base at the
+    start of the initial phase, base after it).  Pinned here: those end points, monotone decrease, the straight line
+    for LINEAR, and for LOG the closed form on a few points plus its shape (below the line: fast at first)."""
+    import math
+    for M0, I, i0 in [(2.0, 100, 0), (3.0, 37, 10), (1.5, 8, 3)]:
+        lin = [oracle.decay_multiplier(_params(decay_kind=3, decay_mult0=M0, decay_len=I, decay_start=i0), i)
+               for i in range(0, i0 + I + 20)]
+        lg = [oracle.decay_multiplier(_params(decay_kind=4, decay_mult0=M0, decay_len=I, decay_start=i0), i)
+              for i in range(0, i0 + I + 20)]
+        for m in (lin, lg):
+            assert all(v == M0 for v in m[:i0 + 1]) and all(v == 1.0 for v in m[i0 + I:])
+            assert all(a >= b for a, b in zip(m, m[1:]))
+            assert all(1.0 <= v <= M0 for v in m)
+        for k in range(I):
+            assert abs(lin[i0 + k] - (M0 - (M0 - 1.0) * k / I)) < 1e-15
+            assert abs(lg[i0 + k] - (M0 - (M0 - 1.0) * math.log1p(k) / math.log1p(I))) < 1e-12
+        assert all(lg[i0 + k] < lin[i0 + k] for k in range(1, I))     # concave in log(1 + k): drops fast at first
+        assert lg[i0 + I - 1] > 1.0                                    # reaches the base only at the end of the phase
+
+
 def test_controller_bound_arithmetic():
     st = _stats_with([(100, 100), (100, 50), (100, 100)], lo=-0.5, hi=1.5)
     # absolute, stepwise at iteration 0 -> doubled
