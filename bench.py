@@ -21,7 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-CARRY_TRAFFIC = 590.7e6  # HBM bytes per launch of the single-pass kernel on cfg3, from the counter runs
+CARRY_TRAFFIC = 591.6e6  # HBM bytes per launch of the single-pass kernel on cfg3, from the counter runs
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
 
@@ -160,7 +160,7 @@ def main():
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     # HBM bytes per launch of the dominant kernel, from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
     # profiles/cfg3_hbm_traffic_pmc.txt (they cannot be collected from inside this process); known for this workload only
-    measured_traffic = {"k_encode": 235.2e6, "k_hist": 671.8e6, "k_decode": 597.4e6, "k_encode_carry": CARRY_TRAFFIC}
+    measured_traffic = {"k_encode": 241.1e6, "k_hist": 671.8e6, "k_decode": 597.4e6, "k_encode_carry": CARRY_TRAFFIC}
     traffic = measured_traffic.get(dom) if (args.workload == "cfg3" and args.chunk_symbols == 256) else None
     result = {
         "metric": "compress+decompress round-trip GB/s of uncompressed fp32 payload, 1 MI355X",
@@ -343,7 +343,74 @@ def all_workloads(b, torch, np, W, dev, S, with_oracle):
         rows.append(_measure(b, torch, np, "5: forward payload, " + tag, fwd, ebs, S, with_oracle))
     ebs = bounds(bwd, gen.meta, 1, probe_abs=1e-5, iteration=100, decay=True)
     rows.append(_measure(b, torch, np, "5: backward payload N(0, 1e-4)", bwd, ebs, S, with_oracle))
+    del gen, fwd, bwd
+    torch.cuda.empty_cache()
+    rows.append(_run_schedule(b, torch, np, W, dev, S))
     return rows
+
+
+def _run_schedule(b, torch, np, W, dev, S, iterations=200):
+    """Workload 5 as a run: forward and backward payload of every iteration compressed and decompressed, bounds from
+    the statistics of iteration 0 and the stepwise schedule; both compress paths over the same sequence of payloads."""
+    row = {"workload": f"5: {iterations} iterations, forward + backward payload each, stepwise schedule"}
+    for key, flags in (("", 0), ("carried_", b.FLAG_CARRY_CODEBOOK)):
+        gen = W.Workload5(device=dev)
+        T, B, D = gen.T, gen.B, gen.D
+        nbytes = T * B * D * 4
+        cf = b.Context(b.make_config(b.F32, T, B, D, chunk_symbols=S, flags=flags))
+        cb = b.Context(b.make_config(b.F32, T, B, D, chunk_symbols=S, flags=flags))
+        out = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
+        sizes = torch.zeros(1 + T, dtype=torch.int64, device=dev)
+        rec = torch.zeros((T, B, D), dtype=torch.float32, device=dev)
+        p = b.ControllerParams(mode=1, decay_kind=b.DECAY_STEPWISE, global_eb=gen.meta["global_eb"], alpha=gen.meta["alpha"],
+                               beta=gen.meta["beta"], h_large=0.0, h_small=0.05, decay_start=0, decay_len=gen.meta["decay_len"],
+                               decay_steps=gen.meta["decay_steps"], reserved=0, decay_mult0=gen.meta["decay_mult0"],
+                               eb_min=0.0, eb_max=0.0, rel_floor=0.0)
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(iterations)]
+        comp_bytes = 0
+        worst = 0.0
+        for it in range(iterations):
+            fwd, bwd = gen.step()
+            if it == 0:
+                lo, hi = fwd.amin(dim=(1, 2)).cpu().numpy(), fwd.amax(dim=(1, 2)).cpu().numpy()
+                stf = cf.stats(fwd, (0.03 * (hi - lo)).astype(np.float32))
+                stb = cb.stats(bwd, np.full(T, 1e-5, np.float32))
+                _, cls0 = cf.set_error_bounds(stats=stf, params=p, iteration=0)
+            ebf, _ = cf.set_error_bounds(stats=stf, params=p, class_override=cls0, iteration=it)
+            ebb, _ = cb.set_error_bounds(stats=stb, params=p, iteration=it)
+            e = ev[it]
+            e[0].record()
+            cf.compress(fwd, out, sizes)
+            e[1].record()
+            cf.decompress(out, out.numel(), rec)
+            e[2].record()
+            if it % 20 == 0 or it == iterations - 1:   # the bound, on the way (the parity tests check every element)
+                comp_bytes_f = int(sizes[0].item())
+                eb_t = torch.from_numpy(ebf.astype(np.float64)).to(dev).view(T, 1, 1)
+                worst = max(worst, float(((fwd.double() - rec.double()).abs() / eb_t).max().item()))
+            else:
+                comp_bytes_f = None
+            e[3].record()
+            cb.compress(bwd, out, sizes)
+            e[4].record()
+            cb.decompress(out, out.numel(), rec)
+            e[5].record()
+            if comp_bytes_f is not None:
+                comp_bytes += comp_bytes_f + int(sizes[0].item())
+        torch.cuda.synchronize()
+        assert cf.sync_status() == 0 and cb.sync_status() == 0
+        c_ms = sum(e[0].elapsed_time(e[1]) + e[3].elapsed_time(e[4]) for e in ev)
+        d_ms = sum(e[1].elapsed_time(e[2]) + e[4].elapsed_time(e[5]) for e in ev)
+        n_sampled = len([it for it in range(iterations) if it % 20 == 0 or it == iterations - 1])
+        moved = 2.0 * nbytes * iterations
+        row[key + "compress_GBps"] = round(moved / c_ms / 1e6, 2)
+        row[key + "decompress_GBps"] = round(moved / d_ms / 1e6, 2)
+        row[key + "compression_ratio_sampled"] = round(2.0 * nbytes * n_sampled / comp_bytes, 3)
+        row[key + "worst_error_over_bound"] = round(worst, 6)
+        del gen, cf, cb
+        torch.cuda.empty_cache()
+    row["payload_MiB"] = round(2.0 * nbytes * iterations / 2 ** 20, 1)
+    return row
 
 
 if __name__ == "__main__":
