@@ -148,6 +148,21 @@ def test_small_alphabet_and_constant_table():
         prev = o.hist
 
 
+def test_wide_alphabet_chain():
+    """Radius 2048 and bins much narrower than the data: most symbols lie outside the 255-symbol window around bin 0
+    (counted and looked up one by one), and chunks are far longer than their LDS words."""
+    T, B, D, S = 2, 1024, 32, 128
+    ch = _Chain((T, B, D), np.float32, S, Rr=2048, LMAX=12)
+    ebs = np.array([2e-5, 1e-4], np.float32)
+    prev = None
+    for k in range(3):
+        x = _batch(T, B, D, 40 + k, sigma=0.01)
+        g = ch.compress(x, ebs)
+        o = oracle.compress(x, ebs, 2048, S, 12, carry_hist=prev, want_hist=True)
+        _same(g, o, x, f"call {k}")
+        prev = o.hist
+
+
 def test_workload3_consecutive_iterations_full_size():
     """The benchmark shape: iteration i+1 coded with iteration i's codebook, byte for byte against the oracle."""
     import torch
