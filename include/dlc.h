@@ -77,7 +77,22 @@ typedef struct {
     int32_t chunk_symbols; /* S: symbols per chunk, one of 64, 128, 256 */
     int32_t max_code_len;  /* LMAX <= 12, 2^LMAX >= 2R */
     int32_t flags;         /* 0, or DLC_FLAG_* */
+    int32_t num_dest;      /* destinations the payload is split over, 1..4096 (0 counts as 1); see below */
 } dlc_config;
+
+/* Per-destination buffers (Section III-E: the payload a GPU sends is cut along the batch axis, one piece per
+ * receiving GPU, and the compressor writes every piece's compressed form straight into the send buffer in one
+ * launch sequence).  With num_dest = n > 1:
+ *   - `batch` is the number of rows of ONE destination's piece; the payload is [n][num_tables][batch][dim], i.e. the
+ *     destination-major layout of an all-to-all send buffer;
+ *   - dlc_compress writes n complete containers, each exactly what a context with num_dest = 1 and the same other
+ *     fields would write for that piece (own code histograms and codebooks per piece, the per-table bounds shared);
+ *     container d starts at byte d * stride of d_out, stride = (out_capacity / n) rounded down to a multiple of 256,
+ *     and must fit into its stride.  The pieces are therefore at fixed displacements, as a variable-size all-to-all
+ *     takes them; their sizes come back in d_out_bytes (see dlc_compress);
+ *   - a destination that does not fit gets size 0 and DLC_ECAPACITY is recorded; the others are still valid;
+ *   - dlc_set_error_bounds still takes num_tables bounds; dlc_decompress and dlc_stats want num_dest = 1 (a
+ *     receiver decodes each container it got with a context of the piece's geometry). */
 
 /* dlc_config.flags: compress with the fused persistent kernel, which reads the payload once and builds each
  * table's codebook inside the kernel, instead of the separate histogram, codebook and encode kernels.  Both
@@ -172,7 +187,9 @@ int dlc_set_error_bounds(dlc_ctx* ctx, const dlc_table_stats* h_stats, const dlc
  * single launch sequence writing all tables into one buffer at scanned offsets).
  *   d_payload    DEVICE  [T][B][D], 16-byte aligned
  *   d_out        DEVICE  container, 16-byte aligned, `out_capacity` bytes; never written past capacity
- *   d_out_bytes  DEVICE  uint64[1+T]: [0] container bytes (0 on failure), [1+t] bytes attributable to table t
+ *   d_out_bytes  DEVICE  uint64[1+T]: [0] container bytes (0 on failure), [1+t] bytes attributable to table t.
+ *                        With num_dest = n > 1: uint64[1 + n*T + n]: [0] sum of the n containers' sizes (0 if any failed),
+ *                        [1 + d*T + t] table t of destination d, [1 + n*T + d] size of destination d's container
  * Asynchronous on `stream`.  DLC_ESTATE if bounds were never set.  Capacity overflow is detected on the GPU
  * before the overflowing write: d_out_bytes[0] = 0 and dlc_sync_status returns DLC_ECAPACITY.
  */

@@ -22,7 +22,7 @@ DECAY_NONE, DECAY_STEPWISE, DECAY_DROP, DECAY_LINEAR, DECAY_LOG = 0, 1, 2, 3, 4
 class Config(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("num_tables", C.c_int32), ("batch", C.c_int64), ("dim", C.c_int64),
                 ("radius", C.c_int32), ("chunk_symbols", C.c_int32), ("max_code_len", C.c_int32),
-                ("flags", C.c_int32)]
+                ("flags", C.c_int32), ("num_dest", C.c_int32)]
 
 
 class TableStats(C.Structure):
@@ -96,8 +96,9 @@ FLAG_FUSED = 1
 FLAG_CARRY_CODEBOOK = 2
 
 
-def make_config(dtype, T, B, D, radius=512, chunk_symbols=256, max_code_len=12, flags=0) -> Config:
-    return Config(dtype, T, B, D, radius, chunk_symbols, max_code_len, flags)
+def make_config(dtype, T, B, D, radius=512, chunk_symbols=256, max_code_len=12, flags=0, num_dest=1) -> Config:
+    """num_dest > 1: B is the batch of ONE destination's piece, the payload is [num_dest][T][B][D]."""
+    return Config(dtype, T, B, D, radius, chunk_symbols, max_code_len, flags, num_dest)
 
 
 def dlc_compress_bound(cfg: Config) -> int:
@@ -127,6 +128,7 @@ class Context:
         self._h = C.c_void_p()
         _check(lib().dlc_create(C.byref(self._h), C.byref(cfg)), "dlc_create")
         self.T, self.B, self.D = cfg.num_tables, cfg.batch, cfg.dim
+        self.ND = max(1, cfg.num_dest)
         self.K = 2 * cfg.radius
 
     def close(self):
@@ -186,13 +188,13 @@ class Context:
                                   _stream_ptr(stream)), "dlc_quantize")
 
     def read_histogram(self, stream=None) -> np.ndarray:
-        h = np.zeros((self.T, self.K), np.uint32)
+        h = np.zeros((self.ND * self.T, self.K), np.uint32)
         _check(lib().dlc_read_histogram(self._h, _np_ptr(h), _stream_ptr(stream)), "dlc_read_histogram")
         return h
 
     def read_codebook(self, stream=None):
-        ln = np.zeros((self.T, self.K), np.uint8)
-        code = np.zeros((self.T, self.K), np.uint16)
+        ln = np.zeros((self.ND * self.T, self.K), np.uint8)
+        code = np.zeros((self.ND * self.T, self.K), np.uint16)
         _check(lib().dlc_read_codebook(self._h, _np_ptr(ln), _np_ptr(code), _stream_ptr(stream)), "dlc_read_codebook")
         return ln, code
 

@@ -86,12 +86,18 @@ static bool make_geom(const dlc_config* c, Geom* g) {
     if (S != 64 && S != 128 && S != 256) return false;
     if (c->flags & ~(int32_t)(DLC_FLAG_FUSED | DLC_FLAG_CARRY_CODEBOOK)) return false;
     if ((c->flags & DLC_FLAG_FUSED) && (c->flags & DLC_FLAG_CARRY_CODEBOOK)) return false;
+    const int64_t nd = c->num_dest == 0 ? 1 : c->num_dest;  // 0: a zero-initialised field means one destination
+    if (nd < 1 || nd > 4096) return false;
+    if (nd > 1 && (c->flags & DLC_FLAG_FUSED)) return false;
+    const uint64_t T = (uint64_t)c->num_tables * (uint64_t)nd;  // tables of the whole payload
+    if (T > 0x7FFFFFFFull) return false;
     const uint64_t GS = (uint64_t)kW * S;
     const uint64_t G = (n + GS - 1) / GS;
-    const uint64_t NG = G * (uint64_t)c->num_tables;
+    const uint64_t NG = G * T;
     if (NG * GS > 0xFFFFFFFFull) return false;                                 // element positions are 32-bit
     if (NG * kW * (((uint64_t)S * L + 31) / 32) > 0xFFFFFFFFull) return false;  // word offsets are 32-bit
-    g->T = (uint32_t)c->num_tables; g->B = (uint32_t)c->batch; g->D = (uint32_t)c->dim; g->n = (uint32_t)n;
+    g->ND = (uint32_t)nd; g->TD = (uint32_t)c->num_tables;
+    g->T = (uint32_t)T; g->B = (uint32_t)c->batch; g->D = (uint32_t)c->dim; g->n = (uint32_t)n;
     g->G = (uint32_t)G; g->NG = (uint32_t)NG; g->S = (uint32_t)S; g->R = (uint32_t)R; g->K = 2u * R;
     g->LMAX = (uint32_t)L; g->dtype = (uint32_t)c->dtype; g->es = c->dtype == DLC_F16 ? 2u : 4u;
     g->vec = (n % 4 == 0) ? 1u : 0u;
@@ -105,9 +111,10 @@ extern "C" size_t dlc_compress_bound(const dlc_config* cfg) {
     if (!make_geom(cfg, &g)) return 0;
     const FixedLayout F = fixed_layout(g);
     const size_t wpc = ((size_t)g.S * g.LMAX + 31) / 32;
-    // every chunk full, every element an escape, every symbol used
-    const size_t off_cb = a16(F.off_payload + 4 * wpc * kW * g.NG + 8 * (size_t)g.n * g.T);
-    return off_cb + (size_t)g.T * ((g.K + 3) & ~3u);
+    // one container: every chunk full, every element an escape, every symbol used
+    const size_t off_cb = a16(F.off_payload + 4 * wpc * kW * g.TD * g.G + 8 * (size_t)g.n * g.TD);
+    const size_t one = off_cb + (size_t)g.TD * ((g.K + 3) & ~3u);
+    return g.ND == 1 ? one : (size_t)g.ND * a256(one);  // several: one every `capacity / num_dest` bytes, see dlc_compress
 }
 
 // carve the workspace; with base == nullptr only sizes are computed
@@ -245,7 +252,7 @@ extern "C" int dlc_set_error_bounds(dlc_ctx* c, const dlc_table_stats* st, const
                                     const int32_t* cls_override, int64_t iteration, float* eb, int32_t* cls_out,
                                     void* stream) {
     if (!c || !eb) return DLC_EINVAL;
-    const uint32_t T = c->g.T;
+    const uint32_t T = c->g.TD;  // a bound per table; the destinations share them
     if (st) {
         if (!p) return DLC_EINVAL;
         if (p->decay_kind < DLC_DECAY_NONE || p->decay_kind > DLC_DECAY_LOG || (p->mode != 0 && p->mode != 1))
@@ -279,9 +286,10 @@ extern "C" int dlc_set_error_bounds(dlc_ctx* c, const dlc_table_stats* st, const
     const int slot = c->pin_next;
     c->pin_next = (slot + 1) % dlc_ctx::kRing;
     if (c->pin_used[slot] && hipEventSynchronize(c->pin_ev[slot]) != hipSuccess) return DLC_EHIP;  // copy 16 calls ago
-    QParam* h = c->pin + (size_t)slot * T;
-    for (uint32_t t = 0; t < T; ++t) h[t] = make_qparam(eb[t]);
-    if (hipMemcpyAsync(c->ws.qp, h, sizeof(QParam) * T, hipMemcpyHostToDevice, (hipStream_t)stream) != hipSuccess)
+    QParam* h = c->pin + (size_t)slot * c->g.T;
+    for (uint32_t d = 0; d < c->g.ND; ++d)
+        for (uint32_t t = 0; t < T; ++t) h[(size_t)d * T + t] = make_qparam(eb[t]);
+    if (hipMemcpyAsync(c->ws.qp, h, sizeof(QParam) * c->g.T, hipMemcpyHostToDevice, (hipStream_t)stream) != hipSuccess)
         return DLC_EHIP;
     if (hipEventRecord(c->pin_ev[slot], (hipStream_t)stream) != hipSuccess) return DLC_EHIP;
     c->pin_used[slot] = true;
@@ -299,6 +307,7 @@ extern "C" int dlc_compress(dlc_ctx* c, const void* d_payload, void* d_out, size
     if (!c || !aligned16(d_payload) || !aligned16(d_out) || !d_out_bytes || (((uintptr_t)d_out_bytes) & 7u))
         return DLC_EINVAL;
     if (!c->bounds_set) return DLC_ESTATE;
+    if (c->g.ND > 1) cap = (cap / c->g.ND) & ~size_t(255);  // per destination: container d starts at d * cap
     if (cap < fixed_layout(c->g).off_payload) return DLC_ECAPACITY;  // the fixed-size sections must fit
     c->epoch += 1;
     if (c->epoch >= (1ull << 30)) {  // look-back records carry a 30-bit call counter
@@ -313,6 +322,7 @@ extern "C" int dlc_compress(dlc_ctx* c, const void* d_payload, void* d_out, size
 
 extern "C" int dlc_decompress(dlc_ctx* c, const void* d_comp, size_t comp_bytes, void* d_out, size_t cap, void* stream) {
     if (!c || !aligned16(d_comp) || !aligned16(d_out)) return DLC_EINVAL;
+    if (c->g.ND != 1) return DLC_ESTATE;  // a container holds one destination's share: decode it with such a context
     if (cap < (size_t)c->g.n * c->g.T * c->g.es) return DLC_ECAPACITY;
     if (comp_bytes < kHeaderBytes) return DLC_ECORRUPT;
     hipError_t e = launch_decompress(c->g, (const uint8_t*)d_comp, comp_bytes, d_out, c->ws, c->prof.level, &c->prof,
@@ -341,6 +351,7 @@ static float ord_dec(uint32_t o) {
 extern "C" int dlc_stats(dlc_ctx* c, const void* d_payload, const float* probe_eb, dlc_table_stats* out, void* stream) {
     if (!c || !aligned16(d_payload) || !probe_eb || !out) return DLC_EINVAL;
     const Geom& g = c->g;
+    if (g.ND != 1) return DLC_ESTATE;  // a table's statistics are over its whole batch: use a context that is not split
     for (uint32_t t = 0; t < g.T; ++t)
         if (!good_eb(probe_eb[t])) return DLC_EINVAL;
     hipStream_t s = (hipStream_t)stream;

@@ -295,6 +295,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
     __syncthreads();
     const uint32_t wg = __builtin_amdgcn_readfirstlane(s_wg);
     const uint32_t t = wg / bpt, b = wg % bpt;
+    // the destination this table belongs to: its container starts `capacity` bytes after the previous one, its
+    // groups are numbered and its words are placed from 0, so the scan over work-groups starts anew at its first
+    const uint32_t dst = t / g.TD, tl = t - dst * g.TD;
+    const uint32_t dom0 = dst * g.TD * bpt;
+    out += (uint64_t)dst * capacity;
     const uint32_t win_lo = win_lo_of(g.R);
     const uint16_t* enc_t = enc + (size_t)t * g.K;
     uint32_t* hist_t = hist + (size_t)t * g.K;
@@ -308,7 +313,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
     __syncthreads();
     const uint32_t grp = b * 4 + wave;
     const bool active = grp < g.G;  // uniform over the wavefront; an idle wavefront only takes part in the barriers
-    const uint32_t gid = t * g.G + (active ? grp : 0u);
+    const uint32_t gid = tl * g.G + (active ? grp : 0u);  // group number inside the container
     const uint8_t* tab = static_cast<const uint8_t*>(payload) + (size_t)t * g.n * g.es;
     const uint32_t gstart = grp * (kW * (uint32_t)S);
     CarryEnv E;
@@ -367,8 +372,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
     //   in a 64-word scratch, and a running maximum spreads it over the words that follow (what the scratch
     //   still holds from earlier segments is smaller than the value carried in, so it never needs clearing).
     LookBack L;
-    lb_init(L, wg);
-    if (wave == 0) lb_publish_aggregate(state, epoch, wg, wg_total, lane);
+    lb_init(L, wg, dom0);
+    if (wave == 0) lb_publish_aggregate(state, epoch, wg, wg_total, lane, dom0);
     uint32_t wb[CAP];
     if (active && !spilled) {
         uint32_t* const heads = stage + CAP * 65u;  // the row that takes what does not fit is free now (nothing spilled)
@@ -414,7 +419,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
     uint32_t excl = s_excl;
     for (uint32_t k = 0; k < wave; ++k) excl += s_tot[k];
     if (F.off_payload + 4ull * ((uint64_t)excl + total) > capacity) {
-        if (active && !dead && lane == 0) { set_status(ctrl, DLC_ECAPACITY); ctrl->abort = 1; }
+        if (active && !dead && lane == 0) { set_status(ctrl, DLC_ECAPACITY); atomicOr(&ctrl->abort, kAbortCapacity); }
         dead = true;
     }
     if (!active) return;

@@ -362,14 +362,15 @@ constexpr uint32_t kSpinLimit = 1u << 22;
 // the work-groups that run at the same time is what bounds a streaming kernel that places its output by such a
 // scan, so the records are few and the steps wide.  Publishes this work-group's records.  Called by one whole
 // wavefront.
+// dom0: the first work-group of this work-group's scan domain (a destination's container: offsets start at 0 there).
 __device__ __forceinline__ uint32_t wg_scan(uint64_t* state, uint64_t epoch, uint32_t wg, uint32_t total, uint32_t lane,
-                                            Ctrl* ctrl, bool* dead) {
+                                            Ctrl* ctrl, bool* dead, uint32_t dom0 = 0) {
     const uint64_t tag = epoch << 34;
     if (lane == 0)
-        __hip_atomic_store(&state[wg], tag | ((uint64_t)(wg == 0 ? kFlagPrefix : kFlagAgg) << 32) | total,
+        __hip_atomic_store(&state[wg], tag | ((uint64_t)(wg == dom0 ? kFlagPrefix : kFlagAgg) << 32) | total,
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     uint32_t excl = 0;
-    if (wg > 0) {
+    if (wg > dom0) {
         int64_t pos = (int64_t)wg - 1;  // nearest record not yet added
         uint32_t spins = 0;
         for (;;) {
@@ -380,8 +381,8 @@ __device__ __forceinline__ uint32_t wg_scan(uint64_t* state, uint64_t epoch, uin
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const int64_t my = pos - (int64_t)(lane * 4u + (uint32_t)k);
-                const uint64_t sv = my >= 0 ? __hip_atomic_load(&state[my], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                            : (tag | ((uint64_t)kFlagPrefix << 32));
+                const uint64_t sv = my >= (int64_t)dom0 ? __hip_atomic_load(&state[my], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                                        : (tag | ((uint64_t)kFlagPrefix << 32));
                 const uint32_t flag = (sv >> 34) == epoch ? (uint32_t)(sv >> 32) & 3u : 0u;
                 if (!has_p) {
                     hole = hole || flag == 0u;
@@ -393,7 +394,7 @@ __device__ __forceinline__ uint32_t wg_scan(uint64_t* state, uint64_t epoch, uin
             const uint32_t first = pm ? (uint32_t)__ffsll((unsigned long long)pm) - 1u : 64u;  // lane of the nearest prefix
             if (__ballot(hole && lane <= first) != 0ull) {  // something nearer than that prefix is not published yet
                 if (++spins > kSpinLimit) {  // never expected; the bound only guarantees termination
-                    if (lane == 0) { set_status(ctrl, DLC_ESTATE); ctrl->abort = 1; }
+                    if (lane == 0) { set_status(ctrl, DLC_ESTATE); atomicOr(&ctrl->abort, kAbortInternal); }
                     *dead = true;
                     break;
                 }
@@ -416,6 +417,7 @@ __device__ __forceinline__ uint32_t wg_scan(uint64_t* state, uint64_t epoch, uin
 // live in device-coherent memory, a few hundred nanoseconds away) costs nothing.  The caller has published its
 // own aggregate record before the first step (publish_aggregate) and publishes the prefix when done.
 struct LookBack {
+    int64_t dom0;     // first work-group of the scan domain (records before it count as an empty prefix)
     int64_t pos;      // nearest record not yet added
     uint32_t excl;    // sum so far
     uint32_t spins;
@@ -423,16 +425,18 @@ struct LookBack {
     uint64_t sv[4];
 };
 
-__device__ __forceinline__ void lb_publish_aggregate(uint64_t* state, uint64_t epoch, uint32_t wg, uint32_t total, uint32_t lane) {
+__device__ __forceinline__ void lb_publish_aggregate(uint64_t* state, uint64_t epoch, uint32_t wg, uint32_t total, uint32_t lane,
+                                                     uint32_t dom0 = 0) {
     if (lane == 0)
-        __hip_atomic_store(&state[wg], (epoch << 34) | ((uint64_t)(wg == 0 ? kFlagPrefix : kFlagAgg) << 32) | total,
+        __hip_atomic_store(&state[wg], (epoch << 34) | ((uint64_t)(wg == dom0 ? kFlagPrefix : kFlagAgg) << 32) | total,
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ void lb_init(LookBack& L, uint32_t wg) {
+__device__ __forceinline__ void lb_init(LookBack& L, uint32_t wg, uint32_t dom0 = 0) {
+    L.dom0 = (int64_t)dom0;
     L.pos = (int64_t)wg - 1;
     L.excl = 0;
     L.spins = 0;
-    L.done = wg == 0;
+    L.done = wg == dom0;
     L.failed = false;
     L.pending = false;
 }
@@ -440,8 +444,8 @@ __device__ __forceinline__ void lb_issue(LookBack& L, const uint64_t* state, uin
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int64_t my = L.pos - (int64_t)(lane * 4u + (uint32_t)k);
-        L.sv[k] = my >= 0 ? __hip_atomic_load(&state[my], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                          : ((epoch << 34) | ((uint64_t)kFlagPrefix << 32));  // before the first work-group: an empty prefix
+        L.sv[k] = my >= L.dom0 ? __hip_atomic_load(&state[my], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                               : ((epoch << 34) | ((uint64_t)kFlagPrefix << 32));  // before the domain's first work-group: an empty prefix
     }
     L.pending = true;
 }
@@ -476,14 +480,14 @@ __device__ __forceinline__ void lb_finish(LookBack& L, uint64_t* state, uint64_t
         if (!L.pending) lb_issue(L, state, epoch, lane);
         if (!lb_consume(L, epoch, lane)) {
             if (++L.spins > kSpinLimit) {  // never expected; the bound only guarantees termination
-                if (lane == 0) { set_status(ctrl, DLC_ESTATE); ctrl->abort = 1; }
+                if (lane == 0) { set_status(ctrl, DLC_ESTATE); atomicOr(&ctrl->abort, kAbortInternal); }
                 L.failed = true;
             } else {
                 __builtin_amdgcn_s_sleep(1);
             }
         }
     }
-    if (wg > 0 && !L.failed && lane == 0)
+    if ((int64_t)wg > L.dom0 && !L.failed && lane == 0)
         __hip_atomic_store(&state[wg], (epoch << 34) | ((uint64_t)kFlagPrefix << 32) | (uint32_t)(L.excl + total),
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }

@@ -213,17 +213,28 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
     __shared__ uint32_t s_lo[1024], s_nl[1024];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const bool first = blockIdx.x == 0;
-    const uint64_t words = word_end[g.T - 1];
+    // blockIdx.y: the destination whose container this work-group finishes; everything below is that container's
+    const uint32_t dst = blockIdx.y, T = g.TD;
+    tmeta += (size_t)dst * T;
+    lens += (size_t)dst * T * g.K;
+    qp += (size_t)dst * T;
+    word_start += (size_t)dst * T;
+    word_end += (size_t)dst * T;
+    if (esc_count) esc_count += (size_t)dst * T;
+    out += (uint64_t)dst * capacity;
+    uint64_t* const table_bytes = out_bytes + 1 + (size_t)dst * T;
+    const uint64_t words = word_end[T - 1];
     const uint64_t off_cb = a16(F.off_payload + 4ull * words);
-    // (only the first work-group looks at the abort flag, which it clears at the end; the others are kept inside the
-    // output by the capacity test alone)
-    const bool aborted = first && ctrl->abort != 0;
+    // an internal failure of the encode kernel spoils every container; one that did not fit spoils only itself, and
+    // the capacity test below fails for it whenever the encode kernel's did.  (The flag is cleared by the last
+    // destination to finish, so every destination's first work-group can still read it.)
+    const bool aborted = first && (__hip_atomic_load(&ctrl->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kAbortInternal) != 0;
     uint64_t cb_carry = 0, nout_carry = 0;
-    for (uint32_t base = 0; base < g.T; base += 1024) {
+    for (uint32_t base = 0; base < T; base += 1024) {
         const uint32_t t = base + tid;
         TMeta m;
         uint32_t cb = 0, no = 0, nl = 0;
-        if (t < g.T) {
+        if (t < T) {
             m = tmeta[t];
             if (first && esc_count) {  // single-pass path: the codebook is older than the payload, the escapes were counted by the encode kernel
                 m.n_outliers = esc_count[t];
@@ -248,7 +259,7 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
         }
         __syncthreads();
         if (s_abort) break;  // uniform
-        const uint32_t nt = min(1024u, g.T - base);
+        const uint32_t nt = min(1024u, T - base);
         // the blocks of this work-group's tables, a wavefront per table, four bytes per lane (the blocks start on
         // 4-byte boundaries and are padded to them)
         for (uint32_t lt = blockIdx.x * 16u + wave; lt < nt; lt += gridDim.x * 16u) {
@@ -265,7 +276,7 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
                 dst[wd] = v;
             }
         }
-        if (first && t < g.T) {
+        if (first && t < T) {
             const uint64_t w0 = word_start[t], w1 = word_end[t];
             uint8_t* d = out + kHeaderBytes + (uint64_t)kDirBytes * t;
             uint32_t* d32 = reinterpret_cast<uint32_t*>(d);
@@ -273,44 +284,69 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
             d32[5] = g.G;
             uint64_t* d64 = reinterpret_cast<uint64_t*>(d + 24);
             d64[0] = off_cb + cb_carry + cb_ex; d64[1] = 0; d64[2] = w0; d64[3] = w1 - w0;
-            out_bytes[1 + t] = 4ull * (w1 - w0) + cb + (uint64_t)(kW + 4u) * g.G + kDirBytes;
+            table_bytes[t] = 4ull * (w1 - w0) + cb + (uint64_t)(kW + 4u) * g.G + kDirBytes;
         }
         cb_carry += cb_tot;
         nout_carry += no_tot;
         __syncthreads();
     }
     if (!first) return;
+    uint64_t container_bytes = 0;  // of this destination; 0 = it did not fit
     if (s_abort) {
         if (tid == 0 && !aborted) set_status(ctrl, DLC_ECAPACITY);
-        for (uint32_t t = tid; t < g.T + 1; t += 1024) out_bytes[t] = 0;
+        for (uint32_t t = tid; t < T; t += 1024) table_bytes[t] = 0;
         if (esc_count)  // whatever the passes after the failing one have not cleared
-            for (uint32_t t = tid; t < g.T; t += 1024) esc_count[t] = 0;
+            for (uint32_t t = tid; t < T; t += 1024) esc_count[t] = 0;
     } else {
         // padding between sections
-        const uint64_t e0 = kHeaderBytes + (uint64_t)kDirBytes * g.T;
+        const uint64_t e0 = kHeaderBytes + (uint64_t)kDirBytes * T;
         for (uint64_t i = e0 + tid; i < F.off_group; i += 1024) out[i] = 0;
-        const uint64_t e1 = F.off_group + 4ull * g.NG;
+        const uint64_t e1 = F.off_group + 4ull * T * g.G;
         for (uint64_t i = e1 + tid; i < F.off_chunk; i += 1024) out[i] = 0;
         const uint64_t e2 = F.off_payload + 4ull * words;
         for (uint64_t i = e2 + tid; i < off_cb; i += 1024) out[i] = 0;
         if (tid == 0) {
             uint32_t* h = reinterpret_cast<uint32_t*>(out);
-            h[H_MAGIC] = kMagic; h[H_VERSION] = kVersion; h[H_DTYPE] = g.dtype; h[H_T] = g.T; h[H_B] = g.B; h[H_D] = g.D;
-            h[H_R] = g.R; h[H_S] = g.S; h[H_LMAX] = g.LMAX; h[H_W] = kW; h[H_V] = kV; h[H_NG] = g.NG;
+            h[H_MAGIC] = kMagic; h[H_VERSION] = kVersion; h[H_DTYPE] = g.dtype; h[H_T] = T; h[H_B] = g.B; h[H_D] = g.D;
+            h[H_R] = g.R; h[H_S] = g.S; h[H_LMAX] = g.LMAX; h[H_W] = kW; h[H_V] = kV; h[H_NG] = T * g.G;
             uint64_t* q = reinterpret_cast<uint64_t*>(out);
             q[HQ_NOUT] = nout_carry; q[HQ_WORDS] = words; q[HQ_OFF_GROUP] = F.off_group; q[HQ_OFF_CHUNK] = F.off_chunk;
             q[HQ_OFF_PAYLOAD] = F.off_payload; q[HQ_OFF_CB] = off_cb;
             const uint64_t total = off_cb + cb_carry;
             q[HQ_TOTAL] = total; q[HQ_TOTAL + 1] = 0; q[HQ_TOTAL + 2] = 0; q[HQ_TOTAL + 3] = 0;
-            out_bytes[0] = total;
+            container_bytes = total;
         }
     }
+    if (tid != 0) return;
+    // sizes: one destination -> out_bytes[0] is its container's size.  Several -> every destination stores its size
+    // behind the per-table entries, and the last one to do so adds them up into out_bytes[0] (0 if any did not fit).
     // the next call starts with ticket 0 and no abort (the histograms were cleared by the codebook step)
-    if (tid == 0) { ctrl->ticket = 0; ctrl->abort = 0; }
+    if (g.ND == 1) {
+        out_bytes[0] = container_bytes;
+        ctrl->ticket = 0;
+        ctrl->abort = 0;
+    } else {
+        unsigned long long* dest_bytes = reinterpret_cast<unsigned long long*>(out_bytes + 1 + (size_t)g.ND * T);
+        __hip_atomic_store(&dest_bytes[dst], (unsigned long long)container_bytes, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (__hip_atomic_fetch_add(&ctrl->dest_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u == g.ND) {
+            unsigned long long sum = 0;
+            bool all = true;
+            for (uint32_t d = 0; d < g.ND; ++d) {
+                const unsigned long long b = __hip_atomic_load(&dest_bytes[d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                all = all && b != 0;
+                sum += b;
+            }
+            out_bytes[0] = all ? sum : 0;
+            __hip_atomic_store(&ctrl->dest_done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ctrl->ticket = 0;
+            __hip_atomic_store(&ctrl->abort, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
 }
 
 // work-groups of the finalize kernel: a wavefront per table, sixteen wavefronts per work-group
-static inline uint32_t finalize_grid(const Geom& g) { return std::min<uint32_t>((std::min<uint32_t>(g.T, 1024u) + 15u) / 16u, 64u); }
+static inline dim3 finalize_grid(const Geom& g) { return dim3(std::min<uint32_t>((std::min<uint32_t>(g.TD, 1024u) + 15u) / 16u, 64u), g.ND); }
 
 hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uint64_t capacity, uint64_t* out_bytes,
                            const Ws& w, uint64_t epoch, bool carry_ready, int pl, void* prof, hipStream_t s) {
@@ -327,7 +363,7 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         }
         if (prof_on(pl, P_CARRY)) prof_end(prof, P_CARRY, s);
         if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
-        hipLaunchKernelGGL(k_finalize, dim3(finalize_grid(g)), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
+        hipLaunchKernelGGL(k_finalize, finalize_grid(g), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
                            w.word_end, out, capacity, out_bytes, w.esc_count);
         if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
         if (prof_on(pl, P_CODEBOOK)) prof_begin(prof, P_CODEBOOK, s);
@@ -342,7 +378,7 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         if (prof_on(pl, P_FUSED)) prof_end(prof, P_FUSED, s);
         if (e != hipSuccess) return e;
         if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
-        hipLaunchKernelGGL(k_finalize, dim3(finalize_grid(g)), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
+        hipLaunchKernelGGL(k_finalize, finalize_grid(g), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
                            w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr);
         if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
         return hipGetLastError();
@@ -379,7 +415,7 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         if (prof_on(pl, P_ENCODE)) prof_end(prof, P_ENCODE, s);
     }
     if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
-    hipLaunchKernelGGL(k_finalize, dim3(finalize_grid(g)), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
+    hipLaunchKernelGGL(k_finalize, finalize_grid(g), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
                        w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr);
     if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
     if (w.carry != 0)  // the codebook the next call will use: this call's counts (kept as the copy), escape symbol included

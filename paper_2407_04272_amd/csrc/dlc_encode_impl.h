@@ -78,6 +78,11 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
     __syncthreads();
     const uint32_t wg = __builtin_amdgcn_readfirstlane(s_wg);
     const uint32_t t = wg / bpt, b = wg % bpt;
+    // the destination this table belongs to: its container starts `capacity` bytes after the previous one, its
+    // groups are numbered and its words are placed from 0, so the scan over work-groups starts anew at its first
+    const uint32_t dst = t / g.TD, tl = t - dst * g.TD;
+    const uint32_t dom0 = dst * g.TD * bpt;
+    out += (uint64_t)dst * capacity;
     DLC_ESTAMP(0);
     const uint32_t win_lo = win_lo_of(g.R);
     const uint16_t* enc_t = enc + (size_t)t * g.K;
@@ -90,7 +95,7 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
     __syncthreads();
     const uint32_t grp = b * 4 + wave;
     const bool active = grp < g.G;  // uniform over the wavefront; an idle wavefront only takes part in the barriers
-    const uint32_t gid = t * g.G + (active ? grp : 0u);
+    const uint32_t gid = tl * g.G + (active ? grp : 0u);  // group number inside the container
     const QParam q = qp[t];
     const float Rf = (float)g.R;
     const uint8_t* tab = static_cast<const uint8_t*>(payload) + (size_t)t * g.n * g.es;
@@ -188,8 +193,8 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
     const uint32_t wg_total = s_tot[0] + s_tot[1] + s_tot[2] + s_tot[3];
     const bool staged = max(max(s_ct[0], s_ct[1]), max(s_ct[2], s_ct[3])) <= kStageWords;  // uniform over the work-group
     LookBack L;
-    lb_init(L, wg);
-    if (wave == 0) lb_publish_aggregate(state, epoch, wg, wg_total, lane);
+    lb_init(L, wg, dom0);
+    if (wave == 0) lb_publish_aggregate(state, epoch, wg, wg_total, lane, dom0);
     if (!staged) {
         if (wave == 0) {
             lb_finish(L, state, epoch, wg, wg_total, lane, ctrl);
@@ -204,7 +209,7 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
         excl = s_excl;
         for (uint32_t k = 0; k < wave; ++k) excl += s_tot[k];
         if (F.off_payload + 4ull * ((uint64_t)excl + total) > capacity) {
-            if (active && !dead && lane == 0) { set_status(ctrl, DLC_ECAPACITY); ctrl->abort = 1; }
+            if (active && !dead && lane == 0) { set_status(ctrl, DLC_ECAPACITY); atomicOr(&ctrl->abort, kAbortCapacity); }
             dead = true;
         }
     }
@@ -272,7 +277,7 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
         excl = s_excl;
         for (uint32_t k = 0; k < wave; ++k) excl += s_tot[k];
         if (F.off_payload + 4ull * ((uint64_t)excl + total) > capacity) {
-            if (active && !dead && lane == 0) { set_status(ctrl, DLC_ECAPACITY); ctrl->abort = 1; }
+            if (active && !dead && lane == 0) { set_status(ctrl, DLC_ECAPACITY); atomicOr(&ctrl->abort, kAbortCapacity); }
             dead = true;
         }
     }

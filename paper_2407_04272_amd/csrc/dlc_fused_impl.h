@@ -248,7 +248,7 @@ __device__ __forceinline__ void fused_phase_b(const FusedEnv& E, const FusedItem
         while (__hip_atomic_load(&E.ready[I.t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != E.epoch) {
             if (++spins > kSpinLimit) {  // never expected; the bound only guarantees termination
                 set_status(E.ctrl, DLC_ESTATE);
-                E.ctrl->abort = 1;
+                atomicOr(&E.ctrl->abort, kAbortInternal);
                 go = 0;
                 break;
             }
@@ -314,7 +314,7 @@ __device__ __forceinline__ void fused_phase_b(const FusedEnv& E, const FusedItem
         for (uint32_t k = 0; k < wave; ++k) excl += s_tot[k];
         DLC_FSTAMP(11);
         if (E.F.off_payload + 4ull * ((uint64_t)excl + total) > E.capacity) {
-            if (!dead && lane == 0) { set_status(E.ctrl, DLC_ECAPACITY); E.ctrl->abort = 1; }
+            if (!dead && lane == 0) { set_status(E.ctrl, DLC_ECAPACITY); atomicOr(&E.ctrl->abort, kAbortCapacity); }
             dead = true;
         }
         if (lane == 0) {

@@ -27,10 +27,12 @@ struct QParam {
 };
 
 struct Geom {
-    uint32_t T, B, D;
+    uint32_t T, B, D;  // T: tables of the whole payload (all destinations: ND * TD)
     uint32_t n;   // B*D symbols per table
     uint32_t G;   // groups per table
     uint32_t NG;  // T*G
+    uint32_t ND;  // destinations: the payload is [ND][TD][B][D], every destination gets a container of its own
+    uint32_t TD;  // tables per destination (= T of a container)
     uint32_t S, R, K, LMAX;
     uint32_t dtype, es;
     uint32_t vec;  // 1: every table starts on a 16-byte (fp32) / 8-byte (fp16) boundary and n % 4 == 0
@@ -42,27 +44,33 @@ struct TMeta {
     uint64_t cb_off, outl_off;  // unused by the kernels; kept for the layout of the array
 };
 
-// offsets of the container sections whose position depends on the geometry alone
+// offsets of the sections of one container (one destination) whose position depends on the geometry alone
 struct FixedLayout {
     uint64_t off_group, off_chunk, off_payload;
 };
 
 inline __host__ __device__ FixedLayout fixed_layout(const Geom& g) {
     FixedLayout F;
-    F.off_group = (kHeaderBytes + (uint64_t)kDirBytes * g.T + 15ull) & ~15ull;
-    F.off_chunk = (F.off_group + 4ull * g.NG + 15ull) & ~15ull;
-    F.off_payload = (F.off_chunk + (uint64_t)kW * g.NG + 15ull) & ~15ull;
+    const uint64_t ngd = (uint64_t)g.TD * g.G;  // groups of one container
+    F.off_group = (kHeaderBytes + (uint64_t)kDirBytes * g.TD + 15ull) & ~15ull;
+    F.off_chunk = (F.off_group + 4ull * ngd + 15ull) & ~15ull;
+    F.off_payload = (F.off_chunk + (uint64_t)kW * ngd + 15ull) & ~15ull;
     return F;
 }
 
 // small control block; `status` is sticky until read by the host, the rest is cleared per call
 struct Ctrl {
     uint32_t ticket;  // ordered work-group ids of the encode kernel
-    uint32_t abort;   // set when the output capacity would be exceeded
-    uint32_t pad0, pad1;
+    uint32_t abort;   // kAbort* bits: why (part of) the call's output is not valid
+    uint32_t dest_done;  // destinations whose container the finalize kernel has finished (zero between calls)
+    uint32_t pad1;
     int32_t status;   // first device-side error
     uint32_t collide; // statistics: a hash match whose rows differ
 };
+
+// Ctrl::abort: a container did not fit its capacity (the finalize kernel finds that out again for the container
+// concerned: other destinations' containers stay valid); an internal wait ran out (nothing of the call is valid)
+constexpr uint32_t kAbortCapacity = 1, kAbortInternal = 2;
 
 struct DecLayout {
     uint32_t valid;

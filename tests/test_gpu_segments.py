@@ -1,0 +1,147 @@
+"""GPU parity of per-destination buffers (dlc_config.num_dest > 1): one dlc_compress call writes one container per
+destination at fixed displacements; each must be, byte for byte, the container the oracle makes of that
+destination's piece on its own (that is the definition: nothing is shared between the pieces but the bounds)."""
+import numpy as np
+import pytest
+
+import oracle
+from gpu_util import to_device
+
+pytestmark = pytest.mark.gpu
+
+R = 512
+
+
+def _pieces(n, T, B, D, seed, dtype=np.float32, sigma=0.02):
+    rng = np.random.default_rng(seed)
+    table = (rng.standard_normal((T, 90, D)) * sigma).astype(np.float32)
+    idx = rng.integers(0, 90, (n, T, B))
+    x = np.stack([np.stack([table[t][idx[d, t]] for t in range(T)]) for d in range(n)])
+    x *= (1 + np.arange(T, dtype=np.float32))[None, :, None, None]
+    return x.astype(dtype)          # [n][T][B][D]
+
+
+def _run(x, ebs, S, flags=0, cap=None, ctx=None):
+    import torch
+    from paper_2407_04272_amd import binding as b
+    n, T, B, D = x.shape
+    dt = b.F16 if x.dtype == np.float16 else b.F32
+    cfg = b.make_config(dt, T, B, D, R, S, 12, flags, num_dest=n)
+    if ctx is None:
+        ctx = b.Context(cfg)
+    bound = b.dlc_compress_bound(cfg)
+    cap = bound if cap is None else cap
+    d = to_device(x)
+    out = torch.full((cap + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+    sizes = torch.zeros(1 + n * T + n, dtype=torch.int64, device="cuda")
+    ctx.set_error_bounds(eb=ebs)
+    rc = ctx.compress(d, out, sizes, capacity=cap)
+    assert rc == 0
+    status = ctx.sync_status()
+    h = out.cpu().numpy()
+    assert np.all(h[cap:] == 0xA5)
+    return ctx, status, h, sizes.cpu().numpy().astype(np.uint64), (cap // n) & ~255
+
+
+def _decode_piece(data, shape, dtype, S):
+    import torch
+    from paper_2407_04272_amd import binding as b
+    T, B, D = shape
+    dt = b.F16 if np.dtype(dtype) == np.float16 else b.F32
+    ctx = b.Context(b.make_config(dt, T, B, D, R, S, 12))
+    comp = to_device(np.concatenate([data, np.zeros(16, np.uint8)]))
+    rec = torch.zeros(shape, dtype=torch.float16 if dt == b.F16 else torch.float32, device="cuda")
+    assert ctx.decompress(comp, data.size, rec) == 0 and ctx.sync_status() == 0
+    return rec.cpu().numpy()
+
+
+CASES = [  # n_dest, T, B, D, S, dtype
+    (2, 1, 256, 16, 256, np.float32),
+    (4, 3, 250, 50, 256, np.float32),      # ragged groups
+    (8, 2, 37, 13, 64, np.float32),        # B*D not a multiple of 4
+    (3, 5, 700, 48, 128, np.float16),
+    (16, 2, 1024, 64, 256, np.float32),
+]
+
+
+@pytest.mark.parametrize("n,T,B,D,S,dtype", CASES)
+def test_every_destination_gets_its_own_container(n, T, B, D, S, dtype):
+    print("destinations", n, T, B, D, S, np.dtype(dtype).name, flush=True)
+    x = _pieces(n, T, B, D, n * 1000 + B)
+    x = x.astype(dtype)
+    x[n - 1].reshape(-1)[::173] = 3e4 if dtype == np.float32 else 6e4    # escapes in the last piece only
+    ebs = (np.float32(2e-3) * (1 + np.arange(T, dtype=np.float32))).astype(np.float32)
+    _, status, h, sizes, stride = _run(x, ebs, S)
+    assert status == 0
+    u = np.uint32 if dtype == np.float32 else np.uint16
+    total = 0
+    for d in range(n):
+        o = oracle.compress(x[d], ebs, R, S, 12)
+        assert o.rc == 0
+        got = int(sizes[1 + n * T + d])
+        assert got == o.data.size, (d, got, o.data.size)
+        piece = h[d * stride:d * stride + got]
+        diff = np.nonzero(piece != o.data)[0]
+        assert diff.size == 0, f"destination {d}: first differing byte {diff[:8]} of {got}"
+        assert np.array_equal(sizes[1 + d * T:1 + (d + 1) * T], o.sizes[1:])
+        total += got
+        rc, orec = oracle.decompress(o.data, x[d].shape, dtype)
+        rec = _decode_piece(piece.copy(), x[d].shape, dtype, S)
+        assert rc == 0 and np.array_equal(rec.view(u), orec.view(u))
+    assert int(sizes[0]) == total
+
+
+def test_carried_codebooks_per_destination():
+    from paper_2407_04272_amd import binding as b
+    n, T, B, D, S = 4, 3, 600, 32, 128
+    ebs = np.full(T, 2e-3, np.float32)
+    ctx = None
+    prev = [None] * n
+    for k in range(3):
+        x = _pieces(n, T, B, D, 50 + k)
+        ctx, status, h, sizes, stride = _run(x, ebs, S, flags=b.FLAG_CARRY_CODEBOOK, ctx=ctx)
+        assert status == 0
+        for d in range(n):
+            o = oracle.compress(x[d], ebs, R, S, 12, carry_hist=prev[d], want_hist=True)
+            got = int(sizes[1 + n * T + d])
+            assert got == o.data.size and np.array_equal(h[d * stride:d * stride + got], o.data), (k, d)
+            prev[d] = o.hist
+
+
+def test_a_destination_that_does_not_fit():
+    """One piece is noise that hardly compresses; with a stride that fits the others it alone is reported as failed,
+    the rest of the output is valid, nothing is written past a piece's stride into the next one."""
+    from paper_2407_04272_amd import binding as b
+    n, T, B, D, S = 4, 2, 512, 64, 64
+    x = _pieces(n, T, B, D, 9)
+    rng = np.random.default_rng(1)
+    x[2] = (rng.standard_normal((T, B, D)) * 0.5).astype(np.float32)      # ~9 bits per symbol at this bound
+    ebs = np.full(T, 1e-3, np.float32)
+    want = [oracle.compress(x[d], ebs, R, S, 12) for d in range(n)]
+    big = max(o.data.size for o in want)
+    small = max(o.data.size for d, o in enumerate(want) if d != 2)
+    assert want[2].data.size == big and small * 2 < big
+    cap = n * ((small + big) // 2 & ~255)
+    ctx, status, h, sizes, stride = _run(x, ebs, S, cap=cap)
+    assert small <= stride < big
+    assert status == b.ECAPACITY
+    assert int(sizes[0]) == 0 and int(sizes[1 + n * T + 2]) == 0
+    for d in (0, 1, 3):
+        got = int(sizes[1 + n * T + d])
+        assert got == want[d].data.size and np.array_equal(h[d * stride:d * stride + got], want[d].data), d
+    # and the context is usable afterwards
+    ctx, status, h, sizes, stride = _run(x, ebs, S, ctx=ctx)
+    assert status == 0 and int(sizes[0]) == sum(o.data.size for o in want)
+
+
+def test_calls_that_want_one_destination():
+    import torch
+    from paper_2407_04272_amd import binding as b
+    ctx = b.Context(b.make_config(b.F32, 2, 64, 16, num_dest=2))
+    d = torch.zeros((2, 2, 64, 16), device="cuda")
+    with pytest.raises(b.DlcError):
+        ctx.stats(d, np.full(2, 1e-3, np.float32))
+    out = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    assert ctx.decompress(out, 1024, d) == b.ESTATE
+    with pytest.raises(b.DlcError):
+        b.Context(b.make_config(b.F32, 2, 64, 16, flags=b.FLAG_FUSED, num_dest=2))
