@@ -293,6 +293,67 @@ def _measure(b, torch, np, name, d, ebs, S, with_oracle):
     return row
 
 
+def _measure_split(b, torch, np, d, ebs, S, n, with_oracle):
+    """Workload 3 cut along the batch axis into n pieces (one per receiving GPU): one compress call writes n containers
+    at fixed displacements; the receiver's side is n decompress calls, one per container."""
+    T, B, D = d.shape
+    Bp = B // n
+    x = d.view(T, n, Bp, D).permute(1, 0, 2, 3).contiguous()          # [n][T][B/n][D]: the send buffer's layout
+    nbytes = x.numel() * 4
+    row = {"workload": f"3 split over {n} destinations ({T} x {Bp} x {D} each)", "payload_MiB": round(nbytes / 2 ** 20, 3)}
+    out = torch.zeros(nbytes, dtype=torch.uint8, device=d.device)
+    sizes = torch.zeros(1 + n * T + n, dtype=torch.int64, device=d.device)
+    rec = torch.empty((T, Bp, D), dtype=torch.float32, device=d.device)
+    stride = (out.numel() // n) & ~255
+
+    def timed(fn, reps=20):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(3):
+            fn()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    for key, flags in (("", 0), ("carried_", b.FLAG_CARRY_CODEBOOK)):
+        ctx = b.Context(b.make_config(b.F32, T, Bp, D, chunk_symbols=S, flags=flags, num_dest=n))
+        ctx.set_error_bounds(eb=ebs)
+        c_ms = timed(lambda: ctx.compress(x, out, sizes))
+        assert ctx.sync_status() == 0
+        total = int(sizes[0].item())
+        row[key + "compression_ratio"] = round(nbytes / total, 3)
+        row[key + "compress_GBps"] = round(nbytes / c_ms / 1e6, 2)
+        if not key:
+            dsz = sizes[1 + n * T:].cpu().numpy()
+            rec_all = torch.empty_like(x)
+            d_ms = timed(lambda: ctx.decompress(out, out.numel(), rec_all))      # all containers, one call
+            assert ctx.sync_status() == 0
+            row["decompress_GBps"] = round(nbytes / d_ms / 1e6, 2)
+            dctx = b.Context(b.make_config(b.F32, T, Bp, D, chunk_symbols=S))
+
+            def dec_all():
+                for k in range(n):
+                    dctx.decompress(out[k * stride:], int(dsz[k]), rec)
+            d_ms = timed(dec_all, 10)
+            assert dctx.sync_status() == 0
+            row["decompress_GBps_one_call_per_container"] = round(nbytes / d_ms / 1e6, 2)
+            assert bool((rec_all[n - 1] == rec).all())
+            eb_t = torch.from_numpy(np.asarray(ebs, np.float64)).to(d.device).view(T, 1, 1)
+            row["bound_held"] = bool(((x[n - 1].double() - rec.double()).abs() <= eb_t * (1 + 1e-6)).all())
+            if with_oracle:
+                import oracle
+                same = True
+                for k in (0, n - 1):       # two pieces against the oracle (the parity tests compare every piece)
+                    o = oracle.compress(x[k].cpu().numpy(), ebs, S=S)
+                    got = out[k * stride:k * stride + int(dsz[k])].cpu().numpy()
+                    same = same and o.rc == 0 and o.data.size == got.size and bool(np.array_equal(o.data, got))
+                row["containers_identical_to_oracle"] = same
+        del ctx
+    return row
+
+
 def all_workloads(b, torch, np, W, dev, S, with_oracle):
     rows = []
 
@@ -325,6 +386,8 @@ def all_workloads(b, torch, np, W, dev, S, with_oracle):
     w = W.workload3(device=dev)
     ebs = bounds(w.payload, w.meta, 1, probe_frac=0.03)
     rows.append(_measure(b, torch, np, "3: 128 x 8192 x 128, range-relative 0.03", w.payload, ebs, S, with_oracle))
+    for n_dest in (8, 32):
+        rows.append(_measure_split(b, torch, np, w.payload, ebs, S, n_dest, with_oracle))
     del w
     torch.cuda.empty_cache()
     w = W.workload4(device=dev)

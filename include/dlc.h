@@ -91,8 +91,13 @@ typedef struct {
  *     and must fit into its stride.  The pieces are therefore at fixed displacements, as a variable-size all-to-all
  *     takes them; their sizes come back in d_out_bytes (see dlc_compress);
  *   - a destination that does not fit gets size 0 and DLC_ECAPACITY is recorded; the others are still valid;
- *   - dlc_set_error_bounds still takes num_tables bounds; dlc_decompress and dlc_stats want num_dest = 1 (a
- *     receiver decodes each container it got with a context of the piece's geometry). */
+ *   - dlc_set_error_bounds still takes num_tables bounds; dlc_stats wants num_dest = 1 (a table's statistics are
+ *     over its whole batch);
+ *   - dlc_decompress decodes n containers in one launch sequence (the receiving side of the exchange: one container
+ *     from every sender): container d is expected at byte d * stride of d_comp, stride = (comp_bytes / n) rounded
+ *     down to a multiple of 256 -- the layout dlc_compress writes for out_capacity = comp_bytes -- and the output
+ *     is [n][num_tables][batch][dim].  Every container says in its header how long it is; one that fails
+ *     validation is reported (DLC_ECORRUPT) and left undecoded, the others are decoded. */
 
 /* dlc_config.flags: compress with the fused persistent kernel, which reads the payload once and builds each
  * table's codebook inside the kernel, instead of the separate histogram, codebook and encode kernels.  Both

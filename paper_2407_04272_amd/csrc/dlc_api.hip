@@ -140,7 +140,7 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
     uint8_t* ready = take(8 * (size_t)g.T);
     uint8_t* escc = take(4 * (size_t)g.T);
     uint8_t* lut = take(((size_t)g.T << g.LMAX) * 2);
-    uint8_t* dlay = take(sizeof(DecLayout));
+    uint8_t* dlay = take(sizeof(DecLayout) * g.ND);
     uint8_t* dtab = take(sizeof(DecTable) * g.T);
     if (w) {
         w->base = base; w->bytes = off;
@@ -322,8 +322,8 @@ extern "C" int dlc_compress(dlc_ctx* c, const void* d_payload, void* d_out, size
 
 extern "C" int dlc_decompress(dlc_ctx* c, const void* d_comp, size_t comp_bytes, void* d_out, size_t cap, void* stream) {
     if (!c || !aligned16(d_comp) || !aligned16(d_out)) return DLC_EINVAL;
-    if (c->g.ND != 1) return DLC_ESTATE;  // a container holds one destination's share: decode it with such a context
     if (cap < (size_t)c->g.n * c->g.T * c->g.es) return DLC_ECAPACITY;
+    if (c->g.ND > 1) comp_bytes = (comp_bytes / c->g.ND) & ~size_t(255);  // per container: container d starts at d * comp_bytes
     if (comp_bytes < kHeaderBytes) return DLC_ECORRUPT;
     hipError_t e = launch_decompress(c->g, (const uint8_t*)d_comp, comp_bytes, d_out, c->ws, c->prof.level, &c->prof,
                                      (hipStream_t)stream);

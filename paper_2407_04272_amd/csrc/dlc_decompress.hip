@@ -9,7 +9,7 @@ namespace dlc {
 __device__ __forceinline__ uint64_t d_a16(uint64_t x) { return (x + 15ull) & ~15ull; }
 
 // ------------------------------------------------------------------------------------------------
-// One work-group per table: checks the header against the context's geometry and the table's
+// One work-group per table (of every container, when there are several): checks the header against the context's geometry and the table's
 // directory entry against the header, rebuilds the canonical code from the stored lengths and fills
 // the table's decode table: entry[i] = len << 12 | symbol for the codeword that prefixes the LMAX-bit
 // string i.  Anything inconsistent marks the table (or the whole container) invalid.
@@ -21,14 +21,17 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
     __shared__ uint16_t s_sorted[4096];
     __shared__ uint8_t s_len[4096];
     const uint32_t tid = threadIdx.x, t = blockIdx.x;
+    // the container this table is in: container d starts at d * comp_bytes (comp_bytes: the room of one container)
+    const uint32_t dst = t / g.TD, tl = t - dst * g.TD;
+    comp += (uint64_t)dst * comp_bytes;
     const uint32_t* h = reinterpret_cast<const uint32_t*>(comp);
     const uint64_t* q = reinterpret_cast<const uint64_t*>(comp);
     DecLayout L;
-    bool ok = comp_bytes >= kHeaderBytes + (uint64_t)kDirBytes * g.T;
+    bool ok = comp_bytes >= kHeaderBytes + (uint64_t)kDirBytes * g.TD;
     if (ok) {
-        ok = h[H_MAGIC] == kMagic && h[H_VERSION] == kVersion && h[H_DTYPE] == g.dtype && h[H_T] == g.T &&
+        ok = h[H_MAGIC] == kMagic && h[H_VERSION] == kVersion && h[H_DTYPE] == g.dtype && h[H_T] == g.TD &&
              h[H_B] == g.B && h[H_D] == g.D && h[H_R] == g.R && h[H_S] == g.S && h[H_LMAX] == g.LMAX &&
-             h[H_W] == kW && h[H_V] == kV && h[H_NG] == g.NG;
+             h[H_W] == kW && h[H_V] == kV && h[H_NG] == g.TD * g.G;
     }
     uint64_t off_cb = 0, n_out = 0, total = 0;
     if (ok) {
@@ -39,12 +42,12 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
         off_cb = q[HQ_OFF_CB];
         total = q[HQ_TOTAL];
         ok = total <= comp_bytes && L.off_group == F.off_group && L.off_chunk == F.off_chunk &&
-             L.off_payload == F.off_payload && L.words_total <= 0xFFFFFFFFull && n_out <= (uint64_t)g.n * g.T &&
+             L.off_payload == F.off_payload && L.words_total <= 0xFFFFFFFFull && n_out <= (uint64_t)g.n * g.TD &&
              off_cb == d_a16(L.off_payload + 4ull * L.words_total) && total >= off_cb;
     }
-    if (t == 0 && tid == 0) {
+    if (tl == 0 && tid == 0) {
         L.valid = ok; L.pad = 0;
-        *dlay = L;
+        dlay[dst] = L;
         if (!ok) set_status(ctrl, DLC_ECORRUPT);
     }
     DecTable D;
@@ -52,7 +55,7 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
     uint32_t sym_lo = 0, sym_hi = 0, n_used = 0;
     uint64_t cb = 0;
     if (ok) {
-        const uint8_t* d = comp + kHeaderBytes + (uint64_t)kDirBytes * t;
+        const uint8_t* d = comp + kHeaderBytes + (uint64_t)kDirBytes * tl;
         const uint32_t* d32 = reinterpret_cast<const uint32_t*>(d);
         const uint64_t* d64 = reinterpret_cast<const uint64_t*>(d + 24);
         const float eb = __uint_as_float(d32[0]);
@@ -166,11 +169,13 @@ constexpr uint32_t kDecWaves = DLC_DEC_WAVES;        // wavefronts per work-grou
 
 template <bool F16, bool VEC>
 __global__ __launch_bounds__(64 * DLC_DEC_WAVES) void k_decode(Geom g, const uint8_t* comp, const uint16_t* lut, const DecLayout* dlay,
-                                                const DecTable* dtab, Ctrl* ctrl, void* outp, uint32_t bpt) {
+                                                const DecTable* dtab, Ctrl* ctrl, void* outp, uint32_t bpt, uint64_t comp_stride) {
     extern __shared__ __align__(16) uint16_t s_lut[];  // [1 << LMAX] decode table, then kDecWaves staging arrays
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t t = blockIdx.x / bpt, b = blockIdx.x % bpt;
-    const DecLayout L = *dlay;
+    const uint32_t dst = t / g.TD, tl = t - dst * g.TD;  // the container this table is in, and its place there
+    comp += (uint64_t)dst * comp_stride;
+    const DecLayout L = dlay[dst];
     const DecTable D = dtab[t];
     if (!L.valid || !D.valid) return;  // uniform over the work-group
     const uint32_t lut_n = 1u << g.LMAX;
@@ -183,13 +188,13 @@ __global__ __launch_bounds__(64 * DLC_DEC_WAVES) void k_decode(Geom g, const uin
     const uint32_t grp = b * kDecWaves + wave;
     if (grp >= g.G) return;  // whole wavefront; no barrier follows
     uint32_t* stage = reinterpret_cast<uint32_t*>(s_lut + lut_n) + wave * (kWin * kW) + lane;  // my column
-    const uint32_t gid = t * g.G + grp;
+    const uint32_t gid = tl * g.G + grp;  // group number inside the container
     const uint32_t cw = comp[L.off_chunk + (uint64_t)gid * kW + lane];
     const uint32_t incl = wave_incl_scan(cw, lane);
     const uint32_t total = __shfl(incl, 63, 64);
     const uint32_t* goffs = reinterpret_cast<const uint32_t*>(comp + L.off_group);
     const uint64_t goff = goffs[gid];
-    const uint64_t gend = gid + 1 < g.NG ? (uint64_t)goffs[gid + 1] : L.words_total;
+    const uint64_t gend = gid + 1 < g.TD * g.G ? (uint64_t)goffs[gid + 1] : L.words_total;
     // the group's words: its chunks, then two words per escape
     if (gend > L.words_total || goff + total > gend || ((gend - goff - total) & 1ull)) {
         if (lane == 0) set_status(ctrl, DLC_ECORRUPT);
@@ -296,7 +301,7 @@ hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_b
         dim3 grid(g.T * bpt), block(64 * kDecWaves);
         const size_t sm = ((size_t)2 << g.LMAX) + (size_t)kDecWaves * kWin * kW * 4;
         if (prof_on(pl, P_DECODE)) prof_begin(prof, P_DECODE, s);
-#define DLC_DEC(F, V) hipLaunchKernelGGL((k_decode<F, V>), grid, block, sm, s, g, comp, w.lut, w.dlay, w.dtab, w.ctrl, out, bpt)
+#define DLC_DEC(F, V) hipLaunchKernelGGL((k_decode<F, V>), grid, block, sm, s, g, comp, w.lut, w.dlay, w.dtab, w.ctrl, out, bpt, (uint64_t)comp_bytes)
         if (f16) { if (g.vec) DLC_DEC(true, true); else DLC_DEC(true, false); }
         else { if (g.vec) DLC_DEC(false, true); else DLC_DEC(false, false); }
 #undef DLC_DEC

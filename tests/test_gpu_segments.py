@@ -134,6 +134,41 @@ def test_a_destination_that_does_not_fit():
     assert status == 0 and int(sizes[0]) == sum(o.data.size for o in want)
 
 
+def test_all_containers_decoded_by_one_call():
+    """The receiving side: n containers at fixed displacements go through one dlc_decompress call; a damaged one is
+    reported and skipped, the others come out right."""
+    import torch
+    from paper_2407_04272_amd import binding as b
+    n, T, B, D, S = 6, 3, 500, 40, 128
+    x = _pieces(n, T, B, D, 77)
+    x[1].reshape(-1)[::97] = 1e5
+    ebs = np.full(T, 2e-3, np.float32)
+    ctx, status, h, sizes, stride = _run(x, ebs, S)
+    assert status == 0
+    cap = b.dlc_compress_bound(ctx.cfg)
+    want = [oracle.decompress(oracle.compress(x[d], ebs, R, S, 12).data, x[d].shape, np.float32)[1] for d in range(n)]
+    comp = to_device(h[:cap + 64].copy())
+    rec = torch.full((n, T, B, D), 7.0, dtype=torch.float32, device="cuda")
+    assert ctx.decompress(comp, cap, rec) == 0 and ctx.sync_status() == 0
+    r = rec.cpu().numpy()
+    for d in range(n):
+        assert np.array_equal(r[d].view(np.uint32), want[d].view(np.uint32)), d
+    # damage container 4 (a directory field), decode again
+    bad = h[:cap + 64].copy()
+    bad[4 * stride + 128 + 4] ^= 0x40                     # n_used of its first table
+    comp = to_device(bad)
+    rec.fill_(7.0)
+    assert ctx.decompress(comp, cap, rec) == 0
+    assert ctx.sync_status() == b.ECORRUPT
+    r = rec.cpu().numpy()
+    for d in range(n):
+        if d != 4:
+            assert np.array_equal(r[d].view(np.uint32), want[d].view(np.uint32)), d
+    assert np.all(r[4, 0] == 7.0)                         # the damaged table was left alone
+    # a displacement that leaves no room for a header
+    assert ctx.decompress(comp, 100 * n, rec) == b.ECORRUPT
+
+
 def test_calls_that_want_one_destination():
     import torch
     from paper_2407_04272_amd import binding as b
@@ -141,7 +176,5 @@ def test_calls_that_want_one_destination():
     d = torch.zeros((2, 2, 64, 16), device="cuda")
     with pytest.raises(b.DlcError):
         ctx.stats(d, np.full(2, 1e-3, np.float32))
-    out = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
-    assert ctx.decompress(out, 1024, d) == b.ESTATE
     with pytest.raises(b.DlcError):
         b.Context(b.make_config(b.F32, 2, 64, 16, flags=b.FLAG_FUSED, num_dest=2))
