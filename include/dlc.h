@@ -105,7 +105,7 @@ typedef struct {
 enum { DLC_FLAG_FUSED = 1, DLC_FLAG_CARRY_CODEBOOK = 2 };
 
 /* DLC_FLAG_CARRY_CODEBOOK: dlc_compress codes each table with the Huffman codebook built from the payload of the
- * PREVIOUS dlc_compress call on this context instead of from its own payload (Section IV-E: the value distributions
+ * PREVIOUS dlc_compress call on this context instead of from its own payload (Section IV-C: the value distributions
  * of the lookups change little from iteration to iteration).  The payload is then read once instead of twice.
  *   - The first call on a context, and the first call after dlc_set_error_bounds changed a bound, build their
  *     codebook from their own payload as without the flag (same bytes as without the flag).

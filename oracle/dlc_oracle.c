@@ -608,7 +608,7 @@ static void free_table_work(orc_table_work* w, int T) {
 /*
  * carry_hist (optional, T*K counts): code table t with the Huffman codebook of carry_hist[t] -- the symbol counts of
  * an EARLIER payload -- instead of its own (the value distributions change little between training iterations,
- * Section IV-E, so the previous iteration's codebook fits the next one).  Readings, the paper being silent:
+ * Section IV-C, so the previous iteration's codebook fits the next one).  Readings, the paper being silent:
  *   - the count of symbol 0 (the escape) is raised by one before the codebook is built, so that an escape can always
  *     be coded;
  *   - a symbol the carried counts do not contain is stored as an escape (symbol 0 in the stream plus a record with

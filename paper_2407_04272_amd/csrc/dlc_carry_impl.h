@@ -1,7 +1,7 @@
 // Single-pass compression with a carried codebook, for one chunk size S (DLC_S, defined by the including source
 // file).
 //
-// The symbol distribution of a table changes little from one training iteration to the next (Section IV-E of the
+// The symbol distribution of a table changes little from one training iteration to the next (Section IV-C of the
 // paper: the value distributions stay put through the phases of training), so the codebook built from the previous
 // call's payload can code this call's.  That removes the histogram -> codebook -> encode dependency: the payload is
 // read from memory once, and the histogram of this call is counted on the way, for the next call's codebook.
