@@ -69,7 +69,12 @@ __global__ __launch_bounds__(256) void k_stats_hash(const void* payload, Geom g,
 #pragma unroll
             for (uint32_t k = 0; k < kRowsPer; ++k)  // a row past the end reads the last row instead; it is not used
                 x[k] = elem_at<F16>(tab, min(row0 + k, g.B - 1u) * g.D + e, raw[k]);
+            // row hash = sum over the elements of value * m(position), m odd and different for every position and for
+            // the two sets (a multilinear hash: rows that differ in one element never collide, others with
+            // probability about 2^-63; integer multiplies are the expensive instructions here, and this needs three
+            // 32-bit ones per element where a full 64-bit mix of every element needed sixteen)
             const uint64_t pos = (uint64_t)(e + 1u) * 0x9E3779B97F4A7C15ull + salt;
+            const uint64_t m_raw = mix64(pos) | 1ull, m_q = mix64(pos ^ 0x5555555555555555ull) | 1ull;
 #pragma unroll
             for (uint32_t k = 0; k < kRowsPer; ++k) {
                 if (row0 + k < g.B && __builtin_fabsf(x[k]) < __builtin_inff()) {
@@ -78,8 +83,8 @@ __global__ __launch_bounds__(256) void k_stats_hash(const void* payload, Geom g,
                     mx = max(mx, o);
                 }
                 const uint32_t c = quant_symbol<F16>(x[k], q, Rf, (int)g.R);
-                hr[k] += mix64((uint64_t)raw[k] + pos);
-                hq[k] += mix64((uint64_t)c + pos);
+                hr[k] += (uint64_t)raw[k] * m_raw;
+                hq[k] += (uint64_t)c * m_q;
             }
         }
         uint64_t hsh = 0;
