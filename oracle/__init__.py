@@ -76,6 +76,8 @@ def lib():
                                    C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.orc_compress_carried.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int,
                                            C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.orc_compress_rows.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int,
+                                        C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.orc_decompress.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p]
         _lib = L
     return _lib
@@ -186,9 +188,11 @@ class Compressed:
 
 
 def compress(payload: np.ndarray, eb, R: int = 512, S: int = 256, LMAX: int = 12, capacity: int | None = None,
-             carry_hist: np.ndarray | None = None, want_hist: bool = False):
+             carry_hist: np.ndarray | None = None, want_hist: bool = False, row_match=None):
     """carry_hist (u64[T, 2R]): code with the codebook of these counts (an earlier payload's) instead of the payload's
-    own; want_hist: also return this payload's counts, which is what the next call is given."""
+    own; want_hist: also return this payload's counts, which is what the next call is given.
+    row_match (bool or T flags): rows equal to an earlier row of their table are stored as references (not together
+    with carry_hist / want_hist)."""
     payload = np.ascontiguousarray(payload)
     T, B, D = payload.shape
     dt = _dtype_code(payload)
@@ -198,7 +202,15 @@ def compress(payload: np.ndarray, eb, R: int = 512, S: int = 256, LMAX: int = 12
         raise ValueError("bad geometry")
     out = np.zeros(max(cap, 1), np.uint8)
     sizes = np.zeros(1 + T, np.uint64)
-    if carry_hist is None and not want_hist:
+    if row_match is not None:
+        if carry_hist is not None or want_hist:
+            raise ValueError("row_match cannot be combined with carry_hist / want_hist")
+        rm = np.ascontiguousarray(np.broadcast_to(np.asarray(row_match, np.uint8), (T,)))
+        cap = cap + 16 * T + 4 * B * T if capacity is None else cap
+        out = np.zeros(max(cap, 1), np.uint8)
+        rc = lib().orc_compress_rows(_ptr(payload), dt, T, B, D, R, S, LMAX, _ptr(ebs), _ptr(out), cap, _ptr(sizes), _ptr(rm))
+        hist = None
+    elif carry_hist is None and not want_hist:
         rc = lib().orc_compress(_ptr(payload), dt, T, B, D, R, S, LMAX, _ptr(ebs), _ptr(out), cap, _ptr(sizes))
         hist = None
     else:

@@ -591,6 +591,7 @@ typedef struct {
     uint64_t* group_word; /* first word of each group, relative to the table */
     uint32_t* words;      /* chunks and escape records of all groups */
     uint64_t n_words;
+    uint32_t* ref;        /* row matching: first row of the batch with this row's content (NULL: not used) */
 } orc_table_work;
 
 static void free_table_work(orc_table_work* w, int T) {
@@ -601,6 +602,7 @@ static void free_table_work(orc_table_work* w, int T) {
         free(w[t].chunk_words);
         free(w[t].group_word);
         free(w[t].words);
+        free(w[t].ref);
     }
     free(w);
 }
@@ -616,9 +618,31 @@ static void free_table_work(orc_table_work* w, int T) {
  * hist_out (optional, T*K): the symbol counts of THIS payload (before that substitution), i.e. what the next call
  * would be given as carry_hist.
  */
+/* rows of one table as sequences of element identities (symbol, or raw bits for an escape), for the row matching */
+static const uint64_t* g_ident;
+static size_t g_ident_D;
+static int ident_row_cmp(const void* a, const void* b) {
+    uint32_t ia = *(const uint32_t*)a, ib = *(const uint32_t*)b;
+    int c = memcmp(g_ident + (size_t)ia * g_ident_D, g_ident + (size_t)ib * g_ident_D, g_ident_D * sizeof(uint64_t));
+    if (c) return c;
+    return ia < ib ? -1 : (ia > ib ? 1 : 0);
+}
+
+/*
+ * row_match (optional, T flags): tables flagged here are coded with the vector-based LZ step of Section III-D
+ * before the entropy coder: a row (embedding vector) that equals an earlier row of the same table in the batch is
+ * not coded at all; it carries a reference to that row.  Readings, the paper giving the idea but no format:
+ *   - the fixed pattern is one whole row, compared after quantisation: two rows are equal when all their symbols
+ *     are, and, where a symbol is the escape, the raw bits too;
+ *   - the window is the whole batch and the reference is always the FIRST row of the batch with that content, so a
+ *     referenced row is always a coded one (no chains) and the decoder can copy rows in parallel;
+ *   - the references are stored as u32 ref[B] (ref[i] = i for a coded row) behind the code-length blocks, 16-byte
+ *     aligned, the directory entry's second u64 giving the byte offset (0 for a table without row matching);
+ *   - the elements of a referencing row take no part in histogram, codebook, chunk bits or escape records.
+ */
 static int compress_impl(const void* payload, int dtype, int T, int64_t B, int64_t D, int R, int S, int LMAX,
                          const float* eb, uint8_t* out, size_t capacity, uint64_t* out_bytes /* 1 + T */,
-                         const uint64_t* carry_hist, uint64_t* hist_out) {
+                         const uint64_t* carry_hist, uint64_t* hist_out, const uint8_t* row_match) {
     int rc = check_geometry(dtype, T, B, D, R, S, LMAX);
     if (rc != ORC_OK) return rc;
     if (!payload || !eb || !out || !out_bytes) return ORC_EINVAL;
@@ -645,14 +669,45 @@ static int compress_impl(const void* payload, int dtype, int T, int64_t B, int64
         const uint8_t* tab = (const uint8_t*)payload + (size_t)t * n * es;
         /* quantise, collect escapes in index order */
         orc_quantize(tab, dtype, n, eb[t], R, sym, NULL);
-        /* histogram and codebook */
-        orc_histogram(sym, n, K, hist);
+        if (row_match && row_match[t]) {
+            uint64_t* ident = (uint64_t*)malloc(sizeof(uint64_t) * n);
+            uint32_t* order = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)B);
+            w->ref = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)B);
+            if (!ident || !order || !w->ref) {
+                free(ident);
+                free(order);
+                free(sym);
+                free(hist);
+                free_table_work(work, T);
+                return ORC_ENOMEM;
+            }
+            for (size_t i = 0; i < n; ++i) ident[i] = sym[i] ? (uint64_t)sym[i] : ((1ull << 32) | load_raw(tab, dtype, i));
+            for (int64_t r = 0; r < B; ++r) order[r] = (uint32_t)r;
+            g_ident = ident;
+            g_ident_D = (size_t)D;
+            qsort(order, (size_t)B, sizeof(uint32_t), ident_row_cmp);
+            for (int64_t k = 0; k < B; ++k) { /* equal rows are adjacent, the smallest index first */
+                if (k > 0 && memcmp(ident + (size_t)order[k] * D, ident + (size_t)order[k - 1] * D, (size_t)D * sizeof(uint64_t)) == 0)
+                    w->ref[order[k]] = w->ref[order[k - 1]];
+                else
+                    w->ref[order[k]] = order[k];
+            }
+            for (int64_t r = 0; r < B; ++r)
+                if (w->ref[r] != (uint32_t)r)
+                    for (int64_t e = 0; e < D; ++e) sym[(size_t)r * D + e] = 0xFFFF; /* not coded */
+            free(ident);
+            free(order);
+        }
+        /* histogram and codebook (elements of referencing rows do not count) */
+        memset(hist, 0, sizeof(uint64_t) * (size_t)K);
+        for (size_t i = 0; i < n; ++i)
+            if (sym[i] != 0xFFFF) hist[sym[i]]++;
         if (hist_out) memcpy(hist_out + (size_t)t * K, hist, sizeof(uint64_t) * (size_t)K);
         if (carry_hist) {
             memcpy(hist, carry_hist + (size_t)t * K, sizeof(uint64_t) * (size_t)K);
             hist[0] += 1;
             for (size_t i = 0; i < n; ++i)
-                if (hist[sym[i]] == 0) sym[i] = 0; /* no code for it: an escape */
+                if (sym[i] != 0xFFFF && hist[sym[i]] == 0) sym[i] = 0; /* no code for it: an escape */
         }
         orc_codebook(hist, K, LMAX, w->len, w->code, &w->n_used, NULL);
         w->sym_lo = -1;
@@ -683,7 +738,7 @@ static int compress_impl(const void* payload, int dtype, int T, int64_t B, int64
                 uint64_t bits = 0;
                 for (uint32_t k = 0; k < (uint32_t)S; ++k) {
                     size_t idx = chunk_symbol_index(g, l, k, (uint32_t)S);
-                    if (idx < n) bits += w->len[sym[idx]];
+                    if (idx < n && sym[idx] != 0xFFFF) bits += w->len[sym[idx]];
                 }
                 uint64_t nw = (bits + 31) / 32;
                 w->chunk_words[g * ORC_W + l] = (uint8_t)nw;
@@ -702,7 +757,7 @@ static int compress_impl(const void* payload, int dtype, int T, int64_t B, int64
                 uint64_t bit = 0; /* bit position inside the chunk */
                 for (uint32_t k = 0; k < (uint32_t)S; ++k) {
                     size_t idx = chunk_symbol_index(g, l, k, (uint32_t)S);
-                    if (idx >= n) continue;
+                    if (idx >= n || sym[idx] == 0xFFFF) continue;
                     uint32_t L = w->len[sym[idx]];
                     uint32_t c = w->code[sym[idx]];
                     for (uint32_t b = 0; b < L; ++b) { /* MSB of the codeword first */
@@ -741,14 +796,24 @@ static int compress_impl(const void* payload, int dtype, int T, int64_t B, int64
         cb_off[t] = cur;
         cur += align_up((size_t)(work[t].sym_hi - work[t].sym_lo + 1), 4);
     }
+    /* row references of the tables that use row matching, behind the code-length blocks */
+    size_t* ref_off = (size_t*)calloc((size_t)T, sizeof(size_t));
+    for (int t = 0; t < T; ++t)
+        if (work[t].ref) {
+            cur = align_up(cur, 16);
+            ref_off[t] = cur;
+            cur += 4 * (size_t)B;
+        }
     size_t total = cur;
     if (words_total > 0xFFFFFFFFull) {
+        free(ref_off);
         free(cb_off);
         free_table_work(work, T);
         return ORC_EINVAL;
     }
     if (total > capacity) {
         free(cb_off);
+        free(ref_off);
         free_table_work(work, T);
         out_bytes[0] = 0;
         return ORC_ECAPACITY;
@@ -786,7 +851,7 @@ static int compress_impl(const void* payload, int dtype, int T, int64_t B, int64
         put32(d + 16, w->n_outliers);
         put32(d + 20, (uint32_t)G);
         put64(d + 24, cb_off[t]);
-        put64(d + 32, 0);
+        put64(d + 32, ref_off[t]);
         put64(d + 40, word_base);
         put64(d + 48, w->n_words);
         memcpy(out + cb_off[t], w->len + w->sym_lo, (size_t)(w->sym_hi - w->sym_lo + 1));
@@ -797,23 +862,34 @@ static int compress_impl(const void* payload, int dtype, int T, int64_t B, int64
         /* bytes attributable to this table (size metadata of the pipeline's second stage) */
         out_bytes[1 + t] = 4 * w->n_words + align_up((size_t)(w->sym_hi - w->sym_lo + 1), 4) + (ORC_W + 4) * G +
                            ORC_DIR_BYTES;
+        if (w->ref) {
+            for (int64_t r = 0; r < B; ++r) put32(out + ref_off[t] + 4 * (size_t)r, w->ref[r]);
+            out_bytes[1 + t] += 4 * (uint64_t)B;
+        }
         word_base += w->n_words;
     }
     out_bytes[0] = total;
     free(cb_off);
+    free(ref_off);
     free_table_work(work, T);
     return ORC_OK;
 }
 
 int orc_compress(const void* payload, int dtype, int T, int64_t B, int64_t D, int R, int S, int LMAX,
                  const float* eb, uint8_t* out, size_t capacity, uint64_t* out_bytes /* 1 + T */) {
-    return compress_impl(payload, dtype, T, B, D, R, S, LMAX, eb, out, capacity, out_bytes, NULL, NULL);
+    return compress_impl(payload, dtype, T, B, D, R, S, LMAX, eb, out, capacity, out_bytes, NULL, NULL, NULL);
 }
 
 int orc_compress_carried(const void* payload, int dtype, int T, int64_t B, int64_t D, int R, int S, int LMAX,
                          const float* eb, uint8_t* out, size_t capacity, uint64_t* out_bytes /* 1 + T */,
                          const uint64_t* carry_hist /* T*K or NULL */, uint64_t* hist_out /* T*K or NULL */) {
-    return compress_impl(payload, dtype, T, B, D, R, S, LMAX, eb, out, capacity, out_bytes, carry_hist, hist_out);
+    return compress_impl(payload, dtype, T, B, D, R, S, LMAX, eb, out, capacity, out_bytes, carry_hist, hist_out, NULL);
+}
+
+int orc_compress_rows(const void* payload, int dtype, int T, int64_t B, int64_t D, int R, int S, int LMAX,
+                      const float* eb, uint8_t* out, size_t capacity, uint64_t* out_bytes /* 1 + T */,
+                      const uint8_t* row_match /* T flags */) {
+    return compress_impl(payload, dtype, T, B, D, R, S, LMAX, eb, out, capacity, out_bytes, NULL, NULL, row_match);
 }
 
 /* ------------------------------------------------------------------ */
@@ -865,6 +941,14 @@ int orc_decompress(const uint8_t* comp, size_t bytes, void* out, size_t out_capa
         uint32_t n_used = get32(d + 4), sym_lo = get32(d + 8), sym_hi = get32(d + 12);
         uint32_t n_outl = get32(d + 16);
         uint64_t cb_off = get64(d + 24);
+        uint64_t ref_off = get64(d + 32); /* row matching: u32 ref[B], 0 = none */
+        if (ref_off) {
+            if (ref_off % 4 || ref_off < off_codebook || ref_off + 4 * (uint64_t)B > total) return ORC_ECORRUPT;
+            for (int64_t r = 0; r < B; ++r) { /* a reference points back to a coded row */
+                uint32_t o = get32(comp + ref_off + 4 * (size_t)r);
+                if (o > (uint32_t)r || get32(comp + ref_off + 4 * (size_t)o) != o) return ORC_ECORRUPT;
+            }
+        }
         if (!(eb > 0.0f) || isinf(eb)) return ORC_ECORRUPT;
         if (get32(d + 20) != G) return ORC_ECORRUPT;
         if (sym_lo > sym_hi || sym_hi >= (uint32_t)K || n_used < 1 || n_used > sym_hi - sym_lo + 1) return ORC_ECORRUPT;
@@ -920,6 +1004,13 @@ int orc_decompress(const uint8_t* comp, size_t bytes, void* out, size_t out_capa
                 for (uint32_t k = 0; k < (uint32_t)S; ++k) {
                     size_t idx = chunk_symbol_index(g, l, k, (uint32_t)S);
                     if (idx >= n) continue;
+                    if (ref_off) { /* a referencing row has no bits in the stream */
+                        size_t row = idx / (size_t)D;
+                        if (get32(comp + ref_off + 4 * row) != (uint32_t)row) {
+                            if (sym_out) sym_out[(size_t)t * n + idx] = 0xFFFF;
+                            continue;
+                        }
+                    }
                     uint32_t c;
                     if (n_used == 1) {
                         c = sym_lo;
@@ -959,6 +1050,16 @@ int orc_decompress(const uint8_t* comp, size_t bytes, void* out, size_t out_capa
             }
         }
         if (seen_outl != n_outl) return ORC_ECORRUPT;
+        if (ref_off) /* referencing rows: copies of the rows they point to */
+            for (int64_t r = 0; r < B; ++r) {
+                uint32_t o = get32(comp + ref_off + 4 * (size_t)r);
+                if (o != (uint32_t)r) {
+                    memcpy(tab_out + (size_t)r * D * es, tab_out + (size_t)o * D * es, (size_t)D * es);
+                    if (sym_out)
+                        memcpy(sym_out + (size_t)t * n + (size_t)r * D, sym_out + (size_t)t * n + (size_t)o * D,
+                               (size_t)D * sizeof(uint16_t));
+                }
+            }
     }
     return ORC_OK;
 }

@@ -28,10 +28,11 @@ class Table:
     n_outliers: int
     n_groups: int
     codebook_off: int
-    reserved: int
+    ref_off: int               # row matching: byte offset of u32 ref[B]; 0 = the table does not use it
     payload_word_off: int
     payload_words: int
     lengths: np.ndarray
+    ref: np.ndarray | None = None
 
 
 @dataclass
@@ -73,7 +74,8 @@ def parse(buf) -> Container:
         e = struct.unpack_from("<6I4Q", raw, HEADER + DIRENT * t)
         eb = struct.unpack("<f", struct.pack("<I", e[0]))[0]
         ln = np.frombuffer(raw, np.uint8, e[3] - e[2] + 1, e[6])
-        tables.append(Table(eb, e[1], e[2], e[3], e[4], e[5], e[6], e[7], e[8], e[9], ln))
+        ref = np.frombuffer(raw, np.uint32, B, e[7]) if e[7] else None
+        tables.append(Table(eb, e[1], e[2], e[3], e[4], e[5], e[6], e[7], e[8], e[9], ln, ref))
     group_off = np.frombuffer(raw, np.uint32, NG, off_g)
     chunk_words = np.frombuffer(raw, np.uint8, W * NG, off_c)
     words = np.frombuffer(raw, np.uint32, n_words, off_p)
@@ -107,7 +109,7 @@ def check_layout(c: Container):
     words = 0
     outl = 0
     for t, tb in enumerate(c.tables):
-        assert tb.n_groups == G and tb.reserved == 0
+        assert tb.n_groups == G
         assert tb.codebook_off == cur
         nlen = tb.sym_hi - tb.sym_lo + 1
         pad = (nlen + 3) // 4 * 4
@@ -123,6 +125,13 @@ def check_layout(c: Container):
             assert tb.sym_lo == tb.sym_hi and tb.lengths[0] == 0 and tb.payload_words == 2 * tb.n_outliers
         else:
             assert np.count_nonzero(tb.lengths) == tb.n_used and tb.lengths[0] and tb.lengths[-1]
+    # row references of the tables that have them: behind the code-length blocks, each 16-byte aligned, zero padding
+    for tb in c.tables:
+        if tb.ref_off:
+            assert tb.ref_off == _a16(cur) and c.raw[cur:tb.ref_off] == b"\0" * (tb.ref_off - cur)
+            cur = tb.ref_off + 4 * c.B
+            rows = np.arange(c.B, dtype=np.uint32)
+            assert np.all(tb.ref <= rows) and np.array_equal(tb.ref[tb.ref], tb.ref)   # points back, at a coded row
     assert cur == c.total_bytes
     assert outl == c.n_outliers_total and words == c.payload_words_total
     # group offsets are the exclusive prefix sum of (chunk words + two words per escape)
@@ -161,6 +170,8 @@ def decode_symbols(c: Container) -> np.ndarray:
             for l in range(W):
                 idx = [g * W * c.S + (k // V) * (W * V) + l * V + (k % V) for k in range(c.S)]
                 idx = [i for i in idx if i < n]
+                if tb.ref is not None:      # a referencing row has nothing in the stream; its symbols stay 0xFFFF
+                    idx = [i for i in idx if tb.ref[i // c.D] == i // c.D]
                 if not idx:
                     assert cw[l] == 0
                     continue
