@@ -102,7 +102,7 @@ typedef struct {
 /* dlc_config.flags: compress with the fused persistent kernel, which reads the payload once and builds each
  * table's codebook inside the kernel, instead of the separate histogram, codebook and encode kernels.  Both
  * produce the same bytes; on MI355X the separate kernels are the faster choice (the default). */
-enum { DLC_FLAG_FUSED = 1, DLC_FLAG_CARRY_CODEBOOK = 2 };
+enum { DLC_FLAG_FUSED = 1, DLC_FLAG_CARRY_CODEBOOK = 2, DLC_FLAG_ROW_MATCH = 4 };
 
 /* DLC_FLAG_CARRY_CODEBOOK: dlc_compress codes each table with the Huffman codebook built from the payload of the
  * PREVIOUS dlc_compress call on this context instead of from its own payload (Section IV-C: the value distributions
@@ -115,6 +115,16 @@ enum { DLC_FLAG_FUSED = 1, DLC_FLAG_CARRY_CODEBOOK = 2 };
  *     for any payload; a payload unlike the previous one costs compression ratio, never correctness.
  *   - The container format is unchanged; dlc_decompress needs no flag.
  * Cannot be combined with DLC_FLAG_FUSED. */
+
+/* DLC_FLAG_ROW_MATCH: the vector-based LZ step of Section III-D in front of the entropy coder.  The pattern is one
+ * whole row (embedding vector): a row that equals an earlier row of its table in the batch after quantisation -- all
+ * symbols and, where a symbol is the escape, the raw bits -- is not coded; the container stores a reference to the
+ * FIRST such row (u32 ref[batch] per table behind the code-length blocks; the directory entry's second u64 is its
+ * byte offset, 0 for a table without).  A referenced row is therefore always a coded one and the decoder copies rows
+ * in parallel.  Per table: dlc_set_row_match switches it on and off (all on after dlc_create), which is what the
+ * compressor selection of Section III-D (Eq. 2, dlc_speedup_estimate) decides offline.  Needs dim % 4 == 0; not
+ * together with the other flags or num_dest > 1.  The search hashes rows; two different rows with one 64-bit hash
+ * (about 2^-33 per table and call for 8192 rows) cost a match, never correctness. */
 
 /* Per-table statistics of a sampled batch: what Eq. 1 needs, plus the value range. */
 typedef struct {
@@ -212,6 +222,15 @@ int dlc_compress(dlc_ctx* ctx, const void* d_payload, void* d_out, size_t out_ca
 int dlc_decompress(dlc_ctx* ctx, const void* d_comp, size_t comp_bytes, void* d_payload_out, size_t out_capacity,
                    void* stream);
 
+/* Row matching per table (contexts with DLC_FLAG_ROW_MATCH): h_flags HOST uint8[T], non-zero = store the table's
+ * repeated rows as references; NULL = all tables.  Synchronises `stream`. */
+int dlc_set_row_match(dlc_ctx* ctx, const uint8_t* h_flags, void* stream);
+
+/* Eq. 2: the speed-up of a transfer that compresses, sends and decompresses over sending raw, for compression ratio
+ * cr, network bandwidth net_gbps and compression / decompression throughputs tc_gbps, td_gbps (same unit):
+ * 1 / (1/cr + net * (1/tc + 1/td)).  0 if an argument is not positive. */
+double dlc_speedup_estimate(double cr, double net_gbps, double tc_gbps, double td_gbps);
+
 /* Waits for `stream`, returns the first device-side error since the previous call (DLC_OK if none), clears it. */
 int dlc_sync_status(dlc_ctx* ctx, void* stream);
 
@@ -220,12 +239,14 @@ int dlc_sync_status(dlc_ctx* ctx, void* stream);
  *   dlc_quantize       symbols (uint16, DEVICE, T*B*D) of d_payload at the current bounds -- the quantiser alone
  *   dlc_read_histogram the code histogram (uint32[T][2R], HOST) left by the last dlc_compress
  *   dlc_read_codebook  code lengths (uint8[T][2R]) and codewords (uint16[T][2R]) left by the last dlc_compress
+ *   dlc_read_row_refs  row references (uint32[T][B], HOST) left by the last dlc_compress (DLC_FLAG_ROW_MATCH only)
  * With DLC_FLAG_CARRY_CODEBOOK the histogram is still that of the last call's payload, and the codebook is the one
  * built from it for the NEXT call (escape count raised by one), not the one the last call's container was coded with.
  */
 int dlc_quantize(dlc_ctx* ctx, const void* d_payload, uint16_t* d_symbols, void* stream);
 int dlc_read_histogram(dlc_ctx* ctx, uint32_t* h_hist, void* stream);
 int dlc_read_codebook(dlc_ctx* ctx, uint8_t* h_len, uint16_t* h_code, void* stream);
+int dlc_read_row_refs(dlc_ctx* ctx, uint32_t* h_ref, void* stream);
 
 /*
  * Kernel timing with HIP events on the caller's stream.

@@ -40,7 +40,8 @@ class ControllerParams(C.Structure):
 
 EXPORTS = ["dlc_create", "dlc_destroy", "dlc_compress_bound", "dlc_workspace_bytes", "dlc_stats",
            "dlc_set_error_bounds", "dlc_compress", "dlc_decompress", "dlc_sync_status", "dlc_quantize",
-           "dlc_read_histogram", "dlc_read_codebook", "dlc_profile_enable", "dlc_profile_read", "dlc_strerror"]
+           "dlc_read_histogram", "dlc_read_codebook", "dlc_read_row_refs", "dlc_set_row_match", "dlc_speedup_estimate",
+           "dlc_profile_enable", "dlc_profile_read", "dlc_strerror"]
 
 _lib = None
 
@@ -69,6 +70,10 @@ def lib():
         L.dlc_quantize.argtypes = [vp, vp, vp, vp]
         L.dlc_read_histogram.argtypes = [vp, vp, vp]
         L.dlc_read_codebook.argtypes = [vp, vp, vp, vp]
+        L.dlc_read_row_refs.argtypes = [vp, vp, vp]
+        L.dlc_set_row_match.argtypes = [vp, vp, vp]
+        L.dlc_speedup_estimate.argtypes = [C.c_double] * 4
+        L.dlc_speedup_estimate.restype = C.c_double
         L.dlc_profile_enable.argtypes = [vp, i32]
         L.dlc_profile_read.argtypes = [vp, i32, vp, vp, vp]
         L.dlc_strerror.argtypes = [i32]
@@ -94,11 +99,16 @@ def _check(status, where):
 
 FLAG_FUSED = 1
 FLAG_CARRY_CODEBOOK = 2
+FLAG_ROW_MATCH = 4
 
 
 def make_config(dtype, T, B, D, radius=512, chunk_symbols=256, max_code_len=12, flags=0, num_dest=1) -> Config:
     """num_dest > 1: B is the batch of ONE destination's piece, the payload is [num_dest][T][B][D]."""
     return Config(dtype, T, B, D, radius, chunk_symbols, max_code_len, flags, num_dest)
+
+
+def dlc_speedup_estimate(cr: float, net_gbps: float, tc_gbps: float, td_gbps: float) -> float:
+    return float(lib().dlc_speedup_estimate(cr, net_gbps, tc_gbps, td_gbps))
 
 
 def dlc_compress_bound(cfg: Config) -> int:
@@ -197,6 +207,15 @@ class Context:
         code = np.zeros((self.ND * self.T, self.K), np.uint16)
         _check(lib().dlc_read_codebook(self._h, _np_ptr(ln), _np_ptr(code), _stream_ptr(stream)), "dlc_read_codebook")
         return ln, code
+
+    def set_row_match(self, flags=None, stream=None):
+        f = None if flags is None else np.ascontiguousarray(np.broadcast_to(np.asarray(flags, np.uint8), (self.T,)))
+        _check(lib().dlc_set_row_match(self._h, _np_ptr(f), _stream_ptr(stream)), "dlc_set_row_match")
+
+    def read_row_refs(self, stream=None) -> np.ndarray:
+        r = np.zeros((self.T, self.B), np.uint32)
+        _check(lib().dlc_read_row_refs(self._h, _np_ptr(r), _stream_ptr(stream)), "dlc_read_row_refs")
+        return r
 
     def profile_enable(self, level: int):
         _check(lib().dlc_profile_enable(self._h, level), "dlc_profile_enable")

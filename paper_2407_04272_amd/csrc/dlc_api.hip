@@ -84,7 +84,10 @@ static bool make_geom(const dlc_config* c, Geom* g) {
     if (L < 1 || L > kLmaxLimit || (1 << L) < 2 * R) return false;
     const int S = c->chunk_symbols;
     if (S != 64 && S != 128 && S != 256) return false;
-    if (c->flags & ~(int32_t)(DLC_FLAG_FUSED | DLC_FLAG_CARRY_CODEBOOK)) return false;
+    if (c->flags & ~(int32_t)(DLC_FLAG_FUSED | DLC_FLAG_CARRY_CODEBOOK | DLC_FLAG_ROW_MATCH)) return false;
+    if (c->flags & DLC_FLAG_ROW_MATCH) {  // on its own for now, and a lane's four elements must lie in one row
+        if (c->flags != DLC_FLAG_ROW_MATCH || c->num_dest > 1 || c->dim % 4 != 0) return false;
+    }
     if ((c->flags & DLC_FLAG_FUSED) && (c->flags & DLC_FLAG_CARRY_CODEBOOK)) return false;
     const int64_t nd = c->num_dest == 0 ? 1 : c->num_dest;  // 0: a zero-initialised field means one destination
     if (nd < 1 || nd > 4096) return false;
@@ -101,6 +104,7 @@ static bool make_geom(const dlc_config* c, Geom* g) {
     g->G = (uint32_t)G; g->NG = (uint32_t)NG; g->S = (uint32_t)S; g->R = (uint32_t)R; g->K = 2u * R;
     g->LMAX = (uint32_t)L; g->dtype = (uint32_t)c->dtype; g->es = c->dtype == DLC_F16 ? 2u : 4u;
     g->vec = (n % 4 == 0) ? 1u : 0u;
+    g->lz = (c->flags & DLC_FLAG_ROW_MATCH) ? 1u : 0u;
     return true;
 }
 
@@ -113,7 +117,8 @@ extern "C" size_t dlc_compress_bound(const dlc_config* cfg) {
     const size_t wpc = ((size_t)g.S * g.LMAX + 31) / 32;
     // one container: every chunk full, every element an escape, every symbol used
     const size_t off_cb = a16(F.off_payload + 4 * wpc * kW * g.TD * g.G + 8 * (size_t)g.n * g.TD);
-    const size_t one = off_cb + (size_t)g.TD * ((g.K + 3) & ~3u);
+    size_t one = off_cb + (size_t)g.TD * ((g.K + 3) & ~3u);
+    if (g.lz) one = a16(one) + (size_t)g.TD * a16(4 * (size_t)g.B);  // the row references
     return g.ND == 1 ? one : (size_t)g.ND * a256(one);  // several: one every `capacity / num_dest` bytes, see dlc_compress
 }
 
@@ -139,6 +144,13 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
     uint8_t* arrive = take(4 * (size_t)g.T);
     uint8_t* ready = take(8 * (size_t)g.T);
     uint8_t* escc = take(4 * (size_t)g.T);
+    uint32_t rm_M = 64;
+    while (rm_M < 2 * g.B) rm_M <<= 1;
+    uint8_t* rm_on = g.lz ? take(g.T) : nullptr;
+    uint8_t* rm_ref = g.lz ? take(4 * (size_t)g.T * g.B) : nullptr;
+    uint8_t* rm_keys = g.lz ? take(8 * (size_t)g.T * rm_M) : nullptr;
+    uint8_t* rm_owner = g.lz ? take(4 * (size_t)g.T * rm_M) : nullptr;
+    uint8_t* rm_hash = g.lz ? take(8 * (size_t)g.T * g.B) : nullptr;
     uint8_t* lut = take(((size_t)g.T << g.LMAX) * 2);
     uint8_t* dlay = take(sizeof(DecLayout) * g.ND);
     uint8_t* dtab = take(sizeof(DecTable) * g.T);
@@ -152,6 +164,8 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
         w->arrive = (uint32_t*)arrive; w->ready = (uint64_t*)ready; w->sym_plane = plane;
         w->esc_count = (uint32_t*)escc;
         w->dlay = (DecLayout*)dlay; w->dtab = (DecTable*)dtab;
+        w->rm_on = rm_on; w->rm_ref = (uint32_t*)rm_ref; w->rm_keys = (uint64_t*)rm_keys; w->rm_owner = (uint32_t*)rm_owner;
+        w->rm_hash = (uint64_t*)rm_hash; w->rm_M = rm_M;
     }
     return off;
 }
@@ -178,6 +192,7 @@ extern "C" int dlc_create(dlc_ctx** out, const dlc_config* cfg) {
     if (hipMemset(base, 0, bytes) != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }
     carve(g, base, &c->ws);
     c->ws.carry = (cfg->flags & DLC_FLAG_CARRY_CODEBOOK) ? 1u : 0u;
+    if (g.lz && hipMemset(c->ws.rm_on, 1, g.T) != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }  // all tables
     if (compress_set_attributes() != hipSuccess || decompress_set_attributes() != hipSuccess ||
         ((cfg->flags & DLC_FLAG_FUSED) && fused_plan(g, &c->ws.fused_grid) != hipSuccess)) {
         (void)hipGetLastError();
@@ -328,6 +343,28 @@ extern "C" int dlc_decompress(dlc_ctx* c, const void* d_comp, size_t comp_bytes,
     hipError_t e = launch_decompress(c->g, (const uint8_t*)d_comp, comp_bytes, d_out, c->ws, c->prof.level, &c->prof,
                                      (hipStream_t)stream);
     return e == hipSuccess ? DLC_OK : DLC_EHIP;
+}
+
+extern "C" int dlc_set_row_match(dlc_ctx* c, const uint8_t* h_flags, void* stream) {
+    if (!c) return DLC_EINVAL;
+    if (!c->g.lz) return DLC_ESTATE;
+    std::vector<uint8_t> f(c->g.T, 1);
+    if (h_flags)
+        for (uint32_t t = 0; t < c->g.T; ++t) f[t] = h_flags[t] ? 1 : 0;
+    if (hipMemcpyAsync(c->ws.rm_on, f.data(), c->g.T, hipMemcpyHostToDevice, (hipStream_t)stream) != hipSuccess) return DLC_EHIP;
+    return hipStreamSynchronize((hipStream_t)stream) == hipSuccess ? DLC_OK : DLC_EHIP;  // f goes out of scope
+}
+
+extern "C" int dlc_read_row_refs(dlc_ctx* c, uint32_t* h_ref, void* stream) {
+    if (!c || !h_ref) return DLC_EINVAL;
+    if (!c->g.lz) return DLC_ESTATE;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return DLC_EHIP;
+    return hipMemcpy(h_ref, c->ws.rm_ref, 4ull * c->g.T * c->g.B, hipMemcpyDeviceToHost) == hipSuccess ? DLC_OK : DLC_EHIP;
+}
+
+extern "C" double dlc_speedup_estimate(double cr, double net_gbps, double tc_gbps, double td_gbps) {
+    if (!(cr > 0.0) || !(net_gbps > 0.0) || !(tc_gbps > 0.0) || !(td_gbps > 0.0)) return 0.0;
+    return 1.0 / (1.0 / cr + net_gbps * (1.0 / tc_gbps + 1.0 / td_gbps));
 }
 
 extern "C" int dlc_sync_status(dlc_ctx* c, void* stream) {

@@ -78,9 +78,15 @@ constexpr uint32_t kHistBlk = 4;  // units whose loads are issued back to back
 // One block of kHistBlk units of one table; a unit is 256 consecutive elements (one 16-byte load per lane).
 // `rem` = elements of the table from the block's first element on, `n_units` = units of the block that are this
 // wavefront's.  FULL: all kHistBlk units are, and all their elements are inside the table (no masking at all).
-template <bool F16, bool VEC, bool FULL>
+// LZ (row matching, only with D % 4 == 0 so that a lane's four elements lie in one row): the elements of a row that
+// refers to an earlier row are not counted and get index 254 in the plane, which the encode kernel's table maps to
+// no bits at all; the window is one symbol narrower for that (the symbol that would have had index 254 goes the
+// way of everything outside the window).  ref_t: the table's row references, first: the block's first element.
+template <bool F16, bool VEC, bool FULL, bool LZ>
 __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, uint32_t n_units, uint32_t lane, const QParam& q,
-                                           float Rf, const HistC& H, uint32_t* plane) {
+                                           float Rf, const HistC& H, uint32_t* plane, const uint32_t* ref_t, uint32_t first,
+                                           uint32_t D) {
+    constexpr uint32_t kBins = LZ ? kWinBins - 1u : kWinBins;  // window indices that stand for a symbol
     float x[kHistBlk][4];
     uint32_t raw[kHistBlk][4];
     uint32_t valid[kHistBlk];
@@ -89,9 +95,25 @@ __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, ui
         const uint32_t lim = FULL ? 0xFFFFFFFFu : (u < n_units ? rem : 0u);
         valid[u] = load4<F16, VEC>(base, lane * kV + u * (kW * kV), lim, x[u], raw[u]);
     }
+    bool skip[kHistBlk];
+#pragma unroll
+    for (uint32_t u = 0; u < kHistBlk; ++u) {
+        skip[u] = false;
+        if constexpr (LZ) {
+            const uint32_t el = lane * kV + u * (kW * kV);  // offset of the lane's four elements in the block
+            if (FULL || (u < n_units && el < rem)) {
+                const uint32_t row = (first + el) / D;
+                skip[u] = ref_t[row] != row;
+            }
+        }
+    }
 #pragma unroll
     for (uint32_t u = 0; u < kHistBlk; ++u) {
         uint32_t w[4], sl[4];
+        if (LZ && __ballot(!skip[u]) == 0ull) {  // uniform: the whole unit belongs to referencing rows
+            if (FULL || u < n_units) plane[u * kW + lane] = 0xFEFEFEFEu;
+            continue;
+        }
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             // the quantiser (same arithmetic as quant_symbol), result as a window index; kEscW for an escape
@@ -102,11 +124,14 @@ __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, ui
             const float d = xv - xh;
             const bool ok = (__builtin_fabsf(r) < Rf) & (__builtin_fabsf(d) <= q.eb);  // no short circuit: no branches
             w[v] = ok ? (uint32_t)((int)r + H.ubias) : kEscW;
-            sl[v] = min(w[v], kWinBins);
+            sl[v] = w[v] < kBins ? w[v] : kWinBins;
+            if constexpr (LZ) {
+                if (skip[u]) { sl[v] = kBins; w[v] = kPastEnd; }  // index 254: nothing to count, nothing to code
+            }
             if constexpr (FULL) {
-                DLC_HIST_COUNT(sl[v] * (kWinCopies * 4u) + H.lanebase);
+                if (!LZ || !skip[u]) DLC_HIST_COUNT(sl[v] * (kWinCopies * 4u) + H.lanebase);
             } else {
-                if ((valid[u] >> v) & 1u) DLC_HIST_COUNT(sl[v] * (kWinCopies * 4u) + H.lanebase);
+                if ((valid[u] >> v) & 1u) { if (!LZ || !skip[u]) DLC_HIST_COUNT(sl[v] * (kWinCopies * 4u) + H.lanebase); }
                 else { sl[v] = kWinBins; w[v] = kPastEnd; }
             }
         }
@@ -124,9 +149,9 @@ __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, ui
 // The payload is cut into units of 256 elements, U per table, and every wavefront of the grid gets the same
 // number of consecutive units (table after table), so that all of them finish together whatever the shape is.
 // A work-group whose units touch several tables handles them one table at a time.
-template <bool F16, bool VEC>
+template <bool F16, bool VEC, bool LZ>
 __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const QParam* qp, uint32_t* hist,
-                                              uint8_t* sym_plane, uint32_t U, uint32_t units_per_wave) {
+                                              uint8_t* sym_plane, uint32_t U, uint32_t units_per_wave, const uint32_t* ref) {
     extern __shared__ __align__(16) uint32_t lh[];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t lds0 = (uint32_t)(uintptr_t)lh;
@@ -164,8 +189,9 @@ __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const
                 const uint32_t rem = g.n - first;
                 const uint32_t n_units = min(kHistBlk, ue - u);
                 uint32_t* plane = reinterpret_cast<uint32_t*>(sym_plane + (size_t)t * plane_stride(g) + first);
-                if (n_units == kHistBlk && rem >= kHistBlk * kW * kV) hist_block<F16, VEC, true>(base, rem, n_units, lane, q, Rf, H, plane);
-                else hist_block<F16, VEC, false>(base, rem, n_units, lane, q, Rf, H, plane);
+                const uint32_t* ref_t = LZ ? ref + (size_t)t * g.B : nullptr;
+                if (n_units == kHistBlk && rem >= kHistBlk * kW * kV) hist_block<F16, VEC, true, LZ>(base, rem, n_units, lane, q, Rf, H, plane, ref_t, first, g.D);
+                else hist_block<F16, VEC, false, LZ>(base, rem, n_units, lane, q, Rf, H, plane, ref_t, first, g.D);
             }
         }
         __syncthreads();
@@ -206,7 +232,8 @@ __device__ __forceinline__ uint64_t a16(uint64_t x) { return (x + 15ull) & ~15ul
 __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const TMeta* tmeta, const uint8_t* __restrict__ lens,
                                                    const QParam* qp, Ctrl* ctrl, const uint32_t* word_start,
                                                    const uint32_t* word_end, uint8_t* __restrict__ out, uint64_t capacity,
-                                                   uint64_t* out_bytes, uint32_t* esc_count) {
+                                                   uint64_t* out_bytes, uint32_t* esc_count, const uint8_t* rm_on,
+                                                   const uint32_t* rm_ref) {
     __shared__ uint32_t s_red[17];
     __shared__ uint32_t s_abort;
     __shared__ uint32_t s_cb[1025];   // start of each table's block, relative to the pass's first block
@@ -290,6 +317,55 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
         nout_carry += no_tot;
         __syncthreads();
     }
+    // row matching: the references of the tables that use it, behind the code-length blocks, each block on a 16-byte
+    // boundary (all blocks are 4*B bytes, so block k starts k * a16(4*B) after the first)
+    uint64_t end_bytes = off_cb + cb_carry;  // where the container ends
+    if (rm_on && !s_abort) {
+        rm_on += (size_t)dst * T;
+        rm_ref += (size_t)dst * T * g.B;
+        const uint64_t rbase = a16(end_bytes), rsz = a16(4ull * g.B);
+        uint32_t n_on = 0;  // tables with references
+        for (uint32_t base = 0; base < T; base += 1024) {
+            uint32_t tot;
+            (void)block_excl_scan<16>((base + tid < T && rm_on[base + tid]) ? 1u : 0u, s_red, tid, &tot);
+            n_on += tot;
+            __syncthreads();
+        }
+        if (n_on) end_bytes = rbase + (uint64_t)(n_on - 1u) * rsz + 4ull * g.B;
+        if (end_bytes > capacity) {  // uniform
+            __syncthreads();
+            if (tid == 0) s_abort = 1;
+            __syncthreads();
+        } else if (n_on) {
+            for (uint64_t i = off_cb + cb_carry + tid; first && i < rbase; i += 1024) out[i] = 0;
+            uint32_t on_carry = 0;
+            for (uint32_t base = 0; base < T; base += 1024) {
+                const uint32_t t = base + tid;
+                const uint32_t on = (t < T && rm_on[t]) ? 1u : 0u;
+                uint32_t tot;
+                const uint32_t ex = block_excl_scan<16>(on, s_red, tid, &tot);
+                s_cb[tid] = on ? on_carry + ex : 0xFFFFFFFFu;  // the table's block number
+                __syncthreads();
+                if (first && on) {
+                    uint64_t* d64 = reinterpret_cast<uint64_t*>(out + kHeaderBytes + (uint64_t)kDirBytes * t + 24);
+                    d64[1] = rbase + (uint64_t)(on_carry + ex) * rsz;
+                    table_bytes[t] += 4ull * g.B;
+                }
+                const uint32_t nt = min(1024u, T - base);
+                for (uint32_t lt = blockIdx.x; lt < nt; lt += gridDim.x) {  // a work-group per table
+                    const uint32_t k = s_cb[lt];
+                    if (k == 0xFFFFFFFFu) continue;  // uniform
+                    uint32_t* dstw = reinterpret_cast<uint32_t*>(out + rbase + (uint64_t)k * rsz);
+                    const uint32_t* src = rm_ref + (size_t)(base + lt) * g.B;
+                    for (uint32_t r = tid; r < g.B; r += 1024) dstw[r] = src[r];
+                    if (k + 1u < n_on)  // padding up to the next block
+                        for (uint32_t r = g.B + tid; r < (uint32_t)(rsz / 4u); r += 1024) dstw[r] = 0u;
+                }
+                on_carry += tot;
+                __syncthreads();
+            }
+        }
+    }
     if (!first) return;
     uint64_t container_bytes = 0;  // of this destination; 0 = it did not fit
     if (s_abort) {
@@ -312,7 +388,7 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
             uint64_t* q = reinterpret_cast<uint64_t*>(out);
             q[HQ_NOUT] = nout_carry; q[HQ_WORDS] = words; q[HQ_OFF_GROUP] = F.off_group; q[HQ_OFF_CHUNK] = F.off_chunk;
             q[HQ_OFF_PAYLOAD] = F.off_payload; q[HQ_OFF_CB] = off_cb;
-            const uint64_t total = off_cb + cb_carry;
+            const uint64_t total = end_bytes;
             q[HQ_TOTAL] = total; q[HQ_TOTAL + 1] = 0; q[HQ_TOTAL + 2] = 0; q[HQ_TOTAL + 3] = 0;
             container_bytes = total;
         }
@@ -346,7 +422,11 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
 }
 
 // work-groups of the finalize kernel: a wavefront per table, sixteen wavefronts per work-group
-static inline dim3 finalize_grid(const Geom& g) { return dim3(std::min<uint32_t>((std::min<uint32_t>(g.TD, 1024u) + 15u) / 16u, 64u), g.ND); }
+static inline dim3 finalize_grid(const Geom& g) {
+    // a wavefront per table for the code-length blocks; with row matching a work-group per table copies its references
+    const uint32_t per_wg = g.lz ? 1u : 16u;
+    return dim3(std::min<uint32_t>((std::min<uint32_t>(g.TD, 1024u) + per_wg - 1u) / per_wg, 64u), g.ND);
+}
 
 hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uint64_t capacity, uint64_t* out_bytes,
                            const Ws& w, uint64_t epoch, bool carry_ready, int pl, void* prof, hipStream_t s) {
@@ -364,7 +444,7 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         if (prof_on(pl, P_CARRY)) prof_end(prof, P_CARRY, s);
         if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
         hipLaunchKernelGGL(k_finalize, finalize_grid(g), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
-                           w.word_end, out, capacity, out_bytes, w.esc_count);
+                           w.word_end, out, capacity, out_bytes, w.esc_count, (const uint8_t*)nullptr, (const uint32_t*)nullptr);
         if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
         if (prof_on(pl, P_CODEBOOK)) prof_begin(prof, P_CODEBOOK, s);
         hipLaunchKernelGGL(k_codebook, dim3(g.T), dim3(256), codebook_smem(g.K), s, g, w.hist, w.hist_view, w.enc, w.lens,
@@ -379,9 +459,13 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         if (e != hipSuccess) return e;
         if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
         hipLaunchKernelGGL(k_finalize, finalize_grid(g), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
-                           w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr);
+                           w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr, g.lz ? (const uint8_t*)w.rm_on : nullptr, (const uint32_t*)w.rm_ref);
         if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
         return hipGetLastError();
+    }
+    if (g.lz) {  // row matching: which rows repeat an earlier one (they take no part in what follows)
+        hipError_t e = launch_row_match(g, payload, w, s);
+        if (e != hipSuccess) return e;
     }
     // histogram
     {
@@ -394,9 +478,11 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         const size_t sm = hist_lds_bytes(g.K);
         dim3 grid(grid_n), block(256);
         if (prof_on(pl, P_HIST)) prof_begin(prof, P_HIST, s);
-#define DLC_HIST(FF, V) hipLaunchKernelGGL((k_hist<FF, V>), grid, block, sm, s, payload, g, w.qp, w.hist, w.sym_plane, U, units_per_wave)
-        if (f16) { if (g.vec) DLC_HIST(true, true); else DLC_HIST(true, false); }
-        else { if (g.vec) DLC_HIST(false, true); else DLC_HIST(false, false); }
+#define DLC_HIST(FF, V, L) hipLaunchKernelGGL((k_hist<FF, V, L>), grid, block, sm, s, payload, g, w.qp, w.hist, w.sym_plane, U, units_per_wave, (const uint32_t*)w.rm_ref)
+        if (g.lz) {  // row matching wants D % 4 == 0, which makes every table start 16-byte aligned with n % 4 == 0
+            if (f16) DLC_HIST(true, true, true); else DLC_HIST(false, true, true);
+        } else if (f16) { if (g.vec) DLC_HIST(true, true, false); else DLC_HIST(true, false, false); }
+        else { if (g.vec) DLC_HIST(false, true, false); else DLC_HIST(false, false, false); }
 #undef DLC_HIST
         if (prof_on(pl, P_HIST)) prof_end(prof, P_HIST, s);
     }
@@ -416,7 +502,7 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
     }
     if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
     hipLaunchKernelGGL(k_finalize, finalize_grid(g), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
-                       w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr);
+                       w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr, g.lz ? (const uint8_t*)w.rm_on : nullptr, (const uint32_t*)w.rm_ref);
     if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
     if (w.carry != 0)  // the codebook the next call will use: this call's counts (kept as the copy), escape symbol included
         hipLaunchKernelGGL(k_codebook, dim3(g.T), dim3(256), codebook_smem(g.K), s, g, w.hist_view, w.hist_view, w.enc,

@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
         if (!ok) set_status(ctrl, DLC_ECORRUPT);
     }
     DecTable D;
-    D.valid = 0; D.n_used = 0; D.sym_lo = 0; D.n_outliers = 0; D.ebx2 = 0.f; D.pad = 0;
+    D.valid = 0; D.n_used = 0; D.sym_lo = 0; D.n_outliers = 0; D.ebx2 = 0.f; D.pad = 0; D.ref_off = 0;
     uint32_t sym_lo = 0, sym_hi = 0, n_used = 0;
     uint64_t cb = 0;
     if (ok) {
@@ -68,10 +68,23 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
         D.ebx2 = eb * 2.0f;
         D.sym_lo = sym_lo;
         D.n_used = n_used;
+        // row matching: references behind the code-length blocks (only a context made for it decodes them, and the
+        // kernels want a lane's four elements in one row)
+        D.ref_off = d64[1];
+        if (D.ref_off != 0)
+            ok = ok && g.lz != 0 && (g.D % 4u) == 0 && (D.ref_off % 4u) == 0 && D.ref_off >= off_cb &&
+                 D.ref_off + 4ull * g.B <= total;
     }
     if (tid == 0) s_ok = ok;
     if (tid < kLmaxLimit + 2) s_cl[tid] = 0;
     __syncthreads();
+    if (ok && D.ref_off != 0) {  // every reference points back, at a row that is coded
+        const uint32_t* ref = reinterpret_cast<const uint32_t*>(comp + D.ref_off);
+        for (uint32_t r = tid; r < g.B; r += 256) {
+            const uint32_t o = ref[r];
+            if (o > r || ref[o] != o) s_ok = 0;
+        }
+    }
     const uint32_t nl = ok ? sym_hi - sym_lo + 1u : 0u;
     for (uint32_t i = tid; i < nl; i += 256) {
         const uint32_t l = comp[cb + i];
@@ -227,11 +240,17 @@ __global__ __launch_bounds__(64 * DLC_DEC_WAVES) void k_decode(Geom g, const uin
     uint8_t* tab = static_cast<uint8_t*>(outp) + (size_t)t * g.n * g.es;
     const uint32_t base = grp * (kW * g.S) + lane * kV;
     const uint32_t turns = g.S / kV;
+    const uint32_t* const ref = D.ref_off ? reinterpret_cast<const uint32_t*>(comp + D.ref_off) : nullptr;
     for (uint32_t j = 0; j < turns; ++j) {
         const uint32_t idx = base + j * (kW * kV);
         // a turn takes at most two more words; restage (whole wavefront) when a lane could run off its rows
         if (__ballot(taken + 2u > wbase + kWin && taken < cw) != 0ull) restage();
-        if (idx < g.n) {
+        bool coded = idx < g.n;
+        if (ref != nullptr && coded) {  // a row that refers to another has no bits in the stream; it is copied afterwards
+            const uint32_t row = idx / g.D;
+            coded = ref[row] == row;
+        }
+        if (coded) {
             float v4[4];
 #pragma unroll
             for (int h2 = 0; h2 < 2; ++h2) {
@@ -290,6 +309,23 @@ __global__ __launch_bounds__(64 * DLC_DEC_WAVES) void k_decode(Geom g, const uin
     }
 }
 
+// rows that refer to an earlier row of their table: copies of that row's reconstruction (after the decode kernel)
+__global__ __launch_bounds__(256) void k_row_copy(Geom g, const uint8_t* comp, const DecLayout* dlay, const DecTable* dtab,
+                                                  void* outp, uint32_t rows_grid) {
+    const uint32_t t = blockIdx.y;
+    const DecTable D = dtab[t];
+    if (!dlay[0].valid || !D.valid || D.ref_off == 0) return;  // uniform
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t* ref = reinterpret_cast<const uint32_t*>(comp + D.ref_off);
+    uint32_t* tab = reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(outp) + (size_t)t * g.n * g.es);
+    const uint32_t words = g.D * g.es / 4u;  // a row in 32-bit words (dim % 4 == 0)
+    for (uint32_t row = blockIdx.x * 4 + (threadIdx.x >> 6); row < g.B; row += rows_grid) {
+        const uint32_t o = ref[row];
+        if (o == row) continue;  // uniform over the wavefront
+        for (uint32_t k = lane; k < words; k += 64) tab[(size_t)row * words + k] = tab[(size_t)o * words + k];
+    }
+}
+
 hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_bytes, void* out, const Ws& w, int pl,
                              void* prof, hipStream_t s) {
     const bool f16 = g.dtype == DLC_F16;
@@ -305,6 +341,10 @@ hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_b
         if (f16) { if (g.vec) DLC_DEC(true, true); else DLC_DEC(true, false); }
         else { if (g.vec) DLC_DEC(false, true); else DLC_DEC(false, false); }
 #undef DLC_DEC
+        if (g.lz) {
+            const uint32_t bx = std::min<uint32_t>((g.B + 3) / 4, 64u);
+            hipLaunchKernelGGL(k_row_copy, dim3(bx, g.T), dim3(256), 0, s, g, comp, w.dlay, w.dtab, out, bx * 4);
+        }
         if (prof_on(pl, P_DECODE)) prof_end(prof, P_DECODE, s);
     }
     return hipGetLastError();

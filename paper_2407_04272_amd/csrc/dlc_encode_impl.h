@@ -87,8 +87,9 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
     const uint32_t win_lo = win_lo_of(g.R);
     const uint16_t* enc_t = enc + (size_t)t * g.K;
     {
+        // (with row matching index 254 marks an element of a row that is stored as a reference: no bits)
         const uint32_t c = win_lo + tid;
-        const uint32_t e = (tid < kWinBins && c < g.K) ? enc_t[c] : 0u;
+        const uint32_t e = (tid < (g.lz ? kWinBins - 1u : kWinBins) && c < g.K) ? enc_t[c] : 0u;
         s_len[tid] = (uint16_t)(e >> 12);
         s_code[tid] = (uint16_t)(e & 0xFFFu);
     }
@@ -104,7 +105,7 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
     const uint32_t rem = active ? g.n - gstart : 0u;
     // can index 255 occur in this group at all?  (an escape, a symbol outside the window, a ragged last group)
     const TMeta tm = tmeta[t];
-    const bool plain = tm.n_outliers == 0u && tm.sym_lo >= win_lo && tm.sym_hi < win_lo + kWinBins && rem >= kW * (uint32_t)S;
+    const bool plain = tm.n_outliers == 0u && tm.sym_lo >= win_lo && tm.sym_hi < win_lo + (g.lz ? kWinBins - 1u : kWinBins) && rem >= kW * (uint32_t)S;
     const uint32_t a_len = (uint32_t)(uintptr_t)s_len, d_code = (uint32_t)(uintptr_t)s_code - a_len;
 
     DLC_ESTAMP(1);

@@ -33,6 +33,7 @@ struct Geom {
     uint32_t NG;  // T*G
     uint32_t ND;  // destinations: the payload is [ND][TD][B][D], every destination gets a container of its own
     uint32_t TD;  // tables per destination (= T of a container)
+    uint32_t lz;  // 1: row matching (vector-based LZ step) is on for the tables flagged in Ws::rm_on
     uint32_t S, R, K, LMAX;
     uint32_t dtype, es;
     uint32_t vec;  // 1: every table starts on a 16-byte (fp32) / 8-byte (fp16) boundary and n % 4 == 0
@@ -82,6 +83,7 @@ struct DecTable {
     uint32_t valid, n_used, sym_lo, n_outliers;
     float ebx2;
     uint32_t pad;
+    uint64_t ref_off;  // row matching: byte offset of the table's u32 ref[B] in its container, 0 = none
 };
 
 // ---- device helpers -----------------------------------------------------------------------------
@@ -200,6 +202,7 @@ hipError_t launch_quantize(const Geom& g, const void* payload, const QParam* qp,
 hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uint64_t capacity, uint64_t* out_bytes,
                            const Ws& w, uint64_t epoch, bool carry_ready, int prof_level, void* prof, hipStream_t s);
 hipError_t fused_plan(const Geom& g, uint32_t* grid_out);
+hipError_t launch_row_match(const Geom& g, const void* payload, const Ws& w, hipStream_t s);
 hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_bytes, void* out, const Ws& w,
                              int prof_level, void* prof, hipStream_t s);
 hipError_t launch_stats(const Geom& g, const void* payload, const QParam* probe, const Ws& w, uint32_t M, uint32_t salt,
@@ -225,6 +228,13 @@ struct Ws {
     uint64_t* ready = nullptr;     // [T] call counter of the call whose codebook of the table is complete
     uint32_t fused_grid = 0;       // work-groups of the fused kernel; 0 = separate histogram / codebook / encode kernels
     uint32_t* esc_count = nullptr; // [T] escapes of the call (single-pass path); zero between calls
+    // row matching (allocated only with DLC_FLAG_ROW_MATCH)
+    uint8_t* rm_on = nullptr;      // [T] 1: the table's repeated rows are stored as references
+    uint32_t* rm_ref = nullptr;    // [T][B] first row of the batch with the row's content (the row itself: a coded row)
+    uint64_t* rm_keys = nullptr;   // [T][rm_M] row-hash sets
+    uint32_t* rm_owner = nullptr;  // [T][rm_M]
+    uint64_t* rm_hash = nullptr;   // [T][B]
+    uint32_t rm_M = 0;
     uint32_t carry = 0;            // 1: the codebook is carried from call to call (single-pass path)
     // decompress
     uint16_t* lut = nullptr;       // [T][1 << LMAX]  len << 12 | symbol

@@ -1,0 +1,120 @@
+"""GPU parity of row matching (DLC_FLAG_ROW_MATCH: the vector-based LZ step): references, containers and
+reconstructions against the oracle, bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+from gpu_util import to_device
+from test_oracle_rows import first_occurrence
+
+pytestmark = pytest.mark.gpu
+
+R = 512
+
+
+def _lookups(T, B, D, seed, rows=60, sigma=0.02, dtype=np.float32):
+    rng = np.random.default_rng(seed)
+    table = (rng.standard_normal((T, rows, D)) * sigma).astype(np.float32)
+    idx = rng.integers(0, rows, (T, B))
+    x = np.stack([table[t][idx[t]] for t in range(T)]) * (1 + np.arange(T, dtype=np.float32))[:, None, None]
+    return x.astype(dtype)
+
+
+def _compress(x, ebs, S, flags_per_table=None):
+    import torch
+    from paper_2407_04272_amd import binding as b
+    T, B, D = x.shape
+    dt = b.F16 if x.dtype == np.float16 else b.F32
+    cfg = b.make_config(dt, T, B, D, R, S, 12, b.FLAG_ROW_MATCH)
+    ctx = b.Context(cfg)
+    if flags_per_table is not None:
+        ctx.set_row_match(flags_per_table)
+    cap = b.dlc_compress_bound(cfg)
+    d = to_device(x)
+    out = torch.full((cap + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+    sizes = torch.zeros(1 + T, dtype=torch.int64, device="cuda")
+    ctx.set_error_bounds(eb=ebs)
+    assert ctx.compress(d, out, sizes, capacity=cap) == 0
+    assert ctx.sync_status() == 0
+    h = out.cpu().numpy()
+    assert np.all(h[cap:] == 0xA5)
+    sz = sizes.cpu().numpy().astype(np.uint64)
+    return ctx, d, out, h[:int(sz[0])].copy(), sz
+
+
+CASES = [  # T, B, D, S, dtype
+    (2, 300, 16, 64, np.float32),
+    (3, 1000, 48, 256, np.float32),     # several groups, a partial last one
+    (4, 2048, 128, 256, np.float32),
+    (2, 700, 40, 128, np.float16),
+    (1, 257, 20, 64, np.float32),       # rows that straddle the turns of a chunk
+]
+
+
+@pytest.mark.parametrize("T,B,D,S,dtype", CASES)
+def test_containers_and_references_match_the_oracle(T, B, D, S, dtype):
+    print("row matching", T, B, D, S, np.dtype(dtype).name, flush=True)
+    x = _lookups(T, B, D, 3 * B + D, dtype=dtype)
+    big = 1e9 if dtype == np.float32 else 6e4
+    x[0, 3, 1] = big
+    x[0, 8] = x[0, 3]                       # a repeated row with an escape
+    x[0, 11] = x[0, 3]
+    x[0, 11, 1] = -big                      # escape at the same place, other raw bits: not a repeat
+    ebs = (np.float32(2e-3) * (1 + np.arange(T, dtype=np.float32))).astype(np.float32)
+    ctx, d, out, data, sizes = _compress(x, ebs, S)
+    sym, _ = oracle.quantize(x[0:1], float(ebs[0]), R)
+    for t in range(T):
+        s_t, _ = oracle.quantize(x[t:t + 1], float(ebs[t]), R)
+        assert np.array_equal(ctx.read_row_refs()[t], first_occurrence(x[t:t + 1], s_t)[0]), t
+    o = oracle.compress(x, ebs, R, S, 12, row_match=True)
+    assert o.rc == 0 and data.size == o.data.size
+    diff = np.nonzero(data != o.data)[0]
+    assert diff.size == 0, f"first differing byte {diff[:8]} of {data.size}"
+    assert np.array_equal(sizes, o.sizes)
+    # the GPU decoder: coded rows decoded, the others copied; equal to the oracle's output and within the bound
+    import torch
+    rec = torch.full_like(d, 7.0)
+    assert ctx.decompress(out, data.size, rec) == 0 and ctx.sync_status() == 0
+    rc, orec = oracle.decompress(o.data, x.shape, dtype)
+    u = np.uint32 if dtype == np.float32 else np.uint16
+    r = rec.cpu().numpy()
+    assert rc == 0 and np.array_equal(r.view(u), orec.view(u))
+    fin = np.isfinite(x.astype(np.float32)) & (np.abs(x.astype(np.float32)) < 1e4)
+    err = np.abs(x.astype(np.float64) - r.astype(np.float64))
+    for t in range(T):
+        assert np.all(err[t][fin[t]] <= float(ebs[t]) * (1 + 1e-6))
+
+
+def test_row_matching_per_table():
+    x = _lookups(3, 400, 32, 5)
+    ebs = np.full(3, 1e-3, np.float32)
+    _, _, _, data, sizes = _compress(x, ebs, 128, flags_per_table=[0, 1, 0])
+    o = oracle.compress(x, ebs, R, 128, 12, row_match=[0, 1, 0])
+    assert np.array_equal(data, o.data) and np.array_equal(sizes, o.sizes)
+    _, _, _, data, _ = _compress(x, ebs, 128, flags_per_table=[0, 0, 0])
+    assert np.array_equal(data, oracle.compress(x, ebs, R, 128, 12).data)      # all off: the plain container
+
+
+def test_damaged_references_are_rejected_on_the_gpu():
+    import torch
+    from paper_2407_04272_amd import binding as b
+    import container_reader as cr
+    x = _lookups(2, 300, 16, 9)
+    ebs = np.full(2, 1e-3, np.float32)
+    ctx, d, out, data, sizes = _compress(x, ebs, 64)
+    tb = cr.parse(data).tables[1]
+    i = int(np.nonzero(tb.ref != np.arange(300))[0][0])
+    for bad_value in (i + 1, 0xFFFFFFF0):                  # points forward; points far outside the table
+        bad = data.copy()
+        bad[tb.ref_off + 4 * i:tb.ref_off + 4 * i + 4] = np.frombuffer(np.uint32(bad_value).tobytes(), np.uint8)
+        comp = to_device(np.concatenate([bad, np.zeros(16, np.uint8)]))
+        rec = torch.full_like(d, 7.0)
+        assert ctx.decompress(comp, bad.size, rec) == 0
+        assert ctx.sync_status() == b.ECORRUPT
+        r = rec.cpu().numpy()
+        assert np.all(r[1] == 7.0)                         # the damaged table was left alone
+    # a context without the flag does not take a container with references
+    plain = b.Context(b.make_config(b.F32, 2, 300, 16, R, 64, 12))
+    rec = torch.full_like(d, 7.0)
+    assert plain.decompress(out, data.size, rec) == 0
+    assert plain.sync_status() == b.ECORRUPT
