@@ -354,6 +354,72 @@ def _measure_split(b, torch, np, d, ebs, S, n, with_oracle):
     return row
 
 
+def _measure_rows(b, torch, np, d, ebs, S, with_oracle):
+    """Workload 3 with the row-matching step (vector-based LZ) in front of the entropy coder: on every table, and on
+    the tables Eq. 2 picks for two network bandwidths (the offline compressor selection of Section III-D, with the
+    whole payload as the sample and the whole-call rates of each choice as its throughputs)."""
+    T, B, D = d.shape
+    nbytes = d.numel() * 4
+    out = torch.zeros(nbytes, dtype=torch.uint8, device=d.device)
+    sizes = torch.zeros(1 + T, dtype=torch.int64, device=d.device)
+    rec = torch.empty_like(d)
+
+    def timed(fn, reps=20):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(3):
+            fn()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def run(ctx):
+        c_ms = timed(lambda: ctx.compress(d, out, sizes))
+        assert ctx.sync_status() == 0
+        sz = sizes.cpu().numpy().astype(np.float64)
+        total = int(sz[0])
+        d_ms = timed(lambda: ctx.decompress(out, total, rec))
+        assert ctx.sync_status() == 0
+        return {"total": total, "per_table": sz[1:], "tc": nbytes / c_ms / 1e6, "td": nbytes / d_ms / 1e6}
+
+    ctx = b.Context(b.make_config(b.F32, T, B, D, chunk_symbols=S, flags=b.FLAG_ROW_MATCH))
+    ctx.set_error_bounds(eb=ebs)
+    pctx = b.Context(b.make_config(b.F32, T, B, D, chunk_symbols=S))
+    pctx.set_error_bounds(eb=ebs)
+    plain = run(pctx)
+    lz = run(ctx)
+    refs = ctx.read_row_refs()
+    coded = float((refs == np.arange(B, dtype=np.uint32)[None, :]).mean())
+    eb_t = torch.from_numpy(np.asarray(ebs, np.float64)).to(d.device).view(T, 1, 1)
+    ok = bool(((d.double() - rec.double()).abs() <= eb_t * (1 + 1e-6)).all())
+    rows = [{"workload": "3 with row matching on every table", "payload_MiB": round(nbytes / 2 ** 20, 3),
+             "compression_ratio": round(nbytes / lz["total"], 3), "compress_GBps": round(lz["tc"], 2),
+             "decompress_GBps": round(lz["td"], 2), "coded_rows_fraction": round(coded, 4), "bound_held": ok}]
+    if with_oracle:
+        import oracle
+        k = 3      # one table against the oracle here (the parity tests compare whole containers)
+        o = oracle.compress(d[k:k + 1].cpu().numpy(), ebs[k:k + 1], S=S, row_match=True)
+        rows[0]["table_bytes_equal_oracle"] = bool(o.rc == 0 and int(o.sizes[1]) == int(lz["per_table"][k]))
+    tb = nbytes / T
+    for net in (25.0, 400.0):      # GB/s per GPU: a 200 Gb/s NIC; about half of the seven xGMI links
+        pick = []
+        for t in range(T):
+            s_plain = b.dlc_speedup_estimate(tb / plain["per_table"][t], net, plain["tc"], plain["td"])
+            s_lz = b.dlc_speedup_estimate(tb / lz["per_table"][t], net, lz["tc"], lz["td"])
+            pick.append(1 if s_lz > s_plain else 0)
+        ctx.set_row_match(pick)
+        hy = run(ctx)
+        rows.append({"workload": f"3 hybrid: row matching where Eq. 2 prefers it at {net:g} GB/s network",
+                     "payload_MiB": round(nbytes / 2 ** 20, 3), "tables_with_row_matching": int(sum(pick)),
+                     "compression_ratio": round(nbytes / hy["total"], 3), "compress_GBps": round(hy["tc"], 2),
+                     "decompress_GBps": round(hy["td"], 2),
+                     "speedup_estimate": round(b.dlc_speedup_estimate(nbytes / hy["total"], net, hy["tc"], hy["td"]), 3),
+                     "speedup_estimate_entropy_coder_only": round(b.dlc_speedup_estimate(nbytes / plain["total"], net, plain["tc"], plain["td"]), 3)})
+    return rows
+
+
 def all_workloads(b, torch, np, W, dev, S, with_oracle):
     rows = []
 
@@ -388,6 +454,7 @@ def all_workloads(b, torch, np, W, dev, S, with_oracle):
     rows.append(_measure(b, torch, np, "3: 128 x 8192 x 128, range-relative 0.03", w.payload, ebs, S, with_oracle))
     for n_dest in (8, 32):
         rows.append(_measure_split(b, torch, np, w.payload, ebs, S, n_dest, with_oracle))
+    rows.extend(_measure_rows(b, torch, np, w.payload, ebs, S, with_oracle))
     del w
     torch.cuda.empty_cache()
     w = W.workload4(device=dev)

@@ -179,6 +179,7 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
 #endif
 constexpr uint32_t kWin = DLC_DEC_WIN;            // staged words per lane
 constexpr uint32_t kDecWaves = DLC_DEC_WAVES;        // wavefronts per work-group
+constexpr uint32_t kSkipWords = 256 * kW / kV / 32;   // row matching: a bit per row of a group, rows of at least four elements
 
 template <bool F16, bool VEC>
 __global__ __launch_bounds__(64 * DLC_DEC_WAVES) void k_decode(Geom g, const uint8_t* comp, const uint16_t* lut, const DecLayout* dlay,
@@ -240,15 +241,29 @@ __global__ __launch_bounds__(64 * DLC_DEC_WAVES) void k_decode(Geom g, const uin
     uint8_t* tab = static_cast<uint8_t*>(outp) + (size_t)t * g.n * g.es;
     const uint32_t base = grp * (kW * g.S) + lane * kV;
     const uint32_t turns = g.S / kV;
+    // row matching: which rows of this group refer to another row, as a bit per row in LDS (at most 64*S/4 rows)
     const uint32_t* const ref = D.ref_off ? reinterpret_cast<const uint32_t*>(comp + D.ref_off) : nullptr;
+    uint32_t* const skipbits = reinterpret_cast<uint32_t*>(s_lut + lut_n) + kDecWaves * (kWin * kW) + wave * kSkipWords;
+    const uint32_t row_lo = (grp * (kW * g.S)) / g.D;
+    if (ref != nullptr) {
+        const uint32_t last_el = min(g.n, (grp + 1u) * (kW * g.S)) - 1u;
+        const uint32_t n_rows = last_el / g.D - row_lo + 1u;  // <= 64*S/4 because dim % 4 == 0 here
+        for (uint32_t r0 = 0; r0 < n_rows; r0 += 64) {  // uniform trip count
+            const uint32_t r = r0 + lane;
+            const bool refers = r < n_rows && ref[row_lo + r] != row_lo + r;
+            const uint64_t m = __ballot(refers);
+            if (lane == 0) { skipbits[r0 / 32u] = (uint32_t)m; skipbits[r0 / 32u + 1u] = (uint32_t)(m >> 32); }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
     for (uint32_t j = 0; j < turns; ++j) {
         const uint32_t idx = base + j * (kW * kV);
         // a turn takes at most two more words; restage (whole wavefront) when a lane could run off its rows
         if (__ballot(taken + 2u > wbase + kWin && taken < cw) != 0ull) restage();
         bool coded = idx < g.n;
         if (ref != nullptr && coded) {  // a row that refers to another has no bits in the stream; it is copied afterwards
-            const uint32_t row = idx / g.D;
-            coded = ref[row] == row;
+            const uint32_t r = idx / g.D - row_lo;
+            coded = ((skipbits[r >> 5] >> (r & 31u)) & 1u) == 0u;
         }
         if (coded) {
             float v4[4];
@@ -309,20 +324,22 @@ __global__ __launch_bounds__(64 * DLC_DEC_WAVES) void k_decode(Geom g, const uin
     }
 }
 
-// rows that refer to an earlier row of their table: copies of that row's reconstruction (after the decode kernel)
+// rows that refer to an earlier row of their table: copies of that row's reconstruction (after the decode kernel).
+// A thread per 16-byte (fp32) / 8-byte (fp16) piece of a row, pieces of a row on neighbouring threads.
+template <typename U>
 __global__ __launch_bounds__(256) void k_row_copy(Geom g, const uint8_t* comp, const DecLayout* dlay, const DecTable* dtab,
-                                                  void* outp, uint32_t rows_grid) {
+                                                  void* outp) {
     const uint32_t t = blockIdx.y;
     const DecTable D = dtab[t];
     if (!dlay[0].valid || !D.valid || D.ref_off == 0) return;  // uniform
-    const uint32_t lane = threadIdx.x & 63u;
     const uint32_t* ref = reinterpret_cast<const uint32_t*>(comp + D.ref_off);
-    uint32_t* tab = reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(outp) + (size_t)t * g.n * g.es);
-    const uint32_t words = g.D * g.es / 4u;  // a row in 32-bit words (dim % 4 == 0)
-    for (uint32_t row = blockIdx.x * 4 + (threadIdx.x >> 6); row < g.B; row += rows_grid) {
+    U* tab = reinterpret_cast<U*>(static_cast<uint8_t*>(outp) + (size_t)t * g.n * g.es);
+    const uint32_t upr = g.D / 4u;  // pieces per row (four elements each; dim % 4 == 0)
+    const uint32_t total = g.B * upr;
+    for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
+        const uint32_t row = i / upr, u = i - row * upr;
         const uint32_t o = ref[row];
-        if (o == row) continue;  // uniform over the wavefront
-        for (uint32_t k = lane; k < words; k += 64) tab[(size_t)row * words + k] = tab[(size_t)o * words + k];
+        if (o != row) tab[(size_t)row * upr + u] = tab[(size_t)o * upr + u];
     }
 }
 
@@ -335,15 +352,16 @@ hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_b
     {
         const uint32_t bpt = (g.G + kDecWaves - 1) / kDecWaves;
         dim3 grid(g.T * bpt), block(64 * kDecWaves);
-        const size_t sm = ((size_t)2 << g.LMAX) + (size_t)kDecWaves * kWin * kW * 4;
+        const size_t sm = ((size_t)2 << g.LMAX) + (size_t)kDecWaves * kWin * kW * 4 + (g.lz ? (size_t)kDecWaves * kSkipWords * 4 : 0);
         if (prof_on(pl, P_DECODE)) prof_begin(prof, P_DECODE, s);
 #define DLC_DEC(F, V) hipLaunchKernelGGL((k_decode<F, V>), grid, block, sm, s, g, comp, w.lut, w.dlay, w.dtab, w.ctrl, out, bpt, (uint64_t)comp_bytes)
         if (f16) { if (g.vec) DLC_DEC(true, true); else DLC_DEC(true, false); }
         else { if (g.vec) DLC_DEC(false, true); else DLC_DEC(false, false); }
 #undef DLC_DEC
         if (g.lz) {
-            const uint32_t bx = std::min<uint32_t>((g.B + 3) / 4, 64u);
-            hipLaunchKernelGGL(k_row_copy, dim3(bx, g.T), dim3(256), 0, s, g, comp, w.dlay, w.dtab, out, bx * 4);
+            const uint32_t bx = std::min<uint32_t>((g.B * (g.D / 4u) + 255u) / 256u, 256u);
+            if (f16) hipLaunchKernelGGL(k_row_copy<uint2>, dim3(bx, g.T), dim3(256), 0, s, g, comp, w.dlay, w.dtab, out);
+            else hipLaunchKernelGGL(k_row_copy<uint4>, dim3(bx, g.T), dim3(256), 0, s, g, comp, w.dlay, w.dtab, out);
         }
         if (prof_on(pl, P_DECODE)) prof_end(prof, P_DECODE, s);
     }
@@ -351,7 +369,7 @@ hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_b
 }
 
 hipError_t decompress_set_attributes() {
-    const int bytes = (2 << kLmaxLimit) + (int)(kDecWaves * kWin * kW * 4);
+    const int bytes = (2 << kLmaxLimit) + (int)(kDecWaves * kWin * kW * 4) + (int)(kDecWaves * kSkipWords * 4);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_decode<false, false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e == hipSuccess)
