@@ -144,13 +144,11 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
     uint8_t* arrive = take(4 * (size_t)g.T);
     uint8_t* ready = take(8 * (size_t)g.T);
     uint8_t* escc = take(4 * (size_t)g.T);
-    uint32_t rm_M = 64;
-    while (rm_M < 2 * g.B) rm_M <<= 1;
     uint8_t* rm_on = g.lz ? take(g.T) : nullptr;
     uint8_t* rm_ref = g.lz ? take(4 * (size_t)g.T * g.B) : nullptr;
-    uint8_t* rm_keys = g.lz ? take(8 * (size_t)g.T * rm_M) : nullptr;
-    uint8_t* rm_owner = g.lz ? take(4 * (size_t)g.T * rm_M) : nullptr;
     uint8_t* rm_hash = g.lz ? take(8 * (size_t)g.T * g.B) : nullptr;
+    uint8_t* rm_own = g.lz ? take(4 * (size_t)g.T * g.B) : nullptr;
+    uint8_t* rm_mult = g.lz ? take(32 * (size_t)(g.D / 4u)) : nullptr;
     uint8_t* lut = take(((size_t)g.T << g.LMAX) * 2);
     uint8_t* dlay = take(sizeof(DecLayout) * g.ND);
     uint8_t* dtab = take(sizeof(DecTable) * g.T);
@@ -164,8 +162,8 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
         w->arrive = (uint32_t*)arrive; w->ready = (uint64_t*)ready; w->sym_plane = plane;
         w->esc_count = (uint32_t*)escc;
         w->dlay = (DecLayout*)dlay; w->dtab = (DecTable*)dtab;
-        w->rm_on = rm_on; w->rm_ref = (uint32_t*)rm_ref; w->rm_keys = (uint64_t*)rm_keys; w->rm_owner = (uint32_t*)rm_owner;
-        w->rm_hash = (uint64_t*)rm_hash; w->rm_M = rm_M;
+        w->rm_on = rm_on; w->rm_ref = (uint32_t*)rm_ref; w->rm_hash = (uint64_t*)rm_hash; w->rm_own = (uint32_t*)rm_own;
+        w->rm_mult = (uint32_t*)rm_mult;
     }
     return off;
 }
@@ -193,7 +191,12 @@ extern "C" int dlc_create(dlc_ctx** out, const dlc_config* cfg) {
     carve(g, base, &c->ws);
     c->ws.carry = (cfg->flags & DLC_FLAG_CARRY_CODEBOOK) ? 1u : 0u;
     if (g.lz && hipMemset(c->ws.rm_on, 1, g.T) != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }  // all tables
-    if (compress_set_attributes() != hipSuccess || decompress_set_attributes() != hipSuccess ||
+    if (g.lz) {
+        std::vector<uint32_t> mult(8 * (size_t)(g.D / 4u));
+        row_match_multipliers(mult.data(), g.D / 4u);
+        if (hipMemcpy(c->ws.rm_mult, mult.data(), 4 * mult.size(), hipMemcpyHostToDevice) != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }
+    }
+    if (compress_set_attributes() != hipSuccess || decompress_set_attributes() != hipSuccess || row_match_set_attributes() != hipSuccess ||
         ((cfg->flags & DLC_FLAG_FUSED) && fused_plan(g, &c->ws.fused_grid) != hipSuccess)) {
         (void)hipGetLastError();
         (void)hipFree(base);

@@ -78,14 +78,12 @@ constexpr uint32_t kHistBlk = 4;  // units whose loads are issued back to back
 // One block of kHistBlk units of one table; a unit is 256 consecutive elements (one 16-byte load per lane).
 // `rem` = elements of the table from the block's first element on, `n_units` = units of the block that are this
 // wavefront's.  FULL: all kHistBlk units are, and all their elements are inside the table (no masking at all).
-// LZ (row matching, only with D % 4 == 0 so that a lane's four elements lie in one row): the elements of a row that
-// refers to an earlier row are not counted and get index 254 in the plane, which the encode kernel's table maps to
-// no bits at all; the window is one symbol narrower for that (the symbol that would have had index 254 goes the
-// way of everything outside the window).  ref_t: the table's row references, first: the block's first element.
+// LZ (row matching): the window is one symbol narrower, because index 254 in the plane stands for an element of a
+// row that is stored as a reference (the row-matching kernels put it there afterwards); the symbol that would have
+// had index 254 goes the way of everything outside the window.
 template <bool F16, bool VEC, bool FULL, bool LZ>
 __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, uint32_t n_units, uint32_t lane, const QParam& q,
-                                           float Rf, const HistC& H, uint32_t* plane, const uint32_t* ref_t, uint32_t first,
-                                           uint32_t D) {
+                                           float Rf, const HistC& H, uint32_t* plane) {
     constexpr uint32_t kBins = LZ ? kWinBins - 1u : kWinBins;  // window indices that stand for a symbol
     float x[kHistBlk][4];
     uint32_t raw[kHistBlk][4];
@@ -95,25 +93,9 @@ __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, ui
         const uint32_t lim = FULL ? 0xFFFFFFFFu : (u < n_units ? rem : 0u);
         valid[u] = load4<F16, VEC>(base, lane * kV + u * (kW * kV), lim, x[u], raw[u]);
     }
-    bool skip[kHistBlk];
-#pragma unroll
-    for (uint32_t u = 0; u < kHistBlk; ++u) {
-        skip[u] = false;
-        if constexpr (LZ) {
-            const uint32_t el = lane * kV + u * (kW * kV);  // offset of the lane's four elements in the block
-            if (FULL || (u < n_units && el < rem)) {
-                const uint32_t row = (first + el) / D;
-                skip[u] = ref_t[row] != row;
-            }
-        }
-    }
 #pragma unroll
     for (uint32_t u = 0; u < kHistBlk; ++u) {
         uint32_t w[4], sl[4];
-        if (LZ && __ballot(!skip[u]) == 0ull) {  // uniform: the whole unit belongs to referencing rows
-            if (FULL || u < n_units) plane[u * kW + lane] = 0xFEFEFEFEu;
-            continue;
-        }
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             // the quantiser (same arithmetic as quant_symbol), result as a window index; kEscW for an escape
@@ -125,13 +107,10 @@ __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, ui
             const bool ok = (__builtin_fabsf(r) < Rf) & (__builtin_fabsf(d) <= q.eb);  // no short circuit: no branches
             w[v] = ok ? (uint32_t)((int)r + H.ubias) : kEscW;
             sl[v] = w[v] < kBins ? w[v] : kWinBins;
-            if constexpr (LZ) {
-                if (skip[u]) { sl[v] = kBins; w[v] = kPastEnd; }  // index 254: nothing to count, nothing to code
-            }
             if constexpr (FULL) {
-                if (!LZ || !skip[u]) DLC_HIST_COUNT(sl[v] * (kWinCopies * 4u) + H.lanebase);
+                DLC_HIST_COUNT(sl[v] * (kWinCopies * 4u) + H.lanebase);
             } else {
-                if ((valid[u] >> v) & 1u) { if (!LZ || !skip[u]) DLC_HIST_COUNT(sl[v] * (kWinCopies * 4u) + H.lanebase); }
+                if ((valid[u] >> v) & 1u) DLC_HIST_COUNT(sl[v] * (kWinCopies * 4u) + H.lanebase);
                 else { sl[v] = kWinBins; w[v] = kPastEnd; }
             }
         }
@@ -151,7 +130,7 @@ __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, ui
 // A work-group whose units touch several tables handles them one table at a time.
 template <bool F16, bool VEC, bool LZ>
 __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const QParam* qp, uint32_t* hist,
-                                              uint8_t* sym_plane, uint32_t U, uint32_t units_per_wave, const uint32_t* ref) {
+                                              uint8_t* sym_plane, uint32_t U, uint32_t units_per_wave) {
     extern __shared__ __align__(16) uint32_t lh[];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t lds0 = (uint32_t)(uintptr_t)lh;
@@ -189,9 +168,8 @@ __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const
                 const uint32_t rem = g.n - first;
                 const uint32_t n_units = min(kHistBlk, ue - u);
                 uint32_t* plane = reinterpret_cast<uint32_t*>(sym_plane + (size_t)t * plane_stride(g) + first);
-                const uint32_t* ref_t = LZ ? ref + (size_t)t * g.B : nullptr;
-                if (n_units == kHistBlk && rem >= kHistBlk * kW * kV) hist_block<F16, VEC, true, LZ>(base, rem, n_units, lane, q, Rf, H, plane, ref_t, first, g.D);
-                else hist_block<F16, VEC, false, LZ>(base, rem, n_units, lane, q, Rf, H, plane, ref_t, first, g.D);
+                if (n_units == kHistBlk && rem >= kHistBlk * kW * kV) hist_block<F16, VEC, true, LZ>(base, rem, n_units, lane, q, Rf, H, plane);
+                else hist_block<F16, VEC, false, LZ>(base, rem, n_units, lane, q, Rf, H, plane);
             }
         }
         __syncthreads();
@@ -463,10 +441,6 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
         return hipGetLastError();
     }
-    if (g.lz) {  // row matching: which rows repeat an earlier one (they take no part in what follows)
-        hipError_t e = launch_row_match(g, payload, w, s);
-        if (e != hipSuccess) return e;
-    }
     // histogram
     {
         // equal shares of 16 units (16 KiB of fp32) per wavefront: measured best on MI355X, a little ahead of one
@@ -478,13 +452,17 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         const size_t sm = hist_lds_bytes(g.K);
         dim3 grid(grid_n), block(256);
         if (prof_on(pl, P_HIST)) prof_begin(prof, P_HIST, s);
-#define DLC_HIST(FF, V, L) hipLaunchKernelGGL((k_hist<FF, V, L>), grid, block, sm, s, payload, g, w.qp, w.hist, w.sym_plane, U, units_per_wave, (const uint32_t*)w.rm_ref)
+#define DLC_HIST(FF, V, L) hipLaunchKernelGGL((k_hist<FF, V, L>), grid, block, sm, s, payload, g, w.qp, w.hist, w.sym_plane, U, units_per_wave)
         if (g.lz) {  // row matching wants D % 4 == 0, which makes every table start 16-byte aligned with n % 4 == 0
             if (f16) DLC_HIST(true, true, true); else DLC_HIST(false, true, true);
         } else if (f16) { if (g.vec) DLC_HIST(true, true, false); else DLC_HIST(true, false, false); }
         else { if (g.vec) DLC_HIST(false, true, false); else DLC_HIST(false, false, false); }
 #undef DLC_HIST
         if (prof_on(pl, P_HIST)) prof_end(prof, P_HIST, s);
+    }
+    if (g.lz) {  // row matching: which rows repeat an earlier one; their elements leave the plane and the counts again
+        hipError_t e = launch_row_match(g, payload, w, s);
+        if (e != hipSuccess) return e;
     }
     if (prof_on(pl, P_CODEBOOK)) prof_begin(prof, P_CODEBOOK, s);
     hipLaunchKernelGGL(k_codebook, dim3(g.T), dim3(256), codebook_smem(g.K), s, g, w.hist, w.hist_view, w.enc, w.lens,

@@ -203,6 +203,9 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
                            const Ws& w, uint64_t epoch, bool carry_ready, int prof_level, void* prof, hipStream_t s);
 hipError_t fused_plan(const Geom& g, uint32_t* grid_out);
 hipError_t launch_row_match(const Geom& g, const void* payload, const Ws& w, hipStream_t s);
+// the row hash's multipliers, eight words per 4-byte piece of a row (six used), computed on the host once
+void row_match_multipliers(uint32_t* mult, uint32_t n_pieces);
+hipError_t row_match_set_attributes();
 hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_bytes, void* out, const Ws& w,
                              int prof_level, void* prof, hipStream_t s);
 hipError_t launch_stats(const Geom& g, const void* payload, const QParam* probe, const Ws& w, uint32_t M, uint32_t salt,
@@ -231,10 +234,9 @@ struct Ws {
     // row matching (allocated only with DLC_FLAG_ROW_MATCH)
     uint8_t* rm_on = nullptr;      // [T] 1: the table's repeated rows are stored as references
     uint32_t* rm_ref = nullptr;    // [T][B] first row of the batch with the row's content (the row itself: a coded row)
-    uint64_t* rm_keys = nullptr;   // [T][rm_M] row-hash sets
-    uint32_t* rm_owner = nullptr;  // [T][rm_M]
-    uint64_t* rm_hash = nullptr;   // [T][B]
-    uint32_t rm_M = 0;
+    uint64_t* rm_hash = nullptr;   // [T][B] row hashes
+    uint32_t* rm_own = nullptr;    // [T][B] the smallest row index with the row's hash
+    uint32_t* rm_mult = nullptr;   // [D/4][8] multipliers of the row hash
     uint32_t carry = 0;            // 1: the codebook is carried from call to call (single-pass path)
     // decompress
     uint16_t* lut = nullptr;       // [T][1 << LMAX]  len << 12 | symbol

@@ -102,8 +102,7 @@ __global__ __launch_bounds__(256) void k_stats_hash(const void* payload, Geom g,
             uint32_t* oo = owner + set * M;
             uint32_t pos = (uint32_t)(hsh >> 20) & (M - 1u);
             for (uint32_t probe_n = 0; probe_n < M; ++probe_n) {
-                const uint64_t prev = atomicCAS(reinterpret_cast<unsigned long long*>(&kk[pos]), 0ull,
-                                                (unsigned long long)hsh);
+                const uint64_t prev = atomicCAS(reinterpret_cast<unsigned long long*>(&kk[pos]), 0ull, (unsigned long long)hsh);
                 if (prev == 0ull || prev == hsh) {
                     atomicMin(&oo[pos], row);
                     break;

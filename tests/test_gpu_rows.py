@@ -48,6 +48,9 @@ CASES = [  # T, B, D, S, dtype
     (4, 2048, 128, 256, np.float32),
     (2, 700, 40, 128, np.float16),
     (1, 257, 20, 64, np.float32),       # rows that straddle the turns of a chunk
+    (1, 200, 260, 64, np.float32),      # long rows: more 4-byte pieces than a wavefront has lanes
+    (1, 130, 1040, 128, np.float32),    # the same with 16-byte pieces
+    (2, 9000, 32, 256, np.float16),     # more rows than one pass of the set kernel's threads
 ]
 
 
