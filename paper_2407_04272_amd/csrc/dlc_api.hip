@@ -54,7 +54,6 @@ struct dlc_ctx {
     int device = 0;
     bool bounds_set = false;
     uint64_t epoch = 0;
-    uint32_t stats_M = 0;
     Prof prof;
     // pinned staging ring for the per-table quantiser parameters (one slot per set_error_bounds call)
     static constexpr int kRing = 16;
@@ -397,24 +396,20 @@ extern "C" int dlc_stats(dlc_ctx* c, const void* d_payload, const float* probe_e
     hipStream_t s = (hipStream_t)stream;
     Ws& w = c->ws;
     if (!w.stats_base) {
-        uint32_t M = 64;
-        while (M < 2ull * g.B) M <<= 1;
         size_t off = 0;
         auto take = [&](size_t b) { size_t o = off; off = a256(off + b); return o; };
         const size_t o_probe = take(sizeof(QParam) * g.T);
-        const size_t o_keys = take(2ull * g.T * M * 8);
-        const size_t o_owner = take(2ull * g.T * M * 4);
+        const size_t o_own = take(2ull * g.T * g.B * 4);
+        const size_t o_mult = take(16ull * g.D);
         const size_t o_hash = take(2ull * g.T * g.B * 8);
         const size_t o_mm = take(8ull * g.T);
         const size_t o_un = take(8ull * g.T);
         uint8_t* base = nullptr;
         if (hipMalloc((void**)&base, off) != hipSuccess) { (void)hipGetLastError(); return DLC_ENOMEM; }
         w.stats_base = base; w.stats_bytes = off;
-        w.probe = (QParam*)(base + o_probe); w.keys = (uint64_t*)(base + o_keys); w.owner = (uint32_t*)(base + o_owner);
+        w.probe = (QParam*)(base + o_probe); w.st_own = (uint32_t*)(base + o_own); w.st_mult = (uint32_t*)(base + o_mult);
         w.rowhash = (uint64_t*)(base + o_hash); w.st_minmax = (uint32_t*)(base + o_mm); w.st_unique = (uint32_t*)(base + o_un);
-        c->stats_M = M;
     }
-    const uint32_t M = c->stats_M;
     std::vector<QParam> pq(g.T);
     for (uint32_t t = 0; t < g.T; ++t) pq[t] = make_qparam(probe_eb[t]);
     std::vector<uint32_t> mm(2 * g.T), un(2 * g.T);
@@ -423,12 +418,10 @@ extern "C" int dlc_stats(dlc_ctx* c, const void* d_payload, const float* probe_e
         for (uint32_t t = 0; t < g.T; ++t) { mm0[2 * t] = 0xFFFFFFFFu; mm0[2 * t + 1] = 0u; }
         if (hipMemcpyAsync(w.probe, pq.data(), sizeof(QParam) * g.T, hipMemcpyHostToDevice, s) != hipSuccess) return DLC_EHIP;
         if (hipMemcpyAsync(w.st_minmax, mm0.data(), 8ull * g.T, hipMemcpyHostToDevice, s) != hipSuccess) return DLC_EHIP;
-        if (hipMemsetAsync(w.keys, 0, 2ull * g.T * M * 8, s) != hipSuccess) return DLC_EHIP;
-        if (hipMemsetAsync(w.owner, 0xFF, 2ull * g.T * M * 4, s) != hipSuccess) return DLC_EHIP;
         if (hipMemsetAsync(w.st_unique, 0, 8ull * g.T, s) != hipSuccess) return DLC_EHIP;
         if (hipMemsetAsync(&w.ctrl->collide, 0, 4, s) != hipSuccess) return DLC_EHIP;
         if (hipStreamSynchronize(s) != hipSuccess) return DLC_EHIP;  // staging vectors above are reused per attempt
-        if (launch_stats(g, d_payload, w.probe, w, M, 0x51ED270Bu * (attempt + 1), s) != hipSuccess) return DLC_EHIP;
+        if (launch_stats(g, d_payload, w.probe, w, 0x51ED270Bu * (attempt + 1), s) != hipSuccess) return DLC_EHIP;
         uint32_t collide = 0;
         if (hipMemcpyAsync(mm.data(), w.st_minmax, 8ull * g.T, hipMemcpyDeviceToHost, s) != hipSuccess) return DLC_EHIP;
         if (hipMemcpyAsync(un.data(), w.st_unique, 8ull * g.T, hipMemcpyDeviceToHost, s) != hipSuccess) return DLC_EHIP;

@@ -206,9 +206,12 @@ hipError_t launch_row_match(const Geom& g, const void* payload, const Ws& w, hip
 // the row hash's multipliers, eight words per 4-byte piece of a row (six used), computed on the host once
 void row_match_multipliers(uint32_t* mult, uint32_t n_pieces);
 hipError_t row_match_set_attributes();
+// per table and set: own[row] = the smallest row index whose hash equals the row's (see k_rm_sets)
+hipError_t launch_row_sets(const Geom& g, uint32_t n_sets, const uint8_t* on, const uint64_t* rowhash, uint32_t* own,
+                           uint32_t* unique, Ctrl* ctrl, hipStream_t s);
 hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_bytes, void* out, const Ws& w,
                              int prof_level, void* prof, hipStream_t s);
-hipError_t launch_stats(const Geom& g, const void* payload, const QParam* probe, const Ws& w, uint32_t M, uint32_t salt,
+hipError_t launch_stats(const Geom& g, const void* payload, const QParam* probe, const Ws& w, uint32_t salt,
                         hipStream_t s);
 
 // device workspace of a context
@@ -246,9 +249,9 @@ struct Ws {
     uint8_t* stats_base = nullptr;
     size_t stats_bytes = 0;
     QParam* probe = nullptr;       // [T]
-    uint64_t* keys = nullptr;      // [2][T][M]
-    uint32_t* owner = nullptr;     // [2][T][M]
-    uint64_t* rowhash = nullptr;   // [2][T][B]
+    uint64_t* rowhash = nullptr;   // [2][T][B] row hashes: raw bits, symbols at the probe bound
+    uint32_t* st_own = nullptr;    // [2][T][B] the smallest row index with the row's hash
+    uint32_t* st_mult = nullptr;   // [D][4] multipliers of the row hashes
     uint32_t* st_minmax = nullptr; // [T][2] order-preserving encodings
     uint32_t* st_unique = nullptr; // [T][2]
 };

@@ -176,22 +176,27 @@ __global__ __launch_bounds__(256) void k_rm_hash(const void* payload, Geom g, co
     }
 }
 
-// the sets: work-group (part, t) takes the rows of table t whose hashes' top bits say `part`, puts them into an
+// the sets: work-group (part, t, set) takes the rows of table t whose hashes' top bits say `part`, puts them into an
 // open-addressing set in LDS (a slot holds a row index; the hash of the row that sits there is read from memory,
 // and only rows with that hash ever replace it, the smaller index winning), and then looks every one of its rows
 // up again: own[row] = the smallest row index with the row's hash.  n_slots (a power of two) is the batch size or
 // more whenever that fits the LDS, so the set cannot fill up; where it is less and does fill up, the rows that
-// found no slot are their own owners, that is, coded rows.
+// found no slot are their own owners (coded rows, for row matching), and ctrl, if given, gets an error (the
+// statistics want exact counts).  rowhash and own: [sets][T][B]; on (optional): tables to skip; unique (optional):
+// [T][sets] counts of the rows that own their hash.
 __global__ __launch_bounds__(1024) void k_rm_sets(Geom g, const uint8_t* on, const uint64_t* rowhash, uint32_t* own,
-                                                  uint32_t n_slots, uint32_t parts) {
+                                                  uint32_t n_slots, uint32_t parts, uint32_t* unique, Ctrl* ctrl) {
     extern __shared__ __align__(16) uint32_t slot[];
-    const uint32_t part = blockIdx.x, t = blockIdx.y, tid = threadIdx.x;
-    if (!on[t]) return;  // uniform
+    __shared__ uint32_t s_owners;
+    const uint32_t part = blockIdx.x, t = blockIdx.y, set = blockIdx.z, tid = threadIdx.x;
+    if (on && !on[t]) return;  // uniform
     constexpr uint32_t kEmpty = 0xFFFFFFFFu;
     constexpr uint32_t kBatch = 4;  // hashes a thread loads back to back
     for (uint32_t k = tid; k < n_slots; k += 1024) slot[k] = kEmpty;
+    if (tid == 0) s_owners = 0u;
     __syncthreads();
-    const uint64_t* rh = rowhash + (size_t)t * g.B;
+    const uint64_t* rh = rowhash + ((size_t)set * g.T + t) * g.B;
+    uint32_t* own_t = own + ((size_t)set * g.T + t) * g.B;
     volatile uint32_t* vslot = slot;
     for (uint32_t r0 = tid; r0 < g.B; r0 += 1024u * kBatch) {
         uint64_t h[kBatch];
@@ -202,21 +207,25 @@ __global__ __launch_bounds__(1024) void k_rm_sets(Geom g, const uint8_t* on, con
             const uint32_t row = r0 + k * 1024u;
             if (row >= g.B || ((uint32_t)(h[k] >> 59) & (parts - 1u)) != part) continue;
             uint32_t pos = (uint32_t)(h[k] >> 20) & (n_slots - 1u);
+            bool placed = false;
             for (uint32_t probe_n = 0; probe_n < n_slots; ++probe_n) {
                 uint32_t cur = vslot[pos];
                 if (cur == kEmpty) {
                     cur = atomicCAS(&slot[pos], kEmpty, row);
-                    if (cur == kEmpty) break;
+                    if (cur == kEmpty) { placed = true; break; }
                 }
                 if (rh[cur] == h[k]) {
                     atomicMin(&slot[pos], row);
+                    placed = true;
                     break;
                 }
                 pos = (pos + 1u) & (n_slots - 1u);
             }
+            if (!placed && ctrl) set_status(ctrl, DLC_ESTATE);
         }
     }
     __syncthreads();
+    uint32_t owners = 0;
     for (uint32_t r0 = tid; r0 < g.B; r0 += 1024u * kBatch) {
         uint64_t h[kBatch];
 #pragma unroll
@@ -233,8 +242,15 @@ __global__ __launch_bounds__(1024) void k_rm_sets(Geom g, const uint8_t* on, con
                 if (cur == row || rh[cur] == h[k]) { o = cur; break; }
                 pos = (pos + 1u) & (n_slots - 1u);
             }
-            own[(size_t)t * g.B + row] = o;
+            own_t[row] = o;
+            owners += o == row ? 1u : 0u;
         }
+    }
+    if (unique) {  // uniform
+        for (int o = 32; o > 0; o >>= 1) owners += (uint32_t)__shfl_xor((int)owners, o, 64);
+        if ((tid & 63u) == 0u && owners) atomicAdd(&s_owners, owners);
+        __syncthreads();
+        if (tid == 0 && s_owners) atomicAdd(&unique[(size_t)t * gridDim.z + set], s_owners);
     }
 }
 
@@ -393,6 +409,18 @@ void row_match_multipliers(uint32_t* mult, uint32_t n_pieces) {
         for (uint32_t i = 0; i < 8; ++i) mult[8 * p + i] = i < 6 ? (rm_mix32(p * 6u + i + 1u) & 0xFFFFFFu) : 0u;
 }
 
+hipError_t launch_row_sets(const Geom& g, uint32_t n_sets, const uint8_t* on, const uint64_t* rowhash, uint32_t* own,
+                           uint32_t* unique, Ctrl* ctrl, hipStream_t s) {
+    // about a thousand work-groups in all, 32 per table and set at most; slots for the whole batch, 64 KiB at most
+    uint32_t parts = 1;
+    while (parts < 32u && parts * g.T * n_sets < 1024u) parts <<= 1;
+    uint32_t n_slots = 64;
+    while (n_slots < g.B && n_slots < 16384u) n_slots <<= 1;
+    hipLaunchKernelGGL(k_rm_sets, dim3(parts, g.T, n_sets), dim3(1024), n_slots * 4u, s, g, on, rowhash, own, n_slots, parts,
+                       unique, ctrl);
+    return hipGetLastError();
+}
+
 hipError_t launch_row_match(const Geom& g, const void* payload, const Ws& w, hipStream_t s) {
     const uint32_t pw = g.D % 16u == 0u ? 4u : 1u;  // words of the plane per lane in pass 2
     uint32_t logL = 0;
@@ -400,17 +428,15 @@ hipError_t launch_row_match(const Geom& g, const void* payload, const Ws& w, hip
     const uint32_t blocks_x = std::min<uint32_t>((g.B + 255u) / 256u, 32u);  // a wavefront takes 64 rows at a time
     const uint32_t waves_grid = blocks_x * 4;
     const size_t sm = hist_lds_bytes(g.K);
-    // the sets: about a thousand work-groups in all, 32 per table at most; slots for the whole batch, 64 KiB at most
-    uint32_t parts = 1;
-    while (parts < 32u && parts * g.T < 1024u) parts <<= 1;
-    uint32_t n_slots = 64;
-    while (n_slots < g.B && n_slots < 16384u) n_slots <<= 1;
     dim3 grid(blocks_x, g.T), block(256);
     if (g.dtype == DLC_F16)
         hipLaunchKernelGGL(k_rm_hash<true>, grid, block, 0, s, payload, g, w.qp, w.rm_on, w.rm_hash, w.sym_plane, w.rm_mult, waves_grid);
     else
         hipLaunchKernelGGL(k_rm_hash<false>, grid, block, 0, s, payload, g, w.qp, w.rm_on, w.rm_hash, w.sym_plane, w.rm_mult, waves_grid);
-    hipLaunchKernelGGL(k_rm_sets, dim3(parts, g.T), dim3(1024), n_slots * 4u, s, g, w.rm_on, w.rm_hash, w.rm_own, n_slots, parts);
+    {
+        hipError_t e = launch_row_sets(g, 1u, w.rm_on, w.rm_hash, w.rm_own, nullptr, nullptr, s);
+        if (e != hipSuccess) return e;
+    }
 #define DLC_RM_OWNER(FF, PP) hipLaunchKernelGGL((k_rm_owner<FF, PP>), grid, block, sm, s, payload, g, w.qp, w.rm_on, w.rm_own, w.rm_ref, w.sym_plane, w.hist, waves_grid, logL)
     if (g.dtype == DLC_F16) { if (pw == 4u) DLC_RM_OWNER(true, 4); else DLC_RM_OWNER(true, 1); }
     else { if (pw == 4u) DLC_RM_OWNER(false, 4); else DLC_RM_OWNER(false, 1); }

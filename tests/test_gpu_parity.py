@@ -187,7 +187,10 @@ def test_stats_small_cases():
     from paper_2407_04272_amd import binding as b
     rng = np.random.default_rng(9)
     for (T, B, D, dtype) in [(2, 40, 5, np.float32), (3, 300, 70, np.float32), (2, 257, 128, np.float16),
-                             (1, 1, 1, np.float32)]:
+                             (1, 1, 1, np.float32), (2, 130, 7, np.float16), (2, 300, 6, np.float16),
+                             (1, 100, 300, np.float32),     # rows longer than a wavefront's 64 16-byte pieces
+                             (1, 5000, 2, np.float32),      # nearly every row repeats another
+                             (2, 1500, 3, np.float16)]:
         vals = rng.choice(np.linspace(-1, 1, 9), (T, B, D)).astype(np.float32)
         vals += (rng.random((T, B, D)) < 0.2) * np.float32(0.003)
         vals[0, 0, 0] = np.nan
