@@ -73,7 +73,7 @@ __device__ __forceinline__ void carry_count(uint32_t addr) {
 // (an escape, a symbol outside the window, NaN, a position past the end of the table).  The index comes straight
 // out of the float pipeline as a byte offset, 4*i, clamped to [0, 1024].
 constexpr uint32_t kCarryRows = 257;
-constexpr uint32_t kCarryRecs = 16;   // escape records a wavefront keeps in LDS; a group with more walks its elements again
+constexpr uint32_t kCarryRecs = 128;  // escapes a wavefront remembers in LDS (offsets in the group); a group with more walks its elements again
 // copies of a histogram row in LDS (copy = lane mod kCarryCopies).  Few, and loads only four turns ahead: the
 // kernel is sized (LDS 40 KiB, 128 registers) so that four work-groups share a CU, which counts for more here than
 // cheaper atomics or deeper prefetch (measured: 16 copies and eight turns ahead at three work-groups, 160 us; this, 153 us)
@@ -97,7 +97,7 @@ struct CarryEnv {
     const uint16_t* enc_t;
     uint32_t* hist_t;
     uint32_t gstart;       // index of the group's first element in the table
-    uint32_t* recs;        // LDS: the wavefront's escape records found on the way, kCarryRecs at most
+    uint16_t* recs;        // LDS: where in the group the wavefront has met escapes, kCarryRecs at most
 };
 
 // One block of kCarryBlk units already loaded: quantise, count, look up, append.
@@ -170,20 +170,14 @@ __device__ __forceinline__ void carry_block(const CarryEnv& E, const float (&x)[
             }
             if constexpr (FIRST) {
                 // the records of these escapes, in element order (the walk meets the elements of a group in
-                // increasing index: turn, lane, position); kept while they fit.  The raw bits are read from the
-                // payload again (half precision: the float in hand need not convert back to the same bits).
+                // increasing index: turn, lane, position); their offsets are kept while they fit.
                 const uint32_t cnt = __popc(em);
                 const uint32_t incl = wave_incl_scan(cnt, E.lane);
                 uint32_t r = nrec + incl - cnt;
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
                     if ((em >> v) & 1u) {
-                        if (r < kCarryRecs) {
-                            const uint32_t off = E.lane * kV + (jb + u) * (kW * kV) + (uint32_t)v;
-                            E.recs[2u * r] = E.gstart + off;
-                            if constexpr (F16) E.recs[2u * r + 1] = reinterpret_cast<const uint16_t*>(E.gbase)[off];
-                            else E.recs[2u * r + 1] = reinterpret_cast<const uint32_t*>(E.gbase)[off];
-                        }
+                        if (r < kCarryRecs) E.recs[r] = (uint16_t)(E.lane * kV + (jb + u) * (kW * kV) + (uint32_t)v);
                         ++r;
                     }
                 nrec += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
@@ -284,7 +278,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
     __shared__ __align__(16) uint32_t s_hist[(kCarryRows + 3u) * kCarryCopies];
     __shared__ __align__(16) uint32_t s_tab[kCarryRows + 3u];  // by table index: len << 16 | codeword; 0 = no code
     __shared__ __align__(16) uint32_t s_stage[4 * kStageWords];
-    __shared__ uint32_t s_recs[4 * 2 * kCarryRecs];
+    __shared__ uint16_t s_recs[4 * kCarryRecs];
     __shared__ uint32_t s_wg, s_tot[4], s_excl, s_dead;
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     if (tid == 0) s_wg = atomicAdd(&ctrl->ticket, 1u);
@@ -330,7 +324,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
     E.enc_t = enc_t;
     E.hist_t = hist_t;
     E.gstart = gstart;
-    E.recs = s_recs + wave * (2 * kCarryRecs);
+    E.recs = s_recs + wave * kCarryRecs;
     const uint8_t* const gbase = E.gbase;
     const uint32_t rem = E.rem;
     const QParam q = E.q;
@@ -453,7 +447,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
     if (n_esc != 0u) {  // uniform over the wavefront
         uint32_t* rec = gw + chunk_total;
         if (n_esc <= kCarryRecs) {  // the records were kept on the way
-            for (uint32_t k = lane; k < 2u * n_esc; k += 64) rec[k] = E.recs[k];
+            for (uint32_t k = lane; k < n_esc; k += 64) {  // (the raw bits come from the payload: the float in hand
+                const uint32_t off = E.recs[k];             //  need not convert back to the same half-precision bits)
+                rec[2u * k] = gstart + off;
+                if constexpr (F16) rec[2u * k + 1] = reinterpret_cast<const uint16_t*>(gbase)[off];
+                else rec[2u * k + 1] = reinterpret_cast<const uint32_t*>(gbase)[off];
+            }
         } else {
             carry_emit_escapes<S, F16, VEC>(rec, lane, gbase, gstart, rem, q, Rf, (int)g.R, enc_t);
         }

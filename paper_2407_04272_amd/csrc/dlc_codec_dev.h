@@ -20,7 +20,11 @@ namespace dlc {
 //   - the encode kernel looks window indices up in a 256-entry LDS table and goes back to the element itself
 //     only for index 255
 // ------------------------------------------------------------------------------------------------
-constexpr uint32_t kWinBins = 255;
+constexpr uint32_t kWinBins = 255;   // index of "see the element itself" (a symbol outside the window, a position past the end)
+constexpr uint32_t kWinEsc = 254;    // index of an escape: its code comes from the table like any other, its record from the payload
+constexpr uint32_t kWinSkip = 253;   // with row matching: an element of a row that is stored as a reference (no bits)
+// window indices that stand for a symbol: [0, win_bins)
+__host__ __device__ inline uint32_t win_bins(uint32_t lz) { return lz ? kWinSkip : kWinEsc; }
 constexpr uint32_t kWinCopies = 16;
 __host__ __device__ inline uint32_t win_lo_of(uint32_t R) { return R > kWinBins / 2u ? R - kWinBins / 2u : 0u; }
 // The symbol plane: the window index of every element, one byte each, in element order; a table's part is padded to

@@ -78,13 +78,13 @@ constexpr uint32_t kHistBlk = 4;  // units whose loads are issued back to back
 // One block of kHistBlk units of one table; a unit is 256 consecutive elements (one 16-byte load per lane).
 // `rem` = elements of the table from the block's first element on, `n_units` = units of the block that are this
 // wavefront's.  FULL: all kHistBlk units are, and all their elements are inside the table (no masking at all).
-// LZ (row matching): the window is one symbol narrower, because index 254 in the plane stands for an element of a
-// row that is stored as a reference (the row-matching kernels put it there afterwards); the symbol that would have
-// had index 254 goes the way of everything outside the window.
+// Index 254 in the plane stands for an escape.  LZ (row matching): the window is one symbol narrower, because index
+// 253 stands for an element of a row that is stored as a reference (the row-matching kernels put it there
+// afterwards); the symbol that would have had that index goes the way of everything outside the window.
 template <bool F16, bool VEC, bool FULL, bool LZ>
 __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, uint32_t n_units, uint32_t lane, const QParam& q,
                                            float Rf, const HistC& H, uint32_t* plane) {
-    constexpr uint32_t kBins = LZ ? kWinBins - 1u : kWinBins;  // window indices that stand for a symbol
+    constexpr uint32_t kBins = LZ ? kWinSkip : kWinEsc;  // window indices that stand for a symbol
     float x[kHistBlk][4];
     uint32_t raw[kHistBlk][4];
     uint32_t valid[kHistBlk];
@@ -106,7 +106,7 @@ __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, ui
             const float d = xv - xh;
             const bool ok = (__builtin_fabsf(r) < Rf) & (__builtin_fabsf(d) <= q.eb);  // no short circuit: no branches
             w[v] = ok ? (uint32_t)((int)r + H.ubias) : kEscW;
-            sl[v] = w[v] < kBins ? w[v] : kWinBins;
+            sl[v] = w[v] < kBins ? w[v] : (w[v] == kEscW ? kWinEsc : kWinBins);
             if constexpr (FULL) {
                 DLC_HIST_COUNT(sl[v] * (kWinCopies * 4u) + H.lanebase);
             } else {
@@ -114,11 +114,11 @@ __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, ui
                 else { sl[v] = kWinBins; w[v] = kPastEnd; }
             }
         }
-        // index 255 is rare: count those elements exactly, by symbol (0 = escape)
-        if (__ballot(max(max(sl[0], sl[1]), max(sl[2], sl[3])) == kWinBins) != 0ull) {
+        // indices 254 and 255 are rare: count those elements exactly, by symbol (0 = escape)
+        if (__ballot(max(max(sl[0], sl[1]), max(sl[2], sl[3])) >= kWinEsc) != 0ull) {
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-                if (sl[v] == kWinBins && w[v] != kPastEnd) lds_count(H.exact + (w[v] == kEscW ? 0u : w[v] + H.win_lo) * 4u);
+                if (sl[v] >= kWinEsc && w[v] != kPastEnd) lds_count(H.exact + (w[v] == kEscW ? 0u : w[v] + H.win_lo) * 4u);
         }
         // the window indices of these four elements, for the encode kernel (a unit of this wavefront only)
         if (FULL || u < n_units) plane[u * kW + lane] = sl[0] | (sl[1] << 8) | (sl[2] << 16) | (sl[3] << 24);
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const
         for (uint32_t k = tid; k < g.K; k += 256) {
             uint32_t s = exact[k];
             const uint32_t w = k - H.win_lo;
-            if (w < kWinBins) {
+            if (w < (LZ ? kWinSkip : kWinEsc)) {
                 const uint32_t* row = lh + w * kWinCopies;
                 for (uint32_t c = 0; c < kWinCopies; ++c) s += row[(c + tid) & (kWinCopies - 1u)];
             }

@@ -71,8 +71,10 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
     __shared__ uint32_t s_wg, s_tot[4], s_ct[4], s_excl, s_dead;
     constexpr uint32_t kStageWords = 8u * (uint32_t)S;  // LDS staging per wavefront: room for a group of up to 4 bits per symbol
     __shared__ __align__(16) uint32_t s_stage[4 * kStageWords];
-    constexpr uint32_t kEncRecs = 32;  // escape records a wavefront keeps in LDS; a group with more walks its elements again
-    __shared__ uint32_t s_recs[4 * 2 * kEncRecs];
+    // escapes a wavefront remembers in LDS (their offsets in the group; the raw bits are read again when the records
+    // are written); a group with more walks its elements again
+    constexpr uint32_t kEncRecs = 128;
+    __shared__ uint16_t s_recs[4 * kEncRecs];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     if (tid == 0) s_wg = atomicAdd(&ctrl->ticket, 1u);
     __syncthreads();
@@ -87,9 +89,10 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
     const uint32_t win_lo = win_lo_of(g.R);
     const uint16_t* enc_t = enc + (size_t)t * g.K;
     {
-        // (with row matching index 254 marks an element of a row that is stored as a reference: no bits)
+        // (index 254 is the escape, symbol 0; with row matching index 253 marks an element of a row that is stored as
+        // a reference: no bits)
         const uint32_t c = win_lo + tid;
-        const uint32_t e = (tid < (g.lz ? kWinBins - 1u : kWinBins) && c < g.K) ? enc_t[c] : 0u;
+        const uint32_t e = tid == kWinEsc ? enc_t[0] : ((tid < win_bins(g.lz) && c < g.K) ? enc_t[c] : 0u);
         s_len[tid] = (uint16_t)(e >> 12);
         s_code[tid] = (uint16_t)(e & 0xFFFu);
     }
@@ -105,13 +108,13 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
     const uint32_t rem = active ? g.n - gstart : 0u;
     // can index 255 occur in this group at all?  (an escape, a symbol outside the window, a ragged last group)
     const TMeta tm = tmeta[t];
-    const bool plain = tm.n_outliers == 0u && tm.sym_lo >= win_lo && tm.sym_hi < win_lo + (g.lz ? kWinBins - 1u : kWinBins) && rem >= kW * (uint32_t)S;
+    const bool plain = tm.n_outliers == 0u && tm.sym_lo >= win_lo && tm.sym_hi < win_lo + win_bins(g.lz) && rem >= kW * (uint32_t)S;
     const uint32_t a_len = (uint32_t)(uintptr_t)s_len, d_code = (uint32_t)(uintptr_t)s_code - a_len;
 
     DLC_ESTAMP(1);
     uint32_t ix[S / 4];  // window indices, four to a word, in element order
     uint32_t bits = 0, my_esc = 0, nrec = 0;
-    uint32_t* const recs = s_recs + wave * (2u * kEncRecs);
+    uint16_t* const recs = s_recs + wave * kEncRecs;
     if (active) {
         const uint32_t* plane = reinterpret_cast<const uint32_t*>(sym_plane + (size_t)t * plane_stride(g) + gstart);
         const bool ragged = rem < kW * (uint32_t)S;  // uniform: the table ends inside this group
@@ -141,16 +144,19 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
 #pragma clang loop unroll(full)
                 for (int u = 0; u < kB1; ++u) {
                     const uint32_t m = ix[jb + u];
-                    if (__ballot(has_ff_byte(m)) == 0ull) continue;
-                    uint32_t em = 0;  // which of the four are escapes
+                    if (__ballot(has_ff_byte(m | 0x01010101u)) == 0ull) continue;  // nothing but window indices
+                    uint32_t em = 0;  // which of the four are escapes (their bits are counted above: the table has their code)
 #pragma clang loop unroll(full)
-                    for (int v = 0; v < 4; ++v) {
-                        const uint32_t off = lane * kV + (uint32_t)(jb + u) * (kW * kV) + (uint32_t)v;
-                        if (((m >> (8 * v)) & 0xFFu) == 0xFFu && off < rem) {
-                            uint32_t esc;
-                            bits += entry_of_element<F16>(gbase, off, q, Rf, (int)g.R, enc_t, &esc) >> 12;
-                            my_esc += esc;
-                            em |= esc << v;
+                    for (int v = 0; v < 4; ++v) em |= (((m >> (8 * v)) & 0xFFu) == kWinEsc ? 1u : 0u) << v;
+                    my_esc += __popc(em);
+                    if (__ballot(has_ff_byte(m)) != 0ull) {  // symbols outside the window
+#pragma clang loop unroll(full)
+                        for (int v = 0; v < 4; ++v) {
+                            const uint32_t off = lane * kV + (uint32_t)(jb + u) * (kW * kV) + (uint32_t)v;
+                            if (((m >> (8 * v)) & 0xFFu) == 0xFFu && off < rem) {
+                                uint32_t esc;
+                                bits += entry_of_element<F16>(gbase, off, q, Rf, (int)g.R, enc_t, &esc) >> 12;
+                            }
                         }
                     }
                     // the records of these escapes, in element order (the walk meets the elements of a group in
@@ -162,12 +168,7 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
 #pragma clang loop unroll(full)
                         for (int v = 0; v < 4; ++v)
                             if ((em >> v) & 1u) {
-                                if (r < kEncRecs) {
-                                    const uint32_t off = lane * kV + (uint32_t)(jb + u) * (kW * kV) + (uint32_t)v;
-                                    recs[2u * r] = gstart + off;
-                                    if constexpr (F16) recs[2u * r + 1] = reinterpret_cast<const uint16_t*>(gbase)[off];
-                                    else recs[2u * r + 1] = reinterpret_cast<const uint32_t*>(gbase)[off];
-                                }
+                                if (r < kEncRecs) recs[r] = (uint16_t)(lane * kV + (uint32_t)(jb + u) * (kW * kV) + (uint32_t)v);
                                 ++r;
                             }
                         nrec += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
@@ -297,7 +298,12 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
     if (n_esc != 0u) {  // uniform over the wavefront
         uint32_t* rec = gw + chunk_total;
         if (n_esc <= kEncRecs) {  // the records were kept on the way
-            for (uint32_t k = lane; k < 2u * n_esc; k += 64) rec[k] = recs[k];
+            for (uint32_t k = lane; k < n_esc; k += 64) {
+                const uint32_t off = recs[k];
+                rec[2u * k] = gstart + off;
+                if constexpr (F16) rec[2u * k + 1] = reinterpret_cast<const uint16_t*>(gbase)[off];
+                else rec[2u * k + 1] = reinterpret_cast<const uint32_t*>(gbase)[off];
+            }
         } else {
             emit_escapes<S, F16, VEC>(rec, lane, gbase, gstart, rem, q, Rf, (int)g.R);
         }

@@ -48,9 +48,10 @@ __device__ __forceinline__ uint64_t rm_identity(const uint8_t* tab, uint32_t i, 
     return c ? (uint64_t)c : ((1ull << 32) | raw);
 }
 
-// does one of the four bytes equal 255 (the plane's "outside the window")?
+// is one of the four bytes 254 or 255 (the plane's "escape" and "outside the window": what the element is, its raw
+// bits or its symbol, is in the payload)?
 __device__ __forceinline__ bool rm_has255(uint32_t w) {
-    const uint32_t x = ~w;
+    const uint32_t x = ~(w | 0x01010101u);
     return ((x - 0x01010101u) & ~x & 0x80808080u) != 0u;
 }
 
@@ -78,8 +79,8 @@ constexpr uint32_t kRmPitch = kRmSlab + 1u;
 }  // namespace
 
 // Both passes read the symbol plane the histogram kernel has written (one byte per element: the symbol's window
-// index, 255 for everything else), four bytes (a piece) at a time.  An element with index 255 is looked up in the
-// payload: its symbol, or the raw bits of an escape.
+// index, 255 for everything else), four bytes (a piece) at a time.  An element with index 254 (escape) or 255 is looked
+// up in the payload: its symbol, or the raw bits of an escape.
 
 // pass 1: hash of every row, a lane per row.  A wavefront takes 64 consecutive rows: it loads their pieces as
 // they lie in memory (16 bytes per lane where the row length allows), kRmSlab pieces of each row at a time, into LDS
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(256) void k_rm_hash(const void* payload, Geom g, co
                     if (other) {  // rare
                         for (uint32_t k = 0; k < 4; ++k) {
                             for (uint32_t v = 0; v < 4; ++v) {
-                                if (((w[k] >> (8u * v)) & 255u) != 255u) continue;
+                                if (((w[k] >> (8u * v)) & 255u) < kWinEsc) continue;
                                 const uint32_t e = (p0 + c0 + k) * 4u + v;
                                 rm_add_other(rm_identity<F16>(tab, (row0 + lane) * g.D + e, q, Rf, (int)g.R), e, a);
                             }
@@ -256,7 +257,7 @@ __global__ __launch_bounds__(1024) void k_rm_sets(Geom g, const uint8_t* on, con
 
 // pass 2: ref[row] = the owner of the row's hash if the two rows are equal element by element, else the row itself.
 // The elements of a row that refers to another leave the table's counts again (the histogram kernel has counted
-// every row) and get index 254 in the plane, which the encode kernel's table maps to no bits at all.  Only rows
+// every row) and get index 253 in the plane, which the encode kernel's table maps to no bits at all.  Only rows
 // that nobody compares with are changed: an owner is never such a row.
 // A lane holds a piece of PW words of the plane (16 bytes where the row length allows, else 4); a row is the work
 // of a team of 2^logL lanes, the smallest power of two that covers the row's pieces (64 at most: longer rows take
@@ -350,7 +351,7 @@ __global__ __launch_bounds__(256) void k_rm_owner(const void* payload, Geom g, c
                         const uint32_t row = row0 + (s0 + s) * rps + team;
                         for (uint32_t k = 0; k < PW; ++k) {
                             for (uint32_t v = 0; v < 4; ++v) {
-                                if (((w[s].v[k] >> (8u * v)) & 255u) != 255u) continue;
+                                if (((w[s].v[k] >> (8u * v)) & 255u) < kWinEsc) continue;
                                 const uint32_t e = (p * PW + k) * 4u + v;
                                 if (rm_identity<F16>(tab, row * g.D + e, q, Rf, (int)g.R) != rm_identity<F16>(tab, own[s] * g.D + e, q, Rf, (int)g.R))
                                     differ[s] = true;
@@ -375,7 +376,7 @@ __global__ __launch_bounds__(256) void k_rm_owner(const void* payload, Geom g, c
                         } else {
                             for (uint32_t v = 0; v < 4; ++v) {
                                 const uint32_t idx = (wv.v[k] >> (8u * v)) & 255u;
-                                if (idx < kWinBins) {
+                                if (idx < kWinEsc) {
                                     atomicSub(&win[idx * kWinCopies], 1u);
                                 } else {
                                     const uint64_t id = rm_identity<F16>(tab, row * g.D + (p * PW + k) * 4u + v, q, Rf, (int)g.R);
@@ -384,8 +385,8 @@ __global__ __launch_bounds__(256) void k_rm_owner(const void* payload, Geom g, c
                             }
                         }
                     }
-                    if constexpr (PW == 4) *reinterpret_cast<uint4*>(plane + ((size_t)row * W + p) * 4u) = make_uint4(0xFEFEFEFEu, 0xFEFEFEFEu, 0xFEFEFEFEu, 0xFEFEFEFEu);
-                    else plane[(size_t)row * W + p] = 0xFEFEFEFEu;
+                    if constexpr (PW == 4) *reinterpret_cast<uint4*>(plane + ((size_t)row * W + p) * 4u) = make_uint4(0xFDFDFDFDu, 0xFDFDFDFDu, 0xFDFDFDFDu, 0xFDFDFDFDu);
+                    else plane[(size_t)row * W + p] = 0xFDFDFDFDu;
                 }
             }
         }
@@ -396,7 +397,7 @@ __global__ __launch_bounds__(256) void k_rm_owner(const void* payload, Geom g, c
     for (uint32_t k = tid; k < g.K; k += 256) {
         uint32_t s = exact[k];
         const uint32_t wi = k - win_lo;
-        if (wi < kWinBins) {
+        if (wi < kWinSkip) {
             const uint32_t* row = lh + wi * kWinCopies;
             for (uint32_t c = 0; c < kWinCopies; ++c) s += row[(c + tid) & (kWinCopies - 1u)];
         }
