@@ -71,8 +71,7 @@ struct HistC {
 #define DLC_HIST_COUNT(addr) lds_count(addr)
 #endif
 
-constexpr uint32_t kEscW = 0x80000000u;  // no bin has this window index (bins below the window wrap to just under 2^32)
-constexpr uint32_t kPastEnd = 0x80000001u;  // nor this one: a position past the end of the table
+constexpr uint32_t kPastEnd = 0x80000001u;  // no element within the radius has this window index: a position past the end of the table
 constexpr uint32_t kHistBlk = 4;  // units whose loads are issued back to back
 
 // One block of kHistBlk units of one table; a unit is 256 consecutive elements (one 16-byte load per lane).
@@ -98,15 +97,16 @@ __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, ui
         uint32_t w[4], sl[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            // the quantiser (same arithmetic as quant_symbol), result as a window index; kEscW for an escape
+            // the quantiser (same arithmetic as quant_symbol), result as a window index
             const float xv = x[u][v];
             const float r = __builtin_rintf(xv * q.inv);
             float xh = r * q.ebx2;
             if constexpr (F16) xh = __half2float(half_rne(xh));
             const float d = xv - xh;
             const bool ok = (__builtin_fabsf(r) < Rf) & (__builtin_fabsf(d) <= q.eb);  // no short circuit: no branches
-            w[v] = ok ? (uint32_t)((int)r + H.ubias) : kEscW;
-            sl[v] = w[v] < kBins ? w[v] : (w[v] == kEscW ? kWinEsc : kWinBins);
+            w[v] = (uint32_t)((int)r + H.ubias);  // (bins below the window wrap to just under 2^32)
+            sl[v] = w[v] < kBins ? w[v] : kWinBins;
+            sl[v] = ok ? sl[v] : kWinEsc;
             if constexpr (FULL) {
                 DLC_HIST_COUNT(sl[v] * (kWinCopies * 4u) + H.lanebase);
             } else {
@@ -114,11 +114,12 @@ __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, ui
                 else { sl[v] = kWinBins; w[v] = kPastEnd; }
             }
         }
-        // indices 254 and 255 are rare: count those elements exactly, by symbol (0 = escape)
-        if (__ballot(max(max(sl[0], sl[1]), max(sl[2], sl[3])) >= kWinEsc) != 0ull) {
+        // index 255 is rare: count those elements exactly, by symbol (escapes are counted in window row 254, which
+        // the merge adds to symbol 0)
+        if (__ballot(max(max(sl[0], sl[1]), max(sl[2], sl[3])) == kWinBins) != 0ull) {
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-                if (sl[v] >= kWinEsc && w[v] != kPastEnd) lds_count(H.exact + (w[v] == kEscW ? 0u : w[v] + H.win_lo) * 4u);
+                if (sl[v] == kWinBins && w[v] != kPastEnd) lds_count(H.exact + (w[v] + H.win_lo) * 4u);
         }
         // the window indices of these four elements, for the encode kernel (a unit of this wavefront only)
         if (FULL || u < n_units) plane[u * kW + lane] = sl[0] | (sl[1] << 8) | (sl[2] << 16) | (sl[3] << 24);
@@ -182,6 +183,10 @@ __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const
             if (w < (LZ ? kWinSkip : kWinEsc)) {
                 const uint32_t* row = lh + w * kWinCopies;
                 for (uint32_t c = 0; c < kWinCopies; ++c) s += row[(c + tid) & (kWinCopies - 1u)];
+            }
+            if (k == 0u) {  // the escapes
+                const uint32_t* row = lh + kWinEsc * kWinCopies;
+                for (uint32_t c = 0; c < kWinCopies; ++c) s += row[c];
             }
             if (s) atomicAdd(&hist[(size_t)t * g.K + k], s);
         }
