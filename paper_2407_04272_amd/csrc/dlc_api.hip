@@ -413,22 +413,21 @@ extern "C" int dlc_stats(dlc_ctx* c, const void* d_payload, const float* probe_e
     std::vector<QParam> pq(g.T);
     for (uint32_t t = 0; t < g.T; ++t) pq[t] = make_qparam(probe_eb[t]);
     std::vector<uint32_t> mm(2 * g.T), un(2 * g.T);
+    if (hipMemcpyAsync(w.probe, pq.data(), sizeof(QParam) * g.T, hipMemcpyHostToDevice, s) != hipSuccess) return DLC_EHIP;
     for (uint32_t attempt = 0; attempt < 4; ++attempt) {
-        std::vector<uint32_t> mm0(2 * g.T);
-        for (uint32_t t = 0; t < g.T; ++t) { mm0[2 * t] = 0xFFFFFFFFu; mm0[2 * t + 1] = 0u; }
-        if (hipMemcpyAsync(w.probe, pq.data(), sizeof(QParam) * g.T, hipMemcpyHostToDevice, s) != hipSuccess) return DLC_EHIP;
-        if (hipMemcpyAsync(w.st_minmax, mm0.data(), 8ull * g.T, hipMemcpyHostToDevice, s) != hipSuccess) return DLC_EHIP;
-        if (hipMemsetAsync(w.st_unique, 0, 8ull * g.T, s) != hipSuccess) return DLC_EHIP;
-        if (hipMemsetAsync(&w.ctrl->collide, 0, 4, s) != hipSuccess) return DLC_EHIP;
-        if (hipStreamSynchronize(s) != hipSuccess) return DLC_EHIP;  // staging vectors above are reused per attempt
+        // (the first kernel of the reduction clears the range words, the counts and the collision counter)
         if (launch_stats(g, d_payload, w.probe, w, 0x51ED270Bu * (attempt + 1), s) != hipSuccess) return DLC_EHIP;
         uint32_t collide = 0;
+        int32_t st = 0;
         if (hipMemcpyAsync(mm.data(), w.st_minmax, 8ull * g.T, hipMemcpyDeviceToHost, s) != hipSuccess) return DLC_EHIP;
         if (hipMemcpyAsync(un.data(), w.st_unique, 8ull * g.T, hipMemcpyDeviceToHost, s) != hipSuccess) return DLC_EHIP;
         if (hipMemcpyAsync(&collide, &w.ctrl->collide, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return DLC_EHIP;
+        if (hipMemcpyAsync(&st, &w.ctrl->status, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return DLC_EHIP;
         if (hipStreamSynchronize(s) != hipSuccess) return DLC_EHIP;
-        const int st = dlc_sync_status(c, stream);
-        if (st != DLC_OK) return st;
+        if (st != DLC_OK) {
+            if (hipMemset(&w.ctrl->status, 0, 4) != hipSuccess) return DLC_EHIP;
+            return st;
+        }
         if (collide == 0) {
             for (uint32_t t = 0; t < g.T; ++t) {
                 out[t].min = mm[2 * t] == 0xFFFFFFFFu ? std::numeric_limits<float>::infinity() : ord_dec(mm[2 * t]);

@@ -12,11 +12,12 @@ namespace dlc {
 
 // ------------------------------------------------------------------------------------------------
 // The symbol window.  Almost every element of a bell-shaped table falls into a few bins around zero, so the
-// streaming kernels work on window indices: index v in [0, 255) stands for symbol win_lo + v, index 255 for
-// everything else (an escape, a symbol outside the window, a position past the end of the table).
+// streaming kernels work on window indices: index v in [0, 254) stands for symbol win_lo + v, index 254 for an
+// escape, index 255 for everything else (a symbol outside the window, a position past the end of the table).
 //   - the histogram kernel counts window indices in LDS with kWinCopies copies per row (copy = lane mod
 //     kWinCopies, so a wavefront's 64 updates spread over the banks whatever the symbols are) and hands the
-//     indices on as one byte per element (the symbol plane); the rare index 255 is counted exactly by symbol
+//     indices on as one byte per element (the symbol plane); the rare index 255 is counted exactly by symbol, the
+//     escapes in row 254
 //   - the encode kernel looks window indices up in a 256-entry LDS table and goes back to the element itself
 //     only for index 255
 // ------------------------------------------------------------------------------------------------

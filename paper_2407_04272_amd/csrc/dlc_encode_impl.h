@@ -23,10 +23,10 @@ namespace dlc {
 // ------------------------------------------------------------------------------------------------
 // bit-packed encode.
 //   walk 1: read the group's window indices from the symbol plane the histogram kernel has written (one byte per
-//           element: 0..254 = symbol win_lo + index, 255 = everything else), keep them in registers four to a
-//           word, look up the code length of each in LDS and sum the chunk's bits.  Index 255 is rare (an escape,
-//           a symbol outside the window, a position past the end of the table): its element is quantised again,
-//           with the code from the full table; escapes are counted.
+//           element: 0..253 = symbol win_lo + index, 254 = escape, 255 = everything else), keep them in registers
+//           four to a word, look up the code length of each in LDS and sum the chunk's bits.  Index 255 is rare (a
+//           symbol outside the window, a position past the end of the table): its element is quantised again,
+//           with the code from the full table.  Escapes are counted and where they are is remembered.
 //   scan  : chunk word counts inside the wavefront; the wavefronts' totals (chunk words + two words per
 //           escape) are joined per work-group, and the work-groups' totals across the grid by a single-pass
 //           look-back (ordered work-group ids: a work-group only ever waits for work-groups that started
@@ -34,8 +34,8 @@ namespace dlc {
 //   walk 2: look up length and codeword of the kept indices (index 255: the element itself once more), join the
 //           two codes of a pair, shift into a 64-bit accumulator, store whole words at the chunk's offset
 //   escapes: their records (element index, raw bits; in increasing element index, behind the group's chunk words)
-//           are collected in LDS during walk 1, up to 32 per group; a group with more walks its elements once
-//           more in a rolled loop
+//           are written from the offsets kept in LDS during walk 1, up to 128 per group; a group with more walks
+//           its elements once more in a rolled loop
 // Keeping bytes instead of (length, codeword) entries halves the registers a wavefront holds between the walks,
 // which doubles the wavefronts per SIMD: the kernel is bound by latency (global scan, table look-ups, stores),
 // not by arithmetic.

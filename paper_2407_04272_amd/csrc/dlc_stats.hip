@@ -1,7 +1,7 @@
 // Statistics reduction for gfx950: per-table value range and exact distinct-row counts of the raw rows
 // and of the rows quantised at a probe bound (the two counts of the Homogenization Index, Eq. 1).
 //
-// Three kernels.  k_stats_hash: two 64-bit hashes per row (raw bits; symbols at the probe bound) and the range.
+// k_stats_init sets an attempt up.  k_stats_hash: two 64-bit hashes per row (raw bits; symbols at the probe bound) and the range.
 // The row sets (dlc_rowmatch.hip: the rows of a table divided among work-groups by hash, open-addressing sets in
 // LDS, the smallest row index of a hash owns it) give every row the owner of its hash and count the owners.
 // k_stats_verify: every row that is not an owner is compared with its owner element by element, so a hash
@@ -93,12 +93,20 @@ __device__ __forceinline__ void st_word(uint32_t w, uint32_t p, const uint4* __r
 
 }  // namespace
 
-// the multipliers of every position of a row for this attempt's salt
-__global__ __launch_bounds__(256) void k_stats_mult(uint32_t* mult, uint32_t D, uint32_t salt) {
+// start of an attempt: the multipliers of every position of a row for this attempt's salt; the tables' range words
+// ("none yet"), the counts of distinct rows and the collision counter cleared
+__global__ __launch_bounds__(256) void k_stats_init(uint32_t* mult, uint32_t D, uint32_t salt, uint32_t* minmax, uint32_t* unique,
+                                                    uint32_t T, Ctrl* ctrl) {
     const uint32_t i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= D * kStMult) return;
-    const uint32_t e = i / kStMult, k = i % kStMult;
-    mult[i] = mix32((e * kStMult + k + 1u) * 0x9E3779B1u + salt) & 0xFFFFFFu;
+    if (i < D * kStMult) {
+        const uint32_t e = i / kStMult, k = i % kStMult;
+        mult[i] = mix32((e * kStMult + k + 1u) * 0x9E3779B1u + salt) & 0xFFFFFFu;
+    }
+    if (i < 2u * T) {
+        minmax[i] = (i & 1u) ? 0u : 0xFFFFFFFFu;
+        unique[i] = 0u;
+    }
+    if (i == 0) ctrl->collide = 0u;
 }
 
 // pass 1, a lane per row.  A wavefront takes 64 consecutive rows, loads kStSlab words of each at a time (PL words
@@ -302,7 +310,8 @@ hipError_t launch_stats(const Geom& g, const void* payload, const QParam* probe,
     const uint32_t blocks_x = std::min<uint32_t>((g.B + 255u) / 256u, DLC_STATS_BLOCKS);  // a wavefront takes 64 rows at a time
     const uint32_t waves_grid = blocks_x * 4;
     dim3 grid(blocks_x, g.T), block(256);
-    hipLaunchKernelGGL(k_stats_mult, dim3((g.D * kStMult + 255u) / 256u), block, 0, s, w.st_mult, g.D, salt);
+    hipLaunchKernelGGL(k_stats_init, dim3((std::max(g.D * kStMult, 2u * g.T) + 255u) / 256u), block, 0, s, w.st_mult, g.D, salt,
+                       w.st_minmax, w.st_unique, g.T, w.ctrl);
 #define DLC_ST_HASH(FF, PK, PL) hipLaunchKernelGGL((k_stats_hash<FF, PK, PL>), grid, block, 0, s, payload, g, probe, reinterpret_cast<const uint4*>(w.st_mult), w.rowhash, w.st_minmax, waves_grid)
     if (g.dtype == DLC_F16) {
         if (g.D % 8u == 0u) DLC_ST_HASH(true, 2, 4);
