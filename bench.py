@@ -160,7 +160,7 @@ def main():
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     # HBM bytes per launch of the dominant kernel, from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
     # profiles/cfg3_hbm_traffic_pmc.txt (they cannot be collected from inside this process); known for this workload only
-    measured_traffic = {"k_encode": 241.1e6, "k_hist": 671.8e6, "k_decode": 597.4e6, "k_encode_carry": CARRY_TRAFFIC}
+    measured_traffic = {"k_encode": 253.9e6, "k_hist": 671.8e6, "k_decode": 597.4e6, "k_encode_carry": CARRY_TRAFFIC}
     traffic = measured_traffic.get(dom) if (args.workload == "cfg3" and args.chunk_symbols == 256) else None
     result = {
         "metric": "compress+decompress round-trip GB/s of uncompressed fp32 payload, 1 MI355X",
