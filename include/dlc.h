@@ -124,7 +124,7 @@ enum { DLC_FLAG_FUSED = 1, DLC_FLAG_CARRY_CODEBOOK = 2, DLC_FLAG_ROW_MATCH = 4 }
  * in parallel.  Per table: dlc_set_row_match switches it on and off (all on after dlc_create), which is what the
  * compressor selection of Section III-D (Eq. 2, dlc_speedup_estimate) decides offline.  Needs dim % 4 == 0; not
  * together with the other flags or num_dest > 1.  The search hashes rows; two different rows with one 64-bit hash
- * (about 2^-33 per table and call for 8192 rows) cost a match, never correctness. */
+ * (at worst 2^-48 for a pair of rows, far less for most contents) cost a match, never correctness. */
 
 /* Per-table statistics of a sampled batch: what Eq. 1 needs, plus the value range. */
 typedef struct {

@@ -121,3 +121,39 @@ def test_damaged_references_are_rejected_on_the_gpu():
     rec = torch.full_like(d, 7.0)
     assert plain.decompress(out, data.size, rec) == 0
     assert plain.sync_status() == b.ECORRUPT
+
+
+def test_random_shapes_rows_and_statistics():
+    """A seeded sweep over row lengths (every team size and load width of the row kernels), batch sizes and both
+    element types: references, containers, reconstructions and the statistics' distinct-row counts against the
+    oracle."""
+    import torch
+    from paper_2407_04272_amd import binding as b
+    rng = np.random.default_rng(2024)
+    dims = [4, 8, 12, 16, 20, 36, 64, 68, 96, 132, 200, 256, 272, 320, 516]
+    for case, D in enumerate(dims):
+        T = int(rng.integers(1, 4))
+        B = int(rng.integers(1, 700))
+        dtype = np.float16 if case % 3 == 2 else np.float32
+        S = int(rng.choice([64, 128, 256]))
+        print("sweep", T, B, D, S, np.dtype(dtype).name, flush=True)
+        x = _lookups(T, B, D, 100 + case, rows=max(2, B // 3), dtype=dtype)
+        if B > 5:
+            x[0, 4, D - 1] = 3e4          # an escape in the last element of a row ...
+            x[0, 5] = x[0, 4]             # ... of a row that is repeated
+        ebs = (np.float32(3e-3) * (1 + np.arange(T, dtype=np.float32))).astype(np.float32)
+        ctx, d, out, data, sizes = _compress(x, ebs, S)
+        o = oracle.compress(x, ebs, R, S, 12, row_match=True)
+        assert o.rc == 0 and data.size == o.data.size and np.array_equal(data, o.data), (T, B, D, S)
+        assert np.array_equal(sizes, o.sizes)
+        rec = torch.full_like(d, 7.0)
+        assert ctx.decompress(out, data.size, rec) == 0 and ctx.sync_status() == 0
+        rc, orec = oracle.decompress(o.data, x.shape, dtype)
+        u = np.uint32 if dtype == np.float32 else np.uint16
+        assert rc == 0 and np.array_equal(rec.cpu().numpy().view(u), orec.view(u)), (T, B, D, S)
+        plain = b.Context(b.make_config(b.F16 if dtype == np.float16 else b.F32, T, B, D, R, S, 12))
+        st = plain.stats(d, ebs)
+        ost = oracle.stats(x, ebs)
+        for t in range(T):
+            assert (st[t].n_unique_raw, st[t].n_unique_quant) == (ost[t].n_unique_raw, ost[t].n_unique_quant), (T, B, D, t)
+            assert st[t].min == ost[t].min and st[t].max == ost[t].max
