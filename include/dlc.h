@@ -123,7 +123,8 @@ enum { DLC_FLAG_FUSED = 1, DLC_FLAG_CARRY_CODEBOOK = 2, DLC_FLAG_ROW_MATCH = 4 }
  * byte offset, 0 for a table without).  A referenced row is therefore always a coded one and the decoder copies rows
  * in parallel.  Per table: dlc_set_row_match switches it on and off (all on after dlc_create), which is what the
  * compressor selection of Section III-D (Eq. 2, dlc_speedup_estimate) decides offline.  Needs dim % 4 == 0; not
- * together with the other flags or num_dest > 1.  The search hashes rows; two different rows with one 64-bit hash
+ * together with the other flags.  With num_dest > 1 rows are matched inside a destination's piece (a container
+ * never refers to another).  The search hashes rows; two different rows with one 64-bit hash
  * (at worst 2^-48 for a pair of rows, far less for most contents) cost a match, never correctness. */
 
 /* Per-table statistics of a sampled batch: what Eq. 1 needs, plus the value range. */
@@ -222,8 +223,8 @@ int dlc_compress(dlc_ctx* ctx, const void* d_payload, void* d_out, size_t out_ca
 int dlc_decompress(dlc_ctx* ctx, const void* d_comp, size_t comp_bytes, void* d_payload_out, size_t out_capacity,
                    void* stream);
 
-/* Row matching per table (contexts with DLC_FLAG_ROW_MATCH): h_flags HOST uint8[T], non-zero = store the table's
- * repeated rows as references; NULL = all tables.  Synchronises `stream`. */
+/* Row matching per table (contexts with DLC_FLAG_ROW_MATCH): h_flags HOST uint8[num_tables] (the same for every
+ * destination), non-zero = store the table's repeated rows as references; NULL = all tables.  Synchronises `stream`. */
 int dlc_set_row_match(dlc_ctx* ctx, const uint8_t* h_flags, void* stream);
 
 /* Eq. 2: the speed-up of a transfer that compresses, sends and decompresses over sending raw, for compression ratio
@@ -239,7 +240,8 @@ int dlc_sync_status(dlc_ctx* ctx, void* stream);
  *   dlc_quantize       symbols (uint16, DEVICE, T*B*D) of d_payload at the current bounds -- the quantiser alone
  *   dlc_read_histogram the code histogram (uint32[T][2R], HOST) left by the last dlc_compress
  *   dlc_read_codebook  code lengths (uint8[T][2R]) and codewords (uint16[T][2R]) left by the last dlc_compress
- *   dlc_read_row_refs  row references (uint32[T][B], HOST) left by the last dlc_compress (DLC_FLAG_ROW_MATCH only)
+ *   dlc_read_row_refs  row references (uint32[num_dest * T][B], HOST) left by the last dlc_compress
+ *                      (DLC_FLAG_ROW_MATCH only)
  * With DLC_FLAG_CARRY_CODEBOOK the histogram is still that of the last call's payload, and the codebook is the one
  * built from it for the NEXT call (escape count raised by one), not the one the last call's container was coded with.
  */

@@ -213,7 +213,7 @@ class Context:
         _check(lib().dlc_set_row_match(self._h, _np_ptr(f), _stream_ptr(stream)), "dlc_set_row_match")
 
     def read_row_refs(self, stream=None) -> np.ndarray:
-        r = np.zeros((self.T, self.B), np.uint32)
+        r = np.zeros((self.ND * self.T, self.B), np.uint32)
         _check(lib().dlc_read_row_refs(self._h, _np_ptr(r), _stream_ptr(stream)), "dlc_read_row_refs")
         return r
 

@@ -84,8 +84,8 @@ static bool make_geom(const dlc_config* c, Geom* g) {
     const int S = c->chunk_symbols;
     if (S != 64 && S != 128 && S != 256) return false;
     if (c->flags & ~(int32_t)(DLC_FLAG_FUSED | DLC_FLAG_CARRY_CODEBOOK | DLC_FLAG_ROW_MATCH)) return false;
-    if (c->flags & DLC_FLAG_ROW_MATCH) {  // on its own for now, and a lane's four elements must lie in one row
-        if (c->flags != DLC_FLAG_ROW_MATCH || c->num_dest > 1 || c->dim % 4 != 0) return false;
+    if (c->flags & DLC_FLAG_ROW_MATCH) {  // not with the other flags, and a lane's four elements must lie in one row
+        if (c->flags != DLC_FLAG_ROW_MATCH || c->dim % 4 != 0) return false;
     }
     if ((c->flags & DLC_FLAG_FUSED) && (c->flags & DLC_FLAG_CARRY_CODEBOOK)) return false;
     const int64_t nd = c->num_dest == 0 ? 1 : c->num_dest;  // 0: a zero-initialised field means one destination
@@ -352,7 +352,7 @@ extern "C" int dlc_set_row_match(dlc_ctx* c, const uint8_t* h_flags, void* strea
     if (!c->g.lz) return DLC_ESTATE;
     std::vector<uint8_t> f(c->g.T, 1);
     if (h_flags)
-        for (uint32_t t = 0; t < c->g.T; ++t) f[t] = h_flags[t] ? 1 : 0;
+        for (uint32_t t = 0; t < c->g.T; ++t) f[t] = h_flags[t % c->g.TD] ? 1 : 0;  // the same for every destination
     if (hipMemcpyAsync(c->ws.rm_on, f.data(), c->g.T, hipMemcpyHostToDevice, (hipStream_t)stream) != hipSuccess) return DLC_EHIP;
     return hipStreamSynchronize((hipStream_t)stream) == hipSuccess ? DLC_OK : DLC_EHIP;  // f goes out of scope
 }

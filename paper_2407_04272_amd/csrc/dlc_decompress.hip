@@ -327,11 +327,13 @@ __global__ __launch_bounds__(64 * DLC_DEC_WAVES) void k_decode(Geom g, const uin
 // rows that refer to an earlier row of their table: copies of that row's reconstruction (after the decode kernel).
 // A thread per 16-byte (fp32) / 8-byte (fp16) piece of a row, pieces of a row on neighbouring threads.
 template <typename U>
-__global__ __launch_bounds__(256) void k_row_copy(Geom g, const uint8_t* comp, const DecLayout* dlay, const DecTable* dtab,
-                                                  void* outp) {
+__global__ __launch_bounds__(256) void k_row_copy(Geom g, const uint8_t* comp, uint64_t comp_bytes, const DecLayout* dlay,
+                                                  const DecTable* dtab, void* outp) {
     const uint32_t t = blockIdx.y;
+    const uint32_t dst = t / g.TD;  // the container this table is in
+    comp += (uint64_t)dst * comp_bytes;
     const DecTable D = dtab[t];
-    if (!dlay[0].valid || !D.valid || D.ref_off == 0) return;  // uniform
+    if (!dlay[dst].valid || !D.valid || D.ref_off == 0) return;  // uniform
     const uint32_t* ref = reinterpret_cast<const uint32_t*>(comp + D.ref_off);
     U* tab = reinterpret_cast<U*>(static_cast<uint8_t*>(outp) + (size_t)t * g.n * g.es);
     const uint32_t upr = g.D / 4u;  // pieces per row (four elements each; dim % 4 == 0)
@@ -360,8 +362,8 @@ hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_b
 #undef DLC_DEC
         if (g.lz) {
             const uint32_t bx = std::min<uint32_t>((g.B * (g.D / 4u) + 255u) / 256u, 256u);
-            if (f16) hipLaunchKernelGGL(k_row_copy<uint2>, dim3(bx, g.T), dim3(256), 0, s, g, comp, w.dlay, w.dtab, out);
-            else hipLaunchKernelGGL(k_row_copy<uint4>, dim3(bx, g.T), dim3(256), 0, s, g, comp, w.dlay, w.dtab, out);
+            if (f16) hipLaunchKernelGGL(k_row_copy<uint2>, dim3(bx, g.T), dim3(256), 0, s, g, comp, (uint64_t)comp_bytes, w.dlay, w.dtab, out);
+            else hipLaunchKernelGGL(k_row_copy<uint4>, dim3(bx, g.T), dim3(256), 0, s, g, comp, (uint64_t)comp_bytes, w.dlay, w.dtab, out);
         }
         if (prof_on(pl, P_DECODE)) prof_end(prof, P_DECODE, s);
     }

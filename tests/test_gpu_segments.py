@@ -178,3 +178,48 @@ def test_calls_that_want_one_destination():
         ctx.stats(d, np.full(2, 1e-3, np.float32))
     with pytest.raises(b.DlcError):
         b.Context(b.make_config(b.F32, 2, 64, 16, flags=b.FLAG_FUSED, num_dest=2))
+
+
+@pytest.mark.parametrize("n,T,B,D,S,dtype", [(3, 2, 300, 16, 64, np.float32), (4, 3, 500, 48, 256, np.float16),
+                                             (8, 1, 129, 132, 128, np.float32)])
+def test_row_matching_per_destination(n, T, B, D, S, dtype):
+    """DLC_FLAG_ROW_MATCH with several destinations: rows are matched inside a destination's piece; every container
+    (row references included) is the oracle's for that piece, and one decompress call restores all pieces."""
+    import torch
+    from paper_2407_04272_amd import binding as b
+    print("row matching, destinations", n, T, B, D, S, np.dtype(dtype).name, flush=True)
+    x = _pieces(n, T, B, D, 77 + n).astype(dtype)
+    x[1, 0, 7, 2] = 3e4
+    x[1, 0, 9] = x[1, 0, 7]                                # a repeated row with an escape, in one piece only
+    ebs = (np.float32(2e-3) * (1 + np.arange(T, dtype=np.float32))).astype(np.float32)
+    ctx, status, h, sizes, stride = _run(x, ebs, S, flags=b.FLAG_ROW_MATCH)
+    assert status == 0
+    refs = ctx.read_row_refs()
+    assert refs.shape == (n * T, B)
+    u = np.uint32 if dtype == np.float32 else np.uint16
+    want = np.zeros(x.shape, dtype)
+    for d in range(n):
+        o = oracle.compress(x[d], ebs, R, S, 12, row_match=True)
+        assert o.rc == 0
+        got = int(sizes[1 + n * T + d])
+        assert got == o.data.size, (d, got, o.data.size)
+        piece = h[d * stride:d * stride + got]
+        diff = np.nonzero(piece != o.data)[0]
+        assert diff.size == 0, f"destination {d}: first differing byte {diff[:8]} of {got}"
+        assert np.array_equal(sizes[1 + d * T:1 + (d + 1) * T], o.sizes[1:])
+        rc, want[d] = oracle.decompress(o.data, x[d].shape, dtype)
+        assert rc == 0
+    assert (refs != np.arange(B)[None, :]).any()            # some rows do refer to others
+    comp = to_device(h.copy())                              # the whole output buffer: capacity + 64 guard bytes
+    rec = torch.full(x.shape, 7.0, dtype=torch.float16 if dtype == np.float16 else torch.float32, device="cuda")
+    assert ctx.decompress(comp, h.size - 64, rec) == 0 and ctx.sync_status() == 0
+    assert np.array_equal(rec.cpu().numpy().view(u), want.view(u))
+    # per table: off for the second table of every destination
+    if T >= 2:
+        flags = [1] + [0] + [1] * (T - 2)
+        ctx.set_row_match(flags)
+        ctx2, status, h2, sizes2, _ = _run(x, ebs, S, flags=b.FLAG_ROW_MATCH, ctx=ctx)
+        for d in range(n):
+            o = oracle.compress(x[d], ebs, R, S, 12, row_match=flags)
+            got = int(sizes2[1 + n * T + d])
+            assert got == o.data.size and np.array_equal(h2[d * stride:d * stride + got], o.data), d
