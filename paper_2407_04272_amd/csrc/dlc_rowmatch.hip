@@ -78,9 +78,9 @@ constexpr uint32_t kRmPitch = kRmSlab + 1u;
 
 }  // namespace
 
-// Both passes read the symbol plane the histogram kernel has written (one byte per element: the symbol's window
-// index, 255 for everything else), four bytes (a piece) at a time.  An element with index 254 (escape) or 255 is looked
-// up in the payload: its symbol, or the raw bits of an escape.
+// The hash and the verify kernel read the symbol plane the histogram kernel has written (one byte per element: the
+// symbol's window index, 254 for an escape, 255 for a symbol outside the window), four bytes (a piece) at a time.
+// An element with index 254 or 255 is looked up in the payload: the raw bits of an escape, or the symbol.
 
 // pass 1: hash of every row, a lane per row.  A wavefront takes 64 consecutive rows: it loads their pieces as
 // they lie in memory (16 bytes per lane where the row length allows), kRmSlab pieces of each row at a time, into LDS
