@@ -123,8 +123,8 @@ enum { DLC_FLAG_FUSED = 1, DLC_FLAG_CARRY_CODEBOOK = 2, DLC_FLAG_ROW_MATCH = 4 }
  * byte offset, 0 for a table without).  A referenced row is therefore always a coded one and the decoder copies rows
  * in parallel.  Per table: dlc_set_row_match switches it on and off (all on after dlc_create), which is what the
  * compressor selection of Section III-D (Eq. 2, dlc_speedup_estimate) decides offline.  Needs dim % 4 == 0; not
- * together with the other flags.  With num_dest > 1 rows are matched inside a destination's piece (a container
- * never refers to another).  The search hashes rows; two different rows with one 64-bit hash
+ * together with the other flags; num_dest * num_tables <= 65535.  With num_dest > 1 rows are matched inside a
+ * destination's piece (a container never refers to another).  The search hashes rows; two different rows with one 64-bit hash
  * (at worst 2^-48 for a pair of rows, far less for most contents) cost a match, never correctness. */
 
 /* Per-table statistics of a sampled batch: what Eq. 1 needs, plus the value range. */
@@ -179,7 +179,8 @@ size_t dlc_workspace_bytes(const dlc_config* cfg /*HOST*/);
  *   h_probe_eb HOST    T bounds at which rows are quantised for N_compressed
  *   h_stats    HOST    T entries, caller-owned, filled on return
  * Distinct-row counts are exact (hashing, then every hash match is verified element by element).
- * Synchronises `stream` before returning.  Allocates its own workspace on first use.
+ * Synchronises `stream` before returning.  Allocates its own workspace on first use.  DLC_ESTATE on a context with
+ * num_dest > 1 (a table's statistics are over its whole batch), DLC_EINVAL with more than 65535 tables.
  */
 int dlc_stats(dlc_ctx* ctx, const void* d_payload, const float* h_probe_eb, dlc_table_stats* h_stats, void* stream);
 

@@ -53,6 +53,11 @@ def lib():
         if not os.path.exists(_LIB_PATH):
             raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2407_04272_amd.build` "
                                "(there is no fallback path)")
+        # PyTorch brings its own HIP runtime.  It has to be the one that initialises the GPU: if this library's first
+        # HIP call came before torch's, torch would find no device afterwards.
+        import torch
+        if torch.cuda.is_available():
+            torch.cuda.init()
         L = C.CDLL(_LIB_PATH)
         vp, i32, i64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
         L.dlc_create.argtypes = [C.POINTER(vp), C.POINTER(Config)]

@@ -104,6 +104,7 @@ static bool make_geom(const dlc_config* c, Geom* g) {
     g->LMAX = (uint32_t)L; g->dtype = (uint32_t)c->dtype; g->es = c->dtype == DLC_F16 ? 2u : 4u;
     g->vec = (n % 4 == 0) ? 1u : 0u;
     g->lz = (c->flags & DLC_FLAG_ROW_MATCH) ? 1u : 0u;
+    if (g->lz && T > 65535ull) return false;  // the row kernels' grids have a table per y index
     return true;
 }
 
@@ -391,6 +392,7 @@ extern "C" int dlc_stats(dlc_ctx* c, const void* d_payload, const float* probe_e
     if (!c || !aligned16(d_payload) || !probe_eb || !out) return DLC_EINVAL;
     const Geom& g = c->g;
     if (g.ND != 1) return DLC_ESTATE;  // a table's statistics are over its whole batch: use a context that is not split
+    if (g.T > 65535u) return DLC_EINVAL;  // the kernels' grids have a table per y index
     for (uint32_t t = 0; t < g.T; ++t)
         if (!good_eb(probe_eb[t])) return DLC_EINVAL;
     hipStream_t s = (hipStream_t)stream;

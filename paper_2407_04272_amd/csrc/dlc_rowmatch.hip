@@ -181,7 +181,8 @@ __global__ __launch_bounds__(256) void k_rm_hash(const void* payload, Geom g, co
 // open-addressing set in LDS (a slot holds a row index; the hash of the row that sits there is read from memory,
 // and only rows with that hash ever replace it, the smaller index winning), and then looks every one of its rows
 // up again: own[row] = the smallest row index with the row's hash.  n_slots (a power of two) is the batch size or
-// more whenever that fits the LDS, so the set cannot fill up; where it is less and does fill up, the rows that
+// more whenever that fits the LDS, so the set cannot fill up; for larger batches a work-group's share of the rows
+// is half the slots or less, and where a set does fill up all the same (hashes that crowd into one share), the rows that
 // found no slot are their own owners (coded rows, for row matching), and ctrl, if given, gets an error (the
 // statistics want exact counts).  rowhash and own: [sets][T][B]; on (optional): tables to skip; unique (optional):
 // [T][sets] counts of the rows that own their hash.
@@ -206,7 +207,7 @@ __global__ __launch_bounds__(1024) void k_rm_sets(Geom g, const uint8_t* on, con
 #pragma unroll
         for (uint32_t k = 0; k < kBatch; ++k) {
             const uint32_t row = r0 + k * 1024u;
-            if (row >= g.B || ((uint32_t)(h[k] >> 59) & (parts - 1u)) != part) continue;
+            if (row >= g.B || ((uint32_t)(h[k] >> 52) & (parts - 1u)) != part) continue;
             uint32_t pos = (uint32_t)(h[k] >> 20) & (n_slots - 1u);
             bool placed = false;
             for (uint32_t probe_n = 0; probe_n < n_slots; ++probe_n) {
@@ -234,7 +235,7 @@ __global__ __launch_bounds__(1024) void k_rm_sets(Geom g, const uint8_t* on, con
 #pragma unroll
         for (uint32_t k = 0; k < kBatch; ++k) {
             const uint32_t row = r0 + k * 1024u;
-            if (row >= g.B || ((uint32_t)(h[k] >> 59) & (parts - 1u)) != part) continue;
+            if (row >= g.B || ((uint32_t)(h[k] >> 52) & (parts - 1u)) != part) continue;
             uint32_t o = row;
             uint32_t pos = (uint32_t)(h[k] >> 20) & (n_slots - 1u);
             for (uint32_t probe_n = 0; probe_n < n_slots; ++probe_n) {
@@ -412,11 +413,13 @@ void row_match_multipliers(uint32_t* mult, uint32_t n_pieces) {
 
 hipError_t launch_row_sets(const Geom& g, uint32_t n_sets, const uint8_t* on, const uint64_t* rowhash, uint32_t* own,
                            uint32_t* unique, Ctrl* ctrl, hipStream_t s) {
-    // about a thousand work-groups in all, 32 per table and set at most; slots for the whole batch, 64 KiB at most
-    uint32_t parts = 1;
-    while (parts < 32u && parts * g.T * n_sets < 1024u) parts <<= 1;
+    // slots for the whole batch, 64 KiB at most; about a thousand work-groups in all (32 per table and set at most),
+    // and more where a batch is large: a work-group's share of the rows is half its slots or less (up to 32 M rows)
     uint32_t n_slots = 64;
     while (n_slots < g.B && n_slots < 16384u) n_slots <<= 1;
+    uint32_t parts = 1;
+    while (parts < 32u && parts * g.T * n_sets < 1024u) parts <<= 1;
+    while (parts < 4096u && (uint64_t)parts * n_slots < 2ull * g.B) parts <<= 1;
     hipLaunchKernelGGL(k_rm_sets, dim3(parts, g.T, n_sets), dim3(1024), n_slots * 4u, s, g, on, rowhash, own, n_slots, parts,
                        unique, ctrl);
     return hipGetLastError();

@@ -190,7 +190,8 @@ def test_stats_small_cases():
                              (1, 1, 1, np.float32), (2, 130, 7, np.float16), (2, 300, 6, np.float16),
                              (1, 100, 300, np.float32),     # rows longer than a wavefront's 64 16-byte pieces
                              (1, 5000, 2, np.float32),      # nearly every row repeats another
-                             (2, 1500, 3, np.float16)]:
+                             (2, 1500, 3, np.float16),
+                             (1, 300000, 4, np.float32)]:    # more rows than 32 row sets of 16384 slots hold
         vals = rng.choice(np.linspace(-1, 1, 9), (T, B, D)).astype(np.float32)
         vals += (rng.random((T, B, D)) < 0.2) * np.float32(0.003)
         vals[0, 0, 0] = np.nan

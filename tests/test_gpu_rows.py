@@ -51,6 +51,7 @@ CASES = [  # T, B, D, S, dtype
     (1, 200, 260, 64, np.float32),      # long rows: more 4-byte pieces than a wavefront has lanes
     (1, 130, 1040, 128, np.float32),    # the same with 16-byte pieces
     (2, 9000, 32, 256, np.float16),     # more rows than one pass of the set kernel's threads
+    (1, 280000, 4, 256, np.float32),    # more rows than 32 row sets hold: the rows are divided further
 ]
 
 
