@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--carry-codebook", action="store_true",
                     help="time the single-pass path (DLC_FLAG_CARRY_CODEBOOK: each step is coded with the codebook built "
                          "from the previous step's payload) instead of the default two-pass path")
+    ap.add_argument("--row-match", action="store_true",
+                    help="time the path with the vector-based LZ step on every table (DLC_FLAG_ROW_MATCH) instead of the "
+                         "default path; the roofline object then still prices the kernel the profile slots see")
     ap.add_argument("--all-workloads", action="store_true",
                     help="also measure the five synthetic workloads one after the other (adds a 'workloads' list to the "
                          "JSON line; takes about a minute more, mostly the oracle)")
@@ -63,7 +66,10 @@ def main():
     d = w.payload
     T, B, D = d.shape
     payload_bytes = d.numel() * 4
-    flags = b.FLAG_CARRY_CODEBOOK if args.carry_codebook else 0
+    if args.carry_codebook and args.row_match:
+        print("bench.py: --carry-codebook and --row-match are two different paths; pick one", file=sys.stderr)
+        sys.exit(2)
+    flags = b.FLAG_CARRY_CODEBOOK if args.carry_codebook else (b.FLAG_ROW_MATCH if args.row_match else 0)
     ctx = b.Context(b.make_config(b.F32, T, B, D, chunk_symbols=args.chunk_symbols, flags=flags))
 
     # offline analysis (Section III-A): statistics -> table classes; timed on its own
@@ -161,7 +167,7 @@ def main():
     # HBM bytes per launch of the dominant kernel, from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
     # profiles/cfg3_hbm_traffic_pmc.txt (they cannot be collected from inside this process); known for this workload only
     measured_traffic = {"k_encode": 253.9e6, "k_hist": 671.8e6, "k_decode": 597.4e6, "k_encode_carry": CARRY_TRAFFIC}
-    traffic = measured_traffic.get(dom) if (args.workload == "cfg3" and args.chunk_symbols == 256) else None
+    traffic = measured_traffic.get(dom) if (args.workload == "cfg3" and args.chunk_symbols == 256 and not args.row_match) else None
     result = {
         "metric": "compress+decompress round-trip GB/s of uncompressed fp32 payload, 1 MI355X",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -170,7 +176,8 @@ def main():
         "config": {"workload": f"{args.workload}: {T} tables x {B} lookups x dim {D} fp32 ({payload_bytes >> 20} MiB), "
                                "Zipf(1.05) single-hot, N(0,sigma_t), table-wise range-relative bounds 0.03",
                    "chunk_symbols": args.chunk_symbols, "radius": 512, "max_code_len": 12,
-                   "codebook": "carried from the previous step" if args.carry_codebook else "built from the step's own payload"},
+                   "codebook": "carried from the previous step" if args.carry_codebook else "built from the step's own payload",
+                   "row_matching": bool(args.row_match)},
         "compression_ratio": round(cr, 3),
         "compress_GBps": round(payload_bytes / comp_ms / 1e6, 2), "compress_ms": round(comp_ms, 4),
         "decompress_GBps": round(payload_bytes / dec_ms / 1e6, 2), "decompress_ms": round(dec_ms, 4),
@@ -183,7 +190,7 @@ def main():
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
     }
 
-    if not args.carry_codebook:
+    if not args.carry_codebook and not args.row_match:
         # for information: the same workload through the single-pass path (not part of `value`)
         ctx2 = b.Context(b.make_config(b.F32, T, B, D, chunk_symbols=args.chunk_symbols, flags=b.FLAG_CARRY_CODEBOOK))
         ctx2.set_error_bounds(eb=ebs)
@@ -216,7 +223,7 @@ def main():
         if args.carry_codebook:  # the steady state of the chain: the counts of the same payload
             carry = oracle.compress(x, ebs, want_hist=True).hist
         t0 = time.perf_counter()
-        o = oracle.compress(x, ebs, carry_hist=carry)
+        o = oracle.compress(x, ebs, carry_hist=carry, row_match=bool(args.row_match))
         tc = time.perf_counter() - t0
         t0 = time.perf_counter()
         rc, orec = oracle.decompress(o.data, x.shape, np.float32)
