@@ -338,10 +338,27 @@ __global__ __launch_bounds__(256) void k_row_copy(Geom g, const uint8_t* comp, u
     U* tab = reinterpret_cast<U*>(static_cast<uint8_t*>(outp) + (size_t)t * g.n * g.es);
     const uint32_t upr = g.D / 4u;  // pieces per row (four elements each; dim % 4 == 0)
     const uint32_t total = g.B * upr;
-    for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
-        const uint32_t row = i / upr, u = i - row * upr;
-        const uint32_t o = ref[row];
-        if (o != row) tab[(size_t)row * upr + u] = tab[(size_t)o * upr + u];
+    constexpr uint32_t kN = 4;  // pieces a thread has in flight: references first, then the rows they point at
+    const uint32_t stride = gridDim.x * 256;
+    for (uint32_t i0 = blockIdx.x * 256 + threadIdx.x; i0 < total; i0 += stride * kN) {
+        uint32_t row[kN], o[kN];
+        U v[kN];
+#pragma unroll
+        for (uint32_t k = 0; k < kN; ++k) {
+            const uint32_t i = i0 + k * stride;
+            row[k] = i < total ? i / upr : 0xFFFFFFFFu;
+            o[k] = i < total ? ref[row[k]] : 0xFFFFFFFFu;
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < kN; ++k) {
+            const uint32_t i = i0 + k * stride;
+            if (o[k] != row[k]) v[k] = tab[(size_t)o[k] * upr + (i - row[k] * upr)];
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < kN; ++k) {
+            const uint32_t i = i0 + k * stride;
+            if (o[k] != row[k]) tab[(size_t)i] = v[k];
+        }
     }
 }
 
