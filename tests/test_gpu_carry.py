@@ -206,3 +206,43 @@ def test_f16_ties_on_the_single_pass_path():
         o = oracle.compress(x, ebs, R, 128, 12, carry_hist=prev, want_hist=True)
         _same(g, o, x, f"call {k}")
         prev = o.hist
+
+
+def test_periodic_reclassification_in_a_carried_run():
+    """Every fourth iteration the tables are classified again from the current payload (dlc_stats, then
+    dlc_set_error_bounds with those statistics); in between the schedule alone moves the bounds.  Statistics,
+    classes, bounds and containers against the oracle; the carried chain starts anew whenever a bound changed."""
+    from paper_2407_04272_amd import binding as b
+    T, B, D, S = 4, 512, 32, 128
+    ch = _Chain((T, B, D), np.float32, S)
+    p = b.ControllerParams(mode=0, decay_kind=b.DECAY_STEPWISE, global_eb=2e-3, alpha=5.0 / 3.0, beta=3.0, h_large=0.0,
+                           h_small=0.05, decay_start=0, decay_len=6, decay_steps=2, reserved=0, decay_mult0=2.0,
+                           eb_min=0.0, eb_max=0.0, rel_floor=0.0)
+    op = oracle.ControllerParams(**{f[0]: getattr(p, f[0]) for f in p._fields_})
+    probe = np.full(T, 2e-3, np.float32)
+    st = ost = None
+    prev_hist, prev_eb = None, None
+    classes, carried_calls, fresh_calls = [], 0, 0
+    for it in range(12):
+        x = _batch(T, B, D, 300 + it, rows=300)
+        if it < 6:                                  # early on the rows of this table merge once quantised ...
+            x[2] = x[2, :1] + np.random.default_rng(it).standard_normal((B, D)).astype(np.float32) * np.float32(1e-5)
+        x[1, B // 2:] = x[1, :B // 2]               # (a table with repeated rows throughout)
+        if it % 4 == 0:                             # ... so its class changes at a later re-classification
+            st = ch.ctx.stats(to_device(x), probe)
+            ost = oracle.stats(x, probe)
+            for t in range(T):
+                assert (st[t].n_unique_raw, st[t].n_unique_quant, st[t].min, st[t].max) == \
+                       (ost[t].n_unique_raw, ost[t].n_unique_quant, ost[t].min, ost[t].max), (it, t)
+        ebs, cls = ch.ctx.set_error_bounds(stats=st, params=p, iteration=it)
+        oeb, ocls = oracle.controller(ost, op, it)
+        assert np.array_equal(ebs.view(np.uint32), oeb.view(np.uint32)) and np.array_equal(cls, ocls), it
+        classes.append(tuple(int(c) for c in cls))
+        carried = prev_eb is not None and np.array_equal(prev_eb.view(np.uint32), oeb.view(np.uint32))
+        carried_calls += carried
+        fresh_calls += not carried
+        o = oracle.compress(x, oeb, R, S, 12, carry_hist=prev_hist if carried else None, want_hist=True)
+        _same(ch.compress(x, ebs), o, x, f"iteration {it}")
+        prev_hist, prev_eb = o.hist, oeb
+    assert len(set(classes)) >= 2                   # a re-classification did change a class
+    assert carried_calls >= 4 and fresh_calls >= 3  # both kinds of call were exercised
