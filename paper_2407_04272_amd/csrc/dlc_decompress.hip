@@ -338,27 +338,27 @@ __global__ __launch_bounds__(256) void k_row_copy(Geom g, const uint8_t* comp, u
     U* tab = reinterpret_cast<U*>(static_cast<uint8_t*>(outp) + (size_t)t * g.n * g.es);
     const uint32_t upr = g.D / 4u;  // pieces per row (four elements each; dim % 4 == 0)
     const uint32_t total = g.B * upr;
-    constexpr uint32_t kN = 4;  // pieces a thread has in flight: references first, then the rows they point at
+    // four pieces a thread has in flight: references first, then the rows they point at (named variables, not an
+    // array: the compiler moved an array of vectors into LDS)
     const uint32_t stride = gridDim.x * 256;
-    for (uint32_t i0 = blockIdx.x * 256 + threadIdx.x; i0 < total; i0 += stride * kN) {
-        uint32_t row[kN], o[kN];
-        U v[kN];
+    for (uint32_t i0 = blockIdx.x * 256 + threadIdx.x; i0 < total; i0 += stride * 4u) {
+        uint32_t row[4], o[4];
 #pragma unroll
-        for (uint32_t k = 0; k < kN; ++k) {
+        for (uint32_t k = 0; k < 4; ++k) {
             const uint32_t i = i0 + k * stride;
             row[k] = i < total ? i / upr : 0xFFFFFFFFu;
             o[k] = i < total ? ref[row[k]] : 0xFFFFFFFFu;
         }
-#pragma unroll
-        for (uint32_t k = 0; k < kN; ++k) {
-            const uint32_t i = i0 + k * stride;
-            if (o[k] != row[k]) v[k] = tab[(size_t)o[k] * upr + (i - row[k] * upr)];
-        }
-#pragma unroll
-        for (uint32_t k = 0; k < kN; ++k) {
-            const uint32_t i = i0 + k * stride;
-            if (o[k] != row[k]) tab[(size_t)i] = v[k];
-        }
+        auto src = [&](uint32_t k) -> size_t { return (size_t)o[k] * upr + (i0 + k * stride - row[k] * upr); };
+        U v0{}, v1{}, v2{}, v3{};
+        if (o[0] != row[0]) v0 = tab[src(0)];
+        if (o[1] != row[1]) v1 = tab[src(1)];
+        if (o[2] != row[2]) v2 = tab[src(2)];
+        if (o[3] != row[3]) v3 = tab[src(3)];
+        if (o[0] != row[0]) tab[(size_t)i0] = v0;
+        if (o[1] != row[1]) tab[(size_t)i0 + stride] = v1;
+        if (o[2] != row[2]) tab[(size_t)i0 + 2u * stride] = v2;
+        if (o[3] != row[3]) tab[(size_t)i0 + 3u * stride] = v3;
     }
 }
 
