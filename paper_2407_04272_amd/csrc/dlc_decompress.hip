@@ -80,9 +80,21 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
     __syncthreads();
     if (ok && D.ref_off != 0) {  // every reference points back, at a row that is coded
         const uint32_t* ref = reinterpret_cast<const uint32_t*>(comp + D.ref_off);
-        for (uint32_t r = tid; r < g.B; r += 256) {
-            const uint32_t o = ref[r];
-            if (o > r || ref[o] != o) s_ok = 0;
+        for (uint32_t r0 = tid; r0 < g.B; r0 += 256u * 4u) {  // four rows in flight per thread
+            uint32_t o[4], oo[4];
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) {
+                const uint32_t r = r0 + k * 256u;
+                o[k] = r < g.B ? ref[r] : 0u;
+            }
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) {
+                const uint32_t r = r0 + k * 256u;
+                oo[k] = (r < g.B && o[k] <= r) ? ref[o[k]] : 0xFFFFFFFFu;
+            }
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k)
+                if (r0 + k * 256u < g.B && oo[k] != o[k]) s_ok = 0;  // (a reference forward left oo at "no row")
         }
     }
     const uint32_t nl = ok ? sym_hi - sym_lo + 1u : 0u;
