@@ -4,6 +4,9 @@
 #include "dlc_internal.h"
 
 // phase time stamps for kernel micro-benchmarks; expands to nothing in the library
+#ifndef DLC_WSTAMP
+#define DLC_WSTAMP(i)
+#endif
 #ifndef DLC_STAMP
 #define DLC_STAMP(i)
 #endif
@@ -60,34 +63,37 @@ __device__ __forceinline__ uint32_t lane_put(uint32_t vec, uint32_t l, uint32_t 
     return lane == l ? val : vec;
 }
 
+// lane read with a wavefront-uniform lane number that the compiler can see is uniform (no broadcast of the number first)
+__device__ __forceinline__ uint32_t lane_read(uint32_t v, uint32_t l) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)l);
+}
+
 // The whole tree of a table with at most 64 used symbols, built by one wavefront without touching memory:
 // lane i holds used symbol i (symbol order) on entry.  Leaves and merged nodes live one per lane; the merge
-// loop runs on wavefront-uniform values (lane reads and writes); depths come from pointer jumping.
-// Lengths above LM are limited as described above.  Returns the code length of the leaf at sorted position
-// `lane` (rising count, then symbol) and that leaf's symbol in *sorted_sym.  2 <= n <= 64.
-__device__ __forceinline__ uint32_t wave_huffman_lengths(uint32_t n, uint32_t LM, uint32_t sym, uint32_t cnt, uint32_t lane,
-                                                         uint32_t* sorted_sym) {
+// loop runs on wavefront-uniform values only (the queue heads sit in scalar registers, lane reads and writes
+// move them); depths come from pointer jumping.  Lengths above LM are limited as described above.  Returns the
+// code length of the symbol the lane came in with.  2 <= n <= 64.
+__device__ __forceinline__ uint32_t wave_huffman_lengths(uint32_t n, uint32_t LM, uint32_t cnt, uint32_t lane) {
     const uint32_t kInf = 0xFFFFFFFFu;
+    DLC_WSTAMP(0);
     // position in (count, symbol) order
     uint32_t rank = 0;
     for (uint32_t j = 0; j < n; ++j) {
-        const uint32_t cj = lane_get(cnt, j);
+        const uint32_t cj = lane_read(cnt, j);
         rank += (cj < cnt || (cj == cnt && j < lane)) ? 1u : 0u;
     }
     if (lane >= n) rank = lane;  // idle lanes keep their place
-    // the sorted sequence: lane r takes the values of the lane whose rank is r (inverse permutation by search)
-    uint32_t src = lane;
-    for (uint32_t j = 0; j < n; ++j) {
-        const uint32_t rj = lane_get(rank, j);
-        src = (rj == lane) ? j : src;
-    }
-    const uint32_t s_sym = __shfl(sym, src, 64), s_cnt = lane < n ? __shfl(cnt, src, 64) : kInf;
-    // two-queue merge; a tie between the heads takes the leaf
-    uint32_t vw = s_cnt, vn = kInf, vpl = 0, vpn = 0;
+    // the sorted sequence: every lane sends its count to the lane of its rank
+    const uint32_t sent = (uint32_t)__builtin_amdgcn_ds_permute((int)(rank << 2), (int)cnt);
+    const uint32_t s_cnt = lane < n ? sent : kInf;
+    DLC_WSTAMP(1);
+    // two-queue merge; a tie between the heads takes the leaf.  l0, l1: the two leaves at the head of the leaf
+    // queue; n0, n1: the same for the merged nodes (node k exists from step k + 1 on)
+    const uint32_t vw = s_cnt;
+    uint32_t vn = kInf, vpl = 0, vpn = 0;
     uint32_t a = 0, bq = 0;
+    uint32_t l0 = lane_read(vw, 0), l1 = lane_read(vw, 1), n0 = kInf, n1 = kInf;
     for (uint32_t k = 0; k + 1 < n; ++k) {
-        const uint32_t l0 = a < n ? lane_get(vw, a) : kInf, l1 = a + 1 < n ? lane_get(vw, a + 1) : kInf;
-        const uint32_t n0 = bq < k ? lane_get(vn, bq) : kInf, n1 = bq + 1 < k ? lane_get(vn, bq + 1) : kInf;
         const bool f_leaf = l0 <= n0;
         const uint32_t s1 = f_leaf ? l0 : n0;
         const uint32_t c_l = f_leaf ? l1 : l0, c_n = f_leaf ? n0 : n1;
@@ -96,7 +102,12 @@ __device__ __forceinline__ uint32_t wave_huffman_lengths(uint32_t n, uint32_t LM
         if (f_leaf) { vpl = lane_put(vpl, a, k, lane); ++a; } else { vpn = lane_put(vpn, bq, k, lane); ++bq; }
         if (s_leaf) { vpl = lane_put(vpl, a, k, lane); ++a; } else { vpn = lane_put(vpn, bq, k, lane); ++bq; }
         vn = lane_put(vn, k, s1 + s2, lane);
+        l0 = a < n ? lane_read(vw, a) : kInf;
+        l1 = a + 1u < n ? lane_read(vw, a + 1u) : kInf;
+        n0 = bq <= k ? lane_read(vn, bq) : kInf;
+        n1 = bq + 1u <= k ? lane_read(vn, bq + 1u) : kInf;
     }
+    DLC_WSTAMP(2);
     // depth of every merged node (lane k = node k, the root is node n-2)
     const uint32_t root = n - 2u;
     uint32_t p = (lane < root) ? vpn : lane;
@@ -107,7 +118,7 @@ __device__ __forceinline__ uint32_t wave_huffman_lengths(uint32_t n, uint32_t LM
         d += dd;
         p = pp;
     }
-    uint32_t len = lane < n ? __shfl(d, vpl, 64) + 1u : 0u;
+    uint32_t len = lane < n ? __shfl(d, vpl, 64) + 1u : 0u;  // of the leaf at sorted position `lane`
     uint32_t m = len;
     for (int o = 32; o > 0; o >>= 1) m = max(m, (uint32_t)__shfl_xor(m, o, 64));
     if (m > LM) {
@@ -132,16 +143,17 @@ __device__ __forceinline__ uint32_t wave_huffman_lengths(uint32_t n, uint32_t LM
             kraft -= 1;
         }
         // lengths are handed out most frequent leaf first (the leaves are sorted by rising count)
-        const uint32_t rank = n - 1u - lane;
+        const uint32_t back = n - 1u - lane;
         uint32_t acc = 0, nl = 1;
         for (uint32_t L = 1; L < LM; ++L) {
             acc += lane_get(clv, L);  // leaves with a length of at most L
-            nl += (rank >= acc) ? 1u : 0u;
+            nl += (back >= acc) ? 1u : 0u;
         }
         len = lane < n ? nl : 0u;
     }
-    *sorted_sym = s_sym;
-    return len;  // of the leaf at sorted position `lane`
+    DLC_WSTAMP(3);
+    // back to symbol order: the lane that came in with a symbol reads the length at that symbol's sorted position
+    return lane < n ? __shfl(len, rank, 64) : 0u;
 }
 
 // hist_t is read, copied to hist_view_t (inspection) and cleared, so that the next call starts from zero counts.
@@ -196,43 +208,58 @@ __device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, 
     DLC_STAMP(1);
     if (n_used >= 2 && n_used <= 64) {
         if (wave == 0) {
-            const uint64_t kv = lane < n_used ? key[lane] : ~0ull;
-            uint32_t s_sym;
-            const uint32_t len = wave_huffman_lengths(n_used, g.LMAX, (uint32_t)(kv & 0xFFFFu), (uint32_t)(kv >> 16), lane,
-                                                      &s_sym);
-            // canonical codewords: first code of each length, then the rank among the symbols of that length
-            uint32_t code = 0, first = 0;
+            const uint64_t kv = lane < n_used ? key[lane] : ~0ull;  // lane i: the i-th used symbol
+            const uint32_t sym = (uint32_t)(kv & 0xFFFFu);
+            const uint32_t len = wave_huffman_lengths(n_used, g.LMAX, (uint32_t)(kv >> 16), lane);
+            // canonical codewords: first code of each length, then the rank among the symbols of that length (the
+            // lanes are in symbol order)
+            const uint64_t below = (1ull << lane) - 1ull;
+            uint32_t code = 0, mine_code = 0;
             for (uint32_t L = 1; L <= g.LMAX; ++L) {
                 code <<= 1;
-                first = (len == L) ? code : first;
-                code += (uint32_t)__popcll(__ballot(len == L));
+                const uint64_t same = __ballot(len == L);
+                mine_code = (len == L) ? code + (uint32_t)__popcll(same & below) : mine_code;
+                code += (uint32_t)__popcll(same);
             }
-            uint32_t r = 0;
-            for (uint32_t j = 0; j < n_used; ++j) {
-                const uint32_t lj = lane_get(len, j), sj = lane_get(s_sym, j);
-                r += (lj == len && sj < s_sym) ? 1u : 0u;
-            }
-            if (lane < n_used) { len_s[s_sym] = (uint16_t)len; nodew[s_sym] = first + r; }
+            if (lane < n_used) { len_s[sym] = (uint16_t)len; nodew[sym] = mine_code; }
             if (lane == 0) sh.codes_done = 1;
         }
         __syncthreads();
     } else if (n_used > 64) {
-        uint32_t P = 2;
-        while (P < n_used) P <<= 1;
-        for (uint32_t i = n_used + tid; i < P; i += 256) key[i] = ~0ull;  // pad to a power of two
-        __syncthreads();
+        const uint32_t n_escape = cnt[0];  // (cnt[] is scratch from here on:
+        __syncthreads();                   //  once every thread has read this)
         DLC_STAMP(2);
-        // bitonic sort, ascending
-        for (uint32_t size = 2; size <= P; size <<= 1) {
-            for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-                for (uint32_t i = tid; i < (P >> 1); i += 256) {
-                    uint32_t lo = 2 * i - (i & (stride - 1));
-                    uint32_t hi = lo + stride;
-                    bool up = (lo & size) == 0;
-                    uint64_t a = key[lo], bb = key[hi];
-                    if ((a > bb) == up) { key[lo] = bb; key[hi] = a; }
+        if (n_used <= 256) {
+            // rank sort, a thread per key: the keys are distinct (the symbol is part of them), so a key's place is
+            // the number of smaller keys; every thread reads the same key at a time (an LDS broadcast)
+            uint64_t* tmp = reinterpret_cast<uint64_t*>(cnt);  // cnt[] and nodew[] together: K words of 64 bits
+            uint64_t mykey = 0;
+            uint32_t rank = 0;
+            if (tid < n_used) {
+                mykey = key[tid];
+                for (uint32_t j = 0; j < n_used; ++j) rank += key[j] < mykey ? 1u : 0u;
+                tmp[rank] = mykey;
+            }
+            __syncthreads();
+            if (tid < n_used) key[tid] = tmp[tid];
+            __syncthreads();
+        } else {
+            uint32_t P = 2;
+            while (P < n_used) P <<= 1;
+            for (uint32_t i = n_used + tid; i < P; i += 256) key[i] = ~0ull;  // pad to a power of two
+            __syncthreads();
+            // bitonic sort, ascending
+            for (uint32_t size = 2; size <= P; size <<= 1) {
+                for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+                    for (uint32_t i = tid; i < (P >> 1); i += 256) {
+                        uint32_t lo = 2 * i - (i & (stride - 1));
+                        uint32_t hi = lo + stride;
+                        bool up = (lo & size) == 0;
+                        uint64_t a = key[lo], bb = key[hi];
+                        if ((a > bb) == up) { key[lo] = bb; key[hi] = a; }
+                    }
+                    __syncthreads();
                 }
-                __syncthreads();
             }
         }
         DLC_STAMP(3);
@@ -251,10 +278,29 @@ __device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, 
                 }
                 nodew[k] = sum;
             }
-            depth_node[n - 2] = 0;
-            for (int k = (int)n - 3; k >= 0; --k) depth_node[k] = depth_node[parent_node[k]] + 1;
         }
         __syncthreads();
+        {
+            // depth of every merged node by pointer jumping (the root, node n - 2, points at itself at distance 0):
+            // after round r a node knows its 2^r-th ancestor and the distance to it.  Two buffers of packed
+            // (distance << 16 | ancestor) words, in cnt[] and nodew[], which are both free here.
+            const uint32_t root = n_used - 2u;
+            uint32_t* cur = cnt;
+            uint32_t* nxt = nodew;
+            for (uint32_t k = tid; k + 1 < n_used; k += 256) cur[k] = k == root ? root : ((1u << 16) | parent_node[k]);
+            __syncthreads();
+            for (uint32_t span = 1; span < n_used; span <<= 1) {  // uniform trip count
+                for (uint32_t k = tid; k + 1 < n_used; k += 256) {
+                    const uint32_t me = cur[k], up = cur[me & 0xFFFFu];
+                    nxt[k] = ((me >> 16) + (up >> 16)) << 16 | (up & 0xFFFFu);
+                }
+                __syncthreads();
+                uint32_t* sw = cur; cur = nxt; nxt = sw;
+            }
+            for (uint32_t k = tid; k + 1 < n_used; k += 256) depth_node[k] = (uint16_t)(cur[k] >> 16);
+            __syncthreads();
+            if (tid == 0) cnt[0] = n_escape;  // read again at the end (nothing below writes cnt[])
+        }
         DLC_STAMP(4);
         // leaf depths; parent_leaf[] is reused to hold the depth of leaf i (sorted order)
         uint32_t local_max = 0;
@@ -311,9 +357,15 @@ __device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, 
                     sh.next[L] = code;
                     code += sh.cl[L];
                 }
-                for (uint32_t k = sym_lo; k <= sym_hi; ++k) {
-                    uint32_t L = len_s[k];
-                    if (L) nodew[k] = sh.next[L]++;
+            }
+            __syncthreads();
+            // a symbol's codeword: the first code of its length plus the number of smaller symbols of that length
+            for (uint32_t k = sym_lo + tid; k <= sym_hi; k += 256) {
+                const uint32_t L = len_s[k];
+                if (L) {
+                    uint32_t r = 0;
+                    for (uint32_t j = sym_lo; j < k; ++j) r += len_s[j] == L ? 1u : 0u;
+                    nodew[k] = sh.next[L] + r;
                 }
             }
             __syncthreads();
