@@ -14,7 +14,7 @@ def to_device(x: np.ndarray):
     return torch.from_numpy(np.ascontiguousarray(x)).cuda()
 
 
-class GpuRun:
+class DeviceRun:
     """compress + decompress of one payload on cuda:0; everything copied back to numpy."""
 
     def __init__(self, payload, eb, R=512, S=256, LMAX=12, capacity=None, ctx=None, d_payload=None, flags=0):

@@ -9,7 +9,7 @@ import pytest
 
 import dlc_workloads as W
 import oracle
-from gpu_util import GpuRun, to_device
+from gpu_util import DeviceRun, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -37,7 +37,7 @@ def _check_bound(x, rec, ebs):
 def _full_parity(x, eb, S=256, LMAX=12, Rr=R, flags=0):
     T = x.shape[0]
     ebs = np.broadcast_to(np.asarray(eb, np.float32), (T,))
-    g = GpuRun(x, ebs, R=Rr, S=S, LMAX=LMAX, flags=flags)
+    g = DeviceRun(x, ebs, R=Rr, S=S, LMAX=LMAX, flags=flags)
     o = oracle.compress(x, ebs, Rr, S, LMAX)
     assert g.rc == 0 and g.status == 0 and o.rc == 0
     assert g.guard_ok
@@ -88,7 +88,7 @@ def test_symbols_histogram_codebook_bit_exact():
     x = _payload(3, 500, 48, 3)
     x.reshape(-1)[::211] = 123.0
     ebs = np.array([1e-3, 3e-3, 2e-2], np.float32)
-    g = GpuRun(x, ebs, S=64)
+    g = DeviceRun(x, ebs, S=64)
     d_sym = torch.zeros(x.size, dtype=torch.int16, device="cuda")
     g.ctx.quantize(g.d_payload, d_sym)
     sym = d_sym.cpu().numpy().view(np.uint16).reshape(x.shape)
@@ -173,7 +173,7 @@ def test_workload1_and_2():
     assert np.array_equal(ebs.view(np.uint32), oeb.view(np.uint32)) and np.array_equal(cls, ocls)
     assert len(set(cls.tolist())) >= 2                 # the workload exercises more than one class
     assert np.all(ebs >= np.float32(1e-4)) and np.all(ebs <= np.float32(1e-2))
-    g = GpuRun(x, ebs, ctx=ctx, d_payload=d)
+    g = DeviceRun(x, ebs, ctx=ctx, d_payload=d)
     o = oracle.compress(x, ebs)
     assert g.status == 0 and np.array_equal(g.data, o.data) and np.array_equal(g.sizes, o.sizes)
     st2, rec = g.decompress()
@@ -226,15 +226,15 @@ def test_errors_and_robustness():
     ctx.set_error_bounds(eb=1e-3)
     assert ctx.compress(d.view(torch.uint8).view(-1)[4:].view(torch.float32), out, sizes) == b.EINVAL   # misaligned
     # exact capacity works, one byte less fails cleanly and writes nothing past the limit
-    g = GpuRun(x, 1e-3, S=64)
+    g = DeviceRun(x, 1e-3, S=64)
     assert g.status == 0
-    g_exact = GpuRun(x, 1e-3, S=64, capacity=g.total)
+    g_exact = DeviceRun(x, 1e-3, S=64, capacity=g.total)
     assert g_exact.status == 0 and np.array_equal(g_exact.data, g.data) and g_exact.guard_ok
     for cap in (g.total - 4, g.total // 2, 1024, 256):
-        bad = GpuRun(x, 1e-3, S=64, capacity=cap)
+        bad = DeviceRun(x, 1e-3, S=64, capacity=cap)
         assert bad.status == b.ECAPACITY and bad.total == 0 and bad.guard_ok, cap
     # the context keeps working after a failure
-    again = GpuRun(x, 1e-3, S=64)
+    again = DeviceRun(x, 1e-3, S=64)
     assert again.status == 0 and np.array_equal(again.data, g.data)
     # corrupt containers are rejected, never fault
     import container_reader as cr
@@ -262,9 +262,9 @@ def test_errors_and_robustness():
 
 def test_deterministic_bytes():
     x = _payload(4, 3000, 64, 11)
-    a = GpuRun(x, 2e-3, S=256)
+    a = DeviceRun(x, 2e-3, S=256)
     for _ in range(3):
-        c = GpuRun(x, 2e-3, S=256, ctx=a.ctx, d_payload=a.d_payload)
+        c = DeviceRun(x, 2e-3, S=256, ctx=a.ctx, d_payload=a.d_payload)
         assert c.status == 0 and np.array_equal(a.data, c.data)
 
 
