@@ -42,6 +42,28 @@ def test_host_only_entry_points():
                 b.make_config(b.F32, 4096, 1 << 18, 1 << 10)]:     # more than 2^32 element positions
         assert b.dlc_compress_bound(bad) == 0
         assert b.dlc_workspace_bytes(bad) == 0
+    # flags: row matching wants whole rows per lane (dim % 4 == 0), goes with several destinations, not with the
+    # other flags, and its kernels have a table per grid row (65535 at most); the fused kernel is for one destination
+    ok = [b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_ROW_MATCH), b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_ROW_MATCH, num_dest=8),
+          b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_CARRY_CODEBOOK, num_dest=8), b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_FUSED)]
+    for cfg in ok:
+        assert b.dlc_compress_bound(cfg) > 0 and b.dlc_workspace_bytes(cfg) > 0
+    bad = [b.make_config(b.F32, 4, 64, 6, flags=b.FLAG_ROW_MATCH),
+           b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_ROW_MATCH | b.FLAG_CARRY_CODEBOOK),
+           b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_ROW_MATCH | b.FLAG_FUSED),
+           b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_FUSED | b.FLAG_CARRY_CODEBOOK),
+           b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_FUSED, num_dest=2),
+           b.make_config(b.F32, 20000, 4, 4, flags=b.FLAG_ROW_MATCH, num_dest=4),
+           b.make_config(b.F32, 4, 64, 8, flags=8), b.make_config(b.F32, 4, 64, 8, num_dest=5000)]
+    for cfg in bad:
+        assert b.dlc_compress_bound(cfg) == 0 and b.dlc_workspace_bytes(cfg) == 0
+    # with row matching the bound has room for the references: 4 bytes per row and table, blocks 16-byte aligned
+    plain = b.dlc_compress_bound(b.make_config(b.F32, 4, 64, 8))
+    rows = b.dlc_compress_bound(b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_ROW_MATCH))
+    assert rows - plain in (4 * 4 * 64, 4 * 4 * 64 + 12)
+    # Eq. 2
+    assert abs(b.dlc_speedup_estimate(10.0, 25.0, 2000.0, 4000.0) - 1.0 / (0.1 + 25.0 * (1 / 2000.0 + 1 / 4000.0))) < 1e-12
+    assert b.dlc_speedup_estimate(0.0, 25.0, 2000.0, 4000.0) == 0.0
 
 
 def test_compress_bound_matches_oracle_formula():
