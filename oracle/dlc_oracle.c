@@ -930,9 +930,13 @@ int orc_decompress(const uint8_t* comp, size_t bytes, void* out, size_t out_capa
     if (off_payload != align_up(off_chunk + ORC_W * NG, 16)) return ORC_ECORRUPT;
     if (words_total > 0xFFFFFFFFull || n_out_total > (uint64_t)n * T) return ORC_ECORRUPT;
     if (off_codebook != align_up(off_payload + 4 * words_total, 16)) return ORC_ECORRUPT;
-    if (total < off_codebook) return ORC_ECORRUPT;
+    /* (every table has a code-length block, padded to four bytes) */
+    if (total < off_codebook || total - off_codebook < 4) return ORC_ECORRUPT;
     if (!out || out_capacity_bytes < n * T * es) return ORC_ECAPACITY;
 
+    uint64_t n_out_tables = 0; /* the header's escape count is the sum of the tables' */
+    for (int t = 0; t < T; ++t) n_out_tables += get32(comp + ORC_HEADER_BYTES + (size_t)ORC_DIR_BYTES * t + 16);
+    if (n_out_tables != n_out_total) return ORC_ECORRUPT;
     for (int t = 0; t < T; ++t) {
         const uint8_t* d = comp + ORC_HEADER_BYTES + (size_t)ORC_DIR_BYTES * t;
         float eb;
@@ -943,7 +947,8 @@ int orc_decompress(const uint8_t* comp, size_t bytes, void* out, size_t out_capa
         uint64_t cb_off = get64(d + 24);
         uint64_t ref_off = get64(d + 32); /* row matching: u32 ref[B], 0 = none */
         if (ref_off) {
-            if (ref_off % 4 || ref_off < off_codebook || ref_off + 4 * (uint64_t)B > total) return ORC_ECORRUPT;
+            /* (written without additions: an offset near 2^64 must not wrap past the test) */
+            if (ref_off % 4 || ref_off < off_codebook || ref_off > total || 4 * (uint64_t)B > total - ref_off) return ORC_ECORRUPT;
             for (int64_t r = 0; r < B; ++r) { /* a reference points back to a coded row */
                 uint32_t o = get32(comp + ref_off + 4 * (size_t)r);
                 if (o > (uint32_t)r || get32(comp + ref_off + 4 * (size_t)o) != o) return ORC_ECORRUPT;
@@ -952,7 +957,7 @@ int orc_decompress(const uint8_t* comp, size_t bytes, void* out, size_t out_capa
         if (!(eb > 0.0f) || isinf(eb)) return ORC_ECORRUPT;
         if (get32(d + 20) != G) return ORC_ECORRUPT;
         if (sym_lo > sym_hi || sym_hi >= (uint32_t)K || n_used < 1 || n_used > sym_hi - sym_lo + 1) return ORC_ECORRUPT;
-        if (cb_off < off_codebook || cb_off + (sym_hi - sym_lo + 1) > total) return ORC_ECORRUPT;
+        if (cb_off < off_codebook || cb_off > total || (uint64_t)(sym_hi - sym_lo + 1) > total - cb_off) return ORC_ECORRUPT;
         uint64_t seen_outl = 0;
         orc_qparam qp = make_qparam(eb);
 

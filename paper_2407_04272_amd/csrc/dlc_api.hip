@@ -42,7 +42,7 @@ void prof_end(void* p, int slot, hipStream_t s) {
 }
 
 static const char* kSlotNames[P_NSLOTS] = {"k_hist", "k_codebook", "k_encode", "k_finalize",
-                                           "k_dec_prepare", "k_decode", "k_fused", "k_encode_carry"};
+                                           "k_decode", "k_fused", "k_encode_carry"};
 }  // namespace dlc
 
 using namespace dlc;
@@ -149,19 +149,19 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
     uint8_t* rm_hash = g.lz ? take(8 * (size_t)g.T * g.B) : nullptr;
     uint8_t* rm_own = g.lz ? take(4 * (size_t)g.T * g.B) : nullptr;
     uint8_t* rm_mult = g.lz ? take(32 * (size_t)(g.D / 4u)) : nullptr;
-    uint8_t* lut = take(((size_t)g.T << g.LMAX) * 2);
-    uint8_t* dlay = take(sizeof(DecLayout) * g.ND);
     uint8_t* dtab = take(sizeof(DecTable) * g.T);
+    uint8_t* desc = take(4 * (size_t)g.T);
+    uint8_t* darr = take(4 * (size_t)g.T);
     if (w) {
         w->base = base; w->bytes = off;
         w->qp = (QParam*)qp;
         w->hist = (uint32_t*)hist; w->hist_view = (uint32_t*)hview; w->ctrl = (Ctrl*)ctrl;
         w->tmeta = (TMeta*)tmeta;
         w->enc = (uint16_t*)enc; w->lens = lens; w->state = (uint64_t*)state;
-        w->word_start = (uint32_t*)ws0; w->word_end = (uint32_t*)ws1; w->lut = (uint16_t*)lut;
+        w->word_start = (uint32_t*)ws0; w->word_end = (uint32_t*)ws1;
         w->arrive = (uint32_t*)arrive; w->ready = (uint64_t*)ready; w->sym_plane = plane;
         w->esc_count = (uint32_t*)escc;
-        w->dlay = (DecLayout*)dlay; w->dtab = (DecTable*)dtab;
+        w->dtab = (DecTable*)dtab; w->dec_esc = (uint32_t*)desc; w->dec_arrive = (uint32_t*)darr;
         w->rm_on = rm_on; w->rm_ref = (uint32_t*)rm_ref; w->rm_hash = (uint64_t*)rm_hash; w->rm_own = (uint32_t*)rm_own;
         w->rm_mult = (uint32_t*)rm_mult;
     }
@@ -342,7 +342,8 @@ extern "C" int dlc_decompress(dlc_ctx* c, const void* d_comp, size_t comp_bytes,
     if (!c || !aligned16(d_comp) || !aligned16(d_out)) return DLC_EINVAL;
     if (cap < (size_t)c->g.n * c->g.T * c->g.es) return DLC_ECAPACITY;
     if (c->g.ND > 1) comp_bytes = (comp_bytes / c->g.ND) & ~size_t(255);  // per container: container d starts at d * comp_bytes
-    if (comp_bytes < kHeaderBytes) return DLC_ECORRUPT;
+    // the sections whose size the geometry fixes (header, directory, group and chunk tables) must be there
+    if (comp_bytes < fixed_layout(c->g).off_payload) return DLC_ECORRUPT;
     hipError_t e = launch_decompress(c->g, (const uint8_t*)d_comp, comp_bytes, d_out, c->ws, c->prof.level, &c->prof,
                                      (hipStream_t)stream);
     return e == hipSuccess ? DLC_OK : DLC_EHIP;

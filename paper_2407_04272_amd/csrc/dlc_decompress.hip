@@ -1,5 +1,5 @@
-// Decompression kernels for gfx950: container validation + decode tables, chunk-parallel decode,
-// escape scatter.
+// Decompression kernels for gfx950: container validation, decode tables and chunk-parallel decode in one kernel,
+// escape scatter, row copies.
 #include <algorithm>
 
 #include "dlc_internal.h"
@@ -8,78 +8,86 @@ namespace dlc {
 
 __device__ __forceinline__ uint64_t d_a16(uint64_t x) { return (x + 15ull) & ~15ull; }
 
-// ------------------------------------------------------------------------------------------------
-// One work-group per table (of every container, when there are several): checks the header against the context's geometry and the table's
-// directory entry against the header, rebuilds the canonical code from the stored lengths and fills
-// the table's decode table: entry[i] = len << 12 | symbol for the codeword that prefixes the LMAX-bit
-// string i.  Anything inconsistent marks the table (or the whole container) invalid.
-// ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp, uint64_t comp_bytes, uint16_t* lut,
-                                                     DecLayout* dlay, DecTable* dtab, Ctrl* ctrl) {
-    __shared__ uint32_t s_ok;
-    __shared__ uint32_t s_cl[kLmaxLimit + 2], s_first[kLmaxLimit + 2], s_index[kLmaxLimit + 2];
-    __shared__ uint16_t s_sorted[4096];
-    __shared__ uint8_t s_len[4096];
-    const uint32_t tid = threadIdx.x, t = blockIdx.x;
-    // the container this table is in: container d starts at d * comp_bytes (comp_bytes: the room of one container)
-    const uint32_t dst = t / g.TD, tl = t - dst * g.TD;
-    comp += (uint64_t)dst * comp_bytes;
+// What a work-group learns from the container about the table it decodes.  Every range test is written without an
+// addition on the untrusted side (an offset near 2^64 must fail the test, not wrap past it).
+struct DecHead {
+    bool ok;
+    uint32_t n_used, sym_lo, sym_hi, n_esc;
+    float ebx2;
+    uint64_t cb;           // byte offset of the table's code lengths
+    uint64_t ref_off;      // row matching: byte offset of the table's u32 ref[B], 0 = none
+    uint64_t words_total;  // payload words of the container
+    uint64_t n_esc_total;  // escapes of the container
+};
+
+// Header against the context's geometry, the table's directory entry against the header.  `comp` is the start of the
+// container, `comp_bytes` the room it has; `tl` the table's place in the container.  The same for every thread.
+__device__ __forceinline__ DecHead dec_validate(const Geom& g, const FixedLayout& F, const uint8_t* comp,
+                                                uint64_t comp_bytes, uint32_t tl) {
+    DecHead H;
+    H.ok = false; H.n_used = 0; H.sym_lo = 0; H.sym_hi = 0; H.n_esc = 0; H.ebx2 = 0.f; H.cb = 0; H.ref_off = 0;
+    H.words_total = 0; H.n_esc_total = 0;
+    if (comp_bytes < F.off_payload) return H;  // header, directory, group and chunk tables: their size is the geometry's
+    // header and directory entry are read together (no test between the loads), then looked at
     const uint32_t* h = reinterpret_cast<const uint32_t*>(comp);
     const uint64_t* q = reinterpret_cast<const uint64_t*>(comp);
-    DecLayout L;
-    bool ok = comp_bytes >= kHeaderBytes + (uint64_t)kDirBytes * g.TD;
-    if (ok) {
-        ok = h[H_MAGIC] == kMagic && h[H_VERSION] == kVersion && h[H_DTYPE] == g.dtype && h[H_T] == g.TD &&
-             h[H_B] == g.B && h[H_D] == g.D && h[H_R] == g.R && h[H_S] == g.S && h[H_LMAX] == g.LMAX &&
-             h[H_W] == kW && h[H_V] == kV && h[H_NG] == g.TD * g.G;
-    }
-    uint64_t off_cb = 0, n_out = 0, total = 0;
-    if (ok) {
-        const FixedLayout F = fixed_layout(g);
-        n_out = q[HQ_NOUT];
-        L.words_total = q[HQ_WORDS];
-        L.off_group = q[HQ_OFF_GROUP]; L.off_chunk = q[HQ_OFF_CHUNK]; L.off_payload = q[HQ_OFF_PAYLOAD];
-        off_cb = q[HQ_OFF_CB];
-        total = q[HQ_TOTAL];
-        ok = total <= comp_bytes && L.off_group == F.off_group && L.off_chunk == F.off_chunk &&
-             L.off_payload == F.off_payload && L.words_total <= 0xFFFFFFFFull && n_out <= (uint64_t)g.n * g.TD &&
-             off_cb == d_a16(L.off_payload + 4ull * L.words_total) && total >= off_cb;
-    }
-    if (tl == 0 && tid == 0) {
-        L.valid = ok; L.pad = 0;
-        dlay[dst] = L;
-        if (!ok) set_status(ctrl, DLC_ECORRUPT);
-    }
-    DecTable D;
-    D.valid = 0; D.n_used = 0; D.sym_lo = 0; D.n_outliers = 0; D.ebx2 = 0.f; D.pad = 0; D.ref_off = 0;
-    uint32_t sym_lo = 0, sym_hi = 0, n_used = 0;
-    uint64_t cb = 0;
-    if (ok) {
-        const uint8_t* d = comp + kHeaderBytes + (uint64_t)kDirBytes * tl;
-        const uint32_t* d32 = reinterpret_cast<const uint32_t*>(d);
-        const uint64_t* d64 = reinterpret_cast<const uint64_t*>(d + 24);
-        const float eb = __uint_as_float(d32[0]);
-        n_used = d32[1]; sym_lo = d32[2]; sym_hi = d32[3];
-        D.n_outliers = d32[4];
-        cb = d64[0];
-        ok = eb > 0.f && eb < __builtin_inff() && d32[5] == g.G && sym_lo <= sym_hi && sym_hi < g.K && n_used >= 1 &&
-             n_used <= sym_hi - sym_lo + 1u && cb >= off_cb && cb + (sym_hi - sym_lo + 1u) <= total &&
-             D.n_outliers <= g.n;
-        D.ebx2 = eb * 2.0f;
-        D.sym_lo = sym_lo;
-        D.n_used = n_used;
-        // row matching: references behind the code-length blocks (only a context made for it decodes them, and the
-        // kernels want a lane's four elements in one row)
-        D.ref_off = d64[1];
-        if (D.ref_off != 0)
-            ok = ok && g.lz != 0 && (g.D % 4u) == 0 && (D.ref_off % 4u) == 0 && D.ref_off >= off_cb &&
-                 D.ref_off + 4ull * g.B <= total;
-    }
-    if (tid == 0) s_ok = ok;
-    if (tid < kLmaxLimit + 2) s_cl[tid] = 0;
+    const uint8_t* d = comp + kHeaderBytes + (uint64_t)kDirBytes * tl;
+    const uint32_t* d32 = reinterpret_cast<const uint32_t*>(d);
+    const uint64_t* d64 = reinterpret_cast<const uint64_t*>(d + 24);
+    uint32_t hw[12];
+#pragma unroll
+    for (int k = 0; k < 12; ++k) hw[k] = h[k];
+    uint64_t hq[7];
+#pragma unroll
+    for (int k = 0; k < 7; ++k) hq[k] = q[HQ_NOUT + k];
+    uint32_t dw[6];
+#pragma unroll
+    for (int k = 0; k < 6; ++k) dw[k] = d32[k];
+    const uint64_t d_cb = d64[0], d_ref = d64[1];
+    bool ok = hw[H_MAGIC] == kMagic && hw[H_VERSION] == kVersion && hw[H_DTYPE] == g.dtype && hw[H_T] == g.TD &&
+              hw[H_B] == g.B && hw[H_D] == g.D && hw[H_R] == g.R && hw[H_S] == g.S && hw[H_LMAX] == g.LMAX &&
+              hw[H_W] == kW && hw[H_V] == kV && hw[H_NG] == g.TD * g.G;
+    H.n_esc_total = hq[HQ_NOUT - HQ_NOUT];
+    H.words_total = hq[HQ_WORDS - HQ_NOUT];
+    const uint64_t off_cb = hq[HQ_OFF_CB - HQ_NOUT], total = hq[HQ_TOTAL - HQ_NOUT];
+    // (the code-length blocks are padded to four bytes and every table has one, so at least four bytes follow the
+    // payload section: the decode kernel may read the word at the payload's end)
+    ok = ok && total <= comp_bytes && hq[HQ_OFF_GROUP - HQ_NOUT] == F.off_group && hq[HQ_OFF_CHUNK - HQ_NOUT] == F.off_chunk &&
+         hq[HQ_OFF_PAYLOAD - HQ_NOUT] == F.off_payload && H.words_total <= 0xFFFFFFFFull &&
+         H.n_esc_total <= (uint64_t)g.n * g.TD;
+    ok = ok && off_cb == d_a16(F.off_payload + 4ull * H.words_total) && total >= off_cb && total - off_cb >= 4ull;
+    const float eb = __uint_as_float(dw[0]);
+    H.n_used = dw[1]; H.sym_lo = dw[2]; H.sym_hi = dw[3]; H.n_esc = dw[4];
+    H.cb = d_cb;
+    H.ref_off = d_ref;
+    H.ebx2 = eb * 2.0f;
+    ok = ok && eb > 0.f && eb < __builtin_inff() && dw[5] == g.G && H.sym_lo <= H.sym_hi && H.sym_hi < g.K &&
+         H.n_used >= 1 && H.n_used <= H.sym_hi - H.sym_lo + 1u && H.n_esc <= g.n;
+    ok = ok && H.cb >= off_cb && H.cb <= total && (uint64_t)(H.sym_hi - H.sym_lo + 1u) <= total - H.cb;
+    // row matching: references behind the code-length blocks (only a context made for it decodes them, and the
+    // kernels want a lane's four elements in one row)
+    if (H.ref_off != 0)
+        ok = ok && g.lz != 0 && (g.D % 4u) == 0 && (H.ref_off % 4u) == 0 && H.ref_off >= off_cb && H.ref_off <= total &&
+             4ull * g.B <= total - H.ref_off;
+    H.ok = ok;
+    return H;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Row matching only: one work-group per table checks that every reference points back, at a row that is coded,
+// and leaves the verdict (and where the references are) for the row-copy kernel.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_dec_refs(Geom g, FixedLayout F, const uint8_t* comp, uint64_t comp_bytes,
+                                                  DecTable* dtab, Ctrl* ctrl) {
+    __shared__ uint32_t s_ok;
+    const uint32_t tid = threadIdx.x, t = blockIdx.x;
+    const uint32_t dst = t / g.TD, tl = t - dst * g.TD;
+    comp += (uint64_t)dst * comp_bytes;
+    const DecHead H = dec_validate(g, F, comp, comp_bytes, tl);
+    if (tid == 0) s_ok = H.ok ? 1u : 0u;
     __syncthreads();
-    if (ok && D.ref_off != 0) {  // every reference points back, at a row that is coded
-        const uint32_t* ref = reinterpret_cast<const uint32_t*>(comp + D.ref_off);
+    if (H.ok && H.ref_off != 0) {
+        const uint32_t* ref = reinterpret_cast<const uint32_t*>(comp + H.ref_off);
         for (uint32_t r0 = tid; r0 < g.B; r0 += 256u * 4u) {  // four rows in flight per thread
             uint32_t o[4], oo[4];
 #pragma unroll
@@ -97,255 +105,414 @@ __global__ __launch_bounds__(256) void k_dec_prepare(Geom g, const uint8_t* comp
                 if (r0 + k * 256u < g.B && oo[k] != o[k]) s_ok = 0;  // (a reference forward left oo at "no row")
         }
     }
-    const uint32_t nl = ok ? sym_hi - sym_lo + 1u : 0u;
-    for (uint32_t i = tid; i < nl; i += 256) {
-        const uint32_t l = comp[cb + i];
-        s_len[i] = (uint8_t)l;
-        if (l > g.LMAX) s_ok = 0;
-        else if (l) atomicAdd(&s_cl[l], 1u);
-    }
-    __syncthreads();
-    const bool ok2 = s_ok != 0;  // every thread reads the same value, then nobody writes before the barrier
-    __syncthreads();
-    uint16_t* my_lut = lut + ((size_t)t << g.LMAX);
-    const uint32_t lut_n = 1u << g.LMAX;
-    if (ok2 && n_used == 1) {
-        if (tid == 0 && (sym_lo != sym_hi || s_len[0] != 0)) s_ok = 0;
-        for (uint32_t i = tid; i < lut_n; i += 256) my_lut[i] = (uint16_t)sym_lo;  // length 0
-    } else if (ok2) {
-        if (tid < 64) {
-            // first wavefront: every lane derives the same per-length tables, then the symbols are put in
-            // (length, symbol) order, 64 at a time: a symbol's place is the number of symbols of its length before it
-            const uint32_t lane = tid;
-            uint64_t kraft = 0;
-            uint32_t cnt = 0, code = 0, index = 0;
-            uint32_t fill[kLmaxLimit + 1];
-#pragma unroll
-            for (uint32_t l = 1; l <= (uint32_t)kLmaxLimit; ++l) {
-                const uint32_t c = l <= g.LMAX ? s_cl[l] : 0u;
-                kraft += l <= g.LMAX ? (uint64_t)c << (g.LMAX - l) : 0ull;
-                cnt += c;
-                code <<= 1;
-                if (lane == 0) { s_first[l] = code; s_index[l] = index; }
-                fill[l] = index;
-                code += c;
-                index += c;
-            }
-            if (kraft != (1ull << g.LMAX) || cnt != n_used) {
-                if (lane == 0) s_ok = 0;
-            } else {
-                const uint64_t below = (1ull << lane) - 1ull;
-                for (uint32_t base = 0; base < nl; base += 64) {
-                    const uint32_t i = base + lane;
-                    const uint32_t L = i < nl ? s_len[i] : 0u;
-#pragma unroll
-                    for (uint32_t l = 1; l <= (uint32_t)kLmaxLimit; ++l) {
-                        const uint64_t m = __ballot(L == l);
-                        if (L == l) s_sorted[fill[l] + (uint32_t)__popcll(m & below)] = (uint16_t)(sym_lo + i);
-                        fill[l] += (uint32_t)__popcll(m);
-                    }
-                }
-            }
-        }
-        __syncthreads();
-        const bool ok3 = s_ok != 0;
-        if (ok3) {
-            // the LMAX-bit string i starts with a codeword of length l iff i < limit[l] and not already
-            // i < limit[l-1]; the limits are the same for every thread (scalar registers)
-            uint32_t limit[kLmaxLimit + 1];
-#pragma unroll
-            for (uint32_t l = 1; l <= (uint32_t)kLmaxLimit; ++l)
-                limit[l] = l <= g.LMAX ? (s_first[l] + s_cl[l]) << (g.LMAX - l) : 0xFFFFFFFFu;
-            for (uint32_t i = tid; i < lut_n; i += 256) {
-                uint32_t l = 1;
-#pragma unroll
-                for (uint32_t k = 1; k < (uint32_t)kLmaxLimit; ++k) l += (i >= limit[k]) ? 1u : 0u;
-                const uint32_t c = i >> (g.LMAX - l);
-                my_lut[i] = (uint16_t)((l << 12) | s_sorted[s_index[l] + (c - s_first[l])]);
-            }
-        }
-    }
     __syncthreads();
     if (tid == 0) {
-        D.valid = s_ok;
+        DecTable D;
+        D.valid = s_ok; D.n_used = H.n_used; D.sym_lo = H.sym_lo; D.n_outliers = H.n_esc; D.ebx2 = H.ebx2; D.pad = 0;
+        D.ref_off = H.ref_off;
         dtab[t] = D;
         if (!s_ok) set_status(ctrl, DLC_ECORRUPT);
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// chunk-parallel decode: one wavefront per group, lane l walks chunk l.  Each lane keeps a 64-bit
-// window of its own bit stream, looks LMAX bits up in the table's LDS decode table, and the four
-// symbols of a turn leave as one 16-byte store (1 KiB contiguous per wavefront instruction).
+// chunk-parallel decode.  A work-group belongs to one table: it checks the container's header and the table's
+// directory entry, rebuilds the canonical code from the stored lengths into an LDS decode table, and then decodes
+// `iters` consecutive blocks of kDecWaves groups, one wavefront per group, lane l walking chunk l.  Each lane keeps
+// a 64-bit window of its own bit stream, looks LMAX bits up in the decode table, and the four symbols of a turn
+// leave as one 16-byte store (1 KiB contiguous per wavefront instruction).  Nothing is read from a table that fails
+// validation.
+//
+// A lane's symbols hang on one another (the next look-up needs the length of the code before it), so the time a
+// group takes is the length of that chain.  The decode table therefore answers for two codewords at a time:
+//   entry[i] = single << 31 | adv << 27 | (len1 - 1) << 24 | bin2 << 12 | bin1     for the LMAX-bit string i,
+// bin = symbol - R as a signed 12-bit number (what the reconstruction multiplies by 2 * bound); bin1: the codeword
+// that prefixes i, len1 its length; bin2: the codeword after it when both fit into the LMAX bits (and len1 <= 8:
+// three bits hold it), adv = len1 + len2 then.  Otherwise single = 1 and adv = len1: a second look-up follows,
+// rare for the short codes of frequent symbols.
 //
 // The bit stream words reach the lanes through LDS: every lane copies the next kWin words of its chunk
 // into column `lane` of a [kWin][64] staging array of its wavefront (bank = lane, so the lanes never
 // collide whatever word each of them is at) and refills its window from there.  The decode loop then
 // holds no global load, so nothing in it ever waits for memory: the stores just stream out.
+//
+// Per table the work-groups add up the escapes they have applied; the last one to finish compares the sum with the
+// directory entry (counters in the workspace, zero between calls).
 // ------------------------------------------------------------------------------------------------
-#ifndef DLC_DEC_WIN
-#define DLC_DEC_WIN 32
-#endif
-#ifndef DLC_DEC_WAVES
-#define DLC_DEC_WAVES 8
-#endif
-constexpr uint32_t kWin = DLC_DEC_WIN;            // staged words per lane
-constexpr uint32_t kDecWaves = DLC_DEC_WAVES;        // wavefronts per work-group
+constexpr uint32_t kWin = 30;                         // staged words per lane (two work-groups share a CU's LDS)
+constexpr uint32_t kDecWaves = 8;                     // wavefronts per work-group
+constexpr uint32_t kDecThreads = 64 * kDecWaves;
 constexpr uint32_t kSkipWords = 256 * kW / kV / 32;   // row matching: a bit per row of a group, rows of at least four elements
 
+struct DecScratch {  // lives in the staging area until the decode table is complete
+    uint32_t ok;
+    uint32_t cl[kLmaxLimit + 2], first[kLmaxLimit + 2], index[kLmaxLimit + 2];
+    uint16_t sorted[4096];
+    uint16_t one[1 << kLmaxLimit];  // len << 12 | symbol of the codeword that prefixes the LMAX-bit string i
+    uint8_t len[4096];
+};
+static_assert(sizeof(DecScratch) <= kDecWaves * kWin * kW * 4, "the scratch must fit the staging area it shares");
+
+// (len << 12 | symbol) of the codeword that prefixes the LMAX-bit string i: its length is one more than the number of
+// limits at or below i (limit[l] = first string that no codeword of length <= l prefixes)
+__device__ __forceinline__ uint32_t dec_first_code(const DecScratch& sc, const uint32_t (&limit)[kLmaxLimit + 1], uint32_t i,
+                                                   uint32_t LMAX) {
+    uint32_t l = 1;
+#pragma unroll
+    for (uint32_t k = 1; k < (uint32_t)kLmaxLimit; ++k) l += (i >= limit[k]) ? 1u : 0u;
+    const uint32_t c = i >> (LMAX - l);
+    return (l << 12) | sc.sorted[sc.index[l] + (c - sc.first[l])];
+}
+
 template <bool F16, bool VEC>
-__global__ __launch_bounds__(64 * DLC_DEC_WAVES) void k_decode(Geom g, const uint8_t* comp, const uint16_t* lut, const DecLayout* dlay,
-                                                const DecTable* dtab, Ctrl* ctrl, void* outp, uint32_t bpt, uint64_t comp_stride) {
-    extern __shared__ __align__(16) uint16_t s_lut[];  // [1 << LMAX] decode table, then kDecWaves staging arrays
+__global__ __launch_bounds__(kDecThreads) void k_decode(Geom g, FixedLayout F, const uint8_t* comp, uint64_t comp_bytes,
+                                                        Ctrl* ctrl, void* outp, uint32_t wpt, uint32_t iters,
+                                                        uint32_t* esc_seen, uint32_t* arrived) {
+    extern __shared__ __align__(16) uint32_t s_lut[];  // [1 << LMAX] decode table, then kDecWaves staging arrays
+    __shared__ uint32_t s_bad;
+    __shared__ unsigned long long s_sum[kDecWaves];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t t = blockIdx.x / bpt, b = blockIdx.x % bpt;
+    const uint32_t t = blockIdx.x / wpt, b = blockIdx.x % wpt;
     const uint32_t dst = t / g.TD, tl = t - dst * g.TD;  // the container this table is in, and its place there
-    comp += (uint64_t)dst * comp_stride;
-    const DecLayout L = dlay[dst];
-    const DecTable D = dtab[t];
-    if (!L.valid || !D.valid) return;  // uniform over the work-group
+    comp += (uint64_t)dst * comp_bytes;
     const uint32_t lut_n = 1u << g.LMAX;
-    {
-        const uint4* src = reinterpret_cast<const uint4*>(lut + ((size_t)t << g.LMAX));
-        uint4* dst = reinterpret_cast<uint4*>(s_lut);
-        for (uint32_t i = tid; i < lut_n / 8; i += 64 * kDecWaves) dst[i] = src[i];
+    DecScratch& sc = *reinterpret_cast<DecScratch*>(s_lut + lut_n);
+    const uint32_t* const goffs = reinterpret_cast<const uint32_t*>(comp + F.off_group);
+    const uint32_t n_groups = g.TD * g.G;
+    // What a group's decoding starts from sits in the sections whose place the geometry fixes (the host has made
+    // sure they lie inside comp_bytes): the loads of the first group go out before anything else is known.
+    struct GroupHead { uint32_t cw, goff, gnext; };
+    auto group_head = [&](uint32_t grp) {
+        GroupHead h;
+        const uint32_t gid = tl * g.G + grp;  // group number inside the container
+        h.cw = comp[F.off_chunk + (uint64_t)gid * kW + lane];
+        h.goff = goffs[gid];
+        h.gnext = gid + 1 < n_groups ? goffs[gid + 1] : 0xFFFFFFFFu;  // (the last group ends where the payload does)
+        return h;
+    };
+    const uint32_t grp_first = b * iters * kDecWaves + wave;
+    GroupHead gh;
+    gh.cw = 0; gh.goff = 0; gh.gnext = 0;
+    if (grp_first < g.G) gh = group_head(grp_first);
+    const DecHead H = dec_validate(g, F, comp, comp_bytes, tl);
+    if (tid == 0) { sc.ok = H.ok ? 1u : 0u; s_bad = 0u; }
+    if (tid < kLmaxLimit + 2) sc.cl[tid] = 0;
+    __syncthreads();
+    const uint32_t nl = H.ok ? H.sym_hi - H.sym_lo + 1u : 0u;
+    for (uint32_t i = tid; i < nl; i += kDecThreads) {
+        const uint32_t l = comp[H.cb + i];
+        sc.len[i] = (uint8_t)l;
+        if (l > g.LMAX) sc.ok = 0;
+        else if (l) atomicAdd(&sc.cl[l], 1u);
+    }
+    // One group of a wavefront: its words (the chunks', then two per escape) checked against the container, then the
+    // lanes' next kWin chunk words fetched into registers.  Branch-free, all loads in flight together: an index past
+    // the chunk's end reads its last word instead (an empty chunk reads the word at its position, which still lies
+    // inside the container: code-length blocks follow the payload) and is masked to zero when it goes to LDS.
+    struct GroupPlace { bool ok; uint32_t n_esc, total; const uint32_t* chunk; };
+    auto group_place = [&](const GroupHead& h) {
+        GroupPlace P;
+        const uint32_t incl = wave_incl_scan(h.cw, lane);
+        P.total = __shfl(incl, 63, 64);
+        const uint64_t gend = h.gnext == 0xFFFFFFFFu ? H.words_total : (uint64_t)h.gnext;
+        P.ok = !(gend > H.words_total || (uint64_t)h.goff + P.total > gend || ((gend - h.goff - P.total) & 1ull));
+        P.n_esc = P.ok ? (uint32_t)((gend - h.goff - P.total) >> 1) : 0u;
+        P.chunk = reinterpret_cast<const uint32_t*>(comp + F.off_payload) + h.goff + (incl - h.cw);
+        return P;
+    };
+    auto fetch_words = [&](const uint32_t* chunk, uint32_t cw, uint32_t from, uint32_t (&w)[kWin]) {
+        const uint32_t last = cw ? cw - 1u : 0u;
+#pragma unroll
+        for (uint32_t k = 0; k < kWin; ++k) w[k] = chunk[min(from + k, last)];
+    };
+    uint32_t* const stage = reinterpret_cast<uint32_t*>(s_lut + lut_n) + wave * (kWin * kW) + lane;  // my column
+    auto put_words = [&](uint32_t cw, uint32_t from, const uint32_t (&w)[kWin]) {
+#pragma unroll
+        for (uint32_t k = 0; k < kWin; ++k) stage[k * kW] = from + k < cw ? w[k] : 0u;
+    };
+    // the first group's words are on their way while the decode table is made
+    GroupPlace gp;
+    gp.ok = false; gp.n_esc = 0; gp.total = 0; gp.chunk = nullptr;
+    uint32_t w_first[kWin];
+#pragma unroll
+    for (uint32_t k = 0; k < kWin; ++k) w_first[k] = 0;
+    if (H.ok && grp_first < g.G) {
+        gp = group_place(gh);
+        if (gp.ok) fetch_words(gp.chunk, gh.cw, 0, w_first);
+    }
+    // the container as a whole: its escapes are those of its tables (first work-group of the container)
+    if (H.ok && tl == 0 && b == 0) {
+        uint32_t part = 0;
+        bool big = false;
+        for (uint32_t k = tid; k < g.TD; k += kDecThreads) {
+            const uint32_t e = reinterpret_cast<const uint32_t*>(comp + kHeaderBytes + (uint64_t)kDirBytes * k)[4];
+            big = big || e > g.n;
+            part += e > g.n ? 0u : e;
+        }
+        // (32-bit partial sums per thread cannot wrap: a thread adds at most TD / 512 counts of less than 2^31 each,
+        // and TD * n < 2^32 positions in all; across threads they are added as 64-bit values)
+        unsigned long long sum = part;
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+        if (lane == 0) s_sum[wave] = sum;
+        __syncthreads();
+        if (tid == 0) {
+            unsigned long long all = 0;
+            for (uint32_t k = 0; k < kDecWaves; ++k) all += s_sum[k];
+            if (all != H.n_esc_total) s_bad = 1u;
+        }
+        if (big) s_bad = 1u;
     }
     __syncthreads();
-    const uint32_t grp = b * kDecWaves + wave;
-    if (grp >= g.G) return;  // whole wavefront; no barrier follows
-    uint32_t* stage = reinterpret_cast<uint32_t*>(s_lut + lut_n) + wave * (kWin * kW) + lane;  // my column
-    const uint32_t gid = tl * g.G + grp;  // group number inside the container
-    const uint32_t cw = comp[L.off_chunk + (uint64_t)gid * kW + lane];
-    const uint32_t incl = wave_incl_scan(cw, lane);
-    const uint32_t total = __shfl(incl, 63, 64);
-    const uint32_t* goffs = reinterpret_cast<const uint32_t*>(comp + L.off_group);
-    const uint64_t goff = goffs[gid];
-    const uint64_t gend = gid + 1 < g.TD * g.G ? (uint64_t)goffs[gid + 1] : L.words_total;
-    // the group's words: its chunks, then two words per escape
-    if (gend > L.words_total || goff + total > gend || ((gend - goff - total) & 1ull)) {
-        if (lane == 0) set_status(ctrl, DLC_ECORRUPT);
-        return;
-    }
-    const uint32_t n_esc = (uint32_t)((gend - goff - total) >> 1);
-    const uint32_t* chunk = reinterpret_cast<const uint32_t*>(comp + L.off_payload) + goff + (incl - cw);
-    uint32_t taken = 0;   // words of the chunk already moved into buf
-    uint32_t wbase = 0;   // chunk word index of staging row 0
-    // stage words [wbase, wbase + kWin) of my chunk (zero past its end).  Branch-free, all loads in flight
-    // together: an index past the end reads the chunk's last word instead (an empty chunk reads the word at
-    // its position, which still lies inside the container: code-length blocks follow the payload) and is
-    // masked to zero.
-    const uint32_t last = cw ? cw - 1u : 0u;
-    auto restage = [&]() {
-        wbase = taken;
-        uint32_t w[kWin];
+    const bool ok2 = sc.ok != 0;  // every thread reads the same value, then nobody writes before the barrier
+    __syncthreads();
+    if (ok2 && H.n_used == 1) {
+        if (tid == 0 && (H.sym_lo != H.sym_hi || sc.len[0] != 0)) sc.ok = 0;
+        // length 0: every look-up gives one symbol and moves on by nothing
+        for (uint32_t i = tid; i < lut_n; i += kDecThreads) s_lut[i] = 0x80000000u | ((H.sym_lo - g.R) & 0xFFFu);
+    } else if (ok2) {
+        if (wave == 0) {
+            // first wavefront: every lane derives the same per-length tables, then the symbols are put in
+            // (length, symbol) order, 64 at a time: a symbol's place is the number of symbols of its length before it
+            uint64_t kraft = 0;
+            uint32_t cnt = 0, code = 0, index = 0;
+            uint32_t fill[kLmaxLimit + 1];
 #pragma unroll
-        for (uint32_t k = 0; k < kWin; ++k) w[k] = chunk[min(wbase + k, last)];
-#pragma unroll
-        for (uint32_t k = 0; k < kWin; ++k) stage[k * kW] = wbase + k < cw ? w[k] : 0u;
-    };
-    restage();
-    uint64_t buf = ((uint64_t)stage[0] << 32) | stage[kW];
-    taken = 2;
-    uint32_t nb = 64;  // bits of buf in use (bits past the end of the chunk read as zero)
-    const float ebx2 = D.ebx2;
-    const int R = (int)g.R;
-    const uint32_t shift = 64u - g.LMAX;
-    uint8_t* tab = static_cast<uint8_t*>(outp) + (size_t)t * g.n * g.es;
-    const uint32_t base = grp * (kW * g.S) + lane * kV;
-    const uint32_t turns = g.S / kV;
-    // row matching: which rows of this group refer to another row, as a bit per row in LDS (at most 64*S/4 rows)
-    const uint32_t* const ref = D.ref_off ? reinterpret_cast<const uint32_t*>(comp + D.ref_off) : nullptr;
-    uint32_t* const skipbits = reinterpret_cast<uint32_t*>(s_lut + lut_n) + kDecWaves * (kWin * kW) + wave * kSkipWords;
-    const uint32_t row_lo = (grp * (kW * g.S)) / g.D;
-    if (ref != nullptr) {
-        const uint32_t last_el = min(g.n, (grp + 1u) * (kW * g.S)) - 1u;
-        const uint32_t n_rows = last_el / g.D - row_lo + 1u;  // <= 64*S/4 because dim % 4 == 0 here
-        for (uint32_t r0 = 0; r0 < n_rows; r0 += 64) {  // uniform trip count
-            const uint32_t r = r0 + lane;
-            const bool refers = r < n_rows && ref[row_lo + r] != row_lo + r;
-            const uint64_t m = __ballot(refers);
-            if (lane == 0) { skipbits[r0 / 32u] = (uint32_t)m; skipbits[r0 / 32u + 1u] = (uint32_t)(m >> 32); }
-        }
-        __builtin_amdgcn_wave_barrier();
-    }
-    for (uint32_t j = 0; j < turns; ++j) {
-        const uint32_t idx = base + j * (kW * kV);
-        // a turn takes at most two more words; restage (whole wavefront) when a lane could run off its rows
-        if (__ballot(taken + 2u > wbase + kWin && taken < cw) != 0ull) restage();
-        bool coded = idx < g.n;
-        if (ref != nullptr && coded) {  // a row that refers to another has no bits in the stream; it is copied afterwards
-            const uint32_t r = idx / g.D - row_lo;
-            coded = ((skipbits[r >> 5] >> (r & 31u)) & 1u) == 0u;
-        }
-        if (coded) {
-            float v4[4];
-#pragma unroll
-            for (int h2 = 0; h2 < 2; ++h2) {
-                if (nb <= 32u) {
-                    const uint32_t k = taken - wbase;  // < kWin by the restage rule (rows past the chunk's end are zero)
-                    buf |= (uint64_t)stage[(k < kWin ? k : kWin - 1u) * kW] << (32u - nb);
-                    nb += 32u;
-                    ++taken;
-                }
-#pragma unroll
-                for (int v = 0; v < 2; ++v) {
-                    const uint32_t e = s_lut[(uint32_t)(buf >> shift)];
-                    const uint32_t len = e >> 12;
-                    buf <<= len;
-                    nb -= len;
-                    v4[h2 * 2 + v] = (float)((int)(e & 0xFFFu) - R) * ebx2;
-                }
+            for (uint32_t l = 1; l <= (uint32_t)kLmaxLimit; ++l) {
+                const uint32_t c = l <= g.LMAX ? sc.cl[l] : 0u;
+                kraft += l <= g.LMAX ? (uint64_t)c << (g.LMAX - l) : 0ull;
+                cnt += c;
+                code <<= 1;
+                if (lane == 0) { sc.first[l] = code; sc.index[l] = index; }
+                fill[l] = index;
+                code += c;
+                index += c;
             }
-            // streaming stores: the output is written once and is larger than the caches
-            if constexpr (VEC) {
-                if constexpr (F16) {
-                    typedef uint32_t u2v __attribute__((ext_vector_type(2)));
-                    u2v o;
-                    o.x = (uint32_t)__half_as_ushort(half_rne(v4[0])) |
-                          ((uint32_t)__half_as_ushort(half_rne(v4[1])) << 16);
-                    o.y = (uint32_t)__half_as_ushort(half_rne(v4[2])) |
-                          ((uint32_t)__half_as_ushort(half_rne(v4[3])) << 16);
-                    __builtin_nontemporal_store(o, reinterpret_cast<u2v*>(reinterpret_cast<uint16_t*>(tab) + idx));
-                } else {
-                    typedef float f4v __attribute__((ext_vector_type(4)));
-                    f4v o4 = {v4[0], v4[1], v4[2], v4[3]};
-                    __builtin_nontemporal_store(o4, reinterpret_cast<f4v*>(reinterpret_cast<float*>(tab) + idx));
-                }
+            if (kraft != (1ull << g.LMAX) || cnt != H.n_used) {
+                if (lane == 0) sc.ok = 0;
             } else {
+                const uint64_t below = (1ull << lane) - 1ull;
+                for (uint32_t base = 0; base < nl; base += 64) {
+                    const uint32_t i = base + lane;
+                    const uint32_t L = i < nl ? sc.len[i] : 0u;
 #pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (idx + v < g.n) {
-                        if constexpr (F16) reinterpret_cast<__half*>(tab)[idx + v] = half_rne(v4[v]);
-                        else reinterpret_cast<float*>(tab)[idx + v] = v4[v];
+                    for (uint32_t l = 1; l <= (uint32_t)kLmaxLimit; ++l) {
+                        const uint64_t m = __ballot(L == l);
+                        if (L == l) sc.sorted[fill[l] + (uint32_t)__popcll(m & below)] = (uint16_t)(H.sym_lo + i);
+                        fill[l] += (uint32_t)__popcll(m);
                     }
+                }
+            }
+        }
+        __syncthreads();
+        if (sc.ok != 0) {
+            // the LMAX-bit string i starts with a codeword of length l iff i < limit[l] and not already
+            // i < limit[l-1]; the limits are the same for every thread (scalar registers).  A thread fills eight
+            // strings in a row: all of them start with one codeword when they agree down to its last bit, which for
+            // the short codes that cover most of the table is the rule.
+            uint32_t limit[kLmaxLimit + 1];
+#pragma unroll
+            for (uint32_t l = 1; l <= (uint32_t)kLmaxLimit; ++l)
+                limit[l] = l <= g.LMAX ? (sc.first[l] + sc.cl[l]) << (g.LMAX - l) : 0xFFFFFFFFu;
+            for (uint32_t i0 = tid * 8u; i0 < lut_n; i0 += kDecThreads * 8u) {  // (lut_n >= 16: a multiple of 8)
+                const uint32_t ea = dec_first_code(sc, limit, i0, g.LMAX), la = ea >> 12;
+                uint32_t e[8];
+                if (g.LMAX - la >= 3u) {
+#pragma unroll
+                    for (uint32_t k = 0; k < 8; ++k) e[k] = ea;
+                } else {
+                    e[0] = ea;
+#pragma unroll
+                    for (uint32_t k = 1; k < 8; ++k) e[k] = dec_first_code(sc, limit, i0 + k, g.LMAX);
+                }
+                uint4 v;
+                v.x = e[0] | (e[1] << 16); v.y = e[2] | (e[3] << 16); v.z = e[4] | (e[5] << 16); v.w = e[6] | (e[7] << 16);
+                *reinterpret_cast<uint4*>(&sc.one[i0]) = v;
+            }
+            __syncthreads();  // (uniform: sc.ok was read after a barrier and nothing has written it since)
+            for (uint32_t i = tid; i < lut_n; i += kDecThreads) {
+                const uint32_t e1 = sc.one[i], l1 = e1 >> 12;
+                const uint32_t e2 = sc.one[(i << l1) & (lut_n - 1u)], l2 = e2 >> 12;  // what follows the first codeword
+                const bool both = l1 + l2 <= g.LMAX && l1 <= 8u;  // the second codeword lies inside the LMAX bits too
+                const uint32_t q1 = ((e1 & 0xFFFu) - g.R) & 0xFFFu, q2 = ((e2 & 0xFFFu) - g.R) & 0xFFFu;
+                s_lut[i] = both ? ((l1 + l2) << 27) | ((l1 - 1u) << 24) | (q2 << 12) | q1 : 0x80000000u | (l1 << 27) | q1;
             }
         }
     }
-    if (n_esc != 0u) {  // uniform over the wavefront: verbatim values over the decoded placeholders
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_s_waitcnt(0);  // the wavefront's own stores above are out before the overwrites below
-        const uint32_t* rec = reinterpret_cast<const uint32_t*>(comp + L.off_payload) + goff + total;
-        const uint32_t lo = grp * (kW * g.S);
-        const uint32_t hi = min(g.n, lo + kW * g.S);
-        for (uint32_t r = lane; r < n_esc; r += 64) {
-            const uint32_t idx = rec[2u * r], raw = rec[2u * r + 1];
-            if (idx < lo || idx >= hi) { set_status(ctrl, DLC_ECORRUPT); continue; }
-            if constexpr (F16) reinterpret_cast<uint16_t*>(tab)[idx] = (uint16_t)raw;
-            else reinterpret_cast<uint32_t*>(tab)[idx] = raw;
+    __syncthreads();
+    const bool valid = sc.ok != 0;
+    __syncthreads();  // the scratch is staging memory from here on
+    uint32_t my_esc = 0;   // escapes this wavefront has applied (uniform)
+    bool bad = false;      // something in this wavefront's groups does not add up
+    if (valid) {
+        const float ebx2 = H.ebx2;
+        const uint32_t lshift = 32u - g.LMAX;
+        uint8_t* tab = static_cast<uint8_t*>(outp) + (size_t)t * g.n * g.es;
+        const uint32_t turns = g.S / kV;
+        const uint32_t* const ref = H.ref_off ? reinterpret_cast<const uint32_t*>(comp + H.ref_off) : nullptr;
+        uint32_t* const skipbits = reinterpret_cast<uint32_t*>(s_lut + lut_n) + kDecWaves * (kWin * kW) + wave * kSkipWords;
+        for (uint32_t it = 0; it < iters; ++it) {
+            const uint32_t grp = grp_first + it * kDecWaves;
+            if (grp >= g.G) break;  // whole wavefront
+            // A lane's place in its bit stream: the two words w0, w1 it is decoding from, `c` bits of w0 already used
+            // (0..31), the word after them in `nxt`, fetched ahead from the staging rows; kr = staging row of `nxt`,
+            // wbase = chunk word index of staging row 0.
+            uint32_t wbase = 0, kr = 0;
+            if (it == 0) {
+                if (gp.ok) put_words(gh.cw, 0, w_first);
+            } else {
+                gh = group_head(grp);
+                gp = group_place(gh);
+                if (gp.ok) {
+                    uint32_t w[kWin];
+                    fetch_words(gp.chunk, gh.cw, 0, w);
+                    put_words(gh.cw, 0, w);
+                }
+            }
+            if (!gp.ok) {
+                bad = true;
+                continue;
+            }
+            const uint32_t cw = gh.cw, n_esc = gp.n_esc, total = gp.total;
+            const uint32_t* const chunk = gp.chunk;
+            // the words from `nxt` on, anew, so that `nxt` is row 0
+            auto restage = [&]() {
+                wbase += kr;
+                kr = 0;
+                uint32_t w[kWin];
+                fetch_words(chunk, cw, wbase, w);
+                put_words(cw, wbase, w);
+            };
+            uint32_t w0 = stage[0], w1 = stage[kW], nxt = stage[2u * kW], c = 0;
+            kr = 2;
+            const uint32_t base = grp * (kW * g.S) + lane * kV;
+            // row matching: which rows of this group refer to another row, as a bit per row in LDS (at most 64*S/4 rows)
+            const uint32_t row_lo = (grp * (kW * g.S)) / g.D;
+            if (ref != nullptr) {
+                const uint32_t last_el = min(g.n, (grp + 1u) * (kW * g.S)) - 1u;
+                const uint32_t n_rows = last_el / g.D - row_lo + 1u;  // <= 64*S/4 because dim % 4 == 0 here
+                for (uint32_t r0 = 0; r0 < n_rows; r0 += 64) {  // uniform trip count
+                    const uint32_t r = r0 + lane;
+                    const bool refers = r < n_rows && ref[row_lo + r] != row_lo + r;
+                    const uint64_t m = __ballot(refers);
+                    if (lane == 0) { skipbits[r0 / 32u] = (uint32_t)m; skipbits[r0 / 32u + 1u] = (uint32_t)(m >> 32); }
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+            for (uint32_t j = 0; j < turns; ++j) {
+                const uint32_t idx = base + j * (kW * kV);
+                // a turn moves at most two more words; restage (whole wavefront) when a lane that still has words to
+                // fetch could run off its rows
+                if (__ballot(kr + 2u >= kWin && wbase + kr + 1u < cw) != 0ull) restage();
+                bool coded = idx < g.n;
+                if (ref != nullptr && coded) {  // a row that refers to another has no bits in the stream; it is copied afterwards
+                    const uint32_t r = idx / g.D - row_lo;
+                    coded = ((skipbits[r >> 5] >> (r & 31u)) & 1u) == 0u;
+                }
+                if (coded) {
+                    float v4[4];
+#pragma unroll
+                    for (int h2 = 0; h2 < 2; ++h2) {
+                        const uint64_t win = (((uint64_t)w0 << 32) | w1) << c;  // the stream from the lane's place on
+                        const uint32_t e = s_lut[(uint32_t)(win >> 32) >> lshift];
+                        uint32_t adv = (e >> 27) & 15u;
+                        int q2 = (int)(e << 8) >> 20;
+                        if (__ballot((int)e < 0) != 0ull) {  // an entry that answers for one codeword only: the next one by a look-up of its own
+                            const uint32_t e2 = s_lut[(uint32_t)((win << adv) >> 32) >> lshift];
+                            if ((int)e < 0) {
+                                q2 = (int)(e2 << 20) >> 20;
+                                adv += (int)e2 < 0 ? (e2 >> 27) & 15u : ((e2 >> 24) & 7u) + 1u;
+                            }
+                        }
+                        if constexpr (!VEC) {  // a turn can reach past the table's end: such a position has no bits
+                            if (idx + (uint32_t)(h2 * 2) + 1u >= g.n) {
+                                const uint32_t l1 = (int)e < 0 ? (e >> 27) & 15u : ((e >> 24) & 7u) + 1u;
+                                adv = idx + (uint32_t)(h2 * 2) < g.n ? l1 : 0u;
+                            }
+                        }
+                        c += adv;
+                        // past the end of w0: move on by a word (the row after `nxt` is read whether or not: same value then)
+                        const bool step = c > 31u;
+                        w0 = step ? w1 : w0;
+                        w1 = step ? nxt : w1;
+                        c &= 31u;
+                        kr += step ? 1u : 0u;
+                        nxt = stage[min(kr, kWin - 1u) * kW];  // (rows past the chunk's end are zero)
+                        v4[h2 * 2] = (float)((int)(e << 20) >> 20) * ebx2;
+                        v4[h2 * 2 + 1] = (float)q2 * ebx2;
+                    }
+                    // streaming stores: the output is written once and is larger than the caches
+                    if constexpr (VEC) {
+                        if constexpr (F16) {
+                            typedef uint32_t u2v __attribute__((ext_vector_type(2)));
+                            u2v o;
+                            o.x = (uint32_t)__half_as_ushort(half_rne(v4[0])) |
+                                  ((uint32_t)__half_as_ushort(half_rne(v4[1])) << 16);
+                            o.y = (uint32_t)__half_as_ushort(half_rne(v4[2])) |
+                                  ((uint32_t)__half_as_ushort(half_rne(v4[3])) << 16);
+                            __builtin_nontemporal_store(o, reinterpret_cast<u2v*>(reinterpret_cast<uint16_t*>(tab) + idx));
+                        } else {
+                            typedef float f4v __attribute__((ext_vector_type(4)));
+                            f4v o4 = {v4[0], v4[1], v4[2], v4[3]};
+                            __builtin_nontemporal_store(o4, reinterpret_cast<f4v*>(reinterpret_cast<float*>(tab) + idx));
+                        }
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            if (idx + v < g.n) {
+                                if constexpr (F16) reinterpret_cast<__half*>(tab)[idx + v] = half_rne(v4[v]);
+                                else reinterpret_cast<float*>(tab)[idx + v] = v4[v];
+                            }
+                    }
+                }
+            }
+            // a chunk's codewords end inside its words: w0 is chunk word wbase + kr - 2, and c of its bits are used
+            if (__ballot(32u * (wbase + kr - 2u) + c > 32u * cw) != 0ull) bad = true;
+            if (n_esc != 0u) {  // uniform over the wavefront: verbatim values over the decoded placeholders
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_s_waitcnt(0);  // the wavefront's own stores above are out before the overwrites below
+                const uint32_t* rec = reinterpret_cast<const uint32_t*>(comp + F.off_payload) + gh.goff + total;
+                const uint32_t lo = grp * (kW * g.S);
+                const uint32_t hi = min(g.n, lo + kW * g.S);
+                bool off_range = false;
+                for (uint32_t r = lane; r < n_esc; r += 64) {
+                    const uint32_t idx = rec[2u * r], raw = rec[2u * r + 1];
+                    if (idx < lo || idx >= hi) { off_range = true; continue; }
+                    if constexpr (F16) reinterpret_cast<uint16_t*>(tab)[idx] = (uint16_t)raw;
+                    else reinterpret_cast<uint32_t*>(tab)[idx] = raw;
+                }
+                if (__ballot(off_range) != 0ull) bad = true;
+                my_esc += n_esc;
+            }
         }
+        if (my_esc != 0u && lane == 0) {
+            __hip_atomic_fetch_add(&esc_seen[t], my_esc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // counted before the work-group says it is done
+        }
+    }
+    if (bad && lane == 0) s_bad = 1u;
+    __syncthreads();
+    if (tid == 0) {
+        bool corrupt = !valid || s_bad != 0u;
+        // the last work-group of the table: all escapes of the table have been seen
+        if (__hip_atomic_fetch_add(&arrived[t], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u == wpt) {
+            const uint32_t seen = __hip_atomic_exchange(&esc_seen[t], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&arrived[t], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (valid && seen != H.n_esc) corrupt = true;
+        }
+        if (corrupt) set_status(ctrl, DLC_ECORRUPT);
     }
 }
 
 // rows that refer to an earlier row of their table: copies of that row's reconstruction (after the decode kernel).
 // A thread per 16-byte (fp32) / 8-byte (fp16) piece of a row, pieces of a row on neighbouring threads.
 template <typename U>
-__global__ __launch_bounds__(256) void k_row_copy(Geom g, const uint8_t* comp, uint64_t comp_bytes, const DecLayout* dlay,
-                                                  const DecTable* dtab, void* outp) {
+__global__ __launch_bounds__(256) void k_row_copy(Geom g, const uint8_t* comp, uint64_t comp_bytes, const DecTable* dtab,
+                                                  void* outp) {
     const uint32_t t = blockIdx.y;
     const uint32_t dst = t / g.TD;  // the container this table is in
     comp += (uint64_t)dst * comp_bytes;
     const DecTable D = dtab[t];
-    if (!dlay[dst].valid || !D.valid || D.ref_off == 0) return;  // uniform
+    if (!D.valid || D.ref_off == 0) return;  // uniform
     const uint32_t* ref = reinterpret_cast<const uint32_t*>(comp + D.ref_off);
     U* tab = reinterpret_cast<U*>(static_cast<uint8_t*>(outp) + (size_t)t * g.n * g.es);
     const uint32_t upr = g.D / 4u;  // pieces per row (four elements each; dim % 4 == 0)
@@ -377,22 +544,27 @@ __global__ __launch_bounds__(256) void k_row_copy(Geom g, const uint8_t* comp, u
 hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_bytes, void* out, const Ws& w, int pl,
                              void* prof, hipStream_t s) {
     const bool f16 = g.dtype == DLC_F16;
-    if (prof_on(pl, P_DEC_PREPARE)) prof_begin(prof, P_DEC_PREPARE, s);
-    hipLaunchKernelGGL(k_dec_prepare, dim3(g.T), dim3(256), 0, s, g, comp, comp_bytes, w.lut, w.dlay, w.dtab, w.ctrl);
-    if (prof_on(pl, P_DEC_PREPARE)) prof_end(prof, P_DEC_PREPARE, s);
+    const FixedLayout F = fixed_layout(g);
+    if (g.lz)  // before the decode kernel: the row-copy kernel follows the references only where they were checked
+        hipLaunchKernelGGL(k_dec_refs, dim3(g.T), dim3(256), 0, s, g, F, comp, comp_bytes, w.dtab, w.ctrl);
     {
+        // a work-group decodes `iters` blocks of kDecWaves groups of one table: enough blocks to spread the cost of
+        // its decode table, enough work-groups (a few thousand) to fill the chip whatever the shape
         const uint32_t bpt = (g.G + kDecWaves - 1) / kDecWaves;
-        dim3 grid(g.T * bpt), block(64 * kDecWaves);
-        const size_t sm = ((size_t)2 << g.LMAX) + (size_t)kDecWaves * kWin * kW * 4 + (g.lz ? (size_t)kDecWaves * kSkipWords * 4 : 0);
+        const uint64_t blocks = (uint64_t)g.T * bpt;
+        const uint32_t iters = (uint32_t)std::min<uint64_t>(4, std::max<uint64_t>(1, blocks / 2048));
+        const uint32_t wpt = (bpt + iters - 1) / iters;  // work-groups per table
+        dim3 grid(g.T * wpt), block(kDecThreads);
+        const size_t sm = ((size_t)4 << g.LMAX) + (size_t)kDecWaves * kWin * kW * 4 + (g.lz ? (size_t)kDecWaves * kSkipWords * 4 : 0);
         if (prof_on(pl, P_DECODE)) prof_begin(prof, P_DECODE, s);
-#define DLC_DEC(F, V) hipLaunchKernelGGL((k_decode<F, V>), grid, block, sm, s, g, comp, w.lut, w.dlay, w.dtab, w.ctrl, out, bpt, (uint64_t)comp_bytes)
+#define DLC_DEC(FF, V) hipLaunchKernelGGL((k_decode<FF, V>), grid, block, sm, s, g, F, comp, (uint64_t)comp_bytes, w.ctrl, out, wpt, iters, w.dec_esc, w.dec_arrive)
         if (f16) { if (g.vec) DLC_DEC(true, true); else DLC_DEC(true, false); }
         else { if (g.vec) DLC_DEC(false, true); else DLC_DEC(false, false); }
 #undef DLC_DEC
         if (g.lz) {
             const uint32_t bx = std::min<uint32_t>((g.B * (g.D / 4u) + 255u) / 256u, 256u);
-            if (f16) hipLaunchKernelGGL(k_row_copy<uint2>, dim3(bx, g.T), dim3(256), 0, s, g, comp, (uint64_t)comp_bytes, w.dlay, w.dtab, out);
-            else hipLaunchKernelGGL(k_row_copy<uint4>, dim3(bx, g.T), dim3(256), 0, s, g, comp, (uint64_t)comp_bytes, w.dlay, w.dtab, out);
+            if (f16) hipLaunchKernelGGL(k_row_copy<uint2>, dim3(bx, g.T), dim3(256), 0, s, g, comp, (uint64_t)comp_bytes, w.dtab, out);
+            else hipLaunchKernelGGL(k_row_copy<uint4>, dim3(bx, g.T), dim3(256), 0, s, g, comp, (uint64_t)comp_bytes, w.dtab, out);
         }
         if (prof_on(pl, P_DECODE)) prof_end(prof, P_DECODE, s);
     }
@@ -400,7 +572,7 @@ hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_b
 }
 
 hipError_t decompress_set_attributes() {
-    const int bytes = (2 << kLmaxLimit) + (int)(kDecWaves * kWin * kW * 4) + (int)(kDecWaves * kSkipWords * 4);
+    const int bytes = (4 << kLmaxLimit) + (int)(kDecWaves * kWin * kW * 4) + (int)(kDecWaves * kSkipWords * 4);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_decode<false, false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e == hipSuccess)

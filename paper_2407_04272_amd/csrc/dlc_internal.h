@@ -73,12 +73,6 @@ struct Ctrl {
 // concerned: other destinations' containers stay valid); an internal wait ran out (nothing of the call is valid)
 constexpr uint32_t kAbortCapacity = 1, kAbortInternal = 2;
 
-struct DecLayout {
-    uint32_t valid;
-    uint32_t pad;
-    uint64_t off_group, off_chunk, off_payload, words_total;
-};
-
 struct DecTable {
     uint32_t valid, n_used, sym_lo, n_outliers;
     float ebx2;
@@ -242,9 +236,9 @@ struct Ws {
     uint32_t* rm_mult = nullptr;   // [D/4][8] multipliers of the row hash
     uint32_t carry = 0;            // 1: the codebook is carried from call to call (single-pass path)
     // decompress
-    uint16_t* lut = nullptr;       // [T][1 << LMAX]  len << 12 | symbol
-    DecLayout* dlay = nullptr;
-    DecTable* dtab = nullptr;      // [T]
+    DecTable* dtab = nullptr;      // [T] row matching: what the reference check found
+    uint32_t* dec_esc = nullptr;   // [T] escapes the decode kernel has applied; zero between calls
+    uint32_t* dec_arrive = nullptr;  // [T] work-groups of the decode kernel that are done with the table; zero between calls
     // statistics (allocated on first use)
     uint8_t* stats_base = nullptr;
     size_t stats_bytes = 0;
@@ -259,7 +253,7 @@ struct Ws {
 // profiling hooks used by the launchers (implemented in dlc_api.hip)
 void prof_begin(void* prof, int slot, hipStream_t s);
 void prof_end(void* prof, int slot, hipStream_t s);
-enum ProfSlot { P_HIST = 0, P_CODEBOOK, P_ENCODE, P_FINALIZE, P_DEC_PREPARE, P_DECODE, P_FUSED, P_CARRY, P_NSLOTS };
+enum ProfSlot { P_HIST = 0, P_CODEBOOK, P_ENCODE, P_FINALIZE, P_DECODE, P_FUSED, P_CARRY, P_NSLOTS };
 inline bool prof_on(int level, int slot) {
     return level >= 2 || (level == 1 && (slot == P_ENCODE || slot == P_DECODE || slot == P_FUSED || slot == P_CARRY));
 }

@@ -239,7 +239,9 @@ def test_errors_and_robustness():
     # corrupt containers are rejected, never fault
     import container_reader as cr
     cont = cr.parse(g.data)
-    for mutate in ("magic", "truncated", "length", "kraft", "geometry", "total"):
+    import oracle
+    for mutate in ("magic", "truncated", "length", "kraft", "geometry", "total", "lengths_offset_wraps",
+                   "lengths_offset_wraps_4", "escape_count", "escape_total", "chunk_short"):
         bad = g.data.copy()
         nbytes = None
         if mutate == "magic":
@@ -254,8 +256,22 @@ def test_errors_and_robustness():
             bad[16] ^= 1
         elif mutate == "total":
             bad[96:104] = np.frombuffer(np.uint64(bad.size + 16).tobytes(), np.uint8)
+        elif mutate == "lengths_offset_wraps":      # offset + block length wraps past 2^64
+            bad[128 + 24:128 + 32] = np.frombuffer(np.uint64(2 ** 64 - 1).tobytes(), np.uint8)
+        elif mutate == "lengths_offset_wraps_4":
+            bad[128 + 56 + 24:128 + 56 + 32] = np.frombuffer(np.uint64(2 ** 64 - 4).tobytes(), np.uint8)
+        elif mutate == "escape_count":              # the directory claims an escape the payload does not have
+            bad[128 + 16:128 + 20] = np.frombuffer(np.uint32(cont.tables[0].n_outliers + 1).tobytes(), np.uint8)
+        elif mutate == "escape_total":              # the header's count is not the sum of the tables'
+            bad[48:56] = np.frombuffer(np.uint64(int.from_bytes(bytes(bad[48:56]), "little") + 1).tobytes(), np.uint8)
+        elif mutate == "chunk_short":               # a chunk one word shorter than its codewords (the next chunk one longer)
+            k = int(np.flatnonzero(cont.chunk_words[:63] > 0)[0])
+            bad[cont.off_chunk + k] -= 1
+            bad[cont.off_chunk + k + 1] += 1
         st, _ = g.decompress(bad, nbytes)
         assert st == b.ECORRUPT, mutate
+        if nbytes is None and mutate != "geometry":   # (the oracle takes the geometry from the container, not from a context)
+            assert oracle.decompress(bad, x.shape, np.float32)[0] == oracle.ECORRUPT, mutate
     st, rec = g.decompress(g.data)
     assert st == 0
 

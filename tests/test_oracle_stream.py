@@ -161,6 +161,21 @@ def test_errors():
     assert oracle.decompress(bad, x.shape, np.float32)[0] == oracle.ECORRUPT
 
 
+def test_directory_offsets_near_2_to_64_are_refused():
+    """A damaged directory whose byte offsets sit just under 2^64 must fail the range test, not wrap past it."""
+    x = _payload(2, 32, 8, 5)
+    c = oracle.compress(x, 1e-3, R, 8, 12)
+    for t in (0, 1):
+        entry = 128 + 56 * t
+        for off in (2 ** 64 - 1, 2 ** 64 - 4, 2 ** 64 - 1024):
+            bad = c.data.copy()
+            bad[entry + 24:entry + 32] = np.frombuffer(np.uint64(off).tobytes(), np.uint8)   # code-length block
+            assert oracle.decompress(bad, x.shape, np.float32)[0] == oracle.ECORRUPT
+            bad = c.data.copy()
+            bad[entry + 32:entry + 40] = np.frombuffer(np.uint64(off).tobytes(), np.uint8)   # row references
+            assert oracle.decompress(bad, x.shape, np.float32)[0] == oracle.ECORRUPT
+
+
 def test_compress_bound_is_an_upper_bound():
     rng = np.random.default_rng(2)
     x = rng.standard_normal((2, 50, 24)).astype(np.float32)       # wide alphabet
