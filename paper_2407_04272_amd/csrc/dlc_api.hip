@@ -42,7 +42,7 @@ void prof_end(void* p, int slot, hipStream_t s) {
 }
 
 static const char* kSlotNames[P_NSLOTS] = {"k_hist", "k_codebook", "k_encode", "k_finalize",
-                                           "k_decode", "k_fused", "k_encode_carry"};
+                                           "k_decode", "k_fused", "k_encode_carry", "k_place"};
 }  // namespace dlc
 
 using namespace dlc;
@@ -104,6 +104,7 @@ static bool make_geom(const dlc_config* c, Geom* g) {
     g->LMAX = (uint32_t)L; g->dtype = (uint32_t)c->dtype; g->es = c->dtype == DLC_F16 ? 2u : 4u;
     g->vec = (n % 4 == 0) ? 1u : 0u;
     g->lz = (c->flags & DLC_FLAG_ROW_MATCH) ? 1u : 0u;
+    g->carry = (c->flags & DLC_FLAG_CARRY_CODEBOOK) ? 1u : 0u;
     if (g->lz && T > 65535ull) return false;  // the row kernels' grids have a table per y index
     return true;
 }
@@ -150,6 +151,9 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
     uint8_t* rm_own = g.lz ? take(4 * (size_t)g.T * g.B) : nullptr;
     uint8_t* rm_mult = g.lz ? take(32 * (size_t)(g.D / 4u)) : nullptr;
     uint8_t* dtab = take(sizeof(DecTable) * g.T);
+    uint8_t* gtot = g.carry ? take(4 * (size_t)g.NG) : nullptr;
+    uint8_t* bsum = g.carry ? take(4 * (size_t)g.ND * sum_blocks_per_dest(g)) : nullptr;
+    uint8_t* slots = g.carry ? take(4 * (size_t)g.NG * (size_t)carry_slot_words(g)) : nullptr;  // (last: by far the largest)
     uint8_t* desc = take(4 * (size_t)g.T);
     uint8_t* darr = take(4 * (size_t)g.T);
     if (w) {
@@ -161,6 +165,7 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
         w->word_start = (uint32_t*)ws0; w->word_end = (uint32_t*)ws1;
         w->arrive = (uint32_t*)arrive; w->ready = (uint64_t*)ready; w->sym_plane = plane;
         w->esc_count = (uint32_t*)escc;
+        w->gtot = (uint32_t*)gtot; w->bsum = (uint32_t*)bsum; w->slots = (uint32_t*)slots;
         w->dtab = (DecTable*)dtab; w->dec_esc = (uint32_t*)desc; w->dec_arrive = (uint32_t*)darr;
         w->rm_on = rm_on; w->rm_ref = (uint32_t*)rm_ref; w->rm_hash = (uint64_t*)rm_hash; w->rm_own = (uint32_t*)rm_own;
         w->rm_mult = (uint32_t*)rm_mult;
@@ -187,8 +192,10 @@ extern "C" int dlc_create(dlc_ctx** out, const dlc_config* cfg) {
     const size_t bytes = carve(g, nullptr, nullptr);
     uint8_t* base = nullptr;
     if (hipMalloc((void**)&base, bytes) != hipSuccess) { (void)hipGetLastError(); delete c; return DLC_ENOMEM; }
-    if (hipMemset(base, 0, bytes) != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }
     carve(g, base, &c->ws);
+    // (the slots of the single-pass path are written before they are read: they need no clearing)
+    const size_t clear_bytes = c->ws.slots ? (size_t)((uint8_t*)c->ws.slots - base) : bytes;
+    if (hipMemset(base, 0, clear_bytes) != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }
     c->ws.carry = (cfg->flags & DLC_FLAG_CARRY_CODEBOOK) ? 1u : 0u;
     if (g.lz && hipMemset(c->ws.rm_on, 1, g.T) != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }  // all tables
     if (g.lz) {

@@ -194,6 +194,80 @@ __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// single-pass path, second step: the groups' words from their slots to their places.  A work-group of four wavefronts
+// takes kPlaceGroups consecutive groups of one destination.  Where they go is the sum of the totals of all groups
+// before them in the container: the encode kernel has added the totals up per block of kSumBlock groups, so a
+// work-group reads the sums of the blocks before its own and the totals of the groups before it in its block (no
+// work-group waits for another).  Then every wavefront copies its group's words (coalesced both ways) and writes
+// the group table; the first and last group of a table leave the table's word range for the finalize kernel.
+// A container that does not fit its capacity gets nothing written past it.
+// ------------------------------------------------------------------------------------------------
+constexpr uint32_t kPlaceGroups = 4;  // a group per wavefront: many short wavefronts keep enough loads in flight
+
+__global__ __launch_bounds__(256) void k_place(Geom g, FixedLayout F, const uint32_t* gtot, const uint32_t* bsum,
+                                               const uint32_t* slots, uint64_t slot_words, Ctrl* ctrl, uint8_t* out,
+                                               uint64_t capacity, uint32_t wpd, uint32_t* word_start, uint32_t* word_end) {
+    __shared__ unsigned long long s_part[4];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t wg = blockIdx.x;
+    const uint32_t dst = wg / wpd, k = wg - dst * wpd;  // wpd work-groups per destination
+    const uint32_t gpd = g.TD * g.G;                    // groups of one destination
+    const uint32_t g0 = k * kPlaceGroups, n = min(kPlaceGroups, gpd - g0);
+    out += (uint64_t)dst * capacity;
+    const uint32_t* const gtot_d = gtot + (size_t)dst * gpd;
+    {
+        const uint32_t blk = g0 / kSumBlock;
+        const uint32_t* const bs = bsum + (size_t)dst * sum_blocks_per_dest(g);
+        unsigned long long acc = 0;
+        for (uint32_t i = tid; i < blk; i += 256) acc += bs[i];
+        for (uint32_t i = blk * kSumBlock + tid; i < g0; i += 256) acc += gtot_d[i];
+        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+        if (lane == 0) s_part[wave] = acc;
+    }
+    __syncthreads();
+    unsigned long long base = s_part[0] + s_part[1] + s_part[2] + s_part[3];
+    for (uint32_t i = 0; i < wave && i < n; ++i) base += gtot_d[g0 + i];
+    uint32_t* const words = reinterpret_cast<uint32_t*>(out + F.off_payload);
+    if (wave < n) {
+        const uint32_t i = wave;
+        const uint32_t gl = g0 + i;  // group number inside the container
+        const size_t gg = (size_t)dst * gpd + gl;
+        const uint32_t total = gtot[gg];
+        const uint32_t tl = gl / g.G, grp = gl - tl * g.G, t = dst * g.TD + tl;
+        // (word offsets are 32-bit: a container of 2^32 words or more does not fit any capacity the format can describe)
+        const uint32_t goff = (uint32_t)min(base, 0xFFFFFFFFull);
+        if (lane == 0) {
+            if (grp == 0) word_start[t] = goff;
+            if (grp == g.G - 1) word_end[t] = (uint32_t)min(base + total, 0xFFFFFFFFull);
+        }
+        if (base + total > 0xFFFFFFFFull || F.off_payload + 4ull * (base + total) > capacity) {  // uniform over the wavefront
+            // (past 2^32 words the finalize kernel could not tell from the clamped word range that the container failed)
+            if (lane == 0) { set_status(ctrl, DLC_ECAPACITY); atomicOr(&ctrl->abort, base + total > 0xFFFFFFFFull ? kAbortInternal : kAbortCapacity); }
+            return;
+        }
+        if (lane == 0) reinterpret_cast<uint32_t*>(out + F.off_group)[gl] = goff;
+        const uint32_t* src = slots + gg * slot_words;
+        uint32_t* dstw = words + goff;
+        uint32_t j = lane;
+        for (; j + 448u < total; j += 512u) {  // eight loads in flight
+            uint32_t v[8];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) v[u] = src[j + 64u * u];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) dstw[j + 64u * u] = v[u];
+        }
+        {  // the rest: up to eight more, all in flight too
+            uint32_t v[8];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u) v[u] = j + 64u * u < total ? src[j + 64u * u] : 0u;
+#pragma unroll
+            for (uint32_t u = 0; u < 8; ++u)
+                if (j + 64u * u < total) dstw[j + 64u * u] = v[u];
+        }
+    }
+}
+
 // carry != 0: the codebook is for the next call (the escape symbol gets a code whether it occurred or not)
 __global__ __launch_bounds__(256) void k_codebook(Geom g, uint32_t* hist, uint32_t* hist_view, uint16_t* enc,
                                                   uint8_t* lens, TMeta* tmeta, uint32_t carry) {
@@ -216,7 +290,7 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
                                                    const QParam* qp, Ctrl* ctrl, const uint32_t* word_start,
                                                    const uint32_t* word_end, uint8_t* __restrict__ out, uint64_t capacity,
                                                    uint64_t* out_bytes, uint32_t* esc_count, const uint8_t* rm_on,
-                                                   const uint32_t* rm_ref) {
+                                                   const uint32_t* rm_ref, uint32_t* bsum) {
     __shared__ uint32_t s_red[17];
     __shared__ uint32_t s_abort;
     __shared__ uint32_t s_cb[1025];   // start of each table's block, relative to the pass's first block
@@ -238,6 +312,10 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
     // an internal failure of the encode kernel spoils every container; one that did not fit spoils only itself, and
     // the capacity test below fails for it whenever the encode kernel's did.  (The flag is cleared by the last
     // destination to finish, so every destination's first work-group can still read it.)
+    if (first && bsum) {  // single-pass path: the block sums of this destination's groups start the next call at zero
+        const uint32_t nb = sum_blocks_per_dest(g);
+        for (uint32_t i = tid; i < nb; i += 1024) bsum[(size_t)dst * nb + i] = 0u;
+    }
     const bool aborted = first && (__hip_atomic_load(&ctrl->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kAbortInternal) != 0;
     uint64_t cb_carry = 0, nout_carry = 0;
     for (uint32_t base = 0; base < T; base += 1024) {
@@ -425,9 +503,16 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
             default: launch_encode_carry_256(g, F, payload, w, epoch, out, capacity, bpt, s); break;
         }
         if (prof_on(pl, P_CARRY)) prof_end(prof, P_CARRY, s);
+        {
+            const uint32_t wpd = (g.TD * g.G + kPlaceGroups - 1) / kPlaceGroups;
+            if (prof_on(pl, P_PLACE)) prof_begin(prof, P_PLACE, s);
+            hipLaunchKernelGGL(k_place, dim3(g.ND * wpd), dim3(256), 0, s, g, F, w.gtot, w.bsum, w.slots, (uint64_t)carry_slot_words(g),
+                               w.ctrl, out, capacity, wpd, w.word_start, w.word_end);
+            if (prof_on(pl, P_PLACE)) prof_end(prof, P_PLACE, s);
+        }
         if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
         hipLaunchKernelGGL(k_finalize, finalize_grid(g), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
-                           w.word_end, out, capacity, out_bytes, w.esc_count, (const uint8_t*)nullptr, (const uint32_t*)nullptr);
+                           w.word_end, out, capacity, out_bytes, w.esc_count, (const uint8_t*)nullptr, (const uint32_t*)nullptr, w.bsum);
         if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
         if (prof_on(pl, P_CODEBOOK)) prof_begin(prof, P_CODEBOOK, s);
         hipLaunchKernelGGL(k_codebook, dim3(g.T), dim3(256), codebook_smem(g.K), s, g, w.hist, w.hist_view, w.enc, w.lens,
@@ -442,7 +527,7 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         if (e != hipSuccess) return e;
         if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
         hipLaunchKernelGGL(k_finalize, finalize_grid(g), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
-                           w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr, g.lz ? (const uint8_t*)w.rm_on : nullptr, (const uint32_t*)w.rm_ref);
+                           w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr, g.lz ? (const uint8_t*)w.rm_on : nullptr, (const uint32_t*)w.rm_ref, (uint32_t*)nullptr);
         if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
         return hipGetLastError();
     }
@@ -485,7 +570,7 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
     }
     if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
     hipLaunchKernelGGL(k_finalize, finalize_grid(g), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
-                       w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr, g.lz ? (const uint8_t*)w.rm_on : nullptr, (const uint32_t*)w.rm_ref);
+                       w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr, g.lz ? (const uint8_t*)w.rm_on : nullptr, (const uint32_t*)w.rm_ref, (uint32_t*)nullptr);
     if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
     if (w.carry != 0)  // the codebook the next call will use: this call's counts (kept as the copy), escape symbol included
         hipLaunchKernelGGL(k_codebook, dim3(g.T), dim3(256), codebook_smem(g.K), s, g, w.hist_view, w.hist_view, w.enc,

@@ -34,6 +34,7 @@ struct Geom {
     uint32_t ND;  // destinations: the payload is [ND][TD][B][D], every destination gets a container of its own
     uint32_t TD;  // tables per destination (= T of a container)
     uint32_t lz;  // 1: row matching (vector-based LZ step) is on for the tables flagged in Ws::rm_on
+    uint32_t carry;  // 1: the codebook is carried from call to call (single-pass path)
     uint32_t S, R, K, LMAX;
     uint32_t dtype, es;
     uint32_t vec;  // 1: every table starts on a 16-byte (fp32) / 8-byte (fp16) boundary and n % 4 == 0
@@ -58,6 +59,16 @@ inline __host__ __device__ FixedLayout fixed_layout(const Geom& g) {
     F.off_payload = (F.off_chunk + (uint64_t)kW * ngd + 15ull) & ~15ull;
     return F;
 }
+
+// Single-pass path: a group's words (its chunks', then two per escape) wait in a slot of the workspace until the scan
+// over the groups' totals has placed them.  A slot takes the worst case: every chunk full of the longest codes, every
+// element an escape.
+inline __host__ __device__ uint64_t carry_slot_words(const Geom& g) {
+    return (uint64_t)kW * (((uint64_t)g.S * g.LMAX + 31ull) / 32ull) + 2ull * kW * g.S;
+}
+
+constexpr uint32_t kSumBlock = 32;   // groups whose totals are added up on the way (single-pass path)
+inline __host__ __device__ uint32_t sum_blocks_per_dest(const Geom& g) { return (g.TD * g.G + kSumBlock - 1u) / kSumBlock; }
 
 // small control block; `status` is sticky until read by the host, the rest is cleared per call
 struct Ctrl {
@@ -235,6 +246,9 @@ struct Ws {
     uint32_t* rm_own = nullptr;    // [T][B] the smallest row index with the row's hash
     uint32_t* rm_mult = nullptr;   // [D/4][8] multipliers of the row hash
     uint32_t carry = 0;            // 1: the codebook is carried from call to call (single-pass path)
+    uint32_t* slots = nullptr;     // [NG][carry_slot_words] the groups' words before they are placed (single-pass path)
+    uint32_t* gtot = nullptr;      // [NG] words of every group (single-pass path)
+    uint32_t* bsum = nullptr;      // [ND][ceil(TD*G / kSumBlock)] words of every block of groups; zero between calls
     // decompress
     DecTable* dtab = nullptr;      // [T] row matching: what the reference check found
     uint32_t* dec_esc = nullptr;   // [T] escapes the decode kernel has applied; zero between calls
@@ -253,7 +267,7 @@ struct Ws {
 // profiling hooks used by the launchers (implemented in dlc_api.hip)
 void prof_begin(void* prof, int slot, hipStream_t s);
 void prof_end(void* prof, int slot, hipStream_t s);
-enum ProfSlot { P_HIST = 0, P_CODEBOOK, P_ENCODE, P_FINALIZE, P_DECODE, P_FUSED, P_CARRY, P_NSLOTS };
+enum ProfSlot { P_HIST = 0, P_CODEBOOK, P_ENCODE, P_FINALIZE, P_DECODE, P_FUSED, P_CARRY, P_PLACE, P_NSLOTS };
 inline bool prof_on(int level, int slot) {
     return level >= 2 || (level == 1 && (slot == P_ENCODE || slot == P_DECODE || slot == P_FUSED || slot == P_CARRY));
 }
