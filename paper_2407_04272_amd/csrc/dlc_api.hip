@@ -2,6 +2,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <utility>
 #include <limits>
 #include <new>
 #include <vector>
@@ -42,7 +43,7 @@ void prof_end(void* p, int slot, hipStream_t s) {
 }
 
 static const char* kSlotNames[P_NSLOTS] = {"k_hist", "k_codebook", "k_encode", "k_finalize",
-                                           "k_decode", "k_fused", "k_encode_carry", "k_place"};
+                                           "k_decode", "k_fused", "k_encode_carry", "k_post"};
 }  // namespace dlc
 
 using namespace dlc;
@@ -152,6 +153,10 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
     uint8_t* rm_mult = g.lz ? take(32 * (size_t)(g.D / 4u)) : nullptr;
     uint8_t* dtab = take(sizeof(DecTable) * g.T);
     uint8_t* gtot = g.carry ? take(4 * (size_t)g.NG) : nullptr;
+    uint8_t* enc2 = g.carry ? take(2 * (size_t)g.T * g.K) : nullptr;
+    uint8_t* lens2 = g.carry ? take((size_t)g.T * g.K) : nullptr;
+    uint8_t* tmeta2 = g.carry ? take(sizeof(TMeta) * g.T) : nullptr;
+    uint8_t* bsum2 = g.carry ? take(4 * (size_t)g.ND * sum_blocks_per_dest(g)) : nullptr;
     uint8_t* bsum = g.carry ? take(4 * (size_t)g.ND * sum_blocks_per_dest(g)) : nullptr;
     uint8_t* slots = g.carry ? take(4 * (size_t)g.NG * (size_t)carry_slot_words(g)) : nullptr;  // (last: by far the largest)
     uint8_t* desc = take(4 * (size_t)g.T);
@@ -166,6 +171,7 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
         w->arrive = (uint32_t*)arrive; w->ready = (uint64_t*)ready; w->sym_plane = plane;
         w->esc_count = (uint32_t*)escc;
         w->gtot = (uint32_t*)gtot; w->bsum = (uint32_t*)bsum; w->slots = (uint32_t*)slots;
+        w->enc_next = (uint16_t*)enc2; w->lens_next = lens2; w->tmeta_next = (TMeta*)tmeta2; w->bsum_next = (uint32_t*)bsum2;
         w->dtab = (DecTable*)dtab; w->dec_esc = (uint32_t*)desc; w->dec_arrive = (uint32_t*)darr;
         w->rm_on = rm_on; w->rm_ref = (uint32_t*)rm_ref; w->rm_hash = (uint64_t*)rm_hash; w->rm_own = (uint32_t*)rm_own;
         w->rm_mult = (uint32_t*)rm_mult;
@@ -339,9 +345,16 @@ extern "C" int dlc_compress(dlc_ctx* c, const void* d_payload, void* d_out, size
         if (hipMemsetAsync(c->ws.state, 0, 8 * (size_t)c->g.NG, (hipStream_t)stream) != hipSuccess) return DLC_EHIP;
         c->epoch = 1;
     }
+    const bool was_single_pass = c->ws.carry != 0 && c->carry_ready;
     hipError_t e = launch_compress(c->g, d_payload, (uint8_t*)d_out, cap, d_out_bytes, c->ws, c->epoch, c->carry_ready,
                                    c->prof.level, &c->prof, (hipStream_t)stream);
     c->carry_ready = e == hipSuccess && c->ws.carry != 0;
+    if (c->ws.carry != 0) {  // the codebook just built for the next call becomes the current one
+        std::swap(c->ws.enc, c->ws.enc_next);
+        std::swap(c->ws.lens, c->ws.lens_next);
+        std::swap(c->ws.tmeta, c->ws.tmeta_next);
+        if (was_single_pass) std::swap(c->ws.bsum, c->ws.bsum_next);  // (the single-pass step has cleared the other set)
+    }
     return e == hipSuccess ? DLC_OK : DLC_EHIP;
 }
 

@@ -194,80 +194,6 @@ __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const
     }
 }
 
-// ------------------------------------------------------------------------------------------------
-// single-pass path, second step: the groups' words from their slots to their places.  A work-group of four wavefronts
-// takes kPlaceGroups consecutive groups of one destination.  Where they go is the sum of the totals of all groups
-// before them in the container: the encode kernel has added the totals up per block of kSumBlock groups, so a
-// work-group reads the sums of the blocks before its own and the totals of the groups before it in its block (no
-// work-group waits for another).  Then every wavefront copies its group's words (coalesced both ways) and writes
-// the group table; the first and last group of a table leave the table's word range for the finalize kernel.
-// A container that does not fit its capacity gets nothing written past it.
-// ------------------------------------------------------------------------------------------------
-constexpr uint32_t kPlaceGroups = 4;  // a group per wavefront: many short wavefronts keep enough loads in flight
-
-__global__ __launch_bounds__(256) void k_place(Geom g, FixedLayout F, const uint32_t* gtot, const uint32_t* bsum,
-                                               const uint32_t* slots, uint64_t slot_words, Ctrl* ctrl, uint8_t* out,
-                                               uint64_t capacity, uint32_t wpd, uint32_t* word_start, uint32_t* word_end) {
-    __shared__ unsigned long long s_part[4];
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t wg = blockIdx.x;
-    const uint32_t dst = wg / wpd, k = wg - dst * wpd;  // wpd work-groups per destination
-    const uint32_t gpd = g.TD * g.G;                    // groups of one destination
-    const uint32_t g0 = k * kPlaceGroups, n = min(kPlaceGroups, gpd - g0);
-    out += (uint64_t)dst * capacity;
-    const uint32_t* const gtot_d = gtot + (size_t)dst * gpd;
-    {
-        const uint32_t blk = g0 / kSumBlock;
-        const uint32_t* const bs = bsum + (size_t)dst * sum_blocks_per_dest(g);
-        unsigned long long acc = 0;
-        for (uint32_t i = tid; i < blk; i += 256) acc += bs[i];
-        for (uint32_t i = blk * kSumBlock + tid; i < g0; i += 256) acc += gtot_d[i];
-        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-        if (lane == 0) s_part[wave] = acc;
-    }
-    __syncthreads();
-    unsigned long long base = s_part[0] + s_part[1] + s_part[2] + s_part[3];
-    for (uint32_t i = 0; i < wave && i < n; ++i) base += gtot_d[g0 + i];
-    uint32_t* const words = reinterpret_cast<uint32_t*>(out + F.off_payload);
-    if (wave < n) {
-        const uint32_t i = wave;
-        const uint32_t gl = g0 + i;  // group number inside the container
-        const size_t gg = (size_t)dst * gpd + gl;
-        const uint32_t total = gtot[gg];
-        const uint32_t tl = gl / g.G, grp = gl - tl * g.G, t = dst * g.TD + tl;
-        // (word offsets are 32-bit: a container of 2^32 words or more does not fit any capacity the format can describe)
-        const uint32_t goff = (uint32_t)min(base, 0xFFFFFFFFull);
-        if (lane == 0) {
-            if (grp == 0) word_start[t] = goff;
-            if (grp == g.G - 1) word_end[t] = (uint32_t)min(base + total, 0xFFFFFFFFull);
-        }
-        if (base + total > 0xFFFFFFFFull || F.off_payload + 4ull * (base + total) > capacity) {  // uniform over the wavefront
-            // (past 2^32 words the finalize kernel could not tell from the clamped word range that the container failed)
-            if (lane == 0) { set_status(ctrl, DLC_ECAPACITY); atomicOr(&ctrl->abort, base + total > 0xFFFFFFFFull ? kAbortInternal : kAbortCapacity); }
-            return;
-        }
-        if (lane == 0) reinterpret_cast<uint32_t*>(out + F.off_group)[gl] = goff;
-        const uint32_t* src = slots + gg * slot_words;
-        uint32_t* dstw = words + goff;
-        uint32_t j = lane;
-        for (; j + 448u < total; j += 512u) {  // eight loads in flight
-            uint32_t v[8];
-#pragma unroll
-            for (uint32_t u = 0; u < 8; ++u) v[u] = src[j + 64u * u];
-#pragma unroll
-            for (uint32_t u = 0; u < 8; ++u) dstw[j + 64u * u] = v[u];
-        }
-        {  // the rest: up to eight more, all in flight too
-            uint32_t v[8];
-#pragma unroll
-            for (uint32_t u = 0; u < 8; ++u) v[u] = j + 64u * u < total ? src[j + 64u * u] : 0u;
-#pragma unroll
-            for (uint32_t u = 0; u < 8; ++u)
-                if (j + 64u * u < total) dstw[j + 64u * u] = v[u];
-        }
-    }
-}
-
 // carry != 0: the codebook is for the next call (the escape symbol gets a code whether it occurred or not)
 __global__ __launch_bounds__(256) void k_codebook(Geom g, uint32_t* hist, uint32_t* hist_view, uint16_t* enc,
                                                   uint8_t* lens, TMeta* tmeta, uint32_t carry) {
@@ -286,19 +212,22 @@ __global__ __launch_bounds__(256) void k_codebook(Geom g, uint32_t* hist, uint32
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint64_t a16(uint64_t x) { return (x + 15ull) & ~15ull; }
 
-__global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const TMeta* tmeta, const uint8_t* __restrict__ lens,
-                                                   const QParam* qp, Ctrl* ctrl, const uint32_t* word_start,
-                                                   const uint32_t* word_end, uint8_t* __restrict__ out, uint64_t capacity,
-                                                   uint64_t* out_bytes, uint32_t* esc_count, const uint8_t* rm_on,
-                                                   const uint32_t* rm_ref, uint32_t* bsum) {
-    __shared__ uint32_t s_red[17];
+// One destination's container, by work-group xi of the xn that share the work (all of NT threads); everything below is
+// that container's.  The tables' word ranges may come from work-groups of the running kernel: they are read past the caches.
+template <uint32_t NT>
+__device__ __forceinline__ void finalize_dest(const Geom& g, const FixedLayout& F, const TMeta* tmeta, const uint8_t* __restrict__ lens,
+                                              const QParam* qp, Ctrl* ctrl, const uint32_t* word_start, const uint32_t* word_end,
+                                              uint8_t* __restrict__ out, uint64_t capacity, uint64_t* out_bytes, uint32_t* esc_count,
+                                              const uint8_t* rm_on, const uint32_t* rm_ref, uint32_t* bsum, uint32_t dst, uint32_t xi,
+                                              uint32_t xn) {
+    constexpr uint32_t NW = NT / 64u;
+    __shared__ uint32_t s_red[NW + 1];
     __shared__ uint32_t s_abort;
-    __shared__ uint32_t s_cb[1025];   // start of each table's block, relative to the pass's first block
-    __shared__ uint32_t s_lo[1024], s_nl[1024];
+    __shared__ uint32_t s_cb[NT + 1];   // start of each table's block, relative to the pass's first block
+    __shared__ uint32_t s_lo[NT], s_nl[NT];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const bool first = blockIdx.x == 0;
-    // blockIdx.y: the destination whose container this work-group finishes; everything below is that container's
-    const uint32_t dst = blockIdx.y, T = g.TD;
+    const bool first = xi == 0;
+    const uint32_t T = g.TD;
     tmeta += (size_t)dst * T;
     lens += (size_t)dst * T * g.K;
     qp += (size_t)dst * T;
@@ -307,18 +236,18 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
     if (esc_count) esc_count += (size_t)dst * T;
     out += (uint64_t)dst * capacity;
     uint64_t* const table_bytes = out_bytes + 1 + (size_t)dst * T;
-    const uint64_t words = word_end[T - 1];
+    const uint64_t words = __hip_atomic_load(&word_end[T - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const uint64_t off_cb = a16(F.off_payload + 4ull * words);
     // an internal failure of the encode kernel spoils every container; one that did not fit spoils only itself, and
     // the capacity test below fails for it whenever the encode kernel's did.  (The flag is cleared by the last
     // destination to finish, so every destination's first work-group can still read it.)
-    if (first && bsum) {  // single-pass path: the block sums of this destination's groups start the next call at zero
+    if (first && bsum) {  // single-pass path: the block sums the next call adds to start at zero (not the ones this call reads)
         const uint32_t nb = sum_blocks_per_dest(g);
-        for (uint32_t i = tid; i < nb; i += 1024) bsum[(size_t)dst * nb + i] = 0u;
+        for (uint32_t i = tid; i < nb; i += NT) bsum[(size_t)dst * nb + i] = 0u;
     }
     const bool aborted = first && (__hip_atomic_load(&ctrl->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kAbortInternal) != 0;
     uint64_t cb_carry = 0, nout_carry = 0;
-    for (uint32_t base = 0; base < T; base += 1024) {
+    for (uint32_t base = 0; base < T; base += NT) {
         const uint32_t t = base + tid;
         TMeta m;
         uint32_t cb = 0, no = 0, nl = 0;
@@ -334,23 +263,23 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
             no = m.n_outliers;
         }
         uint32_t cb_tot, no_tot;
-        const uint32_t cb_ex = block_excl_scan<16>(cb, s_red, tid, &cb_tot);
+        const uint32_t cb_ex = block_excl_scan<(int)NW>(cb, s_red, tid, &cb_tot);
         __syncthreads();
-        (void)block_excl_scan<16>(no, s_red, tid, &no_tot);
+        (void)block_excl_scan<(int)NW>(no, s_red, tid, &no_tot);
         s_cb[tid] = cb_ex;
         s_lo[tid] = m.sym_lo;
         s_nl[tid] = nl;
         if (tid == 0) {
-            s_cb[1024] = cb_tot;
+            s_cb[NT] = cb_tot;
             // the code-length blocks are the last thing in the container: the capacity check of this pass
             s_abort = aborted || off_cb + cb_carry + cb_tot > capacity;
         }
         __syncthreads();
         if (s_abort) break;  // uniform
-        const uint32_t nt = min(1024u, T - base);
+        const uint32_t nt = min(NT, T - base);
         // the blocks of this work-group's tables, a wavefront per table, four bytes per lane (the blocks start on
         // 4-byte boundaries and are padded to them)
-        for (uint32_t lt = blockIdx.x * 16u + wave; lt < nt; lt += gridDim.x * 16u) {
+        for (uint32_t lt = xi * NW + wave; lt < nt; lt += xn * NW) {
             const uint32_t n_l = s_nl[lt];
             const uint8_t* src = lens + (size_t)(base + lt) * g.K + s_lo[lt];
             uint32_t* dst = reinterpret_cast<uint32_t*>(out + off_cb + cb_carry + s_cb[lt]);
@@ -365,7 +294,8 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
             }
         }
         if (first && t < T) {
-            const uint64_t w0 = word_start[t], w1 = word_end[t];
+            const uint64_t w0 = __hip_atomic_load(&word_start[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint64_t w1 = __hip_atomic_load(&word_end[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             uint8_t* d = out + kHeaderBytes + (uint64_t)kDirBytes * t;
             uint32_t* d32 = reinterpret_cast<uint32_t*>(d);
             d32[0] = qp[t].eb_bits; d32[1] = m.n_used; d32[2] = m.sym_lo; d32[3] = m.sym_hi; d32[4] = m.n_outliers;
@@ -386,9 +316,9 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
         rm_ref += (size_t)dst * T * g.B;
         const uint64_t rbase = a16(end_bytes), rsz = a16(4ull * g.B);
         uint32_t n_on = 0;  // tables with references
-        for (uint32_t base = 0; base < T; base += 1024) {
+        for (uint32_t base = 0; base < T; base += NT) {
             uint32_t tot;
-            (void)block_excl_scan<16>((base + tid < T && rm_on[base + tid]) ? 1u : 0u, s_red, tid, &tot);
+            (void)block_excl_scan<(int)NW>((base + tid < T && rm_on[base + tid]) ? 1u : 0u, s_red, tid, &tot);
             n_on += tot;
             __syncthreads();
         }
@@ -398,13 +328,13 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
             if (tid == 0) s_abort = 1;
             __syncthreads();
         } else if (n_on) {
-            for (uint64_t i = off_cb + cb_carry + tid; first && i < rbase; i += 1024) out[i] = 0;
+            for (uint64_t i = off_cb + cb_carry + tid; first && i < rbase; i += NT) out[i] = 0;
             uint32_t on_carry = 0;
-            for (uint32_t base = 0; base < T; base += 1024) {
+            for (uint32_t base = 0; base < T; base += NT) {
                 const uint32_t t = base + tid;
                 const uint32_t on = (t < T && rm_on[t]) ? 1u : 0u;
                 uint32_t tot;
-                const uint32_t ex = block_excl_scan<16>(on, s_red, tid, &tot);
+                const uint32_t ex = block_excl_scan<(int)NW>(on, s_red, tid, &tot);
                 s_cb[tid] = on ? on_carry + ex : 0xFFFFFFFFu;  // the table's block number
                 __syncthreads();
                 if (first && on) {
@@ -412,15 +342,15 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
                     d64[1] = rbase + (uint64_t)(on_carry + ex) * rsz;
                     table_bytes[t] += 4ull * g.B;
                 }
-                const uint32_t nt = min(1024u, T - base);
-                for (uint32_t lt = blockIdx.x; lt < nt; lt += gridDim.x) {  // a work-group per table
+                const uint32_t nt = min(NT, T - base);
+                for (uint32_t lt = xi; lt < nt; lt += xn) {  // a work-group per table
                     const uint32_t k = s_cb[lt];
                     if (k == 0xFFFFFFFFu) continue;  // uniform
                     uint32_t* dstw = reinterpret_cast<uint32_t*>(out + rbase + (uint64_t)k * rsz);
                     const uint32_t* src = rm_ref + (size_t)(base + lt) * g.B;
-                    for (uint32_t r = tid; r < g.B; r += 1024) dstw[r] = src[r];
+                    for (uint32_t r = tid; r < g.B; r += NT) dstw[r] = src[r];
                     if (k + 1u < n_on)  // padding up to the next block
-                        for (uint32_t r = g.B + tid; r < (uint32_t)(rsz / 4u); r += 1024) dstw[r] = 0u;
+                        for (uint32_t r = g.B + tid; r < (uint32_t)(rsz / 4u); r += NT) dstw[r] = 0u;
                 }
                 on_carry += tot;
                 __syncthreads();
@@ -431,17 +361,17 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
     uint64_t container_bytes = 0;  // of this destination; 0 = it did not fit
     if (s_abort) {
         if (tid == 0 && !aborted) set_status(ctrl, DLC_ECAPACITY);
-        for (uint32_t t = tid; t < T; t += 1024) table_bytes[t] = 0;
+        for (uint32_t t = tid; t < T; t += NT) table_bytes[t] = 0;
         if (esc_count)  // whatever the passes after the failing one have not cleared
-            for (uint32_t t = tid; t < T; t += 1024) esc_count[t] = 0;
+            for (uint32_t t = tid; t < T; t += NT) esc_count[t] = 0;
     } else {
         // padding between sections
         const uint64_t e0 = kHeaderBytes + (uint64_t)kDirBytes * T;
-        for (uint64_t i = e0 + tid; i < F.off_group; i += 1024) out[i] = 0;
+        for (uint64_t i = e0 + tid; i < F.off_group; i += NT) out[i] = 0;
         const uint64_t e1 = F.off_group + 4ull * T * g.G;
-        for (uint64_t i = e1 + tid; i < F.off_chunk; i += 1024) out[i] = 0;
+        for (uint64_t i = e1 + tid; i < F.off_chunk; i += NT) out[i] = 0;
         const uint64_t e2 = F.off_payload + 4ull * words;
-        for (uint64_t i = e2 + tid; i < off_cb; i += 1024) out[i] = 0;
+        for (uint64_t i = e2 + tid; i < off_cb; i += NT) out[i] = 0;
         if (tid == 0) {
             uint32_t* h = reinterpret_cast<uint32_t*>(out);
             h[H_MAGIC] = kMagic; h[H_VERSION] = kVersion; h[H_DTYPE] = g.dtype; h[H_T] = T; h[H_B] = g.B; h[H_D] = g.D;
@@ -482,6 +412,131 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
     }
 }
 
+__global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const TMeta* tmeta, const uint8_t* __restrict__ lens,
+                                                   const QParam* qp, Ctrl* ctrl, const uint32_t* word_start,
+                                                   const uint32_t* word_end, uint8_t* __restrict__ out, uint64_t capacity,
+                                                   uint64_t* out_bytes, uint32_t* esc_count, const uint8_t* rm_on,
+                                                   const uint32_t* rm_ref, uint32_t* bsum) {
+    // blockIdx.y: the destination whose container this work-group helps to finish
+    finalize_dest<1024>(g, F, tmeta, lens, qp, ctrl, word_start, word_end, out, capacity, out_bytes, esc_count, rm_on, rm_ref, bsum,
+                        blockIdx.y, blockIdx.x, gridDim.x);
+}
+
+// ------------------------------------------------------------------------------------------------
+// single-pass path, second step: one launch, three jobs that do not wait for one another.  Where a group's words go
+// is the sum of the totals of all groups before it in its container; the encode kernel has added the totals up per
+// block of kSumBlock groups, so whoever needs such a sum reads the sums of the blocks before and the totals of the
+// groups in between.
+//   work-groups [0, T): the codebook of the next call from this call's counts, into the second set of codebook arrays
+//     (this call's set is still being read)
+//   then nf work-groups per destination: the container's header, directory, code-length blocks, sizes (finalize_dest),
+//     from the tables' word ranges, which they work out from the sums themselves
+//   the rest: the groups' words from their slots to their places, kPlaceGroups groups per work-group, a group per
+//     wavefront (coalesced both ways), and the group table.  Nothing is written past a container's capacity.
+// ------------------------------------------------------------------------------------------------
+// words of the groups [0, x) of a destination (called by a whole wavefront, same x)
+__device__ __forceinline__ unsigned long long words_before(const uint32_t* bs, const uint32_t* gtot_d, uint32_t x, uint32_t lane) {
+    const uint32_t blk = x / kSumBlock;
+    unsigned long long acc = 0;
+    for (uint32_t i = lane; i < blk; i += 64) acc += bs[i];
+    for (uint32_t i = blk * kSumBlock + lane; i < x; i += 64) acc += gtot_d[i];
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    return acc;
+}
+
+__global__ __launch_bounds__(256) void k_post(Geom g, FixedLayout F, const uint32_t* gtot, const uint32_t* bsum, uint32_t* bsum_next,
+                                              const uint32_t* slots, uint64_t slot_words, Ctrl* ctrl, uint8_t* out,
+                                              uint64_t capacity, uint32_t wpd, uint32_t nf, uint32_t* word_start,
+                                              uint32_t* word_end, const TMeta* tmeta, const uint8_t* lens, const QParam* qp,
+                                              uint64_t* out_bytes, uint32_t* esc_count, uint32_t* hist, uint32_t* hist_view,
+                                              uint16_t* enc_next, uint8_t* lens_next, TMeta* tmeta_next) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t gpd = g.TD * g.G;  // groups of one destination
+    if (blockIdx.x < g.T) {  // uniform over the work-group; these come first: a codebook takes longer than a copy
+        __shared__ CodebookShared sh;
+        const uint32_t t = blockIdx.x;
+        codebook_build(g, hist + (size_t)t * g.K, hist_view + (size_t)t * g.K, enc_next + (size_t)t * g.K,
+                       lens_next + (size_t)t * g.K, tmeta_next + t, smem, sh, tid, 1u);
+        return;
+    }
+    if (blockIdx.x < g.T + g.ND * nf) {
+        const uint32_t f = blockIdx.x - g.T, dst = f / nf, xi = f - dst * nf;
+        const uint32_t* const bs = bsum + (size_t)dst * sum_blocks_per_dest(g);
+        const uint32_t* const gtot_d = gtot + (size_t)dst * gpd;
+        // The tables' word ranges (stored past the caches: finalize_dest reads them that way): a scan over the block
+        // sums, 256 blocks a pass; the thread of a block looks after the tables that start inside it.  Every one of
+        // the nf work-groups needs the last table's end, only the first of them the rest.
+        __shared__ uint32_t s_scan[5];
+        __shared__ unsigned long long s_sum64[4];
+        const uint32_t nb = sum_blocks_per_dest(g);
+        uint32_t carry = 0;
+        unsigned long long all = 0;
+        for (uint32_t c0 = 0; c0 < nb; c0 += 256) {  // uniform trip count
+            const uint32_t blk = c0 + tid;
+            const uint32_t v = blk < nb ? bs[blk] : 0u;
+            unsigned long long v64 = v;
+            for (int o = 32; o > 0; o >>= 1) v64 += __shfl_xor(v64, o, 64);
+            if (lane == 0) s_sum64[wave] = v64;
+            uint32_t tot;
+            const uint32_t before = carry + block_excl_scan<4>(v, s_scan, tid, &tot);
+            all += s_sum64[0] + s_sum64[1] + s_sum64[2] + s_sum64[3];
+            if (xi == 0 && blk < nb) {
+                const uint32_t x0 = blk * kSumBlock, x1 = min(gpd, x0 + kSumBlock);
+                for (uint32_t tl = (x0 + g.G - 1u) / g.G; tl < g.TD && tl * g.G < x1; ++tl) {
+                    uint32_t w = before;
+                    for (uint32_t i = x0; i < tl * g.G; ++i) w += gtot_d[i];
+                    __hip_atomic_store(&word_start[dst * g.TD + tl], w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (tl > 0) __hip_atomic_store(&word_end[dst * g.TD + tl - 1u], w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            carry += tot;
+            __syncthreads();
+        }
+        if (tid == 0) {  // (clamped; past 2^32 words the format cannot say where a group starts: the call fails)
+            if (all > 0xFFFFFFFFull && xi == 0) { set_status(ctrl, DLC_ECAPACITY); atomicOr(&ctrl->abort, kAbortInternal); }
+            __hip_atomic_store(&word_end[dst * g.TD + g.TD - 1u], (uint32_t)min(all, 0xFFFFFFFFull), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        finalize_dest<256>(g, F, tmeta, lens, qp, ctrl, word_start, word_end, out, capacity, out_bytes, esc_count,
+                           (const uint8_t*)nullptr, (const uint32_t*)nullptr, bsum_next, dst, xi, nf);
+        return;
+    }
+    const uint32_t wg = blockIdx.x - g.T - g.ND * nf;
+    const uint32_t dst = wg / wpd, k = wg - dst * wpd;  // wpd work-groups per destination
+    const uint32_t g0 = k * kPlaceGroups;
+    if (g0 + wave >= gpd) return;  // whole wavefront
+    uint8_t* const out_d = out + (uint64_t)dst * capacity;
+    const uint32_t gl = g0 + wave;  // group number inside the container
+    const size_t gg = (size_t)dst * gpd + gl;
+    const unsigned long long base = words_before(bsum + (size_t)dst * sum_blocks_per_dest(g), gtot + (size_t)dst * gpd, gl, lane);
+    const uint32_t total = gtot[gg];
+    // (word offsets are 32-bit: a container of 2^32 words or more does not fit any capacity the format can describe;
+    // the finishing work-groups come to the same verdict from the same sums and report it)
+    if (base + total > 0xFFFFFFFFull || F.off_payload + 4ull * (base + total) > capacity) return;  // uniform over the wavefront
+    const uint32_t goff = (uint32_t)base;
+    if (lane == 0) reinterpret_cast<uint32_t*>(out_d + F.off_group)[gl] = goff;
+    const uint32_t* src = slots + gg * slot_words;
+    uint32_t* dstw = reinterpret_cast<uint32_t*>(out_d + F.off_payload) + goff;
+    uint32_t j = lane;
+    for (; j + 448u < total; j += 512u) {  // eight loads in flight
+        uint32_t v[8];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) v[u] = src[j + 64u * u];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) dstw[j + 64u * u] = v[u];
+    }
+    {  // the rest: up to eight more, all in flight too
+        uint32_t v[8];
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u) v[u] = j + 64u * u < total ? src[j + 64u * u] : 0u;
+#pragma unroll
+        for (uint32_t u = 0; u < 8; ++u)
+            if (j + 64u * u < total) dstw[j + 64u * u] = v[u];
+    }
+}
+
 // work-groups of the finalize kernel: a wavefront per table, sixteen wavefronts per work-group
 static inline dim3 finalize_grid(const Geom& g) {
     // a wavefront per table for the code-length blocks; with row matching a work-group per table copies its references
@@ -504,20 +559,15 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         }
         if (prof_on(pl, P_CARRY)) prof_end(prof, P_CARRY, s);
         {
-            const uint32_t wpd = (g.TD * g.G + kPlaceGroups - 1) / kPlaceGroups;
-            if (prof_on(pl, P_PLACE)) prof_begin(prof, P_PLACE, s);
-            hipLaunchKernelGGL(k_place, dim3(g.ND * wpd), dim3(256), 0, s, g, F, w.gtot, w.bsum, w.slots, (uint64_t)carry_slot_words(g),
-                               w.ctrl, out, capacity, wpd, w.word_start, w.word_end);
-            if (prof_on(pl, P_PLACE)) prof_end(prof, P_PLACE, s);
+            const uint32_t wpd = (g.TD * g.G + kPlaceGroups - 1) / kPlaceGroups, n_place = g.ND * wpd;
+            const uint32_t nf = std::min<uint32_t>((std::min<uint32_t>(g.TD, 256u) + 3u) / 4u, 64u);  // a wavefront per table's code-length block
+            if (prof_on(pl, P_POST)) prof_begin(prof, P_POST, s);
+            hipLaunchKernelGGL(k_post, dim3(g.T + g.ND * nf + n_place), dim3(256), codebook_smem(g.K), s, g, F, w.gtot, w.bsum,
+                               w.bsum_next, w.slots, (uint64_t)carry_slot_words(g), w.ctrl, out, capacity, wpd, nf, w.word_start,
+                               w.word_end, w.tmeta, w.lens, w.qp, out_bytes, w.esc_count, w.hist, w.hist_view, w.enc_next,
+                               w.lens_next, w.tmeta_next);
+            if (prof_on(pl, P_POST)) prof_end(prof, P_POST, s);
         }
-        if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
-        hipLaunchKernelGGL(k_finalize, finalize_grid(g), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
-                           w.word_end, out, capacity, out_bytes, w.esc_count, (const uint8_t*)nullptr, (const uint32_t*)nullptr, w.bsum);
-        if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
-        if (prof_on(pl, P_CODEBOOK)) prof_begin(prof, P_CODEBOOK, s);
-        hipLaunchKernelGGL(k_codebook, dim3(g.T), dim3(256), codebook_smem(g.K), s, g, w.hist, w.hist_view, w.enc, w.lens,
-                           w.tmeta, 1u);
-        if (prof_on(pl, P_CODEBOOK)) prof_end(prof, P_CODEBOOK, s);
         return hipGetLastError();
     }
     if (w.fused_grid != 0) {
@@ -573,14 +623,18 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
                        w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr, g.lz ? (const uint8_t*)w.rm_on : nullptr, (const uint32_t*)w.rm_ref, (uint32_t*)nullptr);
     if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
     if (w.carry != 0)  // the codebook the next call will use: this call's counts (kept as the copy), escape symbol included
-        hipLaunchKernelGGL(k_codebook, dim3(g.T), dim3(256), codebook_smem(g.K), s, g, w.hist_view, w.hist_view, w.enc,
-                           w.lens, w.tmeta, 1u);
+        hipLaunchKernelGGL(k_codebook, dim3(g.T), dim3(256), codebook_smem(g.K), s, g, w.hist_view, w.hist_view, w.enc_next,
+                           w.lens_next, w.tmeta_next, 1u);
     return hipGetLastError();
 }
 
 hipError_t compress_set_attributes() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(k_codebook), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)codebook_smem(4096));
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_codebook), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)codebook_smem(4096));
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_post), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)codebook_smem(4096));
+    return e;
 }
 
 }  // namespace dlc

@@ -67,6 +67,7 @@ inline __host__ __device__ uint64_t carry_slot_words(const Geom& g) {
     return (uint64_t)kW * (((uint64_t)g.S * g.LMAX + 31ull) / 32ull) + 2ull * kW * g.S;
 }
 
+constexpr uint32_t kPlaceGroups = 4;  // groups a work-group of k_post places: one per wavefront, many short wavefronts keep enough loads in flight
 constexpr uint32_t kSumBlock = 32;   // groups whose totals are added up on the way (single-pass path)
 inline __host__ __device__ uint32_t sum_blocks_per_dest(const Geom& g) { return (g.TD * g.G + kSumBlock - 1u) / kSumBlock; }
 
@@ -248,7 +249,11 @@ struct Ws {
     uint32_t carry = 0;            // 1: the codebook is carried from call to call (single-pass path)
     uint32_t* slots = nullptr;     // [NG][carry_slot_words] the groups' words before they are placed (single-pass path)
     uint32_t* gtot = nullptr;      // [NG] words of every group (single-pass path)
-    uint32_t* bsum = nullptr;      // [ND][ceil(TD*G / kSumBlock)] words of every block of groups; zero between calls
+    uint16_t* enc_next = nullptr;  // single-pass path: the codebook for the next call is built while this call's is still
+    uint8_t* lens_next = nullptr;  // being read; the two sets change places after every call
+    TMeta* tmeta_next = nullptr;
+    uint32_t* bsum = nullptr;      // [ND][ceil(TD*G / kSumBlock)] words of every block of groups (this call's)
+    uint32_t* bsum_next = nullptr; // the next call's, cleared while this call's are read; the two change places after every call
     // decompress
     DecTable* dtab = nullptr;      // [T] row matching: what the reference check found
     uint32_t* dec_esc = nullptr;   // [T] escapes the decode kernel has applied; zero between calls
@@ -267,7 +272,7 @@ struct Ws {
 // profiling hooks used by the launchers (implemented in dlc_api.hip)
 void prof_begin(void* prof, int slot, hipStream_t s);
 void prof_end(void* prof, int slot, hipStream_t s);
-enum ProfSlot { P_HIST = 0, P_CODEBOOK, P_ENCODE, P_FINALIZE, P_DECODE, P_FUSED, P_CARRY, P_PLACE, P_NSLOTS };
+enum ProfSlot { P_HIST = 0, P_CODEBOOK, P_ENCODE, P_FINALIZE, P_DECODE, P_FUSED, P_CARRY, P_POST, P_NSLOTS };
 inline bool prof_on(int level, int slot) {
     return level >= 2 || (level == 1 && (slot == P_ENCODE || slot == P_DECODE || slot == P_FUSED || slot == P_CARRY));
 }
