@@ -304,42 +304,28 @@ __device__ __forceinline__ void carry_emit_escapes(uint32_t* rec, uint32_t lane,
     }
 }
 
+// A work-group takes `ipw` consecutive items (an item: four consecutive groups of one table, one per wavefront) and
+// no work-group waits for another: a group's words go to the group's slot of the workspace, and the kernel that
+// follows (k_post) puts them where the sums of the groups' totals say.  The grid is sized to what the chip holds at
+// once, so the set-up of a work-group is paid once, the code table stays in LDS while the items are of one table,
+// and the first loads of an item are on their way while the item before it is being written out.
 template <int S, bool F16, bool VEC>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k_encode_carry(const void* payload, Geom g, FixedLayout F, const QParam* qp,
                                                       const uint16_t* enc, uint8_t* out, uint64_t capacity, uint32_t bpt,
                                                       uint32_t* hist, uint32_t* esc_count, uint32_t* slots, uint64_t slot_words,
-                                                      uint32_t* gtot, uint32_t* bsum) {
+                                                      uint32_t* gtot, uint32_t* bsum, uint32_t ipw, uint32_t n_items) {
     constexpr uint32_t CAP = (uint32_t)S / 8u;          // words of LDS per chunk: room for 4 bits per symbol
     constexpr uint32_t kStageWords = carry_stage_words(CAP);  // per wavefront
+    constexpr uint32_t kGroupEls = kW * (uint32_t)S;
     __shared__ __align__(16) uint32_t s_tab[kCarryCopies * kCarryCopyBytes / 4u];
     __shared__ __align__(16) uint32_t s_stage[4 * kStageWords];
     __shared__ uint16_t s_recs[4 * kCarryRecs];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // No work-group waits for another: a group's words go to the group's slot of the workspace, and the kernel that
-    // follows (k_place) puts them where the scan over the groups' totals says.
-    const uint32_t wg = blockIdx.x;
-    const uint32_t t = wg / bpt, b = wg % bpt;
-    // the destination this table belongs to: its container starts `capacity` bytes after the previous one and its
-    // groups are numbered from 0
-    const uint32_t dst = t / g.TD, tl = t - dst * g.TD;
-    out += (uint64_t)dst * capacity;
     const uint32_t win_lo = win_lo_of(g.R);
-    const uint16_t* enc_t = enc + (size_t)t * g.K;
-    uint32_t* hist_t = hist + (size_t)t * g.K;
-    const uint32_t grp = b * 4 + wave;
-    const bool active = grp < g.G;  // uniform over the wavefront; an idle wavefront only takes part in the barriers
-    const uint32_t gid = tl * g.G + (active ? grp : 0u);  // group number inside the container
-    const uint8_t* tab = static_cast<const uint8_t*>(payload) + (size_t)t * g.n * g.es;
-    const uint32_t gstart = grp * (kW * (uint32_t)S);
     uint32_t* const stage = s_stage + wave * kStageWords;
+    const uint32_t i0 = blockIdx.x * ipw, i1 = min(n_items, i0 + ipw);
     CarryEnv E;
-    E.gbase = tab + (size_t)gstart * g.es;
-    E.rem = active ? g.n - gstart : 0u;
     E.lane = lane;
-    E.q = qp[t];
-    // |x - r * 2eb| as one fused operation differs from the quantiser's two roundings by at most 2^-24 of |r * 2eb|
-    // (|r| < R inside the table) plus a rounding of the difference: well inside R * 2^-21 of the bound
-    E.eb_sure = E.q.eb * (1.0f - (float)g.R * 0x1p-21f);
     E.Rf = (float)g.R;
     E.R = (int)g.R;
     E.row0 = (uint32_t)(uintptr_t)s_tab + (lane & (kCarryCopies - 1u)) * kCarryCopyBytes;
@@ -347,111 +333,181 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
     E.hi = (float)(E.row0 + (kCarryRows - 1u) * kCarryRowBytes);
     E.bias = (float)(E.row0 + (g.R - win_lo + 1u) * kCarryRowBytes);
     E.win_lo = win_lo;
-    E.enc_t = enc_t;
-    E.hist_t = hist_t;
-    E.gstart = gstart;
     E.recs = s_recs + wave * kCarryRecs;
     E.sp_base = (uint32_t)(uintptr_t)stage + lane * 4u;
     E.row_max = CAP + 1u;
-    const uint8_t* const gbase = E.gbase;
-    const uint32_t rem = E.rem;
-    const QParam q = E.q;
-    const float Rf = E.Rf;
-    const bool full = rem >= kW * (uint32_t)S;
-
-    // the group's first elements are asked for before the code table is set up: their way from memory is the longest
+    // where an item's group of this wavefront lies
+    auto locate = [&](uint32_t item, const uint8_t*& gbase, uint32_t& rem) {
+        const uint32_t t = item / bpt, grp = (item % bpt) * 4u + wave;
+        const uint32_t gstart = grp * kGroupEls;
+        gbase = static_cast<const uint8_t*>(payload) + ((size_t)t * g.n + gstart) * g.es;
+        rem = grp < g.G ? g.n - gstart : 0u;
+    };
+    // this call's histogram of a table, for the next call's codebook: the window rows (sum of the copies; everything
+    // else went to memory directly); the counts start again at zero
+    auto merge_counts = [&](uint32_t t) {
+        if (tid < kCarryRows - 2u) {
+            uint32_t s = 0;
+            for (uint32_t c = 0; c < kCarryCopies; ++c) {
+                uint32_t& w = s_tab[c * (kCarryCopyBytes / 4u) + tid + 1u];
+                s += w >> 16;
+                w &= 0xFFFFu;
+            }
+            const uint32_t sym = win_lo + tid;
+            if (s && sym < g.K) atomicAdd(&hist[(size_t)t * g.K + sym], s);
+        }
+    };
+    // the first item's first elements are asked for before anything else: their way from memory is the longest
     float xa[kCarryLoad][4];
     uint32_t va[kCarryLoad];
-    if (active) {
-        if (full) carry_load<F16, VEC, true>(E, 0, xa, va);
+    locate(i0, E.gbase, E.rem);
+    if (E.rem != 0u) {
+        if (E.rem >= kGroupEls) carry_load<F16, VEC, true>(E, 0, xa, va);
         else carry_load<F16, VEC, false>(E, 0, xa, va);
     }
-    // the code table: every row of every copy, counts zero (rows 0 and 256, the escape symbol and everything without a
-    // code take the rare path)
-    for (uint32_t k = tid; k < kCarryCopies * kCarryRows; k += 256) {
-        const uint32_t row = k % kCarryRows;
-        const uint32_t c = win_lo + row - 1u;
-        const uint32_t e = (row >= 1u && row <= kCarryRows - 2u && c < g.K && c != 0u) ? enc_t[c] : 0u;
-        s_tab[(k / kCarryRows) * (kCarryCopyBytes / 4u) + row] = e;  // (length 0: no code; count 0)
-    }
-    __syncthreads();
-    CarryState St;
-    St.acc = 0; St.nbt = 0; St.esc = 0; St.nrec = 0;
-    if (active) {
-        if (full) carry_walk<S, F16, VEC, true>(E, St, xa, va);
-        else carry_walk<S, F16, VEC, false>(E, St, xa, va);
-        if (St.nbt & 31u)  // the chunk's last, partly filled word
-            *reinterpret_cast<lds_u32*>(E.sp_base + min((St.nbt >> 5) + 1u, E.row_max) * (kW * 4u)) =
-                (uint32_t)St.acc << (32u - (St.nbt & 31u));
-    }
-    const uint32_t nw = (St.nbt + 31u) >> 5;
-    const bool spilled = __ballot(nw > CAP) != 0ull;  // uniform: a chunk of this group did not fit its LDS words
-    const uint32_t n_esc = active ? wave_sum(St.esc) : 0u;
-    const uint32_t incl = wave_incl_scan(nw, lane);
-    const uint32_t lane_off = incl - nw;
-    const uint32_t chunk_total = __shfl(incl, 63, 64);
-    const uint32_t total = chunk_total + 2u * n_esc;  // 0 for an idle wavefront
+    uint32_t cur_t = 0xFFFFFFFFu, since_merge = 0;
+    for (uint32_t item = i0; item < i1; ++item) {
+        const uint32_t t = item / bpt, b = item % bpt;
+        // the destination this table belongs to: its container starts `capacity` bytes after the previous one and
+        // its groups are numbered from 0
+        const uint32_t dst = t / g.TD, tl = t - dst * g.TD;
+        const uint16_t* enc_t = enc + (size_t)t * g.K;
+        if (t != cur_t) {  // uniform over the work-group
+            if (cur_t != 0xFFFFFFFFu) {
+                __syncthreads();  // every wavefront has finished counting
+                merge_counts(cur_t);
+                __syncthreads();
+            }
+            // the code table: every row of every copy, counts zero (rows 0 and 256, the escape symbol and everything
+            // without a code take the rare path)
+            for (uint32_t k = tid; k < kCarryCopies * kCarryRows; k += 256) {
+                const uint32_t row = k % kCarryRows;
+                const uint32_t c = win_lo + row - 1u;
+                const uint32_t e = (row >= 1u && row <= kCarryRows - 2u && c < g.K && c != 0u) ? enc_t[c] : 0u;
+                s_tab[(k / kCarryRows) * (kCarryCopyBytes / 4u) + row] = e;  // (length 0: no code; count 0)
+            }
+            __syncthreads();
+            cur_t = t;
+            since_merge = 0;
+        } else if (since_merge == 3u) {  // (a copy's count of a row has 16 bits: three items of 16384 elements a copy fit)
+            __syncthreads();
+            merge_counts(cur_t);
+            __syncthreads();
+            since_merge = 0;
+        }
+        ++since_merge;
+        const uint32_t grp = b * 4 + wave;
+        const bool active = grp < g.G;  // uniform over the wavefront; an idle wavefront only takes part in the barriers
+        const uint32_t gid = tl * g.G + (active ? grp : 0u);  // group number inside the container
+        const uint32_t gstart = grp * kGroupEls;
+        locate(item, E.gbase, E.rem);
+        E.q = qp[t];
+        // |x - r * 2eb| as one fused operation differs from the quantiser's two roundings by at most 2^-24 of |r * 2eb|
+        // (|r| < R inside the table) plus a rounding of the difference: well inside R * 2^-21 of the bound
+        E.eb_sure = E.q.eb * (1.0f - (float)g.R * 0x1p-21f);
+        E.enc_t = enc_t;
+        E.hist_t = hist + (size_t)t * g.K;
+        E.gstart = gstart;
+        const uint8_t* const gbase = E.gbase;
+        const uint32_t rem = E.rem;
+        const bool full = rem >= kGroupEls;
 
-    // The group's words in output order: a lane takes its chunk's words out of its column into registers and puts
-    // them where they go in a run of chunk_total words over the same LDS (the columns are in registers by then).
-    if (active && !spilled) {
-        uint32_t wb[CAP];
-#pragma unroll
-        for (uint32_t k = 0; k < CAP; ++k) wb[k] = *reinterpret_cast<lds_u32*>(E.sp_base + (k + 1u) * (kW * 4u));
-        __builtin_amdgcn_wave_barrier();
-        const uint32_t lin = (uint32_t)(uintptr_t)stage + lane_off * 4u;
-#pragma unroll
-        for (uint32_t k = 0; k < CAP; ++k)
-            if (k < nw) *reinterpret_cast<lds_u32*>(lin + k * 4u) = wb[k];
-        __builtin_amdgcn_wave_barrier();
-    }
-    if (active) {
-        const uint32_t gg = t * g.G + grp;  // the group's number in the whole payload
-        if (lane == 0) {
-            gtot[gg] = total;
-            atomicAdd(&bsum[dst * sum_blocks_per_dest(g) + gid / kSumBlock], total);  // (integer sums: the order does not matter)
-            if (n_esc) atomicAdd(&esc_count[t], n_esc);
+        CarryState St;
+        St.acc = 0; St.nbt = 0; St.esc = 0; St.nrec = 0;
+        if (active) {
+            if (full) carry_walk<S, F16, VEC, true>(E, St, xa, va);
+            else carry_walk<S, F16, VEC, false>(E, St, xa, va);
+            if (St.nbt & 31u)  // the chunk's last, partly filled word
+                *reinterpret_cast<lds_u32*>(E.sp_base + min((St.nbt >> 5) + 1u, E.row_max) * (kW * 4u)) =
+                    (uint32_t)St.acc << (32u - (St.nbt & 31u));
         }
-        out[F.off_chunk + (uint64_t)gid * kW + lane] = (uint8_t)nw;  // (the sections the geometry fixes always fit: the host checks)
-        uint32_t* gw = slots + (size_t)gg * slot_words;
-        if (!spilled) {
-            for (uint32_t k = lane; k < chunk_total; k += 64) gw[k] = stage[k];
-        } else {
-            carry_walk_to_memory<S, F16, VEC>(E, gw + lane_off);
-        }
-        if (n_esc != 0u) {  // uniform over the wavefront
-            uint32_t* rec = gw + chunk_total;
-            if (n_esc <= kCarryRecs) {  // the records were kept on the way
-                for (uint32_t k = lane; k < n_esc; k += 64) {  // (the raw bits come from the payload: the float in hand
-                    const uint32_t off = E.recs[k];             //  need not convert back to the same half-precision bits)
-                    rec[2u * k] = gstart + off;
-                    if constexpr (F16) rec[2u * k + 1] = reinterpret_cast<const uint16_t*>(gbase)[off];
-                    else rec[2u * k + 1] = reinterpret_cast<const uint32_t*>(gbase)[off];
-                }
-            } else {
-                carry_emit_escapes<S, F16, VEC>(rec, lane, gbase, gstart, rem, q, Rf, (int)g.R, enc_t);
+        // the next item's first elements: on their way while this item is written out
+        if (item + 1u < i1) {
+            CarryEnv En = E;
+            locate(item + 1u, En.gbase, En.rem);
+            if (En.rem != 0u) {
+                if (En.rem >= kGroupEls) carry_load<F16, VEC, true>(En, 0, xa, va);
+                else carry_load<F16, VEC, false>(En, 0, xa, va);
             }
         }
+        const uint32_t nw = (St.nbt + 31u) >> 5;
+        const bool spilled = __ballot(nw > CAP) != 0ull;  // uniform: a chunk of this group did not fit its LDS words
+        const uint32_t n_esc = active ? wave_sum(St.esc) : 0u;
+        const uint32_t incl = wave_incl_scan(nw, lane);
+        const uint32_t lane_off = incl - nw;
+        const uint32_t chunk_total = __shfl(incl, 63, 64);
+        const uint32_t total = chunk_total + 2u * n_esc;  // 0 for an idle wavefront
+
+        // The group's words in output order: a lane takes its chunk's words out of its column into registers and puts
+        // them where they go in a run of chunk_total words over the same LDS (the columns are in registers by then).
+        if (active && !spilled) {
+            uint32_t wb[CAP];
+#pragma unroll
+            for (uint32_t k = 0; k < CAP; ++k) wb[k] = *reinterpret_cast<lds_u32*>(E.sp_base + (k + 1u) * (kW * 4u));
+            __builtin_amdgcn_wave_barrier();
+            const uint32_t lin = (uint32_t)(uintptr_t)stage + lane_off * 4u;
+#pragma unroll
+            for (uint32_t k = 0; k < CAP; ++k)
+                if (k < nw) *reinterpret_cast<lds_u32*>(lin + k * 4u) = wb[k];
+            __builtin_amdgcn_wave_barrier();
+        }
+        if (active) {
+            const uint32_t gg = t * g.G + grp;  // the group's number in the whole payload
+            if (lane == 0) {
+                gtot[gg] = total;
+                atomicAdd(&bsum[dst * sum_blocks_per_dest(g) + gid / kSumBlock], total);  // (integer sums: the order does not matter)
+                if (n_esc) atomicAdd(&esc_count[t], n_esc);
+            }
+            // (the sections the geometry fixes always fit: the host checks)
+            (out + (uint64_t)dst * capacity)[F.off_chunk + (uint64_t)gid * kW + lane] = (uint8_t)nw;
+            uint32_t* gw = slots + (size_t)gg * slot_words;
+            if (!spilled) {
+                for (uint32_t k = lane; k < chunk_total; k += 64) gw[k] = stage[k];
+            } else {
+                carry_walk_to_memory<S, F16, VEC>(E, gw + lane_off);
+            }
+            if (n_esc != 0u) {  // uniform over the wavefront
+                uint32_t* rec = gw + chunk_total;
+                if (n_esc <= kCarryRecs) {  // the records were kept on the way
+                    for (uint32_t k = lane; k < n_esc; k += 64) {  // (the raw bits come from the payload: the float in hand
+                        const uint32_t off = E.recs[k];             //  need not convert back to the same half-precision bits)
+                        rec[2u * k] = gstart + off;
+                        if constexpr (F16) rec[2u * k + 1] = reinterpret_cast<const uint16_t*>(gbase)[off];
+                        else rec[2u * k + 1] = reinterpret_cast<const uint32_t*>(gbase)[off];
+                    }
+                } else {
+                    carry_emit_escapes<S, F16, VEC>(rec, lane, gbase, gstart, rem, E.q, E.Rf, (int)g.R, enc_t);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();  // (the staging rows and the records are written again by the next item)
+        }
     }
-    // this call's histogram, for the next call's codebook: the window rows (sum of the copies); everything else
-    // went to memory directly
     __syncthreads();  // every wavefront of the work-group has finished counting
-    if (tid < kCarryRows - 2u) {
-        uint32_t s = 0;
-        for (uint32_t c = 0; c < kCarryCopies; ++c) s += s_tab[c * (kCarryCopyBytes / 4u) + tid + 1u] >> 16;
-        const uint32_t sym = win_lo + tid;
-        if (s && sym < g.K) atomicAdd(&hist_t[sym], s);
+    if (cur_t != 0xFFFFFFFFu) merge_counts(cur_t);
+}
+
+// work-groups the chip holds at once (four per compute unit: LDS and registers are sized for that)
+static inline uint32_t DLC_CAT(carry_resident_, DLC_S)() {
+    static uint32_t n = 0;
+    if (n == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        n = 4u * (uint32_t)cus;
     }
+    return n;
 }
 
 void DLC_CAT(launch_encode_carry_, DLC_S)(const Geom& g, const FixedLayout& F, const void* payload, const Ws& w,
                                           uint64_t epoch, uint8_t* out, uint64_t capacity, uint32_t bpt, hipStream_t s) {
     constexpr int S = DLC_S;
-    dim3 grid(g.T * bpt), block(256);
+    const uint32_t n_items = g.T * bpt;
+    const uint32_t ipw = (n_items + DLC_CAT(carry_resident_, DLC_S)() - 1u) / DLC_CAT(carry_resident_, DLC_S)();
+    dim3 grid((n_items + ipw - 1u) / ipw), block(256);
     const bool f16 = g.dtype == DLC_F16;
 #define DLC_ENC(FF, V)                                                                                                 \
     hipLaunchKernelGGL((k_encode_carry<S, FF, V>), grid, block, 0, s, payload, g, F, w.qp, w.enc, out, capacity, bpt, w.hist, \
-                       w.esc_count, w.slots, (uint64_t)carry_slot_words(g), w.gtot, w.bsum)
+                       w.esc_count, w.slots, (uint64_t)carry_slot_words(g), w.gtot, w.bsum, ipw, n_items)
     if (f16) { if (g.vec) DLC_ENC(true, true); else DLC_ENC(true, false); }
     else { if (g.vec) DLC_ENC(false, true); else DLC_ENC(false, false); }
 #undef DLC_ENC
