@@ -233,6 +233,27 @@ int dlc_set_row_match(dlc_ctx* ctx, const uint8_t* h_flags, void* stream);
  * 1 / (1/cr + net * (1/tc + 1/td)).  0 if an argument is not positive. */
 double dlc_speedup_estimate(double cr, double net_gbps, double tc_gbps, double td_gbps);
 
+/*
+ * Compressor selection (Section III-D "Selection Between Two Encoders", algorithm "Compressor Selection": offline, on
+ * sampled data, per table the compressor with the largest Eq. 2 estimate).  The two compressors are 0 = the entropy
+ * coder alone and 1 = the vector-based LZ step (row matching) in front of it; the context must have been created with
+ * DLC_FLAG_ROW_MATCH and num_dest <= 1 (DLC_ESTATE otherwise) and its bounds must be set.
+ *   d_sample     DEVICE  a sampled payload of the context's geometry, [T][B][D], 16-byte aligned
+ *   d_out, out_capacity, d_out_bytes   DEVICE  as for dlc_compress (scratch for the two trial compressions; on return
+ *                they hold the container of compressor 1 on every table)
+ *   d_rec, rec_capacity  DEVICE  room for the decompressed sample, only used (and required) when the rates are measured
+ *   net_gbps     network bandwidth B of Eq. 2
+ *   h_tc_gbps, h_td_gbps  HOST  double[2]: compression and decompression throughput of compressor 0 and 1, in the unit
+ *                of net_gbps; both NULL: the call measures them on the sample (three calls each way between events)
+ *   h_choice_out HOST    uint8[T]: the compressor chosen for every table; ties go to compressor 0
+ *   h_speedup_out HOST   double[T] or NULL: the chosen compressor's estimate
+ * A table's compression ratio under a compressor is its uncompressed bytes over the bytes dlc_compress attributes to it
+ * (d_out_bytes[1 + t]).  The choice is installed as by dlc_set_row_match.  Synchronises `stream`.
+ */
+int dlc_select_compressors(dlc_ctx* ctx, const void* d_sample, void* d_out, size_t out_capacity, uint64_t* d_out_bytes,
+                           void* d_rec, size_t rec_capacity, double net_gbps, const double* h_tc_gbps, const double* h_td_gbps,
+                           uint8_t* h_choice_out, double* h_speedup_out, void* stream);
+
 /* Waits for `stream`, returns the first device-side error since the previous call (DLC_OK if none), clears it. */
 int dlc_sync_status(dlc_ctx* ctx, void* stream);
 

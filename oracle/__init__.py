@@ -79,6 +79,11 @@ def lib():
         L.orc_compress_rows.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int,
                                         C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.orc_decompress.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.orc_speedup.restype = C.c_double
+        L.orc_speedup.argtypes = [C.c_double, C.c_double, C.c_double, C.c_double]
+        L.orc_select.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double, C.c_void_p, C.c_void_p]
+        L.orc_select_compressors.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int,
+                                             C.c_void_p, C.c_double, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -234,3 +239,40 @@ def decompress(data: np.ndarray, shape, dtype, want_symbols: bool = False):
     if want_symbols:
         return rc, out, sym.reshape(shape)
     return rc, out
+
+
+def speedup(cr: float, net: float, tc: float, td: float) -> float:
+    """Eq. 2."""
+    return float(lib().orc_speedup(cr, net, tc, td))
+
+
+def select(cr, tc, td, net: float):
+    """cr [n_comp, T], tc / td [n_comp] -> (choice int32[T], estimate float64[T]); ties go to the compressor listed first."""
+    cr = np.ascontiguousarray(cr, np.float64)
+    n_comp, T = cr.shape
+    tc = np.ascontiguousarray(tc, np.float64)
+    td = np.ascontiguousarray(td, np.float64)
+    assert tc.shape == (n_comp,) and td.shape == (n_comp,)
+    choice = np.zeros(T, np.int32)
+    best = np.zeros(T, np.float64)
+    rc = lib().orc_select(T, n_comp, _ptr(cr), _ptr(tc), _ptr(td), net, _ptr(choice), _ptr(best))
+    if rc != OK:
+        raise ValueError(f"orc_select: {rc}")
+    return choice, best
+
+
+def select_compressors(payload: np.ndarray, eb, net: float, tc, td, R: int = 512, S: int = 256, LMAX: int = 12):
+    """The offline procedure on a sampled payload: 0 = entropy coder alone, 1 = row matching in front of it."""
+    payload = np.ascontiguousarray(payload)
+    T, B, D = payload.shape
+    ebs = np.ascontiguousarray(np.broadcast_to(np.asarray(eb, np.float32), (T,)))
+    tc = np.ascontiguousarray(tc, np.float64)
+    td = np.ascontiguousarray(td, np.float64)
+    assert tc.shape == (2,) and td.shape == (2,)
+    choice = np.zeros(T, np.int32)
+    best = np.zeros(T, np.float64)
+    rc = lib().orc_select_compressors(_ptr(payload), _dtype_code(payload), T, B, D, R, S, LMAX, _ptr(ebs), net, _ptr(tc),
+                                      _ptr(td), _ptr(choice), _ptr(best))
+    if rc != OK:
+        raise ValueError(f"orc_select_compressors: {rc}")
+    return choice, best

@@ -893,6 +893,69 @@ int orc_compress_rows(const void* payload, int dtype, int T, int64_t B, int64_t 
 }
 
 /* ------------------------------------------------------------------ */
+/* Compressor selection (Section III-D "Selection Between Two          */
+/* Encoders", Eq. 2, Algorithm "Compressor Selection").                */
+/* ------------------------------------------------------------------ */
+/* Eq. 2: the speed-up of compress + send + decompress over sending raw, for compression ratio cr, network
+ * bandwidth net and compression / decompression throughputs tc, td (one unit for all three).  0 when an
+ * argument is not positive. */
+double orc_speedup(double cr, double net, double tc, double td) {
+    if (!(cr > 0.0) || !(net > 0.0) || !(tc > 0.0) || !(td > 0.0)) return 0.0;
+    return 1.0 / (1.0 / cr + net * (1.0 / tc + 1.0 / td));
+}
+
+/* The algorithm's loop over tables with the speed-ups already estimated from a sample: cr is [n_comp][T]
+ * (compressor-major), tc and td are [n_comp].  Per table the compressor with the largest estimate wins; between
+ * equal estimates the one listed first.  choice[t] gets its index, best[t] (optional) its estimate. */
+int orc_select(int T, int n_comp, const double* cr, const double* tc, const double* td, double net, int32_t* choice,
+               double* best) {
+    if (T < 1 || n_comp < 1 || !cr || !tc || !td || !choice) return ORC_EINVAL;
+    for (int t = 0; t < T; ++t) {
+        int arg = 0;
+        double top = orc_speedup(cr[t], net, tc[0], td[0]);
+        for (int c = 1; c < n_comp; ++c) {
+            double s = orc_speedup(cr[(size_t)c * T + t], net, tc[c], td[c]);
+            if (s > top) {
+                top = s;
+                arg = c;
+            }
+        }
+        choice[t] = arg;
+        if (best) best[t] = top;
+    }
+    return ORC_OK;
+}
+
+/* The whole procedure on a sampled payload with the two compressors of this path: 0 = the entropy coder alone,
+ * 1 = the vector-based LZ step (row matching) in front of it.  Both compress the sample at the given bounds; a
+ * table's ratio under a compressor is its uncompressed bytes over the bytes the container attributes to it. */
+int orc_select_compressors(const void* payload, int dtype, int T, int64_t B, int64_t D, int R, int S, int LMAX,
+                           const float* eb, double net, const double* tc /* 2 */, const double* td /* 2 */,
+                           int32_t* choice /* T */, double* best /* T, optional */) {
+    if (!payload || !eb || !tc || !td || !choice || T < 1) return ORC_EINVAL;
+    size_t cap = orc_compress_bound(dtype, T, B, D, R, S, LMAX);
+    if (cap == 0) return ORC_EINVAL;
+    cap += (size_t)T * (16 + 4 * (size_t)B) + 16;
+    uint8_t* out = (uint8_t*)malloc(cap);
+    uint64_t* sizes = (uint64_t*)malloc(sizeof(uint64_t) * (size_t)(1 + T));
+    uint8_t* flags = (uint8_t*)malloc((size_t)T);
+    double* cr = (double*)malloc(sizeof(double) * 2 * (size_t)T);
+    int rc = (out && sizes && flags && cr) ? ORC_OK : ORC_ENOMEM;
+    const double raw = (double)B * (double)D * (dtype == ORC_F16 ? 2.0 : 4.0);
+    for (int c = 0; c < 2 && rc == ORC_OK; ++c) {
+        memset(flags, c, (size_t)T);
+        rc = orc_compress_rows(payload, dtype, T, B, D, R, S, LMAX, eb, out, cap, sizes, flags);
+        for (int t = 0; t < T && rc == ORC_OK; ++t) cr[(size_t)c * T + t] = raw / (double)sizes[1 + t];
+    }
+    if (rc == ORC_OK) rc = orc_select(T, 2, cr, tc, td, net, choice, best);
+    free(out);
+    free(sizes);
+    free(flags);
+    free(cr);
+    return rc;
+}
+
+/* ------------------------------------------------------------------ */
 /* Decoder: mirrors the container; bit-by-bit canonical decoding with  */
 /* the first code of each length (no lookup table).                    */
 /* ------------------------------------------------------------------ */

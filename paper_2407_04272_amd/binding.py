@@ -41,6 +41,7 @@ class ControllerParams(C.Structure):
 EXPORTS = ["dlc_create", "dlc_destroy", "dlc_compress_bound", "dlc_workspace_bytes", "dlc_stats",
            "dlc_set_error_bounds", "dlc_compress", "dlc_decompress", "dlc_sync_status", "dlc_quantize",
            "dlc_read_histogram", "dlc_read_codebook", "dlc_read_row_refs", "dlc_set_row_match", "dlc_speedup_estimate",
+           "dlc_select_compressors",
            "dlc_profile_enable", "dlc_profile_read", "dlc_strerror"]
 
 _lib = None
@@ -79,6 +80,7 @@ def lib():
         L.dlc_set_row_match.argtypes = [vp, vp, vp]
         L.dlc_speedup_estimate.argtypes = [C.c_double] * 4
         L.dlc_speedup_estimate.restype = C.c_double
+        L.dlc_select_compressors.argtypes = [vp, vp, vp, C.c_size_t, vp, vp, C.c_size_t, C.c_double, vp, vp, vp, vp, vp]
         L.dlc_profile_enable.argtypes = [vp, i32]
         L.dlc_profile_read.argtypes = [vp, i32, vp, vp, vp]
         L.dlc_strerror.argtypes = [i32]
@@ -216,6 +218,23 @@ class Context:
     def set_row_match(self, flags=None, stream=None):
         f = None if flags is None else np.ascontiguousarray(np.broadcast_to(np.asarray(flags, np.uint8), (self.T,)))
         _check(lib().dlc_set_row_match(self._h, _np_ptr(f), _stream_ptr(stream)), "dlc_set_row_match")
+
+    def select_compressors(self, sample, out, out_bytes, net_gbps, tc_gbps=None, td_gbps=None, rec=None, capacity=None,
+                           stream=None):
+        """Per table: entropy coder alone (0) or row matching in front of it (1), by the Eq. 2 estimate on `sample`.
+        tc_gbps / td_gbps: the two compressors' rates, or None to have them measured (then `rec` takes the decoded
+        sample).  Returns (choice uint8[T], estimate float64[T]); the choice is installed in the context."""
+        tc = None if tc_gbps is None else np.ascontiguousarray(tc_gbps, np.float64)
+        td = None if td_gbps is None else np.ascontiguousarray(td_gbps, np.float64)
+        choice = np.zeros(self.T, np.uint8)
+        est = np.zeros(self.T, np.float64)
+        cap = out.numel() * out.element_size() if capacity is None else capacity
+        rec_ptr = None if rec is None else C.c_void_p(rec.data_ptr())
+        rec_cap = 0 if rec is None else rec.numel() * rec.element_size()
+        _check(lib().dlc_select_compressors(self._h, C.c_void_p(sample.data_ptr()), C.c_void_p(out.data_ptr()), cap, C.c_void_p(out_bytes.data_ptr()), rec_ptr,
+                                            rec_cap, float(net_gbps), _np_ptr(tc), _np_ptr(td), _np_ptr(choice),
+                                            _np_ptr(est), _stream_ptr(stream)), "dlc_select_compressors")
+        return choice, est
 
     def read_row_refs(self, stream=None) -> np.ndarray:
         r = np.zeros((self.ND * self.T, self.B), np.uint32)

@@ -1,4 +1,5 @@
 // Host side of libdlc: context, argument checks, workspace, error-bound controller, C ABI.
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -389,6 +390,70 @@ extern "C" int dlc_read_row_refs(dlc_ctx* c, uint32_t* h_ref, void* stream) {
 extern "C" double dlc_speedup_estimate(double cr, double net_gbps, double tc_gbps, double td_gbps) {
     if (!(cr > 0.0) || !(net_gbps > 0.0) || !(tc_gbps > 0.0) || !(td_gbps > 0.0)) return 0.0;
     return 1.0 / (1.0 / cr + net_gbps * (1.0 / tc_gbps + 1.0 / td_gbps));
+}
+
+// The offline procedure of the algorithm "Compressor Selection" (Section III-D) for the two compressors of this library.
+extern "C" int dlc_select_compressors(dlc_ctx* c, const void* d_sample, void* d_out, size_t out_capacity, uint64_t* d_out_bytes,
+                                      void* d_rec, size_t rec_capacity, double net_gbps, const double* h_tc_gbps,
+                                      const double* h_td_gbps, uint8_t* h_choice_out, double* h_speedup_out, void* stream) {
+    if (!c || !h_choice_out || !(net_gbps > 0.0)) return DLC_EINVAL;
+    if ((h_tc_gbps == nullptr) != (h_td_gbps == nullptr)) return DLC_EINVAL;
+    if (!c->g.lz || c->g.ND != 1) return DLC_ESTATE;  // needs both compressors, and one container
+    const bool measure = h_tc_gbps == nullptr;
+    if (measure && !d_rec) return DLC_EINVAL;
+    const uint32_t T = c->g.T;
+    hipStream_t s = (hipStream_t)stream;
+    const double raw_table = (double)c->g.n * c->g.es, raw_all = raw_table * T;
+    std::vector<uint64_t> sizes[2];
+    double tc[2], td[2];
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (measure && (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)) {
+        if (e0) (void)hipEventDestroy(e0);
+        return DLC_EHIP;
+    }
+    int rc = DLC_OK;
+    std::vector<uint8_t> flags(T);
+    for (int comp = 0; comp < 2 && rc == DLC_OK; ++comp) {
+        std::fill(flags.begin(), flags.end(), (uint8_t)comp);
+        rc = dlc_set_row_match(c, flags.data(), stream);
+        if (rc == DLC_OK) rc = dlc_compress(c, d_sample, d_out, out_capacity, d_out_bytes, stream);
+        if (rc == DLC_OK) rc = dlc_sync_status(c, stream);
+        if (rc != DLC_OK) break;
+        sizes[comp].resize(1 + (size_t)T);
+        if (hipMemcpy(sizes[comp].data(), d_out_bytes, 8 * (1 + (size_t)T), hipMemcpyDeviceToHost) != hipSuccess) { rc = DLC_EHIP; break; }
+        if (measure) {  // the rates of this compressor on the sample: a few calls between two events, each direction
+            const int reps = 3;
+            float ms = 0.f;
+            if (hipEventRecord(e0, s) != hipSuccess) { rc = DLC_EHIP; break; }
+            for (int i = 0; i < reps && rc == DLC_OK; ++i) rc = dlc_compress(c, d_sample, d_out, out_capacity, d_out_bytes, stream);
+            if (rc != DLC_OK) break;
+            if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { rc = DLC_EHIP; break; }
+            tc[comp] = raw_all * reps / ((double)ms * 1e6);
+            if (hipEventRecord(e0, s) != hipSuccess) { rc = DLC_EHIP; break; }
+            for (int i = 0; i < reps && rc == DLC_OK; ++i) rc = dlc_decompress(c, d_out, (size_t)sizes[comp][0], d_rec, rec_capacity, stream);
+            if (rc != DLC_OK) break;
+            if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { rc = DLC_EHIP; break; }
+            td[comp] = raw_all * reps / ((double)ms * 1e6);
+            rc = dlc_sync_status(c, stream);
+        } else {
+            tc[comp] = h_tc_gbps[comp];
+            td[comp] = h_td_gbps[comp];
+        }
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (rc != DLC_OK) return rc;
+    for (uint32_t t = 0; t < T; ++t) {
+        // per table the compressor with the larger estimate; the entropy coder alone (listed first) when they are equal
+        const double s0 = dlc_speedup_estimate(raw_table / (double)sizes[0][1 + t], net_gbps, tc[0], td[0]);
+        const double s1 = dlc_speedup_estimate(raw_table / (double)sizes[1][1 + t], net_gbps, tc[1], td[1]);
+        flags[t] = s1 > s0 ? 1 : 0;
+        h_choice_out[t] = flags[t];
+        if (h_speedup_out) h_speedup_out[t] = s1 > s0 ? s1 : s0;
+    }
+    return dlc_set_row_match(c, flags.data(), stream);
 }
 
 extern "C" int dlc_sync_status(dlc_ctx* c, void* stream) {

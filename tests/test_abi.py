@@ -61,9 +61,20 @@ def test_host_only_entry_points():
     plain = b.dlc_compress_bound(b.make_config(b.F32, 4, 64, 8))
     rows = b.dlc_compress_bound(b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_ROW_MATCH))
     assert rows - plain in (4 * 4 * 64, 4 * 4 * 64 + 12)
-    # Eq. 2
-    assert abs(b.dlc_speedup_estimate(10.0, 25.0, 2000.0, 4000.0) - 1.0 / (0.1 + 25.0 * (1 / 2000.0 + 1 / 4000.0))) < 1e-12
-    assert b.dlc_speedup_estimate(0.0, 25.0, 2000.0, 4000.0) == 0.0
+
+
+def test_speedup_estimate_is_the_oracles_eq2():
+    """Eq. 2 in the library against the oracle's (itself pinned to exact rational arithmetic), bit for bit."""
+    import numpy as np
+    import oracle
+    from paper_2407_04272_amd import binding as b
+    rng = np.random.default_rng(8)
+    for _ in range(500):
+        cr, net, tc, td = (float(v) for v in np.exp(rng.uniform(-3, 8, 4)))
+        assert b.dlc_speedup_estimate(cr, net, tc, td) == oracle.speedup(cr, net, tc, td)
+    for bad in ((0.0, 25.0, 2000.0, 4000.0), (10.0, -1.0, 2000.0, 4000.0), (10.0, 25.0, 0.0, 4000.0),
+                (10.0, 25.0, 2000.0, float("nan"))):
+        assert b.dlc_speedup_estimate(*bad) == 0.0 and oracle.speedup(*bad) == 0.0
 
 
 def test_compress_bound_matches_oracle_formula():

@@ -159,3 +159,50 @@ def test_random_shapes_rows_and_statistics():
         for t in range(T):
             assert (st[t].n_unique_raw, st[t].n_unique_quant) == (ost[t].n_unique_raw, ost[t].n_unique_quant), (T, B, D, t)
             assert st[t].min == ost[t].min and st[t].max == ost[t].max
+
+
+def test_compressor_selection_matches_the_oracle():
+    """Section III-D, algorithm "Compressor Selection": the per-table choice between the entropy coder alone and row
+    matching in front of it, made by the library on a sample, against the oracle's choice from its own containers; the
+    container written afterwards is the oracle's container for that choice."""
+    import torch
+    from paper_2407_04272_amd import binding as b
+    rng = np.random.default_rng(21)
+    B, D, S = 900, 32, 128
+    distinct = (rng.standard_normal((B, D)) * 0.02).astype(np.float32)                       # no repeats
+    few = (rng.standard_normal((5, D)) * 0.02).astype(np.float32)[rng.integers(0, 5, B)]     # five rows, repeated
+    some = (rng.standard_normal((300, D)) * 0.02).astype(np.float32)[rng.integers(0, 300, B)]
+    x = np.stack([distinct, few, some, few[::-1].copy(), distinct[::-1].copy()])
+    T = x.shape[0]
+    ebs = np.full(T, 1e-3, np.float32)
+    cfg = b.make_config(b.F32, T, B, D, R, S, 12, b.FLAG_ROW_MATCH)
+    ctx = b.Context(cfg)
+    ctx.set_error_bounds(eb=ebs)
+    cap = b.dlc_compress_bound(cfg)
+    d = to_device(x)
+    out = torch.zeros(cap, dtype=torch.uint8, device="cuda")
+    sizes = torch.zeros(1 + T, dtype=torch.int64, device="cuda")
+    seen = set()
+    for net, tc, td in ((25.0, (2000.0, 1400.0), (4000.0, 2500.0)), (5000.0, (2000.0, 1400.0), (4000.0, 2500.0)),
+                        (400.0, (2000.0, 1400.0), (4000.0, 2500.0)), (25.0, (2000.0, 2000.0), (4000.0, 4000.0))):
+        print("selection at", net, tc, td, flush=True)
+        choice, est = ctx.select_compressors(d, out, sizes, net, tc, td)
+        want, want_est = oracle.select_compressors(x, ebs, net, tc, td, R, S, 12)
+        assert np.array_equal(choice.astype(np.int32), want), (net, choice, want)
+        assert np.array_equal(est, want_est)                       # same sizes, same arithmetic: the same doubles
+        seen.add(tuple(int(v) for v in choice))
+        assert ctx.compress(d, out, sizes, capacity=cap) == 0 and ctx.sync_status() == 0
+        sz = sizes.cpu().numpy().astype(np.uint64)
+        o = oracle.compress(x, ebs, R, S, 12, row_match=want.astype(np.uint8))
+        assert np.array_equal(sz, o.sizes)
+        assert np.array_equal(out[:int(sz[0])].cpu().numpy(), o.data)
+    assert len(seen) >= 2                                          # the cases do not all choose alike
+    # rates measured by the call itself: a valid choice (0 / 1 per table) and a positive estimate
+    rec = torch.empty_like(d)
+    choice, est = ctx.select_compressors(d, out, sizes, 25.0, rec=rec)
+    assert set(np.unique(choice)) <= {0, 1} and np.all(est > 0)
+    # a context without both compressors cannot select
+    plain = b.Context(b.make_config(b.F32, T, B, D, R, S, 12))
+    plain.set_error_bounds(eb=ebs)
+    with pytest.raises(b.DlcError):
+        plain.select_compressors(d, out, sizes, 25.0, tc, td)
