@@ -124,8 +124,9 @@ enum { DLC_FLAG_FUSED = 1, DLC_FLAG_CARRY_CODEBOOK = 2, DLC_FLAG_ROW_MATCH = 4 }
  * in parallel.  Per table: dlc_set_row_match switches it on and off (all on after dlc_create), which is what the
  * compressor selection of Section III-D (Eq. 2, dlc_speedup_estimate) decides offline.  Needs dim % 4 == 0; not
  * together with the other flags; num_dest * num_tables <= 65535.  With num_dest > 1 rows are matched inside a
- * destination's piece (a container never refers to another).  The search hashes rows; two different rows with one 64-bit hash
- * (at worst 2^-48 for a pair of rows, far less for most contents) cost a match, never correctness. */
+ * destination's piece (a container never refers to another).  The search hashes rows and compares every candidate
+ * element by element; rows whose hashes meet are sorted out the long way, so the references are always those of the
+ * definition. */
 
 /* Per-table statistics of a sampled batch: what Eq. 1 needs, plus the value range. */
 typedef struct {
@@ -264,6 +265,9 @@ int dlc_sync_status(dlc_ctx* ctx, void* stream);
  *   dlc_read_codebook  code lengths (uint8[T][2R]) and codewords (uint16[T][2R]) left by the last dlc_compress
  *   dlc_read_row_refs  row references (uint32[num_dest * T][B], HOST) left by the last dlc_compress
  *                      (DLC_FLAG_ROW_MATCH only)
+ *   dlc_set_row_hash_multipliers  replaces the multipliers of the row hash that the row search uses (uint32[dim / 4][8],
+ *                      HOST; DLC_FLAG_ROW_MATCH only).  The references do not depend on them; with all of them zero
+ *                      every row has the same hash, which is how the tests reach the handling of equal hashes
  * With DLC_FLAG_CARRY_CODEBOOK the histogram is still that of the last call's payload, and the codebook is the one
  * built from it for the NEXT call (escape count raised by one), not the one the last call's container was coded with.
  */
@@ -271,6 +275,7 @@ int dlc_quantize(dlc_ctx* ctx, const void* d_payload, uint16_t* d_symbols, void*
 int dlc_read_histogram(dlc_ctx* ctx, uint32_t* h_hist, void* stream);
 int dlc_read_codebook(dlc_ctx* ctx, uint8_t* h_len, uint16_t* h_code, void* stream);
 int dlc_read_row_refs(dlc_ctx* ctx, uint32_t* h_ref, void* stream);
+int dlc_set_row_hash_multipliers(dlc_ctx* ctx, const uint32_t* h_mult, void* stream);
 
 /*
  * Kernel timing with HIP events on the caller's stream.

@@ -41,7 +41,7 @@ class ControllerParams(C.Structure):
 EXPORTS = ["dlc_create", "dlc_destroy", "dlc_compress_bound", "dlc_workspace_bytes", "dlc_stats",
            "dlc_set_error_bounds", "dlc_compress", "dlc_decompress", "dlc_sync_status", "dlc_quantize",
            "dlc_read_histogram", "dlc_read_codebook", "dlc_read_row_refs", "dlc_set_row_match", "dlc_speedup_estimate",
-           "dlc_select_compressors",
+           "dlc_select_compressors", "dlc_set_row_hash_multipliers",
            "dlc_profile_enable", "dlc_profile_read", "dlc_strerror"]
 
 _lib = None
@@ -78,6 +78,7 @@ def lib():
         L.dlc_read_codebook.argtypes = [vp, vp, vp, vp]
         L.dlc_read_row_refs.argtypes = [vp, vp, vp]
         L.dlc_set_row_match.argtypes = [vp, vp, vp]
+        L.dlc_set_row_hash_multipliers.argtypes = [vp, vp, vp]
         L.dlc_speedup_estimate.argtypes = [C.c_double] * 4
         L.dlc_speedup_estimate.restype = C.c_double
         L.dlc_select_compressors.argtypes = [vp, vp, vp, C.c_size_t, vp, vp, C.c_size_t, C.c_double, vp, vp, vp, vp, vp]
@@ -235,6 +236,11 @@ class Context:
                                             rec_cap, float(net_gbps), _np_ptr(tc), _np_ptr(td), _np_ptr(choice),
                                             _np_ptr(est), _stream_ptr(stream)), "dlc_select_compressors")
         return choice, est
+
+    def set_row_hash_multipliers(self, mult, stream=None):
+        m = np.ascontiguousarray(mult, np.uint32)
+        assert m.size == 8 * (self.D // 4)
+        _check(lib().dlc_set_row_hash_multipliers(self._h, _np_ptr(m), _stream_ptr(stream)), "dlc_set_row_hash_multipliers")
 
     def read_row_refs(self, stream=None) -> np.ndarray:
         r = np.zeros((self.ND * self.T, self.B), np.uint32)

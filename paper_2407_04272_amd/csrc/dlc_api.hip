@@ -387,6 +387,13 @@ extern "C" int dlc_read_row_refs(dlc_ctx* c, uint32_t* h_ref, void* stream) {
     return hipMemcpy(h_ref, c->ws.rm_ref, 4ull * c->g.T * c->g.B, hipMemcpyDeviceToHost) == hipSuccess ? DLC_OK : DLC_EHIP;
 }
 
+extern "C" int dlc_set_row_hash_multipliers(dlc_ctx* c, const uint32_t* h_mult, void* stream) {
+    if (!c || !h_mult) return DLC_EINVAL;
+    if (!c->g.lz) return DLC_ESTATE;
+    if (hipMemcpyAsync(c->ws.rm_mult, h_mult, 32 * (size_t)(c->g.D / 4u), hipMemcpyHostToDevice, (hipStream_t)stream) != hipSuccess) return DLC_EHIP;
+    return hipStreamSynchronize((hipStream_t)stream) == hipSuccess ? DLC_OK : DLC_EHIP;
+}
+
 extern "C" double dlc_speedup_estimate(double cr, double net_gbps, double tc_gbps, double td_gbps) {
     if (!(cr > 0.0) || !(net_gbps > 0.0) || !(tc_gbps > 0.0) || !(td_gbps > 0.0)) return 0.0;
     return 1.0 / (1.0 / cr + net_gbps * (1.0 / tc_gbps + 1.0 / td_gbps));

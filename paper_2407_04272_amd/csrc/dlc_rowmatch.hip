@@ -8,7 +8,8 @@
 // work-groups ever meet in a set and no atomic leaves the LDS), the smallest row index of a hash owning it; then
 // every other row is compared with the owner of its hash element by element.  A row whose hash meets a different
 // row's (three multilinear sums modulo 2^32 with 24-bit multipliers: 2^-48 for a pair of rows at worst, far less
-// for most) stays a coded row: the container is valid, one match is lost.
+// for most) is looked up the long way, among the earlier rows with that hash, so the references are those of the
+// definition (the first row with the content) whatever the hashes do.
 #include <algorithm>
 
 #include "dlc_internal.h"
@@ -281,8 +282,8 @@ __device__ __forceinline__ RmPiece<PW> rm_load_piece(const uint32_t* plane, size
 
 template <bool F16, uint32_t PW>
 __global__ __launch_bounds__(256) void k_rm_owner(const void* payload, Geom g, const QParam* qp, const uint8_t* on,
-                                                  const uint32_t* rowown, uint32_t* ref, uint8_t* sym_plane, uint32_t* hist, uint32_t waves_grid,
-                                                  uint32_t logL) {
+                                                  const uint32_t* rowown, const uint64_t* rowhash, uint32_t* ref, uint8_t* sym_plane,
+                                                  uint32_t* hist, uint32_t waves_grid, uint32_t logL) {
     extern __shared__ __align__(16) uint32_t lh[];  // what to take off the counts: window [kWinBins + 1][kWinCopies] | exact [K]
     const uint32_t t = blockIdx.y;
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
@@ -364,7 +365,34 @@ __global__ __launch_bounds__(256) void k_rm_owner(const void* payload, Geom g, c
 #pragma unroll
             for (uint32_t s = 0; s < kRmSteps; ++s) {
                 const uint32_t row = row0 + (s0 + s) * rps + team;
-                const bool same = need[s] && (__ballot(differ[s]) & teammask) == 0ull;  // the same for all lanes of a team
+                bool same = need[s] && (__ballot(differ[s]) & teammask) == 0ull;  // the same for all lanes of a team
+                // A row that is not its hash's owner's equal: two different rows with one hash.  The first earlier row
+                // with the row's content, if there is one, has that hash too: the whole wavefront looks through the
+                // earlier rows with it, one such row at a time (never expected; slow and plain).
+                uint64_t coll = __ballot(need[s] && !same && sub == 0u);
+                while (coll != 0ull) {  // uniform over the wavefront
+                    const uint32_t leader = (uint32_t)__ffsll((unsigned long long)coll) - 1u;
+                    coll &= coll - 1ull;
+                    const uint32_t crow = row0 + (s0 + s) * rps + (leader >> logL);
+                    const uint64_t h = rowhash[(size_t)t * g.B + crow];
+                    uint32_t found = crow;
+                    for (uint32_t j0 = 0; j0 < crow && found == crow; j0 += 64u) {
+                        const uint32_t j = j0 + lane;
+                        uint64_t m = __ballot(j < crow && rowhash[(size_t)t * g.B + j] == h);
+                        while (m != 0ull && found == crow) {
+                            const uint32_t jj = j0 + (uint32_t)__ffsll((unsigned long long)m) - 1u;
+                            m &= m - 1ull;
+                            bool d = false;
+                            for (uint32_t e = lane; e < g.D; e += 64u)
+                                d = d || rm_identity<F16>(tab, crow * g.D + e, q, Rf, (int)g.R) != rm_identity<F16>(tab, jj * g.D + e, q, Rf, (int)g.R);
+                            if (__ballot(d) == 0ull) found = jj;
+                        }
+                    }
+                    if (found != crow && team == (leader >> logL)) {
+                        own[s] = found;
+                        same = true;
+                    }
+                }
                 if (sub == 0 && s0 + s < L && row < g.B) ref_t[row] = same ? own[s] : row;
                 if (!same) continue;
                 for (uint32_t p = sub; p < W; p += L) {
@@ -441,7 +469,7 @@ hipError_t launch_row_match(const Geom& g, const void* payload, const Ws& w, hip
         hipError_t e = launch_row_sets(g, 1u, w.rm_on, w.rm_hash, w.rm_own, nullptr, nullptr, s);
         if (e != hipSuccess) return e;
     }
-#define DLC_RM_OWNER(FF, PP) hipLaunchKernelGGL((k_rm_owner<FF, PP>), grid, block, sm, s, payload, g, w.qp, w.rm_on, w.rm_own, w.rm_ref, w.sym_plane, w.hist, waves_grid, logL)
+#define DLC_RM_OWNER(FF, PP) hipLaunchKernelGGL((k_rm_owner<FF, PP>), grid, block, sm, s, payload, g, w.qp, w.rm_on, w.rm_own, w.rm_hash, w.rm_ref, w.sym_plane, w.hist, waves_grid, logL)
     if (g.dtype == DLC_F16) { if (pw == 4u) DLC_RM_OWNER(true, 4); else DLC_RM_OWNER(true, 1); }
     else { if (pw == 4u) DLC_RM_OWNER(false, 4); else DLC_RM_OWNER(false, 1); }
 #undef DLC_RM_OWNER

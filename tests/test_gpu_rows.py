@@ -20,7 +20,7 @@ def _lookups(T, B, D, seed, rows=60, sigma=0.02, dtype=np.float32):
     return x.astype(dtype)
 
 
-def _compress(x, ebs, S, flags_per_table=None):
+def _compress(x, ebs, S, flags_per_table=None, zero_hash=False):
     import torch
     from paper_2407_04272_amd import binding as b
     T, B, D = x.shape
@@ -29,6 +29,8 @@ def _compress(x, ebs, S, flags_per_table=None):
     ctx = b.Context(cfg)
     if flags_per_table is not None:
         ctx.set_row_match(flags_per_table)
+    if zero_hash:
+        ctx.set_row_hash_multipliers(np.zeros(8 * (D // 4), np.uint32))
     cap = b.dlc_compress_bound(cfg)
     d = to_device(x)
     out = torch.full((cap + 64,), 0xA5, dtype=torch.uint8, device="cuda")
@@ -206,3 +208,32 @@ def test_compressor_selection_matches_the_oracle():
     plain.set_error_bounds(eb=ebs)
     with pytest.raises(b.DlcError):
         plain.select_compressors(d, out, sizes, 25.0, tc, td)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_rows_with_equal_hashes_still_get_the_first_occurrence(dtype):
+    """With every multiplier of the row hash zero all rows of a table hash alike: every repeated row but the
+    repeats of the table's first row meets a different row under its hash.  References and container must be the
+    oracle's all the same (the references are defined by content, not by the hash)."""
+    import torch
+    for (T, B, D, S) in ((2, 300, 16, 64), (1, 130, 40, 128), (1, 70, 260, 64)):
+        print("equal hashes", T, B, D, S, np.dtype(dtype).name, flush=True)
+        x = _lookups(T, B, D, 33 + D, rows=25, dtype=dtype)
+        big = 1e9 if dtype == np.float32 else 6e4
+        x[0, 3, 1] = big
+        x[0, 8] = x[0, 3]                       # a repeated row with an escape
+        x[0, 11] = x[0, 3]
+        x[0, 11, 1] = -big                      # the escape's raw bits differ: not a repeat
+        ebs = np.full(T, 1e-3 if dtype == np.float32 else 4e-3, np.float32)
+        ctx, d, out, data, sizes = _compress(x, ebs, S, zero_hash=True)
+        refs = ctx.read_row_refs()
+        for t in range(T):
+            s_t, _ = oracle.quantize(x[t:t + 1], float(ebs[t]), R)
+            assert np.array_equal(refs[t], first_occurrence(x[t:t + 1], s_t)[0]), t
+        o = oracle.compress(x, ebs, R, S, 12, row_match=True)
+        assert o.rc == 0 and np.array_equal(sizes, o.sizes) and np.array_equal(data, o.data)
+        rec = torch.full_like(d, 7.0)
+        assert ctx.decompress(out, int(sizes[0]), rec) == 0 and ctx.sync_status() == 0
+        rc, orec = oracle.decompress(o.data, x.shape, x.dtype)
+        u = np.uint32 if dtype == np.float32 else np.uint16
+        assert rc == 0 and np.array_equal(rec.cpu().numpy().view(u), orec.view(u))
