@@ -64,7 +64,8 @@ typedef enum {
     DLC_ECAPACITY = -3, /* output buffer too small; nothing was written past its capacity */
     DLC_ECORRUPT = -4,  /* container fails validation */
     DLC_EHIP = -5,      /* a HIP runtime call failed */
-    DLC_ESTATE = -6     /* call order (bounds not set), or an internal invariant failed */
+    DLC_ESTATE = -6,    /* call order (bounds not set), or an internal invariant failed */
+    DLC_ELIMIT = -7     /* a size beyond the fixed maximum of an entry point that allocates nothing */
 } dlc_status;
 
 /* Geometry and format parameters of one payload (Section III-D leaves them open). */
@@ -224,6 +225,24 @@ int dlc_compress(dlc_ctx* ctx, const void* d_payload, void* d_out, size_t out_ca
  */
 int dlc_decompress(dlc_ctx* ctx, const void* d_comp, size_t comp_bytes, void* d_payload_out, size_t out_capacity,
                    void* stream);
+
+/*
+ * dlc_decompress for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  It takes no context: the geometry comes from `cfg` (the one the container was
+ * made with), and the decode kernels' workspace (status word, per-table counters, the row references' table) is a
+ * fixed array inside the library, DLC_STATIC_MAX_TABLES tables' worth (about 160 KiB, held on every GPU the library
+ * is loaded on until the process ends).  The call makes no hipMalloc, hipFree or other allocating call.
+ *   cfg            HOST    as for dlc_create; num_tables * max(num_dest, 1) <= DLC_STATIC_MAX_TABLES, else DLC_ELIMIT
+ *   d_comp, comp_bytes, d_payload_out, out_capacity   as for dlc_decompress
+ *   d_status       DEVICE  int32[1], written on `stream` after the kernels: DLC_OK, or what dlc_sync_status would
+ *                          have returned for this call (DLC_ECORRUPT for a container that fails validation)
+ * Asynchronous on `stream`; output and status are the same as dlc_decompress's on the same container.  All calls on
+ * one GPU share the one array: calls that overlap on a GPU (two streams, two threads) race and must be serialised
+ * by the caller.  The first call on a device looks up the array's address there (no allocation either).
+ */
+#define DLC_STATIC_MAX_TABLES 4096
+int dlc_decompress_static(const dlc_config* cfg, const void* d_comp, size_t comp_bytes, void* d_payload_out,
+                          size_t out_capacity, int32_t* d_status, void* stream);
 
 /* Row matching per table (contexts with DLC_FLAG_ROW_MATCH): h_flags HOST uint8[num_tables] (the same for every
  * destination), non-zero = store the table's repeated rows as references; NULL = all tables.  Synchronises `stream`. */

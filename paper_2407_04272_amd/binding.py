@@ -14,7 +14,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libdlc.so")
 
 F32, F16 = 0, 1
-OK, EINVAL, ENOMEM, ECAPACITY, ECORRUPT, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6
+OK, EINVAL, ENOMEM, ECAPACITY, ECORRUPT, EHIP, ESTATE, ELIMIT = 0, -1, -2, -3, -4, -5, -6, -7
+STATIC_MAX_TABLES = 4096
 CLASS_SMALL, CLASS_MEDIUM, CLASS_LARGE = 0, 1, 2
 DECAY_NONE, DECAY_STEPWISE, DECAY_DROP, DECAY_LINEAR, DECAY_LOG = 0, 1, 2, 3, 4
 
@@ -41,7 +42,7 @@ class ControllerParams(C.Structure):
 EXPORTS = ["dlc_create", "dlc_destroy", "dlc_compress_bound", "dlc_workspace_bytes", "dlc_stats",
            "dlc_set_error_bounds", "dlc_compress", "dlc_decompress", "dlc_sync_status", "dlc_quantize",
            "dlc_read_histogram", "dlc_read_codebook", "dlc_read_row_refs", "dlc_set_row_match", "dlc_speedup_estimate",
-           "dlc_select_compressors", "dlc_set_row_hash_multipliers",
+           "dlc_select_compressors", "dlc_set_row_hash_multipliers", "dlc_decompress_static",
            "dlc_profile_enable", "dlc_profile_read", "dlc_strerror"]
 
 _lib = None
@@ -79,6 +80,7 @@ def lib():
         L.dlc_read_row_refs.argtypes = [vp, vp, vp]
         L.dlc_set_row_match.argtypes = [vp, vp, vp]
         L.dlc_set_row_hash_multipliers.argtypes = [vp, vp, vp]
+        L.dlc_decompress_static.argtypes = [C.POINTER(Config), vp, C.c_size_t, vp, C.c_size_t, vp, vp]
         L.dlc_speedup_estimate.argtypes = [C.c_double] * 4
         L.dlc_speedup_estimate.restype = C.c_double
         L.dlc_select_compressors.argtypes = [vp, vp, vp, C.c_size_t, vp, vp, C.c_size_t, C.c_double, vp, vp, vp, vp, vp]
@@ -125,6 +127,14 @@ def dlc_compress_bound(cfg: Config) -> int:
 
 def dlc_workspace_bytes(cfg: Config) -> int:
     return int(lib().dlc_workspace_bytes(C.byref(cfg)))
+
+
+def dlc_decompress_static(cfg: Config, d_comp, comp_bytes, d_payload_out, d_status, stream=None) -> int:
+    """dlc_decompress without a context and without any allocation; the status goes to the int32 tensor d_status."""
+    cap = d_payload_out.numel() * d_payload_out.element_size()
+    return lib().dlc_decompress_static(C.byref(cfg), C.c_void_p(d_comp.data_ptr()), comp_bytes,
+                                       C.c_void_p(d_payload_out.data_ptr()), cap, C.c_void_p(d_status.data_ptr()),
+                                       _stream_ptr(stream))
 
 
 def _stream_ptr(stream):

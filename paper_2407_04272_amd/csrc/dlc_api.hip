@@ -5,6 +5,7 @@
 #include <cstring>
 #include <utility>
 #include <limits>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -370,6 +371,69 @@ extern "C" int dlc_decompress(dlc_ctx* c, const void* d_comp, size_t comp_bytes,
     return e == hipSuccess ? DLC_OK : DLC_EHIP;
 }
 
+// ---- decompression for callers that cannot allocate --------------------------------------------------------------
+// The decode kernels' workspace (status word, per-table escape and arrival counters, the row references' table) is
+// this array, part of the library's image on every GPU it is loaded on; the kernels get its address on the current
+// device, looked up once per device, never the array's name.
+constexpr uint32_t kStaticTables = DLC_STATIC_MAX_TABLES;
+constexpr size_t kStaticCtrlBytes = 256;
+constexpr size_t kStaticBytes = kStaticCtrlBytes + (size_t)kStaticTables * (4 + 4 + sizeof(DecTable));
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+constexpr int kStaticDevices = 64;
+static std::mutex g_static_mu;
+static unsigned char* g_static_ptr[kStaticDevices] = {};
+
+static int static_scratch(unsigned char** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return DLC_EHIP;
+    if (dev < 0 || dev >= kStaticDevices) return DLC_ELIMIT;
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return DLC_EHIP;
+        if (decompress_set_attributes() != hipSuccess) return DLC_EHIP;
+        g_static_ptr[dev] = static_cast<unsigned char*>(p);
+    }
+    *out = g_static_ptr[dev];
+    return DLC_OK;
+}
+
+// what must start at zero: the status word and the counters of the call's tables (a call that found a bad container
+// may have left counters behind)
+__global__ __launch_bounds__(256) void k_static_clear(uint32_t* ctrl_words, uint32_t* esc, uint32_t* arrive, uint32_t T) {
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i < sizeof(Ctrl) / 4u) ctrl_words[i] = 0u;
+    if (i < T) esc[i] = arrive[i] = 0u;
+}
+
+__global__ void k_static_status(const Ctrl* ctrl, int32_t* status_out) { status_out[0] = ctrl->status; }
+
+extern "C" int dlc_decompress_static(const dlc_config* cfg, const void* d_comp, size_t comp_bytes, void* d_out, size_t cap,
+                                     int32_t* d_status, void* stream) {
+    Geom g;
+    if (!make_geom(cfg, &g) || !d_status || !aligned16(d_comp) || !aligned16(d_out)) return DLC_EINVAL;
+    if (g.T > kStaticTables) return DLC_ELIMIT;
+    if (cap < (size_t)g.n * g.T * g.es) return DLC_ECAPACITY;
+    if (g.ND > 1) comp_bytes = (comp_bytes / g.ND) & ~size_t(255);
+    if (comp_bytes < fixed_layout(g).off_payload) return DLC_ECORRUPT;
+    unsigned char* base = nullptr;
+    const int rc = static_scratch(&base);
+    if (rc != DLC_OK) return rc;
+    Ws w;
+    w.ctrl = reinterpret_cast<Ctrl*>(base);
+    w.dec_esc = reinterpret_cast<uint32_t*>(base + kStaticCtrlBytes);
+    w.dec_arrive = w.dec_esc + kStaticTables;
+    w.dtab = reinterpret_cast<DecTable*>(base + kStaticCtrlBytes + (size_t)kStaticTables * 8);
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(k_static_clear, dim3((std::max<uint32_t>(g.T, 8u) + 255u) / 256u), dim3(256), 0, s,
+                       reinterpret_cast<uint32_t*>(base), w.dec_esc, w.dec_arrive, g.T);
+    hipError_t e = launch_decompress(g, (const uint8_t*)d_comp, comp_bytes, d_out, w, 0, nullptr, s);
+    hipLaunchKernelGGL(k_static_status, dim3(1), dim3(1), 0, s, w.ctrl, d_status);
+    if (e == hipSuccess) e = hipGetLastError();
+    return e == hipSuccess ? DLC_OK : DLC_EHIP;
+}
+
 extern "C" int dlc_set_row_match(dlc_ctx* c, const uint8_t* h_flags, void* stream) {
     if (!c) return DLC_EINVAL;
     if (!c->g.lz) return DLC_ESTATE;
@@ -598,6 +662,7 @@ extern "C" const char* dlc_strerror(int s) {
         case DLC_ECORRUPT: return "corrupt or mismatching container";
         case DLC_EHIP: return "HIP runtime error";
         case DLC_ESTATE: return "bad call order or internal invariant";
+        case DLC_ELIMIT: return "beyond the fixed maximum of an entry point that allocates nothing";
         default: return "unknown status";
     }
 }
