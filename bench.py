@@ -21,8 +21,25 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-CARRY_TRAFFIC = 591.6e6  # HBM bytes per launch of the single-pass kernel on cfg3, from the counter runs
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+TARGET_FRAC = 0.60      # what each direction is asked to reach on the 512 MiB workload
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "cfg3_hbm_traffic_pmc.txt")
+ORACLE_SAMPLE_BYTES = 64 << 20  # the oracle checks a workload's first tables, this many bytes of them at most
+
+
+def profiled_traffic():
+    """HBM bytes per launch by kernel name, from the committed summary of the FETCH_SIZE / WRITE_SIZE counter runs (the
+    counters cannot be collected from inside this process).  Its line `bytes per launch: k_x 1.2e6, k_y ...` is what
+    is read; no such file or line, or a kernel it does not name: no figure."""
+    try:
+        with open(TRAFFIC_PROFILE) as f:
+            for line in f:
+                if line.startswith("bytes per launch:"):
+                    items = [it.split() for it in line.split(":", 1)[1].strip().rstrip(".").split(",")]
+                    return {name: float(val) for name, val in items}
+    except (OSError, ValueError):
+        pass
+    return {}
 
 
 def main():
@@ -40,9 +57,13 @@ def main():
     ap.add_argument("--row-match", action="store_true",
                     help="time the path with the vector-based LZ step on every table (DLC_FLAG_ROW_MATCH) instead of the "
                          "default path; the roofline object then still prices the kernel the profile slots see")
+    ap.add_argument("--no-workloads", action="store_true",
+                    help="leave out the 'workloads' list (the five synthetic workloads, each timed both ways and checked "
+                         "against the oracle on its first tables)")
     ap.add_argument("--all-workloads", action="store_true",
-                    help="also measure the five synthetic workloads one after the other (adds a 'workloads' list to the "
-                         "JSON line; takes about a minute more, mostly the oracle)")
+                    help="the long form of the 'workloads' list: the oracle over every whole payload, workload 3 split over "
+                         "8 and 32 destinations and with row matching, workload 5 as a run of 200 iterations (about a "
+                         "minute more)")
     ap.add_argument("--copy-reference", action="store_true",
                     help="also run three plain device copies of the payload (the known-size kernel that HBM counters are scaled by)")
     args = ap.parse_args()
@@ -164,10 +185,10 @@ def main():
     # them, for every streaming kernel here); the direction-level fractions are in compress_/decompress_roofline_frac
     dom_bytes = algo_bytes
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
-    # HBM bytes per launch of the dominant kernel, from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
-    # profiles/cfg3_hbm_traffic_pmc.txt (they cannot be collected from inside this process); known for this workload only
-    measured_traffic = {"k_encode": 253.9e6, "k_hist": 671.8e6, "k_decode": 597.4e6, "k_encode_carry": CARRY_TRAFFIC}
-    traffic = measured_traffic.get(dom) if (args.workload == "cfg3" and args.chunk_symbols == 256 and not args.row_match) else None
+    # HBM bytes per launch of the dominant kernel, from the committed counter summary; it covers this workload only
+    traffic = profiled_traffic().get(dom) if (args.workload == "cfg3" and args.chunk_symbols == 256 and not args.row_match) else None
+    comp_frac = algo_bytes / (comp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS
+    dec_frac = algo_bytes / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS
     result = {
         "metric": "compress+decompress round-trip GB/s of uncompressed fp32 payload, 1 MI355X",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -181,13 +202,17 @@ def main():
         "compression_ratio": round(cr, 3),
         "compress_GBps": round(payload_bytes / comp_ms / 1e6, 2), "compress_ms": round(comp_ms, 4),
         "decompress_GBps": round(payload_bytes / dec_ms / 1e6, 2), "decompress_ms": round(dec_ms, 4),
-        "compress_roofline_frac": round(algo_bytes / (comp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-        "decompress_roofline_frac": round(algo_bytes / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "compress_roofline_frac": round(comp_frac, 4),
+        "decompress_roofline_frac": round(dec_frac, 4),
         "stats_ms": round(stats_ms, 3), "stats_GBps": round(payload_bytes / stats_ms / 1e6, 2),
         "kernel_ms": {k: round(v, 4) for k, v in kern.items() if v > 0},
         "kernel_ms_all": {k: round(v, 4) for k, v in kern_all.items() if v > 0},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     # what the target is stated on: a whole call of each direction (all its kernels), same bytes
+                     "direction_frac": {"compress": round(comp_frac, 4), "decompress": round(dec_frac, 4)},
+                     "target_frac": TARGET_FRAC,
+                     "target_met": {"compress": bool(comp_frac >= TARGET_FRAC), "decompress": bool(dec_frac >= TARGET_FRAC)}},
     }
 
     if not args.carry_codebook and not args.row_match:
@@ -205,8 +230,13 @@ def main():
             ctx2.decompress(out, out.numel(), rec)
         rt2_ms = timed(step2, n_dir)
         assert ctx2.sync_status() == 0
+        algo2 = payload_bytes * (1.0 + total2 / payload_bytes)
+        carried_frac = algo2 / (comp2_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS
+        result["roofline"]["direction_frac"]["compress_carried_codebook"] = round(carried_frac, 4)
+        result["roofline"]["target_met"]["compress_carried_codebook"] = bool(carried_frac >= TARGET_FRAC)
         result["carried_codebook"] = {"compress_ms": round(comp2_ms, 4),
                                       "compress_GBps": round(payload_bytes / comp2_ms / 1e6, 2),
+                                      "compress_roofline_frac": round(carried_frac, 4),
                                       "round_trip_GBps": round(payload_bytes / rt2_ms / 1e6, 2),
                                       "compression_ratio": round(payload_bytes / total2, 3),
                                       "note": "each call coded with the codebook of the previous call's payload "
@@ -235,15 +265,18 @@ def main():
                                   "compress_GBps": round(payload_bytes / tc / 1e9, 4),
                                   "decompress_GBps": round(payload_bytes / td / 1e9, 4),
                                   "container_identical_to_gpu": same}
-    if args.all_workloads:
+    if args.all_workloads or not args.no_workloads:
         del d, rec, out
         torch.cuda.empty_cache()
-        result["workloads"] = all_workloads(b, torch, np, W, dev, args.chunk_symbols, not args.no_cpu_baseline)
+        result["workloads"] = all_workloads(b, torch, np, W, dev, args.chunk_symbols, not args.no_cpu_baseline,
+                                            long_form=args.all_workloads)
     print(json.dumps(result))
 
 
-def _measure(b, torch, np, name, d, ebs, S, with_oracle):
-    """compress / decompress of one payload at the given bounds: both paths on the GPU, the oracle beside them."""
+def _measure(b, torch, np, name, d, ebs, S, with_oracle, sample_bytes=None):
+    """compress / decompress of one payload at the given bounds: both paths on the GPU, the oracle beside them (on the
+    whole payload, or on its first tables up to sample_bytes: the library then compresses those tables on their own
+    and the two containers are compared byte for byte)."""
     T, B, D = d.shape
     f16 = d.dtype == torch.float16
     nbytes = d.numel() * d.element_size()
@@ -273,11 +306,13 @@ def _measure(b, torch, np, name, d, ebs, S, with_oracle):
         algo = nbytes * (1.0 + 1.0 / cr)
         row[key + "compression_ratio"] = round(cr, 3)
         row[key + "compress_GBps"] = round(nbytes / c_ms / 1e6, 2)
+        row[key + "compress_ms"] = round(c_ms, 4)
         row[key + "compress_roofline_frac"] = round(algo / (c_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
         if not key:
             d_ms = timed(lambda: ctx.decompress(out, total, rec))
             assert ctx.sync_status() == 0
             row["decompress_GBps"] = round(nbytes / d_ms / 1e6, 2)
+            row["decompress_ms"] = round(d_ms, 4)
             row["decompress_roofline_frac"] = round(algo / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
             eb_t = torch.from_numpy(np.asarray(ebs, np.float64)).to(d.device).view(T, 1, 1)
             fin = torch.isfinite(d)
@@ -287,16 +322,25 @@ def _measure(b, torch, np, name, d, ebs, S, with_oracle):
         del ctx
     if with_oracle:
         import oracle
-        x = d.cpu().numpy()
+        Ts = T if sample_bytes is None else max(1, min(T, sample_bytes // (nbytes // T)))
+        if Ts < T:  # the first Ts tables as a payload of their own, through the library again
+            ctx = b.Context(b.make_config(b.F16 if f16 else b.F32, Ts, B, D, chunk_symbols=S))
+            ctx.set_error_bounds(eb=ebs[:Ts])
+            assert ctx.compress(d[:Ts], out, sizes[:1 + Ts]) == 0 and ctx.sync_status() == 0
+            data = out[:int(sizes[0].item())].cpu().numpy()
+            del ctx
+        x = d[:Ts].cpu().numpy()
         t0 = time.perf_counter()
-        o = oracle.compress(x, ebs, S=S)
+        o = oracle.compress(x, ebs[:Ts], S=S)
         tc = time.perf_counter() - t0
         t0 = time.perf_counter()
-        rc, _ = oracle.decompress(o.data, x.shape, x.dtype)
+        rc, orec = oracle.decompress(o.data, x.shape, x.dtype)
         td = time.perf_counter() - t0
-        row["oracle_GBps"] = round(nbytes / (tc + td) / 1e9, 4)
-        row["container_identical_to_oracle"] = bool(o.rc == 0 and rc == 0 and o.data.size == data.size
-                                                     and np.array_equal(o.data, data))
+        u = np.uint16 if f16 else np.uint32
+        row["oracle_GBps"] = round(x.nbytes / (tc + td) / 1e9, 4)
+        row["oracle_sample"] = "the whole payload" if Ts == T else f"the first {Ts} of {T} tables"
+        row["same_bytes_as_oracle"] = bool(o.rc == 0 and rc == 0 and o.data.size == data.size and np.array_equal(o.data, data)
+                                           and np.array_equal(orec.view(u), rec[:Ts].cpu().numpy().view(u)))
     return row
 
 
@@ -409,14 +453,11 @@ def _measure_rows(b, torch, np, d, ebs, S, with_oracle):
         k = 3      # one table against the oracle here (the parity tests compare whole containers)
         o = oracle.compress(d[k:k + 1].cpu().numpy(), ebs[k:k + 1], S=S, row_match=True)
         rows[0]["table_bytes_equal_oracle"] = bool(o.rc == 0 and int(o.sizes[1]) == int(lz["per_table"][k]))
-    tb = nbytes / T
     for net in (25.0, 400.0):      # GB/s per GPU: a 200 Gb/s NIC; about half of the seven xGMI links
-        pick = []
-        for t in range(T):
-            s_plain = b.dlc_speedup_estimate(tb / plain["per_table"][t], net, plain["tc"], plain["td"])
-            s_lz = b.dlc_speedup_estimate(tb / lz["per_table"][t], net, lz["tc"], lz["td"])
-            pick.append(1 if s_lz > s_plain else 0)
-        ctx.set_row_match(pick)
+        # the library's selection procedure (Section III-D): both compressors on the sample (here the whole payload),
+        # Eq. 2 per table with the whole-call rates measured above, the choice installed in the context
+        pick, _ = ctx.select_compressors(d, out, sizes, net, tc_gbps=(plain["tc"], lz["tc"]), td_gbps=(plain["td"], lz["td"]))
+        pick = [int(v) for v in pick]
         hy = run(ctx)
         rows.append({"workload": f"3 hybrid: row matching where Eq. 2 prefers it at {net:g} GB/s network",
                      "payload_MiB": round(nbytes / 2 ** 20, 3), "tables_with_row_matching": int(sum(pick)),
@@ -427,8 +468,12 @@ def _measure_rows(b, torch, np, d, ebs, S, with_oracle):
     return rows
 
 
-def all_workloads(b, torch, np, W, dev, S, with_oracle):
+def all_workloads(b, torch, np, W, dev, S, with_oracle, long_form=False):
+    """The five synthetic workloads, one row each (two for workload 4: fp32 and fp16; three for workload 5: the forward
+    payload at the start and after the decay phase, the backward payload).  long_form: the oracle over whole payloads
+    instead of a sample of tables, and the rows on destinations, row matching and a run of iterations."""
     rows = []
+    sample = None if long_form else ORACLE_SAMPLE_BYTES
 
     def bounds(d, meta, mode, probe_frac=None, probe_abs=None, iteration=0, decay=False, rel_floor=0.0, clamp=(0.0, 0.0)):
         T = d.shape[0]
@@ -451,25 +496,26 @@ def all_workloads(b, torch, np, W, dev, S, with_oracle):
     w = W.workload1()
     d = torch.from_numpy(w.payload).to(dev)
     rows.append(_measure(b, torch, np, "1: 1 table, 256 lookups x 16, absolute bound 1e-3", d,
-                         np.full(1, w.meta["eb"], np.float32), S, with_oracle))
+                         np.full(1, w.meta["eb"], np.float32), S, with_oracle, sample))
     w = W.workload2()
     d = torch.from_numpy(w.payload).to(dev)
     ebs = bounds(d, w.meta, 0, probe_abs=w.meta["global_eb"], clamp=(w.meta["eb_min"], w.meta["eb_max"]))
-    rows.append(_measure(b, torch, np, "2: 26 tables x 4096 x 64, controller with absolute bounds", d, ebs, S, with_oracle))
+    rows.append(_measure(b, torch, np, "2: 26 tables x 4096 x 64, controller with absolute bounds", d, ebs, S, with_oracle, sample))
     w = W.workload3(device=dev)
     ebs = bounds(w.payload, w.meta, 1, probe_frac=0.03)
-    rows.append(_measure(b, torch, np, "3: 128 x 8192 x 128, range-relative 0.03", w.payload, ebs, S, with_oracle))
-    for n_dest in (8, 32):
-        rows.append(_measure_split(b, torch, np, w.payload, ebs, S, n_dest, with_oracle))
-    rows.extend(_measure_rows(b, torch, np, w.payload, ebs, S, with_oracle))
+    rows.append(_measure(b, torch, np, "3: 128 x 8192 x 128, range-relative 0.03", w.payload, ebs, S, with_oracle, sample))
+    if long_form:
+        for n_dest in (8, 32):
+            rows.append(_measure_split(b, torch, np, w.payload, ebs, S, n_dest, with_oracle))
+        rows.extend(_measure_rows(b, torch, np, w.payload, ebs, S, with_oracle))
     del w
     torch.cuda.empty_cache()
     w = W.workload4(device=dev)
     ebs = bounds(w.payload, w.meta, 1, probe_frac=0.03)
-    rows.append(_measure(b, torch, np, "4: 64 x 16384 x 128 multi-hot, fp32", w.payload, ebs, S, with_oracle))
+    rows.append(_measure(b, torch, np, "4: 64 x 16384 x 128 multi-hot, fp32", w.payload, ebs, S, with_oracle, sample))
     h = w.meta["payload_f16"]
     ebs = bounds(h, w.meta, 1, probe_frac=0.03, rel_floor=w.meta["rel_floor_f16"])
-    rows.append(_measure(b, torch, np, "4: the same sums in fp16, floor 2^-10 of the range", h, ebs, S, with_oracle))
+    rows.append(_measure(b, torch, np, "4: the same sums in fp16, floor 2^-10 of the range", h, ebs, S, with_oracle, sample))
     del w, h
     torch.cuda.empty_cache()
     gen = W.Workload5(device=dev)
@@ -477,12 +523,13 @@ def all_workloads(b, torch, np, W, dev, S, with_oracle):
     fwd, bwd = fwd.clone(), bwd.clone()
     for it, tag in ((0, "iteration 0 (bound x2)"), (100, "iteration 100 (bound x1)")):
         ebs = bounds(fwd, gen.meta, 1, probe_frac=0.03, iteration=it, decay=True)
-        rows.append(_measure(b, torch, np, "5: forward payload, " + tag, fwd, ebs, S, with_oracle))
+        rows.append(_measure(b, torch, np, "5: forward payload, " + tag, fwd, ebs, S, with_oracle, sample))
     ebs = bounds(bwd, gen.meta, 1, probe_abs=1e-5, iteration=100, decay=True)
-    rows.append(_measure(b, torch, np, "5: backward payload N(0, 1e-4)", bwd, ebs, S, with_oracle))
+    rows.append(_measure(b, torch, np, "5: backward payload N(0, 1e-4)", bwd, ebs, S, with_oracle, sample))
     del gen, fwd, bwd
     torch.cuda.empty_cache()
-    rows.append(_run_schedule(b, torch, np, W, dev, S))
+    if long_form:
+        rows.append(_run_schedule(b, torch, np, W, dev, S))
     return rows
 
 
