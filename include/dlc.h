@@ -100,10 +100,8 @@ typedef struct {
  *     is [n][num_tables][batch][dim].  Every container says in its header how long it is; one that fails
  *     validation is reported (DLC_ECORRUPT) and left undecoded, the others are decoded. */
 
-/* dlc_config.flags: compress with the fused persistent kernel, which reads the payload once and builds each
- * table's codebook inside the kernel, instead of the separate histogram, codebook and encode kernels.  Both
- * produce the same bytes; on MI355X the separate kernels are the faster choice (the default). */
-enum { DLC_FLAG_FUSED = 1, DLC_FLAG_CARRY_CODEBOOK = 2, DLC_FLAG_ROW_MATCH = 4 };
+/* dlc_config.flags (bit 0 is not used) */
+enum { DLC_FLAG_CARRY_CODEBOOK = 2, DLC_FLAG_ROW_MATCH = 4 };
 
 /* DLC_FLAG_CARRY_CODEBOOK: dlc_compress codes each table with the Huffman codebook built from the payload of the
  * PREVIOUS dlc_compress call on this context instead of from its own payload (Section IV-C: the value distributions
@@ -115,7 +113,8 @@ enum { DLC_FLAG_FUSED = 1, DLC_FLAG_CARRY_CODEBOOK = 2, DLC_FLAG_ROW_MATCH = 4 }
  *   - A symbol the carried codebook has no code for is stored as an escape (raw value), so the error bound holds
  *     for any payload; a payload unlike the previous one costs compression ratio, never correctness.
  *   - The container format is unchanged; dlc_decompress needs no flag.
- * Cannot be combined with DLC_FLAG_FUSED. */
+ *   - The workspace of such a context also holds every group's words before they are put in place, with room for
+ *     every group's worst case: about 2.6 times an fp32 payload in all (dlc_workspace_bytes says how much). */
 
 /* DLC_FLAG_ROW_MATCH: the vector-based LZ step of Section III-D in front of the entropy coder.  The pattern is one
  * whole row (embedding vector): a row that equals an earlier row of its table in the batch after quantisation -- all
@@ -298,7 +297,7 @@ int dlc_set_row_hash_multipliers(dlc_ctx* ctx, const uint32_t* h_mult, void* str
 
 /*
  * Kernel timing with HIP events on the caller's stream.
- *   dlc_profile_enable  level 0 off; 1 = the dominant kernel of each direction (encode or fused, decode); 2 = every
+ *   dlc_profile_enable  level 0 off; 1 = the dominant kernel of each direction (encode, decode); 2 = every
  *                       kernel.  Each timed kernel costs two event records per call (a few microseconds).
  *   dlc_profile_read    synchronises, returns the number of kernel slots; for slot i < max_slots:
  *                       names[i] (static string), total_ms[i], launches[i]; then resets the counters

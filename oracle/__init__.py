@@ -129,7 +129,7 @@ def histogram(sym: np.ndarray, K: int) -> np.ndarray:
 
 
 def codebook(hist: np.ndarray, LMAX: int = 12):
-    """-> (len u8[K], code u32[K], n_used, n_halvings)."""
+    """-> (len u8[K], code u32[K], n_used, n_repairs)."""
     hist = np.ascontiguousarray(hist, np.uint64)
     K = hist.size
     ln = np.zeros(K, np.uint8)

@@ -280,7 +280,7 @@ static int huffman_depths(const orc_leaf* leaf, int n, int* depth) {
 }
 
 int orc_codebook(const uint64_t* hist, int K, int LMAX, uint8_t* len, uint32_t* code, int* n_used_out,
-                 int* n_halvings_out) {
+                 int* n_repairs_out) {
     if (!hist || !len || !code || K < 2 || K > 4096 || LMAX < 1 || LMAX > ORC_LMAX_LIMIT) return ORC_EINVAL;
     if ((1 << LMAX) < K) return ORC_EINVAL; /* a code for every symbol must exist */
     orc_leaf* leaf = (orc_leaf*)malloc(sizeof(orc_leaf) * (size_t)K);
@@ -295,7 +295,7 @@ int orc_codebook(const uint64_t* hist, int K, int LMAX, uint8_t* len, uint32_t* 
             n++;
         }
     }
-    int halvings = 0; /* number of Kraft repair steps (0: plain Huffman) */
+    int repairs = 0; /* number of Kraft repair steps (0: plain Huffman) */
     if (n >= 2) {
         qsort(leaf, (size_t)n, sizeof(orc_leaf), leaf_cmp);
         int longest = huffman_depths(leaf, n, depth);
@@ -314,7 +314,7 @@ int orc_codebook(const uint64_t* hist, int K, int LMAX, uint8_t* len, uint32_t* 
                         break;
                     }
                 kraft -= 1;
-                halvings++;
+                repairs++;
             }
             int i = n - 1; /* leaves are sorted by rising count: the last one is the most frequent */
             for (int L = 1; L <= LMAX; ++L)
@@ -340,7 +340,7 @@ int orc_codebook(const uint64_t* hist, int K, int LMAX, uint8_t* len, uint32_t* 
         }
     }
     if (n_used_out) *n_used_out = n;
-    if (n_halvings_out) *n_halvings_out = halvings;
+    if (n_repairs_out) *n_repairs_out = repairs;
     free(leaf);
     free(depth);
     return ORC_OK;

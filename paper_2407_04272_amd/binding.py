@@ -107,7 +107,6 @@ def _check(status, where):
         raise DlcError(status, where)
 
 
-FLAG_FUSED = 1
 FLAG_CARRY_CODEBOOK = 2
 FLAG_ROW_MATCH = 4
 

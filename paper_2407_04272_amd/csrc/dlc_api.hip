@@ -45,7 +45,7 @@ void prof_end(void* p, int slot, hipStream_t s) {
 }
 
 static const char* kSlotNames[P_NSLOTS] = {"k_hist", "k_codebook", "k_encode", "k_finalize",
-                                           "k_decode", "k_fused", "k_encode_carry", "k_post"};
+                                           "k_decode", "k_encode_carry", "k_post"};
 }  // namespace dlc
 
 using namespace dlc;
@@ -86,14 +86,12 @@ static bool make_geom(const dlc_config* c, Geom* g) {
     if (L < 1 || L > kLmaxLimit || (1 << L) < 2 * R) return false;
     const int S = c->chunk_symbols;
     if (S != 64 && S != 128 && S != 256) return false;
-    if (c->flags & ~(int32_t)(DLC_FLAG_FUSED | DLC_FLAG_CARRY_CODEBOOK | DLC_FLAG_ROW_MATCH)) return false;
+    if (c->flags & ~(int32_t)(DLC_FLAG_CARRY_CODEBOOK | DLC_FLAG_ROW_MATCH)) return false;
     if (c->flags & DLC_FLAG_ROW_MATCH) {  // not with the other flags, and a lane's four elements must lie in one row
         if (c->flags != DLC_FLAG_ROW_MATCH || c->dim % 4 != 0) return false;
     }
-    if ((c->flags & DLC_FLAG_FUSED) && (c->flags & DLC_FLAG_CARRY_CODEBOOK)) return false;
     const int64_t nd = c->num_dest == 0 ? 1 : c->num_dest;  // 0: a zero-initialised field means one destination
     if (nd < 1 || nd > 4096) return false;
-    if (nd > 1 && (c->flags & DLC_FLAG_FUSED)) return false;
     const uint64_t T = (uint64_t)c->num_tables * (uint64_t)nd;  // tables of the whole payload
     if (T > 0x7FFFFFFFull) return false;
     const uint64_t GS = (uint64_t)kW * S;
@@ -145,8 +143,6 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
     uint8_t* ws0 = take(4 * (size_t)g.T);
     uint8_t* ws1 = take(4 * (size_t)g.T);
     uint8_t* plane = take((size_t)g.NG * kW * g.S);
-    uint8_t* arrive = take(4 * (size_t)g.T);
-    uint8_t* ready = take(8 * (size_t)g.T);
     uint8_t* escc = take(4 * (size_t)g.T);
     uint8_t* rm_on = g.lz ? take(g.T) : nullptr;
     uint8_t* rm_ref = g.lz ? take(4 * (size_t)g.T * g.B) : nullptr;
@@ -170,7 +166,7 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
         w->tmeta = (TMeta*)tmeta;
         w->enc = (uint16_t*)enc; w->lens = lens; w->state = (uint64_t*)state;
         w->word_start = (uint32_t*)ws0; w->word_end = (uint32_t*)ws1;
-        w->arrive = (uint32_t*)arrive; w->ready = (uint64_t*)ready; w->sym_plane = plane;
+        w->sym_plane = plane;
         w->esc_count = (uint32_t*)escc;
         w->gtot = (uint32_t*)gtot; w->bsum = (uint32_t*)bsum; w->slots = (uint32_t*)slots;
         w->enc_next = (uint16_t*)enc2; w->lens_next = lens2; w->tmeta_next = (TMeta*)tmeta2; w->bsum_next = (uint32_t*)bsum2;
@@ -211,8 +207,7 @@ extern "C" int dlc_create(dlc_ctx** out, const dlc_config* cfg) {
         row_match_multipliers(mult.data(), g.D / 4u);
         if (hipMemcpy(c->ws.rm_mult, mult.data(), 4 * mult.size(), hipMemcpyHostToDevice) != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }
     }
-    if (compress_set_attributes() != hipSuccess || decompress_set_attributes() != hipSuccess || row_match_set_attributes() != hipSuccess ||
-        ((cfg->flags & DLC_FLAG_FUSED) && fused_plan(g, &c->ws.fused_grid) != hipSuccess)) {
+    if (compress_set_attributes() != hipSuccess || decompress_set_attributes() != hipSuccess || row_match_set_attributes() != hipSuccess) {
         (void)hipGetLastError();
         (void)hipFree(base);
         delete c;
@@ -335,16 +330,27 @@ extern "C" int dlc_set_error_bounds(dlc_ctx* c, const dlc_table_stats* st, const
 
 static bool aligned16(const void* p) { return p && (((uintptr_t)p) & 15u) == 0; }
 
+// clears 64-bit words on a stream (a kernel, not a memset: a caller may be capturing the stream into a graph)
+__global__ __launch_bounds__(256) void k_zero_words(uint64_t* p, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256u + threadIdx.x; i < n; i += (size_t)gridDim.x * 256u) p[i] = 0ull;
+}
+
 extern "C" int dlc_compress(dlc_ctx* c, const void* d_payload, void* d_out, size_t cap, uint64_t* d_out_bytes,
                             void* stream) {
     if (!c || !aligned16(d_payload) || !aligned16(d_out) || !d_out_bytes || (((uintptr_t)d_out_bytes) & 7u))
         return DLC_EINVAL;
     if (!c->bounds_set) return DLC_ESTATE;
     if (c->g.ND > 1) cap = (cap / c->g.ND) & ~size_t(255);  // per destination: container d starts at d * cap
-    if (cap < fixed_layout(c->g).off_payload) return DLC_ECAPACITY;  // the fixed-size sections must fit
+    if (cap < fixed_layout(c->g).off_payload) {  // the fixed-size sections must fit: nothing is written but the size, 0
+        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(256), 0, (hipStream_t)stream, d_out_bytes, (size_t)1);
+        return hipGetLastError() == hipSuccess ? DLC_ECAPACITY : DLC_EHIP;
+    }
     c->epoch += 1;
     if (c->epoch >= (1ull << 30)) {  // look-back records carry a 30-bit call counter
-        if (hipMemsetAsync(c->ws.state, 0, 8 * (size_t)c->g.NG, (hipStream_t)stream) != hipSuccess) return DLC_EHIP;
+        const size_t n = c->g.NG;
+        hipLaunchKernelGGL(k_zero_words, dim3((unsigned)std::min<size_t>((n + 255) / 256, 4096)), dim3(256), 0, (hipStream_t)stream,
+                           c->ws.state, n);
+        if (hipGetLastError() != hipSuccess) return DLC_EHIP;
         c->epoch = 1;
     }
     const bool was_single_pass = c->ws.carry != 0 && c->carry_ready;

@@ -4,12 +4,6 @@
 #include "dlc_internal.h"
 
 // phase time stamps for kernel micro-benchmarks; expands to nothing in the library
-#ifndef DLC_WSTAMP
-#define DLC_WSTAMP(i)
-#endif
-#ifndef DLC_STAMP
-#define DLC_STAMP(i)
-#endif
 
 namespace dlc {
 
@@ -36,10 +30,6 @@ __host__ __device__ inline uint32_t win_lo_of(uint32_t R) { return R > kWinBins 
 __host__ __device__ inline size_t plane_stride(const Geom& g) { return (size_t)g.G * kW * g.S; }
 // LDS of the histogram kernel in words: window [kWinBins + 1][kWinCopies] | exact counts [K]
 __host__ __device__ inline size_t hist_lds_bytes(uint32_t K) { return (((size_t)(kWinBins + 1) * kWinCopies + K) * 4 + 15) & ~size_t(15); }
-
-// legacy helpers of the fused kernel's own histogram layout
-constexpr uint32_t kHistWin = 256;
-__host__ __device__ inline uint32_t hist_win_bins(uint32_t K) { return K < kHistWin ? K : kHistWin; }
 
 // ------------------------------------------------------------------------------------------------
 // Huffman codebook of one table, built by one work-group of 256 threads from the table's histogram.
@@ -75,7 +65,6 @@ __device__ __forceinline__ uint32_t lane_read(uint32_t v, uint32_t l) {
 // code length of the symbol the lane came in with.  2 <= n <= 64.
 __device__ __forceinline__ uint32_t wave_huffman_lengths(uint32_t n, uint32_t LM, uint32_t cnt, uint32_t lane) {
     const uint32_t kInf = 0xFFFFFFFFu;
-    DLC_WSTAMP(0);
     // position in (count, symbol) order
     uint32_t rank = 0;
     for (uint32_t j = 0; j < n; ++j) {
@@ -86,7 +75,6 @@ __device__ __forceinline__ uint32_t wave_huffman_lengths(uint32_t n, uint32_t LM
     // the sorted sequence: every lane sends its count to the lane of its rank
     const uint32_t sent = (uint32_t)__builtin_amdgcn_ds_permute((int)(rank << 2), (int)cnt);
     const uint32_t s_cnt = lane < n ? sent : kInf;
-    DLC_WSTAMP(1);
     // two-queue merge; a tie between the heads takes the leaf.  l0, l1: the two leaves at the head of the leaf
     // queue; n0, n1: the same for the merged nodes (node k exists from step k + 1 on)
     const uint32_t vw = s_cnt;
@@ -107,7 +95,6 @@ __device__ __forceinline__ uint32_t wave_huffman_lengths(uint32_t n, uint32_t LM
         n0 = bq <= k ? lane_read(vn, bq) : kInf;
         n1 = bq + 1u <= k ? lane_read(vn, bq + 1u) : kInf;
     }
-    DLC_WSTAMP(2);
     // depth of every merged node (lane k = node k, the root is node n-2)
     const uint32_t root = n - 2u;
     uint32_t p = (lane < root) ? vpn : lane;
@@ -151,7 +138,6 @@ __device__ __forceinline__ uint32_t wave_huffman_lengths(uint32_t n, uint32_t LM
         }
         len = lane < n ? nl : 0u;
     }
-    DLC_WSTAMP(3);
     // back to symbol order: the lane that came in with a symbol reads the length at that symbol's sorted position
     return lane < n ? __shfl(len, rank, 64) : 0u;
 }
@@ -173,7 +159,6 @@ __device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, 
     uint32_t* scratch = reinterpret_cast<uint32_t*>(len_s + K);  // [64]
     const uint32_t lane = tid & 63u, wave = tid >> 6;
 
-    DLC_STAMP(0);
     // each thread owns `per` consecutive symbols
     const uint32_t per = (K + 255) / 256;
     const uint32_t k0 = tid * per, k1 = min(K, k0 + per);
@@ -205,7 +190,6 @@ __device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, 
     const uint32_t sym_lo = n_used ? (uint32_t)(key[0] & 0xFFFFu) : 0u;
     const uint32_t sym_hi = n_used ? (uint32_t)(key[n_used - 1] & 0xFFFFu) : 0u;
 
-    DLC_STAMP(1);
     if (n_used >= 2 && n_used <= 64) {
         if (wave == 0) {
             const uint64_t kv = lane < n_used ? key[lane] : ~0ull;  // lane i: the i-th used symbol
@@ -228,7 +212,6 @@ __device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, 
     } else if (n_used > 64) {
         const uint32_t n_escape = cnt[0];  // (cnt[] is scratch from here on:
         __syncthreads();                   //  once every thread has read this)
-        DLC_STAMP(2);
         if (n_used <= 256) {
             // rank sort, a thread per key: the keys are distinct (the symbol is part of them), so a key's place is
             // the number of smaller keys; every thread reads the same key at a time (an LDS broadcast)
@@ -262,7 +245,6 @@ __device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, 
                 }
             }
         }
-        DLC_STAMP(3);
         if (tid == 0) {
             const uint32_t n = n_used;
             uint32_t a = 0, bq = 0;  // heads of the leaf queue and of the merged-node queue
@@ -301,7 +283,6 @@ __device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, 
             __syncthreads();
             if (tid == 0) cnt[0] = n_escape;  // read again at the end (nothing below writes cnt[])
         }
-        DLC_STAMP(4);
         // leaf depths; parent_leaf[] is reused to hold the depth of leaf i (sorted order)
         uint32_t local_max = 0;
         for (uint32_t i = tid; i < n_used; i += 256) {
@@ -346,7 +327,6 @@ __device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, 
             for (uint32_t i = tid; i < n_used; i += 256) len_s[(uint32_t)(key[i] & 0xFFFFu)] = parent_leaf[i];
             __syncthreads();
             // codewords
-            DLC_STAMP(5);
             for (uint32_t k = k0; k < k1; ++k)
                 if (len_s[k]) atomicAdd(&sh.cl[len_s[k]], 1u);
             __syncthreads();
@@ -371,7 +351,6 @@ __device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, 
             __syncthreads();
         }
     }
-    DLC_STAMP(6);
     for (uint32_t k = k0; k < k1; ++k) {
         uint32_t L = len_s[k];
         __hip_atomic_store(&enc_t[k], (uint16_t)(L ? ((L << 12) | nodew[k]) : 0u), __ATOMIC_RELAXED,
@@ -383,29 +362,9 @@ __device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, 
         // an empty histogram cannot come out of the histogram step (every table has an element); should it
         // happen anyway, the symbol range is still a valid one for the kernels that size things from it
         m.n_used = n_used; m.sym_lo = sym_lo; m.sym_hi = sym_hi; m.n_outliers = cnt[0];  // symbol 0 = escape
-        m.cb_off = 0; m.outl_off = 0;
         *tmeta_t = m;
     }
     __syncthreads();
-    DLC_STAMP(7);
-}
-
-// LDS of the fused kernel, in bytes from the start of its dynamic LDS (alphabets of up to kFusedMaxK symbols):
-//   [0, kFusedTab)             code lengths of the table's symbols, u16[K+1]  (index = symbol; entry 0 is empty and
-//                              stands for a position past the end of the table, entry K is the escape)
-//   [kFusedTab, 2*kFusedTab)   codewords, same indexing
-//   [2*kFusedTab, ...)         the work-group's histogram, later the codebook builder's scratch
-//   histogram in words: window [win_bins + 1][kFusedCopies] (the last row counts everything outside the window)
-//                       | single-copy counts [K] | scratch [64]
-constexpr uint32_t kFusedMaxK = 1024;
-constexpr uint32_t kFusedTab = (kFusedMaxK + 1) * 2 + 14;  // 2064: a 16-byte multiple
-constexpr uint32_t kFusedCopies = 16;
-__host__ __device__ inline size_t fused_hist_bytes(uint32_t K) {
-    return ((size_t)(hist_win_bins(K) + 1) * kFusedCopies + K + kW) * 4;
-}
-__host__ __device__ inline size_t fused_lds_bytes(uint32_t K) {
-    const size_t a = fused_hist_bytes(K), b = codebook_smem(K);
-    return 2 * (size_t)kFusedTab + (((a > b ? a : b) + 15) & ~size_t(15));
 }
 
 // ------------------------------------------------------------------------------------------------

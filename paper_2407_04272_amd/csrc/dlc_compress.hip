@@ -22,8 +22,6 @@ void launch_encode_carry_128(const Geom& g, const FixedLayout& F, const void* pa
                              uint64_t capacity, uint32_t bpt, hipStream_t s);
 void launch_encode_carry_256(const Geom& g, const FixedLayout& F, const void* payload, const Ws& w, uint64_t epoch, uint8_t* out,
                              uint64_t capacity, uint32_t bpt, hipStream_t s);
-hipError_t launch_fused(const Geom& g, const FixedLayout& F, const void* payload, const Ws& w, uint64_t epoch, uint8_t* out,
-                        uint64_t capacity, hipStream_t s);
 
 // ------------------------------------------------------------------------------------------------
 // quantiser alone (inspection entry point)
@@ -67,9 +65,6 @@ struct HistC {
 };
 
 // hook for micro-benchmarks (counting switched off); the library counts
-#ifndef DLC_HIST_COUNT
-#define DLC_HIST_COUNT(addr) lds_count(addr)
-#endif
 
 constexpr uint32_t kPastEnd = 0x80000001u;  // no element within the radius has this window index: a position past the end of the table
 constexpr uint32_t kHistBlk = 4;  // units whose loads are issued back to back
@@ -108,9 +103,9 @@ __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, ui
             sl[v] = w[v] < kBins ? w[v] : kWinBins;
             sl[v] = ok ? sl[v] : kWinEsc;
             if constexpr (FULL) {
-                DLC_HIST_COUNT(sl[v] * (kWinCopies * 4u) + H.lanebase);
+                lds_count(sl[v] * (kWinCopies * 4u) + H.lanebase);
             } else {
-                if ((valid[u] >> v) & 1u) DLC_HIST_COUNT(sl[v] * (kWinCopies * 4u) + H.lanebase);
+                if ((valid[u] >> v) & 1u) lds_count(sl[v] * (kWinCopies * 4u) + H.lanebase);
                 else { sl[v] = kWinBins; w[v] = kPastEnd; }
             }
         }
@@ -568,17 +563,6 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
                                w.lens_next, w.tmeta_next);
             if (prof_on(pl, P_POST)) prof_end(prof, P_POST, s);
         }
-        return hipGetLastError();
-    }
-    if (w.fused_grid != 0) {
-        if (prof_on(pl, P_FUSED)) prof_begin(prof, P_FUSED, s);
-        hipError_t e = launch_fused(g, F, payload, w, epoch, out, capacity, s);
-        if (prof_on(pl, P_FUSED)) prof_end(prof, P_FUSED, s);
-        if (e != hipSuccess) return e;
-        if (prof_on(pl, P_FINALIZE)) prof_begin(prof, P_FINALIZE, s);
-        hipLaunchKernelGGL(k_finalize, finalize_grid(g), dim3(1024), 0, s, g, F, w.tmeta, w.lens, w.qp, w.ctrl, w.word_start,
-                           w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr, g.lz ? (const uint8_t*)w.rm_on : nullptr, (const uint32_t*)w.rm_ref, (uint32_t*)nullptr);
-        if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
         return hipGetLastError();
     }
     // histogram

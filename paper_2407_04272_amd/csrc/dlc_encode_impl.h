@@ -5,18 +5,8 @@
 #define DLC_CAT2(a, b) a##b
 #define DLC_CAT(a, b) DLC_CAT2(a, b)
 
-// phase time stamps of one work-group, for micro-benchmarks only (compiled out of the library)
-#ifdef DLC_EXP_STAMPS
-__device__ long long g_estamp[32];
-#define DLC_ESTAMP(i) do { if (wg == DLC_EXP_STAMPS && threadIdx.x == 0) g_estamp[i] = wall_clock64(); } while (0)
-extern "C" void dlc_debug_stamps(long long* out) { (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_estamp), sizeof(g_estamp)); }
-#else
-#define DLC_ESTAMP(i)
-#endif
-
-#ifndef DLC_ENC_WAVES  // wavefronts per SIMD the register allocation aims at
+// wavefronts per SIMD the register allocation aims at
 #define DLC_ENC_WAVES(S) ((S) == 128 ? 3 : 4)
-#endif
 
 namespace dlc {
 
@@ -85,7 +75,6 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
     const uint32_t dst = t / g.TD, tl = t - dst * g.TD;
     const uint32_t dom0 = dst * g.TD * bpt;
     out += (uint64_t)dst * capacity;
-    DLC_ESTAMP(0);
     const uint32_t win_lo = win_lo_of(g.R);
     const uint16_t* enc_t = enc + (size_t)t * g.K;
     {
@@ -111,7 +100,6 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
     const bool plain = tm.n_outliers == 0u && tm.sym_lo >= win_lo && tm.sym_hi < win_lo + win_bins(g.lz) && rem >= kW * (uint32_t)S;
     const uint32_t a_len = (uint32_t)(uintptr_t)s_len, d_code = (uint32_t)(uintptr_t)s_code - a_len;
 
-    DLC_ESTAMP(1);
     uint32_t ix[S / 4];  // window indices, four to a word, in element order
     uint32_t bits = 0, my_esc = 0, nrec = 0;
     uint16_t* const recs = s_recs + wave * kEncRecs;
@@ -177,7 +165,6 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
             }
         }
     }
-    DLC_ESTAMP(2);
     const uint32_t n_esc = (plain || !active) ? 0u : wave_sum(my_esc);
     const uint32_t nw = (bits + 31u) >> 5;
     const uint32_t incl = wave_incl_scan(nw, lane);
@@ -215,7 +202,6 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
             dead = true;
         }
     }
-    DLC_ESTAMP(3);
     uint32_t* const stage = s_stage + wave * kStageWords;
     if (active && !(dead && !staged)) {
         uint32_t* p = staged ? stage + lane_off : reinterpret_cast<uint32_t*>(out + F.off_payload) + excl + lane_off;
@@ -268,7 +254,6 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
         }
         if (nb) *p = (uint32_t)(acc << (32u - nb));
     }
-    DLC_ESTAMP(4);
     if (staged) {
         if (wave == 0) {
             lb_finish(L, state, epoch, wg, wg_total, lane, ctrl);
@@ -294,7 +279,6 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
     uint32_t* gw = reinterpret_cast<uint32_t*>(out + F.off_payload) + excl;
     if (staged)
         for (uint32_t k = lane; k < chunk_total; k += 64) gw[k] = stage[k];
-    DLC_ESTAMP(5);
     if (n_esc != 0u) {  // uniform over the wavefront
         uint32_t* rec = gw + chunk_total;
         if (n_esc <= kEncRecs) {  // the records were kept on the way

@@ -43,7 +43,6 @@ struct Geom {
 // per-table results of the codebook step
 struct TMeta {
     uint32_t n_used, sym_lo, sym_hi, n_outliers;
-    uint64_t cb_off, outl_off;  // unused by the kernels; kept for the layout of the array
 };
 
 // offsets of the sections of one container (one destination) whose position depends on the geometry alone
@@ -207,7 +206,6 @@ struct Ws;  // workspace, see dlc_api.hip
 hipError_t launch_quantize(const Geom& g, const void* payload, const QParam* qp, uint16_t* sym, hipStream_t s);
 hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uint64_t capacity, uint64_t* out_bytes,
                            const Ws& w, uint64_t epoch, bool carry_ready, int prof_level, void* prof, hipStream_t s);
-hipError_t fused_plan(const Geom& g, uint32_t* grid_out);
 hipError_t launch_row_match(const Geom& g, const void* payload, const Ws& w, hipStream_t s);
 // the row hash's multipliers, eight words per 4-byte piece of a row (six used), computed on the host once
 void row_match_multipliers(uint32_t* mult, uint32_t n_pieces);
@@ -236,9 +234,6 @@ struct Ws {
     uint32_t* word_start = nullptr;  // [T]
     uint32_t* word_end = nullptr;    // [T]
     uint8_t* sym_plane = nullptr;  // [T][G*64*S] window index of every element (255: see the element itself)
-    uint32_t* arrive = nullptr;    // [T] items of a table that have added their counts (fused kernel); zero between calls
-    uint64_t* ready = nullptr;     // [T] call counter of the call whose codebook of the table is complete
-    uint32_t fused_grid = 0;       // work-groups of the fused kernel; 0 = separate histogram / codebook / encode kernels
     uint32_t* esc_count = nullptr; // [T] escapes of the call (single-pass path); zero between calls
     // row matching (allocated only with DLC_FLAG_ROW_MATCH)
     uint8_t* rm_on = nullptr;      // [T] 1: the table's repeated rows are stored as references
@@ -272,9 +267,9 @@ struct Ws {
 // profiling hooks used by the launchers (implemented in dlc_api.hip)
 void prof_begin(void* prof, int slot, hipStream_t s);
 void prof_end(void* prof, int slot, hipStream_t s);
-enum ProfSlot { P_HIST = 0, P_CODEBOOK, P_ENCODE, P_FINALIZE, P_DECODE, P_FUSED, P_CARRY, P_POST, P_NSLOTS };
+enum ProfSlot { P_HIST = 0, P_CODEBOOK, P_ENCODE, P_FINALIZE, P_DECODE, P_CARRY, P_POST, P_NSLOTS };
 inline bool prof_on(int level, int slot) {
-    return level >= 2 || (level == 1 && (slot == P_ENCODE || slot == P_DECODE || slot == P_FUSED || slot == P_CARRY));
+    return level >= 2 || (level == 1 && (slot == P_ENCODE || slot == P_DECODE || slot == P_CARRY));
 }
 
 }  // namespace dlc

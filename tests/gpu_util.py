@@ -30,7 +30,7 @@ class DeviceRun:
         bound = b.dlc_compress_bound(self.cfg)
         cap = bound if capacity is None else capacity
         self.d_out = torch.full((max(cap, 16) + 64,), 0xA5, dtype=torch.uint8, device="cuda")  # guard bytes after cap
-        self.d_sizes = torch.zeros(1 + T, dtype=torch.int64, device="cuda")
+        self.d_sizes = torch.full((1 + T,), 77, dtype=torch.int64, device="cuda")  # (a size word nobody wrote would show)
         self.eb, _ = self.ctx.set_error_bounds(eb=eb)
         self.rc = self.ctx.compress(d_payload, self.d_out, self.d_sizes, capacity=cap)
         self.status = self.ctx.sync_status() if self.rc == 0 else self.rc

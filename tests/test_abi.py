@@ -43,16 +43,14 @@ def test_host_only_entry_points():
         assert b.dlc_compress_bound(bad) == 0
         assert b.dlc_workspace_bytes(bad) == 0
     # flags: row matching wants whole rows per lane (dim % 4 == 0), goes with several destinations, not with the
-    # other flags, and its kernels have a table per grid row (65535 at most); the fused kernel is for one destination
+    # other flags, and its kernels have a table per grid row (65535 at most); bit 0 is not a flag
     ok = [b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_ROW_MATCH), b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_ROW_MATCH, num_dest=8),
-          b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_CARRY_CODEBOOK, num_dest=8), b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_FUSED)]
+          b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_CARRY_CODEBOOK, num_dest=8)]
     for cfg in ok:
         assert b.dlc_compress_bound(cfg) > 0 and b.dlc_workspace_bytes(cfg) > 0
     bad = [b.make_config(b.F32, 4, 64, 6, flags=b.FLAG_ROW_MATCH),
            b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_ROW_MATCH | b.FLAG_CARRY_CODEBOOK),
-           b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_ROW_MATCH | b.FLAG_FUSED),
-           b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_FUSED | b.FLAG_CARRY_CODEBOOK),
-           b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_FUSED, num_dest=2),
+           b.make_config(b.F32, 4, 64, 8, flags=1),
            b.make_config(b.F32, 20000, 4, 4, flags=b.FLAG_ROW_MATCH, num_dest=4),
            b.make_config(b.F32, 4, 64, 8, flags=8), b.make_config(b.F32, 4, 64, 8, num_dest=5000)]
     for cfg in bad:

@@ -176,8 +176,6 @@ def test_calls_that_want_one_destination():
     d = torch.zeros((2, 2, 64, 16), device="cuda")
     with pytest.raises(b.DlcError):
         ctx.stats(d, np.full(2, 1e-3, np.float32))
-    with pytest.raises(b.DlcError):
-        b.Context(b.make_config(b.F32, 2, 64, 16, flags=b.FLAG_FUSED, num_dest=2))
 
 
 @pytest.mark.parametrize("n,T,B,D,S,dtype", [(3, 2, 300, 16, 64, np.float32), (4, 3, 500, 48, 256, np.float16),
