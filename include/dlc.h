@@ -100,8 +100,11 @@ typedef struct {
  *     is [n][num_tables][batch][dim].  Every container says in its header how long it is; one that fails
  *     validation is reported (DLC_ECORRUPT) and left undecoded, the others are decoded. */
 
-/* dlc_config.flags (bit 0 is not used) */
-enum { DLC_FLAG_CARRY_CODEBOOK = 2, DLC_FLAG_ROW_MATCH = 4 };
+/* dlc_config.flags (bit 0 is not used).  DLC_FLAG_STATS_WORKSPACE: dlc_create also allocates the buffers of
+ * dlc_stats (about 24 bytes per row and table), so that statistics taken again in the middle of a run (periodic
+ * re-classification of the tables) allocate nothing; without it the first dlc_stats call allocates them.  Goes
+ * with every other flag. */
+enum { DLC_FLAG_CARRY_CODEBOOK = 2, DLC_FLAG_ROW_MATCH = 4, DLC_FLAG_STATS_WORKSPACE = 8 };
 
 /* DLC_FLAG_CARRY_CODEBOOK: dlc_compress codes each table with the Huffman codebook built from the payload of the
  * PREVIOUS dlc_compress call on this context instead of from its own payload (Section IV-C: the value distributions
@@ -171,7 +174,7 @@ void dlc_destroy(dlc_ctx* ctx);
 
 /* Worst-case container size in bytes for this geometry (every element an escape); 0 if cfg is invalid. */
 size_t dlc_compress_bound(const dlc_config* cfg /*HOST*/);
-/* Device workspace a context of this geometry holds (statistics workspace excluded: allocated on first use). */
+/* Device workspace a context of this geometry holds (the statistics buffers excluded, also with DLC_FLAG_STATS_WORKSPACE). */
 size_t dlc_workspace_bytes(const dlc_config* cfg /*HOST*/);
 
 /*
@@ -180,7 +183,8 @@ size_t dlc_workspace_bytes(const dlc_config* cfg /*HOST*/);
  *   h_probe_eb HOST    T bounds at which rows are quantised for N_compressed
  *   h_stats    HOST    T entries, caller-owned, filled on return
  * Distinct-row counts are exact (hashing, then every hash match is verified element by element).
- * Synchronises `stream` before returning.  Allocates its own workspace on first use.  DLC_ESTATE on a context with
+ * Synchronises `stream` before returning.  Allocates its own workspace on first use (unless the context was created
+ * with DLC_FLAG_STATS_WORKSPACE).  DLC_ESTATE on a context with
  * num_dest > 1 (a table's statistics are over its whole batch), DLC_EINVAL with more than 65535 tables.
  */
 int dlc_stats(dlc_ctx* ctx, const void* d_payload, const float* h_probe_eb, dlc_table_stats* h_stats, void* stream);

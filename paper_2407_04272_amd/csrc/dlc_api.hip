@@ -86,9 +86,9 @@ static bool make_geom(const dlc_config* c, Geom* g) {
     if (L < 1 || L > kLmaxLimit || (1 << L) < 2 * R) return false;
     const int S = c->chunk_symbols;
     if (S != 64 && S != 128 && S != 256) return false;
-    if (c->flags & ~(int32_t)(DLC_FLAG_CARRY_CODEBOOK | DLC_FLAG_ROW_MATCH)) return false;
+    if (c->flags & ~(int32_t)(DLC_FLAG_CARRY_CODEBOOK | DLC_FLAG_ROW_MATCH | DLC_FLAG_STATS_WORKSPACE)) return false;
     if (c->flags & DLC_FLAG_ROW_MATCH) {  // not with the other flags, and a lane's four elements must lie in one row
-        if (c->flags != DLC_FLAG_ROW_MATCH || c->dim % 4 != 0) return false;
+        if ((c->flags & ~(int32_t)DLC_FLAG_STATS_WORKSPACE) != DLC_FLAG_ROW_MATCH || c->dim % 4 != 0) return false;
     }
     const int64_t nd = c->num_dest == 0 ? 1 : c->num_dest;  // 0: a zero-initialised field means one destination
     if (nd < 1 || nd > 4096) return false;
@@ -183,6 +183,26 @@ extern "C" size_t dlc_workspace_bytes(const dlc_config* cfg) {
     return carve(g, nullptr, nullptr);
 }
 
+// the statistics reduction's own buffers: allocated by the first dlc_stats call, or by dlc_create when the
+// configuration asks for them there (DLC_FLAG_STATS_WORKSPACE), so that a later call never allocates
+static int stats_workspace(const Geom& g, Ws& w) {
+    if (w.stats_base) return DLC_OK;
+    size_t off = 0;
+    auto take = [&](size_t b) { size_t o = off; off = a256(off + b); return o; };
+    const size_t o_probe = take(sizeof(QParam) * g.T);
+    const size_t o_own = take(2ull * g.T * g.B * 4);
+    const size_t o_mult = take(16ull * g.D);
+    const size_t o_hash = take(2ull * g.T * g.B * 8);
+    const size_t o_mm = take(8ull * g.T);
+    const size_t o_un = take(8ull * g.T);
+    uint8_t* base = nullptr;
+    if (hipMalloc((void**)&base, off) != hipSuccess) { (void)hipGetLastError(); return DLC_ENOMEM; }
+    w.stats_base = base; w.stats_bytes = off;
+    w.probe = (QParam*)(base + o_probe); w.st_own = (uint32_t*)(base + o_own); w.st_mult = (uint32_t*)(base + o_mult);
+    w.rowhash = (uint64_t*)(base + o_hash); w.st_minmax = (uint32_t*)(base + o_mm); w.st_unique = (uint32_t*)(base + o_un);
+    return DLC_OK;
+}
+
 extern "C" int dlc_create(dlc_ctx** out, const dlc_config* cfg) {
     if (!out) return DLC_EINVAL;
     *out = nullptr;
@@ -224,6 +244,12 @@ extern "C" int dlc_create(dlc_ctx** out, const dlc_config* cfg) {
             dlc_destroy(c);
             return DLC_EHIP;
         }
+    if ((cfg->flags & DLC_FLAG_STATS_WORKSPACE) && g.ND == 1) {
+        if (const int rc = stats_workspace(g, c->ws); rc != DLC_OK) {
+            dlc_destroy(c);
+            return rc;
+        }
+    }
     *out = c;
     return DLC_OK;
 }
@@ -560,21 +586,7 @@ extern "C" int dlc_stats(dlc_ctx* c, const void* d_payload, const float* probe_e
         if (!good_eb(probe_eb[t])) return DLC_EINVAL;
     hipStream_t s = (hipStream_t)stream;
     Ws& w = c->ws;
-    if (!w.stats_base) {
-        size_t off = 0;
-        auto take = [&](size_t b) { size_t o = off; off = a256(off + b); return o; };
-        const size_t o_probe = take(sizeof(QParam) * g.T);
-        const size_t o_own = take(2ull * g.T * g.B * 4);
-        const size_t o_mult = take(16ull * g.D);
-        const size_t o_hash = take(2ull * g.T * g.B * 8);
-        const size_t o_mm = take(8ull * g.T);
-        const size_t o_un = take(8ull * g.T);
-        uint8_t* base = nullptr;
-        if (hipMalloc((void**)&base, off) != hipSuccess) { (void)hipGetLastError(); return DLC_ENOMEM; }
-        w.stats_base = base; w.stats_bytes = off;
-        w.probe = (QParam*)(base + o_probe); w.st_own = (uint32_t*)(base + o_own); w.st_mult = (uint32_t*)(base + o_mult);
-        w.rowhash = (uint64_t*)(base + o_hash); w.st_minmax = (uint32_t*)(base + o_mm); w.st_unique = (uint32_t*)(base + o_un);
-    }
+    if (const int rc = stats_workspace(g, w); rc != DLC_OK) return rc;
     std::vector<QParam> pq(g.T);
     for (uint32_t t = 0; t < g.T; ++t) pq[t] = make_qparam(probe_eb[t]);
     std::vector<uint32_t> mm(2 * g.T), un(2 * g.T);

@@ -163,9 +163,17 @@ __device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, 
     const uint32_t per = (K + 255) / 256;
     const uint32_t k0 = tid * per, k1 = min(K, k0 + per);
     uint32_t mine = 0;
-    for (uint32_t k = k0; k < k1; ++k) {
-        // the counts were added by device-scope atomics of other work-groups, possibly on other dies
-        const uint32_t h = __hip_atomic_load(&hist_t[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // the counts were added by device-scope atomics of other work-groups, possibly on other dies; a thread's loads
+    // go out together (at most 16: an alphabet of 4096 symbols)
+    uint32_t hv[16];
+#pragma unroll
+    for (uint32_t i = 0; i < 16; ++i)
+        hv[i] = k0 + i < k1 ? __hip_atomic_load(&hist_t[k0 + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+#pragma unroll
+    for (uint32_t i = 0; i < 16; ++i) {
+        const uint32_t k = k0 + i;
+        if (k >= k1) break;
+        const uint32_t h = hv[i];
         // a codebook that is carried to the next call always has a code for the escape symbol
         cnt[k] = h + ((carry != 0u && k == 0u) ? 1u : 0u);
         if (hist_t != hist_view_t) {  // (the copy itself can be the source: it is left as it is)

@@ -204,3 +204,53 @@ def test_workload5_iteration_schedule():
     s = np.array(seen_mult)
     assert np.all(np.diff(s) <= 0) and len(set(s[:100].tolist())) == 5 and len(set(s[100:].tolist())) == 1
     assert abs(s[0] / s[-1] - 2.0) < 1e-6
+
+
+def test_workload5_full_size_backward_payload():
+    """The backward payload (gradients, N(0, 1e-4)) of workload 5 at its full size, 128 x 8192 x 128: container and
+    reconstruction against the oracle byte for byte, default path and single-pass path (second call of a chain)."""
+    import torch
+    from paper_2407_04272_amd import binding as b
+    print("workload 5: backward payload at full size", flush=True)
+    gen = W.Workload5(device="cuda")
+    _, bwd = gen.step()
+    bwd = bwd.clone()
+    T = bwd.shape[0]
+    ctx = b.Context(b.make_config(b.F32, *bwd.shape, flags=b.FLAG_STATS_WORKSPACE))
+    probe = np.full(T, 1e-5, np.float32)
+    st = ctx.stats(bwd, probe)
+    p = _params(b, gen.meta, decay=True)
+    ebs, _ = ctx.set_error_bounds(stats=st, params=p, iteration=100)
+    data, sizes, rec = _roundtrip(ctx, bwd, ebs)
+    _check_bound_gpu(bwd, rec, ebs)
+    x = bwd.cpu().numpy()
+    print("oracle...", flush=True)
+    ost = oracle.stats(x, probe)
+    oeb, _ = oracle.controller(ost, _oracle_params(p), 100)
+    assert np.array_equal(oeb.view(np.uint32), ebs.view(np.uint32))
+    o = oracle.compress(x, oeb, want_hist=True)
+    assert o.rc == 0 and o.data.size == data.size and np.array_equal(o.data, data)
+    assert np.array_equal(o.sizes, sizes)
+    rc, orec = oracle.decompress(o.data, x.shape, np.float32)
+    assert rc == 0 and np.array_equal(orec.view(np.uint32), rec.cpu().numpy().view(np.uint32))
+    # the single-pass path: the second call is coded with the codebook of the first call's counts
+    cctx = b.Context(b.make_config(b.F32, *bwd.shape, flags=b.FLAG_CARRY_CODEBOOK))
+    _roundtrip(cctx, bwd, ebs)
+    data2, sizes2, rec2 = _roundtrip(cctx, bwd, ebs)
+    o2 = oracle.compress(x, oeb, carry_hist=o.hist)
+    assert o2.rc == 0 and o2.data.size == data2.size and np.array_equal(o2.data, data2)
+    assert np.array_equal(o2.sizes, sizes2)
+    _check_bound_gpu(bwd, rec2, ebs)
+
+
+def test_statistics_workspace_at_create_time():
+    """DLC_FLAG_STATS_WORKSPACE: the same statistics, from buffers that dlc_create has allocated."""
+    from paper_2407_04272_amd import binding as b
+    w = W.workload3(T=4, B=2048, D=64, rows=5000, device="cuda")
+    d = w.payload
+    probe = np.full(4, 1e-3, np.float32)
+    a = b.Context(b.make_config(b.F32, *d.shape)).stats(d, probe)
+    for flags in (b.FLAG_STATS_WORKSPACE, b.FLAG_STATS_WORKSPACE | b.FLAG_CARRY_CODEBOOK, b.FLAG_STATS_WORKSPACE | b.FLAG_ROW_MATCH):
+        c = b.Context(b.make_config(b.F32, *d.shape, flags=flags)).stats(d, probe)
+        for t in range(4):
+            assert (a[t].min, a[t].max, a[t].n_unique_raw, a[t].n_unique_quant) == (c[t].min, c[t].max, c[t].n_unique_raw, c[t].n_unique_quant)
