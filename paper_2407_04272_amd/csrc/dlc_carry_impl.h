@@ -32,7 +32,7 @@ namespace dlc {
 typedef __attribute__((address_space(3))) uint32_t lds_u32;
 
 constexpr uint32_t kCarryBlk = 2;   // units (16-byte loads per lane) worked on together
-constexpr uint32_t kCarryLoad = 4;  // units loaded together, one such block ahead of the work
+constexpr uint32_t kCarryLoad = 2;  // units loaded together, one such block ahead of the work (4: registers spill, slower)
 
 // The kernel's code table: row i in [1, 255] stands for symbol win_lo + i - 1; rows 0 and 256 for everything else
 // (a symbol outside the window, NaN, a position past the end of the table).  A row is one word: codeword in bits 0-11,
