@@ -294,6 +294,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geom g, FixedLayout F, c
                 for (uint32_t base = 0; base < nl; base += 64) {
                     const uint32_t i = base + lane;
                     const uint32_t L = i < nl ? sc.len[i] : 0u;
+                    if (__ballot(L != 0u) == 0ull) continue;  // (a stretch of unused symbols: the escape symbol's code can lie far below the others)
 #pragma unroll
                     for (uint32_t l = 1; l <= (uint32_t)kLmaxLimit; ++l) {
                         const uint64_t m = __ballot(L == l);

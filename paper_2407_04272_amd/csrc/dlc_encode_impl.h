@@ -108,7 +108,7 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
         const bool ragged = rem < kW * (uint32_t)S;  // uniform: the table ends inside this group
 #pragma clang loop unroll(full)
         for (int j = 0; j < S / 4; ++j) ix[j] = plane[(uint32_t)j * kW + lane];
-        constexpr int kB1 = 8;  // words whose table reads are in flight together
+        constexpr int kB1 = 4;  // words whose table reads are in flight together
 #pragma clang loop unroll(full)
         for (int jb = 0; jb < S / 4; jb += kB1) {
             if (ragged) {  // whatever the plane holds past the end of the table does not count
@@ -207,7 +207,7 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
         uint32_t* p = staged ? stage + lane_off : reinterpret_cast<uint32_t*>(out + F.off_payload) + excl + lane_off;
         uint64_t acc = 0;
         uint32_t nb = 0;
-        constexpr int kB2 = 4;  // words of indices whose table reads are in flight together
+        constexpr int kB2 = 2;  // words of indices whose table reads are in flight together
 #pragma clang loop unroll(full)
         for (int jb = 0; jb < S / 4; jb += kB2) {
             if (staged && wave == 0 && !L.done && (jb % 8) == 0) {  // uniform: one look-back step per eight words
