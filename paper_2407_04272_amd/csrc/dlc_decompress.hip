@@ -376,8 +376,12 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geom g, FixedLayout F, c
             const uint32_t cw = gh.cw, n_esc = gp.n_esc, total = gp.total;
             const uint32_t* const chunk = gp.chunk;
             // the words from `nxt` on, anew, so that `nxt` is row 0
+            // more = words of the chunk past row 0 of the staging rows, less one: a lane needs new rows when `nxt` is
+            // among the last two rows (a turn moves at most two words on) and kr < more
+            int more = (int)cw - 1;
             auto restage = [&]() {
                 wbase += kr;
+                more -= (int)kr;
                 kr = 0;
                 uint32_t w[kWin];
                 fetch_words(chunk, cw, wbase, w);
@@ -403,7 +407,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geom g, FixedLayout F, c
                 const uint32_t idx = base + j * (kW * kV);
                 // a turn moves at most two more words; restage (whole wavefront) when a lane that still has words to
                 // fetch could run off its rows
-                if (__ballot(kr + 2u >= kWin && wbase + kr + 1u < cw) != 0ull) restage();
+                if (__ballot(kr >= kWin - 2u && (int)kr < more) != 0ull) restage();
                 bool coded = idx < g.n;
                 if (ref != nullptr && coded) {  // a row that refers to another has no bits in the stream; it is copied afterwards
                     const uint32_t r = idx / g.D - row_lo;
