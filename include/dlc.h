@@ -71,7 +71,8 @@ typedef enum {
 /* Geometry and format parameters of one payload (Section III-D leaves them open). */
 typedef struct {
     int32_t dtype;         /* DLC_F32 or DLC_F16 */
-    int32_t num_tables;    /* T >= 1 */
+    int32_t num_tables;    /* T >= 1; a container's worst case (every element an escape: two words each on top of the
+                              codewords) must stay below 2^32 words, which allows about 1.6e9 elements per container */
     int64_t batch;         /* B >= 1 rows per table */
     int64_t dim;           /* D >= 1 elements per row; B*D < 2^31 */
     int32_t radius;        /* R: power of two in [8, 2048]; alphabet 2R, symbol 0 = verbatim escape */

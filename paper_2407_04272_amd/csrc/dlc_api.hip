@@ -99,6 +99,9 @@ static bool make_geom(const dlc_config* c, Geom* g) {
     const uint64_t NG = G * T;
     if (NG * GS > 0xFFFFFFFFull) return false;                                 // element positions are 32-bit
     if (NG * kW * (((uint64_t)S * L + 31) / 32) > 0xFFFFFFFFull) return false;  // word offsets are 32-bit
+    // ... also when every element of a container is an escape (two more words each): group offsets, scan records and
+    // word ranges could not say where such a payload's groups start
+    if ((uint64_t)c->num_tables * G * kW * (((uint64_t)S * L + 31) / 32) + 2ull * n * (uint64_t)c->num_tables > 0xFFFFFFFFull) return false;
     g->ND = (uint32_t)nd; g->TD = (uint32_t)c->num_tables;
     g->T = (uint32_t)T; g->B = (uint32_t)c->batch; g->D = (uint32_t)c->dim; g->n = (uint32_t)n;
     g->G = (uint32_t)G; g->NG = (uint32_t)NG; g->S = (uint32_t)S; g->R = (uint32_t)R; g->K = 2u * R;

@@ -39,7 +39,8 @@ def test_host_only_entry_points():
                 b.make_config(b.F32, 1, 8, 8, radius=4096), b.make_config(b.F32, 1, 8, 8, chunk_symbols=100),
                 b.make_config(b.F32, 1, 8, 8, max_code_len=9), b.make_config(b.F32, 1, 8, 8, max_code_len=13),
                 b.make_config(b.F32, 1, 1 << 20, 1 << 12),          # B*D >= 2^31
-                b.make_config(b.F32, 4096, 1 << 18, 1 << 10)]:     # more than 2^32 element positions
+                b.make_config(b.F32, 4096, 1 << 18, 1 << 10),      # more than 2^32 element positions
+                b.make_config(b.F32, 16, 1 << 20, 128)]:            # 2^31 elements: all escapes would need more than 2^32 words
         assert b.dlc_compress_bound(bad) == 0
         assert b.dlc_workspace_bytes(bad) == 0
     # flags: row matching wants whole rows per lane (dim % 4 == 0), goes with several destinations, not with the
