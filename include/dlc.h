@@ -127,7 +127,7 @@ enum { DLC_FLAG_CARRY_CODEBOOK = 2, DLC_FLAG_ROW_MATCH = 4, DLC_FLAG_STATS_WORKS
  * byte offset, 0 for a table without).  A referenced row is therefore always a coded one and the decoder copies rows
  * in parallel.  Per table: dlc_set_row_match switches it on and off (all on after dlc_create), which is what the
  * compressor selection of Section III-D (Eq. 2, dlc_speedup_estimate) decides offline.  Needs dim % 4 == 0; not
- * together with the other flags; num_dest * num_tables <= 65535.  With num_dest > 1 rows are matched inside a
+ * together with DLC_FLAG_CARRY_CODEBOOK; num_dest * num_tables <= 65535.  With num_dest > 1 rows are matched inside a
  * destination's piece (a container never refers to another).  The search hashes rows and compares every candidate
  * element by element; rows whose hashes meet are sorted out the long way, so the references are always those of the
  * definition. */

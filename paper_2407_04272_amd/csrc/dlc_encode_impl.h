@@ -59,7 +59,9 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
               uint32_t* word_start, uint32_t* word_end) {
     __shared__ __align__(16) uint16_t s_len[256], s_code[256];  // by window index; entry 255 is empty
     __shared__ uint32_t s_wg, s_tot[4], s_ct[4], s_excl, s_dead;
-    constexpr uint32_t kStageWords = 8u * (uint32_t)S;  // LDS staging per wavefront: room for a group of up to 4 bits per symbol
+    // LDS staging per wavefront: room for a group of up to 4.7 bits per symbol, which is what four work-groups per
+    // compute unit leave (with 4 bits a payload compressed 7 times no longer fitted and the kernel took twice as long)
+    constexpr uint32_t kStageWords = 75u * (uint32_t)S / 8u;
     __shared__ __align__(16) uint32_t s_stage[4 * kStageWords];
     // escapes a wavefront remembers in LDS (their offsets in the group; the raw bits are read again when the records
     // are written); a group with more walks its elements again
