@@ -68,6 +68,7 @@ struct CarryEnv {
     uint16_t* recs;        // LDS: where in the group the wavefront has met escapes, kCarryRecs at most
     uint32_t sp_base;      // LDS address of this lane's column of the staging rows
     uint32_t row_max;      // the last staging row
+    uint32_t* dst;         // second walk of a group that did not fit its staging rows: the lane's chunk in memory
 };
 
 struct CarryState {
@@ -82,6 +83,16 @@ __device__ __forceinline__ void carry_flush(const CarryEnv& E, const CarryState&
     const uint32_t row = min(S.nbt >> 5, E.row_max);
     const uint32_t word = __builtin_amdgcn_alignbit((uint32_t)(S.acc >> 32), (uint32_t)S.acc, S.nbt);  // (shift: nbt mod 32)
     *reinterpret_cast<lds_u32*>(E.sp_base + row * (kW * 4u)) = word;
+}
+
+// the same for a walk that writes a chunk straight to memory (the chunks' places are known by then): a word goes
+// out once, when it is complete (S.nrec counts the words written: the second walk keeps no records)
+__device__ __forceinline__ void carry_flush_mem(const CarryEnv& E, CarryState& S) {
+    const uint32_t k = S.nbt >> 5;
+    if (k != S.nrec) {
+        E.dst[k - 1u] = __builtin_amdgcn_alignbit((uint32_t)(S.acc >> 32), (uint32_t)S.acc, S.nbt);
+        S.nrec = k;
+    }
 }
 
 // codeword and length of an element the table had no answer for, with the quantiser's own arithmetic: a symbol
@@ -112,7 +123,9 @@ __device__ __forceinline__ void carry_slow_entry(const CarryEnv& E, float x, boo
 }
 
 // One block of kCarryBlk units already loaded: quantise, count, look up, append.
-template <bool F16, bool FULL>
+// REWALK: the group is walked a second time because a chunk did not fit its staging rows; nothing is counted or
+// recorded again, and the words go to memory.
+template <bool F16, bool FULL, bool REWALK>
 __device__ __forceinline__ void carry_block(const CarryEnv& E, const float (&x)[kCarryBlk][4], const uint32_t (&valid)[kCarryBlk],
                                             uint32_t jb, CarryState& S) {
     uint32_t a[kCarryBlk][4];
@@ -143,11 +156,13 @@ __device__ __forceinline__ void carry_block(const CarryEnv& E, const float (&x)[
     for (uint32_t u = 0; u < kCarryBlk; ++u)
 #pragma unroll
         for (int v = 0; v < 4; ++v) code[u][v] = *reinterpret_cast<lds_u32*>(a[u][v]);
+    if constexpr (!REWALK) {
 #pragma unroll
-    for (uint32_t u = 0; u < kCarryBlk; ++u)
+        for (uint32_t u = 0; u < kCarryBlk; ++u)
 #pragma unroll
-        for (int v = 0; v < 4; ++v)
-            __hip_atomic_fetch_add(reinterpret_cast<lds_u32*>(a[u][v]), 0x10000u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            for (int v = 0; v < 4; ++v)
+                __hip_atomic_fetch_add(reinterpret_cast<lds_u32*>(a[u][v]), 0x10000u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
 #pragma unroll
     for (uint32_t u = 0; u < kCarryBlk; ++u)
 #pragma unroll
@@ -177,8 +192,8 @@ __device__ __forceinline__ void carry_block(const CarryEnv& E, const float (&x)[
             for (int v = 0; v < 4; ++v) {
                 if (len[u][v] != 0u) continue;
                 bool is_esc;
-                carry_slow_entry<F16>(E, x[u][v], FULL || ((valid[u] >> v) & 1u), a[u][v], len[u][v], code[u][v], is_esc, true);
-                if (is_esc) { ++S.esc; em |= 1u << v; }
+                carry_slow_entry<F16>(E, x[u][v], FULL || ((valid[u] >> v) & 1u), a[u][v], len[u][v], code[u][v], is_esc, !REWALK);
+                if (is_esc && !REWALK) { ++S.esc; em |= 1u << v; }
             }
             // the records of these escapes, in element order (the walk meets the elements of a group in
             // increasing index: turn, lane, position); their offsets are kept while they fit.
@@ -201,15 +216,15 @@ __device__ __forceinline__ void carry_block(const CarryEnv& E, const float (&x)[
             // the rule: the four codewords as one piece of at most 32 bits
             S.acc = (S.acc << L) | ((c01 << l23) | c23);
             S.nbt += L;
-            carry_flush(E, S);
+            if constexpr (REWALK) carry_flush_mem(E, S); else carry_flush(E, S);
         } else {
             // two pieces of at most 24 bits
             S.acc = (S.acc << l01) | c01;
             S.nbt += l01;
-            carry_flush(E, S);
+            if constexpr (REWALK) carry_flush_mem(E, S); else carry_flush(E, S);
             S.acc = (S.acc << l23) | c23;
             S.nbt += l23;
-            carry_flush(E, S);
+            if constexpr (REWALK) carry_flush_mem(E, S); else carry_flush(E, S);
         }
     }
 }
@@ -225,7 +240,7 @@ __device__ __forceinline__ void carry_load(const CarryEnv& E, uint32_t jb, float
 // One walk over a group: lane l codes chunk l (at turn j the four elements group_base + j*256 + 4*l .. +3).  The
 // loads of the next kCarryLoad turns are issued before the current ones are worked on; those of the first turns
 // (xa, va) are already on their way when the walk starts.
-template <int S, bool F16, bool VEC, bool FULL>
+template <int S, bool F16, bool VEC, bool FULL, bool REWALK = false>
 __device__ __forceinline__ void carry_walk(const CarryEnv& E, CarryState& St, float (&xa)[kCarryLoad][4], uint32_t (&va)[kCarryLoad]) {
     constexpr uint32_t N = (uint32_t)S / kV;  // turns
     static_assert(N % (2 * kCarryLoad) == 0 && kCarryLoad % kCarryBlk == 0, "two load blocks per trip, whole work blocks per load block");
@@ -237,39 +252,12 @@ __device__ __forceinline__ void carry_walk(const CarryEnv& E, CarryState& St, fl
         carry_load<F16, VEC, FULL>(E, jb + kCarryLoad, xb, vb);
 #pragma unroll
         for (uint32_t k = 0; k < kCarryLoad; k += kCarryBlk)
-            carry_block<F16, FULL>(E, reinterpret_cast<XBlk>(xa[k]), reinterpret_cast<VBlk>(va[k]), jb + k, St);
+            carry_block<F16, FULL, REWALK>(E, reinterpret_cast<XBlk>(xa[k]), reinterpret_cast<VBlk>(va[k]), jb + k, St);
         if (jb + 2 * kCarryLoad < N) carry_load<F16, VEC, FULL>(E, jb + 2 * kCarryLoad, xa, va);
 #pragma unroll
         for (uint32_t k = 0; k < kCarryLoad; k += kCarryBlk)
-            carry_block<F16, FULL>(E, reinterpret_cast<XBlk>(xb[k]), reinterpret_cast<VBlk>(vb[k]), jb + kCarryLoad + k, St);
+            carry_block<F16, FULL, REWALK>(E, reinterpret_cast<XBlk>(xb[k]), reinterpret_cast<VBlk>(vb[k]), jb + kCarryLoad + k, St);
     }
-}
-
-// A group with a chunk that did not fit its staging rows is coded once more, straight to memory now that the
-// chunks' places are known (a rolled loop: rare for the compression ratios the staging is sized for).  Nothing
-// is counted again.
-template <int S, bool F16, bool VEC>
-__device__ __forceinline__ void carry_walk_to_memory(const CarryEnv& E, uint32_t* dst) {
-    uint64_t acc = 0;
-    uint32_t nb = 0;
-    for (uint32_t j = 0; j < (uint32_t)S / kV; ++j) {
-        float x[4];
-        uint32_t raw[4];
-        const uint32_t valid = load4<F16, VEC>(E.gbase, E.lane * kV + j * (kW * kV), E.rem, x, raw);
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            uint32_t len, code;
-            bool is_esc;
-            carry_slow_entry<F16>(E, x[v], ((valid >> v) & 1u) != 0u, E.row0, len, code, is_esc, false);
-            acc = (acc << len) | code;
-            nb += len;
-            if (nb >= 32u) {
-                nb -= 32u;
-                *dst++ = (uint32_t)(acc >> nb);
-            }
-        }
-    }
-    if (nb) *dst = (uint32_t)(acc << (32u - nb));
 }
 
 // escape records of one group under a carried codebook: as emit_escapes, but a symbol without a code is one too
@@ -422,14 +410,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
                     (uint32_t)St.acc << (32u - (St.nbt & 31u));
         }
         // the next item's first elements: on their way while this item is written out
-        if (item + 1u < i1) {
-            CarryEnv En = E;
-            locate(item + 1u, En.gbase, En.rem);
-            if (En.rem != 0u) {
-                if (En.rem >= kGroupEls) carry_load<F16, VEC, true>(En, 0, xa, va);
-                else carry_load<F16, VEC, false>(En, 0, xa, va);
+        auto ask_for_next = [&]() {
+            if (item + 1u < i1) {
+                CarryEnv En = E;
+                locate(item + 1u, En.gbase, En.rem);
+                if (En.rem != 0u) {
+                    if (En.rem >= kGroupEls) carry_load<F16, VEC, true>(En, 0, xa, va);
+                    else carry_load<F16, VEC, false>(En, 0, xa, va);
+                }
             }
-        }
+        };
+        ask_for_next();
         const uint32_t nw = (St.nbt + 31u) >> 5;
         const bool spilled = __ballot(nw > CAP) != 0ull;  // uniform: a chunk of this group did not fit its LDS words
         const uint32_t n_esc = active ? wave_sum(St.esc) : 0u;
@@ -464,7 +455,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
             if (!spilled) {
                 for (uint32_t k = lane; k < chunk_total; k += 64) gw[k] = stage[k];
             } else {
-                carry_walk_to_memory<S, F16, VEC>(E, gw + lane_off);
+                // A chunk of the group has more words than its staging rows: the group is walked again, the same way
+                // but for the counts and the records, and every lane writes its chunk's words to memory as they get
+                // complete (4 bytes a lane and 64 lines an instruction: the slow way out, for payloads that take more
+                // than 4 bits per symbol).  The loads of the next item, already on their way, are asked for again.
+                E.dst = gw + lane_off;
+                CarryState Sr;
+                Sr.acc = 0; Sr.nbt = 0; Sr.esc = 0; Sr.nrec = 0;
+                if (full) {
+                    carry_load<F16, VEC, true>(E, 0, xa, va);
+                    carry_walk<S, F16, VEC, true, true>(E, Sr, xa, va);
+                } else {
+                    carry_load<F16, VEC, false>(E, 0, xa, va);
+                    carry_walk<S, F16, VEC, false, true>(E, Sr, xa, va);
+                }
+                if (Sr.nbt & 31u) E.dst[Sr.nbt >> 5] = (uint32_t)Sr.acc << (32u - (Sr.nbt & 31u));
+                ask_for_next();
             }
             if (n_esc != 0u) {  // uniform over the wavefront
                 uint32_t* rec = gw + chunk_total;
