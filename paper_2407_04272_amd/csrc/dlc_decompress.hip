@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void k_dec_refs(Geom g, FixedLayout F, const u
 // ------------------------------------------------------------------------------------------------
 // chunk-parallel decode.  A work-group belongs to one table: it checks the container's header and the table's
 // directory entry, rebuilds the canonical code from the stored lengths into an LDS decode table, and then decodes
-// `iters` consecutive blocks of kDecWaves groups, one wavefront per group, lane l walking chunk l.  Each lane keeps
+// `iters` consecutive blocks of NW groups (NW = wavefronts of the work-group), one wavefront per group, lane l walking chunk l.  Each lane keeps
 // a 64-bit window of its own bit stream, looks LMAX bits up in the decode table, and the four symbols of a turn
 // leave as one 16-byte store (1 KiB contiguous per wavefront instruction).  Nothing is read from a table that fails
 // validation.
@@ -140,8 +140,8 @@ __global__ __launch_bounds__(256) void k_dec_refs(Geom g, FixedLayout F, const u
 // directory entry (counters in the workspace, zero between calls).
 // ------------------------------------------------------------------------------------------------
 constexpr uint32_t kWin = 30;                         // staged words per lane (two work-groups share a CU's LDS)
-constexpr uint32_t kDecWaves = 8;                     // wavefronts per work-group
-constexpr uint32_t kDecThreads = 64 * kDecWaves;
+constexpr uint32_t kDecWaves = 8;                     // wavefronts per work-group; 4 or 2 for tables of fewer groups (a
+                                                      // destination's piece of a table can be two groups: no idle wavefronts)
 constexpr uint32_t kSkipWords = 256 * kW / kV / 32;   // row matching: a bit per row of a group, rows of at least four elements
 
 struct DecScratch {  // lives in the staging area until the decode table is complete
@@ -151,7 +151,10 @@ struct DecScratch {  // lives in the staging area until the decode table is comp
     uint16_t one[1 << kLmaxLimit];  // len << 12 | symbol of the codeword that prefixes the LMAX-bit string i
     uint8_t len[4096];
 };
-static_assert(sizeof(DecScratch) <= kDecWaves * kWin * kW * 4, "the scratch must fit the staging area it shares");
+// bytes behind the decode table: the staging arrays of the NW wavefronts, or the scratch where that is larger
+__host__ __device__ constexpr uint32_t dec_area_bytes(uint32_t nw) {
+    return nw * kWin * kW * 4u > (uint32_t)((sizeof(DecScratch) + 15u) & ~15u) ? nw * kWin * kW * 4u : (uint32_t)((sizeof(DecScratch) + 15u) & ~15u);
+}
 
 // (len << 12 | symbol) of the codeword that prefixes the LMAX-bit string i: its length is one more than the number of
 // limits at or below i (limit[l] = first string that no codeword of length <= l prefixes)
@@ -164,13 +167,14 @@ __device__ __forceinline__ uint32_t dec_first_code(const DecScratch& sc, const u
     return (l << 12) | sc.sorted[sc.index[l] + (c - sc.first[l])];
 }
 
-template <bool F16, bool VEC>
-__global__ __launch_bounds__(kDecThreads) void k_decode(Geom g, FixedLayout F, const uint8_t* comp, uint64_t comp_bytes,
+template <bool F16, bool VEC, uint32_t NW>
+__global__ __launch_bounds__(64 * NW) void k_decode(Geom g, FixedLayout F, const uint8_t* comp, uint64_t comp_bytes,
                                                         Ctrl* ctrl, void* outp, uint32_t wpt, uint32_t iters,
                                                         uint32_t* esc_seen, uint32_t* arrived) {
-    extern __shared__ __align__(16) uint32_t s_lut[];  // [1 << LMAX] decode table, then kDecWaves staging arrays
+    constexpr uint32_t kDecThreads = 64u * NW;
+    extern __shared__ __align__(16) uint32_t s_lut[];  // [1 << LMAX] decode table, then NW staging arrays
     __shared__ uint32_t s_bad;
-    __shared__ unsigned long long s_sum[kDecWaves];
+    __shared__ unsigned long long s_sum[NW];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t t = blockIdx.x / wpt, b = blockIdx.x % wpt;
     const uint32_t dst = t / g.TD, tl = t - dst * g.TD;  // the container this table is in, and its place there
@@ -190,7 +194,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geom g, FixedLayout F, c
         h.gnext = gid + 1 < n_groups ? goffs[gid + 1] : 0xFFFFFFFFu;  // (the last group ends where the payload does)
         return h;
     };
-    const uint32_t grp_first = b * iters * kDecWaves + wave;
+    const uint32_t grp_first = b * iters * NW + wave;
     GroupHead gh;
     gh.cw = 0; gh.goff = 0; gh.gnext = 0;
     if (grp_first < g.G) gh = group_head(grp_first);
@@ -257,7 +261,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geom g, FixedLayout F, c
         __syncthreads();
         if (tid == 0) {
             unsigned long long all = 0;
-            for (uint32_t k = 0; k < kDecWaves; ++k) all += s_sum[k];
+            for (uint32_t k = 0; k < NW; ++k) all += s_sum[k];
             if (all != H.n_esc_total) s_bad = 1u;
         }
         if (big) s_bad = 1u;
@@ -350,9 +354,9 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(Geom g, FixedLayout F, c
         uint8_t* tab = static_cast<uint8_t*>(outp) + (size_t)t * g.n * g.es;
         const uint32_t turns = g.S / kV;
         const uint32_t* const ref = H.ref_off ? reinterpret_cast<const uint32_t*>(comp + H.ref_off) : nullptr;
-        uint32_t* const skipbits = reinterpret_cast<uint32_t*>(s_lut + lut_n) + kDecWaves * (kWin * kW) + wave * kSkipWords;
+        uint32_t* const skipbits = reinterpret_cast<uint32_t*>(s_lut + lut_n) + dec_area_bytes(NW) / 4u + wave * kSkipWords;
         for (uint32_t it = 0; it < iters; ++it) {
-            const uint32_t grp = grp_first + it * kDecWaves;
+            const uint32_t grp = grp_first + it * NW;
             if (grp >= g.G) break;  // whole wavefront
             // A lane's place in its bit stream: the two words w0, w1 it is decoding from, `c` bits of w0 already used
             // (0..31), the word after them in `nxt`, fetched ahead from the staging rows; kr = staging row of `nxt`,
@@ -553,19 +557,23 @@ hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_b
     if (g.lz)  // before the decode kernel: the row-copy kernel follows the references only where they were checked
         hipLaunchKernelGGL(k_dec_refs, dim3(g.T), dim3(256), 0, s, g, F, comp, comp_bytes, w.dtab, w.ctrl);
     {
-        // a work-group decodes `iters` blocks of kDecWaves groups of one table: enough blocks to spread the cost of
-        // its decode table, enough work-groups (a few thousand) to fill the chip whatever the shape
-        const uint32_t bpt = (g.G + kDecWaves - 1) / kDecWaves;
+        // a work-group decodes `iters` blocks of nw groups of one table, a wavefront each: enough blocks to spread the
+        // cost of its decode table, enough work-groups (a few thousand) to fill the chip whatever the shape, and no
+        // more wavefronts than a table has groups
+        const uint32_t nw = g.G >= 6u ? kDecWaves : (g.G >= 3u ? 4u : 2u);
+        const uint32_t bpt = (g.G + nw - 1) / nw;
         const uint64_t blocks = (uint64_t)g.T * bpt;
         const uint32_t iters = (uint32_t)std::min<uint64_t>(4, std::max<uint64_t>(1, blocks / 2048));
         const uint32_t wpt = (bpt + iters - 1) / iters;  // work-groups per table
-        dim3 grid(g.T * wpt), block(kDecThreads);
-        const size_t sm = ((size_t)4 << g.LMAX) + (size_t)kDecWaves * kWin * kW * 4 + (g.lz ? (size_t)kDecWaves * kSkipWords * 4 : 0);
+        dim3 grid(g.T * wpt), block(64 * nw);
+        const size_t sm = ((size_t)4 << g.LMAX) + dec_area_bytes(nw) + (g.lz ? (size_t)nw * kSkipWords * 4 : 0);
         if (prof_on(pl, P_DECODE)) prof_begin(prof, P_DECODE, s);
-#define DLC_DEC(FF, V) hipLaunchKernelGGL((k_decode<FF, V>), grid, block, sm, s, g, F, comp, (uint64_t)comp_bytes, w.ctrl, out, wpt, iters, w.dec_esc, w.dec_arrive)
+#define DLC_DEC2(FF, V, N) hipLaunchKernelGGL((k_decode<FF, V, N>), grid, block, sm, s, g, F, comp, (uint64_t)comp_bytes, w.ctrl, out, wpt, iters, w.dec_esc, w.dec_arrive)
+#define DLC_DEC(FF, V) do { if (nw == 8u) DLC_DEC2(FF, V, 8u); else if (nw == 4u) DLC_DEC2(FF, V, 4u); else DLC_DEC2(FF, V, 2u); } while (0)
         if (f16) { if (g.vec) DLC_DEC(true, true); else DLC_DEC(true, false); }
         else { if (g.vec) DLC_DEC(false, true); else DLC_DEC(false, false); }
 #undef DLC_DEC
+#undef DLC_DEC2
         if (g.lz) {
             const uint32_t bx = std::min<uint32_t>((g.B * (g.D / 4u) + 255u) / 256u, 256u);
             if (f16) hipLaunchKernelGGL(k_row_copy<uint2>, dim3(bx, g.T), dim3(256), 0, s, g, comp, (uint64_t)comp_bytes, w.dtab, out);
@@ -576,19 +584,27 @@ hipError_t launch_decompress(const Geom& g, const uint8_t* comp, uint64_t comp_b
     return hipGetLastError();
 }
 
-hipError_t decompress_set_attributes() {
-    const int bytes = (4 << kLmaxLimit) + (int)(kDecWaves * kWin * kW * 4) + (int)(kDecWaves * kSkipWords * 4);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_decode<false, false>),
+template <uint32_t NW>
+static hipError_t decode_set_attributes() {
+    const int bytes = (4 << kLmaxLimit) + (int)dec_area_bytes(NW) + (int)(NW * kSkipWords * 4);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_decode<false, false, NW>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e == hipSuccess)
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_decode<false, true>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_decode<false, true, NW>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e == hipSuccess)
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_decode<true, false>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_decode<true, false, NW>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e == hipSuccess)
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_decode<true, true>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_decode<true, true, NW>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    return e;
+}
+
+hipError_t decompress_set_attributes() {
+    hipError_t e = decode_set_attributes<8u>();
+    if (e == hipSuccess) e = decode_set_attributes<4u>();
+    if (e == hipSuccess) e = decode_set_attributes<2u>();
     return e;
 }
 
