@@ -142,6 +142,83 @@ __device__ __forceinline__ uint32_t wave_huffman_lengths(uint32_t n, uint32_t LM
     return lane < n ? __shfl(len, rank, 64) : 0u;
 }
 
+// The codebook of a table with at most 64 used symbols (the rule), by ONE wavefront: same inputs and outputs as
+// codebook_build below, which takes every other table.  The wavefront reads the histogram 64 symbols at a time,
+// gathers the used symbols into its lanes through `wsm` (LDS of this wavefront: 64 keys, then K entries of 16
+// bits), builds the tree in registers, and writes the K entries of the table and the code lengths.  Returns false,
+// with the histogram untouched, when the table has more than 64 used symbols.
+//   wsm: 512 + 2 * K bytes, 8-byte aligned.
+__host__ __device__ constexpr size_t codebook_wave_smem(uint32_t K) { return 512 + 2 * (size_t)K; }
+__device__ __forceinline__ bool codebook_build_wave(const Geom& g, uint32_t* hist_t, uint32_t* hist_view_t, uint16_t* enc_t,
+                                                    uint8_t* lens_t, TMeta* tmeta_t, unsigned char* wsm, uint32_t lane,
+                                                    uint32_t carry) {
+    const uint32_t K = g.K;  // (a multiple of 64: twice a power of two of at least 8)
+    uint64_t* key = reinterpret_cast<uint64_t*>(wsm);            // [64] count << 16 | symbol of the used symbols, symbol order
+    uint16_t* ent = reinterpret_cast<uint16_t*>(wsm + 512);      // [K] len << 12 | codeword
+    const uint64_t below = (1ull << lane) - 1ull;
+    uint32_t n_used = 0, n_escape = 0;
+    for (uint32_t kb = 0; kb < K; kb += 16u * 64u) {  // sixteen loads of 64 symbols in flight together
+        // the counts were added by device-scope atomics of other work-groups, possibly on other dies
+        uint32_t hv[16];
+#pragma unroll
+        for (uint32_t i = 0; i < 16; ++i)
+            hv[i] = kb + i * 64u < K ? __hip_atomic_load(&hist_t[kb + i * 64u + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+#pragma unroll
+        for (uint32_t i = 0; i < 16; ++i) {
+            const uint32_t k = kb + i * 64u + lane;
+            if (kb + i * 64u >= K) continue;  // uniform
+            const uint32_t h = hv[i];
+            // a codebook that is carried to the next call always has a code for the escape symbol
+            const uint32_t c = h + ((carry != 0u && k == 0u) ? 1u : 0u);
+            if (hist_t != hist_view_t) hist_view_t[k] = h;  // (the copy itself can be the source: it is left as it is)
+            if (kb + i == 0u) n_escape = (uint32_t)__builtin_amdgcn_readfirstlane((int)c);
+            ent[k] = 0;
+            const uint64_t m = __ballot(c != 0u);
+            const uint32_t at = n_used + (uint32_t)__popcll(m & below);
+            if (c != 0u && at < 64u) key[at] = ((uint64_t)c << 16) | k;
+            n_used += (uint32_t)__popcll(m);
+        }
+    }
+    if (n_used > 64u) return false;  // uniform
+    if (hist_t != hist_view_t)
+        for (uint32_t k0 = 0; k0 < K; k0 += 64)
+            __hip_atomic_store(&hist_t[k0 + lane], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_wave_barrier();
+    const uint64_t kv = lane < n_used ? key[lane] : ~0ull;  // lane i: the i-th used symbol
+    const uint32_t sym = (uint32_t)(kv & 0xFFFFu);
+    if (n_used >= 2u) {
+        const uint32_t len = wave_huffman_lengths(n_used, g.LMAX, (uint32_t)(kv >> 16), lane);
+        // canonical codewords: first code of each length, then the rank among the symbols of that length (the lanes
+        // are in symbol order)
+        uint32_t code = 0, mine_code = 0;
+        for (uint32_t L = 1; L <= g.LMAX; ++L) {
+            code <<= 1;
+            const uint64_t same = __ballot(len == L);
+            mine_code = (len == L) ? code + (uint32_t)__popcll(same & below) : mine_code;
+            code += (uint32_t)__popcll(same);
+        }
+        if (lane < n_used) ent[sym] = (uint16_t)((len << 12) | mine_code);
+    }
+    __builtin_amdgcn_wave_barrier();
+    for (uint32_t k0 = 0; k0 < K; k0 += 64) {
+        const uint32_t e = ent[k0 + lane];
+        __hip_atomic_store(&enc_t[k0 + lane], (uint16_t)e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        lens_t[k0 + lane] = (uint8_t)(e >> 12);
+    }
+    if (lane == 0) {
+        TMeta m;
+        m.n_used = n_used;
+        m.sym_lo = n_used ? (uint32_t)(key[0] & 0xFFFFu) : 0u;
+        m.sym_hi = n_used ? (uint32_t)(key[n_used - 1u] & 0xFFFFu) : 0u;
+        m.n_outliers = n_escape;  // symbol 0 = escape
+        *tmeta_t = m;
+    }
+    return true;
+}
+
+// A work-group of four wavefronts builds the codebooks of the tables [t0, t0 + 4): a wavefront each where the table
+// has at most 64 used symbols, the whole work-group one after the other for the rest.
+//   smem: codebook_smem(K) bytes, 16-byte aligned (the wavefronts' areas lie inside it).
 // hist_t is read, copied to hist_view_t (inspection) and cleared, so that the next call starts from zero counts.
 // enc_t is written with device-scope stores: other work-groups of a running kernel may read it once they have
 // seen the caller's completion flag.
@@ -373,6 +450,27 @@ __device__ __forceinline__ void codebook_build(const Geom& g, uint32_t* hist_t, 
         *tmeta_t = m;
     }
     __syncthreads();
+}
+
+__device__ __forceinline__ void codebook_build_four(const Geom& g, uint32_t t0, uint32_t* hist, uint32_t* hist_view, uint16_t* enc,
+                                                    uint8_t* lens, TMeta* tmeta, unsigned char* smem, CodebookShared& sh,
+                                                    uint32_t* slow, uint32_t tid, uint32_t carry) {
+    static_assert(4 * (512 + 2 * 4096) <= 4096 * 24 + 256, "the wavefronts' areas must fit the work-group's");
+    const uint32_t lane = tid & 63u, wave = tid >> 6, t = t0 + wave;
+    if (t < g.T) {  // uniform over the wavefront
+        const bool done = codebook_build_wave(g, hist + (size_t)t * g.K, hist_view + (size_t)t * g.K, enc + (size_t)t * g.K,
+                                              lens + (size_t)t * g.K, tmeta + t, smem + wave * codebook_wave_smem(g.K), lane, carry);
+        if (lane == 0) slow[wave] = done ? 0u : 1u;
+    } else if (lane == 0) {
+        slow[wave] = 0u;
+    }
+    __syncthreads();
+    for (uint32_t w = 0; w < 4; ++w) {
+        if (slow[w] == 0u) continue;  // uniform over the work-group
+        const uint32_t ts = t0 + w;
+        codebook_build(g, hist + (size_t)ts * g.K, hist_view + (size_t)ts * g.K, enc + (size_t)ts * g.K, lens + (size_t)ts * g.K,
+                       tmeta + ts, smem, sh, tid, carry);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------

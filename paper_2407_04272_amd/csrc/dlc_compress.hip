@@ -190,14 +190,25 @@ __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const
 }
 
 // carry != 0: the codebook is for the next call (the escape symbol gets a code whether it occurred or not)
+// tpw: tables per work-group, 1 or 4 (see codebook_tables_per_wg)
 __global__ __launch_bounds__(256) void k_codebook(Geom g, uint32_t* hist, uint32_t* hist_view, uint16_t* enc,
-                                                  uint8_t* lens, TMeta* tmeta, uint32_t carry) {
+                                                  uint8_t* lens, TMeta* tmeta, uint32_t carry, uint32_t tpw) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ CodebookShared sh;
-    const uint32_t t = blockIdx.x;
-    codebook_build(g, hist + (size_t)t * g.K, hist_view + (size_t)t * g.K, enc + (size_t)t * g.K,
-                   lens + (size_t)t * g.K, tmeta + t, smem, sh, threadIdx.x, carry);
+    __shared__ uint32_t s_slow[4];
+    if (tpw == 4u) {
+        codebook_build_four(g, blockIdx.x * 4u, hist, hist_view, enc, lens, tmeta, smem, sh, s_slow, threadIdx.x, carry);
+    } else {
+        const uint32_t t = blockIdx.x;
+        codebook_build(g, hist + (size_t)t * g.K, hist_view + (size_t)t * g.K, enc + (size_t)t * g.K,
+                       lens + (size_t)t * g.K, tmeta + t, smem, sh, threadIdx.x, carry);
+    }
 }
+
+// With few tables a work-group per table (all its threads read the histogram: the shortest way to one codebook); with
+// many, four tables per work-group, a wavefront each (a quarter of the work-groups, and no idle wavefronts while
+// one of them builds the tree).
+static inline uint32_t codebook_tables_per_wg(const Geom& g) { return g.T >= 512u ? 4u : 1u; }
 
 // ------------------------------------------------------------------------------------------------
 // finalize: code-length blocks behind the payload, header, directory, padding, size metadata; clears the
@@ -422,7 +433,7 @@ __global__ __launch_bounds__(1024) void k_finalize(Geom g, FixedLayout F, const 
 // is the sum of the totals of all groups before it in its container; the encode kernel has added the totals up per
 // block of kSumBlock groups, so whoever needs such a sum reads the sums of the blocks before and the totals of the
 // groups in between.
-//   work-groups [0, T): the codebook of the next call from this call's counts, into the second set of codebook arrays
+//   the first work-groups, one per table or per four tables: the codebook of the next call from this call's counts, into the second set of codebook arrays
 //     (this call's set is still being read)
 //   then nf work-groups per destination: the container's header, directory, code-length blocks, sizes (finalize_dest),
 //     from the tables' word ranges, which they work out from the sums themselves
@@ -444,19 +455,25 @@ __global__ __launch_bounds__(256) void k_post(Geom g, FixedLayout F, const uint3
                                               uint64_t capacity, uint32_t wpd, uint32_t nf, uint32_t* word_start,
                                               uint32_t* word_end, const TMeta* tmeta, const uint8_t* lens, const QParam* qp,
                                               uint64_t* out_bytes, uint32_t* esc_count, uint32_t* hist, uint32_t* hist_view,
-                                              uint16_t* enc_next, uint8_t* lens_next, TMeta* tmeta_next) {
+                                              uint16_t* enc_next, uint8_t* lens_next, TMeta* tmeta_next, uint32_t tpw) {
     extern __shared__ __align__(16) unsigned char smem[];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t gpd = g.TD * g.G;  // groups of one destination
-    if (blockIdx.x < g.T) {  // uniform over the work-group; these come first: a codebook takes longer than a copy
+    const uint32_t n_cb = (g.T + tpw - 1u) / tpw;  // work-groups that build the next call's codebooks, tpw (1 or 4) tables each
+    if (blockIdx.x < n_cb) {  // uniform over the work-group; these come first: a codebook takes longer than a copy
         __shared__ CodebookShared sh;
-        const uint32_t t = blockIdx.x;
-        codebook_build(g, hist + (size_t)t * g.K, hist_view + (size_t)t * g.K, enc_next + (size_t)t * g.K,
-                       lens_next + (size_t)t * g.K, tmeta_next + t, smem, sh, tid, 1u);
+        __shared__ uint32_t s_slow[4];
+        if (tpw == 4u) {
+            codebook_build_four(g, blockIdx.x * 4u, hist, hist_view, enc_next, lens_next, tmeta_next, smem, sh, s_slow, tid, 1u);
+        } else {
+            const uint32_t t = blockIdx.x;
+            codebook_build(g, hist + (size_t)t * g.K, hist_view + (size_t)t * g.K, enc_next + (size_t)t * g.K,
+                           lens_next + (size_t)t * g.K, tmeta_next + t, smem, sh, tid, 1u);
+        }
         return;
     }
-    if (blockIdx.x < g.T + g.ND * nf) {
-        const uint32_t f = blockIdx.x - g.T, dst = f / nf, xi = f - dst * nf;
+    if (blockIdx.x < n_cb + g.ND * nf) {
+        const uint32_t f = blockIdx.x - n_cb, dst = f / nf, xi = f - dst * nf;
         const uint32_t* const bs = bsum + (size_t)dst * sum_blocks_per_dest(g);
         const uint32_t* const gtot_d = gtot + (size_t)dst * gpd;
         // The tables' word ranges (stored past the caches: finalize_dest reads them that way): a scan over the block
@@ -498,7 +515,7 @@ __global__ __launch_bounds__(256) void k_post(Geom g, FixedLayout F, const uint3
                            (const uint8_t*)nullptr, (const uint32_t*)nullptr, bsum_next, dst, xi, nf);
         return;
     }
-    const uint32_t wg = blockIdx.x - g.T - g.ND * nf;
+    const uint32_t wg = blockIdx.x - n_cb - g.ND * nf;
     const uint32_t dst = wg / wpd, k = wg - dst * wpd;  // wpd work-groups per destination
     const uint32_t g0 = k * kPlaceGroups;
     if (g0 + wave >= gpd) return;  // whole wavefront
@@ -557,10 +574,11 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
             const uint32_t wpd = (g.TD * g.G + kPlaceGroups - 1) / kPlaceGroups, n_place = g.ND * wpd;
             const uint32_t nf = std::min<uint32_t>((std::min<uint32_t>(g.TD, 256u) + 3u) / 4u, 64u);  // a wavefront per table's code-length block
             if (prof_on(pl, P_POST)) prof_begin(prof, P_POST, s);
-            hipLaunchKernelGGL(k_post, dim3(g.T + g.ND * nf + n_place), dim3(256), codebook_smem(g.K), s, g, F, w.gtot, w.bsum,
+            const uint32_t tpw = codebook_tables_per_wg(g);
+            hipLaunchKernelGGL(k_post, dim3((g.T + tpw - 1u) / tpw + g.ND * nf + n_place), dim3(256), codebook_smem(g.K), s, g, F, w.gtot, w.bsum,
                                w.bsum_next, w.slots, (uint64_t)carry_slot_words(g), w.ctrl, out, capacity, wpd, nf, w.word_start,
                                w.word_end, w.tmeta, w.lens, w.qp, out_bytes, w.esc_count, w.hist, w.hist_view, w.enc_next,
-                               w.lens_next, w.tmeta_next);
+                               w.lens_next, w.tmeta_next, tpw);
             if (prof_on(pl, P_POST)) prof_end(prof, P_POST, s);
         }
         return hipGetLastError();
@@ -589,8 +607,9 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         if (e != hipSuccess) return e;
     }
     if (prof_on(pl, P_CODEBOOK)) prof_begin(prof, P_CODEBOOK, s);
-    hipLaunchKernelGGL(k_codebook, dim3(g.T), dim3(256), codebook_smem(g.K), s, g, w.hist, w.hist_view, w.enc, w.lens,
-                       w.tmeta, 0u);
+    const uint32_t tpw = codebook_tables_per_wg(g);
+    hipLaunchKernelGGL(k_codebook, dim3((g.T + tpw - 1u) / tpw), dim3(256), codebook_smem(g.K), s, g, w.hist, w.hist_view, w.enc, w.lens,
+                       w.tmeta, 0u, tpw);
     if (prof_on(pl, P_CODEBOOK)) prof_end(prof, P_CODEBOOK, s);
     {
         const uint32_t bpt = (g.G + 3) / 4;
@@ -607,8 +626,8 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
                        w.word_end, out, capacity, out_bytes, (uint32_t*)nullptr, g.lz ? (const uint8_t*)w.rm_on : nullptr, (const uint32_t*)w.rm_ref, (uint32_t*)nullptr);
     if (prof_on(pl, P_FINALIZE)) prof_end(prof, P_FINALIZE, s);
     if (w.carry != 0)  // the codebook the next call will use: this call's counts (kept as the copy), escape symbol included
-        hipLaunchKernelGGL(k_codebook, dim3(g.T), dim3(256), codebook_smem(g.K), s, g, w.hist_view, w.hist_view, w.enc_next,
-                           w.lens_next, w.tmeta_next, 1u);
+        hipLaunchKernelGGL(k_codebook, dim3((g.T + tpw - 1u) / tpw), dim3(256), codebook_smem(g.K), s, g, w.hist_view, w.hist_view, w.enc_next,
+                           w.lens_next, w.tmeta_next, 1u, tpw);
     return hipGetLastError();
 }
 
