@@ -246,3 +246,40 @@ def test_periodic_reclassification_in_a_carried_run():
         prev_hist, prev_eb = o.hist, oeb
     assert len(set(classes)) >= 2                   # a re-classification did change a class
     assert carried_calls >= 4 and fresh_calls >= 3  # both kinds of call were exercised
+
+
+def test_many_small_tables_both_paths():
+    """600 tables of two groups each: the codebook kernels build four tables per work-group (a wavefront each, the
+    whole work-group for the tables with more than 64 used symbols), the decoder runs work-groups of two wavefronts.
+    Tables of one symbol, of a few, of a wide alphabet and with escapes; the default path and a chain of three calls
+    on the single-pass path, each against the oracle."""
+    T, B, D, S = 600, 32, 64, 64             # 2048 elements a table = 1 group of 64 x 64 symbols, half of a second
+    rng = np.random.default_rng(99)
+    ebs = np.full(T, 2e-3, np.float32)
+
+    def batch(k):
+        x = (rng.standard_normal((T, B, D)) * 0.01).astype(np.float32)
+        x[0:600:7] *= 40.0                   # wide alphabets: more than 64 used symbols
+        x[3:600:50] = 0.25                   # one symbol
+        x[5:600:50, :, ::2] = 0.0            # two or three symbols
+        x[9:600:31, 2, 3] = 1e6              # an escape
+        if k == 2:
+            x[11:600:13] *= 25.0             # other tables turn wide: symbols without a carried code
+        return x
+
+    x0 = batch(0)
+    from gpu_util import DeviceRun
+    g = DeviceRun(x0, ebs, S=S)
+    o = oracle.compress(x0, ebs, R, S, 12)
+    assert g.status == 0 and o.rc == 0 and np.array_equal(g.sizes, o.sizes) and np.array_equal(g.data, o.data)
+    st, rec = g.decompress()
+    rc, orec = oracle.decompress(o.data, x0.shape, x0.dtype)
+    assert st == 0 and rc == 0 and np.array_equal(rec.view(np.uint32), orec.view(np.uint32))
+    ch = _Chain((T, B, D), np.float32, S)
+    prev = None
+    for k in range(3):
+        x = batch(k)
+        gk = ch.compress(x, ebs)
+        ok = oracle.compress(x, ebs, R, S, 12, carry_hist=prev, want_hist=True)
+        _same(gk, ok, x, f"many tables, call {k}")
+        prev = ok.hist
