@@ -159,9 +159,11 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
     uint8_t* tmeta2 = g.carry ? take(sizeof(TMeta) * g.T) : nullptr;
     uint8_t* bsum2 = g.carry ? take(4 * (size_t)g.ND * sum_blocks_per_dest(g)) : nullptr;
     uint8_t* bsum = g.carry ? take(4 * (size_t)g.ND * sum_blocks_per_dest(g)) : nullptr;
-    uint8_t* slots = g.carry ? take(4 * (size_t)g.NG * (size_t)carry_slot_words(g)) : nullptr;  // (last: by far the largest)
     uint8_t* desc = take(4 * (size_t)g.T);
     uint8_t* darr = take(4 * (size_t)g.T);
+    // the slots come last: they are by far the largest part and the only one that dlc_create does not clear (everything
+    // before them starts at zero: counters, flags, histograms)
+    uint8_t* slots = g.carry ? take(4 * (size_t)g.NG * (size_t)carry_slot_words(g)) : nullptr;
     if (w) {
         w->base = base; w->bytes = off;
         w->qp = (QParam*)qp;

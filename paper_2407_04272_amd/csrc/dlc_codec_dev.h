@@ -614,21 +614,24 @@ __device__ __forceinline__ void lb_finish(LookBack& L, uint64_t* state, uint64_t
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// escape records of one group, in increasing element index, behind its chunk words: the group's elements are
-// read and quantised once more in a rolled loop (rare for fp32)
+// escape records of one group, in increasing element index, behind its chunk words, for a group with more escapes
+// than the encode kernel remembers on the way: a rolled loop over the group's plane words (index 254 marks an
+// escape; an element of a row that is stored as a reference has index 253 and no record) and, for the raw bits,
+// over its elements
 template <int S, bool F16, bool VEC>
-__device__ __forceinline__ void emit_escapes(uint32_t* rec, uint32_t lane, const uint8_t* gbase, uint32_t gstart,
-                                             uint32_t rem, const QParam& q, float Rf, int R) {
+__device__ __forceinline__ void emit_escapes(uint32_t* rec, uint32_t lane, const uint8_t* gbase, const uint32_t* plane_g,
+                                             uint32_t gstart, uint32_t rem) {
     uint32_t opos = 0;
     for (uint32_t j = 0; j < (uint32_t)S / kV; ++j) {
         const uint32_t off = lane * kV + j * (kW * kV);
         float x[4];
         uint32_t raw[4];
         const uint32_t valid = load4<F16, VEC>(gbase, off, rem, x, raw);
+        const uint32_t m = plane_g[j * kW + lane];
         uint32_t esc = 0;
 #pragma unroll
         for (int v = 0; v < 4; ++v)
-            esc |= (((valid >> v) & 1u) && quant_symbol<F16>(x[v], q, Rf, R) == 0u) ? (1u << v) : 0u;
+            esc |= (((valid >> v) & 1u) && ((m >> (8 * v)) & 0xFFu) == kWinEsc) ? (1u << v) : 0u;
         if (__ballot(esc != 0u) == 0ull) continue;
         const uint32_t cnt = __popc(esc);
         const uint32_t incl = wave_incl_scan(cnt, lane);
@@ -642,36 +645,6 @@ __device__ __forceinline__ void emit_escapes(uint32_t* rec, uint32_t lane, const
             }
         opos += __shfl(incl, 63, 64);
     }
-}
-
-// walk 2 and everything after the group's offset is known.  pk[] holds S/2 words of two (len<<12|code) each.
-template <int S, bool F16, bool VEC>
-__device__ __forceinline__ void emit_group(const uint32_t (&pk)[S / 2], uint32_t nw, uint32_t lane_off, uint32_t excl,
-                                           uint32_t chunk_total, uint32_t n_esc, uint32_t gid, uint32_t lane,
-                                           const uint8_t* gbase, uint32_t gstart, uint32_t rem, const QParam& q, float Rf,
-                                           int R, const FixedLayout& F, uint8_t* out) {
-    out[F.off_chunk + (uint64_t)gid * kW + lane] = (uint8_t)nw;
-    if (lane == 0) reinterpret_cast<uint32_t*>(out + F.off_group)[gid] = excl;
-    uint32_t* gw = reinterpret_cast<uint32_t*>(out + F.off_payload) + excl;
-    uint32_t* p = gw + lane_off;
-    uint64_t acc = 0;
-    uint32_t nb = 0;
-#pragma clang loop unroll(full)
-    for (int i = 0; i < S / 2; ++i) {
-        const uint32_t w = pk[i];
-        const uint32_t l0 = (w >> 12) & 0xFu, l1 = w >> 28;
-        acc = (acc << l0) | (w & 0xFFFu);
-        acc = (acc << l1) | ((w >> 16) & 0xFFFu);
-        nb += l0 + l1;
-        if (nb >= 32u) {
-            nb -= 32u;
-            *p++ = (uint32_t)(acc >> nb);
-        }
-        if ((i & 3) == 3) __builtin_amdgcn_sched_barrier(0);  // do not unpack far ahead of the serial chain
-    }
-    if (nb) *p = (uint32_t)(acc << (32u - nb));
-    if (n_esc != 0u)  // uniform over the wavefront
-        emit_escapes<S, F16, VEC>(gw + chunk_total, lane, gbase, gstart, rem, q, Rf, R);
 }
 
 }  // namespace dlc

@@ -291,7 +291,8 @@ void k_encode(const void* payload, const uint8_t* sym_plane, Geom g, FixedLayout
                 else rec[2u * k + 1] = reinterpret_cast<const uint32_t*>(gbase)[off];
             }
         } else {
-            emit_escapes<S, F16, VEC>(rec, lane, gbase, gstart, rem, q, Rf, (int)g.R);
+            emit_escapes<S, F16, VEC>(rec, lane, gbase, reinterpret_cast<const uint32_t*>(sym_plane + (size_t)t * plane_stride(g) + gstart),
+                                      gstart, rem);
         }
     }
 }

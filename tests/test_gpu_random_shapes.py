@@ -1,0 +1,75 @@
+"""A seeded sweep of small random geometries through every compress path, each against the oracle byte for byte."""
+import numpy as np
+import pytest
+
+import oracle
+from gpu_util import to_device
+
+pytestmark = pytest.mark.gpu
+
+R = 512
+
+
+def _one(rng, k):
+    import torch
+    from paper_2407_04272_amd import binding as b
+    T = int(rng.integers(1, 7))
+    B = int(rng.choice([1, 3, 17, 64, 130, 257, 700, 2100]))
+    D = int(rng.choice([1, 4, 7, 16, 20, 48, 64, 132]))
+    S = int(rng.choice([64, 128, 256]))
+    f16 = bool(rng.integers(0, 2))
+    mode = int(rng.integers(0, 3))           # 0 default, 1 single-pass chain, 2 row matching
+    if mode == 2 and D % 4 != 0:
+        mode = 0
+    n = int(rng.choice([1, 1, 2, 3])) if mode != 2 or T * 3 <= 65535 else 1
+    dtype = np.float16 if f16 else np.float32
+    sigma = float(rng.choice([1e-3, 0.02, 0.5]))
+    eb = np.float32(sigma * rng.choice([0.02, 0.1, 0.4, 3.0]) * (8.0 if f16 else 1.0))
+    ebs = (eb * (1 + np.arange(T, dtype=np.float32) % 3)).astype(np.float32)
+    print(f"random shape {k}: n={n} T={T} B={B} D={D} S={S} {np.dtype(dtype).name} mode={mode} eb={eb:g}", flush=True)
+    flags = [0, b.FLAG_CARRY_CODEBOOK, b.FLAG_ROW_MATCH][mode]
+    # what the next allocation gets is not zero: a context must not rely on fresh memory
+    junk = torch.full((48 << 20,), 0xA5, dtype=torch.uint8, device="cuda")
+    del junk
+    torch.cuda.empty_cache()
+    cfg = b.make_config(b.F16 if f16 else b.F32, T, B, D, R, S, 12, flags, num_dest=n)
+    ctx = b.Context(cfg)
+    ctx.set_error_bounds(eb=ebs)
+    cap = b.dlc_compress_bound(cfg)
+    stride = (cap // n) & ~255 if n > 1 else cap
+    out = torch.zeros(cap + 64, dtype=torch.uint8, device="cuda")
+    sizes = torch.zeros(1 + n * T + (n if n > 1 else 0), dtype=torch.int64, device="cuda")
+    prev = [None] * n
+    for call in range(3 if mode == 1 else 1):
+        rows = max(1, B // 3)
+        table = (rng.standard_normal((n, T, rows, D)) * sigma).astype(np.float32)
+        idx = rng.integers(0, rows, (n, T, B))
+        x = np.take_along_axis(table, idx[..., None], axis=2).astype(dtype)     # repeated rows
+        x.reshape(-1)[::int(rng.choice([53, 911, 7]))] = 6e4 if f16 else 1e9    # escapes: some, few, very many
+        d = to_device(x if n > 1 else x[0])
+        out.fill_(0xA5)
+        assert ctx.compress(d, out, sizes, capacity=cap) == 0 and ctx.sync_status() == 0
+        h = out.cpu().numpy()
+        sz = sizes.cpu().numpy().astype(np.uint64)
+        assert np.all(h[cap:] == 0xA5)
+        rec = torch.full_like(d, 7.0)
+        assert ctx.decompress(out, cap if n > 1 else int(sz[0]), rec) == 0 and ctx.sync_status() == 0
+        r = rec.cpu().numpy().reshape(x.shape)
+        u = np.uint16 if f16 else np.uint32
+        for p in range(n):
+            o = oracle.compress(x[p], ebs, R, S, 12, carry_hist=prev[p] if mode == 1 else None,
+                                want_hist=(mode == 1), row_match=(True if mode == 2 else None))
+            assert o.rc == 0
+            nbytes = int(sz[1 + n * T + p]) if n > 1 else int(sz[0])
+            got = h[p * stride:p * stride + nbytes]
+            assert nbytes == o.data.size and np.array_equal(got, o.data), (k, call, p)
+            rc, orec = oracle.decompress(o.data, x[p].shape, dtype)
+            assert rc == 0 and np.array_equal(r[p].view(u), orec.view(u)), (k, call, p)
+            if mode == 1:
+                prev[p] = o.hist
+
+
+def test_random_geometries():
+    rng = np.random.default_rng(20240704)
+    for k in range(150):
+        _one(rng, k)

@@ -237,3 +237,16 @@ def test_rows_with_equal_hashes_still_get_the_first_occurrence(dtype):
         rc, orec = oracle.decompress(o.data, x.shape, x.dtype)
         u = np.uint32 if dtype == np.float32 else np.uint16
         assert rc == 0 and np.array_equal(rec.cpu().numpy().view(u), orec.view(u))
+
+
+def test_more_escapes_in_a_group_than_the_encoder_remembers():
+    """More than 128 escapes in one group, many of them in rows that are stored as references: the records are those
+    of the coded rows only (the encoder's second look at such a group goes by the symbol plane, where an element of a
+    referencing row is marked as such)."""
+    x = _lookups(1, 130, 64, 4, rows=40)
+    x.reshape(-1)[::53] = 1e9                   # 157 escapes in the one group of 8320 elements
+    x[0, 100:130] = x[0, 10:40]                 # repeated rows, escapes and all
+    ebs = np.full(1, 1e-2, np.float32)
+    ctx, d, out, data, sizes = _compress(x, ebs, 256)
+    o = oracle.compress(x, ebs, R, 256, 12, row_match=True)
+    assert o.rc == 0 and np.array_equal(sizes, o.sizes) and np.array_equal(data, o.data)
