@@ -297,3 +297,47 @@ def test_every_schedule_gives_the_oracles_bounds():
                 oeb, ocls = oracle.controller(ost, op, it)
                 assert np.array_equal(ebs.view(np.uint32), oeb.view(np.uint32)), (kind, mode, it)
                 assert np.array_equal(cls, ocls)
+
+
+def test_calls_on_a_stream_of_the_callers():
+    """Everything the library launches goes to the stream it is given (here not the default stream): statistics,
+    bounds, the three compress paths, decompress, the context-free decompress; containers against the oracle."""
+    import torch
+    from paper_2407_04272_amd import binding as b
+    rng = np.random.default_rng(5)
+    table = (rng.standard_normal((3, 200, 32)) * 0.02).astype(np.float32)
+    x = np.stack([table[t][rng.integers(0, 200, 900)] for t in range(3)])
+    x[1, 7, 3] = 1e9
+    ebs = np.array([1e-3, 2e-3, 5e-4], np.float32)
+    d = to_device(x)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for flags in (0, b.FLAG_CARRY_CODEBOOK, b.FLAG_ROW_MATCH):
+            cfg = b.make_config(b.F32, 3, 900, 32, R, 128, 12, flags)
+            ctx = b.Context(cfg)
+            st = ctx.stats(d, ebs)
+            ost = oracle.stats(x, ebs)
+            assert [s.n_unique_quant for s in st] == [s.n_unique_quant for s in ost]
+            ctx.set_error_bounds(eb=ebs)
+            out = torch.zeros(b.dlc_compress_bound(cfg), dtype=torch.uint8, device="cuda")
+            sizes = torch.zeros(4, dtype=torch.int64, device="cuda")
+            prev = None
+            for call in range(2 if flags == b.FLAG_CARRY_CODEBOOK else 1):
+                assert ctx.compress(d, out, sizes) == 0 and ctx.sync_status() == 0
+                n = int(sizes[0].item())
+                o = oracle.compress(x, ebs, R, 128, 12, carry_hist=prev, want_hist=(flags == b.FLAG_CARRY_CODEBOOK),
+                                    row_match=(True if flags == b.FLAG_ROW_MATCH else None))
+                assert o.rc == 0 and n == o.data.size and np.array_equal(out[:n].cpu().numpy(), o.data), (flags, call)
+                prev = o.hist
+                rec = torch.full_like(d, 7.0)
+                rec2 = torch.full_like(d, 7.0)
+                status = torch.full((1,), 99, dtype=torch.int32, device="cuda")
+                assert ctx.decompress(out, n, rec) == 0 and ctx.sync_status() == 0
+                assert b.dlc_decompress_static(cfg, out, n, rec2, status) == 0
+                side.synchronize()
+                rc, orec = oracle.decompress(o.data, x.shape, np.float32)
+                assert rc == 0 and int(status.item()) == 0
+                assert np.array_equal(rec.cpu().numpy().view(np.uint32), orec.view(np.uint32))
+                assert np.array_equal(rec2.cpu().numpy().view(np.uint32), orec.view(np.uint32))
+    torch.cuda.current_stream().wait_stream(side)
