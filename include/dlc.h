@@ -215,6 +215,8 @@ int dlc_set_error_bounds(dlc_ctx* ctx, const dlc_table_stats* h_stats, const dlc
  *                        [1 + d*T + t] table t of destination d, [1 + n*T + d] size of destination d's container
  * Asynchronous on `stream`.  DLC_ESTATE if bounds were never set.  Capacity overflow is detected on the GPU
  * before the overflowing write: d_out_bytes[0] = 0 and dlc_sync_status returns DLC_ECAPACITY.
+ * Not for HIP graph capture: every call advances state kept on the host (the call counter that tags the look-back
+ * records, the two codebook buffers a carrying context alternates between), which a replayed graph would not see.
  */
 int dlc_compress(dlc_ctx* ctx, const void* d_payload, void* d_out, size_t out_capacity, uint64_t* d_out_bytes,
                  void* stream);
@@ -225,7 +227,8 @@ int dlc_compress(dlc_ctx* ctx, const void* d_payload, void* d_out, size_t out_ca
  *   d_payload_out DEVICE  [T][B][D] in the context's dtype, 16-byte aligned, out_capacity >= T*B*D*sizeof(dtype)
  * Asynchronous on `stream`.  The container is self-describing (geometry, per-table bounds, code lengths); it is
  * validated on the GPU and a mismatch or inconsistency is reported by dlc_sync_status as DLC_ECORRUPT, in
- * which case the output holds unspecified values but no access left the two buffers.
+ * which case the output holds unspecified values but no access left the two buffers.  The call keeps no state on
+ * the host and enqueues kernels only, so it may be recorded into a HIP graph (with profiling off).
  */
 int dlc_decompress(dlc_ctx* ctx, const void* d_comp, size_t comp_bytes, void* d_payload_out, size_t out_capacity,
                    void* stream);

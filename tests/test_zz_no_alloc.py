@@ -103,3 +103,53 @@ def test_limits_and_arguments():
     assert b.dlc_decompress_static(ok, buf, buf.numel(), small, status) == b.ECAPACITY
     assert b.dlc_decompress_static(ok, buf, 64, rec, status) == b.ECORRUPT
     torch.cuda.synchronize()
+
+
+def test_decompress_under_graph_capture():
+    """Both decompress entry points recorded into a HIP graph (they keep no per-call state on the host and allocate
+    nothing) and replayed with other containers in the same buffer: every replay against the eager result."""
+    import torch
+    from paper_2407_04272_amd import binding as b
+    T, B, D, S = 4, 1500, 32, 128
+    ebs = np.full(T, 2e-3, np.float32)
+    payloads = [_lookups(T, B, D, 31 + k, np.float32) for k in range(3)]
+    cfg = b.make_config(b.F32, T, B, D, R, S, 12)
+    ctx = b.Context(cfg)
+    ctx.set_error_bounds(eb=ebs)
+    cap = b.dlc_compress_bound(cfg)
+    out = torch.zeros(cap, dtype=torch.uint8, device="cuda")
+    sizes = torch.zeros(1 + T, dtype=torch.int64, device="cuda")
+    rec0 = torch.zeros((T, B, D), dtype=torch.float32, device="cuda")
+    rec1 = torch.zeros_like(rec0)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    d = to_device(payloads[0])
+    assert ctx.compress(d, out, sizes, capacity=cap) == 0 and ctx.sync_status() == 0
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        # once outside the capture: the first call on a device looks up the fixed array's address
+        assert ctx.decompress(out, cap, rec0) == 0 and b.dlc_decompress_static(cfg, out, cap, rec1, status) == 0
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            assert ctx.decompress(out, cap, rec0) == 0
+            assert b.dlc_decompress_static(cfg, out, cap, rec1, status) == 0
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for k, x in enumerate(payloads):
+        d = to_device(x)                                                  # eager work between the replays
+        assert ctx.compress(d, out, sizes, capacity=cap) == 0 and ctx.sync_status() == 0
+        want = torch.zeros_like(rec0)
+        assert ctx.decompress(out, cap, want) == 0 and ctx.sync_status() == 0
+        rec0.fill_(7.0)
+        rec1.fill_(7.0)
+        status.fill_(99)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert ctx.sync_status() == 0 and int(status.item()) == 0, k
+        assert torch.equal(rec0.view(torch.int32), want.view(torch.int32)), k
+        assert torch.equal(rec1.view(torch.int32), want.view(torch.int32)), k
+        o = oracle.compress(x, ebs, R, S, 12)
+        rc, orec = oracle.decompress(o.data, x.shape, np.float32)
+        assert rc == 0 and np.array_equal(want.cpu().numpy().view(np.uint32), orec.view(np.uint32)), k
