@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--carry-codebook", action="store_true",
                     help="time the single-pass path (DLC_FLAG_CARRY_CODEBOOK: each step is coded with the codebook built "
                          "from the previous step's payload) instead of the default two-pass path")
+    ap.add_argument("--sample-codebook", action="store_true",
+                    help="time the single-pass path that builds every table's codebook from a sample of the step's own "
+                         "payload (DLC_FLAG_SAMPLE_CODEBOOK) instead of the default two-pass path")
     ap.add_argument("--row-match", action="store_true",
                     help="time the path with the vector-based LZ step on every table (DLC_FLAG_ROW_MATCH) instead of the "
                          "default path; the roofline object then still prices the kernel the profile slots see")
@@ -87,10 +90,11 @@ def main():
     d = w.payload
     T, B, D = d.shape
     payload_bytes = d.numel() * 4
-    if args.carry_codebook and args.row_match:
-        print("bench.py: --carry-codebook and --row-match are two different paths; pick one", file=sys.stderr)
+    if args.carry_codebook + args.row_match + args.sample_codebook > 1:
+        print("bench.py: --carry-codebook, --sample-codebook and --row-match are different paths; pick one", file=sys.stderr)
         sys.exit(2)
-    flags = b.FLAG_CARRY_CODEBOOK if args.carry_codebook else (b.FLAG_ROW_MATCH if args.row_match else 0)
+    flags = (b.FLAG_CARRY_CODEBOOK if args.carry_codebook else b.FLAG_SAMPLE_CODEBOOK if args.sample_codebook
+             else b.FLAG_ROW_MATCH if args.row_match else 0)
     ctx = b.Context(b.make_config(b.F32, T, B, D, chunk_symbols=args.chunk_symbols, flags=flags))
 
     # offline analysis (Section III-A): statistics -> table classes; timed on its own
@@ -197,7 +201,9 @@ def main():
         "config": {"workload": f"{args.workload}: {T} tables x {B} lookups x dim {D} fp32 ({payload_bytes >> 20} MiB), "
                                "Zipf(1.05) single-hot, N(0,sigma_t), table-wise range-relative bounds 0.03",
                    "chunk_symbols": args.chunk_symbols, "radius": 512, "max_code_len": 12,
-                   "codebook": "carried from the previous step" if args.carry_codebook else "built from the step's own payload",
+                   "codebook": ("carried from the previous step" if args.carry_codebook else
+                                "built from a sample of the step's own payload" if args.sample_codebook else
+                                "built from the step's own payload"),
                    "row_matching": bool(args.row_match)},
         "compression_ratio": round(cr, 3),
         "compress_GBps": round(payload_bytes / comp_ms / 1e6, 2), "compress_ms": round(comp_ms, 4),
@@ -215,33 +221,38 @@ def main():
                      "target_met": {"compress": bool(comp_frac >= TARGET_FRAC), "decompress": bool(dec_frac >= TARGET_FRAC)}},
     }
 
-    if not args.carry_codebook and not args.row_match:
-        # for information: the same workload through the single-pass path (not part of `value`)
-        ctx2 = b.Context(b.make_config(b.F32, T, B, D, chunk_symbols=args.chunk_symbols, flags=b.FLAG_CARRY_CODEBOOK))
-        ctx2.set_error_bounds(eb=ebs)
-        for _ in range(3):
-            ctx2.compress(d, out, sizes)
-        assert ctx2.sync_status() == 0
-        total2 = int(sizes[0].item())
-        comp2_ms = timed(lambda: ctx2.compress(d, out, sizes), n_dir)
+    if not args.carry_codebook and not args.row_match and not args.sample_codebook:
+        # for information: the same workload through the two single-pass paths (not part of `value`)
+        for name, fl, note in (("carried_codebook", b.FLAG_CARRY_CODEBOOK,
+                                "each call coded with the codebook of the previous call's payload (here the same "
+                                "payload); see --carry-codebook"),
+                               ("sampled_codebook", b.FLAG_SAMPLE_CODEBOOK,
+                                "each call coded with the codebook of a sample of its own payload (four groups of "
+                                "16384 elements per table); see --sample-codebook")):
+            ctx2 = b.Context(b.make_config(b.F32, T, B, D, chunk_symbols=args.chunk_symbols, flags=fl))
+            ctx2.set_error_bounds(eb=ebs)
+            for _ in range(3):
+                ctx2.compress(d, out, sizes)
+            assert ctx2.sync_status() == 0
+            total2 = int(sizes[0].item())
+            comp2_ms = timed(lambda: ctx2.compress(d, out, sizes), n_dir)
 
-        def step2():
-            ctx2.compress(d, out, sizes)
-            ctx2.decompress(out, out.numel(), rec)
-        rt2_ms = timed(step2, n_dir)
-        assert ctx2.sync_status() == 0
-        algo2 = payload_bytes * (1.0 + total2 / payload_bytes)
-        carried_frac = algo2 / (comp2_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS
-        result["roofline"]["direction_frac"]["compress_carried_codebook"] = round(carried_frac, 4)
-        result["roofline"]["target_met"]["compress_carried_codebook"] = bool(carried_frac >= TARGET_FRAC)
-        result["carried_codebook"] = {"compress_ms": round(comp2_ms, 4),
-                                      "compress_GBps": round(payload_bytes / comp2_ms / 1e6, 2),
-                                      "compress_roofline_frac": round(carried_frac, 4),
-                                      "round_trip_GBps": round(payload_bytes / rt2_ms / 1e6, 2),
-                                      "compression_ratio": round(payload_bytes / total2, 3),
-                                      "note": "each call coded with the codebook of the previous call's payload "
-                                              "(here the same payload); see --carry-codebook"}
-        del ctx2
+            def step2():
+                ctx2.compress(d, out, sizes)
+                ctx2.decompress(out, out.numel(), rec)
+            rt2_ms = timed(step2, n_dir)
+            assert ctx2.sync_status() == 0
+            algo2 = payload_bytes * (1.0 + total2 / payload_bytes)
+            frac2 = algo2 / (comp2_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS
+            result["roofline"]["direction_frac"]["compress_" + name] = round(frac2, 4)
+            result["roofline"]["target_met"]["compress_" + name] = bool(frac2 >= TARGET_FRAC)
+            result[name] = {"compress_ms": round(comp2_ms, 4),
+                            "compress_GBps": round(payload_bytes / comp2_ms / 1e6, 2),
+                            "compress_roofline_frac": round(frac2, 4),
+                            "round_trip_GBps": round(payload_bytes / rt2_ms / 1e6, 2),
+                            "compression_ratio": round(payload_bytes / total2, 3),
+                            "note": note}
+            del ctx2
         # leave the default path's container in `out` for the comparison below
         ctx.compress(d, out, sizes)
         assert ctx.sync_status() == 0
@@ -253,7 +264,8 @@ def main():
         if args.carry_codebook:  # the steady state of the chain: the counts of the same payload
             carry = oracle.compress(x, ebs, want_hist=True).hist
         t0 = time.perf_counter()
-        o = oracle.compress(x, ebs, carry_hist=carry, row_match=bool(args.row_match))
+        o = oracle.compress(x, ebs, carry_hist=carry, row_match=(True if args.row_match else None),
+                            sample_codebook=bool(args.sample_codebook))
         tc = time.perf_counter() - t0
         t0 = time.perf_counter()
         rc, orec = oracle.decompress(o.data, x.shape, np.float32)
@@ -296,7 +308,7 @@ def _measure(b, torch, np, name, d, ebs, S, with_oracle, sample_bytes=None):
         e1.synchronize()
         return e0.elapsed_time(e1) / n
 
-    for key, flags in (("", 0), ("carried_", b.FLAG_CARRY_CODEBOOK)):
+    for key, flags in (("", 0), ("carried_", b.FLAG_CARRY_CODEBOOK), ("sampled_", b.FLAG_SAMPLE_CODEBOOK)):
         ctx = b.Context(b.make_config(b.F16 if f16 else b.F32, T, B, D, chunk_symbols=S, flags=flags))
         ctx.set_error_bounds(eb=ebs)
         c_ms = timed(lambda: ctx.compress(d, out, sizes))

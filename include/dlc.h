@@ -105,7 +105,7 @@ typedef struct {
  * dlc_stats (about 24 bytes per row and table), so that statistics taken again in the middle of a run (periodic
  * re-classification of the tables) allocate nothing; without it the first dlc_stats call allocates them.  Goes
  * with every other flag. */
-enum { DLC_FLAG_CARRY_CODEBOOK = 2, DLC_FLAG_ROW_MATCH = 4, DLC_FLAG_STATS_WORKSPACE = 8 };
+enum { DLC_FLAG_CARRY_CODEBOOK = 2, DLC_FLAG_ROW_MATCH = 4, DLC_FLAG_STATS_WORKSPACE = 8, DLC_FLAG_SAMPLE_CODEBOOK = 16 };
 
 /* DLC_FLAG_CARRY_CODEBOOK: dlc_compress codes each table with the Huffman codebook built from the payload of the
  * PREVIOUS dlc_compress call on this context instead of from its own payload (Section IV-C: the value distributions
@@ -120,6 +120,17 @@ enum { DLC_FLAG_CARRY_CODEBOOK = 2, DLC_FLAG_ROW_MATCH = 4, DLC_FLAG_STATS_WORKS
  *   - The workspace of such a context also holds every group's words before they are put in place, with room for
  *     every group's worst case: about 2.6 times an fp32 payload in all (dlc_workspace_bytes says how much). */
 
+/* DLC_FLAG_SAMPLE_CODEBOOK: the payload is read once as with DLC_FLAG_CARRY_CODEBOOK, but no call depends on the one
+ * before it: the Huffman codebook of a table (Section III-D) is built from the symbol counts of a SAMPLE of the same
+ * payload, a few whole groups of the table (a group = 64 * chunk_symbols consecutive elements):
+ *   - ns = ceil(65536 / (64 * chunk_symbols)) groups at most, groups 0, stride, 2 * stride, ... with
+ *     stride = max(1, floor(groups of the table / ns)); a table of at most ns groups is counted whole;
+ *   - the count of symbol 0 (the escape) is raised by one and a symbol the sample has not seen is stored as an escape,
+ *     exactly as with a carried codebook, so the error bound holds whatever the sample missed.
+ * Costs: a fraction of a percent of compression ratio where a table's symbols take bits at all; a table that is one
+ * symbol throughout takes one bit per element instead of none.  Same container format, same workspace as with
+ * DLC_FLAG_CARRY_CODEBOOK less the symbol plane; not together with DLC_FLAG_CARRY_CODEBOOK or DLC_FLAG_ROW_MATCH. */
+
 /* DLC_FLAG_ROW_MATCH: the vector-based LZ step of Section III-D in front of the entropy coder.  The pattern is one
  * whole row (embedding vector): a row that equals an earlier row of its table in the batch after quantisation -- all
  * symbols and, where a symbol is the escape, the raw bits -- is not coded; the container stores a reference to the
@@ -127,7 +138,7 @@ enum { DLC_FLAG_CARRY_CODEBOOK = 2, DLC_FLAG_ROW_MATCH = 4, DLC_FLAG_STATS_WORKS
  * byte offset, 0 for a table without).  A referenced row is therefore always a coded one and the decoder copies rows
  * in parallel.  Per table: dlc_set_row_match switches it on and off (all on after dlc_create), which is what the
  * compressor selection of Section III-D (Eq. 2, dlc_speedup_estimate) decides offline.  Needs dim % 4 == 0; not
- * together with DLC_FLAG_CARRY_CODEBOOK; num_dest * num_tables <= 65535.  With num_dest > 1 rows are matched inside a
+ * together with DLC_FLAG_CARRY_CODEBOOK or DLC_FLAG_SAMPLE_CODEBOOK; num_dest * num_tables <= 65535.  With num_dest > 1 rows are matched inside a
  * destination's piece (a container never refers to another).  The search hashes rows and compares every candidate
  * element by element; rows whose hashes meet are sorted out the long way, so the references are always those of the
  * definition. */

@@ -192,13 +192,52 @@ class Compressed:
     hist: np.ndarray | None = None   # u64[T, K] symbol counts of this payload (compress(..., want_hist=True))
 
 
+SAMPLE_ELEMS = 65536  # a table's codebook sample: at least this many elements where the table has them
+
+
+def sample_groups(n: int, S: int = 256) -> list[int]:
+    """The groups (64 * S consecutive elements each) of a table of n elements whose symbols are counted when the
+    codebook is built from a sample of the payload (a reading of ours: Section III-D builds the Huffman code from the
+    data it codes and does not speak of sampling).  ns = ceil(SAMPLE_ELEMS / (64 S)) groups at most, evenly spread from
+    group 0 on: 0, stride, 2 stride, ... with stride = max(1, floor(G / ns))."""
+    gs = 64 * S
+    G = (n + gs - 1) // gs
+    ns = (SAMPLE_ELEMS + gs - 1) // gs
+    stride = max(1, G // ns)
+    return list(range(0, G, stride))[:ns]
+
+
+def sample_histogram(payload: np.ndarray, eb, R: int = 512, S: int = 256) -> np.ndarray:
+    """u64[T, 2R]: per table, the symbol counts of the elements of its sampled groups."""
+    payload = np.ascontiguousarray(payload)
+    T = payload.shape[0]
+    n = payload[0].size
+    ebs = np.broadcast_to(np.asarray(eb, np.float32), (T,))
+    gs = 64 * S
+    h = np.zeros((T, 2 * R), np.uint64)
+    for t in range(T):
+        flat = payload[t].reshape(-1)
+        for g in sample_groups(n, S):
+            sym, _ = quantize(flat[g * gs:min(n, (g + 1) * gs)], float(ebs[t]), R)
+            h[t] += histogram(sym, 2 * R)
+    return h
+
+
 def compress(payload: np.ndarray, eb, R: int = 512, S: int = 256, LMAX: int = 12, capacity: int | None = None,
-             carry_hist: np.ndarray | None = None, want_hist: bool = False, row_match=None):
+             carry_hist: np.ndarray | None = None, want_hist: bool = False, row_match=None,
+             sample_codebook: bool = False):
     """carry_hist (u64[T, 2R]): code with the codebook of these counts (an earlier payload's) instead of the payload's
     own; want_hist: also return this payload's counts, which is what the next call is given.
     row_match (bool or T flags): rows equal to an earlier row of their table are stored as references (not together
-    with carry_hist / want_hist)."""
+    with carry_hist / want_hist).
+    sample_codebook: code with the codebook of the counts of the payload's own sampled groups (sample_histogram),
+    under the rules of a carried codebook: the escape always has a code, a symbol the sample has not seen is stored as
+    an escape."""
     payload = np.ascontiguousarray(payload)
+    if sample_codebook:
+        if carry_hist is not None or row_match is not None:
+            raise ValueError("sample_codebook cannot be combined with carry_hist / row_match")
+        carry_hist = sample_histogram(payload, eb, R, S)
     T, B, D = payload.shape
     dt = _dtype_code(payload)
     ebs = np.ascontiguousarray(np.broadcast_to(np.asarray(eb, np.float32), (T,)))

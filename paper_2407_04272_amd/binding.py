@@ -110,6 +110,7 @@ def _check(status, where):
 FLAG_CARRY_CODEBOOK = 2
 FLAG_ROW_MATCH = 4
 FLAG_STATS_WORKSPACE = 8
+FLAG_SAMPLE_CODEBOOK = 16
 
 
 def make_config(dtype, T, B, D, radius=512, chunk_symbols=256, max_code_len=12, flags=0, num_dest=1) -> Config:

@@ -86,7 +86,8 @@ static bool make_geom(const dlc_config* c, Geom* g) {
     if (L < 1 || L > kLmaxLimit || (1 << L) < 2 * R) return false;
     const int S = c->chunk_symbols;
     if (S != 64 && S != 128 && S != 256) return false;
-    if (c->flags & ~(int32_t)(DLC_FLAG_CARRY_CODEBOOK | DLC_FLAG_ROW_MATCH | DLC_FLAG_STATS_WORKSPACE)) return false;
+    if (c->flags & ~(int32_t)(DLC_FLAG_CARRY_CODEBOOK | DLC_FLAG_ROW_MATCH | DLC_FLAG_STATS_WORKSPACE | DLC_FLAG_SAMPLE_CODEBOOK)) return false;
+    if ((c->flags & DLC_FLAG_SAMPLE_CODEBOOK) && (c->flags & DLC_FLAG_CARRY_CODEBOOK)) return false;  // one source of the codebook
     if (c->flags & DLC_FLAG_ROW_MATCH) {  // not with the other flags, and a lane's four elements must lie in one row
         if ((c->flags & ~(int32_t)DLC_FLAG_STATS_WORKSPACE) != DLC_FLAG_ROW_MATCH || c->dim % 4 != 0) return false;
     }
@@ -109,6 +110,7 @@ static bool make_geom(const dlc_config* c, Geom* g) {
     g->vec = (n % 4 == 0) ? 1u : 0u;
     g->lz = (c->flags & DLC_FLAG_ROW_MATCH) ? 1u : 0u;
     g->carry = (c->flags & DLC_FLAG_CARRY_CODEBOOK) ? 1u : 0u;
+    g->sample = (c->flags & DLC_FLAG_SAMPLE_CODEBOOK) ? 1u : 0u;
     if (g->lz && T > 65535ull) return false;  // the row kernels' grids have a table per y index
     return true;
 }
@@ -145,7 +147,7 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
     uint8_t* state = take(8 * (size_t)g.NG);
     uint8_t* ws0 = take(4 * (size_t)g.T);
     uint8_t* ws1 = take(4 * (size_t)g.T);
-    uint8_t* plane = take((size_t)g.NG * kW * g.S);
+    uint8_t* plane = g.sample ? nullptr : take((size_t)g.NG * kW * g.S);  // (with a sampled codebook every call is a single pass)
     uint8_t* escc = take(4 * (size_t)g.T);
     uint8_t* rm_on = g.lz ? take(g.T) : nullptr;
     uint8_t* rm_ref = g.lz ? take(4 * (size_t)g.T * g.B) : nullptr;
@@ -153,17 +155,18 @@ static size_t carve(const Geom& g, uint8_t* base, Ws* w) {
     uint8_t* rm_own = g.lz ? take(4 * (size_t)g.T * g.B) : nullptr;
     uint8_t* rm_mult = g.lz ? take(32 * (size_t)(g.D / 4u)) : nullptr;
     uint8_t* dtab = take(sizeof(DecTable) * g.T);
-    uint8_t* gtot = g.carry ? take(4 * (size_t)g.NG) : nullptr;
+    const bool single = g.carry != 0 || g.sample != 0;  // the single-pass path's buffers
+    uint8_t* gtot = single ? take(4 * (size_t)g.NG) : nullptr;
     uint8_t* enc2 = g.carry ? take(2 * (size_t)g.T * g.K) : nullptr;
     uint8_t* lens2 = g.carry ? take((size_t)g.T * g.K) : nullptr;
     uint8_t* tmeta2 = g.carry ? take(sizeof(TMeta) * g.T) : nullptr;
-    uint8_t* bsum2 = g.carry ? take(4 * (size_t)g.ND * sum_blocks_per_dest(g)) : nullptr;
-    uint8_t* bsum = g.carry ? take(4 * (size_t)g.ND * sum_blocks_per_dest(g)) : nullptr;
+    uint8_t* bsum2 = single ? take(4 * (size_t)g.ND * sum_blocks_per_dest(g)) : nullptr;
+    uint8_t* bsum = single ? take(4 * (size_t)g.ND * sum_blocks_per_dest(g)) : nullptr;
     uint8_t* desc = take(4 * (size_t)g.T);
     uint8_t* darr = take(4 * (size_t)g.T);
     // the slots come last: they are by far the largest part and the only one that dlc_create does not clear (everything
     // before them starts at zero: counters, flags, histograms)
-    uint8_t* slots = g.carry ? take(4 * (size_t)g.NG * (size_t)carry_slot_words(g)) : nullptr;
+    uint8_t* slots = single ? take(4 * (size_t)g.NG * (size_t)carry_slot_words(g)) : nullptr;
     if (w) {
         w->base = base; w->bytes = off;
         w->qp = (QParam*)qp;
@@ -226,6 +229,7 @@ extern "C" int dlc_create(dlc_ctx** out, const dlc_config* cfg) {
     const size_t clear_bytes = c->ws.slots ? (size_t)((uint8_t*)c->ws.slots - base) : bytes;
     if (hipMemset(base, 0, clear_bytes) != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }
     c->ws.carry = (cfg->flags & DLC_FLAG_CARRY_CODEBOOK) ? 1u : 0u;
+    c->ws.sample = (cfg->flags & DLC_FLAG_SAMPLE_CODEBOOK) ? 1u : 0u;
     if (g.lz && hipMemset(c->ws.rm_on, 1, g.T) != hipSuccess) { (void)hipFree(base); delete c; return DLC_EHIP; }  // all tables
     if (g.lz) {
         std::vector<uint32_t> mult(8 * (size_t)(g.D / 4u));
@@ -384,7 +388,7 @@ extern "C" int dlc_compress(dlc_ctx* c, const void* d_payload, void* d_out, size
         if (hipGetLastError() != hipSuccess) return DLC_EHIP;
         c->epoch = 1;
     }
-    const bool was_single_pass = c->ws.carry != 0 && c->carry_ready;
+    const bool was_single_pass = c->ws.sample != 0 || (c->ws.carry != 0 && c->carry_ready);
     hipError_t e = launch_compress(c->g, d_payload, (uint8_t*)d_out, cap, d_out_bytes, c->ws, c->epoch, c->carry_ready,
                                    c->prof.level, &c->prof, (hipStream_t)stream);
     c->carry_ready = e == hipSuccess && c->ws.carry != 0;
@@ -392,8 +396,8 @@ extern "C" int dlc_compress(dlc_ctx* c, const void* d_payload, void* d_out, size
         std::swap(c->ws.enc, c->ws.enc_next);
         std::swap(c->ws.lens, c->ws.lens_next);
         std::swap(c->ws.tmeta, c->ws.tmeta_next);
-        if (was_single_pass) std::swap(c->ws.bsum, c->ws.bsum_next);  // (the single-pass step has cleared the other set)
     }
+    if (was_single_pass) std::swap(c->ws.bsum, c->ws.bsum_next);  // (the single-pass step has cleared the other set)
     return e == hipSuccess ? DLC_OK : DLC_EHIP;
 }
 

@@ -69,6 +69,7 @@ struct CarryEnv {
     uint32_t sp_base;      // LDS address of this lane's column of the staging rows
     uint32_t row_max;      // the last staging row
     uint32_t* dst;         // second walk of a group that did not fit its staging rows: the lane's chunk in memory
+    uint32_t count;        // 0: nobody wants this call's counts (the codebook is not carried to the next call)
 };
 
 struct CarryState {
@@ -192,7 +193,7 @@ __device__ __forceinline__ void carry_block(const CarryEnv& E, const float (&x)[
             for (int v = 0; v < 4; ++v) {
                 if (len[u][v] != 0u) continue;
                 bool is_esc;
-                carry_slow_entry<F16>(E, x[u][v], FULL || ((valid[u] >> v) & 1u), a[u][v], len[u][v], code[u][v], is_esc, !REWALK);
+                carry_slow_entry<F16>(E, x[u][v], FULL || ((valid[u] >> v) & 1u), a[u][v], len[u][v], code[u][v], is_esc, !REWALK && E.count != 0u);
                 if (is_esc && !REWALK) { ++S.esc; em |= 1u << v; }
             }
             // the records of these escapes, in element order (the walk meets the elements of a group in
@@ -301,7 +302,7 @@ template <int S, bool F16, bool VEC>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k_encode_carry(const void* payload, Geom g, FixedLayout F, const QParam* qp,
                                                       const uint16_t* enc, uint8_t* out, uint64_t capacity, uint32_t bpt,
                                                       uint32_t* hist, uint32_t* esc_count, uint32_t* slots, uint64_t slot_words,
-                                                      uint32_t* gtot, uint32_t* bsum, uint32_t ipw, uint32_t n_items) {
+                                                      uint32_t* gtot, uint32_t* bsum, uint32_t ipw, uint32_t n_items, uint32_t count) {
     constexpr uint32_t CAP = (uint32_t)S / 8u;          // words of LDS per chunk: room for 4 bits per symbol
     constexpr uint32_t kStageWords = carry_stage_words(CAP);  // per wavefront
     constexpr uint32_t kGroupEls = kW * (uint32_t)S;
@@ -324,6 +325,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
     E.recs = s_recs + wave * kCarryRecs;
     E.sp_base = (uint32_t)(uintptr_t)stage + lane * 4u;
     E.row_max = CAP + 1u;
+    E.count = count;
     // where an item's group of this wavefront lies
     auto locate = [&](uint32_t item, const uint8_t*& gbase, uint32_t& rem) {
         const uint32_t t = item / bpt, grp = (item % bpt) * 4u + wave;
@@ -342,7 +344,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
                 w &= 0xFFFFu;
             }
             const uint32_t sym = win_lo + tid;
-            if (s && sym < g.K) atomicAdd(&hist[(size_t)t * g.K + sym], s);
+            if (s && sym < g.K && count) atomicAdd(&hist[(size_t)t * g.K + sym], s);
         }
     };
     // the first item's first elements are asked for before anything else: their way from memory is the longest
@@ -513,7 +515,7 @@ void DLC_CAT(launch_encode_carry_, DLC_S)(const Geom& g, const FixedLayout& F, c
     const bool f16 = g.dtype == DLC_F16;
 #define DLC_ENC(FF, V)                                                                                                 \
     hipLaunchKernelGGL((k_encode_carry<S, FF, V>), grid, block, 0, s, payload, g, F, w.qp, w.enc, out, capacity, bpt, w.hist, \
-                       w.esc_count, w.slots, (uint64_t)carry_slot_words(g), w.gtot, w.bsum, ipw, n_items)
+                       w.esc_count, w.slots, (uint64_t)carry_slot_words(g), w.gtot, w.bsum, ipw, n_items, w.sample != 0 ? 0u : 1u)
     if (f16) { if (g.vec) DLC_ENC(true, true); else DLC_ENC(true, false); }
     else { if (g.vec) DLC_ENC(false, true); else DLC_ENC(false, false); }
 #undef DLC_ENC

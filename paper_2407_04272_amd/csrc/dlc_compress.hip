@@ -75,7 +75,7 @@ constexpr uint32_t kHistBlk = 4;  // units whose loads are issued back to back
 // Index 254 in the plane stands for an escape.  LZ (row matching): the window is one symbol narrower, because index
 // 253 stands for an element of a row that is stored as a reference (the row-matching kernels put it there
 // afterwards); the symbol that would have had that index goes the way of everything outside the window.
-template <bool F16, bool VEC, bool FULL, bool LZ>
+template <bool F16, bool VEC, bool FULL, bool LZ, bool PLANE = true>
 __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, uint32_t n_units, uint32_t lane, const QParam& q,
                                            float Rf, const HistC& H, uint32_t* plane) {
     constexpr uint32_t kBins = LZ ? kWinSkip : kWinEsc;  // window indices that stand for a symbol
@@ -117,17 +117,29 @@ __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, ui
                 if (sl[v] == kWinBins && w[v] != kPastEnd) lds_count(H.exact + (w[v] + H.win_lo) * 4u);
         }
         // the window indices of these four elements, for the encode kernel (a unit of this wavefront only)
-        if (FULL || u < n_units) plane[u * kW + lane] = sl[0] | (sl[1] << 8) | (sl[2] << 16) | (sl[3] << 24);
+        if constexpr (PLANE) {
+            if (FULL || u < n_units) plane[u * kW + lane] = sl[0] | (sl[1] << 8) | (sl[2] << 16) | (sl[3] << 24);
+        }
     }
 }
 
 // The payload is cut into units of 256 elements, U per table, and every wavefront of the grid gets the same
 // number of consecutive units (table after table), so that all of them finish together whatever the shape is.
 // A work-group whose units touch several tables handles them one table at a time.
-template <bool F16, bool VEC, bool LZ>
+// SAMPLE (single-pass path with DLC_FLAG_SAMPLE_CODEBOOK): only a few groups of every table are counted, for the
+// codebook; U is then the number of units of a table's sampled groups, unit u of them stands for unit
+// (u / upg) * gstride * upg + u % upg of the table (upg = units of a group, gstride = groups from one sampled group
+// to the next), and no plane is written.  (Building a table's codebook in the same launch, by the work-group
+// that is the last to add its counts, was tried: the launch then takes as long as the two it replaces.)
+struct SampleArgs {
+    uint32_t upg, gstride;
+};
+
+template <bool F16, bool VEC, bool LZ, bool SAMPLE = false>
 __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const QParam* qp, uint32_t* hist,
-                                              uint8_t* sym_plane, uint32_t U, uint32_t units_per_wave) {
+                                              uint8_t* sym_plane, uint32_t U, uint32_t units_per_wave, SampleArgs sa) {
     extern __shared__ __align__(16) uint32_t lh[];
+    const uint32_t upg = sa.upg, gstride = sa.gstride;
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t lds0 = (uint32_t)(uintptr_t)lh;
     HistC H;
@@ -159,13 +171,18 @@ __global__ __launch_bounds__(256) void k_hist(const void* payload, Geom g, const
             uint32_t u = (uint32_t)(a - t0);
             const uint32_t ue = (uint32_t)(b - t0);
             for (; u < ue; u += kHistBlk) {
-                const uint32_t first = u * (kW * kV);  // element of the table
+                uint32_t ur = u;  // (a block of kHistBlk units never straddles two groups: upg is a multiple of it)
+                if constexpr (SAMPLE) ur = (u / upg) * gstride * upg + u % upg;
+                const uint32_t first = ur * (kW * kV);  // element of the table
+                if constexpr (SAMPLE) {
+                    if (first >= g.n) continue;  // (the last sampled group may be the table's last, ragged one)
+                }
                 const uint8_t* base = tab + (size_t)first * g.es;
                 const uint32_t rem = g.n - first;
                 const uint32_t n_units = min(kHistBlk, ue - u);
-                uint32_t* plane = reinterpret_cast<uint32_t*>(sym_plane + (size_t)t * plane_stride(g) + first);
-                if (n_units == kHistBlk && rem >= kHistBlk * kW * kV) hist_block<F16, VEC, true, LZ>(base, rem, n_units, lane, q, Rf, H, plane);
-                else hist_block<F16, VEC, false, LZ>(base, rem, n_units, lane, q, Rf, H, plane);
+                uint32_t* plane = SAMPLE ? nullptr : reinterpret_cast<uint32_t*>(sym_plane + (size_t)t * plane_stride(g) + first);
+                if (n_units == kHistBlk && rem >= kHistBlk * kW * kV) hist_block<F16, VEC, true, LZ, !SAMPLE>(base, rem, n_units, lane, q, Rf, H, plane);
+                else hist_block<F16, VEC, false, LZ, !SAMPLE>(base, rem, n_units, lane, q, Rf, H, plane);
             }
         }
         __syncthreads();
@@ -459,7 +476,8 @@ __global__ __launch_bounds__(256) void k_post(Geom g, FixedLayout F, const uint3
     extern __shared__ __align__(16) unsigned char smem[];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t gpd = g.TD * g.G;  // groups of one destination
-    const uint32_t n_cb = (g.T + tpw - 1u) / tpw;  // work-groups that build the next call's codebooks, tpw (1 or 4) tables each
+    // work-groups that build the next call's codebooks, tpw (1 or 4) tables each; tpw == 0: none (no codebook is carried)
+    const uint32_t n_cb = tpw ? (g.T + tpw - 1u) / tpw : 0u;
     if (blockIdx.x < n_cb) {  // uniform over the work-group; these come first: a codebook takes longer than a copy
         __shared__ CodebookShared sh;
         __shared__ uint32_t s_slow[4];
@@ -560,8 +578,35 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
                            const Ws& w, uint64_t epoch, bool carry_ready, int pl, void* prof, hipStream_t s) {
     const bool f16 = g.dtype == DLC_F16;
     const FixedLayout F = fixed_layout(g);
-    if (w.carry != 0 && carry_ready) {
+    if (w.sample != 0) {
+        // single pass without a carried codebook: the counts of a few groups of every table, their codebook (the escape
+        // symbol always gets a code: an element whose symbol the sample has not seen is stored as an escape)
+        uint32_t ns, gstride;
+        sample_groups(g, &ns, &gstride);
+        const uint32_t upg = g.S / kV;  // units of a group
+        const uint32_t U = ns * upg;
+        const uint64_t total_units = (uint64_t)g.T * U;
+        const uint32_t units_per_wave = 4 * kHistBlk;
+        const uint32_t grid_n = (uint32_t)((total_units + 4ull * units_per_wave - 1) / (4ull * units_per_wave));
+        SampleArgs sa;
+        sa.upg = upg; sa.gstride = gstride;
+        const size_t sm = hist_lds_bytes(g.K);
+        if (prof_on(pl, P_HIST)) prof_begin(prof, P_HIST, s);
+#define DLC_HIST(FF, V) hipLaunchKernelGGL((k_hist<FF, V, false, true>), dim3(grid_n), dim3(256), sm, s, payload, g, w.qp, w.hist, \
+                                           (uint8_t*)nullptr, U, units_per_wave, sa)
+        if (f16) { if (g.vec) DLC_HIST(true, true); else DLC_HIST(true, false); }
+        else { if (g.vec) DLC_HIST(false, true); else DLC_HIST(false, false); }
+#undef DLC_HIST
+        if (prof_on(pl, P_HIST)) prof_end(prof, P_HIST, s);
+        if (prof_on(pl, P_CODEBOOK)) prof_begin(prof, P_CODEBOOK, s);
+        const uint32_t tpw = codebook_tables_per_wg(g);
+        hipLaunchKernelGGL(k_codebook, dim3((g.T + tpw - 1u) / tpw), dim3(256), codebook_smem(g.K), s, g, w.hist, w.hist_view, w.enc, w.lens,
+                           w.tmeta, 1u, tpw);
+        if (prof_on(pl, P_CODEBOOK)) prof_end(prof, P_CODEBOOK, s);
+    }
+    if (w.sample != 0 || (w.carry != 0 && carry_ready)) {
         // single pass: encode with the codebook of the previous call, then build the next one from this call's counts
+        // (or, with the sample's codebook, nothing to build)
         const uint32_t bpt = (g.G + 3) / 4;
         if (prof_on(pl, P_CARRY)) prof_begin(prof, P_CARRY, s);
         switch (g.S) {
@@ -574,8 +619,8 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
             const uint32_t wpd = (g.TD * g.G + kPlaceGroups - 1) / kPlaceGroups, n_place = g.ND * wpd;
             const uint32_t nf = std::min<uint32_t>((std::min<uint32_t>(g.TD, 256u) + 3u) / 4u, 64u);  // a wavefront per table's code-length block
             if (prof_on(pl, P_POST)) prof_begin(prof, P_POST, s);
-            const uint32_t tpw = codebook_tables_per_wg(g);
-            hipLaunchKernelGGL(k_post, dim3((g.T + tpw - 1u) / tpw + g.ND * nf + n_place), dim3(256), codebook_smem(g.K), s, g, F, w.gtot, w.bsum,
+            const uint32_t tpw = w.sample != 0 ? 0u : codebook_tables_per_wg(g);
+            hipLaunchKernelGGL(k_post, dim3((tpw ? (g.T + tpw - 1u) / tpw : 0u) + g.ND * nf + n_place), dim3(256), codebook_smem(g.K), s, g, F, w.gtot, w.bsum,
                                w.bsum_next, w.slots, (uint64_t)carry_slot_words(g), w.ctrl, out, capacity, wpd, nf, w.word_start,
                                w.word_end, w.tmeta, w.lens, w.qp, out_bytes, w.esc_count, w.hist, w.hist_view, w.enc_next,
                                w.lens_next, w.tmeta_next, tpw);
@@ -594,7 +639,7 @@ hipError_t launch_compress(const Geom& g, const void* payload, uint8_t* out, uin
         const size_t sm = hist_lds_bytes(g.K);
         dim3 grid(grid_n), block(256);
         if (prof_on(pl, P_HIST)) prof_begin(prof, P_HIST, s);
-#define DLC_HIST(FF, V, L) hipLaunchKernelGGL((k_hist<FF, V, L>), grid, block, sm, s, payload, g, w.qp, w.hist, w.sym_plane, U, units_per_wave)
+#define DLC_HIST(FF, V, L) hipLaunchKernelGGL((k_hist<FF, V, L>), grid, block, sm, s, payload, g, w.qp, w.hist, w.sym_plane, U, units_per_wave, SampleArgs{})
         if (g.lz) {  // row matching wants D % 4 == 0, which makes every table start 16-byte aligned with n % 4 == 0
             if (f16) DLC_HIST(true, true, true); else DLC_HIST(false, true, true);
         } else if (f16) { if (g.vec) DLC_HIST(true, true, false); else DLC_HIST(true, false, false); }

@@ -35,6 +35,7 @@ struct Geom {
     uint32_t TD;  // tables per destination (= T of a container)
     uint32_t lz;  // 1: row matching (vector-based LZ step) is on for the tables flagged in Ws::rm_on
     uint32_t carry;  // 1: the codebook is carried from call to call (single-pass path)
+    uint32_t sample;  // 1: the codebook comes from a sample of the payload (single-pass path, no state between calls)
     uint32_t S, R, K, LMAX;
     uint32_t dtype, es;
     uint32_t vec;  // 1: every table starts on a 16-byte (fp32) / 8-byte (fp16) boundary and n % 4 == 0
@@ -64,6 +65,16 @@ inline __host__ __device__ FixedLayout fixed_layout(const Geom& g) {
 // element an escape.
 inline __host__ __device__ uint64_t carry_slot_words(const Geom& g) {
     return (uint64_t)kW * (((uint64_t)g.S * g.LMAX + 31ull) / 32ull) + 2ull * kW * g.S;
+}
+
+// DLC_FLAG_SAMPLE_CODEBOOK: the groups of a table whose symbols are counted for its codebook: groups 0, stride,
+// 2 * stride, ..., `ns` of them at most (fewer when the table ends first), together at least kSampleElems elements
+// where the table has that many
+constexpr uint32_t kSampleElems = 65536;
+inline __host__ __device__ void sample_groups(const Geom& g, uint32_t* ns, uint32_t* stride) {
+    const uint32_t gs = kW * g.S;
+    *ns = (kSampleElems + gs - 1u) / gs;
+    *stride = g.G / *ns > 1u ? g.G / *ns : 1u;
 }
 
 constexpr uint32_t kPlaceGroups = 4;  // groups a work-group of k_post places: one per wavefront, many short wavefronts keep enough loads in flight
@@ -242,6 +253,7 @@ struct Ws {
     uint32_t* rm_own = nullptr;    // [T][B] the smallest row index with the row's hash
     uint32_t* rm_mult = nullptr;   // [D/4][8] multipliers of the row hash
     uint32_t carry = 0;            // 1: the codebook is carried from call to call (single-pass path)
+    uint32_t sample = 0;           // 1: the codebook comes from a sample of the payload (single-pass path)
     uint32_t* slots = nullptr;     // [NG][carry_slot_words] the groups' words before they are placed (single-pass path)
     uint32_t* gtot = nullptr;      // [NG] words of every group (single-pass path)
     uint16_t* enc_next = nullptr;  // single-pass path: the codebook for the next call is built while this call's is still

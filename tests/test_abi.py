@@ -48,14 +48,18 @@ def test_host_only_entry_points():
     ok = [b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_ROW_MATCH), b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_ROW_MATCH, num_dest=8),
           b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_CARRY_CODEBOOK, num_dest=8),
           b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_ROW_MATCH | b.FLAG_STATS_WORKSPACE),
-          b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_CARRY_CODEBOOK | b.FLAG_STATS_WORKSPACE)]
+          b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_CARRY_CODEBOOK | b.FLAG_STATS_WORKSPACE),
+          b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_SAMPLE_CODEBOOK, num_dest=3),
+          b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_SAMPLE_CODEBOOK | b.FLAG_STATS_WORKSPACE)]
     for cfg in ok:
         assert b.dlc_compress_bound(cfg) > 0 and b.dlc_workspace_bytes(cfg) > 0
     bad = [b.make_config(b.F32, 4, 64, 6, flags=b.FLAG_ROW_MATCH),
            b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_ROW_MATCH | b.FLAG_CARRY_CODEBOOK),
            b.make_config(b.F32, 4, 64, 8, flags=1),
            b.make_config(b.F32, 20000, 4, 4, flags=b.FLAG_ROW_MATCH, num_dest=4),
-           b.make_config(b.F32, 4, 64, 8, flags=16), b.make_config(b.F32, 4, 64, 8, num_dest=5000)]
+           b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_SAMPLE_CODEBOOK | b.FLAG_CARRY_CODEBOOK),
+           b.make_config(b.F32, 4, 64, 8, flags=b.FLAG_SAMPLE_CODEBOOK | b.FLAG_ROW_MATCH),
+           b.make_config(b.F32, 4, 64, 8, flags=32), b.make_config(b.F32, 4, 64, 8, num_dest=5000)]
     for cfg in bad:
         assert b.dlc_compress_bound(cfg) == 0 and b.dlc_workspace_bytes(cfg) == 0
     # with row matching the bound has room for the references: 4 bytes per row and table, blocks 16-byte aligned

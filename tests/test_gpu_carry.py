@@ -283,3 +283,87 @@ def test_many_small_tables_both_paths():
         ok = oracle.compress(x, ebs, R, S, 12, carry_hist=prev, want_hist=True)
         _same(gk, ok, x, f"many tables, call {k}")
         prev = ok.hist
+
+
+# ------------------------------------------------------------------------------------------------
+# DLC_FLAG_SAMPLE_CODEBOOK: the same single-pass kernels, the codebook from a few groups of the payload itself
+# ------------------------------------------------------------------------------------------------
+def _sampled(x, ebs, S, n_calls=1, Rr=R, LMAX=12):
+    import torch
+    from paper_2407_04272_amd import binding as b
+    T, B, D = x.shape
+    f16 = x.dtype == np.float16
+    cfg = b.make_config(b.F16 if f16 else b.F32, T, B, D, Rr, S, LMAX, b.FLAG_SAMPLE_CODEBOOK)
+    ctx = b.Context(cfg)
+    ctx.set_error_bounds(eb=ebs)
+    cap = b.dlc_compress_bound(cfg)
+    out = torch.zeros(cap + 64, dtype=torch.uint8, device="cuda")
+    sizes = torch.zeros(1 + T, dtype=torch.int64, device="cuda")
+    d = to_device(x)
+    for _ in range(n_calls):
+        out.fill_(0xA5)
+        assert ctx.compress(d, out, sizes, capacity=cap) == 0 and ctx.sync_status() == 0
+    sz = sizes.cpu().numpy().astype(np.uint64)
+    h = out.cpu().numpy()
+    assert np.all(h[cap:] == 0xA5)
+    rec = torch.full_like(d, 7.0)
+    assert ctx.decompress(out, int(sz[0]), rec) == 0 and ctx.sync_status() == 0
+    return (h[:int(sz[0])].copy(), sz, rec.cpu().numpy()), ctx
+
+
+@pytest.mark.parametrize("T,B,D,S,eb,dtype", CASES + [
+    (2, 8192, 128, 256, 2e-3, np.float32),   # 64 groups a table: groups 0, 16, 32, 48 are the sample
+    (3, 4096, 64, 64, 2e-3, np.float32),     # 64 groups of 4096 elements: sixteen sampled
+    (2, 5000, 100, 128, 3e-3, np.float16),   # 62 groups, the last ragged; stride 7
+])
+def test_sampled_codebook_matches_the_oracle(T, B, D, S, eb, dtype):
+    x = _batch(T, B, D, 17 * B + D, dtype=dtype, rows=max(80, B // 4))
+    x.reshape(-1)[::1013] = 6e4 if dtype == np.float16 else 1e9
+    ebs = (np.float32(eb) * (1 + np.arange(T, dtype=np.float32))).astype(np.float32)
+    g, _ = _sampled(x, ebs, S, n_calls=2)    # (the second call finds what the first left in the workspace)
+    _same(g, oracle.compress(x, ebs, R, S, 12, sample_codebook=True), x, "sampled codebook")
+
+
+def test_sampled_codebook_symbols_outside_the_sample_become_escapes():
+    T, B, D, S = 2, 8192, 128, 256
+    rng = np.random.default_rng(5)
+    x = (rng.integers(-2, 3, (T, B, D)) * 4e-3).astype(np.float32)       # five symbols
+    flat = x.reshape(T, -1)
+    flat[:, 16384 * 5:16384 * 7] = (rng.integers(-40, 41, (T, 16384 * 2)) * 4e-3).astype(np.float32)  # groups 5, 6: eighty-one
+    ebs = np.full(T, 2e-3, np.float32)
+    g, ctx = _sampled(x, ebs, S)
+    o = oracle.compress(x, ebs, R, S, 12, sample_codebook=True)
+    _same(g, o, x, "symbols outside the sample")
+    assert o.data.size > oracle.compress(x, ebs, R, S, 12).data.size
+    hist = ctx.read_histogram()              # the counts the codebook was built from: the sample's
+    assert np.array_equal(hist.astype(np.uint64), oracle.sample_histogram(x, ebs, R, S))
+
+
+def test_sampled_codebook_workload3_full_size():
+    """The whole workload-3 payload (128 x 8192 x 128): sizes against the oracle on the first tables, the bound on all."""
+    import torch
+    from paper_2407_04272_amd import binding as b
+    w = W.workload3(device="cuda")
+    x = w.payload
+    T, B, D = x.shape
+    flat = x.reshape(T, -1)
+    rng_t = (flat.max(dim=1).values - flat.min(dim=1).values).cpu().numpy()
+    ebs = (0.03 * rng_t).astype(np.float32)
+    cfg = b.make_config(b.F32, T, B, D, R, 256, 12, b.FLAG_SAMPLE_CODEBOOK)
+    ctx = b.Context(cfg)
+    ctx.set_error_bounds(eb=ebs)
+    cap = b.dlc_compress_bound(cfg)
+    out = torch.zeros(cap, dtype=torch.uint8, device="cuda")
+    sizes = torch.zeros(1 + T, dtype=torch.int64, device="cuda")
+    assert ctx.compress(x, out, sizes, capacity=cap) == 0 and ctx.sync_status() == 0
+    sz = sizes.cpu().numpy().astype(np.uint64)
+    rec = torch.empty_like(x)
+    assert ctx.decompress(out, int(sz[0]), rec) == 0 and ctx.sync_status() == 0
+    err = (rec.double() - x.double()).abs().reshape(T, -1).max(dim=1).values.cpu().numpy()
+    assert np.all(err <= ebs.astype(np.float64))
+    nt = 6
+    xs = x[:nt].cpu().numpy()
+    o = oracle.compress(xs, ebs[:nt], R, 256, 12, sample_codebook=True)
+    assert o.rc == 0 and np.array_equal(sz[1:1 + nt], o.sizes[1:1 + nt])
+    rc, orec = oracle.decompress(o.data, xs.shape, np.float32)
+    assert rc == 0 and np.array_equal(rec[:nt].cpu().numpy().view(np.uint32), orec.view(np.uint32))

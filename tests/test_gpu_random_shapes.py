@@ -9,7 +9,7 @@ pytestmark = pytest.mark.gpu
 
 
 
-def _one(rng, k, large=False):
+def _one(rng, k, large=False, force_mode=None):
     import torch
     from paper_2407_04272_amd import binding as b
     T = int(rng.integers(1, 7))
@@ -24,6 +24,8 @@ def _one(rng, k, large=False):
         R, LMAX = [(64, 8), (64, 12), (512, 10), (512, 12), (2048, 12)][int(rng.integers(0, 5))]
     f16 = bool(rng.integers(0, 2))
     mode = int(rng.integers(0, 3))           # 0 default, 1 single-pass chain, 2 row matching
+    if force_mode is not None:
+        mode = force_mode                    # 3: single pass with the codebook of a sample of the payload
     if mode == 2 and D % 4 != 0:
         mode = 0
     n = int(rng.choice([1, 1, 2, 3])) if mode != 2 or T * 3 <= 65535 else 1
@@ -32,7 +34,7 @@ def _one(rng, k, large=False):
     eb = np.float32(sigma * rng.choice([0.02, 0.1, 0.4, 3.0]) * (8.0 if f16 else 1.0))
     ebs = (eb * (1 + np.arange(T, dtype=np.float32) % 3)).astype(np.float32)
     print(f"random shape {k}: n={n} T={T} B={B} D={D} S={S} R={R} LMAX={LMAX} {np.dtype(dtype).name} mode={mode} eb={eb:g}", flush=True)
-    flags = [0, b.FLAG_CARRY_CODEBOOK, b.FLAG_ROW_MATCH][mode]
+    flags = [0, b.FLAG_CARRY_CODEBOOK, b.FLAG_ROW_MATCH, b.FLAG_SAMPLE_CODEBOOK][mode]
     # what the next allocation gets is not zero: a context must not rely on fresh memory
     junk = torch.full((48 << 20,), 0xA5, dtype=torch.uint8, device="cuda")
     del junk
@@ -45,7 +47,7 @@ def _one(rng, k, large=False):
     out = torch.zeros(cap + 64, dtype=torch.uint8, device="cuda")
     sizes = torch.zeros(1 + n * T + (n if n > 1 else 0), dtype=torch.int64, device="cuda")
     prev = [None] * n
-    for call in range(3 if mode == 1 else 1):
+    for call in range({1: 3, 3: 2}.get(mode, 1)):  # (a context with a sampled codebook keeps nothing from call to call)
         rows = max(1, B // 3)
         table = (rng.standard_normal((n, T, rows, D)) * sigma).astype(np.float32)
         idx = rng.integers(0, rows, (n, T, B))
@@ -63,7 +65,8 @@ def _one(rng, k, large=False):
         u = np.uint16 if f16 else np.uint32
         for p in range(n):
             o = oracle.compress(x[p], ebs, R, S, LMAX, carry_hist=prev[p] if mode == 1 else None,
-                                want_hist=(mode == 1), row_match=(True if mode == 2 else None))
+                                want_hist=(mode == 1), row_match=(True if mode == 2 else None),
+                                sample_codebook=(mode == 3))
             assert o.rc == 0
             nbytes = int(sz[1 + n * T + p]) if n > 1 else int(sz[0])
             got = h[p * stride:p * stride + nbytes]
@@ -101,3 +104,15 @@ def test_random_larger_geometries():
     rng = np.random.default_rng(20240705)
     for k in range(24):
         _one(rng, k, large=True)
+
+
+def test_random_geometries_sampled_codebook():
+    rng = np.random.default_rng(20240706)
+    for k in range(80):
+        _one(rng, k, force_mode=3)
+
+
+def test_random_larger_geometries_sampled_codebook():
+    rng = np.random.default_rng(20240707)
+    for k in range(14):
+        _one(rng, k, large=True, force_mode=3)
