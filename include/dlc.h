@@ -307,6 +307,8 @@ int dlc_sync_status(dlc_ctx* ctx, void* stream);
  *                      every row has the same hash, which is how the tests reach the handling of equal hashes
  * With DLC_FLAG_CARRY_CODEBOOK the histogram is still that of the last call's payload, and the codebook is the one
  * built from it for the NEXT call (escape count raised by one), not the one the last call's container was coded with.
+ * With DLC_FLAG_SAMPLE_CODEBOOK the histogram holds the counts of the last call's sampled groups only, and the codebook
+ * is the one built from them (escape count raised by one), which the last call's container was coded with.
  */
 int dlc_quantize(dlc_ctx* ctx, const void* d_payload, uint16_t* d_symbols, void* stream);
 int dlc_read_histogram(dlc_ctx* ctx, uint32_t* h_hist, void* stream);

@@ -337,6 +337,12 @@ def test_sampled_codebook_symbols_outside_the_sample_become_escapes():
     assert o.data.size > oracle.compress(x, ebs, R, S, 12).data.size
     hist = ctx.read_histogram()              # the counts the codebook was built from: the sample's
     assert np.array_equal(hist.astype(np.uint64), oracle.sample_histogram(x, ebs, R, S))
+    ln, code = ctx.read_codebook()           # and the codebook the container was coded with: theirs, the escape counted once more
+    for t in range(T):
+        h = hist[t].astype(np.uint64)
+        h[0] += 1
+        oln, ocode, _, _ = oracle.codebook(h, 12)
+        assert np.array_equal(ln[t], oln) and np.array_equal(code[t][oln > 0], ocode[oln > 0].astype(np.uint16))
 
 
 def test_sampled_codebook_workload3_full_size():
