@@ -1,5 +1,6 @@
-// Single-pass compression with a carried codebook, for one chunk size S (DLC_S, defined by the including source
-// file).
+// Single-pass compression with a codebook that exists before the payload is read, for one chunk size S (DLC_S,
+// defined by the including source file): the codebook carried over from the previous call (below), or the one built
+// from a sample of this call's payload just before (DLC_FLAG_SAMPLE_CODEBOOK: same kernel, same rules, no counting).
 //
 // The symbol distribution of a table changes little from one training iteration to the next (Section IV-C of the
 // paper: the value distributions stay put through the phases of training), so the codebook built from the previous
