@@ -373,3 +373,34 @@ def test_sampled_codebook_workload3_full_size():
     assert o.rc == 0 and np.array_equal(sz[1:1 + nt], o.sizes[1:1 + nt])
     rc, orec = oracle.decompress(o.data, xs.shape, np.float32)
     assert rc == 0 and np.array_equal(rec[:nt].cpu().numpy().view(np.uint32), orec.view(np.uint32))
+
+
+def test_sampled_codebook_workload4_f16_full_size():
+    """Workload 4 in half precision at its full size (64 x 16384 x 128, escapes in the percent range): the whole
+    container against the oracle's, byte for byte."""
+    import torch
+    from paper_2407_04272_amd import binding as b
+    w = W.workload4(device="cuda")
+    d = w.meta["payload_f16"]
+    del w
+    T, B, D = d.shape
+    lo = d.float().amin(dim=(1, 2)).cpu().numpy()
+    hi = d.float().amax(dim=(1, 2)).cpu().numpy()
+    ebs = np.maximum(0.03 * (hi - lo), np.float32(2.0 ** -10) * (hi - lo)).astype(np.float32)
+    cfg = b.make_config(b.F16, T, B, D, R, 256, 12, b.FLAG_SAMPLE_CODEBOOK)
+    ctx = b.Context(cfg)
+    ctx.set_error_bounds(eb=ebs)
+    cap = b.dlc_compress_bound(cfg)
+    out = torch.zeros(cap, dtype=torch.uint8, device="cuda")
+    sizes = torch.zeros(1 + T, dtype=torch.int64, device="cuda")
+    assert ctx.compress(d, out, sizes, capacity=cap) == 0 and ctx.sync_status() == 0
+    sz = sizes.cpu().numpy().astype(np.uint64)
+    rec = torch.empty_like(d)
+    assert ctx.decompress(out, int(sz[0]), rec) == 0 and ctx.sync_status() == 0
+    x = d.cpu().numpy()
+    print("oracle at full size", flush=True)
+    o = oracle.compress(x, ebs, R, 256, 12, sample_codebook=True)
+    assert o.rc == 0 and o.data.size == int(sz[0]) and np.array_equal(o.sizes, sz)
+    assert np.array_equal(o.data, out[:int(sz[0])].cpu().numpy())
+    rc, orec = oracle.decompress(o.data, x.shape, np.float16)
+    assert rc == 0 and np.array_equal(rec.cpu().numpy().view(np.uint16), orec.view(np.uint16))
