@@ -129,8 +129,9 @@ __device__ __forceinline__ void hist_block(const uint8_t* base, uint32_t rem, ui
 // SAMPLE (single-pass path with DLC_FLAG_SAMPLE_CODEBOOK): only a few groups of every table are counted, for the
 // codebook; U is then the number of units of a table's sampled groups, unit u of them stands for unit
 // (u / upg) * gstride * upg + u % upg of the table (upg = units of a group, gstride = groups from one sampled group
-// to the next), and no plane is written.  (Building a table's codebook in the same launch, by the work-group
-// that is the last to add its counts, was tried: the launch then takes as long as the two it replaces.)
+// to the next), and no plane is written.  (Building a table's codebook in the same launch was tried
+// both ways: by the work-group that is the last to add its counts, the launch takes as long as the two it replaces;
+// by a single work-group per table that also does all the counting, longer.)
 struct SampleArgs {
     uint32_t upg, gstride;
 };
