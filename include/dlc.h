@@ -123,8 +123,9 @@ enum { DLC_FLAG_CARRY_CODEBOOK = 2, DLC_FLAG_ROW_MATCH = 4, DLC_FLAG_STATS_WORKS
 /* DLC_FLAG_SAMPLE_CODEBOOK: the payload is read once as with DLC_FLAG_CARRY_CODEBOOK, but no call depends on the one
  * before it: the Huffman codebook of a table (Section III-D) is built from the symbol counts of a SAMPLE of the same
  * payload, a few whole groups of the table (a group = 64 * chunk_symbols consecutive elements):
- *   - ns = ceil(65536 / (64 * chunk_symbols)) groups at most, groups 0, stride, 2 * stride, ... with
- *     stride = max(1, floor(groups of the table / ns)); a table of at most ns groups is counted whole;
+ *   - ns groups: as many as hold 65536 elements, ceil(65536 / (64 * chunk_symbols)), but no more than a quarter of
+ *     the table's groups (rounded up); they are groups 0, stride, 2 * stride, ... with stride = floor(groups / ns);
+ *     a table of one group is counted whole;
  *   - the count of symbol 0 (the escape) is raised by one and a symbol the sample has not seen is stored as an escape,
  *     exactly as with a carried codebook, so the error bound holds whatever the sample missed.
  * Costs: a fraction of a percent of compression ratio where a table's symbols take bits at all; a table that is one

@@ -198,12 +198,13 @@ SAMPLE_ELEMS = 65536  # a table's codebook sample: at least this many elements w
 def sample_groups(n: int, S: int = 256) -> list[int]:
     """The groups (64 * S consecutive elements each) of a table of n elements whose symbols are counted when the
     codebook is built from a sample of the payload (a reading of ours: Section III-D builds the Huffman code from the
-    data it codes and does not speak of sampling).  ns = ceil(SAMPLE_ELEMS / (64 S)) groups at most, evenly spread from
-    group 0 on: 0, stride, 2 stride, ... with stride = max(1, floor(G / ns))."""
+    data it codes and does not speak of sampling).  ns groups, evenly spread from group 0 on (0, stride, 2 stride, ...
+    with stride = floor(G / ns)): as many as hold SAMPLE_ELEMS elements, ceil(SAMPLE_ELEMS / (64 S)), but no more than
+    a quarter of the table's G groups, rounded up."""
     gs = 64 * S
     G = (n + gs - 1) // gs
-    ns = (SAMPLE_ELEMS + gs - 1) // gs
-    stride = max(1, G // ns)
+    ns = min((SAMPLE_ELEMS + gs - 1) // gs, (G + 3) // 4)
+    stride = G // ns
     return list(range(0, G, stride))[:ns]
 
 

@@ -68,13 +68,14 @@ inline __host__ __device__ uint64_t carry_slot_words(const Geom& g) {
 }
 
 // DLC_FLAG_SAMPLE_CODEBOOK: the groups of a table whose symbols are counted for its codebook: groups 0, stride,
-// 2 * stride, ..., `ns` of them at most (fewer when the table ends first), together at least kSampleElems elements
-// where the table has that many
+// 2 * stride, ..., `ns` of them: as many as hold kSampleElems elements, but no more than a quarter of the table's
+// groups (rounded up), so that the sample of a small table is not the whole table
 constexpr uint32_t kSampleElems = 65536;
 inline __host__ __device__ void sample_groups(const Geom& g, uint32_t* ns, uint32_t* stride) {
     const uint32_t gs = kW * g.S;
-    *ns = (kSampleElems + gs - 1u) / gs;
-    *stride = g.G / *ns > 1u ? g.G / *ns : 1u;
+    const uint32_t want = (kSampleElems + gs - 1u) / gs, quarter = (g.G + 3u) / 4u;
+    *ns = want < quarter ? want : quarter;  // (at least one: G >= 1)
+    *stride = g.G / *ns;                    // (>= 1: ns <= G)
 }
 
 constexpr uint32_t kPlaceGroups = 4;  // groups a work-group of k_post places: one per wavefront, many short wavefronts keep enough loads in flight

@@ -2,7 +2,7 @@
 groups).
 
 What fixes the result without reference to the code under test: the sampled groups for shapes worked out by hand from
-the rule (ceil(65536 / (64 S)) groups at most, evenly spread from group 0 on); the sample's counts against numpy's
+the rule (as many groups as hold 65536 elements, no more than a quarter of the table's, evenly spread from group 0 on); the sample's counts against numpy's
 bincount over the elements whose index falls into those groups; the container against the carried-codebook mode (pinned
 on its own, against the independent stream reader) given those counts; the bound on every element, and the raw value
 back for an element whose symbol the sample has not seen.
@@ -19,11 +19,13 @@ K = 2 * R
 @pytest.mark.parametrize("n,S,want", [
     (8192 * 128, 256, [0, 16, 32, 48]),            # 64 groups of 16384: four groups, every sixteenth
     (4096 * 64, 256, [0, 4, 8, 12]),               # 16 groups
-    (5 * 16384 - 100, 256, [0, 1, 2, 3]),          # 5 groups (the last ragged): stride 1, the first four
-    (7 * 16384, 256, [0, 1, 2, 3]),
-    (9 * 16384, 256, [0, 2, 4, 6]),
-    (100, 256, [0]),                               # less than a group
-    (3 * 16384, 256, [0, 1, 2]),                   # fewer groups than the sample may take: the whole table
+    (5 * 16384 - 100, 256, [0, 2]),                # 5 groups (the last ragged): a quarter, rounded up, is two; stride 2
+    (7 * 16384, 256, [0, 3]),
+    (9 * 16384, 256, [0, 3, 6]),
+    (17 * 16384, 256, [0, 4, 8, 12]),              # four groups hold 65536 elements: no more, though a quarter would be five
+    (100, 256, [0]),                               # less than a group: the whole table
+    (2 * 16384, 256, [0]),                         # two groups: the first
+    (4 * 16384, 256, [0]),
     (8192 * 128, 64, list(range(0, 256, 16))),     # groups of 4096: sixteen of 256
     (8192 * 128, 128, list(range(0, 128, 16))),    # groups of 8192: eight of 128
 ])
@@ -66,7 +68,7 @@ def test_sample_counts_and_container(T, B, D, S):
 
 
 def test_a_symbol_the_sample_has_not_seen_comes_back_as_the_raw_value():
-    S = 8                       # groups of 512 elements, 128 groups sampled at most: elements from 65536 on are not
+    S = 8                       # groups of 512 elements, every third of the first 103 sampled: elements from 65536 on are not
     T, B, D = 1, 1100, 64       # 70400 elements
     rng = np.random.default_rng(3)
     x = (rng.integers(-3, 4, (T, B, D)) * 2e-3).astype(np.float32)  # seven symbols throughout
@@ -75,7 +77,7 @@ def test_a_symbol_the_sample_has_not_seen_comes_back_as_the_raw_value():
     x.reshape(-1)[[65536, 65537 + 640, 70399]] = far
     h = oracle.sample_histogram(x, eb, R, S)
     sym, _ = oracle.quantize(x.reshape(-1), eb, R)
-    assert h[0][sym[65536]] == 0 and h[0].sum() == 65536
+    assert h[0][sym[65536]] == 0 and h[0].sum() == 35 * 512   # 138 groups of 512: a quarter of them, every third from group 0
     own = oracle.compress(x, eb, R, S, 12)
     smp = oracle.compress(x, eb, R, S, 12, sample_codebook=True)
     rc, rec = oracle.decompress(smp.data, x.shape, np.float32)
@@ -87,8 +89,8 @@ def test_a_symbol_the_sample_has_not_seen_comes_back_as_the_raw_value():
     assert smp.data.size > own.data.size
 
 
-def test_a_table_no_larger_than_the_sample_is_coded_with_its_own_counts():
-    x = _payload(2, 500, 64, 9)     # 32000 elements: two groups at S = 256, both sampled
+def test_a_table_of_one_group_is_coded_with_its_own_counts():
+    x = _payload(2, 250, 64, 9)     # 16000 elements: one group at S = 256, the sample
     eb = 2e-3
     whole = oracle.compress(x, eb, R, 256, 12, want_hist=True)
     smp = oracle.compress(x, eb, R, 256, 12, sample_codebook=True)
