@@ -514,9 +514,9 @@ __global__ __launch_bounds__(256) void k_post(Geom g, FixedLayout F, const uint3
             all += s_sum64[0] + s_sum64[1] + s_sum64[2] + s_sum64[3];
             if (xi == 0 && blk < nb) {
                 const uint32_t x0 = blk * kSumBlock, x1 = min(gpd, x0 + kSumBlock);
+                uint32_t w = before, i = x0;  // (one walk over the block's groups serves all the tables that start in it)
                 for (uint32_t tl = (x0 + g.G - 1u) / g.G; tl < g.TD && tl * g.G < x1; ++tl) {
-                    uint32_t w = before;
-                    for (uint32_t i = x0; i < tl * g.G; ++i) w += gtot_d[i];
+                    for (; i < tl * g.G; ++i) w += gtot_d[i];
                     __hip_atomic_store(&word_start[dst * g.TD + tl], w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     if (tl > 0) __hip_atomic_store(&word_end[dst * g.TD + tl - 1u], w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
